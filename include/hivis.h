@@ -1,0 +1,163 @@
+/*
+ * hivis.h -- C ABI of the HiViS draft-verify decode path on one MI355X (gfx950).
+ *
+ * The calls follow the paper's statement of the procedure (Algorithm 1, "Residual-Aided
+ * Drafting and Verification Process", and section 3.2): the target VLM M_p is prefilled on
+ * [visual embeddings ; text embeddings]; its final-layer features at the text positions
+ * (f_fused) are fused with the causally shifted token embeddings by one FC (2d -> d),
+ * get a step-dependent residual vector added, and feed a one-layer drafter M_q that keeps
+ * a TEXT-ONLY KV cache; the drafter proposes K tokens autoregressively; the target scores
+ * them in one pass against its visual+text cache; the longest matching prefix plus the
+ * target's own next token is accepted (section 2.1).
+ *
+ * Conventions
+ *   - Every function returns 0 (HIVIS_OK) or a negative HIVIS_E* code; none throws or aborts.
+ *     hivis_last_error() returns a human-readable message for the last failure on a context.
+ *   - "host" / "device" on a pointer says where the memory must live.  Pointers marked
+ *     "host or device" may be either (they are read with a default-kind hipMemcpy).
+ *   - The caller owns every buffer it passes; the library copies what it needs before the call
+ *     returns (weights at create; prompts at prefill) and owns all device state of a context.
+ *   - dtype: HIVIS_F32 = IEEE float32; HIVIS_BF16 = bfloat16 bit patterns (uint16_t).  It is the
+ *     storage type of weights, embedding tables, KV caches and vis_embeds.  All accumulation
+ *     is float32.
+ *   - Matrix orientation is the paper's row-vector form y = x W: W is [in][out] row-major,
+ *     except embed and lm_head, which are [vocab][d] row-major.
+ *   - Work is enqueued on the hipStream_t given at create.  hivis_accept, hivis_prefill (for
+ *     its first_token output) and the hivis_get_* / hivis_kv_lengths hooks synchronise that stream;
+ *     hivis_draft and hivis_verify only enqueue.
+ *   - A context is not thread-safe; use one per host thread.
+ *   - Shape limits: d, n_q_heads*head_dim, n_kv_heads*head_dim, ffn and vocab must be multiples
+ *     of 32 (16 for HIVIS_F32); head_dim is 64 or 128; batch*(k_max+1) <= 32.
+ */
+#ifndef HIVIS_H
+#define HIVIS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HIVIS_OK       0
+#define HIVIS_EINVAL  -1   /* null pointer, bad dimension, K out of range, token id >= vocab */
+#define HIVIS_ESTATE  -2   /* call out of order (draft before prefill, accept before verify, ...) */
+#define HIVIS_ECAP    -3   /* v, l or the generated length exceeds the capacity given at create */
+#define HIVIS_EHIP    -4   /* HIP runtime error; see hivis_last_error */
+
+#define HIVIS_F32  0
+#define HIVIS_BF16 1
+
+typedef struct hivis_ctx hivis_ctx;   /* opaque; created by hivis_create, freed by hivis_destroy */
+
+typedef struct {
+    int32_t n_layers;      /* N: decoder layers of the target (the drafter has exactly one) */
+    int32_t d;             /* hidden size */
+    int32_t n_q_heads, n_kv_heads, head_dim;
+    int32_t ffn;           /* SwiGLU inner width */
+    int32_t vocab;
+    int32_t dtype;         /* HIVIS_F32 or HIVIS_BF16 */
+    int32_t batch;         /* B independent sequences, same v and same prompt length */
+    int32_t k_max;         /* largest chain draft length K that will be requested */
+    int32_t max_vis;       /* capacity: visual embeddings per sequence */
+    int32_t max_text;      /* capacity: text tokens per sequence (prompt + everything generated + k_max + 1) */
+    float   rope_theta;
+    float   rms_eps;
+    int32_t n_resid;       /* number of residual vectors rho_0..rho_{n_resid-1}; the last is reused (section 4: r^3) */
+} hivis_config;
+
+/* Weights of one decoder layer, all host pointers of the context's dtype:
+ * norm1 [d], wq [d][Hq*hd], wk [d][Hkv*hd], wv [d][Hkv*hd], wo [Hq*hd][d],
+ * norm2 [d], wg [d][ffn], wu [d][ffn], wd [ffn][d].  No biases. */
+typedef struct {
+    const void *norm1, *wq, *wk, *wv, *wo, *norm2, *wg, *wu, *wd;
+} hivis_layer_weights;
+
+typedef struct {
+    const void *embed;                  /* [vocab][d]; shared by target and drafter */
+    const void *lm_head;                /* [vocab][d]; shared by target and drafter (Algorithm 1: "LM Head(f')") */
+    const void *final_norm;             /* [d]; target's final RMSNorm gain */
+    const hivis_layer_weights *layers;  /* [n_layers] */
+    hivis_layer_weights draft_layer;    /* the drafter's single decoder layer */
+    const void *fuse_w;                 /* [2d][d] = [w1 ; w2] of the fusion e^ = f w1 + e w2 (section 3.2) */
+    const void *resid_rho;              /* [n_resid][d]: rho_i = r^i w, the folded bias-correction residuals */
+} hivis_weights;
+
+/* Create a context: validates the config, allocates device state (weights re-laid-out for
+ * streaming, target KV for max_vis+max_text positions, drafter KV for max_text positions) and
+ * copies the weights from host memory.  hip_stream: a hipStream_t (NULL = the default stream).
+ * Errors: HIVIS_EINVAL, HIVIS_EHIP (then *out is NULL). */
+int hivis_create(const hivis_config *cfg, const hivis_weights *w, void *hip_stream, hivis_ctx **out);
+
+/* Free everything the context owns.  NULL is accepted. */
+int hivis_destroy(hivis_ctx *ctx);
+
+/* Algorithm 1, inputs line and steps 1-2.  Target prefill over [vis_embeds ; Embed(text_ids)]
+ * (positions 0..v+l-1, fully causal), which fills the target KV cache and yields f_fused^{1:l}
+ * and the first generated token x_{l+1}; then the drafter is prefilled over the l text positions
+ * only, with inputs f^j w1 + Embed(x_{j+1}) w2 + rho_0.
+ *   vis_embeds : [B][v][d], context dtype, host or device.
+ *   text_ids   : [B][l] int32, host or device; every id in [0, vocab).
+ *   first_token: [B] int32, host; receives x_{l+1} (may be NULL).
+ * May be called again at any time to start new sequences (all state is reset).
+ * Errors: EINVAL (null, v<0, l<1, id out of range), ECAP (v>max_vis or l+k_max+2>max_text), EHIP. */
+int hivis_prefill(hivis_ctx *ctx, const void *vis_embeds, int32_t v, const int32_t *text_ids, int32_t l,
+                  int32_t *first_token);
+
+/* Algorithm 1, the drafting loop: K serial drafter steps, each LM head -> greedy token ->
+ * fusion FC on [f' ; Embed(token)] + rho_min(i, n_resid-1) -> drafter layer over the text-only
+ * cache.  Tokens stay on the device.  1 <= K <= k_max.  State READY -> DRAFTED.
+ * Errors: ESTATE, EINVAL, ECAP (a sequence would exceed max_text). */
+int hivis_draft(hivis_ctx *ctx, int32_t K);
+
+/* Test hook: plant drafts instead of running the drafter.  tokens: [B][K] int32, host.
+ * State READY -> DRAFTED.  Errors: ESTATE, EINVAL, ECAP. */
+int hivis_set_drafts(hivis_ctx *ctx, const int32_t *tokens, int32_t K);
+
+/* Algorithm 1, "Parallel Verify": one target pass over the rows [x_{l+1}, x'_{l+2..l+1+K}] of
+ * every sequence against its full visual+text cache (causal among the new rows), LM head and
+ * greedy token per row.  State DRAFTED -> VERIFIED.  Errors: ESTATE, EHIP. */
+int hivis_verify(hivis_ctx *ctx);
+
+/* Greedy acceptance (section 2.1) and roll-forward.  Per sequence b: n_b = length of the longest
+ * prefix of drafts equal to the target's greedy tokens; tokens[b][0..n_b-1] are those drafts and
+ * tokens[b][n_b] is the target's own next token.  The target cache keeps n_b+1 new rows; the
+ * drafter's speculative rows are dropped and n_b+1 rows rebuilt from the target's true features
+ * (section 3.3, Eq. (1)).  Synchronises.  State VERIFIED -> READY.
+ *   n_accepted: [B] int32 host.   tokens: [B][k_max+1] int32 host (entries beyond n_b are -1).
+ * Errors: ESTATE, EINVAL, EHIP. */
+int hivis_accept(hivis_ctx *ctx, int32_t *n_accepted, int32_t *tokens);
+
+/* ---- test / measurement hooks (all synchronise) ---- */
+
+/* which = 0: logits of the last verify, [B][K+1][vocab]; which = 1: logits of the last draft round,
+ * [K][B][vocab]; which = 2: logits that chose x_{l+1} at prefill, [B][vocab].  out: float32, host. */
+int hivis_get_logits(hivis_ctx *ctx, int32_t which, float *out);
+
+/* which = 0: post-final-norm target features g of the last verify, [B][K+1][d];
+ * which = 1: the drafter's pending hidden state f'_1 for the next round, [B][d].  out: float32, host. */
+int hivis_get_hidden(hivis_ctx *ctx, int32_t which, float *out);
+
+/* Current KV lengths per sequence: target (visual + text rows) and drafter (text rows only). */
+int hivis_kv_lengths(hivis_ctx *ctx, int32_t *target_len, int32_t *drafter_len);
+
+/* Drafts of the last round, [B][K] int32 host, and the target's greedy tokens of the last verify,
+ * [B][K+1] int32 host.  Either pointer may be NULL. */
+int hivis_get_tokens(hivis_ctx *ctx, int32_t *drafts, int32_t *target_tokens);
+
+/* Timing hook: when enabled, hivis_draft / hivis_verify / hivis_accept / hivis_prefill record HIP
+ * events on the context's stream around their work; hivis_phase_ms returns and clears the accumulated
+ * milliseconds and call counts.  phase: 0 prefill, 1 draft (one call = K steps), 2 verify, 3 accept+roll. */
+int hivis_timing(hivis_ctx *ctx, int32_t enable);
+int hivis_phase_ms(hivis_ctx *ctx, int32_t phase, double *total_ms, int64_t *calls);
+
+/* Algorithmic HBM bytes of the last verify pass and of one draft step at the current lengths
+ * (every weight once, the KV rows read once; see the formulas in the implementation). */
+int hivis_algorithmic_bytes(hivis_ctx *ctx, double *verify_bytes, double *draft_step_bytes);
+
+const char *hivis_last_error(hivis_ctx *ctx);   /* never NULL; "" if no error */
+const char *hivis_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HIVIS_H */

@@ -1,0 +1,226 @@
+"""ctypes binding of libhivis.so: the same entry points as include/hivis.h, argument
+marshalling only.  Every step of the draft-verify path runs inside the library's HIP
+kernels; there is no Python or CPU fallback -- if the library is missing, loading fails.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhivis.so")
+
+HIVIS_OK, HIVIS_EINVAL, HIVIS_ESTATE, HIVIS_ECAP, HIVIS_EHIP = 0, -1, -2, -3, -4
+HIVIS_F32, HIVIS_BF16 = 0, 1
+
+LAYER_FIELDS = ("norm1", "wq", "wk", "wv", "wo", "norm2", "wg", "wu", "wd")
+
+
+class HivisError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"hivis error {code}: {msg}")
+        self.code = code
+
+
+class hivis_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32), ("dtype", C.c_int32),
+                ("batch", C.c_int32), ("k_max", C.c_int32), ("max_vis", C.c_int32), ("max_text", C.c_int32),
+                ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("n_resid", C.c_int32)]
+
+
+class hivis_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS]
+
+
+class hivis_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("layers", C.POINTER(hivis_layer_weights)), ("draft_layer", hivis_layer_weights),
+                ("fuse_w", C.c_void_p), ("resid_rho", C.c_void_p)]
+
+
+_lib = None
+
+
+def load_library(path=LIB_PATH):
+    """Loads libhivis.so (build it first with paper_2509_23928_amd.build.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} not built: run `python -m paper_2509_23928_amd.build` (hipcc, gfx950)")
+    lib = C.CDLL(path)
+    P, I32 = C.c_void_p, C.c_int32
+    sig = {
+        "hivis_create": (C.c_int, [C.POINTER(hivis_config), C.POINTER(hivis_weights), P, C.POINTER(P)]),
+        "hivis_destroy": (C.c_int, [P]),
+        "hivis_prefill": (C.c_int, [P, P, I32, P, I32, P]),
+        "hivis_draft": (C.c_int, [P, I32]),
+        "hivis_set_drafts": (C.c_int, [P, P, I32]),
+        "hivis_verify": (C.c_int, [P]),
+        "hivis_accept": (C.c_int, [P, P, P]),
+        "hivis_get_logits": (C.c_int, [P, I32, P]),
+        "hivis_get_hidden": (C.c_int, [P, I32, P]),
+        "hivis_kv_lengths": (C.c_int, [P, P, P]),
+        "hivis_get_tokens": (C.c_int, [P, P, P]),
+        "hivis_timing": (C.c_int, [P, I32]),
+        "hivis_phase_ms": (C.c_int, [P, I32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+        "hivis_algorithmic_bytes": (C.c_int, [P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "hivis_last_error": (C.c_char_p, [P]),
+        "hivis_version": (C.c_char_p, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_set_drafts",
+                    "hivis_verify", "hivis_accept", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
+                    "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_algorithmic_bytes",
+                    "hivis_last_error", "hivis_version")
+
+
+def _ptr(a):
+    """Address of a numpy array (host) or of anything with data_ptr() (a torch tensor, host or device)."""
+    if a is None:
+        return None
+    if hasattr(a, "data_ptr"):
+        return C.c_void_p(a.data_ptr())
+    assert a.flags["C_CONTIGUOUS"]
+    return C.c_void_p(a.ctypes.data)
+
+
+def _host_weight(a, dtype):
+    """Host array in the library's storage type: float32, or uint16 bf16 bit patterns."""
+    a = np.asarray(a)
+    if dtype == HIVIS_BF16:
+        if a.dtype == np.uint16:
+            return np.ascontiguousarray(a)
+        assert a.dtype == np.float32
+        bits = a.view(np.uint32)
+        assert not np.any(bits & np.uint32(0xFFFF)), "float32 weights of a bf16 model must hold bf16-representable values"
+        return np.ascontiguousarray((bits >> np.uint32(16)).astype(np.uint16))
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+class Hivis:
+    """One library context.  Method names mirror the C entry points."""
+
+    def __init__(self, cfg, weights, *, max_vis=None, max_text=None, k_max=None, batch=None, stream=None):
+        self.lib = load_library()
+        self.cfg = cfg
+        dt = HIVIS_BF16 if cfg.dtype == "bf16" else HIVIS_F32
+        self.dtype = dt
+        self.B = cfg.batch if batch is None else batch
+        self.k_max = cfg.K if k_max is None else k_max
+        gen = cfg.gen_tokens if cfg.gen_tokens else cfg.gen_cycles * (self.k_max + 1)
+        self.max_vis = cfg.n_vis if max_vis is None else max_vis
+        self.max_text = (cfg.n_text + gen + 2 * (self.k_max + 2)) if max_text is None else max_text
+        c = hivis_config(cfg.n_layers, cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.ffn, cfg.vocab, dt,
+                         self.B, self.k_max, self.max_vis, self.max_text, cfg.rope_theta, cfg.rms_eps, cfg.n_resid)
+        keep = []
+
+        def hw(a):
+            h = _host_weight(a, dt)
+            keep.append(h)
+            return C.c_void_p(h.ctypes.data)
+
+        def layer(lw):
+            return hivis_layer_weights(*[hw(lw[n]) for n in LAYER_FIELDS])
+
+        layers = (hivis_layer_weights * cfg.n_layers)(*[layer(lw) for lw in weights["layers"]])
+        w = hivis_weights(hw(weights["embed"]), hw(weights["lm_head"]), hw(weights["final_norm"]), layers,
+                          layer(weights["draft_layer"]), hw(weights["fuse_w"]), hw(weights["resid_rho"]))
+        self.ctx = C.c_void_p()
+        rc = self.lib.hivis_create(C.byref(c), C.byref(w), C.c_void_p(stream or 0), C.byref(self.ctx))
+        if rc:
+            raise HivisError(rc, self.lib.hivis_last_error(None).decode())
+        self.K = 0
+
+    def _check(self, rc):
+        if rc:
+            raise HivisError(rc, self.lib.hivis_last_error(self.ctx).decode())
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            self.lib.hivis_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- the four calls ------------------------------------------------------------
+    def prefill(self, vis_embeds, text_ids):
+        """vis_embeds [B][v][d] (numpy float32/uint16, or a torch tensor on host or device in the storage
+        dtype), text_ids [B][l] int32.  Returns first tokens [B]."""
+        if isinstance(vis_embeds, np.ndarray):
+            vis_embeds = _host_weight(vis_embeds, self.dtype)
+        if isinstance(text_ids, np.ndarray):
+            text_ids = np.ascontiguousarray(text_ids, dtype=np.int32)
+        v, l = int(vis_embeds.shape[-2]), int(text_ids.shape[-1])
+        first = np.zeros(self.B, np.int32)
+        self._check(self.lib.hivis_prefill(self.ctx, _ptr(vis_embeds), v, _ptr(text_ids), l, _ptr(first)))
+        return first
+
+    def draft(self, K):
+        self._check(self.lib.hivis_draft(self.ctx, K))
+        self.K = K
+
+    def set_drafts(self, tokens):
+        t = np.ascontiguousarray(tokens, dtype=np.int32).reshape(self.B, -1)
+        self._check(self.lib.hivis_set_drafts(self.ctx, _ptr(t), t.shape[1]))
+        self.K = t.shape[1]
+
+    def verify(self):
+        self._check(self.lib.hivis_verify(self.ctx))
+
+    def accept(self):
+        """Returns (n_accepted [B], tokens [B][k_max+1], -1 beyond n_b+1 entries)."""
+        n = np.zeros(self.B, np.int32)
+        t = np.zeros((self.B, self.k_max + 1), np.int32)
+        self._check(self.lib.hivis_accept(self.ctx, _ptr(n), _ptr(t)))
+        return n, t
+
+    # -- hooks -----------------------------------------------------------------------
+    def get_logits(self, which):
+        V = self.cfg.vocab
+        shape = {0: (self.B, self.K + 1, V), 1: (self.K, self.B, V), 2: (self.B, V)}[which]
+        out = np.zeros(shape, np.float32)
+        self._check(self.lib.hivis_get_logits(self.ctx, which, _ptr(out)))
+        return out
+
+    def get_hidden(self, which):
+        shape = {0: (self.B, self.K + 1, self.cfg.d), 1: (self.B, self.cfg.d)}[which]
+        out = np.zeros(shape, np.float32)
+        self._check(self.lib.hivis_get_hidden(self.ctx, which, _ptr(out)))
+        return out
+
+    def kv_lengths(self):
+        t = np.zeros(self.B, np.int32)
+        d = np.zeros(self.B, np.int32)
+        self._check(self.lib.hivis_kv_lengths(self.ctx, _ptr(t), _ptr(d)))
+        return t, d
+
+    def get_tokens(self):
+        dr = np.zeros((self.B, self.K), np.int32)
+        tt = np.zeros((self.B, self.K + 1), np.int32)
+        self._check(self.lib.hivis_get_tokens(self.ctx, _ptr(dr), _ptr(tt)))
+        return dr, tt
+
+    def timing(self, enable):
+        self._check(self.lib.hivis_timing(self.ctx, int(enable)))
+
+    def phase_ms(self, phase):
+        ms, calls = C.c_double(), C.c_int64()
+        self._check(self.lib.hivis_phase_ms(self.ctx, phase, C.byref(ms), C.byref(calls)))
+        return ms.value, calls.value
+
+    def algorithmic_bytes(self):
+        a, b = C.c_double(), C.c_double()
+        self._check(self.lib.hivis_algorithmic_bytes(self.ctx, C.byref(a), C.byref(b)))
+        return a.value, b.value

@@ -1,0 +1,680 @@
+// Host side of the HiViS draft-verify library: context, state machine, launch sequences.
+// The C ABI is declared and documented in include/hivis.h.
+#include "hivis.h"
+#include "hivis_kernels.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace hivis;
+
+namespace {
+
+enum State { ST_CREATED = 0, ST_READY, ST_DRAFTED, ST_VERIFIED };
+
+constexpr int MAX_ROWS = 32;   // rows per pass (verify rows B*(K+1), prefill chunk)
+
+struct LayerDev {
+    void* norm1 = nullptr; void* norm2 = nullptr;   // [d] storage dtype
+    uint4* wqkv = nullptr;                          // packed [d] -> [q_dim + 2 kv_dim]
+    uint4* wo = nullptr;                            // packed [q_dim] -> [d]
+    uint4* wgu = nullptr;                           // packed [d] -> [2 ffn]  (gate | up)
+    uint4* wd = nullptr;                            // packed [ffn] -> [d]
+};
+
+struct KVDev { void* k = nullptr; void* v = nullptr; int maxL = 0; };   // [B][Hkv][maxL][hd]
+
+}  // namespace
+
+struct hivis_ctx {
+    hivis_config cfg{};
+    hipStream_t stream = nullptr;
+    int state = ST_CREATED;
+    std::string err;
+    int esize = 4;
+    int num_cu = 256;
+
+    // weights
+    void* embed = nullptr; void* final_norm = nullptr; void* rho = nullptr;
+    uint4* lm_head = nullptr; uint4* fuse_w = nullptr;
+    std::vector<LayerDev> layers; LayerDev draft;
+    std::vector<KVDev> tkv; KVDev dkv;
+
+    // per-sequence state (device) + host mirrors
+    int* tlen = nullptr; int* dlen = nullptr; int* zeros = nullptr;
+    int32_t* text = nullptr; int text_stride = 0;
+    std::vector<int> h_tlen, h_dlen;
+    int v = 0, K = 0;
+
+    // activations (fp32)
+    float *x = nullptr, *a = nullptr, *qkv = nullptr, *att = nullptr, *proj = nullptr, *gu = nullptr, *act = nullptr;
+    float *catT = nullptr;      // [MAX_ROWS][2d]: verify features g | embeddings of the following tokens
+    float *catD = nullptr;      // [B][2d]: drafter hidden f' | embedding of the drafted token
+    float *u = nullptr, *dout = nullptr;
+    float *feat = nullptr;      // [B][max_text][d] true features of prompt text rows (prefill only)
+    float *attn_ws = nullptr; size_t attn_ws_floats = 0;
+    float *logits_v = nullptr, *logits_d = nullptr, *logits_p = nullptr;
+    int32_t *row_tok = nullptr, *drafts = nullptr, *ttok = nullptr, *nacc = nullptr, *out_tok = nullptr, *next_tok = nullptr;
+    void* vis = nullptr;        // staging for vis_embeds [B][max_vis][d]
+    std::vector<int32_t> h_ids;
+
+    // timing
+    bool timing = false;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    double phase_ms[4] = {0, 0, 0, 0}; int64_t phase_calls[4] = {0, 0, 0, 0};
+    std::vector<void*> allocs;
+};
+
+namespace {
+
+int fail(hivis_ctx* c, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap; va_start(ap, fmt); vsnprintf(buf, sizeof buf, fmt, ap); va_end(ap);
+    if (c) c->err = buf;
+    return code;
+}
+
+#define HIP_TRY(c, expr)                                                                              \
+    do {                                                                                              \
+        hipError_t e_ = (expr);                                                                       \
+        if (e_ != hipSuccess) return fail((c), HIVIS_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+template <typename T> int dev_alloc(hivis_ctx* c, T** p, size_t count) {
+    void* q = nullptr;
+    HIP_TRY(c, hipMalloc(&q, std::max<size_t>(count, 1) * sizeof(T)));
+    c->allocs.push_back(q);
+    *p = (T*)q;
+    return HIVIS_OK;
+}
+
+// ---- weight upload + re-layout -------------------------------------------------------------
+template <typename WT>
+int pack_matrix(hivis_ctx* c, const void* const* srcs, const int* ncols, int nsrc, int K, int transposed, void* staging,
+                uint4** out) {
+    int N = 0;
+    PackSrc ps{};
+    char* st = (char*)staging;
+    for (int i = 0; i < 3; ++i) { ps.p[i] = nullptr; ps.n[i] = 0; }
+    for (int i = 0; i < nsrc; ++i) {
+        const size_t bytes = (size_t)K * ncols[i] * sizeof(WT);
+        HIP_TRY(c, hipMemcpy(st, srcs[i], bytes, hipMemcpyHostToDevice));
+        ps.p[i] = st; ps.n[i] = ncols[i];
+        st += (bytes + 255) & ~(size_t)255;
+        N += ncols[i];
+    }
+    ps.transposed = transposed;
+    const size_t n16 = (size_t)K * N * sizeof(WT) / 16;
+    if (int rc = dev_alloc(c, out, n16)) return rc;
+    const int blocks = (int)std::min<size_t>((n16 + 255) / 256, 65535);
+    hipLaunchKernelGGL(pack_weights_kernel<WT>, dim3(blocks), dim3(256), 0, c->stream, ps, K, N, *out);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int upload_vec(hivis_ctx* c, const void* src, size_t count, void** out) {
+    WT* p = nullptr;
+    if (int rc = dev_alloc(c, &p, count)) return rc;
+    HIP_TRY(c, hipMemcpy(p, src, count * sizeof(WT), hipMemcpyHostToDevice));
+    *out = p;
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int upload_layer(hivis_ctx* c, const hivis_layer_weights& w, void* staging, LayerDev& L) {
+    const hivis_config& g = c->cfg;
+    const int qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim;
+    if (!w.norm1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.norm2 || !w.wg || !w.wu || !w.wd)
+        return fail(c, HIVIS_EINVAL, "null layer weight pointer");
+    if (int rc = upload_vec<WT>(c, w.norm1, g.d, &L.norm1)) return rc;
+    if (int rc = upload_vec<WT>(c, w.norm2, g.d, &L.norm2)) return rc;
+    { const void* s[3] = {w.wq, w.wk, w.wv}; int n[3] = {qd, kd, kd};
+      if (int rc = pack_matrix<WT>(c, s, n, 3, g.d, 0, staging, &L.wqkv)) return rc; }
+    { const void* s[1] = {w.wo}; int n[1] = {g.d};
+      if (int rc = pack_matrix<WT>(c, s, n, 1, qd, 0, staging, &L.wo)) return rc; }
+    { const void* s[2] = {w.wg, w.wu}; int n[2] = {g.ffn, g.ffn};
+      if (int rc = pack_matrix<WT>(c, s, n, 2, g.d, 0, staging, &L.wgu)) return rc; }
+    { const void* s[1] = {w.wd}; int n[1] = {g.d};
+      if (int rc = pack_matrix<WT>(c, s, n, 1, g.ffn, 0, staging, &L.wd)) return rc; }
+    return HIVIS_OK;
+}
+
+// ---- launches --------------------------------------------------------------------------------
+template <typename WT>
+int gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy, int epi) {
+    if (M < 1 || M > MAX_ROWS) return fail(c, HIVIS_EINVAL, "gemm rows %d out of range", M);
+    const int ntiles = N / 16;
+    const int grid = std::min(ntiles, c->num_cu);
+    constexpr int ROWS = WTraits<WT>::ROWS;
+    const int T = (M + ROWS - 1) / ROWS;
+    if constexpr (sizeof(WT) == 2) {
+        if (T == 1) hipLaunchKernelGGL((gemm_skinny_kernel<WT, 1, 4, 8, 16>), dim3(grid), dim3(1024), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);
+        else if (T == 2) hipLaunchKernelGGL((gemm_skinny_kernel<WT, 2, 4, 4, 16>), dim3(grid), dim3(1024), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);
+        else hipLaunchKernelGGL((gemm_skinny_kernel<WT, 4, 2, 2, 16>), dim3(grid), dim3(1024), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);
+    } else {
+        if (T == 1) hipLaunchKernelGGL((gemm_skinny_kernel<WT, 1, 4, 4, 16>), dim3(grid), dim3(1024), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);
+        else hipLaunchKernelGGL((gemm_skinny_kernel<WT, 2, 4, 2, 16>), dim3(grid), dim3(1024), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);
+    }
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int attention(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int* base, int offset, int seq0, int nseq,
+              int m, int max_keys, float* out, int ldo) {
+    const hivis_config& g = c->cfg;
+    AttnShape sh{};
+    sh.Hq = g.n_q_heads; sh.Hkv = g.n_kv_heads; sh.m = m;
+    const int group = g.n_q_heads / g.n_kv_heads;
+    if (m >= ATT_RMAX) { sh.mi = ATT_RMAX; sh.gh = 1; }
+    else { sh.mi = m; sh.gh = std::max(1, std::min(group, ATT_RMAX / m)); }
+    sh.n_hblk = (group + sh.gh - 1) / sh.gh; sh.n_rblk = (m + sh.mi - 1) / sh.mi;
+    sh.seq0 = seq0; sh.offset = offset; sh.maxL = kv.maxL; sh.ldq = ldq;
+    const int items = nseq * g.n_kv_heads * sh.n_hblk * sh.n_rblk;
+    // enough workgroups to occupy the chip, at most one 64-key tile per wavefront slot
+    const int tiles = (max_keys + 63) / 64;
+    int nsplit = std::max(1, std::min((2 * c->num_cu + items - 1) / items, (tiles + 3) / 4));
+    nsplit = std::min(nsplit, 16);
+    sh.nsplit = nsplit;
+    const size_t need = (size_t)items * nsplit * 4 * ATT_RMAX * (g.head_dim + 2);
+    if (need > c->attn_ws_floats) return fail(c, HIVIS_EINVAL, "attention workspace too small (%zu > %zu)", need, c->attn_ws_floats);
+    if (g.head_dim == 128) {
+        hipLaunchKernelGGL((attn_partial_kernel<WT, 128>), dim3(items, nsplit), dim3(256), 0, c->stream, q, (const WT*)kv.k, (const WT*)kv.v, base, sh, c->attn_ws);
+        hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(items), dim3(256), 0, c->stream, c->attn_ws, sh, out, ldo);
+    } else {
+        hipLaunchKernelGGL((attn_partial_kernel<WT, 64>), dim3(items, nsplit), dim3(256), 0, c->stream, q, (const WT*)kv.k, (const WT*)kv.v, base, sh, c->attn_ws);
+        hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(items), dim3(256), 0, c->stream, c->attn_ws, sh, out, ldo);
+    }
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
+// One decoder layer on M = nseq*m rows.  h: residual stream [M][d] (in place).  `pending` (may be null) is a delta
+// from the previous layer that has not been added to h yet; on return *pending_out is this layer's MLP output, still
+// to be added by the caller (the next layer's first norm, or a final norm/add, fuses that addition).
+template <typename WT>
+int layer_forward(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, const float* pending, const int* base,
+                  int offset, int seq0, int nseq, int m, int max_keys) {
+    const hivis_config& g = c->cfg;
+    const int M = nseq * m, d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn;
+    const int nqkv = qd + 2 * kd;
+    hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, pending, d, (const WT*)L.norm1, c->a, d, d, g.rms_eps);
+    if (int rc = gemm<WT>(c, c->a, d, M, d, L.wqkv, nqkv, c->qkv, nqkv, EPI_STORE)) return rc;
+    hipLaunchKernelGGL((rope_append_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (WT*)kv.k, (WT*)kv.v, kv.maxL, g.rope_theta);
+    if (int rc = attention<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, max_keys, c->att, qd)) return rc;
+    if (int rc = gemm<WT>(c, c->att, qd, M, qd, L.wo, d, c->proj, d, EPI_STORE)) return rc;
+    hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, (const float*)c->proj, d, (const WT*)L.norm2, c->a, d, d, g.rms_eps);
+    if (int rc = gemm<WT>(c, c->a, d, M, d, L.wgu, 2 * F, c->gu, 2 * F, EPI_STORE)) return rc;
+    hipLaunchKernelGGL(silu_mul_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->gu, c->act, F);
+    if (int rc = gemm<WT>(c, c->act, F, M, F, L.wd, d, c->proj, d, EPI_STORE)) return rc;
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;   // c->proj holds the MLP delta, not yet added to h
+}
+
+// Target pass over M = nseq*m rows already in c->x; leaves post-final-norm features in out (row stride ldo)
+// for rows >= first_out_row (pointer arithmetic done by the caller through first_out_row).
+template <typename WT>
+int target_forward(hivis_ctx* c, int seq0, int nseq, int m, const int* base, int offset, int max_keys, float* out, int ldo,
+                   int first_out_row) {
+    const hivis_config& g = c->cfg;
+    const int M = nseq * m;
+    const float* pending = nullptr;
+    for (int l = 0; l < g.n_layers; ++l) {
+        // KV of layer l for all sequences
+        if (int rc = layer_forward<WT>(c, c->layers[l], c->tkv[l], c->x, pending, base, offset, seq0, nseq, m, max_keys)) return rc;
+        pending = c->proj;
+    }
+    const int nout = M - first_out_row;
+    if (nout > 0)
+        hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(nout), dim3(256), 0, c->stream, c->x + (size_t)first_out_row * g.d, g.d,
+                           pending + (size_t)first_out_row * g.d, g.d, (const WT*)c->final_norm, out, ldo, g.d, g.rms_eps);
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
+// Drafter: fusion FC on cat rows [M][2d] + rho_idx, then its single layer; output rows (h + mlp delta) to out.
+template <typename WT>
+int drafter_forward(hivis_ctx* c, const float* cat, int seq0, int nseq, int m, int rho_idx, int offset, int max_keys,
+                    float* out, int ldo) {
+    const hivis_config& g = c->cfg;
+    const int M = nseq * m, d = g.d;
+    if (int rc = gemm<WT>(c, cat, 2 * d, M, 2 * d, c->fuse_w, d, c->u, d, EPI_STORE)) return rc;
+    hipLaunchKernelGGL((add_rho_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->u, d, (const WT*)c->rho, rho_idx, d);
+    if (int rc = layer_forward<WT>(c, c->draft, c->dkv, c->u, nullptr, c->dlen, offset, seq0, nseq, m, max_keys)) return rc;
+    hipLaunchKernelGGL(add_rows_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->u, d, (const float*)c->proj, d, out, ldo, d);
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
+struct PhaseTimer {
+    hivis_ctx* c; int phase;
+    PhaseTimer(hivis_ctx* c_, int p) : c(c_), phase(p) { if (c->timing) (void)hipEventRecord(c->ev0, c->stream); }
+    void stop() {
+        if (!c->timing) return;
+        (void)hipEventRecord(c->ev1, c->stream);
+        (void)hipEventSynchronize(c->ev1);
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) { c->phase_ms[phase] += ms; c->phase_calls[phase]++; }
+    }
+};
+
+// ---- the four calls, typed -------------------------------------------------------------------
+template <typename WT>
+int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_ids, int l, int32_t* first_token) {
+    const hivis_config& g = c->cfg;
+    const int B = g.batch, d = g.d;
+    PhaseTimer pt(c, 0);
+    // stage inputs
+    if (v > 0) {
+        for (int b = 0; b < B; ++b)
+            HIP_TRY(c, hipMemcpyAsync((char*)c->vis + (size_t)b * g.max_vis * d * sizeof(WT), (const char*)vis_embeds + (size_t)b * v * d * sizeof(WT),
+                                      (size_t)v * d * sizeof(WT), hipMemcpyDefault, c->stream));
+    }
+    for (int b = 0; b < B; ++b)
+        HIP_TRY(c, hipMemcpyAsync(c->text + (size_t)b * c->text_stride, c->h_ids.data() + (size_t)b * l, (size_t)l * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+    hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, c->tlen, B, 0);
+    hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, c->dlen, B, 0);
+
+    const int total = v + l;
+    for (int b = 0; b < B; ++b) {
+        for (int p0 = 0; p0 < total; p0 += MAX_ROWS) {
+            const int m = std::min(MAX_ROWS, total - p0);
+            hipLaunchKernelGGL((prefill_rows_kernel<WT>), dim3(m), dim3(256), 0, c->stream, (const WT*)c->vis + (size_t)b * g.max_vis * d, v,
+                               (const WT*)c->embed, (const int32_t*)(c->text + (size_t)b * c->text_stride), p0, c->x, d);
+            const int first_out = std::max(0, v - p0);       // rows of this chunk before the first text row produce no feature
+            float* out = c->feat + ((size_t)b * g.max_text + std::max(0, p0 - v)) * d;
+            if (int rc = target_forward<WT>(c, b, 1, m, c->zeros, p0, p0 + m, out, d, std::min(first_out, m))) return rc;
+        }
+    }
+    hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, c->tlen, B, total);
+    // first token x_{l+1}: LM head on the last text row of every sequence
+    if (int rc = gemm<WT>(c, c->feat + (size_t)(l - 1) * d, g.max_text * d, B, d, c->lm_head, g.vocab, c->logits_p, g.vocab, EPI_STORE)) return rc;
+    hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)c->logits_p, g.vocab, c->text + l, c->text_stride);
+    // drafter prefill over the l text positions: rows [f^j ; Embed(x_{j+1})] + rho_0
+    for (int b = 0; b < B; ++b) {
+        for (int j0 = 0; j0 < l; j0 += MAX_ROWS) {
+            const int m = std::min(MAX_ROWS, l - j0);
+            hipLaunchKernelGGL((fuse_rows_kernel<WT>), dim3(m), dim3(256), 0, c->stream, (const float*)(c->feat + (size_t)b * g.max_text * d),
+                               (const WT*)c->embed, (const int32_t*)(c->text + (size_t)b * c->text_stride), j0, c->catT, d);
+            if (int rc = drafter_forward<WT>(c, c->catT, b, 1, m, 0, j0, j0 + m, c->dout, d)) return rc;
+            if (j0 + m == l)   // f'_1: drafter output at the last true-feature row
+                hipLaunchKernelGGL(copy_rows_kernel, dim3(1), dim3(256), 0, c->stream, (const float*)(c->dout + (size_t)(m - 1) * d), d, c->catD + (size_t)b * 2 * d, 2 * d, d);
+        }
+    }
+    hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, c->dlen, B, l);
+    HIP_TRY(c, hipGetLastError());
+    pt.stop();
+    std::vector<int32_t> ft(B);
+    for (int b = 0; b < B; ++b)
+        HIP_TRY(c, hipMemcpyAsync(&ft[b], c->text + (size_t)b * c->text_stride + l, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (first_token) for (int b = 0; b < B; ++b) first_token[b] = ft[b];
+    for (int b = 0; b < B; ++b) { c->h_tlen[b] = total; c->h_dlen[b] = l; }
+    c->v = v;
+    c->state = ST_READY;
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int do_draft(hivis_ctx* c, int K) {
+    const hivis_config& g = c->cfg;
+    const int B = g.batch, d = g.d, V = g.vocab;
+    PhaseTimer pt(c, 1);
+    int max_keys = 0;
+    for (int b = 0; b < B; ++b) max_keys = std::max(max_keys, c->h_dlen[b]);
+    for (int i = 1; i <= K; ++i) {
+        float* lg = c->logits_d + (size_t)(i - 1) * B * V;
+        if (int rc = gemm<WT>(c, c->catD, 2 * d, B, d, c->lm_head, V, lg, V, EPI_STORE)) return rc;
+        hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)lg, V, c->drafts + (i - 1), g.k_max);
+        if (i < K) {
+            hipLaunchKernelGGL((gather_rows_kernel<WT>), dim3(B), dim3(256), 0, c->stream, (const WT*)c->embed, (const int32_t*)(c->drafts + (i - 1)), g.k_max, c->catD + d, 2 * d, d);
+            if (int rc = drafter_forward<WT>(c, c->catD, 0, B, 1, std::min(i, g.n_resid - 1), i - 1, max_keys + i, c->catD, 2 * d)) return rc;
+        }
+    }
+    HIP_TRY(c, hipGetLastError());
+    pt.stop();
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int do_verify(hivis_ctx* c) {
+    const hivis_config& g = c->cfg;
+    const int B = g.batch, d = g.d, V = g.vocab, K = c->K, M = B * (K + 1);
+    PhaseTimer pt(c, 2);
+    int max_keys = 0;
+    for (int b = 0; b < B; ++b) max_keys = std::max(max_keys, c->h_tlen[b]);
+    hipLaunchKernelGGL(verify_tokens_kernel, dim3(1), dim3(64), 0, c->stream, (const int32_t*)c->text, c->text_stride, (const int*)c->dlen, (const int32_t*)c->drafts, g.k_max, K, c->row_tok, B);
+    hipLaunchKernelGGL((gather_rows_kernel<WT>), dim3(M), dim3(256), 0, c->stream, (const WT*)c->embed, (const int32_t*)c->row_tok, 1, c->x, d, d);
+    if (int rc = target_forward<WT>(c, 0, B, K + 1, c->tlen, 0, max_keys + K + 1, c->catT, 2 * d, 0)) return rc;
+    if (int rc = gemm<WT>(c, c->catT, 2 * d, M, d, c->lm_head, V, c->logits_v, V, EPI_STORE)) return rc;
+    // target's greedy token after each row: ttok[b][i], row stride k_max+1
+    for (int b = 0; b < B; ++b)
+        hipLaunchKernelGGL(argmax_kernel, dim3(K + 1), dim3(256), 0, c->stream, (const float*)(c->logits_v + (size_t)b * (K + 1) * V), V, c->ttok + (size_t)b * (g.k_max + 1), 1);
+    HIP_TRY(c, hipGetLastError());
+    pt.stop();
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int do_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
+    const hivis_config& g = c->cfg;
+    const int B = g.batch, d = g.d, K = c->K, M = B * (K + 1);
+    PhaseTimer pt(c, 3);
+    hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(64), 0, c->stream, (const int32_t*)c->drafts, (const int32_t*)c->ttok, g.k_max, K, c->text, c->text_stride,
+                       (const int*)c->dlen, c->tlen, c->nacc, c->out_tok, c->next_tok);
+    // roll-forward: K+1 rows per sequence [g_i ; Embed(token after row i)] + rho_0 through the drafter at positions
+    // dlen..dlen+K; rows beyond n_b are computed but become dead (the drafter length advances by n_b+1 only).
+    for (int b = 0; b < B; ++b)
+        hipLaunchKernelGGL((gather_rows_kernel<WT>), dim3(K + 1), dim3(256), 0, c->stream, (const WT*)c->embed, (const int32_t*)(c->next_tok + (size_t)b * (g.k_max + 1)), 1,
+                           c->catT + (size_t)b * (K + 1) * 2 * d + d, 2 * d, d);
+    int max_keys = 0;
+    for (int b = 0; b < B; ++b) max_keys = std::max(max_keys, c->h_dlen[b]);
+    if (int rc = drafter_forward<WT>(c, c->catT, 0, B, K + 1, 0, 0, max_keys + K + 1, c->dout, d)) return rc;
+    hipLaunchKernelGGL(select_row_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)c->dout, K + 1, (const int32_t*)c->nacc, c->catD, 2 * d, c->dlen, d);
+    HIP_TRY(c, hipGetLastError());
+    pt.stop();
+    std::vector<int32_t> hn(B), ht((size_t)B * (g.k_max + 1));
+    HIP_TRY(c, hipMemcpyAsync(hn.data(), c->nacc, B * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(ht.data(), c->out_tok, ht.size() * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (int b = 0; b < B; ++b) {
+        c->h_tlen[b] += hn[b] + 1; c->h_dlen[b] += hn[b] + 1;
+        if (n_accepted) n_accepted[b] = hn[b];
+    }
+    if (tokens) memcpy(tokens, ht.data(), ht.size() * sizeof(int32_t));
+    c->state = ST_READY;
+    (void)M;
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int do_create(hivis_ctx* c, const hivis_weights* w) {
+    const hivis_config& g = c->cfg;
+    const int d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn, V = g.vocab, B = g.batch;
+    // staging big enough for the largest source set of one packed matrix
+    size_t stg = std::max({(size_t)d * (qd + 2 * kd), (size_t)qd * d, (size_t)2 * d * F, (size_t)F * d, (size_t)V * d, (size_t)2 * d * d}) * sizeof(WT) + 4096;
+    void* staging = nullptr;
+    HIP_TRY(c, hipMalloc(&staging, stg));
+    int rc = HIVIS_OK;
+    do {
+        if ((rc = upload_vec<WT>(c, w->embed, (size_t)V * d, &c->embed))) break;
+        if ((rc = upload_vec<WT>(c, w->final_norm, d, &c->final_norm))) break;
+        if ((rc = upload_vec<WT>(c, w->resid_rho, (size_t)g.n_resid * d, &c->rho))) break;
+        { const void* s[1] = {w->lm_head}; int n[1] = {V};
+          if ((rc = pack_matrix<WT>(c, s, n, 1, d, 1, staging, &c->lm_head))) break; }
+        { const void* s[1] = {w->fuse_w}; int n[1] = {d};
+          if ((rc = pack_matrix<WT>(c, s, n, 1, 2 * d, 0, staging, &c->fuse_w))) break; }
+        c->layers.resize(g.n_layers);
+        for (int l = 0; l < g.n_layers && !rc; ++l) rc = upload_layer<WT>(c, w->layers[l], staging, c->layers[l]);
+        if (rc) break;
+        if ((rc = upload_layer<WT>(c, w->draft_layer, staging, c->draft))) break;
+    } while (0);
+    (void)hipFree(staging);
+    if (rc) return rc;
+
+    // KV caches
+    const int maxLt = g.max_vis + g.max_text, maxLd = g.max_text;
+    c->tkv.resize(g.n_layers);
+    for (int l = 0; l < g.n_layers; ++l) {
+        WT *k, *v;
+        if ((rc = dev_alloc(c, &k, (size_t)B * kd * maxLt))) return rc;
+        if ((rc = dev_alloc(c, &v, (size_t)B * kd * maxLt))) return rc;
+        c->tkv[l].k = k; c->tkv[l].v = v; c->tkv[l].maxL = maxLt;
+    }
+    { WT *k, *v;
+      if ((rc = dev_alloc(c, &k, (size_t)B * kd * maxLd))) return rc;
+      if ((rc = dev_alloc(c, &v, (size_t)B * kd * maxLd))) return rc;
+      c->dkv.k = k; c->dkv.v = v; c->dkv.maxL = maxLd; }
+    { WT* vis; if ((rc = dev_alloc(c, &vis, (size_t)B * std::max(1, g.max_vis) * d))) return rc; c->vis = vis; }
+
+    // state + activations
+    c->text_stride = g.max_text + g.k_max + 2;
+    if ((rc = dev_alloc(c, &c->tlen, B))) return rc;
+    if ((rc = dev_alloc(c, &c->dlen, B))) return rc;
+    if ((rc = dev_alloc(c, &c->zeros, B))) return rc;
+    HIP_TRY(c, hipMemset(c->zeros, 0, B * sizeof(int)));
+    if ((rc = dev_alloc(c, &c->text, (size_t)B * c->text_stride))) return rc;
+    HIP_TRY(c, hipMemset(c->text, 0, (size_t)B * c->text_stride * sizeof(int32_t)));
+    const int R = MAX_ROWS;
+    if ((rc = dev_alloc(c, &c->x, (size_t)R * d))) return rc;
+    if ((rc = dev_alloc(c, &c->a, (size_t)R * d))) return rc;
+    if ((rc = dev_alloc(c, &c->qkv, (size_t)R * (qd + 2 * kd)))) return rc;
+    if ((rc = dev_alloc(c, &c->att, (size_t)R * qd))) return rc;
+    if ((rc = dev_alloc(c, &c->proj, (size_t)R * d))) return rc;
+    if ((rc = dev_alloc(c, &c->gu, (size_t)R * 2 * F))) return rc;
+    if ((rc = dev_alloc(c, &c->act, (size_t)R * F))) return rc;
+    if ((rc = dev_alloc(c, &c->catT, (size_t)R * 2 * d))) return rc;
+    if ((rc = dev_alloc(c, &c->catD, (size_t)B * 2 * d))) return rc;
+    if ((rc = dev_alloc(c, &c->u, (size_t)R * d))) return rc;
+    if ((rc = dev_alloc(c, &c->dout, (size_t)R * d))) return rc;
+    if ((rc = dev_alloc(c, &c->feat, (size_t)B * g.max_text * d))) return rc;
+    // attention workspace: (items * nsplit) work groups x 4 wave slots x RMAX rows x (hd + 2) floats, where
+    // items * nsplit <= 2 * num_cu + items and items <= max(2, B) * n_q_heads
+    {
+        const size_t max_items = (size_t)std::max(2, B) * g.n_q_heads;
+        c->attn_ws_floats = (2 * (size_t)c->num_cu + max_items) * 4 * ATT_RMAX * (g.head_dim + 2);
+        if ((rc = dev_alloc(c, &c->attn_ws, c->attn_ws_floats))) return rc;
+    }
+    if ((rc = dev_alloc(c, &c->logits_v, (size_t)R * V))) return rc;
+    if ((rc = dev_alloc(c, &c->logits_d, (size_t)g.k_max * B * V))) return rc;
+    if ((rc = dev_alloc(c, &c->logits_p, (size_t)B * V))) return rc;
+    if ((rc = dev_alloc(c, &c->row_tok, R))) return rc;
+    if ((rc = dev_alloc(c, &c->drafts, (size_t)B * g.k_max))) return rc;
+    if ((rc = dev_alloc(c, &c->ttok, (size_t)B * (g.k_max + 1)))) return rc;
+    if ((rc = dev_alloc(c, &c->nacc, B))) return rc;
+    if ((rc = dev_alloc(c, &c->out_tok, (size_t)B * (g.k_max + 1)))) return rc;
+    if ((rc = dev_alloc(c, &c->next_tok, (size_t)B * (g.k_max + 1)))) return rc;
+    c->h_tlen.assign(B, 0); c->h_dlen.assign(B, 0);
+    HIP_TRY(c, hipEventCreate(&c->ev0));
+    HIP_TRY(c, hipEventCreate(&c->ev1));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return HIVIS_OK;
+}
+
+int check_config(const hivis_config* g, std::string& why) {
+    char buf[256];
+#define BAD(...) do { snprintf(buf, sizeof buf, __VA_ARGS__); why = buf; return HIVIS_EINVAL; } while (0)
+    if (g->dtype != HIVIS_F32 && g->dtype != HIVIS_BF16) BAD("dtype %d unknown", g->dtype);
+    const int al = g->dtype == HIVIS_BF16 ? 32 : 16;
+    if (g->n_layers < 1 || g->d < al || g->n_q_heads < 1 || g->n_kv_heads < 1 || g->ffn < al || g->vocab < 16) BAD("non-positive dimension");
+    if (g->head_dim != 64 && g->head_dim != 128) BAD("head_dim %d not in {64,128}", g->head_dim);
+    if (g->n_q_heads % g->n_kv_heads) BAD("n_q_heads %% n_kv_heads != 0");
+    if (g->d % al || (g->n_q_heads * g->head_dim) % al || (g->n_kv_heads * g->head_dim) % al || g->ffn % al) BAD("d, q_dim, kv_dim, ffn must be multiples of %d", al);
+    if (g->vocab % 16) BAD("vocab must be a multiple of 16");
+    if (g->batch < 1 || g->k_max < 1 || g->batch * (g->k_max + 1) > MAX_ROWS) BAD("batch*(k_max+1) must be in 2..%d", MAX_ROWS);
+    if (g->max_vis < 0 || g->max_text < 2 + g->k_max) BAD("capacity too small");
+    if (g->n_resid < 1) BAD("n_resid must be >= 1");
+    if (!(g->rope_theta > 1.f) || !(g->rms_eps >= 0.f)) BAD("rope_theta / rms_eps out of range");
+#undef BAD
+    return HIVIS_OK;
+}
+
+thread_local std::string g_create_err;
+
+}  // namespace
+
+#define DISPATCH(c, fn, ...) ((c)->cfg.dtype == HIVIS_BF16 ? fn<bf16_t>(__VA_ARGS__) : fn<float>(__VA_ARGS__))
+
+extern "C" {
+
+int hivis_create(const hivis_config* cfg, const hivis_weights* w, void* hip_stream, hivis_ctx** out) {
+    if (out) *out = nullptr;
+    if (!cfg || !w || !out) { g_create_err = "null argument"; return HIVIS_EINVAL; }
+    if (int rc = check_config(cfg, g_create_err)) return rc;
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->layers || !w->fuse_w || !w->resid_rho) { g_create_err = "null weight pointer"; return HIVIS_EINVAL; }
+    hivis_ctx* c = new hivis_ctx();
+    c->cfg = *cfg;
+    c->stream = (hipStream_t)hip_stream;
+    c->esize = cfg->dtype == HIVIS_BF16 ? 2 : 4;
+    int dev = 0; hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        g_create_err = "no HIP device"; delete c; return HIVIS_EHIP;
+    }
+    c->num_cu = prop.multiProcessorCount;
+    int rc = DISPATCH(c, do_create, c, w);
+    if (rc) { g_create_err = c->err; hivis_destroy(c); return rc; }
+    *out = c;
+    return HIVIS_OK;
+}
+
+int hivis_destroy(hivis_ctx* c) {
+    if (!c) return HIVIS_OK;
+    (void)hipStreamSynchronize(c->stream);
+    for (void* p : c->allocs) (void)hipFree(p);
+    if (c->ev0) (void)hipEventDestroy(c->ev0);
+    if (c->ev1) (void)hipEventDestroy(c->ev1);
+    delete c;
+    return HIVIS_OK;
+}
+
+int hivis_prefill(hivis_ctx* c, const void* vis_embeds, int32_t v, const int32_t* text_ids, int32_t l, int32_t* first_token) {
+    if (!c) return HIVIS_EINVAL;
+    const hivis_config& g = c->cfg;
+    if (!text_ids || v < 0 || l < 1 || (v > 0 && !vis_embeds)) return fail(c, HIVIS_EINVAL, "bad prefill arguments (v=%d, l=%d)", v, l);
+    if (v > g.max_vis || l + g.k_max + 2 > g.max_text) return fail(c, HIVIS_ECAP, "prompt exceeds capacity (v=%d/%d, l=%d/%d)", v, g.max_vis, l, g.max_text);
+    c->h_ids.resize((size_t)g.batch * l);
+    HIP_TRY(c, hipMemcpy(c->h_ids.data(), text_ids, c->h_ids.size() * sizeof(int32_t), hipMemcpyDefault));
+    for (int32_t id : c->h_ids)
+        if (id < 0 || id >= g.vocab) return fail(c, HIVIS_EINVAL, "token id %d outside [0,%d)", id, g.vocab);
+    c->state = ST_CREATED;
+    return DISPATCH(c, do_prefill, c, vis_embeds, v, text_ids, l, first_token);
+}
+
+static int check_room(hivis_ctx* c, int K) {
+    const hivis_config& g = c->cfg;
+    for (int b = 0; b < g.batch; ++b) {
+        if (c->h_dlen[b] + K + 2 > g.max_text) return fail(c, HIVIS_ECAP, "sequence %d: text length %d + K + 2 exceeds max_text %d", b, c->h_dlen[b], g.max_text);
+        if (c->h_tlen[b] + K + 1 > g.max_vis + g.max_text) return fail(c, HIVIS_ECAP, "sequence %d: target cache full", b);
+    }
+    return HIVIS_OK;
+}
+
+int hivis_draft(hivis_ctx* c, int32_t K) {
+    if (!c) return HIVIS_EINVAL;
+    if (c->state != ST_READY) return fail(c, HIVIS_ESTATE, "hivis_draft needs a prefilled/accepted context");
+    if (K < 1 || K > c->cfg.k_max) return fail(c, HIVIS_EINVAL, "K=%d outside [1,%d]", K, c->cfg.k_max);
+    if (int rc = check_room(c, K)) return rc;
+    int rc = DISPATCH(c, do_draft, c, K);
+    if (rc) return rc;
+    c->K = K; c->state = ST_DRAFTED;
+    return HIVIS_OK;
+}
+
+int hivis_set_drafts(hivis_ctx* c, const int32_t* tokens, int32_t K) {
+    if (!c) return HIVIS_EINVAL;
+    if (c->state != ST_READY) return fail(c, HIVIS_ESTATE, "hivis_set_drafts needs a prefilled/accepted context");
+    if (!tokens || K < 1 || K > c->cfg.k_max) return fail(c, HIVIS_EINVAL, "bad planted drafts (K=%d)", K);
+    if (int rc = check_room(c, K)) return rc;
+    for (int i = 0; i < c->cfg.batch * K; ++i)
+        if (tokens[i] < 0 || tokens[i] >= c->cfg.vocab) return fail(c, HIVIS_EINVAL, "planted token %d outside vocab", tokens[i]);
+    for (int b = 0; b < c->cfg.batch; ++b)
+        HIP_TRY(c, hipMemcpyAsync(c->drafts + (size_t)b * c->cfg.k_max, tokens + (size_t)b * K, K * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->K = K; c->state = ST_DRAFTED;
+    return HIVIS_OK;
+}
+
+int hivis_verify(hivis_ctx* c) {
+    if (!c) return HIVIS_EINVAL;
+    if (c->state != ST_DRAFTED) return fail(c, HIVIS_ESTATE, "hivis_verify needs drafts");
+    int rc = DISPATCH(c, do_verify, c);
+    if (rc) return rc;
+    c->state = ST_VERIFIED;
+    return HIVIS_OK;
+}
+
+int hivis_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
+    if (!c) return HIVIS_EINVAL;
+    if (c->state != ST_VERIFIED) return fail(c, HIVIS_ESTATE, "hivis_accept needs a verified context");
+    if (!n_accepted || !tokens) return fail(c, HIVIS_EINVAL, "null output pointer");
+    return DISPATCH(c, do_accept, c, n_accepted, tokens);
+}
+
+int hivis_get_logits(hivis_ctx* c, int32_t which, float* out) {
+    if (!c || !out) return HIVIS_EINVAL;
+    const hivis_config& g = c->cfg;
+    const float* src; size_t n;
+    if (which == 0) { if (c->state != ST_VERIFIED && c->state != ST_READY) return fail(c, HIVIS_ESTATE, "no verify logits"); src = c->logits_v; n = (size_t)g.batch * (c->K + 1) * g.vocab; }
+    else if (which == 1) { src = c->logits_d; n = (size_t)c->K * g.batch * g.vocab; }
+    else if (which == 2) { src = c->logits_p; n = (size_t)g.batch * g.vocab; }
+    else return fail(c, HIVIS_EINVAL, "which=%d", which);
+    if (c->state == ST_CREATED) return fail(c, HIVIS_ESTATE, "nothing computed yet");
+    HIP_TRY(c, hipMemcpyAsync(out, src, n * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return HIVIS_OK;
+}
+
+int hivis_get_hidden(hivis_ctx* c, int32_t which, float* out) {
+    if (!c || !out) return HIVIS_EINVAL;
+    const hivis_config& g = c->cfg;
+    if (c->state == ST_CREATED) return fail(c, HIVIS_ESTATE, "nothing computed yet");
+    const int d = g.d;
+    if (which == 0) {
+        HIP_TRY(c, hipMemcpy2DAsync(out, d * sizeof(float), c->catT, 2 * d * sizeof(float), d * sizeof(float), (size_t)g.batch * (c->K + 1), hipMemcpyDeviceToHost, c->stream));
+    } else if (which == 1) {
+        HIP_TRY(c, hipMemcpy2DAsync(out, d * sizeof(float), c->catD, 2 * d * sizeof(float), d * sizeof(float), (size_t)g.batch, hipMemcpyDeviceToHost, c->stream));
+    } else return fail(c, HIVIS_EINVAL, "which=%d", which);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return HIVIS_OK;
+}
+
+int hivis_kv_lengths(hivis_ctx* c, int32_t* target_len, int32_t* drafter_len) {
+    if (!c) return HIVIS_EINVAL;
+    const int B = c->cfg.batch;
+    if (target_len) HIP_TRY(c, hipMemcpyAsync(target_len, c->tlen, B * sizeof(int), hipMemcpyDeviceToHost, c->stream));
+    if (drafter_len) HIP_TRY(c, hipMemcpyAsync(drafter_len, c->dlen, B * sizeof(int), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return HIVIS_OK;
+}
+
+int hivis_get_tokens(hivis_ctx* c, int32_t* drafts, int32_t* target_tokens) {
+    if (!c) return HIVIS_EINVAL;
+    const hivis_config& g = c->cfg;
+    if (c->state == ST_CREATED || c->K < 1) return fail(c, HIVIS_ESTATE, "no draft round yet");
+    std::vector<int32_t> hd((size_t)g.batch * g.k_max), ht((size_t)g.batch * (g.k_max + 1));
+    HIP_TRY(c, hipMemcpyAsync(hd.data(), c->drafts, hd.size() * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(ht.data(), c->ttok, ht.size() * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (int b = 0; b < g.batch; ++b) {
+        if (drafts) for (int i = 0; i < c->K; ++i) drafts[b * c->K + i] = hd[(size_t)b * g.k_max + i];
+        if (target_tokens) for (int i = 0; i <= c->K; ++i) target_tokens[b * (c->K + 1) + i] = ht[(size_t)b * (g.k_max + 1) + i];
+    }
+    return HIVIS_OK;
+}
+
+int hivis_timing(hivis_ctx* c, int32_t enable) {
+    if (!c) return HIVIS_EINVAL;
+    c->timing = enable != 0;
+    return HIVIS_OK;
+}
+
+int hivis_phase_ms(hivis_ctx* c, int32_t phase, double* total_ms, int64_t* calls) {
+    if (!c || phase < 0 || phase > 3) return HIVIS_EINVAL;
+    if (total_ms) *total_ms = c->phase_ms[phase];
+    if (calls) *calls = c->phase_calls[phase];
+    c->phase_ms[phase] = 0; c->phase_calls[phase] = 0;
+    return HIVIS_OK;
+}
+
+int hivis_algorithmic_bytes(hivis_ctx* c, double* verify_bytes, double* draft_step_bytes) {
+    if (!c) return HIVIS_EINVAL;
+    const hivis_config& g = c->cfg;
+    const double b = c->esize, d = g.d, qd = (double)g.n_q_heads * g.head_dim, kd = (double)g.n_kv_heads * g.head_dim, F = g.ffn, V = g.vocab;
+    const double w_layer = (2 * d * qd + 2 * d * kd + 3 * d * F) * b;
+    double kv_t = 0, kv_d = 0;
+    for (int s = 0; s < g.batch; ++s) { kv_t += 2.0 * c->h_tlen[s] * kd * b * g.n_layers; kv_d += 2.0 * c->h_dlen[s] * kd * b; }
+    if (verify_bytes) *verify_bytes = g.n_layers * w_layer + V * d * b + kv_t;
+    if (draft_step_bytes) *draft_step_bytes = w_layer + 2 * d * d * b + V * d * b + kv_d;
+    return HIVIS_OK;
+}
+
+const char* hivis_last_error(hivis_ctx* c) { return c ? c->err.c_str() : g_create_err.c_str(); }
+const char* hivis_version(void) { return "hivis-gfx950 0.1"; }
+
+}  // extern "C"

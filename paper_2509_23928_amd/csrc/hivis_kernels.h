@@ -1,0 +1,636 @@
+// HIP kernels of the HiViS draft-verify path for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// Decode, draft and verify are weight-streaming problems: every weight is read once per pass
+// and multiplies a handful of activation rows.  The weights are therefore re-laid-out once,
+// at load time, into 1 KiB blocks that one wavefront reads with a single 16-byte-per-lane load
+// in exactly the register layout the MFMA B operand wants; the kernel is a linear stream of
+// such blocks.  The activation rows are the MFMA A operand: for bf16 weights each fp32
+// activation is split into a bf16 "hi" and a bf16 "lo" part which occupy two of the 16 tile
+// rows (8 real rows per tile), so activations keep ~16 mantissa bits at no extra HBM traffic;
+// fp32 weights use the fp32 MFMA with 16 real rows per tile.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hivis {
+
+typedef uint16_t bf16_t;                                  // bfloat16 bit pattern
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round to nearest even, finite inputs
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x); }
+__device__ __forceinline__ void from_f32(float& dst, float x) { dst = x; }
+__device__ __forceinline__ void from_f32(bf16_t& dst, float x) { dst = f32_to_bf16(x); }
+
+// ------------------------------------------------------------------------------------------
+// Streaming layout of a weight matrix W (logical [K][N], y = x W).
+//   tile  t = n / 16      (16 output columns)
+//   block kb = k / KB     (KB = 32 k-values for bf16, 16 for fp32)  -> 1 KiB = 64 lanes x 16 B
+//   lane  = (n % 16) + 16 * g
+//     bf16: the lane's 8 values are k = 32 kb + 8 g + e, e = 0..7
+//     fp32: the lane's 4 values are k = 16 kb + 4 g + e, e = 0..3
+//   address (in 16-byte units) = (t * (K / KB) + kb) * 64 + lane
+// ------------------------------------------------------------------------------------------
+template <typename WT> struct WTraits;
+template <> struct WTraits<bf16_t> {
+    static constexpr int KB = 32;      // k per block
+    static constexpr int EPL = 8;      // elements per lane per block
+    static constexpr int ROWS = 8;     // real activation rows per MFMA tile (hi/lo split)
+    static constexpr int RPL = 2;      // real output rows per lane
+};
+template <> struct WTraits<float> {
+    static constexpr int KB = 16;
+    static constexpr int EPL = 4;
+    static constexpr int ROWS = 16;
+    static constexpr int RPL = 4;
+};
+
+// Sources of a packed matrix: up to three matrices concatenated along the output dimension
+// (fused QKV, fused gate|up).  transposed = 1 means the source is [N][K] (LM head).
+struct PackSrc {
+    const void* p[3];
+    int n[3];          // output columns of each source
+    int transposed;
+};
+
+template <typename WT>
+__global__ void pack_weights_kernel(PackSrc src, int K, int N, uint4* __restrict__ dst) {
+    constexpr int KB = WTraits<WT>::KB, EPL = WTraits<WT>::EPL;
+    const size_t total = (size_t)(N / 16) * (K / KB) * 64;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(idx & 63);
+        const size_t blk = idx >> 6;
+        const int kb = (int)(blk % (size_t)(K / KB));
+        const int t = (int)(blk / (size_t)(K / KB));
+        int n = t * 16 + (lane & 15);
+        const int g = lane >> 4;
+        const int k0 = kb * KB + g * EPL;
+        int s = 0;
+        while (s < 2 && n >= src.n[s]) { n -= src.n[s]; ++s; }
+        const WT* base = (const WT*)src.p[s];
+        const int ns = src.n[s];
+        WT vals[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e)
+            vals[e] = src.transposed ? base[(size_t)n * K + (k0 + e)] : base[(size_t)(k0 + e) * ns + n];
+        dst[idx] = *reinterpret_cast<const uint4*>(vals);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Skinny GEMM  Y[M][N] (+)= A[M][K] . W      (M <= T * ROWS rows; W in streaming layout)
+//
+// One workgroup of NW wavefronts owns a contiguous range of 16-column tiles and always covers
+// the whole K range, so every output element is produced by exactly one workgroup in a fixed
+// summation order (bit-reproducible; no atomics).  Inside the workgroup the K range is cut
+// into passes of NW*KBW blocks; in a pass wave w holds the A fragments of its KBW blocks in
+// registers and streams the matching weight blocks of up to G tiles through the MFMA unit,
+// with the loads of the next tile issued before the MFMAs of the current one.  The NW partial
+// tiles are then summed through LDS.
+// ------------------------------------------------------------------------------------------
+template <typename WT> struct AFrag;
+template <> struct AFrag<bf16_t> { typedef bf16x8_t type; };
+template <> struct AFrag<float> { typedef float4 type; };
+
+// A fragment of tile tt, block kb for this lane.  a_scale (optional, per k) multiplies the
+// activation before the hi/lo split (used to apply an RMSNorm gain on the fly).
+__device__ __forceinline__ void load_afrag(bf16x8_t& out, const float* __restrict__ A, int lda, int M, int tt, int kb,
+                                           int lane) {
+    const int i = lane & 15, g = lane >> 4;
+    const int row = tt * 8 + 2 * (i >> 2) + (i & 1);
+    const bool lo = (i & 2) != 0;
+    uint32_t pk[4] = {0u, 0u, 0u, 0u};
+    if (row < M) {
+        const float4* p = reinterpret_cast<const float4*>(A + (size_t)row * lda + kb * 32 + g * 8);
+        float4 x0 = p[0], x1 = p[1];
+        float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+        bf16_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            bf16_t hi = f32_to_bf16(x[e]);
+            h[e] = lo ? f32_to_bf16(x[e] - bf16_to_f32(hi)) : hi;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = (uint32_t)h[2 * e] | ((uint32_t)h[2 * e + 1] << 16);
+    }
+    uint4 u = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+    out = __builtin_bit_cast(bf16x8_t, u);
+}
+__device__ __forceinline__ void load_afrag(float4& out, const float* __restrict__ A, int lda, int M, int tt, int kb,
+                                           int lane) {
+    const int i = lane & 15, g = lane >> 4;
+    const int row = tt * 16 + i;
+    out = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (row < M) out = *reinterpret_cast<const float4*>(A + (size_t)row * lda + kb * 16 + g * 4);
+}
+
+__device__ __forceinline__ void mfma_block(f32x4_t& d, const bf16x8_t& a, const uint4& w) {
+    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8_t, w), d, 0, 0, 0);
+}
+__device__ __forceinline__ void mfma_block(f32x4_t& d, const float4& a, const uint4& w) {
+    d = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, __uint_as_float(w.x), d, 0, 0, 0);
+    d = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, __uint_as_float(w.y), d, 0, 0, 0);
+    d = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, __uint_as_float(w.z), d, 0, 0, 0);
+    d = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, __uint_as_float(w.w), d, 0, 0, 0);
+}
+
+// Epilogue modes of the skinny GEMM
+enum { EPI_STORE = 0, EPI_ACCUM = 1 };
+
+template <typename WT, int T, int KBW, int G, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const float* __restrict__ A, int lda, int M, int K,
+                                                               const uint4* __restrict__ Wp, int N,
+                                                               float* __restrict__ Y, int ldy, int epi) {
+    typedef WTraits<WT> TR;
+    typedef typename AFrag<WT>::type afrag_t;
+    constexpr int RPL = TR::RPL;
+    static_assert(G * T * RPL <= 16, "LDS reduction buffer limited to 64 KiB");
+    __shared__ float red[NW * G * T * 64 * RPL];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kblks = K / TR::KB;
+    const int ntiles = N / 16;
+    const int t_begin = (int)(((long long)blockIdx.x * ntiles) / gridDim.x);
+    const int t_end = (int)(((long long)(blockIdx.x + 1) * ntiles) / gridDim.x);
+    const int npass = (kblks + NW * KBW - 1) / (NW * KBW);
+
+    for (int tg = t_begin; tg < t_end; tg += G) {
+        const int ng = min(G, t_end - tg);
+        f32x4_t acc[G][T];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt) acc[g][tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        for (int pass = 0; pass < npass; ++pass) {
+            const int kb0 = (pass * NW + wave) * KBW;
+            const int nkb = max(0, min(KBW, kblks - kb0));       // wave-uniform
+            if (nkb == 0) continue;
+            afrag_t af[T][KBW];
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+                for (int j = 0; j < KBW; ++j) {
+                    if (j < nkb) load_afrag(af[tt][j], A, lda, M, tt, kb0 + j, lane);
+                    else load_afrag(af[tt][j], A, lda, 0, tt, 0, lane);   // zeros
+                }
+            uint4 wb[2][KBW];
+            const uint4* wp = Wp + ((size_t)tg * kblks + kb0) * 64 + lane;
+#pragma unroll
+            for (int j = 0; j < KBW; ++j)
+                if (j < nkb) wb[0][j] = wp[(size_t)j * 64]; else wb[0][j] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (g < ng) {
+                    if (g + 1 < ng) {
+                        const uint4* wn = wp + (size_t)(g + 1) * kblks * 64;
+#pragma unroll
+                        for (int j = 0; j < KBW; ++j)
+                            if (j < nkb) wb[(g + 1) & 1][j] = wn[(size_t)j * 64]; else wb[(g + 1) & 1][j] = make_uint4(0, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int j = 0; j < KBW; ++j)
+#pragma unroll
+                        for (int tt = 0; tt < T; ++tt) mfma_block(acc[g][tt], af[tt][j], wb[g & 1][j]);
+                }
+            }
+        }
+        // cross-wave reduction through LDS: red[wave][g][tt][lane][r]
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt) {
+                float* dst = red + ((((size_t)wave * G + g) * T + tt) * 64 + lane) * RPL;
+                if constexpr (RPL == 2) {
+                    dst[0] = acc[g][tt][0] + acc[g][tt][2];          // hi + lo of real row 2a
+                    dst[1] = acc[g][tt][1] + acc[g][tt][3];          // hi + lo of real row 2a+1
+                } else {
+                    dst[0] = acc[g][tt][0]; dst[1] = acc[g][tt][1]; dst[2] = acc[g][tt][2]; dst[3] = acc[g][tt][3];
+                }
+            }
+        __syncthreads();
+        constexpr int PER_WAVE = G * T * 64 * RPL;
+        for (int idx = threadIdx.x; idx < PER_WAVE; idx += NW * 64) {
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) s += red[(size_t)w * PER_WAVE + idx];
+            const int r = idx % RPL;
+            const int ln = (idx / RPL) & 63;
+            const int tt = (idx / (RPL * 64)) % T;
+            const int g = idx / (RPL * 64 * T);
+            const int row = tt * TR::ROWS + RPL * (ln >> 4) + r;
+            const int col = (tg + g) * 16 + (ln & 15);
+            if (g < ng && row < M) {
+                float* y = Y + (size_t)row * ldy + col;
+                *y = (epi == EPI_ACCUM) ? (*y + s) : s;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Row-wise small kernels (activations are a few rows of fp32; these are launch-bound, not
+// bandwidth-bound)
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// h[row] += delta[row] (if delta), then out[row] = h[row] * gain / sqrt(mean(h^2) + eps).
+// One workgroup (256 threads) per row.
+template <typename WT>
+__global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h, int ldh, const float* __restrict__ delta,
+                                                           int ldd, const WT* __restrict__ gain, float* __restrict__ out,
+                                                           int ldo, int d, float eps) {
+    __shared__ float part[4];
+    const int row = blockIdx.x;
+    float* hr = h + (size_t)row * ldh;
+    const float* dr = delta ? delta + (size_t)row * ldd : nullptr;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) {
+        float x = hr[c];
+        if (dr) { x += dr[c]; hr[c] = x; }
+        ss += x * x;
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = part[0] + part[1] + part[2] + part[3];
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    float* o = out + (size_t)row * ldo;
+    for (int c = threadIdx.x; c < d; c += 256) o[c] = hr[c] * to_f32(gain[c]) * inv;
+}
+
+// out[row] = h[row] + delta[row]
+__global__ void add_rows_kernel(const float* __restrict__ h, int ldh, const float* __restrict__ delta, int ldd,
+                                float* __restrict__ out, int ldo, int d) {
+    const int row = blockIdx.x;
+    for (int c = threadIdx.x; c < d; c += blockDim.x)
+        out[(size_t)row * ldo + c] = h[(size_t)row * ldh + c] + delta[(size_t)row * ldd + c];
+}
+
+// u[row] += rho[idx]   (residual vector of the row: step-dependent bias correction)
+template <typename WT>
+__global__ void add_rho_kernel(float* __restrict__ u, int ldu, const WT* __restrict__ rho, int idx, int d) {
+    const int row = blockIdx.x;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) u[(size_t)row * ldu + c] += to_f32(rho[(size_t)idx * d + c]);
+}
+
+// act[row][c] = silu(gu[row][c]) * gu[row][F + c]
+__global__ void silu_mul_kernel(const float* __restrict__ gu, float* __restrict__ act, int F) {
+    const int row = blockIdx.x;
+    for (int c = threadIdx.x; c < F; c += blockDim.x) {
+        const float g = gu[(size_t)row * 2 * F + c], u = gu[(size_t)row * 2 * F + F + c];
+        act[(size_t)row * F + c] = g / (1.0f + expf(-g)) * u;
+    }
+}
+
+// RoPE (rotate-half pairing) on q and k of the fused qkv rows, then append k, v to the cache.
+// Row r belongs to sequence seq0 + r / m and sits at position base[seq] + offset + r % m, which is
+// both its rotary position and its slot in the cache.  Cache layout: [seq][Hkv][maxL][HD].
+// The angle is evaluated in double so that large positions keep full fp32 accuracy.
+template <typename ST>
+__global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int HD, const int* __restrict__ base,
+                                   int offset, int seq0, int m, ST* __restrict__ kc, ST* __restrict__ vc, int maxL,
+                                   float theta) {
+    const int row = blockIdx.x;
+    const int seq = seq0 + row / m;
+    const int pos = base[seq] + offset + row % m;
+    const int half = HD / 2;
+    float* r = qkv + (size_t)row * (Hq + 2 * Hkv) * HD;
+    const int npair = (Hq + Hkv) * half;
+    for (int idx = threadIdx.x; idx < npair; idx += blockDim.x) {
+        const int head = idx / half, i = idx % half;
+        const double inv_freq = exp2(-2.0 * (double)i / (double)HD * log2((double)theta));
+        double s, c;
+        sincos((double)pos * inv_freq, &s, &c);
+        float* x = r + (size_t)head * HD;
+        const float x1 = x[i], x2 = x[i + half];
+        const float y1 = (float)((double)x1 * c - (double)x2 * s);
+        const float y2 = (float)((double)x2 * c + (double)x1 * s);
+        if (head < Hq) {
+            x[i] = y1; x[i + half] = y2;
+        } else {
+            ST* dst = kc + (((size_t)seq * Hkv + (head - Hq)) * maxL + pos) * HD;
+            from_f32(dst[i], y1); from_f32(dst[i + half], y2);
+        }
+    }
+    const float* v = r + (size_t)(Hq + Hkv) * HD;
+    for (int idx = threadIdx.x; idx < Hkv * HD; idx += blockDim.x) {
+        const int head = idx / HD, c = idx % HD;
+        from_f32(vc[(((size_t)seq * Hkv + head) * maxL + pos) * HD + c], v[idx]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Attention of a few query rows against a long cached K/V (verify: K+1 rows; draft: 1 row;
+// prefill chunks: up to 16 rows of one head).  A work item is (sequence, kv head, a range of
+// query heads of that kv head, a range of rows) with at most RMAX (head,row) pairs; it is
+// processed by `nsplit` workgroups x 4 wavefronts, each wavefront taking every (4*nsplit)-th
+// tile of 64 keys and writing an (unnormalised accumulator, max, sum) partial; a second kernel
+// merges the partials in a fixed order.
+// Query row i of a sequence sits at position base[seq] + offset + i and sees keys 0..position.
+// ------------------------------------------------------------------------------------------
+constexpr int ATT_RMAX = 16;
+
+struct AttnShape {
+    int Hq, Hkv, m;          // m rows per sequence in this pass
+    int gh, mi;              // query heads / rows per work item (gh*mi <= ATT_RMAX)
+    int n_hblk, n_rblk;      // ceil(group/gh), ceil(m/mi)
+    int seq0, offset, maxL, nsplit;
+    int ldq;                 // row stride of the q buffer
+};
+
+template <typename ST, int HD>
+__global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restrict__ q, const ST* __restrict__ kc,
+                                                            const ST* __restrict__ vc, const int* __restrict__ base,
+                                                            AttnShape sh, float* __restrict__ ws) {
+    constexpr int CH = 16 / sizeof(ST);          // elements per 16-byte chunk
+    constexpr int DPL = HD / 64;                 // value dims per lane
+    __shared__ float qs[ATT_RMAX * HD];
+    __shared__ float pw[4][ATT_RMAX][64];
+
+    int item = blockIdx.x;
+    const int rblk = item % sh.n_rblk; item /= sh.n_rblk;
+    const int hblk = item % sh.n_hblk; item /= sh.n_hblk;
+    const int kvh = item % sh.Hkv;
+    const int sl = item / sh.Hkv;                 // local sequence index
+    const int seq = sh.seq0 + sl;
+    const int group = sh.Hq / sh.Hkv;
+    const int h0 = hblk * sh.gh, nh = min(sh.gh, group - h0);
+    const int i0 = rblk * sh.mi, ni = min(sh.mi, sh.m - i0);
+    const int R = nh * ni;
+    const int pos0 = base[seq] + sh.offset;       // position of row 0 of this sequence
+    const int nkeys = pos0 + i0 + ni;             // keys visible to the last row of the item
+    const int ntiles = (nkeys + 63) / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int slot = blockIdx.y * 4 + wave, nslots = sh.nsplit * 4;
+    const float scale = rsqrtf((float)HD);
+
+    for (int idx = threadIdx.x; idx < R * HD; idx += 256) {
+        const int r = idx / HD, c = idx % HD;
+        const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
+        qs[idx] = q[(size_t)(sl * sh.m + i) * sh.ldq + (size_t)hh * HD + c] * scale;
+    }
+    __syncthreads();
+
+    const ST* kbase = kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
+    const ST* vbase = vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
+
+    float mrun[ATT_RMAX], lrun[ATT_RMAX], acc[ATT_RMAX][DPL];
+#pragma unroll
+    for (int r = 0; r < ATT_RMAX; ++r) {
+        mrun[r] = -INFINITY; lrun[r] = 0.f;
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) acc[r][e] = 0.f;
+    }
+
+    for (int ti = slot; ti < ntiles; ti += nslots) {
+        const int j = ti * 64 + lane;
+        const bool valid = j < nkeys;
+        float s[ATT_RMAX];
+#pragma unroll
+        for (int r = 0; r < ATT_RMAX; ++r) s[r] = 0.f;
+        if (valid) {
+            const uint4* kp = reinterpret_cast<const uint4*>(kbase + (size_t)j * HD);
+#pragma unroll 4
+            for (int c = 0; c < HD / CH; ++c) {
+                const uint4 raw = kp[c];
+                float kf[CH];
+                if constexpr (sizeof(ST) == 2) {
+                    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        kf[2 * e] = __uint_as_float(w[e] << 16);
+                        kf[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+                    }
+                } else {
+                    kf[0] = __uint_as_float(raw.x); kf[1] = __uint_as_float(raw.y);
+                    kf[2] = __uint_as_float(raw.z); kf[3] = __uint_as_float(raw.w);
+                }
+#pragma unroll
+                for (int r = 0; r < ATT_RMAX; ++r) {
+                    if (r < R) {
+                        const float* qr = qs + r * HD + c * CH;
+#pragma unroll
+                        for (int e = 0; e < CH; ++e) s[r] += qr[e] * kf[e];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < ATT_RMAX; ++r) {
+            if (r < R) {
+                const int qpos = pos0 + i0 + r % ni;
+                const float sv = (valid && j <= qpos) ? s[r] : -INFINITY;
+                const float tmax = wave_max(sv);
+                const float mnew = fmaxf(mrun[r], tmax);
+                float alpha = 1.f, p = 0.f;
+                if (mnew != -INFINITY) {
+                    alpha = (mrun[r] == -INFINITY) ? 0.f : __expf(mrun[r] - mnew);
+                    p = (sv == -INFINITY) ? 0.f : __expf(sv - mnew);
+                }
+                mrun[r] = mnew;
+                lrun[r] = lrun[r] * alpha + p;
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) acc[r][e] *= alpha;
+                pw[wave][r][lane] = p;
+            }
+        }
+        // the probabilities of this wavefront's tile are read back by the same wavefront only
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int nk = min(64, nkeys - ti * 64);
+        for (int jj = 0; jj < nk; ++jj) {
+            float vf[DPL];
+            const ST* vp = vbase + (size_t)(ti * 64 + jj) * HD + lane * DPL;
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) vf[e] = to_f32(vp[e]);
+#pragma unroll
+            for (int r = 0; r < ATT_RMAX; ++r) {
+                if (r < R) {
+                    const float p = pw[wave][r][jj];
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) acc[r][e] += p * vf[e];
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    // partial: ws[(item * nslots + slot)][r][HD + 2]
+    float* out = ws + ((size_t)blockIdx.x * nslots + slot) * ATT_RMAX * (HD + 2);
+#pragma unroll
+    for (int r = 0; r < ATT_RMAX; ++r) {
+        if (r < R) {
+            const float lsum = wave_sum(lrun[r]);
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) out[r * (HD + 2) + lane * DPL + e] = acc[r][e];
+            if (lane == 0) { out[r * (HD + 2) + HD] = mrun[r]; out[r * (HD + 2) + HD + 1] = lsum; }
+        }
+    }
+}
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ ws, AttnShape sh,
+                                                          float* __restrict__ out, int ldo) {
+    int item = blockIdx.x;
+    const int rblk = item % sh.n_rblk; item /= sh.n_rblk;
+    const int hblk = item % sh.n_hblk; item /= sh.n_hblk;
+    const int kvh = item % sh.Hkv;
+    const int sl = item / sh.Hkv;
+    const int group = sh.Hq / sh.Hkv;
+    const int h0 = hblk * sh.gh, nh = min(sh.gh, group - h0);
+    const int i0 = rblk * sh.mi, ni = min(sh.mi, sh.m - i0);
+    const int R = nh * ni;
+    const int nslots = sh.nsplit * 4;
+    const float* base = ws + (size_t)blockIdx.x * nslots * ATT_RMAX * (HD + 2);
+    for (int idx = threadIdx.x; idx < R * HD; idx += 256) {
+        const int r = idx / HD, c = idx % HD;
+        float mx = -INFINITY;
+        for (int s = 0; s < nslots; ++s) mx = fmaxf(mx, base[((size_t)s * ATT_RMAX + r) * (HD + 2) + HD]);
+        float num = 0.f, den = 0.f;
+        for (int s = 0; s < nslots; ++s) {
+            const float* p = base + ((size_t)s * ATT_RMAX + r) * (HD + 2);
+            const float ms = p[HD];
+            if (ms == -INFINITY) continue;
+            const float w = __expf(ms - mx);
+            num += p[c] * w; den += p[HD + 1] * w;
+        }
+        const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
+        out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c] = num / den;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Token-level kernels
+// ------------------------------------------------------------------------------------------
+// Greedy token per row: index of the largest logit, lowest index on ties.  One workgroup per row.
+__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int V, int32_t* __restrict__ out,
+                                                      int out_stride) {
+    __shared__ float bv[4];
+    __shared__ int bi[4];
+    const int row = blockIdx.x;
+    const float* l = logits + (size_t)row * V;
+    float best = -INFINITY; int besti = 0x7FFFFFFF;
+    for (int c = threadIdx.x; c < V; c += 256) {
+        const float x = l[c];
+        if (x > best || (x == best && c < besti)) { best = x; besti = c; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o, 64); const int oi = __shfl_xor(besti, o, 64);
+        if (ov > best || (ov == best && oi < besti)) { best = ov; besti = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = besti; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w)
+            if (bv[w] > best || (bv[w] == best && bi[w] < besti)) { best = bv[w]; besti = bi[w]; }
+        out[(size_t)row * out_stride] = besti;
+    }
+}
+
+// rows[r][0..d) = table[ids[r]]  (embedding gather, converted to fp32)
+template <typename WT>
+__global__ void gather_rows_kernel(const WT* __restrict__ table, const int32_t* __restrict__ ids, int id_stride,
+                                   float* __restrict__ out, int ldo, int d) {
+    const int row = blockIdx.x;
+    const WT* src = table + (size_t)ids[(size_t)row * id_stride] * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) out[(size_t)row * ldo + c] = to_f32(src[c]);
+}
+
+// Prefill input rows of one sequence: position p < v -> visual embedding p, else Embed(text[p - v]).
+template <typename WT>
+__global__ void prefill_rows_kernel(const WT* __restrict__ vis, int v, const WT* __restrict__ table,
+                                    const int32_t* __restrict__ text, int p0, float* __restrict__ out, int d) {
+    const int p = p0 + blockIdx.x;
+    const WT* src = (p < v) ? vis + (size_t)p * d : table + (size_t)text[p - v] * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) out[(size_t)blockIdx.x * d + c] = to_f32(src[c]);
+}
+
+// Fusion input rows [f_j ; Embed(x_{j+1})] for drafter prefill rows j0.. of one sequence.
+template <typename WT>
+__global__ void fuse_rows_kernel(const float* __restrict__ feat, const WT* __restrict__ table,
+                                 const int32_t* __restrict__ text, int j0, float* __restrict__ cat, int d) {
+    const int j = j0 + blockIdx.x;
+    const float* f = feat + (size_t)j * d;
+    const WT* e = table + (size_t)text[j + 1] * d;
+    float* o = cat + (size_t)blockIdx.x * 2 * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) { o[c] = f[c]; o[d + c] = to_f32(e[c]); }
+}
+
+// Verify input tokens: row 0 of sequence b = last known text token, rows 1..K = its drafts.
+__global__ void verify_tokens_kernel(const int32_t* __restrict__ text, int text_stride, const int* __restrict__ dlen,
+                                     const int32_t* __restrict__ drafts, int kmax, int K, int32_t* __restrict__ rows,
+                                     int B) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * (K + 1)) return;
+    const int b = idx / (K + 1), i = idx % (K + 1);
+    rows[idx] = (i == 0) ? text[(size_t)b * text_stride + dlen[b]] : drafts[b * kmax + i - 1];
+}
+
+// Greedy acceptance: one wavefront per sequence.  Lane i < K compares draft i with the target's
+// token for the same position; the accepted length is the number of leading matches, read off
+// the ballot mask.  Also emits tokens, appends them to the text, advances the target length and
+// prepares the tokens that follow each re-fed row.
+__global__ __launch_bounds__(64) void accept_kernel(const int32_t* __restrict__ drafts, const int32_t* __restrict__ tt,
+                                                     int kmax, int K, int32_t* __restrict__ text, int text_stride,
+                                                     const int* __restrict__ dlen, int* __restrict__ tlen,
+                                                     int32_t* __restrict__ nacc, int32_t* __restrict__ out_tokens,
+                                                     int32_t* __restrict__ next_tok) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const bool match = (lane < K) ? (drafts[b * kmax + lane] == tt[b * (kmax + 1) + lane]) : false;
+    const unsigned long long mism = ~__ballot(match);
+    const int n = min(K, (int)__builtin_ctzll(mism | (1ull << 63)));
+    if (lane <= kmax) {
+        int tok = -1;
+        if (lane < n) tok = drafts[b * kmax + lane];
+        else if (lane == n) tok = tt[b * (kmax + 1) + n];
+        out_tokens[b * (kmax + 1) + lane] = tok;
+        if (lane <= n) text[(size_t)b * text_stride + dlen[b] + 1 + lane] = tok;
+        if (lane <= K) {
+            const int e = min(lane, n);
+            next_tok[b * (kmax + 1) + lane] = (e < n) ? drafts[b * kmax + e] : tt[b * (kmax + 1) + n];
+        }
+    }
+    if (lane == 0) { nacc[b] = n; tlen[b] += n + 1; }
+}
+
+// After the re-feed: the drafter's pending hidden state is its output at row n_b; its cache keeps n_b+1 rows.
+__global__ void select_row_kernel(const float* __restrict__ dout, int m, const int32_t* __restrict__ nacc,
+                                  float* __restrict__ fnext, int ldf, int* __restrict__ dlen, int d) {
+    const int b = blockIdx.x;
+    const int n = nacc[b];
+    for (int c = threadIdx.x; c < d; c += blockDim.x) fnext[(size_t)b * ldf + c] = dout[((size_t)b * m + n) * d + c];
+    if (threadIdx.x == 0) dlen[b] += n + 1;
+}
+
+__global__ void set_ints_kernel(int* __restrict__ p, int n, int val) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = val;
+}
+
+__global__ void copy_rows_kernel(const float* __restrict__ src, int lds, float* __restrict__ dst, int ldd, int d) {
+    const int row = blockIdx.x;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) dst[(size_t)row * ldd + c] = src[(size_t)row * lds + c];
+}
+
+}  // namespace hivis

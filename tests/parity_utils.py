@@ -1,0 +1,113 @@
+"""Drives the HIP library and the CPU oracle side by side on the same seeded inputs.
+
+The oracle runs in follow mode: every cycle it is handed the library's drafts and emitted
+tokens, recomputes everything on its own state, and the comparison is made on logits
+(tolerance) and on tokens (bit-exact unless the oracle's top-2 logit gap at that position is
+below the tolerance, in which case either of the two near-tied tokens is accepted)."""
+import numpy as np
+
+from oracle import HivisOracle, accept_length, top2_gap
+
+
+def logit_tol(cfg, ref_logits):
+    """max-abs tolerance: 1e-4 for fp32 models, 3e-2 * RMS(logits) for bf16 models."""
+    if cfg.dtype == "f32":
+        return 1e-4
+    return 3e-2 * float(np.sqrt(np.mean(np.asarray(ref_logits, np.float64) ** 2)))
+
+
+def check_token(tok, ref_logits_row, tol):
+    """tok must be the oracle's argmax, or within `tol` of it when the top-2 gap is below tol."""
+    ref = int(np.argmax(ref_logits_row))
+    if int(tok) == ref:
+        return False
+    gap = float(ref_logits_row[ref] - ref_logits_row[int(tok)])
+    assert gap <= 2 * tol, f"token {tok} differs from oracle argmax {ref} with logit gap {gap} > {2 * tol}"
+    return True   # near-tie
+
+
+class SideBySide:
+    def __init__(self, cfg, weights, hv, vis, ids):
+        self.cfg, self.hv = cfg, hv
+        self.B = ids.shape[0]
+        self.oracles = [HivisOracle(cfg, weights) for _ in range(self.B)]
+        self.near_ties = 0
+        self.max_err = {"prefill": 0.0, "draft": 0.0, "verify": 0.0, "g": 0.0, "fnext": 0.0}
+        first = hv.prefill(vis, ids)
+        plog = hv.get_logits(2)
+        for b, o in enumerate(self.oracles):
+            x, logits = o.prefill(vis[b], ids[b])
+            tol = logit_tol(cfg, logits)
+            err = float(np.max(np.abs(plog[b] - logits)))
+            self.max_err["prefill"] = max(self.max_err["prefill"], err / tol)
+            assert err <= tol, f"prefill logits off by {err} > {tol}"
+            if check_token(first[b], logits, tol):
+                self.near_ties += 1
+                o.text[-1] = int(first[b])
+                # the drafter prefill row l used the other token: rebuild the oracle from the library's token
+                raise AssertionError("near-tie at the first token: pick another seed for this test")
+        self.first = first
+        self._check_fnext()
+        self.emitted = [[int(first[b])] for b in range(self.B)]
+
+    def _check_fnext(self):
+        f = self.hv.get_hidden(1)
+        for b, o in enumerate(self.oracles):
+            scale = float(np.sqrt(np.mean(o.f_next ** 2)))
+            rel = float(np.max(np.abs(f[b] - o.f_next))) / max(scale, 1e-30)
+            lim = 2e-4 if self.cfg.dtype == "f32" else 6e-2
+            self.max_err["fnext"] = max(self.max_err["fnext"], rel / lim)
+            assert rel <= lim, f"drafter pending hidden state off by {rel} (relative to its RMS)"
+
+    def cycle(self, K, planted=None):
+        """planted: [B][K] drafts to plant, or None to let the library draft."""
+        cfg, hv = self.cfg, self.hv
+        if planted is None:
+            hv.draft(K)
+        else:
+            hv.set_drafts(planted)
+        hv.verify()
+        drafts, ttok = hv.get_tokens()
+        vlog = hv.get_logits(0)
+        g = hv.get_hidden(0)
+        dlog = hv.get_logits(1) if planted is None else None
+        n, toks = hv.accept()
+        tl, dl = hv.kv_lengths()
+        out = []
+        for b, o in enumerate(self.oracles):
+            # --- drafts: oracle follows the library's tokens, logits compared step by step
+            if planted is None:
+                _, ologits = o.draft(K, follow=drafts[b])
+                tol = logit_tol(cfg, ologits)
+                err = float(np.max(np.abs(dlog[:, b, :] - ologits)))
+                self.max_err["draft"] = max(self.max_err["draft"], err / tol)
+                assert err <= tol, f"draft logits off by {err} > {tol}"
+                for i in range(K):
+                    self.near_ties += check_token(drafts[b, i], ologits[i], tol)
+            else:
+                assert list(drafts[b]) == [int(t) for t in planted[b]]
+            # --- verify
+            og, ologits, ot = o.verify(drafts[b])
+            tol = logit_tol(cfg, ologits)
+            err = float(np.max(np.abs(vlog[b] - ologits)))
+            self.max_err["verify"] = max(self.max_err["verify"], err / tol)
+            assert err <= tol, f"verify logits off by {err} > {tol}"
+            gscale = float(np.sqrt(np.mean(og ** 2)))
+            gerr = float(np.max(np.abs(g[b] - og))) / gscale
+            glim = 1e-4 if cfg.dtype == "f32" else 6e-2
+            self.max_err["g"] = max(self.max_err["g"], gerr / glim)
+            assert gerr <= glim, f"verify features off by {gerr}"
+            for i in range(K + 1):
+                self.near_ties += check_token(ttok[b, i], ologits[i], tol)
+            # --- acceptance: bit-exact given the library's own target tokens
+            n_exp = accept_length(drafts[b], ttok[b, :K])
+            assert int(n[b]) == n_exp, f"accepted length {n[b]} != {n_exp}"
+            exp_tokens = [int(t) for t in drafts[b, :n_exp]] + [int(ttok[b, n_exp])]
+            assert [int(t) for t in toks[b, :n_exp + 1]] == exp_tokens
+            assert all(int(t) == -1 for t in toks[b, n_exp + 1:])
+            o.accept(drafts[b], og, ot, force=(n_exp, exp_tokens))
+            assert int(tl[b]) == o.target.kv_len and int(dl[b]) == o.drafter.kv_len == o.l
+            self.emitted[b] += exp_tokens
+            out.append({"n": n_exp, "emitted": exp_tokens, "oracle_tokens": ot, "drafts": [int(t) for t in drafts[b]]})
+        self._check_fnext()
+        return out

@@ -1,0 +1,135 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs (tokens bit-exact up to near-ties, logits within the stated tolerance)."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import greedy_reference
+from parity_utils import SideBySide
+
+pytestmark = pytest.mark.gpu
+
+
+def make(cfg, seed):
+    from paper_2509_23928_amd import Hivis
+    w = synth.make_weights(cfg, seed=seed)
+    vis, ids = synth.make_prompt(cfg, seed=seed)
+    hv = Hivis(cfg, w)
+    return w, vis, ids, hv
+
+
+def small_bf16(**kw):
+    base = dict(name="small-bf16", n_layers=2, d=512, n_q_heads=4, n_kv_heads=4, head_dim=128, ffn=1376, vocab=2048,
+                dtype="bf16", n_vis=150, n_text=37, K=5, batch=1, gen_tokens=0, gen_cycles=6)
+    base.update(kw)
+    return synth.HivisConfig(**base)
+
+
+def test_c1_end_to_end_own_drafts():
+    cfg = synth.get_config("C1")
+    w, vis, ids, hv = make(cfg, 0)
+    sbs = SideBySide(cfg, w, hv, vis, ids)
+    for c in range(cfg.gen_cycles):
+        sbs.cycle(cfg.K)
+    print("C1 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    # lossless: the emitted stream is the plain greedy decode of the target
+    ref, _ = greedy_reference(cfg, w, vis[0], ids[0], len(sbs.emitted[0]))
+    if sbs.near_ties == 0:
+        assert sbs.emitted[0] == ref
+
+
+def test_c1_planted_drafts_accept_lengths():
+    cfg = synth.get_config("C1")
+    w, vis, ids, hv = make(cfg, 1)
+    ref, _ = greedy_reference(cfg, w, vis[0], ids[0], 1 + 10 * (cfg.K + 1))
+    sbs = SideBySide(cfg, w, hv, vis, ids)
+    plan = [0, 1, 2, 3, 4, 4, 2, 0, 3, 1]
+    for m in plan:
+        done = len(sbs.emitted[0])
+        good = ref[done: done + m]
+        bad = [(ref[done + j] + 1 + j) % cfg.vocab for j in range(m, cfg.K)]
+        r = sbs.cycle(cfg.K, planted=np.array([good + bad], np.int32))
+        if sbs.near_ties == 0:
+            assert r[0]["n"] == m
+    if sbs.near_ties == 0:
+        assert sbs.emitted[0] == ref[: len(sbs.emitted[0])]
+    print("C1 planted max error / tolerance:", sbs.max_err)
+
+
+@pytest.mark.parametrize("variant", ["mha", "gqa", "hd64"])
+def test_small_bf16_end_to_end(variant):
+    if variant == "mha":
+        cfg = small_bf16()
+    elif variant == "gqa":
+        cfg = small_bf16(n_q_heads=7, n_kv_heads=1, d=896, ffn=2368, K=6, n_vis=200, n_text=70, rope_theta=1e6, rms_eps=1e-6)
+    else:
+        cfg = small_bf16(n_q_heads=8, n_kv_heads=4, head_dim=64, K=3)
+    w, vis, ids, hv = make(cfg, 5)
+    sbs = SideBySide(cfg, w, hv, vis, ids)
+    ref, _ = greedy_reference(cfg, w, vis[0], ids[0], 1 + 6 * (cfg.K + 1))
+    for c in range(3):
+        sbs.cycle(cfg.K)
+    for m in [cfg.K, 1, 2]:
+        done = len(sbs.emitted[0])
+        if sbs.emitted[0] != ref[:done]:
+            break                                 # a near-tie moved the trajectory: planted prefixes no longer apply
+        planted = ref[done: done + m] + [(ref[done + j] + 3) % cfg.vocab for j in range(m, cfg.K)]
+        sbs.cycle(cfg.K, planted=np.array([planted], np.int32))
+    print(variant, "max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+
+
+def test_batch_per_sequence_acceptance():
+    cfg = small_bf16(batch=4, K=7, n_vis=90, n_text=45, n_q_heads=4, n_kv_heads=4)
+    w, vis, ids, hv = make(cfg, 9)
+    sbs = SideBySide(cfg, w, hv, vis, ids)
+    refs = [greedy_reference(cfg, w, vis[b], ids[b], 40)[0] for b in range(cfg.batch)]
+    sbs.cycle(cfg.K)
+    plans = [[0, 3, 7, 2], [7, 7, 0, 1], [1, 0, 5, 4]]
+    for plan in plans:
+        planted = []
+        for b in range(cfg.batch):
+            done = len(sbs.emitted[b])
+            ok = sbs.emitted[b] == refs[b][:done]
+            m = plan[b] if ok else 0
+            planted.append(refs[b][done: done + m] + [(refs[b][done + j] + 5) % cfg.vocab for j in range(m, cfg.K)])
+        r = sbs.cycle(cfg.K, planted=np.array(planted, np.int32))
+        if sbs.near_ties == 0:
+            assert [x["n"] for x in r] == plan
+    print("batch max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+
+
+def test_error_codes():
+    from paper_2509_23928_amd import Hivis, HivisError, HIVIS_ESTATE, HIVIS_EINVAL, HIVIS_ECAP
+    cfg = synth.get_config("C1")
+    w, vis, ids, hv = make(cfg, 0)
+    with pytest.raises(HivisError) as e:
+        hv.draft(2)
+    assert e.value.code == HIVIS_ESTATE
+    with pytest.raises(HivisError) as e:
+        hv.verify()
+    assert e.value.code == HIVIS_ESTATE
+    bad = ids.copy(); bad[0, 3] = cfg.vocab
+    with pytest.raises(HivisError) as e:
+        hv.prefill(vis, bad)
+    assert e.value.code == HIVIS_EINVAL
+    hv.prefill(vis, ids)
+    with pytest.raises(HivisError) as e:
+        hv.draft(cfg.K + 1)
+    assert e.value.code == HIVIS_EINVAL
+    with pytest.raises(HivisError) as e:
+        hv.accept()
+    assert e.value.code == HIVIS_ESTATE
+    hv.draft(cfg.K)
+    with pytest.raises(HivisError) as e:
+        hv.draft(cfg.K)
+    assert e.value.code == HIVIS_ESTATE
+    hv.verify(); hv.accept()
+    small = Hivis(cfg, w, max_text=cfg.n_text + cfg.K + 2 + 3)
+    small.prefill(vis, ids)
+    with pytest.raises(HivisError) as e:
+        for _ in range(10):
+            small.draft(cfg.K); small.verify(); small.accept()
+    assert e.value.code == HIVIS_ECAP
+    with pytest.raises(HivisError) as e:
+        small.prefill(np.concatenate([vis, vis], 1), ids)
+    assert e.value.code == HIVIS_ECAP

@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the HiViS draft-verify path on one MI355X.
+
+One "step" = the whole hot path on one batch of synthetic input: target prefill over
+[visual ; text], drafter prefill over the text rows, then draft(K) -> verify -> accept cycles
+until the workload's number of tokens has been generated.  Default workload: the
+LLaVA-1.5-7B-shaped bf16 model (32 layers, d 4096, 576 visual + 64 text rows, K = 5 chain,
+128 generated tokens, batch 1) with seeded random weights.
+
+Prints ONE JSON line: whole-job tokens/s, per-phase latencies from HIP events recorded on the
+library's stream inside the timed region, the HBM roofline of the verify pass (algorithmic
+bytes / event-timed duration vs 8 TB/s), and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+PAPER_TAU = {"C2": 5.37, "C3": 5.06, "C4": 4.39, "C5": 5.15}    # Table 2, T=0 averages (tree drafting, A800): context only
+
+
+def run_step(hv, cfg, vis, ids, K):
+    """prefill + cycles until cfg.gen_tokens tokens (or cfg.gen_cycles cycles).  Returns (tokens, cycles, accepted)."""
+    first = hv.prefill(vis, ids)
+    produced = np.ones(hv.B, np.int64)
+    cycles = 0
+    accepted = 0
+    target = cfg.gen_tokens
+    while True:
+        hv.draft(K)
+        hv.verify()
+        n, _ = hv.accept()
+        produced += n + 1
+        accepted += int(n.sum())
+        cycles += 1
+        if cfg.gen_cycles and cycles >= cfg.gen_cycles:
+            break
+        if target and int(produced.min()) >= target:
+            break
+    tokens = int(np.minimum(produced, target).sum()) if target else int(produced.sum())
+    return tokens, cycles, accepted, first
+
+
+def cpu_baseline(cfg, K, seed, sample_layers=2):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: a `sample_layers`-layer slice of the
+    same widths, same prompt shape; prefill once, then one draft-verify-accept cycle.  The cycle time is scaled to
+    the full depth (target-layer part x N/sample_layers; drafter, LM head and fusion parts are depth-independent)."""
+    from oracle import HivisOracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    scfg = cfg.scaled(n_layers=sample_layers)
+    w = synth.make_weights(scfg, seed=seed, threads=min(16, os.cpu_count() or 1))
+    vis, ids = synth.make_prompt(scfg, seed=seed, batch=1)
+    o = HivisOracle(scfg, w)
+    t0 = time.time()
+    o.prefill(vis[0], ids[0])
+    t_prefill = time.time() - t0
+    t0 = time.time()
+    drafts, _ = o.draft(K)
+    t_draft = time.time() - t0
+    t0 = time.time()
+    g, logits, t = o.verify(drafts)
+    t_verify = time.time() - t0
+    t0 = time.time()
+    n, emitted = o.accept(drafts, g, t)
+    t_accept = time.time() - t0
+    # verify: layers scale with depth; its LM head part does not.  Estimate the LM-head share by timing it alone.
+    t0 = time.time()
+    o.target.logits(g)
+    t_lm = time.time() - t0
+    scale = cfg.n_layers / float(sample_layers)
+    t_verify_full = (t_verify - t_lm) * scale + t_lm
+    cycle_full = t_draft + t_verify_full + t_accept
+    tokens_per_cycle = n + 1
+    return {"value": tokens_per_cycle / cycle_full, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": (f"{sample_layers}-layer slice of the same widths, batch 1: prefill {t_prefill:.1f}s (not counted), one cycle: "
+                       f"{K} draft steps {t_draft:.2f}s + verify {t_verify:.2f}s (layer part scaled x{scale:.0f} -> {t_verify_full:.1f}s) "
+                       f"+ accept/roll {t_accept:.2f}s; float64 numpy"),
+            "draft_step_us": t_draft / K * 1e6, "verify_us": t_verify_full * 1e6}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C2")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of target layers (debug only; invalid as a result)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_23928_amd import Hivis
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+
+    cfg = synth.get_config(args.config)
+    if args.layers:
+        cfg = cfg.scaled(n_layers=args.layers)
+    K = cfg.K
+    t0 = time.time()
+    nthreads = min(16, os.cpu_count() or 1)
+    w = synth.make_weights(cfg, seed=args.seed, bits=(cfg.dtype == "bf16"), threads=nthreads)
+    vis, ids = synth.make_prompt(cfg, seed=args.seed)
+    t_gen = time.time() - t0
+    t0 = time.time()
+    stream = torch.cuda.Stream()
+    hv = Hivis(cfg, w, stream=stream.cuda_stream)
+    del w
+    t_load = time.time() - t0
+    # inputs resident in HBM before the timed region
+    if cfg.dtype == "bf16":
+        vis_dev = torch.from_numpy(synth.to_bf16_bits(vis).reshape(vis.shape).view(np.int16)).cuda()
+    else:
+        vis_dev = torch.from_numpy(vis).cuda()
+    ids_dev = torch.from_numpy(ids).cuda()
+    torch.cuda.synchronize()
+    print(f"[bench] {cfg.name}: weights generated in {t_gen:.1f}s, uploaded+packed in {t_load:.1f}s", file=sys.stderr, flush=True)
+
+    for _ in range(args.warmup):
+        run_step(hv, cfg, vis_dev, ids_dev, K)
+    hv.timing(True)
+    for ph in range(4):
+        hv.phase_ms(ph)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tokens = cycles = accepted = 0
+    for _ in range(args.steps):
+        tk, cy, ac, _ = run_step(hv, cfg, vis_dev, ids_dev, K)
+        tokens += tk; cycles += cy; accepted += ac
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    phases = [hv.phase_ms(ph) for ph in range(4)]
+    hv.timing(False)
+    verify_bytes_end, draft_bytes_end = hv.algorithmic_bytes()
+
+    prefill_ms = phases[0][0] / max(phases[0][1], 1)
+    draft_us = phases[1][0] / max(phases[1][1], 1) / K * 1e3
+    verify_us = phases[2][0] / max(phases[2][1], 1) * 1e3
+    accept_us = phases[3][0] / max(phases[3][1], 1) * 1e3
+    # algorithmic bytes of an average verify / draft step: weights once + KV at the mean length of the run
+    esize = 2 if cfg.dtype == "bf16" else 4
+    kd = cfg.kv_dim
+    gen_per_seq = tokens / args.steps / cfg.batch
+    mean_text = cfg.n_text + gen_per_seq / 2.0
+    w_layer = (2 * cfg.d * cfg.q_dim + 2 * cfg.d * kd + 3 * cfg.d * cfg.ffn) * esize
+    verify_bytes = cfg.n_layers * w_layer + cfg.vocab * cfg.d * esize + cfg.batch * cfg.n_layers * 2 * (cfg.n_vis + mean_text) * kd * esize
+    draft_bytes = w_layer + 2 * cfg.d * cfg.d * esize + cfg.vocab * cfg.d * esize + cfg.batch * 2 * mean_text * kd * esize
+    verify_gbs = verify_bytes / (verify_us * 1e-6) / 1e9
+    draft_gbs = draft_bytes / (draft_us * 1e-6) / 1e9
+
+    out = {
+        "metric": "tokens/s at fixed K (draft+verify cycles incl. prefill), with draft/verify step latency and HBM GB/s",
+        "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.config}: {cfg.name} N={cfg.n_layers} d={cfg.d} Hq/Hkv={cfg.n_q_heads}/{cfg.n_kv_heads} F={cfg.ffn} V={cfg.vocab}, "
+                               f"{cfg.n_vis} visual + {cfg.n_text} text rows, K={K} chain, {cfg.gen_tokens or cfg.gen_cycles * (K + 1)} generated tokens, batch {cfg.batch}, "
+                               "random-init weights (seeded)", "K": K, "batch": cfg.batch},
+        "prefill_ms": prefill_ms, "draft_step_us": draft_us, "verify_us": verify_us, "accept_roll_us": accept_us,
+        "cycle_us": K * draft_us + verify_us + accept_us,
+        "draft_step_hbm_gbs": draft_gbs, "draft_step_frac_of_peak": draft_gbs / HBM_PEAK_GBS,
+        "cycles": cycles, "mean_accepted_drafts": accepted / max(cycles * cfg.batch, 1),
+        "roofline": {"bound": "hbm", "kernel": "hivis_verify pass (all launches of one verify), HIP events on the library stream",
+                     "achieved": verify_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": verify_gbs / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes": verify_bytes},
+    }
+    tau = PAPER_TAU.get(args.config)
+    if tau:
+        out["projected_tokens_per_s_at_paper_tau"] = cfg.batch * tau / ((K * draft_us + verify_us + accept_us) * 1e-6)
+        out["projection_note"] = f"PROJECTION: (paper tau {tau} tokens/cycle, Table 2 T=0 avg, tree drafting on A800) / measured cycle time; random-init drafts are almost never accepted"
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, K, args.seed)
+    hv.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

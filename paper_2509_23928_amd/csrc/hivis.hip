@@ -168,6 +168,7 @@ int gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, i
 template <typename WT>
 int attention(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int* base, int offset, int seq0, int nseq,
               int m, int max_keys, float* out, int ldo) {
+    typedef typename KVType<WT>::type KT;
     const hivis_config& g = c->cfg;
     AttnShape sh{};
     sh.Hq = g.n_q_heads; sh.Hkv = g.n_kv_heads; sh.m = m;
@@ -185,10 +186,10 @@ int attention(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int*
     const size_t need = (size_t)items * nsplit * 4 * ATT_RMAX * (g.head_dim + 2);
     if (need > c->attn_ws_floats) return fail(c, HIVIS_EINVAL, "attention workspace too small (%zu > %zu)", need, c->attn_ws_floats);
     if (g.head_dim == 128) {
-        hipLaunchKernelGGL((attn_partial_kernel<WT, 128>), dim3(items, nsplit), dim3(256), 0, c->stream, q, (const WT*)kv.k, (const WT*)kv.v, base, sh, c->attn_ws);
+        hipLaunchKernelGGL((attn_partial_kernel<KT, 128>), dim3(items, nsplit), dim3(256), 0, c->stream, q, (const KT*)kv.k, (const KT*)kv.v, base, sh, c->attn_ws);
         hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(items), dim3(256), 0, c->stream, c->attn_ws, sh, out, ldo);
     } else {
-        hipLaunchKernelGGL((attn_partial_kernel<WT, 64>), dim3(items, nsplit), dim3(256), 0, c->stream, q, (const WT*)kv.k, (const WT*)kv.v, base, sh, c->attn_ws);
+        hipLaunchKernelGGL((attn_partial_kernel<KT, 64>), dim3(items, nsplit), dim3(256), 0, c->stream, q, (const KT*)kv.k, (const KT*)kv.v, base, sh, c->attn_ws);
         hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(items), dim3(256), 0, c->stream, c->attn_ws, sh, out, ldo);
     }
     HIP_TRY(c, hipGetLastError());
@@ -201,12 +202,13 @@ int attention(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int*
 template <typename WT>
 int layer_forward(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, const float* pending, const int* base,
                   int offset, int seq0, int nseq, int m, int max_keys) {
+    typedef typename KVType<WT>::type KT;
     const hivis_config& g = c->cfg;
     const int M = nseq * m, d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn;
     const int nqkv = qd + 2 * kd;
     hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, pending, d, (const WT*)L.norm1, c->a, d, d, g.rms_eps);
     if (int rc = gemm<WT>(c, c->a, d, M, d, L.wqkv, nqkv, c->qkv, nqkv, EPI_STORE)) return rc;
-    hipLaunchKernelGGL((rope_append_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (WT*)kv.k, (WT*)kv.v, kv.maxL, g.rope_theta);
+    hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
     if (int rc = attention<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, max_keys, c->att, qd)) return rc;
     if (int rc = gemm<WT>(c, c->att, qd, M, qd, L.wo, d, c->proj, d, EPI_STORE)) return rc;
     hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, (const float*)c->proj, d, (const WT*)L.norm2, c->a, d, d, g.rms_eps);
@@ -422,12 +424,12 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     const int maxLt = g.max_vis + g.max_text, maxLd = g.max_text;
     c->tkv.resize(g.n_layers);
     for (int l = 0; l < g.n_layers; ++l) {
-        WT *k, *v;
+        typename KVType<WT>::type *k, *v;
         if ((rc = dev_alloc(c, &k, (size_t)B * kd * maxLt))) return rc;
         if ((rc = dev_alloc(c, &v, (size_t)B * kd * maxLt))) return rc;
         c->tkv[l].k = k; c->tkv[l].v = v; c->tkv[l].maxL = maxLt;
     }
-    { WT *k, *v;
+    { typename KVType<WT>::type *k, *v;
       if ((rc = dev_alloc(c, &k, (size_t)B * kd * maxLd))) return rc;
       if ((rc = dev_alloc(c, &v, (size_t)B * kd * maxLd))) return rc;
       c->dkv.k = k; c->dkv.v = v; c->dkv.maxL = maxLd; }

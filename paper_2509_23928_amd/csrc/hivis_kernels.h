@@ -24,10 +24,37 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round to nearest e
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (bf16_t)(u >> 16);
 }
+typedef _Float16 f16_t;                                   // IEEE half: KV-cache storage of bf16 models
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x); }
+__device__ __forceinline__ float to_f32(f16_t x) { return (float)x; }
 __device__ __forceinline__ void from_f32(float& dst, float x) { dst = x; }
 __device__ __forceinline__ void from_f32(bf16_t& dst, float x) { dst = f32_to_bf16(x); }
+__device__ __forceinline__ void from_f32(f16_t& dst, float x) {   // round to nearest even, saturating
+    dst = (f16_t)fminf(fmaxf(x, -65504.f), 65504.f);
+}
+
+// KV-cache storage type that goes with a weight type.  bf16 models keep K and V in IEEE half:
+// same bytes as bf16, but 10 mantissa bits, which keeps the rounding of V (the dominant
+// low-precision error of the whole pass) an order of magnitude below the parity tolerance.
+template <typename WT> struct KVType;
+template <> struct KVType<bf16_t> { typedef f16_t type; };
+template <> struct KVType<float> { typedef float type; };
+
+// 16 raw bytes of cache -> floats
+__device__ __forceinline__ void decode_chunk(const uint4& raw, float (&kf)[8], f16_t) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const h2 v = __builtin_bit_cast(h2, w[e]);
+        kf[2 * e] = (float)v[0]; kf[2 * e + 1] = (float)v[1];
+    }
+}
+__device__ __forceinline__ void decode_chunk(const uint4& raw, float (&kf)[4], float) {
+    kf[0] = __uint_as_float(raw.x); kf[1] = __uint_as_float(raw.y);
+    kf[2] = __uint_as_float(raw.z); kf[3] = __uint_as_float(raw.w);
+}
 
 // ------------------------------------------------------------------------------------------
 // Streaming layout of a weight matrix W (logical [K][N], y = x W).
@@ -412,17 +439,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
             for (int c = 0; c < HD / CH; ++c) {
                 const uint4 raw = kp[c];
                 float kf[CH];
-                if constexpr (sizeof(ST) == 2) {
-                    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        kf[2 * e] = __uint_as_float(w[e] << 16);
-                        kf[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
-                    }
-                } else {
-                    kf[0] = __uint_as_float(raw.x); kf[1] = __uint_as_float(raw.y);
-                    kf[2] = __uint_as_float(raw.z); kf[3] = __uint_as_float(raw.w);
-                }
+                decode_chunk(raw, kf, ST());
 #pragma unroll
                 for (int r = 0; r < ATT_RMAX; ++r) {
                     if (r < R) {

@@ -95,7 +95,7 @@ template <typename T> int dev_alloc(hivis_ctx* c, T** p, size_t count) {
 // ---- weight upload + re-layout -------------------------------------------------------------
 template <typename WT>
 int pack_matrix(hivis_ctx* c, const void* const* srcs, const int* ncols, int nsrc, int K, int transposed, void* staging,
-                uint4** out) {
+                uint4** out, int mode = PACK_PLAIN) {
     int N = 0;
     PackSrc ps{};
     char* st = (char*)staging;
@@ -107,7 +107,7 @@ int pack_matrix(hivis_ctx* c, const void* const* srcs, const int* ncols, int nsr
         st += (bytes + 255) & ~(size_t)255;
         N += ncols[i];
     }
-    ps.transposed = transposed;
+    ps.transposed = transposed; ps.mode = mode; ps.hd = c->cfg.head_dim;
     const size_t n16 = (size_t)K * N * sizeof(WT) / 16;
     if (int rc = dev_alloc(c, out, n16)) return rc;
     const int blocks = (int)std::min<size_t>((n16 + 255) / 256, 65535);
@@ -135,11 +135,11 @@ int upload_layer(hivis_ctx* c, const hivis_layer_weights& w, void* staging, Laye
     if (int rc = upload_vec<WT>(c, w.norm1, g.d, &L.norm1)) return rc;
     if (int rc = upload_vec<WT>(c, w.norm2, g.d, &L.norm2)) return rc;
     { const void* s[3] = {w.wq, w.wk, w.wv}; int n[3] = {qd, kd, kd};
-      if (int rc = pack_matrix<WT>(c, s, n, 3, g.d, 0, staging, &L.wqkv)) return rc; }
+      if (int rc = pack_matrix<WT>(c, s, n, 3, g.d, 0, staging, &L.wqkv, PACK_QKV)) return rc; }
     { const void* s[1] = {w.wo}; int n[1] = {g.d};
       if (int rc = pack_matrix<WT>(c, s, n, 1, qd, 0, staging, &L.wo)) return rc; }
     { const void* s[2] = {w.wg, w.wu}; int n[2] = {g.ffn, g.ffn};
-      if (int rc = pack_matrix<WT>(c, s, n, 2, g.d, 0, staging, &L.wgu)) return rc; }
+      if (int rc = pack_matrix<WT>(c, s, n, 2, g.d, 0, staging, &L.wgu, PACK_GATEUP)) return rc; }
     { const void* s[1] = {w.wd}; int n[1] = {g.d};
       if (int rc = pack_matrix<WT>(c, s, n, 1, g.ffn, 0, staging, &L.wd)) return rc; }
     return HIVIS_OK;

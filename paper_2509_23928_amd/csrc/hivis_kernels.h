@@ -85,7 +85,16 @@ struct PackSrc {
     const void* p[3];
     int n[3];          // output columns of each source
     int transposed;
+    int mode;          // PACK_PLAIN, PACK_QKV, PACK_GATEUP
+    int hd;            // head_dim (PACK_QKV)
 };
+// Column orders of the packed matrices (chosen so that the GEMM epilogues are local to a 16-column tile):
+//   PACK_QKV    [q heads | k heads | v heads]; inside every q and k head the rotary pair (i, i + hd/2) is
+//               stored in adjacent columns (2i, 2i+1).  q and k are only ever used in dot products with
+//               each other, so the K cache simply keeps this order; v keeps the natural order.
+//   PACK_GATEUP tile t holds gate columns 8t..8t+7 in its first 8 columns and up columns 8t..8t+7 in its
+//               last 8, so silu(gate)*up needs one tile only.
+enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATEUP = 2 };
 
 template <typename WT>
 __global__ void pack_weights_kernel(PackSrc src, int K, int N, uint4* __restrict__ dst) {
@@ -100,7 +109,16 @@ __global__ void pack_weights_kernel(PackSrc src, int K, int N, uint4* __restrict
         const int g = lane >> 4;
         const int k0 = kb * KB + g * EPL;
         int s = 0;
-        while (s < 2 && n >= src.n[s]) { n -= src.n[s]; ++s; }
+        if (src.mode == PACK_GATEUP) {
+            s = (lane & 15) >> 3;                 // 0 = gate, 1 = up
+            n = t * 8 + (lane & 7);
+        } else {
+            while (s < 2 && n >= src.n[s]) { n -= src.n[s]; ++s; }
+            if (src.mode == PACK_QKV && s < 2) {  // q or k: un-interleave the rotary pair
+                const int within = n % src.hd;
+                n = n - within + (within >> 1) + (within & 1) * (src.hd / 2);
+            }
+        }
         const WT* base = (const WT*)src.p[s];
         const int ns = src.n[s];
         WT vals[EPL];
@@ -318,16 +336,17 @@ __global__ void add_rho_kernel(float* __restrict__ u, int ldu, const WT* __restr
     for (int c = threadIdx.x; c < d; c += blockDim.x) u[(size_t)row * ldu + c] += to_f32(rho[(size_t)idx * d + c]);
 }
 
-// act[row][c] = silu(gu[row][c]) * gu[row][F + c]
+// act[row][c] = silu(gate c) * up c, with gate|up interleaved per 16-column tile (PACK_GATEUP order)
 __global__ void silu_mul_kernel(const float* __restrict__ gu, float* __restrict__ act, int F) {
     const int row = blockIdx.x;
     for (int c = threadIdx.x; c < F; c += blockDim.x) {
-        const float g = gu[(size_t)row * 2 * F + c], u = gu[(size_t)row * 2 * F + F + c];
+        const size_t o = (size_t)row * 2 * F + (size_t)(c >> 3) * 16 + (c & 7);
+        const float g = gu[o], u = gu[o + 8];
         act[(size_t)row * F + c] = g / (1.0f + expf(-g)) * u;
     }
 }
 
-// RoPE (rotate-half pairing) on q and k of the fused qkv rows, then append k, v to the cache.
+// RoPE (rotate-half pairing, pairs stored in adjacent columns) on q and k of the fused qkv rows, then append k, v.
 // Row r belongs to sequence seq0 + r / m and sits at position base[seq] + offset + r % m, which is
 // both its rotary position and its slot in the cache.  Cache layout: [seq][Hkv][maxL][HD].
 // The angle is evaluated in double so that large positions keep full fp32 accuracy.
@@ -346,15 +365,15 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int
         const double inv_freq = exp2(-2.0 * (double)i / (double)HD * log2((double)theta));
         double s, c;
         sincos((double)pos * inv_freq, &s, &c);
-        float* x = r + (size_t)head * HD;
-        const float x1 = x[i], x2 = x[i + half];
+        float* x = r + (size_t)head * HD;          // the pair (i, i + hd/2) sits in columns 2i, 2i+1 (PACK_QKV order)
+        const float x1 = x[2 * i], x2 = x[2 * i + 1];
         const float y1 = (float)((double)x1 * c - (double)x2 * s);
         const float y2 = (float)((double)x2 * c + (double)x1 * s);
         if (head < Hq) {
-            x[i] = y1; x[i + half] = y2;
+            x[2 * i] = y1; x[2 * i + 1] = y2;
         } else {
             ST* dst = kc + (((size_t)seq * Hkv + (head - Hq)) * maxL + pos) * HD;
-            from_f32(dst[i], y1); from_f32(dst[i + half], y2);
+            from_f32(dst[2 * i], y1); from_f32(dst[2 * i + 1], y2);
         }
     }
     const float* v = r + (size_t)(Hq + Hkv) * HD;

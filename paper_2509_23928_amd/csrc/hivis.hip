@@ -2,11 +2,14 @@
 // The C ABI is declared and documented in include/hivis.h.
 #include "hivis.h"
 #include "hivis_kernels.h"
+#include "hivis_fused.h"
 
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
+#include <map>
 #include <string>
 #include <vector>
 
@@ -61,6 +64,14 @@ struct hivis_ctx {
     int32_t *row_tok = nullptr, *drafts = nullptr, *ttok = nullptr, *nacc = nullptr, *out_tok = nullptr, *next_tok = nullptr;
     void* vis = nullptr;        // staging for vis_embeds [B][max_vis][d]
     std::vector<int32_t> h_ids;
+
+    // persistent-kernel path (passes of at most one MFMA tile of rows)
+    bool fused = false;
+    int fused_grid = 0; size_t fused_lds = 0;
+    float* rope_tab = nullptr; float* pm = nullptr; int* pi = nullptr; unsigned* bar = nullptr;
+    float* fattn_ws = nullptr; size_t fattn_ws_floats = 0;
+    struct Program { hivis::Phase* dev = nullptr; int n = 0; };
+    std::map<int, Program> programs;     // key = kind * 64 + K
 
     // timing
     bool timing = false;
@@ -176,7 +187,7 @@ int attention(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int*
     if (m >= ATT_RMAX) { sh.mi = ATT_RMAX; sh.gh = 1; }
     else { sh.mi = m; sh.gh = std::max(1, std::min(group, ATT_RMAX / m)); }
     sh.n_hblk = (group + sh.gh - 1) / sh.gh; sh.n_rblk = (m + sh.mi - 1) / sh.mi;
-    sh.seq0 = seq0; sh.offset = offset; sh.maxL = kv.maxL; sh.ldq = ldq;
+    sh.seq0 = seq0; sh.offset = offset; sh.maxL = kv.maxL; sh.ldq = ldq; sh.nwaves = 4;
     const int items = nseq * g.n_kv_heads * sh.n_hblk * sh.n_rblk;
     // enough workgroups to occupy the chip, at most one 64-key tile per wavefront slot
     const int tiles = (max_keys + 63) / 64;
@@ -187,10 +198,10 @@ int attention(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int*
     if (need > c->attn_ws_floats) return fail(c, HIVIS_EINVAL, "attention workspace too small (%zu > %zu)", need, c->attn_ws_floats);
     if (g.head_dim == 128) {
         hipLaunchKernelGGL((attn_partial_kernel<KT, 128>), dim3(items, nsplit), dim3(256), 0, c->stream, q, (const KT*)kv.k, (const KT*)kv.v, base, sh, c->attn_ws);
-        hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(items), dim3(256), 0, c->stream, c->attn_ws, sh, out, ldo);
+        hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(items), dim3(256), 0, c->stream, c->attn_ws, base, sh, out, ldo);
     } else {
         hipLaunchKernelGGL((attn_partial_kernel<KT, 64>), dim3(items, nsplit), dim3(256), 0, c->stream, q, (const KT*)kv.k, (const KT*)kv.v, base, sh, c->attn_ws);
-        hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(items), dim3(256), 0, c->stream, c->attn_ws, sh, out, ldo);
+        hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(items), dim3(256), 0, c->stream, c->attn_ws, base, sh, out, ldo);
     }
     HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;
@@ -251,6 +262,155 @@ int drafter_forward(hivis_ctx* c, const float* cat, int seq0, int nseq, int m, i
     if (int rc = layer_forward<WT>(c, c->draft, c->dkv, c->u, nullptr, c->dlen, offset, seq0, nseq, m, max_keys)) return rc;
     hipLaunchKernelGGL(add_rows_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->u, d, (const float*)c->proj, d, out, ldo, d);
     HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
+
+// ---- persistent-kernel path --------------------------------------------------------------------
+enum { PROG_VERIFY = 0, PROG_DRAFT = 1, PROG_ROLL = 2 };
+
+template <typename WT>
+bool fused_rows_ok(int M) { return M <= WTraits<WT>::ROWS; }
+
+AttnShape fused_attn_shape(hivis_ctx* c, int nseq, int m, int offset, int maxL, int ldq, int* items_out) {
+    const hivis_config& g = c->cfg;
+    AttnShape sh{};
+    sh.Hq = g.n_q_heads; sh.Hkv = g.n_kv_heads; sh.m = m;
+    const int group = g.n_q_heads / g.n_kv_heads;
+    if (m >= FUSED_RMAX) { sh.mi = FUSED_RMAX; sh.gh = 1; }
+    else { sh.mi = m; sh.gh = std::max(1, std::min(group, FUSED_RMAX / m)); }
+    sh.n_hblk = (group + sh.gh - 1) / sh.gh; sh.n_rblk = (m + sh.mi - 1) / sh.mi;
+    sh.seq0 = 0; sh.offset = offset; sh.maxL = maxL; sh.ldq = ldq; sh.nwaves = 16;
+    const int items = nseq * g.n_kv_heads * sh.n_hblk * sh.n_rblk;
+    sh.nsplit = std::max(1, c->fused_grid / items);
+    *items_out = items;
+    return sh;
+}
+
+// phases of one decoder layer on rows h [M][d]; the MLP result is written as dst = h + mlp (dst may be h)
+template <typename WT>
+void layer_phases(hivis_ctx* c, std::vector<Phase>& P, const LayerDev& L, const KVDev& kv, float* h, const int* base,
+                  int offset, int nseq, int m, float* dst, int ldd) {
+    const hivis_config& g = c->cfg;
+    const int d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn, nqkv = qd + 2 * kd;
+    Phase q{}; q.type = PH_GEMM; q.pro = PRO_RMS; q.epi = FEPI_QKV; q.K = d; q.N = nqkv; q.W = L.wqkv; q.A = h; q.lda = d;
+    q.gain = L.norm1; q.Y = c->qkv; q.ldy = nqkv; q.kc = kv.k; q.vc = kv.v; q.maxL = kv.maxL; q.base = base; q.offset = offset;
+    P.push_back(q);
+    Phase a{}; a.type = PH_ATTN; a.A = c->qkv; a.lda = nqkv; a.kc = kv.k; a.vc = kv.v; a.maxL = kv.maxL; a.base = base; a.offset = offset;
+    a.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, nqkv, &a.att_items);
+    P.push_back(a);
+    Phase mg = a; mg.type = PH_ATTN_MERGE; mg.Y = c->att; mg.ldy = qd;
+    P.push_back(mg);
+    Phase o{}; o.type = PH_GEMM; o.pro = PRO_PLAIN; o.epi = FEPI_ADD_TO; o.K = qd; o.N = d; o.W = L.wo; o.A = c->att; o.lda = qd;
+    o.Y = h; o.ldy = d; o.R = h; o.ldr = d;
+    P.push_back(o);
+    Phase gu{}; gu.type = PH_GEMM; gu.pro = PRO_RMS; gu.epi = FEPI_SILU; gu.K = d; gu.N = 2 * F; gu.W = L.wgu; gu.A = h; gu.lda = d;
+    gu.gain = L.norm2; gu.Y = c->act; gu.ldy = F;
+    P.push_back(gu);
+    Phase dn{}; dn.type = PH_GEMM; dn.pro = PRO_PLAIN; dn.epi = FEPI_ADD_TO; dn.K = F; dn.N = d; dn.W = L.wd; dn.A = c->act; dn.lda = F;
+    dn.Y = dst; dn.ldy = ldd; dn.R = h; dn.ldr = d;
+    P.push_back(dn);
+}
+
+template <typename WT>
+int get_program(hivis_ctx* c, int kind, int K, hivis_ctx::Program* out) {
+    const int key = kind * 64 + K;
+    auto it = c->programs.find(key);
+    if (it != c->programs.end()) { *out = it->second; return HIVIS_OK; }
+    const hivis_config& g = c->cfg;
+    const int B = g.batch, d = g.d, V = g.vocab;
+    std::vector<Phase> P;
+    if (kind == PROG_VERIFY) {
+        const int m = K + 1;
+        Phase pr{}; pr.type = PH_PREP; pr.ids = c->row_tok; pr.id_sseq = m; pr.id_srow = 1; pr.gain = c->embed; pr.Y = c->x; pr.ldy = d;
+        pr.base = c->tlen; pr.offset = 0;
+        P.push_back(pr);
+        for (int l = 0; l < g.n_layers; ++l) layer_phases<WT>(c, P, c->layers[l], c->tkv[l], c->x, c->tlen, 0, B, m, c->x, d);
+        Phase nr{}; nr.type = PH_NORM_ROWS; nr.A = c->x; nr.lda = d; nr.gain = c->final_norm; nr.Y = c->catT; nr.ldy = 2 * d;
+        P.push_back(nr);
+        Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = c->catT; lm.lda = 2 * d;
+        lm.Y = c->logits_v; lm.ldy = V;
+        P.push_back(lm);
+        Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->ttok; am.o_sseq = g.k_max + 1; am.o_srow = 1;
+        P.push_back(am);
+    } else if (kind == PROG_DRAFT) {
+        for (int i = 1; i <= K; ++i) {
+            Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = c->catD; lm.lda = 2 * d;
+            lm.Y = c->logits_d + (size_t)(i - 1) * B * V; lm.ldy = V;
+            P.push_back(lm);
+            Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->drafts + (i - 1); am.o_sseq = g.k_max; am.o_srow = 0;
+            P.push_back(am);
+            if (i < K) {
+                Phase pr{}; pr.type = PH_PREP; pr.ids = c->drafts + (i - 1); pr.id_sseq = g.k_max; pr.id_srow = 0; pr.gain = c->embed;
+                pr.Y = c->catD + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = i - 1;
+                P.push_back(pr);
+                Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = c->catD; fu.lda = 2 * d;
+                fu.Y = c->u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = std::min(i, g.n_resid - 1);
+                P.push_back(fu);
+                layer_phases<WT>(c, P, c->draft, c->dkv, c->u, c->dlen, i - 1, B, 1, c->catD, 2 * d);
+            }
+        }
+    } else {
+        const int m = K + 1;
+        Phase pr{}; pr.type = PH_PREP; pr.ids = c->next_tok; pr.id_sseq = g.k_max + 1; pr.id_srow = 1; pr.gain = c->embed;
+        pr.Y = c->catT + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = 0;
+        P.push_back(pr);
+        Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = c->catT; fu.lda = 2 * d;
+        fu.Y = c->u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = 0;
+        P.push_back(fu);
+        layer_phases<WT>(c, P, c->draft, c->dkv, c->u, c->dlen, 0, B, m, c->dout, d);
+    }
+    hivis_ctx::Program pg;
+    pg.n = (int)P.size();
+    if (int rc = dev_alloc(c, &pg.dev, P.size())) return rc;
+    HIP_TRY(c, hipMemcpy(pg.dev, P.data(), P.size() * sizeof(Phase), hipMemcpyHostToDevice));
+    c->programs[key] = pg;
+    *out = pg;
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
+    hivis_ctx::Program pg;
+    if (int rc = get_program<WT>(c, kind, K, &pg)) return rc;
+    const hivis_config& g = c->cfg;
+    PassParams pp{};
+    pp.phases = pg.dev; pp.nphases = pg.n;
+    pp.M = nseq * m; pp.nseq = nseq; pp.m = m;
+    pp.d = g.d; pp.Hq = g.n_q_heads; pp.Hkv = g.n_kv_heads; pp.hd = g.head_dim; pp.F = g.ffn; pp.V = g.vocab;
+    pp.eps = g.rms_eps; pp.theta = g.rope_theta;
+    pp.rope_tab = c->rope_tab; pp.attn_ws = c->fattn_ws; pp.pm = c->pm; pp.pi = c->pi; pp.bar = c->bar;
+    pp.spin_limit = 1u << 22;
+    hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, (int*)c->bar, 1, 0);
+    void* args[] = {&pp};
+    HIP_TRY(c, hipLaunchCooperativeKernel((const void*)fused_pass_kernel<WT>, dim3(c->fused_grid), dim3(1024), args, c->fused_lds, c->stream));
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int fused_setup(hivis_ctx* c) {
+    typedef WTraits<WT> TR;
+    const hivis_config& g = c->cfg;
+    const char* env = getenv("HIVIS_FUSED");
+    if (env && env[0] == '0') { c->fused = false; return HIVIS_OK; }
+    const size_t gemm_f = fused_gemm_lds_floats(FusedCfg<WT>::NW, FusedCfg<WT>::G, TR::RPL, TR::ROWS);
+    const size_t attn_f = attn_lds_floats(g.head_dim, 16, FUSED_RMAX);
+    c->fused_lds = std::max(gemm_f, attn_f) * sizeof(float);
+    HIP_TRY(c, hipFuncSetAttribute((const void*)fused_pass_kernel<WT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
+    int nb = 0;
+    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)fused_pass_kernel<WT>, 1024, c->fused_lds));
+    if (nb < 1) return fail(c, HIVIS_EHIP, "persistent kernel does not fit on a compute unit");
+    c->fused_grid = c->num_cu;
+    int rc;
+    if ((rc = dev_alloc(c, &c->rope_tab, (size_t)MAX_ROWS * g.head_dim))) return rc;
+    if ((rc = dev_alloc(c, &c->pm, (size_t)MAX_ROWS * c->fused_grid))) return rc;
+    if ((rc = dev_alloc(c, &c->pi, (size_t)MAX_ROWS * c->fused_grid))) return rc;
+    if ((rc = dev_alloc(c, &c->bar, 2))) return rc;
+    HIP_TRY(c, hipMemset(c->bar, 0, 2 * sizeof(unsigned)));
+    const size_t max_items = (size_t)g.batch * g.n_q_heads * 2;             // gh >= 1, at most two row blocks
+    c->fattn_ws_floats = ((size_t)c->fused_grid + max_items) * 16 * FUSED_RMAX * (g.head_dim + 2);
+    if ((rc = dev_alloc(c, &c->fattn_ws, c->fattn_ws_floats))) return rc;
+    c->fused = true;
     return HIVIS_OK;
 }
 
@@ -328,6 +488,11 @@ int do_draft(hivis_ctx* c, int K) {
     const hivis_config& g = c->cfg;
     const int B = g.batch, d = g.d, V = g.vocab;
     PhaseTimer pt(c, 1);
+    if (c->fused && fused_rows_ok<WT>(B)) {
+        if (int rc = run_program<WT>(c, PROG_DRAFT, K, B, 1)) return rc;
+        pt.stop();
+        return HIVIS_OK;
+    }
     int max_keys = 0;
     for (int b = 0; b < B; ++b) max_keys = std::max(max_keys, c->h_dlen[b]);
     for (int i = 1; i <= K; ++i) {
@@ -352,6 +517,11 @@ int do_verify(hivis_ctx* c) {
     int max_keys = 0;
     for (int b = 0; b < B; ++b) max_keys = std::max(max_keys, c->h_tlen[b]);
     hipLaunchKernelGGL(verify_tokens_kernel, dim3(1), dim3(64), 0, c->stream, (const int32_t*)c->text, c->text_stride, (const int*)c->dlen, (const int32_t*)c->drafts, g.k_max, K, c->row_tok, B);
+    if (c->fused && fused_rows_ok<WT>(M)) {
+        if (int rc = run_program<WT>(c, PROG_VERIFY, K, B, K + 1)) return rc;
+        pt.stop();
+        return HIVIS_OK;
+    }
     hipLaunchKernelGGL((gather_rows_kernel<WT>), dim3(M), dim3(256), 0, c->stream, (const WT*)c->embed, (const int32_t*)c->row_tok, 1, c->x, d, d);
     if (int rc = target_forward<WT>(c, 0, B, K + 1, c->tlen, 0, max_keys + K + 1, c->catT, 2 * d, 0)) return rc;
     if (int rc = gemm<WT>(c, c->catT, 2 * d, M, d, c->lm_head, V, c->logits_v, V, EPI_STORE)) return rc;
@@ -372,19 +542,26 @@ int do_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
                        (const int*)c->dlen, c->tlen, c->nacc, c->out_tok, c->next_tok);
     // roll-forward: K+1 rows per sequence [g_i ; Embed(token after row i)] + rho_0 through the drafter at positions
     // dlen..dlen+K; rows beyond n_b are computed but become dead (the drafter length advances by n_b+1 only).
-    for (int b = 0; b < B; ++b)
-        hipLaunchKernelGGL((gather_rows_kernel<WT>), dim3(K + 1), dim3(256), 0, c->stream, (const WT*)c->embed, (const int32_t*)(c->next_tok + (size_t)b * (g.k_max + 1)), 1,
-                           c->catT + (size_t)b * (K + 1) * 2 * d + d, 2 * d, d);
-    int max_keys = 0;
-    for (int b = 0; b < B; ++b) max_keys = std::max(max_keys, c->h_dlen[b]);
-    if (int rc = drafter_forward<WT>(c, c->catT, 0, B, K + 1, 0, 0, max_keys + K + 1, c->dout, d)) return rc;
+    if (c->fused && fused_rows_ok<WT>(M)) {
+        if (int rc = run_program<WT>(c, PROG_ROLL, K, B, K + 1)) return rc;
+    } else {
+        for (int b = 0; b < B; ++b)
+            hipLaunchKernelGGL((gather_rows_kernel<WT>), dim3(K + 1), dim3(256), 0, c->stream, (const WT*)c->embed, (const int32_t*)(c->next_tok + (size_t)b * (g.k_max + 1)), 1,
+                               c->catT + (size_t)b * (K + 1) * 2 * d + d, 2 * d, d);
+        int max_keys = 0;
+        for (int b = 0; b < B; ++b) max_keys = std::max(max_keys, c->h_dlen[b]);
+        if (int rc = drafter_forward<WT>(c, c->catT, 0, B, K + 1, 0, 0, max_keys + K + 1, c->dout, d)) return rc;
+    }
     hipLaunchKernelGGL(select_row_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)c->dout, K + 1, (const int32_t*)c->nacc, c->catD, 2 * d, c->dlen, d);
     HIP_TRY(c, hipGetLastError());
     pt.stop();
     std::vector<int32_t> hn(B), ht((size_t)B * (g.k_max + 1));
     HIP_TRY(c, hipMemcpyAsync(hn.data(), c->nacc, B * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipMemcpyAsync(ht.data(), c->out_tok, ht.size() * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    unsigned aborted = 0;
+    if (c->fused) HIP_TRY(c, hipMemcpyAsync(&aborted, c->bar + 1, sizeof(unsigned), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (aborted) return fail(c, HIVIS_EHIP, "persistent kernel: grid barrier timed out (pass aborted)");
     for (int b = 0; b < B; ++b) {
         c->h_tlen[b] += hn[b] + 1; c->h_dlen[b] += hn[b] + 1;
         if (n_accepted) n_accepted[b] = hn[b];
@@ -475,6 +652,7 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     c->h_tlen.assign(B, 0); c->h_dlen.assign(B, 0);
     HIP_TRY(c, hipEventCreate(&c->ev0));
     HIP_TRY(c, hipEventCreate(&c->ev1));
+    if ((rc = fused_setup<WT>(c))) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return HIVIS_OK;
 }

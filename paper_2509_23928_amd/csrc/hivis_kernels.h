@@ -400,18 +400,29 @@ struct AttnShape {
     int n_hblk, n_rblk;      // ceil(group/gh), ceil(m/mi)
     int seq0, offset, maxL, nsplit;
     int ldq;                 // row stride of the q buffer
+    int nwaves;              // wavefronts per workgroup working on one (item, split)
 };
 
-template <typename ST, int HD>
-__global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restrict__ q, const ST* __restrict__ kc,
-                                                            const ST* __restrict__ vc, const int* __restrict__ base,
-                                                            AttnShape sh, float* __restrict__ ws) {
+// LDS needed by attn_item_partial: q rows + one probability tile per wavefront
+__host__ __device__ constexpr size_t attn_lds_floats(int hd, int nwaves, int rmax = ATT_RMAX) {
+    return (size_t)rmax * hd + (size_t)nwaves * rmax * 64;
+}
+
+// One (item, split) by the calling workgroup of sh.nwaves wavefronts.  Partial results go to
+// ws[(item * nslots + slot)][ATT_RMAX][HD + 2] with slot = wave * nsplit + split; slots beyond the
+// number of key tiles have no work and write nothing.
+template <typename ST, int HD, int RM>
+__device__ __forceinline__ void attn_item_partial(const float* __restrict__ q, const ST* __restrict__ kc,
+                                                  const ST* __restrict__ vc, const int* __restrict__ base,
+                                                  const AttnShape& sh, int item_id, int split, float* __restrict__ lds,
+                                                  float* __restrict__ ws) {
     constexpr int CH = 16 / sizeof(ST);          // elements per 16-byte chunk
     constexpr int DPL = HD / 64;                 // value dims per lane
-    __shared__ float qs[ATT_RMAX * HD];
-    __shared__ float pw[4][ATT_RMAX][64];
+    const int nthreads = sh.nwaves * 64;
+    float* qs = lds;                                         // [RM][HD]
+    float* pw_all = lds + RM * HD;                     // [nwaves][RM][64]
 
-    int item = blockIdx.x;
+    int item = item_id;
     const int rblk = item % sh.n_rblk; item /= sh.n_rblk;
     const int hblk = item % sh.n_hblk; item /= sh.n_hblk;
     const int kvh = item % sh.Hkv;
@@ -425,10 +436,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
     const int nkeys = pos0 + i0 + ni;             // keys visible to the last row of the item
     const int ntiles = (nkeys + 63) / 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int slot = blockIdx.y * 4 + wave, nslots = sh.nsplit * 4;
+    const int slot = wave * sh.nsplit + split, nslots = sh.nsplit * sh.nwaves;   // consecutive tiles go to different workgroups
     const float scale = rsqrtf((float)HD);
+    float* pw = pw_all + (size_t)wave * RM * 64;
 
-    for (int idx = threadIdx.x; idx < R * HD; idx += 256) {
+    for (int idx = threadIdx.x; idx < R * HD; idx += nthreads) {
         const int r = idx / HD, c = idx % HD;
         const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
         qs[idx] = q[(size_t)(sl * sh.m + i) * sh.ldq + (size_t)hh * HD + c] * scale;
@@ -438,9 +450,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
     const ST* kbase = kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
     const ST* vbase = vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
 
-    float mrun[ATT_RMAX], lrun[ATT_RMAX], acc[ATT_RMAX][DPL];
+    float mrun[RM], lrun[RM], acc[RM][DPL];
 #pragma unroll
-    for (int r = 0; r < ATT_RMAX; ++r) {
+    for (int r = 0; r < RM; ++r) {
         mrun[r] = -INFINITY; lrun[r] = 0.f;
 #pragma unroll
         for (int e = 0; e < DPL; ++e) acc[r][e] = 0.f;
@@ -449,9 +461,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
     for (int ti = slot; ti < ntiles; ti += nslots) {
         const int j = ti * 64 + lane;
         const bool valid = j < nkeys;
-        float s[ATT_RMAX];
+        float s[RM];
 #pragma unroll
-        for (int r = 0; r < ATT_RMAX; ++r) s[r] = 0.f;
+        for (int r = 0; r < RM; ++r) s[r] = 0.f;
         if (valid) {
             const uint4* kp = reinterpret_cast<const uint4*>(kbase + (size_t)j * HD);
 #pragma unroll 4
@@ -460,7 +472,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
                 float kf[CH];
                 decode_chunk(raw, kf, ST());
 #pragma unroll
-                for (int r = 0; r < ATT_RMAX; ++r) {
+                for (int r = 0; r < RM; ++r) {
                     if (r < R) {
                         const float* qr = qs + r * HD + c * CH;
 #pragma unroll
@@ -470,7 +482,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
             }
         }
 #pragma unroll
-        for (int r = 0; r < ATT_RMAX; ++r) {
+        for (int r = 0; r < RM; ++r) {
             if (r < R) {
                 const int qpos = pos0 + i0 + r % ni;
                 const float sv = (valid && j <= qpos) ? s[r] : -INFINITY;
@@ -485,7 +497,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
                 lrun[r] = lrun[r] * alpha + p;
 #pragma unroll
                 for (int e = 0; e < DPL; ++e) acc[r][e] *= alpha;
-                pw[wave][r][lane] = p;
+                pw[r * 64 + lane] = p;
             }
         }
         // the probabilities of this wavefront's tile are read back by the same wavefront only
@@ -499,9 +511,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
 #pragma unroll
             for (int e = 0; e < DPL; ++e) vf[e] = to_f32(vp[e]);
 #pragma unroll
-            for (int r = 0; r < ATT_RMAX; ++r) {
+            for (int r = 0; r < RM; ++r) {
                 if (r < R) {
-                    const float p = pw[wave][r][jj];
+                    const float p = pw[r * 64 + jj];
 #pragma unroll
                     for (int e = 0; e < DPL; ++e) acc[r][e] += p * vf[e];
                 }
@@ -511,10 +523,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
-    // partial: ws[(item * nslots + slot)][r][HD + 2]
-    float* out = ws + ((size_t)blockIdx.x * nslots + slot) * ATT_RMAX * (HD + 2);
+    if (slot >= ntiles) return;
+    float* out = ws + ((size_t)item_id * nslots + slot) * RM * (HD + 2);
 #pragma unroll
-    for (int r = 0; r < ATT_RMAX; ++r) {
+    for (int r = 0; r < RM; ++r) {
         if (r < R) {
             const float lsum = wave_sum(lrun[r]);
 #pragma unroll
@@ -524,10 +536,12 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
     }
 }
 
-template <int HD>
-__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ ws, AttnShape sh,
-                                                          float* __restrict__ out, int ldo) {
-    int item = blockIdx.x;
+// Merge of the partials of one item by `nthreads` threads, in slot order (fixed summation order).
+template <int HD, int RM>
+__device__ __forceinline__ void attn_item_merge(const float* __restrict__ ws, const int* __restrict__ kvbase,
+                                                const AttnShape& sh, int item_id, int nthreads, float* __restrict__ out,
+                                                int ldo) {
+    int item = item_id;
     const int rblk = item % sh.n_rblk; item /= sh.n_rblk;
     const int hblk = item % sh.n_hblk; item /= sh.n_hblk;
     const int kvh = item % sh.Hkv;
@@ -536,15 +550,16 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
     const int h0 = hblk * sh.gh, nh = min(sh.gh, group - h0);
     const int i0 = rblk * sh.mi, ni = min(sh.mi, sh.m - i0);
     const int R = nh * ni;
-    const int nslots = sh.nsplit * 4;
-    const float* base = ws + (size_t)blockIdx.x * nslots * ATT_RMAX * (HD + 2);
-    for (int idx = threadIdx.x; idx < R * HD; idx += 256) {
+    const int nkeys = kvbase[sh.seq0 + sl] + sh.offset + i0 + ni;
+    const int nslots = min(sh.nsplit * sh.nwaves, (nkeys + 63) / 64);   // slots that had a key tile
+    const float* base = ws + (size_t)item_id * (sh.nsplit * sh.nwaves) * RM * (HD + 2);
+    for (int idx = threadIdx.x; idx < R * HD; idx += nthreads) {
         const int r = idx / HD, c = idx % HD;
         float mx = -INFINITY;
-        for (int s = 0; s < nslots; ++s) mx = fmaxf(mx, base[((size_t)s * ATT_RMAX + r) * (HD + 2) + HD]);
+        for (int s = 0; s < nslots; ++s) mx = fmaxf(mx, base[((size_t)s * RM + r) * (HD + 2) + HD]);
         float num = 0.f, den = 0.f;
         for (int s = 0; s < nslots; ++s) {
-            const float* p = base + ((size_t)s * ATT_RMAX + r) * (HD + 2);
+            const float* p = base + ((size_t)s * RM + r) * (HD + 2);
             const float ms = p[HD];
             if (ms == -INFINITY) continue;
             const float w = __expf(ms - mx);
@@ -553,6 +568,20 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
         const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
         out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c] = num / den;
     }
+}
+
+template <typename ST, int HD>
+__global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restrict__ q, const ST* __restrict__ kc,
+                                                            const ST* __restrict__ vc, const int* __restrict__ base,
+                                                            AttnShape sh, float* __restrict__ ws) {
+    __shared__ float lds[attn_lds_floats(HD, 4)];
+    attn_item_partial<ST, HD, ATT_RMAX>(q, kc, vc, base, sh, blockIdx.x, blockIdx.y, lds, ws);
+}
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ ws, const int* __restrict__ base,
+                                                          AttnShape sh, float* __restrict__ out, int ldo) {
+    attn_item_merge<HD, ATT_RMAX>(ws, base, sh, blockIdx.x, 256, out, ldo);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -72,6 +72,7 @@ struct hivis_ctx {
     float* fattn_ws = nullptr; size_t fattn_ws_floats = 0;
     struct Program { hivis::Phase* dev = nullptr; int n = 0; };
     std::map<int, Program> programs;     // key = kind * 64 + K
+    unsigned long long* prof = nullptr; int prof_left = 0;   // developer aid: HIVIS_PROF=n dumps per-phase times of n verify passes
 
     // timing
     bool timing = false;
@@ -280,36 +281,122 @@ AttnShape fused_attn_shape(hivis_ctx* c, int nseq, int m, int offset, int maxL, 
     if (m >= FUSED_RMAX) { sh.mi = FUSED_RMAX; sh.gh = 1; }
     else { sh.mi = m; sh.gh = std::max(1, std::min(group, FUSED_RMAX / m)); }
     sh.n_hblk = (group + sh.gh - 1) / sh.gh; sh.n_rblk = (m + sh.mi - 1) / sh.mi;
-    sh.seq0 = 0; sh.offset = offset; sh.maxL = maxL; sh.ldq = ldq; sh.nwaves = 16;
+    sh.seq0 = 0; sh.offset = offset; sh.maxL = maxL; sh.ldq = ldq; sh.nwaves = FUSED_NW;
     const int items = nseq * g.n_kv_heads * sh.n_hblk * sh.n_rblk;
     sh.nsplit = std::max(1, c->fused_grid / items);
     *items_out = items;
     return sh;
 }
 
-// phases of one decoder layer on rows h [M][d]; the MLP result is written as dst = h + mlp (dst may be h)
+// Bump allocator for the per-phase output buffers of one program (first pass counts, second pass hands out).
+struct Pool {
+    float* base = nullptr; size_t used = 0;
+    float* take(size_t floats) {
+        floats = (floats + 63) & ~(size_t)63;            // 256-byte granules: buffers never share a cache line
+        float* p = base ? base + used : nullptr;
+        used += floats;
+        return p;
+    }
+};
+
+// phases of one decoder layer on rows h [M][d]; returns the buffer holding h + attention + MLP.  Every phase
+// writes into a buffer of its own (see the memory discipline in hivis_fused.h).  dst: optional fixed destination
+// of the layer output (row stride ldd).
 template <typename WT>
-void layer_phases(hivis_ctx* c, std::vector<Phase>& P, const LayerDev& L, const KVDev& kv, float* h, const int* base,
-                  int offset, int nseq, int m, float* dst, int ldd) {
+float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const LayerDev& L, const KVDev& kv, float* h, const int* base,
+                    int offset, int nseq, int m, float* rope, float* dst, int ldd, int* ld_out) {
     const hivis_config& g = c->cfg;
+    const int M = nseq * m;
     const int d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn, nqkv = qd + 2 * kd;
+    float* qkv = pool.take((size_t)M * nqkv);
+    float* att = pool.take((size_t)M * qd);
+    float* h1 = pool.take((size_t)M * d);
+    float* act = pool.take((size_t)M * F);
+    float* h2 = dst ? dst : pool.take((size_t)M * d);
+    const int ld2 = dst ? ldd : d;
     Phase q{}; q.type = PH_GEMM; q.pro = PRO_RMS; q.epi = FEPI_QKV; q.K = d; q.N = nqkv; q.W = L.wqkv; q.A = h; q.lda = d;
-    q.gain = L.norm1; q.Y = c->qkv; q.ldy = nqkv; q.kc = kv.k; q.vc = kv.v; q.maxL = kv.maxL; q.base = base; q.offset = offset;
+    q.gain = L.norm1; q.Y = qkv; q.ldy = nqkv; q.kc = kv.k; q.vc = kv.v; q.maxL = kv.maxL; q.base = base; q.offset = offset; q.rope = rope;
     P.push_back(q);
-    Phase a{}; a.type = PH_ATTN; a.A = c->qkv; a.lda = nqkv; a.kc = kv.k; a.vc = kv.v; a.maxL = kv.maxL; a.base = base; a.offset = offset;
+    Phase a{}; a.type = PH_ATTN; a.A = qkv; a.lda = nqkv; a.kc = kv.k; a.vc = kv.v; a.maxL = kv.maxL; a.base = base; a.offset = offset;
     a.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, nqkv, &a.att_items);
+    a.ws = pool.take((size_t)a.att_items * a.att.nsplit * FUSED_RMAX * (g.head_dim + 2));
     P.push_back(a);
-    Phase mg = a; mg.type = PH_ATTN_MERGE; mg.Y = c->att; mg.ldy = qd;
+    Phase mg = a; mg.type = PH_ATTN_MERGE; mg.Y = att; mg.ldy = qd;
     P.push_back(mg);
-    Phase o{}; o.type = PH_GEMM; o.pro = PRO_PLAIN; o.epi = FEPI_ADD_TO; o.K = qd; o.N = d; o.W = L.wo; o.A = c->att; o.lda = qd;
-    o.Y = h; o.ldy = d; o.R = h; o.ldr = d;
+    Phase o{}; o.type = PH_GEMM; o.pro = PRO_PLAIN; o.epi = FEPI_ADD_TO; o.K = qd; o.N = d; o.W = L.wo; o.A = att; o.lda = qd;
+    o.Y = h1; o.ldy = d; o.R = h; o.ldr = d;
     P.push_back(o);
-    Phase gu{}; gu.type = PH_GEMM; gu.pro = PRO_RMS; gu.epi = FEPI_SILU; gu.K = d; gu.N = 2 * F; gu.W = L.wgu; gu.A = h; gu.lda = d;
-    gu.gain = L.norm2; gu.Y = c->act; gu.ldy = F;
+    Phase gu{}; gu.type = PH_GEMM; gu.pro = PRO_RMS; gu.epi = FEPI_SILU; gu.K = d; gu.N = 2 * F; gu.W = L.wgu; gu.A = h1; gu.lda = d;
+    gu.gain = L.norm2; gu.Y = act; gu.ldy = F;
     P.push_back(gu);
-    Phase dn{}; dn.type = PH_GEMM; dn.pro = PRO_PLAIN; dn.epi = FEPI_ADD_TO; dn.K = F; dn.N = d; dn.W = L.wd; dn.A = c->act; dn.lda = F;
-    dn.Y = dst; dn.ldy = ldd; dn.R = h; dn.ldr = d;
+    Phase dn{}; dn.type = PH_GEMM; dn.pro = PRO_PLAIN; dn.epi = FEPI_ADD_TO; dn.K = F; dn.N = d; dn.W = L.wd; dn.A = act; dn.lda = F;
+    dn.Y = h2; dn.ldy = ld2; dn.R = h1; dn.ldr = d;
     P.push_back(dn);
+    *ld_out = ld2;
+    return h2;
+}
+
+template <typename WT>
+void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>& P) {
+    const hivis_config& g = c->cfg;
+    const int B = g.batch, d = g.d, V = g.vocab, G = c->fused_grid;
+    int ld = d;
+    if (kind == PROG_VERIFY) {
+        const int m = K + 1, M = B * m;
+        float* x = pool.take((size_t)M * d);
+        float* rope = pool.take((size_t)M * g.head_dim);
+        Phase pr{}; pr.type = PH_PREP; pr.ids = c->row_tok; pr.id_sseq = m; pr.id_srow = 1; pr.gain = c->embed; pr.Y = x; pr.ldy = d;
+        pr.base = c->tlen; pr.offset = 0; pr.rope = rope;
+        P.push_back(pr);
+        for (int l = 0; l < g.n_layers; ++l) x = layer_phases<WT>(c, P, pool, c->layers[l], c->tkv[l], x, c->tlen, 0, B, m, rope, nullptr, 0, &ld);
+        Phase nr{}; nr.type = PH_NORM_ROWS; nr.A = x; nr.lda = d; nr.gain = c->final_norm; nr.Y = c->catT; nr.ldy = 2 * d;
+        P.push_back(nr);
+        Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = c->catT; lm.lda = 2 * d;
+        lm.Y = c->logits_v; lm.ldy = V; lm.pm = pool.take((size_t)M * G); lm.pi = (int*)pool.take((size_t)M * G);
+        P.push_back(lm);
+        Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->ttok; am.o_sseq = g.k_max + 1; am.o_srow = 1; am.pm = lm.pm; am.pi = lm.pi;
+        P.push_back(am);
+    } else if (kind == PROG_DRAFT) {
+        // cat: [B][2d] = drafter hidden f' | embedding of the token drafted from it; a fresh buffer per step
+        float* cat = c->catD;
+        for (int i = 1; i <= K; ++i) {
+            Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = cat; lm.lda = 2 * d;
+            lm.Y = c->logits_d + (size_t)(i - 1) * B * V; lm.ldy = V; lm.pm = pool.take((size_t)B * G); lm.pi = (int*)pool.take((size_t)B * G);
+            P.push_back(lm);
+            Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->drafts + (i - 1); am.o_sseq = g.k_max; am.o_srow = 0; am.pm = lm.pm; am.pi = lm.pi;
+            P.push_back(am);
+            if (i < K) {
+                float* rope = pool.take((size_t)B * g.head_dim);
+                float* u = pool.take((size_t)B * d);
+                float* cat_next = pool.take((size_t)B * 2 * d);
+                Phase pr{}; pr.type = PH_PREP; pr.ids = c->drafts + (i - 1); pr.id_sseq = g.k_max; pr.id_srow = 0; pr.gain = c->embed;
+                pr.Y = cat + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = i - 1; pr.rope = rope;
+                P.push_back(pr);
+                Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = cat; fu.lda = 2 * d;
+                fu.Y = u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = std::min(i, g.n_resid - 1);
+                P.push_back(fu);
+                layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, i - 1, B, 1, rope, cat_next, 2 * d, &ld);
+                cat = cat_next;
+            }
+        }
+    } else {
+        const int m = K + 1, M = B * m;
+        float* rope = pool.take((size_t)M * g.head_dim);
+        float* u = pool.take((size_t)M * d);
+        Phase pr{}; pr.type = PH_PREP; pr.ids = c->next_tok; pr.id_sseq = g.k_max + 1; pr.id_srow = 1; pr.gain = c->embed;
+        pr.Y = c->catT + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = 0; pr.rope = rope;
+        P.push_back(pr);
+        Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = c->catT; fu.lda = 2 * d;
+        fu.Y = u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = 0;
+        P.push_back(fu);
+        layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, 0, B, m, rope, c->dout, d, &ld);
+    }
+    // chain the GEMM phases for the cross-barrier weight prefetch
+    for (size_t i = 0; i < P.size(); ++i) {
+        if (P[i].type != PH_GEMM) continue;
+        for (size_t j = i + 1; j < P.size(); ++j)
+            if (P[j].type == PH_GEMM) { P[i].next_W = P[j].W; P[i].next_K = P[j].K; P[i].next_N = P[j].N; break; }
+    }
 }
 
 template <typename WT>
@@ -317,49 +404,14 @@ int get_program(hivis_ctx* c, int kind, int K, hivis_ctx::Program* out) {
     const int key = kind * 64 + K;
     auto it = c->programs.find(key);
     if (it != c->programs.end()) { *out = it->second; return HIVIS_OK; }
-    const hivis_config& g = c->cfg;
-    const int B = g.batch, d = g.d, V = g.vocab;
     std::vector<Phase> P;
-    if (kind == PROG_VERIFY) {
-        const int m = K + 1;
-        Phase pr{}; pr.type = PH_PREP; pr.ids = c->row_tok; pr.id_sseq = m; pr.id_srow = 1; pr.gain = c->embed; pr.Y = c->x; pr.ldy = d;
-        pr.base = c->tlen; pr.offset = 0;
-        P.push_back(pr);
-        for (int l = 0; l < g.n_layers; ++l) layer_phases<WT>(c, P, c->layers[l], c->tkv[l], c->x, c->tlen, 0, B, m, c->x, d);
-        Phase nr{}; nr.type = PH_NORM_ROWS; nr.A = c->x; nr.lda = d; nr.gain = c->final_norm; nr.Y = c->catT; nr.ldy = 2 * d;
-        P.push_back(nr);
-        Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = c->catT; lm.lda = 2 * d;
-        lm.Y = c->logits_v; lm.ldy = V;
-        P.push_back(lm);
-        Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->ttok; am.o_sseq = g.k_max + 1; am.o_srow = 1;
-        P.push_back(am);
-    } else if (kind == PROG_DRAFT) {
-        for (int i = 1; i <= K; ++i) {
-            Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = c->catD; lm.lda = 2 * d;
-            lm.Y = c->logits_d + (size_t)(i - 1) * B * V; lm.ldy = V;
-            P.push_back(lm);
-            Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->drafts + (i - 1); am.o_sseq = g.k_max; am.o_srow = 0;
-            P.push_back(am);
-            if (i < K) {
-                Phase pr{}; pr.type = PH_PREP; pr.ids = c->drafts + (i - 1); pr.id_sseq = g.k_max; pr.id_srow = 0; pr.gain = c->embed;
-                pr.Y = c->catD + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = i - 1;
-                P.push_back(pr);
-                Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = c->catD; fu.lda = 2 * d;
-                fu.Y = c->u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = std::min(i, g.n_resid - 1);
-                P.push_back(fu);
-                layer_phases<WT>(c, P, c->draft, c->dkv, c->u, c->dlen, i - 1, B, 1, c->catD, 2 * d);
-            }
-        }
-    } else {
-        const int m = K + 1;
-        Phase pr{}; pr.type = PH_PREP; pr.ids = c->next_tok; pr.id_sseq = g.k_max + 1; pr.id_srow = 1; pr.gain = c->embed;
-        pr.Y = c->catT + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = 0;
-        P.push_back(pr);
-        Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = c->catT; fu.lda = 2 * d;
-        fu.Y = c->u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = 0;
-        P.push_back(fu);
-        layer_phases<WT>(c, P, c->draft, c->dkv, c->u, c->dlen, 0, B, m, c->dout, d);
-    }
+    Pool count;
+    build_phases<WT>(c, kind, K, count, P);           // sizes only
+    Pool pool;
+    if (int rc = dev_alloc(c, &pool.base, count.used)) return rc;
+    HIP_TRY(c, hipMemset(pool.base, 0, count.used * sizeof(float)));
+    P.clear();
+    build_phases<WT>(c, kind, K, pool, P);
     hivis_ctx::Program pg;
     pg.n = (int)P.size();
     if (int rc = dev_alloc(c, &pg.dev, P.size())) return rc;
@@ -379,11 +431,34 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
     pp.M = nseq * m; pp.nseq = nseq; pp.m = m;
     pp.d = g.d; pp.Hq = g.n_q_heads; pp.Hkv = g.n_kv_heads; pp.hd = g.head_dim; pp.F = g.ffn; pp.V = g.vocab;
     pp.eps = g.rms_eps; pp.theta = g.rope_theta;
-    pp.rope_tab = c->rope_tab; pp.attn_ws = c->fattn_ws; pp.pm = c->pm; pp.pi = c->pi; pp.bar = c->bar;
+    pp.bar = c->bar;
     pp.spin_limit = 1u << 22;
+    const bool do_prof = c->prof && kind == PROG_VERIFY && c->prof_left > 0;
+    pp.prof = do_prof ? c->prof : nullptr;
+    pp.prof2 = do_prof ? c->prof + 4096 * 3 : nullptr;
     hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, (int*)c->bar, 1, 0);
     void* args[] = {&pp};
-    HIP_TRY(c, hipLaunchCooperativeKernel((const void*)fused_pass_kernel<WT>, dim3(c->fused_grid), dim3(1024), args, c->fused_lds, c->stream));
+    HIP_TRY(c, hipLaunchCooperativeKernel((const void*)fused_pass_kernel<WT>, dim3(c->fused_grid), dim3(FUSED_NT), args, c->fused_lds, c->stream));
+    if (do_prof) {
+        std::vector<unsigned long long> t((size_t)pg.n * 3), t2((size_t)pg.n * 8);
+        std::vector<Phase> P(pg.n);
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        HIP_TRY(c, hipMemcpy(t.data(), c->prof, t.size() * 8, hipMemcpyDeviceToHost));
+        HIP_TRY(c, hipMemcpy(P.data(), pg.dev, P.size() * sizeof(Phase), hipMemcpyDeviceToHost));
+        HIP_TRY(c, hipMemcpy(t2.data(), c->prof + 4096 * 3, t2.size() * 8, hipMemcpyDeviceToHost));
+        for (int p = 7; p < 13 && p < pg.n; ++p) if (P[p].type == PH_GEMM)
+            fprintf(stderr, "[hivis prof2] phase %d epi %d: entry+%.2f  staged+%.2f  pass0+%.2f  allpass+%.2f  reduced+%.2f  end+%.2f us\n", p, P[p].epi,
+                    (t2[p*8]-t[p*3])*0.01, (t2[p*8+1]-t2[p*8])*0.01, (t2[p*8+2]-t2[p*8+1])*0.01, (t2[p*8+3]-t2[p*8+2])*0.01, (t2[p*8+4]-t2[p*8+3])*0.01, (t2[p*8+5]-t2[p*8+4])*0.01);
+        double tot[8][8] = {}, bar[8][8] = {}; int cnt[8][8] = {};
+        for (int p = 0; p < pg.n; ++p) {
+            const int ty = P[p].type, ep = P[p].type == PH_GEMM ? P[p].epi : 0;
+            tot[ty][ep] += (t[p * 3 + 1] - t[p * 3]) * 0.01; bar[ty][ep] += (t[p * 3 + 2] - t[p * 3 + 1]) * 0.01; cnt[ty][ep]++;
+        }
+        fprintf(stderr, "[hivis prof] verify pass %.1f us (workgroup 0 view)\n", (t[pg.n * 3 - 1] - t[0]) * 0.01);
+        for (int ty = 0; ty < 8; ++ty) for (int ep = 0; ep < 8; ++ep) if (cnt[ty][ep])
+            fprintf(stderr, "[hivis prof]   type %d epi %d: n=%3d  work %7.2f us avg, barrier wait %7.2f us avg\n", ty, ep, cnt[ty][ep], tot[ty][ep] / cnt[ty][ep], bar[ty][ep] / cnt[ty][ep]);
+        c->prof_left--;
+    }
     return HIVIS_OK;
 }
 
@@ -393,23 +468,18 @@ int fused_setup(hivis_ctx* c) {
     const hivis_config& g = c->cfg;
     const char* env = getenv("HIVIS_FUSED");
     if (env && env[0] == '0') { c->fused = false; return HIVIS_OK; }
-    const size_t gemm_f = fused_gemm_lds_floats(FusedCfg<WT>::NW, FusedCfg<WT>::G, TR::RPL, TR::ROWS);
-    const size_t attn_f = attn_lds_floats(g.head_dim, 16, FUSED_RMAX);
+    const size_t gemm_f = fused_gemm_lds_floats(FusedCfg<WT>::NW, FusedCfg<WT>::G, TR::RPL, FusedCfg<WT>::KBW);
+    const size_t attn_f = fused_attn_lds_floats(g.head_dim, FUSED_NW, FUSED_RMAX);
     c->fused_lds = std::max(gemm_f, attn_f) * sizeof(float);
     HIP_TRY(c, hipFuncSetAttribute((const void*)fused_pass_kernel<WT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
     int nb = 0;
-    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)fused_pass_kernel<WT>, 1024, c->fused_lds));
+    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)fused_pass_kernel<WT>, FUSED_NT, c->fused_lds));
     if (nb < 1) return fail(c, HIVIS_EHIP, "persistent kernel does not fit on a compute unit");
     c->fused_grid = c->num_cu;
     int rc;
-    if ((rc = dev_alloc(c, &c->rope_tab, (size_t)MAX_ROWS * g.head_dim))) return rc;
-    if ((rc = dev_alloc(c, &c->pm, (size_t)MAX_ROWS * c->fused_grid))) return rc;
-    if ((rc = dev_alloc(c, &c->pi, (size_t)MAX_ROWS * c->fused_grid))) return rc;
     if ((rc = dev_alloc(c, &c->bar, 2))) return rc;
     HIP_TRY(c, hipMemset(c->bar, 0, 2 * sizeof(unsigned)));
-    const size_t max_items = (size_t)g.batch * g.n_q_heads * 2;             // gh >= 1, at most two row blocks
-    c->fattn_ws_floats = ((size_t)c->fused_grid + max_items) * 16 * FUSED_RMAX * (g.head_dim + 2);
-    if ((rc = dev_alloc(c, &c->fattn_ws, c->fattn_ws_floats))) return rc;
+    if (const char* pe = getenv("HIVIS_PROF")) { c->prof_left = atoi(pe); if (c->prof_left > 0 && (rc = dev_alloc(c, &c->prof, (size_t)4096 * 11))) return rc; }
     c->fused = true;
     return HIVIS_OK;
 }

@@ -1,6 +1,6 @@
 // Persistent "pass" kernel: a whole verify pass (N layers + LM head + greedy tokens), a whole
 // K-step draft round, or the roll-forward of the drafter runs as ONE cooperative launch of one
-// 1024-thread workgroup per compute unit that interprets a list of phases, with a grid-wide
+// 512-thread workgroup per compute unit that interprets a list of phases, with a grid-wide
 // barrier between phases.  The small row-wise operations are folded into the GEMM phases:
 //   RMSNorm     -> prologue (gain applied while building the MFMA A fragments, 1/rms in the epilogue)
 //   RoPE+append -> epilogue of the fused QKV GEMM (rotary pairs are adjacent columns of a tile)
@@ -8,6 +8,13 @@
 //   residual    -> epilogue of the O and down GEMMs (each output element has exactly one writer)
 //   argmax      -> epilogue of the LM-head GEMM (per-workgroup candidates) + a tiny reduction phase
 // Used for passes of at most one MFMA tile of rows (8 rows for bf16 weights, 16 for fp32).
+//
+// Memory discipline between phases (the L2 is per XCD and not coherent across XCDs): every buffer that one
+// phase writes and a later phase reads is written AT MOST ONCE per launch, with write-through stores, and is
+// not read before that write in the same launch (the host gives every phase its own output buffer).  A
+// reader's first touch therefore misses its caches and fetches the fresh value from memory, and the grid
+// barrier needs no cache write-back or invalidation.  The few words that are rewritten inside one launch
+// (drafted token ids) are read with agent-scope loads.
 #pragma once
 #include "hivis_kernels.h"
 
@@ -32,6 +39,10 @@ struct Phase {
     const int32_t* ids; int id_sseq, id_srow;      // PREP: token of row (seq, i) = ids[seq*id_sseq + i*id_srow] (ids may be null: no gather)
     int32_t* tok_out; int o_sseq, o_srow;          // ARGMAX: destination of the greedy token of row (seq, i)
     AttnShape att; int att_items;                  // ATTN / ATTN_MERGE
+    float* rope;                                   // PREP writes, QKV epilogue reads: [rows][hd/2][2] cos, sin
+    float* ws;                                     // ATTN writes, ATTN_MERGE reads: partials
+    float* pm; int* pi;                            // LOGITS writes, ARGMAX reads: greedy candidates [row][workgroup]
+    const uint4* next_W; int next_K, next_N;       // GEMM: weights of the next GEMM phase of the program (prefetch), or null
 };
 
 struct PassParams {
@@ -39,18 +50,18 @@ struct PassParams {
     int M, nseq, m;                 // rows of the pass = nseq * m
     int d, Hq, Hkv, hd, F, V;
     float eps, theta;
-    float* rope_tab;                // [rows][hd/2][2] cos, sin
-    float* attn_ws;
-    float* pm; int* pi;             // greedy-token candidates [row][workgroup]
     unsigned* bar;                  // [0] arrival counter (zeroed before launch), [1] abort flag
     unsigned spin_limit;
+    unsigned long long* prof2;      // optional [nphases][8] finer timestamps inside GEMM phases (workgroup 0)
+    unsigned long long* prof;       // optional [nphases][3] timestamps of workgroup 0 (phase start, phase end, barrier end), 100 MHz
 };
 
-// Grid-wide barrier.  Every thread releases its writes at agent scope, one thread arrives and
-// spins (bounded: on timeout the abort flag is raised and every workgroup leaves), every
-// thread acquires.  Returns false if the pass was aborted.
+// Grid-wide barrier.  Every thread first waits until its own (write-through) stores have been acknowledged
+// (workgroup-scope release = s_waitcnt), then one thread arrives and spins; bounded: on timeout the abort flag
+// is raised and every workgroup leaves.  No cache maintenance (see the memory discipline above).  Returns false
+// if the pass was aborted.
 __device__ __forceinline__ bool grid_barrier(unsigned* bar, unsigned target, unsigned spin_limit) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (threadIdx.x == 0) {
         __hip_atomic_fetch_add(&bar[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -63,96 +74,152 @@ __device__ __forceinline__ bool grid_barrier(unsigned* bar, unsigned target, uns
         }
     }
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     return __hip_atomic_load(&bar[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u;
 }
 
-// ---- A fragments with optional gain and sum of squares ------------------------------------------
-template <typename WT>
-__device__ __forceinline__ void fused_afrag(bf16x8_t& out, const float* __restrict__ A, int lda, int M, int kb, int lane,
-                                            const WT* __restrict__ gain, float& ssq) {
-    const int i = lane & 15, g = lane >> 4;
-    const int row = 2 * (i >> 2) + (i & 1);
-    const bool lo = (i & 2) != 0;
-    uint32_t pk[4] = {0u, 0u, 0u, 0u};
-    if (row < M) {
-        const int k0 = kb * 32 + g * 8;
-        const float4* p = reinterpret_cast<const float4*>(A + (size_t)row * lda + k0);
-        float4 x0 = p[0], x1 = p[1];
-        float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-        if (gain) {
-            float s = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { s += x[e] * x[e]; x[e] *= to_f32(gain[k0 + e]); }
-            if (!lo) ssq += s;
-        }
-        bf16_t h[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            bf16_t hi = f32_to_bf16(x[e]);
-            h[e] = lo ? f32_to_bf16(x[e] - bf16_to_f32(hi)) : hi;
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pk[e] = (uint32_t)h[2 * e] | ((uint32_t)h[2 * e + 1] << 16);
-    }
-    out = __builtin_bit_cast(bf16x8_t, make_uint4(pk[0], pk[1], pk[2], pk[3]));
-}
-template <typename WT>
-__device__ __forceinline__ void fused_afrag(float4& out, const float* __restrict__ A, int lda, int M, int kb, int lane,
-                                            const WT* __restrict__ gain, float& ssq) {
-    const int i = lane & 15, g = lane >> 4;
-    out = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < M) {
-        const int k0 = kb * 16 + g * 4;
-        float4 x = *reinterpret_cast<const float4*>(A + (size_t)i * lda + k0);
-        if (gain) {
-            ssq += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
-            x.x *= to_f32(gain[k0]); x.y *= to_f32(gain[k0 + 1]); x.z *= to_f32(gain[k0 + 2]); x.w *= to_f32(gain[k0 + 3]);
-        }
-        out = x;
-    }
-}
-
-// lane (i = lane & 15) -> activation row whose sum of squares this lane accumulated, or -1
-template <typename WT> __device__ __forceinline__ int ssq_row_of_lane(int i);
-template <> __device__ __forceinline__ int ssq_row_of_lane<bf16_t>(int i) { return (i & 2) ? -1 : 2 * (i >> 2) + (i & 1); }
-template <> __device__ __forceinline__ int ssq_row_of_lane<float>(int i) { return i; }
-
+// ---- GEMM phase -----------------------------------------------------------------------------------
 template <typename WT> struct FusedCfg;
-template <> struct FusedCfg<bf16_t> { static constexpr int KBW = 2, G = 4, NW = 16; };
-template <> struct FusedCfg<float> { static constexpr int KBW = 2, G = 2, NW = 16; };
+// KBW weight blocks per wavefront per K pass (= one unit of the software pipeline); G tiles per tile group
+// 512 threads (8 wavefronts, two per SIMD) so that every wavefront may use up to 256 registers: the pipeline
+// state (two 8 KiB weight units, 8 activation fragments, accumulators, staged rows) must never spill, because a
+// spill reload after the barrier's cache invalidation is a full memory round trip.
+constexpr int FUSED_NW = 8, FUSED_NT = FUSED_NW * 64;
+template <> struct FusedCfg<bf16_t> { static constexpr int KBW = 8, G = 4, NW = FUSED_NW; };
+template <> struct FusedCfg<float> { static constexpr int KBW = 8, G = 2, NW = FUSED_NW; };
+constexpr int FUSED_U = 8;
+constexpr int FUSED_QM = 8;       // activation rows staged per thread per pass (8 rows / 1 for bf16, 16 rows / 2 for fp32)
 
-__host__ __device__ constexpr size_t fused_gemm_lds_floats(int NW, int G, int RPL, int ROWS) {
-    return (size_t)NW * G * 64 * RPL + (size_t)G * 64 * RPL + (size_t)NW * 16 + 16 + 4 * 16;
+// LDS of a GEMM phase (floats): cross-wave reduction [NW][TILE] | reduced tiles [TILE] | ssq partials [NW][QM]
+// | inv_rms [16] | A chunk of one K pass in MFMA fragment order [NW*KBW blocks][4][RU] x 16 bytes
+__host__ __device__ constexpr size_t fused_gemm_lds_floats(int NW, int G, int RPL, int KBW) {
+    return (size_t)NW * G * 64 * RPL + (size_t)G * 64 * RPL + (size_t)NW * FUSED_QM + 16 + (size_t)NW * KBW * 4 * 16 * 4;
 }
 
+// Loads of one unit: the wavefront's K blocks [kb0, kb0+nkb) of tile `tile`.
+__device__ __forceinline__ void issue_unit(uint4 (&wb)[FUSED_U], const uint4* __restrict__ W, int kblks, int tile, int kb0,
+                                           int nkb, int lane) {
+    const uint4* p = W + ((size_t)tile * kblks + kb0) * 64 + lane;
+#pragma unroll
+    for (int j = 0; j < FUSED_U; ++j)
+        if (j < nkb) wb[j] = p[(size_t)j * 64]; else wb[j] = make_uint4(0, 0, 0, 0);
+}
+
+// tile row (MFMA A row) that holds activation row `row`: bf16 keeps hi at 4*(row/2) + row%2 and lo two rows below
+template <typename WT> __device__ __forceinline__ int tile_row_of(int row);
+template <> __device__ __forceinline__ int tile_row_of<bf16_t>(int row) { return 4 * (row >> 1) + (row & 1); }
+template <> __device__ __forceinline__ int tile_row_of<float>(int row) { return row; }
+
+// Writes 4 consecutive k of one activation row (already multiplied by the gain) into the LDS chunk.
+__device__ __forceinline__ void stage_store(bf16_t, uint4* chunk, int RU, int row, int kl /*k within the chunk, multiple of 4*/,
+                                            const float (&x)[4]) {
+    const int kb = kl >> 5, g = (kl & 31) >> 3, e0 = kl & 7;
+    const int slot = (kb * 4 + g) * RU + tile_row_of<bf16_t>(row);
+    bf16_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { hi[e] = f32_to_bf16(x[e]); lo[e] = f32_to_bf16(x[e] - bf16_to_f32(hi[e])); }
+    uint2* ph = reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(chunk + slot) + e0);
+    uint2* pl = reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(chunk + slot + 2) + e0);
+    *ph = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+    *pl = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+}
+__device__ __forceinline__ void stage_store(float, uint4* chunk, int RU, int row, int kl, const float (&x)[4]) {
+    const int kb = kl >> 4, g = (kl & 15) >> 2;
+    chunk[(kb * 4 + g) * RU + row] = make_uint4(__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3]));
+}
+__device__ __forceinline__ void frag_from(bf16x8_t& f, const uint4& u) { f = __builtin_bit_cast(bf16x8_t, u); }
+__device__ __forceinline__ void frag_from(float4& f, const uint4& u) {
+    f = make_float4(__uint_as_float(u.x), __uint_as_float(u.y), __uint_as_float(u.z), __uint_as_float(u.w));
+}
+
+// GEMM phase of the persistent kernel (rows <= one MFMA tile).  Work split as in gemm_skinny_kernel: the
+// workgroup owns a contiguous range of 16-column tiles and covers all of K; in K pass p wavefront w owns
+// blocks [(p*NW + w)*KBW, +KBW) of every tile.
+//  * Activations: per pass the workgroup's threads load the pass's K range of all rows once (coalesced float4), apply
+//    the RMSNorm gain, accumulate the rows' sums of squares, convert to MFMA fragments and park them in LDS;
+//    the wavefronts then fetch their fragments with ds_read (LDS traffic is counted separately from global
+//    loads, so waiting for fragments never waits for weight loads).  The next pass's rows are already being
+//    loaded into registers while the current pass streams.
+//  * Weights: one unit (KBW KiB per wavefront) ahead, and the chain of prefetches does not stop at the end of
+//    a tile group, a pass or the phase: the last unit of a phase loads the first unit of the NEXT GEMM phase
+//    (`head`), so those loads are in flight while the workgroup waits at the grid barrier.
 template <typename WT>
-__device__ void gemm_phase(const Phase& ph, const PassParams& pp, float* __restrict__ lds) {
+__device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp, float* __restrict__ lds, uint4 (&head)[FUSED_U],
+                           bool& head_valid, int pidx) {
+#define HIVIS_MARK(k) if (pp.prof2 && blockIdx.x == 0 && threadIdx.x == 0) pp.prof2[pidx * 8 + (k)] = wall_clock64();
     typedef WTraits<WT> TR;
     typedef typename AFrag<WT>::type afrag_t;
     typedef typename KVType<WT>::type KT;
-    constexpr int RPL = TR::RPL, ROWS = TR::ROWS, KBW = FusedCfg<WT>::KBW, G = FusedCfg<WT>::G, NW = FusedCfg<WT>::NW;
+    constexpr int RPL = TR::RPL, ROWS = TR::ROWS, KB = TR::KB, KBW = FusedCfg<WT>::KBW, G = FusedCfg<WT>::G, NW = FusedCfg<WT>::NW;
+    constexpr int U = FUSED_U, QM = FUSED_QM;
+    static_assert(KBW == U && (G % 2) == 0, "one unit per tile slice; tiles are processed in pairs");
     constexpr int TILE = G * 64 * RPL;
-    float* red = lds;                       // [NW][G][64][RPL]
-    float* tile = red + (size_t)NW * TILE;  // [G][64][RPL]
-    float* ssq_w = tile + TILE;             // [NW][16]
-    float* inv_rms = ssq_w + NW * 16;       // [16]
-    float* cand_v = inv_rms + 16;           // [16] per-row best value (LOGITS)
-    int* cand_i = (int*)(cand_v + 16);      // [16]
+    constexpr int CW = NW * KBW * KB;        // k per pass (64 blocks)
+    constexpr int C4 = CW / 4;               // float4 columns per pass (<= 512)
+    float* red = lds;                        // [NW][G][64][RPL]
+    float* tile = red + (size_t)NW * TILE;   // [G][64][RPL]
+    float* ssq_w = tile + TILE;              // [NW][QM]
+    float* inv_rms = ssq_w + NW * QM;        // [16]
+    uint4* chunk = reinterpret_cast<uint4*>(inv_rms + 16);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int M = pp.M, K = ph.K, N = ph.N;
-    const int kblks = K / TR::KB, ntiles = N / 16;
+    const int kblks = K / KB, ntiles = N / 16;
     const int t_begin = (int)(((long long)blockIdx.x * ntiles) / gridDim.x);
     const int t_end = (int)(((long long)(blockIdx.x + 1) * ntiles) / gridDim.x);
     const int npass = (kblks + NW * KBW - 1) / (NW * KBW);
     const WT* gain = (ph.pro == PRO_RMS) ? (const WT*)ph.gain : nullptr;
     const float* A = ph.A;
     const int lda = ph.lda;
-    float ssq = 0.f;
-    // greedy-token candidate of this thread's output slots (LOGITS): a thread always serves the same row
-    float best_v = -INFINITY; int best_i = 0x7FFFFFFF;
+    const uint4* W = ph.W;
+    const int RU = (RPL == 2) ? 4 * ((M + 1) >> 1) : ((M + 3) & ~3);      // tile rows in use
+    const int col4 = threadIdx.x % C4, row0 = threadIdx.x / C4;          // this thread stages rows row0, row0 + RSTEP, ...
+    constexpr int RSTEP = FUSED_NT / C4;
+    float ssq_acc[QM];
+#pragma unroll
+    for (int q = 0; q < QM; ++q) ssq_acc[q] = 0.f;
+    float best_v = -INFINITY; int best_i = 0x7FFFFFFF;   // greedy-token candidate (LOGITS): a thread always serves one row
 
+    // first unit of the next GEMM phase for this wavefront (prefetched by the last unit of this phase)
+    const int n_kblks = ph.next_K / KB, n_ntiles = ph.next_N / 16;
+    const int n_tile = ph.next_W ? (int)(((long long)blockIdx.x * n_ntiles) / gridDim.x) : 0;
+    const bool n_has = ph.next_W && n_tile < (int)(((long long)(blockIdx.x + 1) * n_ntiles) / gridDim.x);
+
+    if (t_begin >= t_end) {
+        // no tiles in this phase: still start the next phase's stream
+        if (!head_valid && n_has) {
+            issue_unit(head, ph.next_W, n_kblks, n_tile, wave * KBW, max(0, min(KBW, n_kblks - wave * KBW)), lane);
+            head_valid = true;
+        }
+        if (ph.epi == FEPI_LOGITS && threadIdx.x < ROWS && (int)threadIdx.x < M) {
+            st_wt(&ph.pm[(size_t)threadIdx.x * gridDim.x + blockIdx.x], -INFINITY); st_wt(&ph.pi[(size_t)threadIdx.x * gridDim.x + blockIdx.x], 0x7FFFFFFF);
+        }
+        return;
+    }
+    if (!head_valid) issue_unit(head, W, kblks, t_begin, wave * KBW, max(0, min(KBW, kblks - wave * KBW)), lane);
+    head_valid = false;
+
+    // raw activation loads of pass `ps`: float4 (row0 + q*RSTEP, ps*CW + 4*col4) and the gain of those 4 columns
+    static_assert(QM * RSTEP >= ROWS, "every row is staged by some thread");
+    float4 araw[QM]; float graw[4];
+    // (unconditional loads from clamped addresses: a load under a divergent branch is followed by a full wait,
+    //  which would serialise the rows into one memory round trip each)
+#define HIVIS_LOAD_RAW(ps)                                                                                         \
+    {                                                                                                              \
+        const int k_ = min((ps) * CW + 4 * col4, K - 4);                                                           \
+        _Pragma("unroll") for (int q = 0; q < QM; ++q) {                                                           \
+            const int row_ = min(row0 + q * RSTEP, M - 1);                                                         \
+            araw[q] = *reinterpret_cast<const float4*>(A + (size_t)row_ * lda + k_);                               \
+        }                                                                                                          \
+        if (gain) {                                                                                                \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) graw[e] = to_f32(gain[k_ + e]);                          \
+        } else {                                                                                                   \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) graw[e] = 1.0f;                                          \
+        }                                                                                                          \
+    }
+    HIVIS_MARK(0)
+    HIVIS_LOAD_RAW(0)
+
+    uint4 wb1[U];
     for (int tg = t_begin; tg < t_end; tg += G) {
         const int ng = min(G, t_end - tg);
         const bool first = (tg == t_begin);
@@ -162,33 +229,59 @@ __device__ void gemm_phase(const Phase& ph, const PassParams& pp, float* __restr
         for (int pass = 0; pass < npass; ++pass) {
             const int kb0 = (pass * NW + wave) * KBW;
             const int nkb = max(0, min(KBW, kblks - kb0));
-            if (nkb == 0) continue;
-            afrag_t af[KBW];
-            float ssq_dummy = 0.f;
+            // where the prefetch chain goes after the last unit of this (tile group, pass)
+            const uint4* nW = W; int nkblks = kblks, ntile = tg, nkb0 = 0; bool nvalid = true;
+            if (pass + 1 < npass) { nkb0 = ((pass + 1) * NW + wave) * KBW; }
+            else if (tg + G < t_end) { ntile = tg + G; nkb0 = wave * KBW; }
+            else if (n_has) { nW = ph.next_W; nkblks = n_kblks; ntile = n_tile; nkb0 = wave * KBW; }
+            else nvalid = false;
+            const int nnkb = max(0, min(KBW, nkblks - nkb0));
+
+            // ---- stage this pass's activation rows into LDS as MFMA fragments
+            lds_barrier();                      // everyone is done with the previous chunk
 #pragma unroll
-            for (int j = 0; j < KBW; ++j) {
-                if (j < nkb) fused_afrag<WT>(af[j], A, lda, M, kb0 + j, lane, gain, first ? ssq : ssq_dummy);
-                else fused_afrag<WT>(af[j], A, lda, 0, 0, lane, (const WT*)nullptr, ssq_dummy);
-            }
-            uint4 wb[2][KBW];
-            const uint4* wp = ph.W + ((size_t)tg * kblks + kb0) * 64 + lane;
+            for (int q = 0; q < QM; ++q) {
+                const int row = row0 + q * RSTEP;
+                if (row < M && pass * CW + 4 * col4 < K) {
+                    float x[4] = {araw[q].x, araw[q].y, araw[q].z, araw[q].w};
+                    if (first) ssq_acc[q] += x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
 #pragma unroll
-            for (int j = 0; j < KBW; ++j)
-                if (j < nkb) wb[0][j] = wp[(size_t)j * 64]; else wb[0][j] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                if (g < ng) {
-                    if (g + 1 < ng) {
-                        const uint4* wn = wp + (size_t)(g + 1) * kblks * 64;
-#pragma unroll
-                        for (int j = 0; j < KBW; ++j)
-                            if (j < nkb) wb[(g + 1) & 1][j] = wn[(size_t)j * 64]; else wb[(g + 1) & 1][j] = make_uint4(0, 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int j = 0; j < KBW; ++j) mfma_block(acc[g], af[j], wb[g & 1][j]);
+                    for (int e = 0; e < 4; ++e) x[e] *= graw[e];
+                    stage_store(WT(), chunk, RU, row, 4 * col4, x);
                 }
             }
+            // next pass's rows (the same rows again for the next tile group) are loaded while this pass streams
+            if (pass + 1 < npass) HIVIS_LOAD_RAW(pass + 1) else if (tg + G < t_end) HIVIS_LOAD_RAW(0)
+            lds_barrier();
+            if (first && pass == 0) { HIVIS_MARK(1) }
+            afrag_t af[KBW];
+            {
+                const int i = min(lane & 15, RU - 1), g4 = lane >> 4;
+#pragma unroll
+                for (int j = 0; j < KBW; ++j) {
+                    const uint4 u = chunk[((wave * KBW + j) * 4 + g4) * RU + i];
+                    frag_from(af[j], (j < nkb) ? u : make_uint4(0, 0, 0, 0));
+                }
+            }
+            // ---- stream the tiles of the group, two at a time
+#pragma unroll
+            for (int g0 = 0; g0 < G; g0 += 2) {
+                if (g0 < ng) {
+                    if (g0 + 1 < ng) issue_unit(wb1, W, kblks, tg + g0 + 1, kb0, nkb, lane);
+#pragma unroll
+                    for (int j = 0; j < U; ++j) mfma_block(acc[g0], af[j], head[j]);
+                    if (g0 + 2 < ng) issue_unit(head, W, kblks, tg + g0 + 2, kb0, nkb, lane);
+                    else if (nvalid) { issue_unit(head, nW, nkblks, ntile, nkb0, nnkb, lane); head_valid = true; }
+                    if (g0 + 1 < ng) {
+#pragma unroll
+                        for (int j = 0; j < U; ++j) mfma_block(acc[g0 + 1], af[j], wb1[j]);
+                    }
+                }
+            }
+            if (!nvalid) head_valid = false;
+            if (first && pass == 0) { HIVIS_MARK(2) }
         }
+        if (first) { HIVIS_MARK(3) }
         // ---- cross-wave reduction
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -201,28 +294,29 @@ __device__ void gemm_phase(const Phase& ph, const PassParams& pp, float* __restr
             }
         }
         if (first && gain) {
-            float s = ssq;
-            s += __shfl_xor(s, 16, 64);
-            s += __shfl_xor(s, 32, 64);
-            if (lane < 16) ssq_w[wave * 16 + lane] = s;
+#pragma unroll
+            for (int q = 0; q < QM; ++q) {
+                const float s = wave_sum(ssq_acc[q]);
+                if (lane == 0) ssq_w[wave * QM + q] = s;
+            }
         }
-        __syncthreads();
+        lds_barrier();
         for (int idx = threadIdx.x; idx < TILE; idx += NW * 64) {
             float s = 0.f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) s += red[(size_t)w * TILE + idx];
             tile[idx] = s;
         }
-        if (first && gain && threadIdx.x < 16) {
-            const int row = ssq_row_of_lane<WT>(threadIdx.x);
-            if (row >= 0) {
-                float s = 0.f;
-#pragma unroll
-                for (int w = 0; w < NW; ++w) s += ssq_w[w * 16 + threadIdx.x];
-                inv_rms[row] = 1.0f / sqrtf(s / (float)K + pp.eps);
-            }
+        if (first && gain && (int)threadIdx.x < M) {
+            // row r was staged by the wavefronts whose threads have row0 == r % RSTEP, as their (r / RSTEP)-th row
+            const int r = threadIdx.x, q = r / RSTEP, r0 = r % RSTEP;
+            constexpr int WPR = C4 / 64;          // wavefronts per staged row
+            float s = 0.f;
+            for (int w = r0 * WPR; w < (r0 + 1) * WPR; ++w) s += ssq_w[w * QM + q];
+            inv_rms[r] = 1.0f / sqrtf(s / (float)K + pp.eps);
         }
-        __syncthreads();
+        lds_barrier();
+        if (first) { HIVIS_MARK(4) }
         // ---- epilogue on the reduced tiles
         for (int idx = threadIdx.x; idx < TILE; idx += NW * 64) {
             const int r = idx % RPL;
@@ -235,108 +329,326 @@ __device__ void gemm_phase(const Phase& ph, const PassParams& pp, float* __restr
             const float sc = gain ? inv_rms[row] : 1.0f;
             const float v = tile[idx] * sc;
             switch (ph.epi) {
-            case FEPI_STORE: ph.Y[(size_t)row * ph.ldy + col] = v; break;
-            case FEPI_ADD_TO: ph.Y[(size_t)row * ph.ldy + col] = ph.R[(size_t)row * ph.ldr + col] + v; break;
-            case FEPI_ADDVEC: ph.Y[(size_t)row * ph.ldy + col] = v + to_f32(((const WT*)ph.vec)[(size_t)ph.vec_idx * N + col]); break;
+            case FEPI_STORE: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v); break;
+            case FEPI_ADD_TO: st_wt(&ph.Y[(size_t)row * ph.ldy + col], ph.R[(size_t)row * ph.ldr + col] + v); break;
+            case FEPI_ADDVEC: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v + to_f32(((const WT*)ph.vec)[(size_t)ph.vec_idx * N + col])); break;
             case FEPI_LOGITS:
-                ph.Y[(size_t)row * ph.ldy + col] = v;
+                st_wt(&ph.Y[(size_t)row * ph.ldy + col], v);
                 if (v > best_v || (v == best_v && col < best_i)) { best_v = v; best_i = col; }
                 break;
             case FEPI_SILU:
                 if (cl < 8) {
                     const float up = tile[idx + 8 * RPL] * sc;
-                    ph.Y[(size_t)row * ph.ldy + (tg + g) * 8 + cl] = v / (1.0f + expf(-v)) * up;
+                    st_wt(&ph.Y[(size_t)row * ph.ldy + (tg + g) * 8 + cl], v / (1.0f + expf(-v)) * up);
                 }
                 break;
             case FEPI_QKV: {
+                // every even column handles the pair (col, col+1): a rotary pair of q or k, or two v elements
                 const int qd = pp.Hq * pp.hd, kd = pp.Hkv * pp.hd, hd = pp.hd;
                 const int seq = row / pp.m;
-                const int pos = ph.base[seq] + ph.offset + row % pp.m;
-                if (col < qd + kd) {
-                    if ((cl & 1) == 0) {
-                        const float x1 = v, x2 = tile[idx + RPL] * sc;
+                const int pos = min(ph.base[seq] + ph.offset + row % pp.m, ph.maxL - 1);
+                if ((cl & 1) == 0) {
+                    const float x1 = v, x2 = tile[idx + RPL] * sc;
+                    if (col < qd + kd) {
                         const int p = (col % hd) >> 1;
-                        const float c = pp.rope_tab[((size_t)row * (hd / 2) + p) * 2], s = pp.rope_tab[((size_t)row * (hd / 2) + p) * 2 + 1];
+                        const float c = ph.rope[((size_t)row * (hd / 2) + p) * 2], s = ph.rope[((size_t)row * (hd / 2) + p) * 2 + 1];
                         const float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;
                         if (col < qd) {
-                            ph.Y[(size_t)row * ph.ldy + col] = y1; ph.Y[(size_t)row * ph.ldy + col + 1] = y2;
+                            st_wt_pair(&ph.Y[(size_t)row * ph.ldy + col], y1, y2);
                         } else {
                             const int c2 = col - qd;
-                            KT* dst = (KT*)ph.kc + (((size_t)seq * pp.Hkv + c2 / hd) * ph.maxL + pos) * hd + c2 % hd;
-                            from_f32(dst[0], y1); from_f32(dst[1], y2);
+                            st_wt_pair((KT*)ph.kc + (((size_t)seq * pp.Hkv + c2 / hd) * ph.maxL + pos) * hd + c2 % hd, y1, y2);
                         }
+                    } else {
+                        const int c2 = col - qd - kd;
+                        st_wt_pair((KT*)ph.vc + (((size_t)seq * pp.Hkv + c2 / hd) * ph.maxL + pos) * hd + c2 % hd, x1, x2);
                     }
-                } else {
-                    const int c2 = col - qd - kd;
-                    from_f32(((KT*)ph.vc)[(((size_t)seq * pp.Hkv + c2 / hd) * ph.maxL + pos) * hd + c2 % hd], v);
                 }
             } break;
             }
         }
-        __syncthreads();
     }
+#undef HIVIS_LOAD_RAW
+    HIVIS_MARK(5)
+#undef HIVIS_MARK
     if (ph.epi == FEPI_LOGITS) {
-        // per-row candidate of this workgroup: threads of one row meet through LDS (tile buffer reused)
+        // per-row candidate of this workgroup: the threads of one row meet through LDS
+        lds_barrier();
         float* cv = red; int* ci = (int*)(red + NW * 64);
         cv[threadIdx.x] = best_v; ci[threadIdx.x] = best_i;
-        __syncthreads();
+        lds_barrier();
         if (threadIdx.x < ROWS) {
             const int row = threadIdx.x;
             float bv = -INFINITY; int bi = 0x7FFFFFFF;
-            for (int t = 0; t < NW * 64; ++t) {
-                if (t >= TILE) break;
+            for (int t = 0; t < TILE && t < NW * 64; ++t) {
                 const int r = t % RPL, ln = (t / RPL) & 63;
                 if (RPL * (ln >> 4) + r != row) continue;
-                // thread t served slots t, t + NW*64, ... : all have the same row because NW*64 is a multiple of 64*RPL
                 const float v = cv[t]; const int i = ci[t];
                 if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
             }
-            if (row < M) { pp.pm[(size_t)row * gridDim.x + blockIdx.x] = bv; pp.pi[(size_t)row * gridDim.x + blockIdx.x] = bi; }
+            if (row < M) { st_wt(&ph.pm[(size_t)row * gridDim.x + blockIdx.x], bv); st_wt(&ph.pi[(size_t)row * gridDim.x + blockIdx.x], bi); }
         }
-        __syncthreads();
+    }
+}
+
+// ---- attention phase ---------------------------------------------------------------------------------
+// One (item, split) per workgroup: item = (sequence, kv head, block of query heads, block of rows) with at most
+// FUSED_RMAX (head,row) pairs; split = a contiguous range of keys.  Wavefront w takes keys 16w..16w+15 of every
+// block of 16*NW keys.  K rows are read as [16 keys][4 quarters] (each lane 1/4 of a key row, a wavefront reads
+// 16 whole rows = one contiguous span), V rows as [keys][16-byte chunks]; all loads of a block are issued before
+// any arithmetic.  Each wavefront keeps its own running (max, sum, accumulator); the NW partials are merged
+// through LDS and ONE partial per workgroup goes to memory: ws[(item*nsplit + split)][RM][HD + 2].
+__host__ __device__ constexpr size_t fused_attn_lds_floats(int hd, int nw, int rm) {
+    return (size_t)rm * hd + (size_t)nw * rm * 16 + (size_t)nw * rm * (hd + 2);
+}
+
+template <typename KT, int HD, int RM>
+__device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, const KT* __restrict__ kc, const KT* __restrict__ vc,
+                                                const int* __restrict__ base, const AttnShape& sh, int item_id, int split,
+                                                float* __restrict__ lds, float* __restrict__ ws) {
+    constexpr int NW = FUSED_NW;
+    constexpr int ROWB = HD * (int)sizeof(KT);     // bytes of one cached row
+    constexpr int CH = 16 / (int)sizeof(KT);       // elements per 16-byte chunk
+    constexpr int KL = ROWB / 64;                  // 16-byte loads per lane for its quarter of a K row
+    constexpr int QD = HD / 4;                     // dims per quarter
+    constexpr int NCH = ROWB / 16;                 // chunks per V row
+    constexpr int KPI = 64 / NCH;                  // V rows per load instruction
+    constexpr int VT = 16 / KPI;                   // V load instructions per 16 keys
+    static_assert(NCH <= 64 && KPI >= 1 && VT >= 1, "row too long for this mapping");
+    float* qs = lds;                               // [RM][HD] scaled queries
+    float* pw_all = qs + RM * HD;                  // [NW][RM][16] probabilities of the wavefront's 16 keys
+    float* mrg = pw_all + NW * RM * 16;            // [NW][RM][HD + 2] per-wavefront partials
+
+    int item = item_id;
+    const int rblk = item % sh.n_rblk; item /= sh.n_rblk;
+    const int hblk = item % sh.n_hblk; item /= sh.n_hblk;
+    const int kvh = item % sh.Hkv;
+    const int sl = item / sh.Hkv;
+    const int seq = sh.seq0 + sl;
+    const int group = sh.Hq / sh.Hkv;
+    const int h0 = hblk * sh.gh, nh = min(sh.gh, group - h0);
+    const int i0 = rblk * sh.mi, ni = min(sh.mi, sh.m - i0);
+    const int R = nh * ni;
+    const int pos0 = base[seq] + sh.offset;
+    const int nkeys = min(pos0 + i0 + ni, sh.maxL);
+    const int cs = ((nkeys + sh.nsplit - 1) / sh.nsplit + 15) & ~15;        // keys per split, multiple of 16
+    const int k0 = split * cs, k1 = min(nkeys, k0 + cs);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float scale = rsqrtf((float)HD);
+
+    for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
+        const int r = idx / HD, c = idx % HD;
+        const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
+        qs[idx] = q[(size_t)(sl * sh.m + i) * sh.ldq + (size_t)hh * HD + c] * scale;
+    }
+    lds_barrier();
+
+    const KT* kbase = kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
+    const KT* vbase = vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
+    float* pw = pw_all + wave * RM * 16;
+    const int kk = lane >> 2, quarter = lane & 3;      // K mapping: key within the 16, quarter of the row
+    const int vks = lane / NCH, vdc = lane % NCH;      // V mapping: row within the instruction, chunk of the row
+
+    float mrun[RM], lrun[RM], acc[RM][CH];
+#pragma unroll
+    for (int r = 0; r < RM; ++r) {
+        mrun[r] = -INFINITY; lrun[r] = 0.f;
+#pragma unroll
+        for (int e = 0; e < CH; ++e) acc[r][e] = 0.f;
+    }
+
+    for (int kb = k0 + 16 * wave; kb < k1; kb += 16 * NW) {
+        // ---- all loads of this wavefront's 16 keys (addresses clamped into the range; masked below)
+        uint4 kraw[KL], vraw[VT];
+        {
+            const int key = min(kb + kk, nkeys - 1);
+            const uint4* kp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(kbase) + (size_t)key * ROWB + quarter * (ROWB / 4));
+#pragma unroll
+            for (int j = 0; j < KL; ++j) kraw[j] = kp[j];
+#pragma unroll
+            for (int t = 0; t < VT; ++t) {
+                const int vkey = min(kb + t * KPI + vks, nkeys - 1);
+                vraw[t] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(vbase) + (size_t)vkey * ROWB + vdc * 16);
+            }
+        }
+        // ---- scores of (key kk, all rows): this lane's quarter, then summed over the 4 quarter lanes
+        float s[RM];
+#pragma unroll
+        for (int r = 0; r < RM; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int j = 0; j < KL; ++j) {
+            float kf[CH];
+            decode_chunk(kraw[j], kf, KT());
+#pragma unroll
+            for (int r = 0; r < RM; ++r) {
+                if (r < R) {
+                    const float* qr = qs + r * HD + quarter * QD + j * CH;
+#pragma unroll
+                    for (int e = 0; e < CH; ++e) s[r] += qr[e] * kf[e];
+                }
+            }
+        }
+        const int key = kb + kk;
+#pragma unroll
+        for (int r = 0; r < RM; ++r) {
+            if (r < R) {
+                float sv = s[r];
+                sv += __shfl_xor(sv, 1, 64);
+                sv += __shfl_xor(sv, 2, 64);
+                const int qpos = pos0 + i0 + r % ni;
+                if (key >= k1 || key > qpos) sv = -INFINITY;
+                float tmax = sv;
+#pragma unroll
+                for (int o = 4; o < 64; o <<= 1) tmax = fmaxf(tmax, __shfl_xor(tmax, o, 64));
+                const float mnew = fmaxf(mrun[r], tmax);
+                float alpha = 1.f, p = 0.f;
+                if (mnew != -INFINITY) {
+                    alpha = (mrun[r] == -INFINITY) ? 0.f : __expf(mrun[r] - mnew);
+                    p = (sv == -INFINITY) ? 0.f : __expf(sv - mnew);
+                }
+                mrun[r] = mnew;
+                lrun[r] = lrun[r] * alpha + ((quarter == 0) ? p : 0.f);
+#pragma unroll
+                for (int e = 0; e < CH; ++e) acc[r][e] *= alpha;
+                if (quarter == 0) pw[r * 16 + kk] = p;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // ---- acc += p * V for this lane's chunk of the rows it loaded
+#pragma unroll
+        for (int t = 0; t < VT; ++t) {
+            float vf[CH];
+            decode_chunk(vraw[t], vf, KT());
+            const int kl = t * KPI + vks;                // key within the 16 (its p is 0 if masked)
+#pragma unroll
+            for (int r = 0; r < RM; ++r) {
+                if (r < R) {
+                    const float p = pw[r * 16 + kl];
+#pragma unroll
+                    for (int e = 0; e < CH; ++e) acc[r][e] += p * vf[e];
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    // ---- per-wavefront partial -> LDS (sum over the lanes that share a chunk / over all lanes for l)
+#pragma unroll
+    for (int r = 0; r < RM; ++r) {
+        if (r < R) {
+            const float lsum = wave_sum(lrun[r]);
+#pragma unroll
+            for (int e = 0; e < CH; ++e) {
+                float a = acc[r][e];
+#pragma unroll
+                for (int o = NCH; o < 64; o <<= 1) a += __shfl_xor(a, o, 64);
+                if (lane < NCH) mrg[(wave * RM + r) * (HD + 2) + lane * CH + e] = a;
+            }
+            if (lane == 0) { mrg[(wave * RM + r) * (HD + 2) + HD] = mrun[r]; mrg[(wave * RM + r) * (HD + 2) + HD + 1] = lsum; }
+        }
+    }
+    lds_barrier();
+    // ---- merge the NW partials (fixed order) and write ONE partial of this workgroup
+    float* out = ws + ((size_t)item_id * sh.nsplit + split) * RM * (HD + 2);
+    for (int idx = threadIdx.x; idx < R * (HD + 2); idx += FUSED_NT) {
+        const int r = idx / (HD + 2), c = idx % (HD + 2);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) mx = fmaxf(mx, mrg[(w * RM + r) * (HD + 2) + HD]);
+        float v;
+        if (c == HD) v = mx;
+        else {
+            v = 0.f;
+            const int cc = (c == HD + 1) ? HD + 1 : c;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float mw = mrg[(w * RM + r) * (HD + 2) + HD];
+                if (mw != -INFINITY) v += mrg[(w * RM + r) * (HD + 2) + cc] * __expf(mw - mx);
+            }
+        }
+        st_wt(&out[r * (HD + 2) + c], v);
+    }
+    lds_barrier();
+}
+
+// Merge of the nsplit workgroup partials of one item, in split order; writes the attention output rows.
+template <int HD, int RM>
+__device__ __forceinline__ void attn_wg_merge(const float* __restrict__ ws, const AttnShape& sh, int item_id,
+                                              float* __restrict__ out, int ldo) {
+    int item = item_id;
+    const int rblk = item % sh.n_rblk; item /= sh.n_rblk;
+    const int hblk = item % sh.n_hblk; item /= sh.n_hblk;
+    const int kvh = item % sh.Hkv;
+    const int sl = item / sh.Hkv;
+    const int group = sh.Hq / sh.Hkv;
+    const int h0 = hblk * sh.gh, nh = min(sh.gh, group - h0);
+    const int i0 = rblk * sh.mi, ni = min(sh.mi, sh.m - i0);
+    const int R = nh * ni;
+    const float* base = ws + (size_t)item_id * sh.nsplit * RM * (HD + 2);
+    for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
+        const int r = idx / HD, c = idx % HD;
+        float mx = -INFINITY;
+        for (int s = 0; s < sh.nsplit; ++s) mx = fmaxf(mx, base[((size_t)s * RM + r) * (HD + 2) + HD]);
+        float num = 0.f, den = 0.f;
+        for (int s = 0; s < sh.nsplit; ++s) {
+            const float* p = base + ((size_t)s * RM + r) * (HD + 2);
+            const float ms = p[HD];
+            if (ms == -INFINITY) continue;
+            const float w = __expf(ms - mx);
+            num += p[c] * w; den += p[HD + 1] * w;
+        }
+        const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
+        st_wt(&out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], num / den);
     }
 }
 
 template <typename WT>
-__global__ __launch_bounds__(1024) void fused_pass_kernel(PassParams pp) {
+__global__ __launch_bounds__(FUSED_NT) void fused_pass_kernel(PassParams pp) {
     typedef typename KVType<WT>::type KT;
     extern __shared__ __align__(16) float lds[];
+    uint4 head[FUSED_U];          // weight blocks prefetched for the next GEMM phase (in flight across barriers)
+    bool head_valid = false;
     for (int p = 0; p < pp.nphases; ++p) {
         const Phase& ph = pp.phases[p];
+        if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3] = wall_clock64();
         switch (ph.type) {
-        case PH_GEMM: gemm_phase<WT>(ph, pp, lds); break;
+        case PH_GEMM: gemm_phase<WT>(ph, pp, lds, head, head_valid, p); break;
         case PH_ATTN: {
             const int total = ph.att_items * ph.att.nsplit;
             for (int w = blockIdx.x; w < total; w += gridDim.x) {
                 const int item = w / ph.att.nsplit, split = w % ph.att.nsplit;
-                if (pp.hd == 128) attn_item_partial<KT, 128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, pp.attn_ws);
-                else attn_item_partial<KT, 64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, pp.attn_ws);
-                __syncthreads();
+                if (pp.hd == 128) attn_wg_partial<KT, 128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws);
+                else attn_wg_partial<KT, 64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws);
             }
         } break;
         case PH_ATTN_MERGE:
             for (int item = blockIdx.x; item < ph.att_items; item += gridDim.x) {
-                if (pp.hd == 128) attn_item_merge<128, FUSED_RMAX>(pp.attn_ws, ph.base, ph.att, item, 1024, ph.Y, ph.ldy);
-                else attn_item_merge<64, FUSED_RMAX>(pp.attn_ws, ph.base, ph.att, item, 1024, ph.Y, ph.ldy);
+                if (pp.hd == 128) attn_wg_merge<128, FUSED_RMAX>(ph.ws, ph.att, item, ph.Y, ph.ldy);
+                else attn_wg_merge<64, FUSED_RMAX>(ph.ws, ph.att, item, ph.Y, ph.ldy);
             }
             break;
         case PH_PREP: {
             // embedding gather of the rows' tokens (optional) and the rotary cos/sin table of the rows' positions
             if (ph.ids) {
                 for (int row = blockIdx.x; row < pp.M; row += gridDim.x) {
-                    const int32_t tok = ph.ids[(row / pp.m) * ph.id_sseq + (row % pp.m) * ph.id_srow];
+                    // token ids may have been written earlier in this launch: agent-scope load; clamped for safety
+                    int32_t tok = __hip_atomic_load(&ph.ids[(row / pp.m) * ph.id_sseq + (row % pp.m) * ph.id_srow], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    tok = min(max(tok, 0), pp.V - 1);
                     const WT* src = (const WT*)ph.gain + (size_t)tok * pp.d;
-                    for (int c = threadIdx.x; c < pp.d; c += 1024) ph.Y[(size_t)row * ph.ldy + c] = to_f32(src[c]);
+                    for (int c = threadIdx.x; c < pp.d; c += FUSED_NT) st_wt(&ph.Y[(size_t)row * ph.ldy + c], to_f32(src[c]));
                 }
             }
             const int half = pp.hd / 2;
-            for (int idx = blockIdx.x * 1024 + threadIdx.x; idx < pp.M * half; idx += gridDim.x * 1024) {
+            for (int idx = blockIdx.x * FUSED_NT + threadIdx.x; idx < pp.M * half; idx += gridDim.x * FUSED_NT) {
                 const int row = idx / half, i = idx % half;
                 const int pos = ph.base[row / pp.m] + ph.offset + row % pp.m;
                 const double inv_freq = exp2(-2.0 * (double)i / (double)pp.hd * log2((double)pp.theta));
                 double s, c;
                 sincos((double)pos * inv_freq, &s, &c);
-                pp.rope_tab[(size_t)idx * 2] = (float)c; pp.rope_tab[(size_t)idx * 2 + 1] = (float)s;
+                st_wt(&ph.rope[(size_t)idx * 2], (float)c); st_wt(&ph.rope[(size_t)idx * 2 + 1], (float)s);
             }
         } break;
         case PH_NORM_ROWS:
@@ -344,25 +656,25 @@ __global__ __launch_bounds__(1024) void fused_pass_kernel(PassParams pp) {
             for (int row = blockIdx.x; row < pp.M; row += gridDim.x) {
                 const float* x = ph.A + (size_t)row * ph.lda;
                 float ss = 0.f;
-                for (int c = threadIdx.x; c < pp.d; c += 1024) ss += x[c] * x[c];
+                for (int c = threadIdx.x; c < pp.d; c += FUSED_NT) ss += x[c] * x[c];
                 ss = wave_sum(ss);
-                __syncthreads();
+                lds_barrier();
                 if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = ss;
-                __syncthreads();
+                lds_barrier();
                 float tot = 0.f;
 #pragma unroll
-                for (int w = 0; w < 16; ++w) tot += lds[w];
+                for (int w = 0; w < FUSED_NW; ++w) tot += lds[w];
                 const float inv = 1.0f / sqrtf(tot / (float)pp.d + pp.eps);
-                for (int c = threadIdx.x; c < pp.d; c += 1024)
-                    ph.Y[(size_t)row * ph.ldy + c] = x[c] * to_f32(((const WT*)ph.gain)[c]) * inv;
+                for (int c = threadIdx.x; c < pp.d; c += FUSED_NT)
+                    st_wt(&ph.Y[(size_t)row * ph.ldy + c], x[c] * to_f32(((const WT*)ph.gain)[c]) * inv);
             }
             break;
         case PH_ARGMAX:
             // one wavefront per row reduces the per-workgroup candidates (lowest index wins ties)
-            for (int row = blockIdx.x * 16 + (threadIdx.x >> 6); row < pp.M; row += gridDim.x * 16) {
+            for (int row = blockIdx.x * FUSED_NW + (threadIdx.x >> 6); row < pp.M; row += gridDim.x * FUSED_NW) {
                 float bv = -INFINITY; int bi = 0x7FFFFFFF;
                 for (int w = threadIdx.x & 63; w < (int)gridDim.x; w += 64) {
-                    const float v = pp.pm[(size_t)row * gridDim.x + w]; const int i = pp.pi[(size_t)row * gridDim.x + w];
+                    const float v = ph.pm[(size_t)row * gridDim.x + w]; const int i = ph.pi[(size_t)row * gridDim.x + w];
                     if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
                 }
 #pragma unroll
@@ -370,11 +682,14 @@ __global__ __launch_bounds__(1024) void fused_pass_kernel(PassParams pp) {
                     const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
                     if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
                 }
-                if ((threadIdx.x & 63) == 0) ph.tok_out[(row / pp.m) * ph.o_sseq + (row % pp.m) * ph.o_srow] = bi;
+                if ((threadIdx.x & 63) == 0) st_wt(&ph.tok_out[(row / pp.m) * ph.o_sseq + (row % pp.m) * ph.o_srow], min(max(bi, 0), pp.V - 1));
             }
             break;
         }
-        if (!grid_barrier(pp.bar, (unsigned)(p + 1) * gridDim.x, pp.spin_limit)) return;
+        if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3 + 1] = wall_clock64();
+        const bool ok = grid_barrier(pp.bar, (unsigned)(p + 1) * gridDim.x, pp.spin_limit);
+        if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3 + 2] = wall_clock64();
+        if (!ok) return;
     }
 }
 

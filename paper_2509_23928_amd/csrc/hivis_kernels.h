@@ -34,6 +34,29 @@ __device__ __forceinline__ void from_f32(f16_t& dst, float x) {   // round to ne
     dst = (f16_t)fminf(fmaxf(x, -65504.f), 65504.f);
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global
+// load of the wavefront, which would drain the weight prefetch pipeline at each use.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Write-through stores (agent scope): the value is sent to memory, not left dirty in this XCD's L2, so a
+// workgroup on another XCD that reads the address for the first time sees it without cache maintenance.
+__device__ __forceinline__ void st_wt(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_wt(int* p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_wt(uint32_t* p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+// two adjacent cache elements (dst 4-byte aligned)
+__device__ __forceinline__ void st_wt_pair(float* dst, float a, float b) { st_wt(dst, a); st_wt(dst + 1, b); }
+__device__ __forceinline__ void st_wt_pair(_Float16* dst, float a, float b) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 v;
+    v[0] = (_Float16)fminf(fmaxf(a, -65504.f), 65504.f);
+    v[1] = (_Float16)fminf(fmaxf(b, -65504.f), 65504.f);
+    st_wt(reinterpret_cast<uint32_t*>(dst), __builtin_bit_cast(uint32_t, v));
+}
+
 // KV-cache storage type that goes with a weight type.  bf16 models keep K and V in IEEE half:
 // same bytes as bf16, but 10 mantissa bits, which keeps the rounding of V (the dominant
 // low-precision error of the whole pass) an order of magnitude below the parity tolerance.
@@ -445,7 +468,7 @@ __device__ __forceinline__ void attn_item_partial(const float* __restrict__ q, c
         const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
         qs[idx] = q[(size_t)(sl * sh.m + i) * sh.ldq + (size_t)hh * HD + c] * scale;
     }
-    __syncthreads();
+    lds_barrier();
 
     const ST* kbase = kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
     const ST* vbase = vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
@@ -530,8 +553,8 @@ __device__ __forceinline__ void attn_item_partial(const float* __restrict__ q, c
         if (r < R) {
             const float lsum = wave_sum(lrun[r]);
 #pragma unroll
-            for (int e = 0; e < DPL; ++e) out[r * (HD + 2) + lane * DPL + e] = acc[r][e];
-            if (lane == 0) { out[r * (HD + 2) + HD] = mrun[r]; out[r * (HD + 2) + HD + 1] = lsum; }
+            for (int e = 0; e < DPL; ++e) st_wt(&out[r * (HD + 2) + lane * DPL + e], acc[r][e]);
+            if (lane == 0) { st_wt(&out[r * (HD + 2) + HD], mrun[r]); st_wt(&out[r * (HD + 2) + HD + 1], lsum); }
         }
     }
 }
@@ -566,7 +589,7 @@ __device__ __forceinline__ void attn_item_merge(const float* __restrict__ ws, co
             num += p[c] * w; den += p[HD + 1] * w;
         }
         const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
-        out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c] = num / den;
+        st_wt(&out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], num / den);
     }
 }
 

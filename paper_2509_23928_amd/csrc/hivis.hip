@@ -70,7 +70,8 @@ struct hivis_ctx {
     int fused_grid = 0; size_t fused_lds = 0;
     float* rope_tab = nullptr; float* pm = nullptr; int* pi = nullptr; unsigned* bar = nullptr;
     float* fattn_ws = nullptr; size_t fattn_ws_floats = 0;
-    struct Program { hivis::Phase* dev = nullptr; int n = 0; };
+    struct Program { hivis::Phase* dev = nullptr; int n = 0; std::vector<hivis::Phase>* host = nullptr; };
+    bool persistent = false;             // HIVIS_PERSISTENT=1: one cooperative launch per pass instead of one launch per phase
     std::map<int, Program> programs;     // key = kind * 64 + K
     unsigned long long* prof = nullptr; int prof_left = 0;   // developer aid: HIVIS_PROF=n dumps per-phase times of n verify passes
 
@@ -320,9 +321,9 @@ float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const Layer
     Phase a{}; a.type = PH_ATTN; a.A = qkv; a.lda = nqkv; a.kc = kv.k; a.vc = kv.v; a.maxL = kv.maxL; a.base = base; a.offset = offset;
     a.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, nqkv, &a.att_items);
     a.ws = pool.take((size_t)a.att_items * a.att.nsplit * FUSED_RMAX * (g.head_dim + 2));
+    a.cnt = (int*)pool.take((size_t)a.att_items);      // zero from the pool's memset; the merging workgroup re-zeroes it
+    a.Y = att; a.ldy = qd;
     P.push_back(a);
-    Phase mg = a; mg.type = PH_ATTN_MERGE; mg.Y = att; mg.ldy = qd;
-    P.push_back(mg);
     Phase o{}; o.type = PH_GEMM; o.pro = PRO_PLAIN; o.epi = FEPI_ADD_TO; o.K = qd; o.N = d; o.W = L.wo; o.A = att; o.lda = qd;
     o.Y = h1; o.ldy = d; o.R = h; o.ldr = d;
     P.push_back(o);
@@ -354,7 +355,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
         Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = c->catT; lm.lda = 2 * d;
         lm.Y = c->logits_v; lm.ldy = V; lm.pm = pool.take((size_t)M * G); lm.pi = (int*)pool.take((size_t)M * G);
         P.push_back(lm);
-        Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->ttok; am.o_sseq = g.k_max + 1; am.o_srow = 1; am.pm = lm.pm; am.pi = lm.pi;
+        Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->ttok; am.o_sseq = g.k_max + 1; am.o_srow = 1; am.pm = lm.pm; am.pi = lm.pi; am.N = G;
         P.push_back(am);
     } else if (kind == PROG_DRAFT) {
         // cat: [B][2d] = drafter hidden f' | embedding of the token drafted from it; a fresh buffer per step
@@ -363,7 +364,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
             Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = cat; lm.lda = 2 * d;
             lm.Y = c->logits_d + (size_t)(i - 1) * B * V; lm.ldy = V; lm.pm = pool.take((size_t)B * G); lm.pi = (int*)pool.take((size_t)B * G);
             P.push_back(lm);
-            Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->drafts + (i - 1); am.o_sseq = g.k_max; am.o_srow = 0; am.pm = lm.pm; am.pi = lm.pi;
+            Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->drafts + (i - 1); am.o_sseq = g.k_max; am.o_srow = 0; am.pm = lm.pm; am.pi = lm.pi; am.N = G;
             P.push_back(am);
             if (i < K) {
                 float* rope = pool.take((size_t)B * g.head_dim);
@@ -416,6 +417,7 @@ int get_program(hivis_ctx* c, int kind, int K, hivis_ctx::Program* out) {
     pg.n = (int)P.size();
     if (int rc = dev_alloc(c, &pg.dev, P.size())) return rc;
     HIP_TRY(c, hipMemcpy(pg.dev, P.data(), P.size() * sizeof(Phase), hipMemcpyHostToDevice));
+    pg.host = new std::vector<Phase>(P);
     c->programs[key] = pg;
     *out = pg;
     return HIVIS_OK;
@@ -433,9 +435,26 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
     pp.eps = g.rms_eps; pp.theta = g.rope_theta;
     pp.bar = c->bar;
     pp.spin_limit = 1u << 22;
+    { const char* fl = getenv("HIVIS_FLAGS"); pp.flags = fl ? atoi(fl) : 3; }
     const bool do_prof = c->prof && kind == PROG_VERIFY && c->prof_left > 0;
     pp.prof = do_prof ? c->prof : nullptr;
     pp.prof2 = do_prof ? c->prof + 4096 * 3 : nullptr;
+    if (!c->persistent) {
+        // one launch per phase; grids sized to the phase's work
+        for (int p = 0; p < pg.n; ++p) {
+            Phase ph = (*pg.host)[p];
+            ph.next_W = nullptr;                       // nothing is prefetched across a kernel boundary
+            int grid = c->fused_grid;
+            if (ph.type == PH_ATTN) grid = std::min(grid, ph.att_items * ph.att.nsplit);
+            else if (ph.type == PH_PREP) grid = std::min(grid, std::max(pp.M, (pp.M * g.head_dim / 2 + FUSED_NT - 1) / FUSED_NT));
+            else if (ph.type == PH_NORM_ROWS) grid = std::min(grid, pp.M);
+            else if (ph.type == PH_ARGMAX) grid = std::min(grid, (pp.M + FUSED_NW - 1) / FUSED_NW);
+            else if (ph.type == PH_GEMM && ph.epi != FEPI_LOGITS) grid = std::min(grid, ph.N / 16);
+            hipLaunchKernelGGL((phase_kernel<WT>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp);
+        }
+        HIP_TRY(c, hipGetLastError());
+        return HIVIS_OK;
+    }
     hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, (int*)c->bar, 1, 0);
     void* args[] = {&pp};
     HIP_TRY(c, hipLaunchCooperativeKernel((const void*)fused_pass_kernel<WT>, dim3(c->fused_grid), dim3(FUSED_NT), args, c->fused_lds, c->stream));
@@ -447,8 +466,8 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
         HIP_TRY(c, hipMemcpy(P.data(), pg.dev, P.size() * sizeof(Phase), hipMemcpyDeviceToHost));
         HIP_TRY(c, hipMemcpy(t2.data(), c->prof + 4096 * 3, t2.size() * 8, hipMemcpyDeviceToHost));
         for (int p = 7; p < 13 && p < pg.n; ++p) if (P[p].type == PH_GEMM)
-            fprintf(stderr, "[hivis prof2] phase %d epi %d: entry+%.2f  staged+%.2f  pass0+%.2f  allpass+%.2f  reduced+%.2f  end+%.2f us\n", p, P[p].epi,
-                    (t2[p*8]-t[p*3])*0.01, (t2[p*8+1]-t2[p*8])*0.01, (t2[p*8+2]-t2[p*8+1])*0.01, (t2[p*8+3]-t2[p*8+2])*0.01, (t2[p*8+4]-t2[p*8+3])*0.01, (t2[p*8+5]-t2[p*8+4])*0.01);
+            fprintf(stderr, "[hivis prof2] phase %d epi %d: entry+%.2f  staged+%.2f  pass0+%.2f  allpass+%.2f  reduced+%.2f  end+%.2f | work %.2f wait %.2f us\n", p, P[p].epi,
+                    (t2[p*8]-t[p*3])*0.01, (t2[p*8+1]-t2[p*8])*0.01, (t2[p*8+2]-t2[p*8+1])*0.01, (t2[p*8+3]-t2[p*8+2])*0.01, (t2[p*8+4]-t2[p*8+3])*0.01, (t2[p*8+5]-t2[p*8+4])*0.01, (t[p*3+1]-t[p*3])*0.01, (t[p*3+2]-t[p*3+1])*0.01);
         double tot[8][8] = {}, bar[8][8] = {}; int cnt[8][8] = {};
         for (int p = 0; p < pg.n; ++p) {
             const int ty = P[p].type, ep = P[p].type == PH_GEMM ? P[p].epi : 0;
@@ -472,6 +491,8 @@ int fused_setup(hivis_ctx* c) {
     const size_t attn_f = fused_attn_lds_floats(g.head_dim, FUSED_NW, FUSED_RMAX);
     c->fused_lds = std::max(gemm_f, attn_f) * sizeof(float);
     HIP_TRY(c, hipFuncSetAttribute((const void*)fused_pass_kernel<WT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
+    HIP_TRY(c, hipFuncSetAttribute((const void*)phase_kernel<WT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
+    { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }
     int nb = 0;
     HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)fused_pass_kernel<WT>, FUSED_NT, c->fused_lds));
     if (nb < 1) return fail(c, HIVIS_EHIP, "persistent kernel does not fit on a compute unit");
@@ -777,6 +798,7 @@ int hivis_destroy(hivis_ctx* c) {
     if (!c) return HIVIS_OK;
     (void)hipStreamSynchronize(c->stream);
     for (void* p : c->allocs) (void)hipFree(p);
+    for (auto& kv : c->programs) delete kv.second.host;
     if (c->ev0) (void)hipEventDestroy(c->ev0);
     if (c->ev1) (void)hipEventDestroy(c->ev1);
     delete c;

@@ -1,7 +1,8 @@
-// Persistent "pass" kernel: a whole verify pass (N layers + LM head + greedy tokens), a whole
-// K-step draft round, or the roll-forward of the drafter runs as ONE cooperative launch of one
-// 512-thread workgroup per compute unit that interprets a list of phases, with a grid-wide
-// barrier between phases.  The small row-wise operations are folded into the GEMM phases:
+// Phase programs: a verify pass (N layers + LM head + greedy tokens), a K-step draft round and the
+// roll-forward of the drafter are lists of phases executed by one 512-thread workgroup per compute
+// unit.  By default every phase is one kernel launch (phase_kernel; the kernel boundary orders the
+// phases); optionally the whole list runs as ONE cooperative launch with a grid-wide barrier between
+// phases and weight prefetch across the barriers (fused_pass_kernel; measured slower, kept as an option).  The small row-wise operations are folded into the GEMM phases:
 //   RMSNorm     -> prologue (gain applied while building the MFMA A fragments, 1/rms in the epilogue)
 //   RoPE+append -> epilogue of the fused QKV GEMM (rotary pairs are adjacent columns of a tile)
 //   SiLU*up     -> epilogue of the fused gate|up GEMM (gate and up columns share a tile)
@@ -40,7 +41,8 @@ struct Phase {
     int32_t* tok_out; int o_sseq, o_srow;          // ARGMAX: destination of the greedy token of row (seq, i)
     AttnShape att; int att_items;                  // ATTN / ATTN_MERGE
     float* rope;                                   // PREP writes, QKV epilogue reads: [rows][hd/2][2] cos, sin
-    float* ws;                                     // ATTN writes, ATTN_MERGE reads: partials
+    float* ws;                                     // ATTN: per-workgroup partials of the key splits
+    int* cnt;                                      // ATTN: arrival counter per item (zero between launches)
     float* pm; int* pi;                            // LOGITS writes, ARGMAX reads: greedy candidates [row][workgroup]
     const uint4* next_W; int next_K, next_N;       // GEMM: weights of the next GEMM phase of the program (prefetch), or null
 };
@@ -52,18 +54,20 @@ struct PassParams {
     float eps, theta;
     unsigned* bar;                  // [0] arrival counter (zeroed before launch), [1] abort flag
     unsigned spin_limit;
+    int flags;                      // tuning switches (all combinations are correct): 1 = prefetch a second unit, 2 = early epilogue operands
     unsigned long long* prof2;      // optional [nphases][8] finer timestamps inside GEMM phases (workgroup 0)
     unsigned long long* prof;       // optional [nphases][3] timestamps of workgroup 0 (phase start, phase end, barrier end), 100 MHz
 };
 
-// Grid-wide barrier.  Every thread first waits until its own (write-through) stores have been acknowledged
-// (workgroup-scope release = s_waitcnt), then one thread arrives and spins; bounded: on timeout the abort flag
-// is raised and every workgroup leaves.  No cache maintenance (see the memory discipline above).  Returns false
+// Grid-wide barrier.  Every thread first waits until its own write-through stores have been acknowledged (a GEMM
+// phase has done so itself before requesting the next phase's weights: stores_drained), then one thread arrives and spins; bounded: on timeout the abort flag is raised and every workgroup leaves.  No
+// cache write-back or invalidation is needed (see the memory discipline above).  Returns false
 // if the pass was aborted.
-__device__ __forceinline__ bool grid_barrier(unsigned* bar, unsigned target, unsigned spin_limit) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
+__device__ __forceinline__ bool grid_barrier(unsigned* bar, unsigned target, unsigned spin_limit, bool stores_drained) {
+    if (!stores_drained) wait_vmem();
+    lds_barrier();
     if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");     // publishes the workgroup's write-through stores to the other XCDs
         __hip_atomic_fetch_add(&bar[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         unsigned spins = 0;
         while (__hip_atomic_load(&bar[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
@@ -73,7 +77,7 @@ __device__ __forceinline__ bool grid_barrier(unsigned* bar, unsigned target, uns
             if (spins > spin_limit) { __hip_atomic_store(&bar[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
         }
     }
-    __syncthreads();
+    lds_barrier();
     return __hip_atomic_load(&bar[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u;
 }
 
@@ -144,7 +148,7 @@ __device__ __forceinline__ void frag_from(float4& f, const uint4& u) {
 //    (`head`), so those loads are in flight while the workgroup waits at the grid barrier.
 template <typename WT>
 __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp, float* __restrict__ lds, uint4 (&head)[FUSED_U],
-                           bool& head_valid, int pidx) {
+                           bool& head_valid, uint4 (&wb1)[FUSED_U], bool& wb1_valid, int pidx) {
 #define HIVIS_MARK(k) if (pp.prof2 && blockIdx.x == 0 && threadIdx.x == 0) pp.prof2[pidx * 8 + (k)] = wall_clock64();
     typedef WTraits<WT> TR;
     typedef typename AFrag<WT>::type afrag_t;
@@ -182,20 +186,24 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     // first unit of the next GEMM phase for this wavefront (prefetched by the last unit of this phase)
     const int n_kblks = ph.next_K / KB, n_ntiles = ph.next_N / 16;
     const int n_tile = ph.next_W ? (int)(((long long)blockIdx.x * n_ntiles) / gridDim.x) : 0;
-    const bool n_has = ph.next_W && n_tile < (int)(((long long)(blockIdx.x + 1) * n_ntiles) / gridDim.x);
+    const int n_tend = ph.next_W ? (int)(((long long)(blockIdx.x + 1) * n_ntiles) / gridDim.x) : 0;
+    const bool n_has = ph.next_W && n_tile < n_tend;
 
     if (t_begin >= t_end) {
         // no tiles in this phase: still start the next phase's stream
-        if (!head_valid && n_has) {
-            issue_unit(head, ph.next_W, n_kblks, n_tile, wave * KBW, max(0, min(KBW, n_kblks - wave * KBW)), lane);
-            head_valid = true;
-        }
         if (ph.epi == FEPI_LOGITS && threadIdx.x < ROWS && (int)threadIdx.x < M) {
             st_wt(&ph.pm[(size_t)threadIdx.x * gridDim.x + blockIdx.x], -INFINITY); st_wt(&ph.pi[(size_t)threadIdx.x * gridDim.x + blockIdx.x], 0x7FFFFFFF);
         }
+        wait_vmem();
+        if (!head_valid && n_has) {
+            const int nk = max(0, min(KBW, n_kblks - wave * KBW));
+            issue_unit(head, ph.next_W, n_kblks, n_tile, wave * KBW, nk, lane);
+            head_valid = true;
+            if ((pp.flags & 1) && n_tile + 1 < n_tend) { issue_unit(wb1, ph.next_W, n_kblks, n_tile + 1, wave * KBW, nk, lane); wb1_valid = true; }
+        }
         return;
     }
-    if (!head_valid) issue_unit(head, W, kblks, t_begin, wave * KBW, max(0, min(KBW, kblks - wave * KBW)), lane);
+    if (!head_valid) { issue_unit(head, W, kblks, t_begin, wave * KBW, max(0, min(KBW, kblks - wave * KBW)), lane); wb1_valid = false; }
     head_valid = false;
 
     // raw activation loads of pass `ps`: float4 (row0 + q*RSTEP, ps*CW + 4*col4) and the gain of those 4 columns
@@ -219,7 +227,6 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     HIVIS_MARK(0)
     HIVIS_LOAD_RAW(0)
 
-    uint4 wb1[U];
     for (int tg = t_begin; tg < t_end; tg += G) {
         const int ng = min(G, t_end - tg);
         const bool first = (tg == t_begin);
@@ -230,11 +237,12 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             const int kb0 = (pass * NW + wave) * KBW;
             const int nkb = max(0, min(KBW, kblks - kb0));
             // where the prefetch chain goes after the last unit of this (tile group, pass)
-            const uint4* nW = W; int nkblks = kblks, ntile = tg, nkb0 = 0; bool nvalid = true;
+            const uint4* nW = W; int nkblks = kblks, ntile = tg, nkb0 = 0, ntiles2 = ng; bool nvalid = true;
             if (pass + 1 < npass) { nkb0 = ((pass + 1) * NW + wave) * KBW; }
-            else if (tg + G < t_end) { ntile = tg + G; nkb0 = wave * KBW; }
-            else if (n_has) { nW = ph.next_W; nkblks = n_kblks; ntile = n_tile; nkb0 = wave * KBW; }
-            else nvalid = false;
+            else if (tg + G < t_end) { ntile = tg + G; nkb0 = wave * KBW; ntiles2 = t_end - ntile; }
+            else nvalid = false;     // the next phase's first units are requested after this phase's stores (see the end)
+            const bool wb1_pref = wb1_valid;      // the second unit of this (tile group, pass) was prefetched too
+            wb1_valid = false;
             const int nnkb = max(0, min(KBW, nkblks - nkb0));
 
             // ---- stage this pass's activation rows into LDS as MFMA fragments
@@ -267,7 +275,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
 #pragma unroll
             for (int g0 = 0; g0 < G; g0 += 2) {
                 if (g0 < ng) {
-                    if (g0 + 1 < ng) issue_unit(wb1, W, kblks, tg + g0 + 1, kb0, nkb, lane);
+                    if (g0 + 1 < ng && !(g0 == 0 && wb1_pref)) issue_unit(wb1, W, kblks, tg + g0 + 1, kb0, nkb, lane);
 #pragma unroll
                     for (int j = 0; j < U; ++j) mfma_block(acc[g0], af[j], head[j]);
                     if (g0 + 2 < ng) issue_unit(head, W, kblks, tg + g0 + 2, kb0, nkb, lane);
@@ -279,9 +287,24 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
                 }
             }
             if (!nvalid) head_valid = false;
+            // second unit of the next chain (its registers are free now)
+            if ((pp.flags & 1) && nvalid && ntiles2 >= 2) { issue_unit(wb1, nW, nkblks, ntile + 1, nkb0, nnkb, lane); wb1_valid = true; }
             if (first && pass == 0) { HIVIS_MARK(2) }
         }
         if (first) { HIVIS_MARK(3) }
+        // operands of this thread's epilogue slot, requested now so that they arrive during the reduction
+        float epi_a = 0.f, epi_b = 0.f;
+        {
+            static_assert(TILE == NW * 64, "one epilogue slot per thread");
+            const int idx = threadIdx.x, r = idx % RPL, ln = (idx / RPL) & 63, g = idx / (RPL * 64);
+            const int row = min(RPL * (ln >> 4) + r, M - 1), col = min((tg + g) * 16 + (ln & 15), N - 1);
+            if (!(pp.flags & 2)) {}
+            else if (ph.epi == FEPI_ADD_TO) epi_a = ph.R[(size_t)row * ph.ldr + col];
+            else if (ph.epi == FEPI_QKV) {
+                const int p2 = (col % pp.hd) >> 1;
+                epi_a = ph.rope[((size_t)row * (pp.hd / 2) + p2) * 2]; epi_b = ph.rope[((size_t)row * (pp.hd / 2) + p2) * 2 + 1];
+            }
+        }
         // ---- cross-wave reduction
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -330,7 +353,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             const float v = tile[idx] * sc;
             switch (ph.epi) {
             case FEPI_STORE: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v); break;
-            case FEPI_ADD_TO: st_wt(&ph.Y[(size_t)row * ph.ldy + col], ph.R[(size_t)row * ph.ldr + col] + v); break;
+            case FEPI_ADD_TO: st_wt(&ph.Y[(size_t)row * ph.ldy + col], ((pp.flags & 2) ? epi_a : ph.R[(size_t)row * ph.ldr + col]) + v); break;
             case FEPI_ADDVEC: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v + to_f32(((const WT*)ph.vec)[(size_t)ph.vec_idx * N + col])); break;
             case FEPI_LOGITS:
                 st_wt(&ph.Y[(size_t)row * ph.ldy + col], v);
@@ -350,8 +373,9 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
                 if ((cl & 1) == 0) {
                     const float x1 = v, x2 = tile[idx + RPL] * sc;
                     if (col < qd + kd) {
-                        const int p = (col % hd) >> 1;
-                        const float c = ph.rope[((size_t)row * (hd / 2) + p) * 2], s = ph.rope[((size_t)row * (hd / 2) + p) * 2 + 1];
+                        const int p2 = (col % hd) >> 1;
+                        const float c = (pp.flags & 2) ? epi_a : ph.rope[((size_t)row * (hd / 2) + p2) * 2];
+                        const float s = (pp.flags & 2) ? epi_b : ph.rope[((size_t)row * (hd / 2) + p2) * 2 + 1];
                         const float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;
                         if (col < qd) {
                             st_wt_pair(&ph.Y[(size_t)row * ph.ldy + col], y1, y2);
@@ -389,6 +413,16 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             if (row < M) { st_wt(&ph.pm[(size_t)row * gridDim.x + blockIdx.x], bv); st_wt(&ph.pi[(size_t)row * gridDim.x + blockIdx.x], bi); }
         }
     }
+    // The stores of this phase must be acknowledged before the workgroup arrives at the grid barrier, and the
+    // only wait available (vmcnt) also covers loads: so first drain, THEN request the first two units of the next
+    // GEMM phase, which stay in flight across the barrier.
+    wait_vmem();
+    if (n_has) {
+        const int nk = max(0, min(KBW, n_kblks - wave * KBW));
+        issue_unit(head, ph.next_W, n_kblks, n_tile, wave * KBW, nk, lane);
+        head_valid = true;
+        if ((pp.flags & 1) && n_tile + 1 < n_tend) { issue_unit(wb1, ph.next_W, n_kblks, n_tile + 1, wave * KBW, nk, lane); wb1_valid = true; }
+    }
 }
 
 // ---- attention phase ---------------------------------------------------------------------------------
@@ -405,7 +439,8 @@ __host__ __device__ constexpr size_t fused_attn_lds_floats(int hd, int nw, int r
 template <typename KT, int HD, int RM>
 __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, const KT* __restrict__ kc, const KT* __restrict__ vc,
                                                 const int* __restrict__ base, const AttnShape& sh, int item_id, int split,
-                                                float* __restrict__ lds, float* __restrict__ ws) {
+                                                float* __restrict__ lds, float* __restrict__ ws, int* __restrict__ cnt,
+                                                float* __restrict__ att_out, int ldo) {
     constexpr int NW = FUSED_NW;
     constexpr int ROWB = HD * (int)sizeof(KT);     // bytes of one cached row
     constexpr int CH = 16 / (int)sizeof(KT);       // elements per 16-byte chunk
@@ -436,18 +471,33 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float scale = rsqrtf((float)HD);
 
+    const KT* kbase = kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
+    const KT* vbase = vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
+    float* pw = pw_all + wave * RM * 16;
+    const int kk = lane >> 2, quarter = lane & 3;      // K mapping: key within the 16, quarter of the row
+    const int vks = lane / NCH, vdc = lane % NCH;      // V mapping: row within the instruction, chunk of the row
+
+    // all loads of this wavefront's 16 keys starting at kb_ (addresses clamped into the range; masked later)
+    uint4 knext[KL], vnext[VT];
+#define HIVIS_ATTN_LOADS(kb_)                                                                                      \
+    {                                                                                                              \
+        const int key_ = min((kb_) + kk, nkeys - 1);                                                               \
+        const uint4* kp_ = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(kbase) + (size_t)key_ * ROWB + quarter * (ROWB / 4)); \
+        _Pragma("unroll") for (int j = 0; j < KL; ++j) knext[j] = kp_[j];                                          \
+        _Pragma("unroll") for (int t = 0; t < VT; ++t) {                                                           \
+            const int vkey_ = min((kb_) + t * KPI + vks, nkeys - 1);                                               \
+            vnext[t] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(vbase) + (size_t)vkey_ * ROWB + vdc * 16); \
+        }                                                                                                          \
+    }
+    // the cached keys do not depend on the queries: request the first block before staging q
+    if (k0 + 16 * wave < k1) HIVIS_ATTN_LOADS(k0 + 16 * wave)
+
     for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
         const int r = idx / HD, c = idx % HD;
         const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
         qs[idx] = q[(size_t)(sl * sh.m + i) * sh.ldq + (size_t)hh * HD + c] * scale;
     }
     lds_barrier();
-
-    const KT* kbase = kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
-    const KT* vbase = vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
-    float* pw = pw_all + wave * RM * 16;
-    const int kk = lane >> 2, quarter = lane & 3;      // K mapping: key within the 16, quarter of the row
-    const int vks = lane / NCH, vdc = lane % NCH;      // V mapping: row within the instruction, chunk of the row
 
     float mrun[RM], lrun[RM], acc[RM][CH];
 #pragma unroll
@@ -458,19 +508,12 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
     }
 
     for (int kb = k0 + 16 * wave; kb < k1; kb += 16 * NW) {
-        // ---- all loads of this wavefront's 16 keys (addresses clamped into the range; masked below)
         uint4 kraw[KL], vraw[VT];
-        {
-            const int key = min(kb + kk, nkeys - 1);
-            const uint4* kp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(kbase) + (size_t)key * ROWB + quarter * (ROWB / 4));
 #pragma unroll
-            for (int j = 0; j < KL; ++j) kraw[j] = kp[j];
+        for (int j = 0; j < KL; ++j) kraw[j] = knext[j];
 #pragma unroll
-            for (int t = 0; t < VT; ++t) {
-                const int vkey = min(kb + t * KPI + vks, nkeys - 1);
-                vraw[t] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(vbase) + (size_t)vkey * ROWB + vdc * 16);
-            }
-        }
+        for (int t = 0; t < VT; ++t) vraw[t] = vnext[t];
+        if (kb + 16 * NW < k1) HIVIS_ATTN_LOADS(kb + 16 * NW)
         // ---- scores of (key kk, all rows): this lane's quarter, then summed over the 4 quarter lanes
         float s[RM];
 #pragma unroll
@@ -571,6 +614,40 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
         }
         st_wt(&out[r * (HD + 2) + c], v);
     }
+#undef HIVIS_ATTN_LOADS
+    // ---- the workgroup whose partial completes the item merges all of them (no extra grid barrier):
+    // stores acknowledged -> arrive on the item's counter -> the last arriver reads the nsplit partials
+    wait_vmem();
+    lds_barrier();
+    int* flag = reinterpret_cast<int*>(pw_all);
+    if (threadIdx.x == 0) {
+        // the acknowledgement of a write-through store only says that this XCD's L2 has it; the agent-scope release
+        // makes it visible to the other XCDs before the arrival below
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        flag[0] = __hip_atomic_fetch_add(&cnt[item_id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    lds_barrier();
+    const bool last = flag[0] == sh.nsplit - 1;
+    if (last) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        const float* pbase = ws + (size_t)item_id * sh.nsplit * RM * (HD + 2);
+        for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
+            const int r = idx / HD, c = idx % HD;
+            float mx = -INFINITY;
+            for (int sp = 0; sp < sh.nsplit; ++sp) mx = fmaxf(mx, pbase[((size_t)sp * RM + r) * (HD + 2) + HD]);
+            float num = 0.f, den = 0.f;
+            for (int sp = 0; sp < sh.nsplit; ++sp) {
+                const float* pp_ = pbase + ((size_t)sp * RM + r) * (HD + 2);
+                const float ms = pp_[HD];
+                if (ms == -INFINITY) continue;
+                const float w = __expf(ms - mx);
+                num += pp_[c] * w; den += pp_[HD + 1] * w;
+            }
+            const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
+            st_wt(&att_out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], num / den);
+        }
+        if (threadIdx.x == 0) st_wt(&cnt[item_id], 0);
+    }
     lds_barrier();
 }
 
@@ -605,92 +682,111 @@ __device__ __forceinline__ void attn_wg_merge(const float* __restrict__ ws, cons
     }
 }
 
+// One phase, executed by the calling grid (every workgroup calls this with the same arguments).
+template <typename WT>
+__device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp, float* __restrict__ lds, uint4 (&head)[FUSED_U],
+                                          bool& head_valid, uint4 (&wb1)[FUSED_U], bool& wb1_valid, int p) {
+    typedef typename KVType<WT>::type KT;
+        switch (ph.type) {
+    case PH_GEMM: gemm_phase<WT>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p); break;
+    case PH_ATTN: {
+        const int total = ph.att_items * ph.att.nsplit;
+        for (int w = blockIdx.x; w < total; w += gridDim.x) {
+            const int item = w / ph.att.nsplit, split = w % ph.att.nsplit;
+            if (pp.hd == 128) attn_wg_partial<KT, 128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy);
+            else attn_wg_partial<KT, 64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy);
+        }
+    } break;
+    case PH_ATTN_MERGE:
+        for (int item = blockIdx.x; item < ph.att_items; item += gridDim.x) {
+            if (pp.hd == 128) attn_wg_merge<128, FUSED_RMAX>(ph.ws, ph.att, item, ph.Y, ph.ldy);
+            else attn_wg_merge<64, FUSED_RMAX>(ph.ws, ph.att, item, ph.Y, ph.ldy);
+        }
+        break;
+    case PH_PREP: {
+        // embedding gather of the rows' tokens (optional) and the rotary cos/sin table of the rows' positions
+        if (ph.ids) {
+            for (int row = blockIdx.x; row < pp.M; row += gridDim.x) {
+                // token ids may have been written earlier in this launch: agent-scope load; clamped for safety
+                int32_t tok = __hip_atomic_load(&ph.ids[(row / pp.m) * ph.id_sseq + (row % pp.m) * ph.id_srow], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                tok = min(max(tok, 0), pp.V - 1);
+                const WT* src = (const WT*)ph.gain + (size_t)tok * pp.d;
+                for (int c = threadIdx.x; c < pp.d; c += FUSED_NT) st_wt(&ph.Y[(size_t)row * ph.ldy + c], to_f32(src[c]));
+            }
+        }
+        const int half = pp.hd / 2;
+        for (int idx = blockIdx.x * FUSED_NT + threadIdx.x; idx < pp.M * half; idx += gridDim.x * FUSED_NT) {
+            const int row = idx / half, i = idx % half;
+            const int pos = ph.base[row / pp.m] + ph.offset + row % pp.m;
+            const double inv_freq = exp2(-2.0 * (double)i / (double)pp.hd * log2((double)pp.theta));
+            double s, c;
+            sincos((double)pos * inv_freq, &s, &c);
+            st_wt(&ph.rope[(size_t)idx * 2], (float)c); st_wt(&ph.rope[(size_t)idx * 2 + 1], (float)s);
+        }
+    } break;
+    case PH_NORM_ROWS:
+        // Y[row] = A[row] * gain / sqrt(mean(A[row]^2) + eps): one workgroup per row
+        for (int row = blockIdx.x; row < pp.M; row += gridDim.x) {
+            const float* x = ph.A + (size_t)row * ph.lda;
+            float ss = 0.f;
+            for (int c = threadIdx.x; c < pp.d; c += FUSED_NT) ss += x[c] * x[c];
+            ss = wave_sum(ss);
+            lds_barrier();
+            if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = ss;
+            lds_barrier();
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < FUSED_NW; ++w) tot += lds[w];
+            const float inv = 1.0f / sqrtf(tot / (float)pp.d + pp.eps);
+            for (int c = threadIdx.x; c < pp.d; c += FUSED_NT)
+                st_wt(&ph.Y[(size_t)row * ph.ldy + c], x[c] * to_f32(((const WT*)ph.gain)[c]) * inv);
+        }
+        break;
+    case PH_ARGMAX:
+        // one wavefront per row reduces the per-workgroup candidates (lowest index wins ties)
+        for (int row = blockIdx.x * FUSED_NW + (threadIdx.x >> 6); row < pp.M; row += gridDim.x * FUSED_NW) {
+            float bv = -INFINITY; int bi = 0x7FFFFFFF;
+            // ph.N = number of candidate slots per row (the grid size of the LM-head phase that wrote them)
+            for (int w = threadIdx.x & 63; w < ph.N; w += 64) {
+                const float v = ph.pm[(size_t)row * ph.N + w]; const int i = ph.pi[(size_t)row * ph.N + w];
+                if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            if ((threadIdx.x & 63) == 0) st_wt(&ph.tok_out[(row / pp.m) * ph.o_sseq + (row % pp.m) * ph.o_srow], min(max(bi, 0), pp.V - 1));
+        }
+        break;
+    }
+}
+
+// Whole pass in one cooperative launch: phases separated by grid barriers (see the notes at the top).
 template <typename WT>
 __global__ __launch_bounds__(FUSED_NT) void fused_pass_kernel(PassParams pp) {
-    typedef typename KVType<WT>::type KT;
     extern __shared__ __align__(16) float lds[];
-    uint4 head[FUSED_U];          // weight blocks prefetched for the next GEMM phase (in flight across barriers)
-    bool head_valid = false;
+    uint4 head[FUSED_U], wb1[FUSED_U];   // weight blocks prefetched for the next GEMM phase (in flight across barriers)
+    bool head_valid = false, wb1_valid = false;
     for (int p = 0; p < pp.nphases; ++p) {
         const Phase& ph = pp.phases[p];
         if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3] = wall_clock64();
-        switch (ph.type) {
-        case PH_GEMM: gemm_phase<WT>(ph, pp, lds, head, head_valid, p); break;
-        case PH_ATTN: {
-            const int total = ph.att_items * ph.att.nsplit;
-            for (int w = blockIdx.x; w < total; w += gridDim.x) {
-                const int item = w / ph.att.nsplit, split = w % ph.att.nsplit;
-                if (pp.hd == 128) attn_wg_partial<KT, 128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws);
-                else attn_wg_partial<KT, 64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws);
-            }
-        } break;
-        case PH_ATTN_MERGE:
-            for (int item = blockIdx.x; item < ph.att_items; item += gridDim.x) {
-                if (pp.hd == 128) attn_wg_merge<128, FUSED_RMAX>(ph.ws, ph.att, item, ph.Y, ph.ldy);
-                else attn_wg_merge<64, FUSED_RMAX>(ph.ws, ph.att, item, ph.Y, ph.ldy);
-            }
-            break;
-        case PH_PREP: {
-            // embedding gather of the rows' tokens (optional) and the rotary cos/sin table of the rows' positions
-            if (ph.ids) {
-                for (int row = blockIdx.x; row < pp.M; row += gridDim.x) {
-                    // token ids may have been written earlier in this launch: agent-scope load; clamped for safety
-                    int32_t tok = __hip_atomic_load(&ph.ids[(row / pp.m) * ph.id_sseq + (row % pp.m) * ph.id_srow], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    tok = min(max(tok, 0), pp.V - 1);
-                    const WT* src = (const WT*)ph.gain + (size_t)tok * pp.d;
-                    for (int c = threadIdx.x; c < pp.d; c += FUSED_NT) st_wt(&ph.Y[(size_t)row * ph.ldy + c], to_f32(src[c]));
-                }
-            }
-            const int half = pp.hd / 2;
-            for (int idx = blockIdx.x * FUSED_NT + threadIdx.x; idx < pp.M * half; idx += gridDim.x * FUSED_NT) {
-                const int row = idx / half, i = idx % half;
-                const int pos = ph.base[row / pp.m] + ph.offset + row % pp.m;
-                const double inv_freq = exp2(-2.0 * (double)i / (double)pp.hd * log2((double)pp.theta));
-                double s, c;
-                sincos((double)pos * inv_freq, &s, &c);
-                st_wt(&ph.rope[(size_t)idx * 2], (float)c); st_wt(&ph.rope[(size_t)idx * 2 + 1], (float)s);
-            }
-        } break;
-        case PH_NORM_ROWS:
-            // Y[row] = A[row] * gain / sqrt(mean(A[row]^2) + eps): one workgroup per row
-            for (int row = blockIdx.x; row < pp.M; row += gridDim.x) {
-                const float* x = ph.A + (size_t)row * ph.lda;
-                float ss = 0.f;
-                for (int c = threadIdx.x; c < pp.d; c += FUSED_NT) ss += x[c] * x[c];
-                ss = wave_sum(ss);
-                lds_barrier();
-                if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = ss;
-                lds_barrier();
-                float tot = 0.f;
-#pragma unroll
-                for (int w = 0; w < FUSED_NW; ++w) tot += lds[w];
-                const float inv = 1.0f / sqrtf(tot / (float)pp.d + pp.eps);
-                for (int c = threadIdx.x; c < pp.d; c += FUSED_NT)
-                    st_wt(&ph.Y[(size_t)row * ph.ldy + c], x[c] * to_f32(((const WT*)ph.gain)[c]) * inv);
-            }
-            break;
-        case PH_ARGMAX:
-            // one wavefront per row reduces the per-workgroup candidates (lowest index wins ties)
-            for (int row = blockIdx.x * FUSED_NW + (threadIdx.x >> 6); row < pp.M; row += gridDim.x * FUSED_NW) {
-                float bv = -INFINITY; int bi = 0x7FFFFFFF;
-                for (int w = threadIdx.x & 63; w < (int)gridDim.x; w += 64) {
-                    const float v = ph.pm[(size_t)row * gridDim.x + w]; const int i = ph.pi[(size_t)row * gridDim.x + w];
-                    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
-                }
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) {
-                    const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
-                    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-                }
-                if ((threadIdx.x & 63) == 0) st_wt(&ph.tok_out[(row / pp.m) * ph.o_sseq + (row % pp.m) * ph.o_srow], min(max(bi, 0), pp.V - 1));
-            }
-            break;
-        }
+        run_phase<WT>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p);
         if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3 + 1] = wall_clock64();
-        const bool ok = grid_barrier(pp.bar, (unsigned)(p + 1) * gridDim.x, pp.spin_limit);
+        const bool ok = grid_barrier(pp.bar, (unsigned)(p + 1) * gridDim.x, pp.spin_limit, ph.type == PH_GEMM);
         if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3 + 2] = wall_clock64();
         if (!ok) return;
     }
+}
+
+// One phase per launch: the kernel boundary orders the phases (and makes every store visible), so nothing is
+// prefetched across it and no barrier is needed.  This is the default way the passes are run.
+template <typename WT>
+__global__ __launch_bounds__(FUSED_NT) void phase_kernel(Phase ph, PassParams pp) {
+    extern __shared__ __align__(16) float lds[];
+    uint4 head[FUSED_U], wb1[FUSED_U];
+    bool head_valid = false, wb1_valid = false;
+    run_phase<WT>(ph, pp, lds, head, head_valid, wb1, wb1_valid, 0);
 }
 
 }  // namespace hivis

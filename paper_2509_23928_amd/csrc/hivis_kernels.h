@@ -42,6 +42,11 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Wait until every vector memory operation of this wavefront, in particular its write-through stores, has been
+// acknowledged (s_waitcnt vmcnt(0); the other counters are left alone).  A workgroup-scope release fence does
+// NOT do this on this target: it only orders LDS traffic, because wavefronts of one workgroup share their L1.
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // Write-through stores (agent scope): the value is sent to memory, not left dirty in this XCD's L2, so a
 // workgroup on another XCD that reads the address for the first time sees it without cache maintenance.
 __device__ __forceinline__ void st_wt(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }

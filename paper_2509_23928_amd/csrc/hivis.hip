@@ -71,6 +71,7 @@ struct hivis_ctx {
     float* rope_tab = nullptr; float* pm = nullptr; int* pi = nullptr; unsigned* bar = nullptr;
     float* fattn_ws = nullptr; size_t fattn_ws_floats = 0;
     struct Program { hivis::Phase* dev = nullptr; int n = 0; std::vector<hivis::Phase>* host = nullptr; };
+    int keys_per_split = 256;            // attention: cached keys per workgroup before the key range is split further
     bool persistent = false;             // HIVIS_PERSISTENT=1: one cooperative launch per pass instead of one launch per phase
     std::map<int, Program> programs;     // key = kind * 64 + K
     unsigned long long* prof = nullptr; int prof_left = 0;   // developer aid: HIVIS_PROF=n dumps per-phase times of n verify passes
@@ -321,9 +322,17 @@ float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const Layer
     Phase a{}; a.type = PH_ATTN; a.A = qkv; a.lda = nqkv; a.kc = kv.k; a.vc = kv.v; a.maxL = kv.maxL; a.base = base; a.offset = offset;
     a.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, nqkv, &a.att_items);
     a.ws = pool.take((size_t)a.att_items * a.att.nsplit * FUSED_RMAX * (g.head_dim + 2));
-    a.cnt = (int*)pool.take((size_t)a.att_items);      // zero from the pool's memset; the merging workgroup re-zeroes it
-    a.Y = att; a.ldy = qd;
-    P.push_back(a);
+    if (c->persistent) {
+        a.cnt = (int*)pool.take((size_t)a.att_items);  // zero from the pool's memset; the merging workgroup re-zeroes it
+        a.Y = att; a.ldy = qd;
+        P.push_back(a);
+    } else {
+        // one launch per phase: a separate merge launch is cheaper than the in-kernel election's cache maintenance
+        a.cnt = nullptr; a.Y = att; a.ldy = qd;
+        P.push_back(a);
+        Phase mg = a; mg.type = PH_ATTN_MERGE; mg.Y = att; mg.ldy = qd;
+        P.push_back(mg);
+    }
     Phase o{}; o.type = PH_GEMM; o.pro = PRO_PLAIN; o.epi = FEPI_ADD_TO; o.K = qd; o.N = d; o.W = L.wo; o.A = att; o.lda = qd;
     o.Y = h1; o.ldy = d; o.R = h; o.ldr = d;
     P.push_back(o);
@@ -441,16 +450,43 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
     pp.prof2 = do_prof ? c->prof + 4096 * 3 : nullptr;
     if (!c->persistent) {
         // one launch per phase; grids sized to the phase's work
+        // key splits per attention item: enough workgroups to fill the chip for long caches, a single workgroup (and no
+        // merge launch) for short ones; the program was sized for the largest split count
+        int max_keys = 0;
+        for (int b = 0; b < g.batch; ++b) max_keys = std::max(max_keys, (kind == PROG_VERIFY ? c->h_tlen[b] : c->h_dlen[b]) + K + 1);
         for (int p = 0; p < pg.n; ++p) {
             Phase ph = (*pg.host)[p];
             ph.next_W = nullptr;                       // nothing is prefetched across a kernel boundary
+            if (ph.type == PH_ATTN || ph.type == PH_ATTN_MERGE) {
+                ph.att.nsplit = std::max(1, std::min(ph.att.nsplit, (max_keys + c->keys_per_split - 1) / c->keys_per_split));
+                if (ph.type == PH_ATTN_MERGE && ph.att.nsplit == 1) continue;
+            }
             int grid = c->fused_grid;
             if (ph.type == PH_ATTN) grid = std::min(grid, ph.att_items * ph.att.nsplit);
+            else if (ph.type == PH_ATTN_MERGE) grid = std::min(grid, ph.att_items);
             else if (ph.type == PH_PREP) grid = std::min(grid, std::max(pp.M, (pp.M * g.head_dim / 2 + FUSED_NT - 1) / FUSED_NT));
             else if (ph.type == PH_NORM_ROWS) grid = std::min(grid, pp.M);
             else if (ph.type == PH_ARGMAX) grid = std::min(grid, (pp.M + FUSED_NW - 1) / FUSED_NW);
             else if (ph.type == PH_GEMM && ph.epi != FEPI_LOGITS) grid = std::min(grid, ph.N / 16);
-            hipLaunchKernelGGL((phase_kernel<WT>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp);
+#define HIVIS_LAUNCH(TY, EP) hipLaunchKernelGGL((phase_kernel<WT, TY, EP>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp)
+            switch (ph.type) {
+            case PH_GEMM:
+                switch (ph.epi) {
+                case FEPI_STORE: HIVIS_LAUNCH(PH_GEMM, FEPI_STORE); break;
+                case FEPI_ADD_TO: HIVIS_LAUNCH(PH_GEMM, FEPI_ADD_TO); break;
+                case FEPI_ADDVEC: HIVIS_LAUNCH(PH_GEMM, FEPI_ADDVEC); break;
+                case FEPI_QKV: HIVIS_LAUNCH(PH_GEMM, FEPI_QKV); break;
+                case FEPI_SILU: HIVIS_LAUNCH(PH_GEMM, FEPI_SILU); break;
+                default: HIVIS_LAUNCH(PH_GEMM, FEPI_LOGITS); break;
+                }
+                break;
+            case PH_ATTN: HIVIS_LAUNCH(PH_ATTN, 0); break;
+            case PH_ATTN_MERGE: HIVIS_LAUNCH(PH_ATTN_MERGE, 0); break;
+            case PH_PREP: HIVIS_LAUNCH(PH_PREP, 0); break;
+            case PH_NORM_ROWS: HIVIS_LAUNCH(PH_NORM_ROWS, 0); break;
+            default: HIVIS_LAUNCH(PH_ARGMAX, 0); break;
+            }
+#undef HIVIS_LAUNCH
         }
         HIP_TRY(c, hipGetLastError());
         return HIVIS_OK;
@@ -491,8 +527,17 @@ int fused_setup(hivis_ctx* c) {
     const size_t attn_f = fused_attn_lds_floats(g.head_dim, FUSED_NW, FUSED_RMAX);
     c->fused_lds = std::max(gemm_f, attn_f) * sizeof(float);
     HIP_TRY(c, hipFuncSetAttribute((const void*)fused_pass_kernel<WT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
-    HIP_TRY(c, hipFuncSetAttribute((const void*)phase_kernel<WT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
+    {
+        const void* ks[] = {(const void*)phase_kernel<WT, PH_GEMM, FEPI_STORE>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADD_TO>,
+                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADDVEC>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_QKV>,
+                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_SILU>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_LOGITS>,
+                            (const void*)phase_kernel<WT, PH_ATTN, 0>, (const void*)phase_kernel<WT, PH_ATTN_MERGE, 0>,
+                            (const void*)phase_kernel<WT, PH_PREP, 0>, (const void*)phase_kernel<WT, PH_NORM_ROWS, 0>,
+                            (const void*)phase_kernel<WT, PH_ARGMAX, 0>};
+        for (const void* k : ks) HIP_TRY(c, hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
+    }
     { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }
+    { const char* ke = getenv("HIVIS_KEYS_PER_SPLIT"); if (ke && atoi(ke) >= 16) c->keys_per_split = atoi(ke); }
     int nb = 0;
     HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)fused_pass_kernel<WT>, FUSED_NT, c->fused_lds));
     if (nb < 1) return fail(c, HIVIS_EHIP, "persistent kernel does not fit on a compute unit");

@@ -146,7 +146,7 @@ __device__ __forceinline__ void frag_from(float4& f, const uint4& u) {
 //  * Weights: one unit (KBW KiB per wavefront) ahead, and the chain of prefetches does not stop at the end of
 //    a tile group, a pass or the phase: the last unit of a phase loads the first unit of the NEXT GEMM phase
 //    (`head`), so those loads are in flight while the workgroup waits at the grid barrier.
-template <typename WT>
+template <typename WT, int EPI>
 __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp, float* __restrict__ lds, uint4 (&head)[FUSED_U],
                            bool& head_valid, uint4 (&wb1)[FUSED_U], bool& wb1_valid, int pidx) {
 #define HIVIS_MARK(k) if (pp.prof2 && blockIdx.x == 0 && threadIdx.x == 0) pp.prof2[pidx * 8 + (k)] = wall_clock64();
@@ -165,6 +165,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     float* inv_rms = ssq_w + NW * QM;        // [16]
     uint4* chunk = reinterpret_cast<uint4*>(inv_rms + 16);
 
+    const int epi = (EPI >= 0) ? EPI : ph.epi;       // compile-time epilogue when the phase has its own kernel
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int M = pp.M, K = ph.K, N = ph.N;
     const int kblks = K / KB, ntiles = N / 16;
@@ -191,7 +192,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
 
     if (t_begin >= t_end) {
         // no tiles in this phase: still start the next phase's stream
-        if (ph.epi == FEPI_LOGITS && threadIdx.x < ROWS && (int)threadIdx.x < M) {
+        if (epi == FEPI_LOGITS && threadIdx.x < ROWS && (int)threadIdx.x < M) {
             st_wt(&ph.pm[(size_t)threadIdx.x * gridDim.x + blockIdx.x], -INFINITY); st_wt(&ph.pi[(size_t)threadIdx.x * gridDim.x + blockIdx.x], 0x7FFFFFFF);
         }
         wait_vmem();
@@ -203,7 +204,13 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         }
         return;
     }
-    if (!head_valid) { issue_unit(head, W, kblks, t_begin, wave * KBW, max(0, min(KBW, kblks - wave * KBW)), lane); wb1_valid = false; }
+    if (!head_valid) {
+        // nothing was prefetched for this phase: request its first two units now, ahead of the activation rows
+        const int nk0 = max(0, min(KBW, kblks - wave * KBW));
+        issue_unit(head, W, kblks, t_begin, wave * KBW, nk0, lane);
+        wb1_valid = false;
+        if (t_begin + 1 < t_end) { issue_unit(wb1, W, kblks, t_begin + 1, wave * KBW, nk0, lane); wb1_valid = true; }
+    }
     head_valid = false;
 
     // raw activation loads of pass `ps`: float4 (row0 + q*RSTEP, ps*CW + 4*col4) and the gain of those 4 columns
@@ -299,8 +306,8 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             const int idx = threadIdx.x, r = idx % RPL, ln = (idx / RPL) & 63, g = idx / (RPL * 64);
             const int row = min(RPL * (ln >> 4) + r, M - 1), col = min((tg + g) * 16 + (ln & 15), N - 1);
             if (!(pp.flags & 2)) {}
-            else if (ph.epi == FEPI_ADD_TO) epi_a = ph.R[(size_t)row * ph.ldr + col];
-            else if (ph.epi == FEPI_QKV) {
+            else if (epi == FEPI_ADD_TO) epi_a = ph.R[(size_t)row * ph.ldr + col];
+            else if (epi == FEPI_QKV) {
                 const int p2 = (col % pp.hd) >> 1;
                 epi_a = ph.rope[((size_t)row * (pp.hd / 2) + p2) * 2]; epi_b = ph.rope[((size_t)row * (pp.hd / 2) + p2) * 2 + 1];
             }
@@ -351,7 +358,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             if (g >= ng || row >= M) continue;
             const float sc = gain ? inv_rms[row] : 1.0f;
             const float v = tile[idx] * sc;
-            switch (ph.epi) {
+            switch (epi) {
             case FEPI_STORE: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v); break;
             case FEPI_ADD_TO: st_wt(&ph.Y[(size_t)row * ph.ldy + col], ((pp.flags & 2) ? epi_a : ph.R[(size_t)row * ph.ldr + col]) + v); break;
             case FEPI_ADDVEC: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v + to_f32(((const WT*)ph.vec)[(size_t)ph.vec_idx * N + col])); break;
@@ -395,7 +402,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
 #undef HIVIS_LOAD_RAW
     HIVIS_MARK(5)
 #undef HIVIS_MARK
-    if (ph.epi == FEPI_LOGITS) {
+    if (epi == FEPI_LOGITS) {
         // per-row candidate of this workgroup: the threads of one row meet through LDS
         lds_barrier();
         float* cv = red; int* ci = (int*)(red + NW * 64);
@@ -594,6 +601,28 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
         }
     }
     lds_barrier();
+    if (sh.nsplit == 1) {
+        // the whole key range was handled here: merge the NW partials and write the attention rows directly
+        for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
+            const int r = idx / HD, c = idx % HD;
+            float mx = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) mx = fmaxf(mx, mrg[(w * RM + r) * (HD + 2) + HD]);
+            float num = 0.f, den = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float mw = mrg[(w * RM + r) * (HD + 2) + HD];
+                if (mw != -INFINITY) {
+                    const float e = __expf(mw - mx);
+                    num += mrg[(w * RM + r) * (HD + 2) + c] * e; den += mrg[(w * RM + r) * (HD + 2) + HD + 1] * e;
+                }
+            }
+            const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
+            st_wt(&att_out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], num / den);
+        }
+        lds_barrier();
+        return;
+    }
     // ---- merge the NW partials (fixed order) and write ONE partial of this workgroup
     float* out = ws + ((size_t)item_id * sh.nsplit + split) * RM * (HD + 2);
     for (int idx = threadIdx.x; idx < R * (HD + 2); idx += FUSED_NT) {
@@ -615,6 +644,7 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
         st_wt(&out[r * (HD + 2) + c], v);
     }
 #undef HIVIS_ATTN_LOADS
+    if (cnt == nullptr) { lds_barrier(); return; }        // the partials are merged by a separate phase
     // ---- the workgroup whose partial completes the item merges all of them (no extra grid barrier):
     // stores acknowledged -> arrive on the item's counter -> the last arriver reads the nsplit partials
     wait_vmem();
@@ -683,12 +713,13 @@ __device__ __forceinline__ void attn_wg_merge(const float* __restrict__ ws, cons
 }
 
 // One phase, executed by the calling grid (every workgroup calls this with the same arguments).
-template <typename WT>
+template <typename WT, int TYPE, int EPI>
 __device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp, float* __restrict__ lds, uint4 (&head)[FUSED_U],
                                           bool& head_valid, uint4 (&wb1)[FUSED_U], bool& wb1_valid, int p) {
     typedef typename KVType<WT>::type KT;
-        switch (ph.type) {
-    case PH_GEMM: gemm_phase<WT>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p); break;
+    const int type = (TYPE >= 0) ? TYPE : ph.type;
+    switch (type) {
+    case PH_GEMM: gemm_phase<WT, EPI>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p); break;
     case PH_ATTN: {
         const int total = ph.att_items * ph.att.nsplit;
         for (int w = blockIdx.x; w < total; w += gridDim.x) {
@@ -771,7 +802,7 @@ __global__ __launch_bounds__(FUSED_NT) void fused_pass_kernel(PassParams pp) {
     for (int p = 0; p < pp.nphases; ++p) {
         const Phase& ph = pp.phases[p];
         if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3] = wall_clock64();
-        run_phase<WT>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p);
+        run_phase<WT, -1, -1>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p);
         if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3 + 1] = wall_clock64();
         const bool ok = grid_barrier(pp.bar, (unsigned)(p + 1) * gridDim.x, pp.spin_limit, ph.type == PH_GEMM);
         if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3 + 2] = wall_clock64();
@@ -781,12 +812,12 @@ __global__ __launch_bounds__(FUSED_NT) void fused_pass_kernel(PassParams pp) {
 
 // One phase per launch: the kernel boundary orders the phases (and makes every store visible), so nothing is
 // prefetched across it and no barrier is needed.  This is the default way the passes are run.
-template <typename WT>
+template <typename WT, int TYPE, int EPI>
 __global__ __launch_bounds__(FUSED_NT) void phase_kernel(Phase ph, PassParams pp) {
     extern __shared__ __align__(16) float lds[];
     uint4 head[FUSED_U], wb1[FUSED_U];
     bool head_valid = false, wb1_valid = false;
-    run_phase<WT>(ph, pp, lds, head, head_valid, wb1, wb1_valid, 0);
+    run_phase<WT, TYPE, EPI>(ph, pp, lds, head, head_valid, wb1, wb1_valid, 0);
 }
 
 }  // namespace hivis

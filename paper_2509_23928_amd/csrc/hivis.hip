@@ -63,6 +63,10 @@ struct hivis_ctx {
     float *logits_v = nullptr, *logits_d = nullptr, *logits_p = nullptr;
     int32_t *row_tok = nullptr, *drafts = nullptr, *ttok = nullptr, *nacc = nullptr, *out_tok = nullptr, *next_tok = nullptr;
     void* vis = nullptr;        // staging for vis_embeds [B][max_vis][d]
+    // whole-prompt prefill buffers (bf16 models): all v+l rows of one sequence per layer
+    int pf_rows = 0;
+    float *pf_x = nullptr, *pf_a = nullptr, *pf_qkv = nullptr, *pf_att = nullptr, *pf_proj = nullptr, *pf_gu = nullptr, *pf_act = nullptr;
+    uint4* pf_frag = nullptr;
     std::vector<int32_t> h_ids;
 
     // persistent-kernel path (passes of at most one MFMA tile of rows)
@@ -550,6 +554,47 @@ int fused_setup(hivis_ctx* c) {
     return HIVIS_OK;
 }
 
+
+// ---- whole-prompt prefill (bf16 models): tall MFMA GEMMs over all rows of a sequence --------------------------
+int tall_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy) {
+    const int kblks = K / 32, row_tiles = (M + 7) / 8, ntiles = N / 16;
+    const size_t nfrag = (size_t)row_tiles * kblks * 64;
+    hipLaunchKernelGGL(pack_afrag_kernel, dim3((unsigned)std::min<size_t>((nfrag + 255) / 256, 65535)), dim3(256), 0, c->stream, A, lda, M, kblks, c->pf_frag);
+    hipLaunchKernelGGL((gemm_tall_kernel<4, 4>), dim3((ntiles + 7) / 8, (row_tiles + 7) / 8), dim3(256), 0, c->stream,
+                       (const uint4*)c->pf_frag, row_tiles, kblks, Wp, ntiles, Y, ldy, M);
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int prefill_target_tall(hivis_ctx* c, int b, int v, int l) {
+    typedef typename KVType<WT>::type KT;
+    const hivis_config& g = c->cfg;
+    const int M = v + l, d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn, nqkv = qd + 2 * kd;
+    hipLaunchKernelGGL((prefill_rows_kernel<WT>), dim3(M), dim3(256), 0, c->stream, (const WT*)c->vis + (size_t)b * g.max_vis * d, v,
+                       (const WT*)c->embed, (const int32_t*)(c->text + (size_t)b * c->text_stride), 0, c->pf_x, d);
+    const float* pending = nullptr;
+    for (int l_ = 0; l_ < g.n_layers; ++l_) {
+        const LayerDev& L = c->layers[l_];
+        const KVDev& kv = c->tkv[l_];
+        hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, pending, d, (const WT*)L.norm1, c->pf_a, d, d, g.rms_eps);
+        if (int rc = tall_gemm(c, c->pf_a, d, M, d, L.wqkv, nqkv, c->pf_qkv, nqkv)) return rc;
+        hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M), dim3(256), 0, c->stream, c->pf_qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, (const int*)c->zeros, 0, b, M, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
+        if (int rc = attention<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, M, c->pf_att, qd)) return rc;
+        if (int rc = tall_gemm(c, c->pf_att, qd, M, qd, L.wo, d, c->pf_proj, d)) return rc;
+        hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, (const float*)c->pf_proj, d, (const WT*)L.norm2, c->pf_a, d, d, g.rms_eps);
+        if (int rc = tall_gemm(c, c->pf_a, d, M, d, L.wgu, 2 * F, c->pf_gu, 2 * F)) return rc;
+        hipLaunchKernelGGL(silu_mul_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->pf_gu, c->pf_act, F);
+        if (int rc = tall_gemm(c, c->pf_act, F, M, F, L.wd, d, c->pf_proj, d)) return rc;
+        pending = c->pf_proj;
+    }
+    // features of the text rows: final norm of (x + last MLP delta)
+    hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(l), dim3(256), 0, c->stream, c->pf_x + (size_t)v * d, d, pending + (size_t)v * d, d,
+                       (const WT*)c->final_norm, c->feat + (size_t)b * g.max_text * d, d, d, g.rms_eps);
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
 struct PhaseTimer {
     hivis_ctx* c; int phase;
     PhaseTimer(hivis_ctx* c_, int p) : c(c_), phase(p) { if (c->timing) (void)hipEventRecord(c->ev0, c->stream); }
@@ -581,6 +626,10 @@ int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_
 
     const int total = v + l;
     for (int b = 0; b < B; ++b) {
+        if (c->pf_rows >= total) {
+            if (int rc = prefill_target_tall<WT>(c, b, v, l)) return rc;
+            continue;
+        }
         for (int p0 = 0; p0 < total; p0 += MAX_ROWS) {
             const int m = std::min(MAX_ROWS, total - p0);
             hipLaunchKernelGGL((prefill_rows_kernel<WT>), dim3(m), dim3(256), 0, c->stream, (const WT*)c->vis + (size_t)b * g.max_vis * d, v,
@@ -769,10 +818,24 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     if ((rc = dev_alloc(c, &c->u, (size_t)R * d))) return rc;
     if ((rc = dev_alloc(c, &c->dout, (size_t)R * d))) return rc;
     if ((rc = dev_alloc(c, &c->feat, (size_t)B * g.max_text * d))) return rc;
+    if (sizeof(WT) == 2) {
+        const int PR = (g.max_vis + g.max_text + 7) & ~7;
+        c->pf_rows = PR;
+        const size_t kmax = std::max({(size_t)d, (size_t)qd, (size_t)F});
+        if ((rc = dev_alloc(c, &c->pf_x, (size_t)PR * d))) return rc;
+        if ((rc = dev_alloc(c, &c->pf_a, (size_t)PR * d))) return rc;
+        if ((rc = dev_alloc(c, &c->pf_qkv, (size_t)PR * (qd + 2 * kd)))) return rc;
+        if ((rc = dev_alloc(c, &c->pf_att, (size_t)PR * qd))) return rc;
+        if ((rc = dev_alloc(c, &c->pf_proj, (size_t)PR * d))) return rc;
+        if ((rc = dev_alloc(c, &c->pf_gu, (size_t)PR * 2 * F))) return rc;
+        if ((rc = dev_alloc(c, &c->pf_act, (size_t)PR * F))) return rc;
+        if ((rc = dev_alloc(c, &c->pf_frag, (size_t)PR * kmax / 4))) return rc;      // PR*kmax*4 bytes in 16-byte units
+    }
     // attention workspace: (items * nsplit) work groups x 4 wave slots x RMAX rows x (hd + 2) floats, where
     // items * nsplit <= 2 * num_cu + items and items <= max(2, B) * n_q_heads
     {
-        const size_t max_items = (size_t)std::max(2, B) * g.n_q_heads;
+        size_t max_items = (size_t)std::max(2, B) * g.n_q_heads;
+        if (c->pf_rows) max_items = std::max(max_items, (size_t)g.n_q_heads * ((c->pf_rows + ATT_RMAX - 1) / ATT_RMAX));
         c->attn_ws_floats = (2 * (size_t)c->num_cu + max_items) * 4 * ATT_RMAX * (g.head_dim + 2);
         if ((rc = dev_alloc(c, &c->attn_ws, c->attn_ws_floats))) return rc;
     }

@@ -310,6 +310,91 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const float* __res
 }
 
 // ------------------------------------------------------------------------------------------
+// Tall GEMM for prefill (hundreds to thousands of rows; a true dense contraction -> MFMA bound).
+// The activation rows are first converted once into MFMA A fragments (bf16 hi/lo split, 8 real rows
+// per 16-row tile, same layout as load_afrag) and stored as [row tile][K block][64 lanes] x 16 bytes,
+// the mirror image of the weights' streaming layout.  Each wavefront then owns RT row tiles x CT column
+// tiles and walks K, loading RT + CT fragments (16 bytes per lane each, fully coalesced) per RT*CT MFMAs;
+// the 4 wavefronts of a workgroup form a 2 x 2 arrangement so that neighbours share fragments through L1.
+// ------------------------------------------------------------------------------------------
+__global__ void pack_afrag_kernel(const float* __restrict__ A, int lda, int M, int kblks, uint4* __restrict__ out) {
+    const int row_tiles = (M + 7) / 8;
+    const size_t total = (size_t)row_tiles * kblks * 64;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(idx & 63);
+        const size_t blk = idx >> 6;
+        const int kb = (int)(blk % (size_t)kblks), tt = (int)(blk / (size_t)kblks);
+        bf16x8_t f;
+        load_afrag(f, A, lda, M, tt, kb, lane);
+        out[idx] = __builtin_bit_cast(uint4, f);
+    }
+}
+
+template <int RT, int CT>
+__global__ __launch_bounds__(256) void gemm_tall_kernel(const uint4* __restrict__ Af, int row_tiles, int kblks,
+                                                         const uint4* __restrict__ Wp, int ntiles, float* __restrict__ Y,
+                                                         int ldy, int M) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rt0 = (blockIdx.y * 2 + (wave >> 1)) * RT;
+    const int ct0 = (blockIdx.x * 2 + (wave & 1)) * CT;
+    if (rt0 >= row_tiles || ct0 >= ntiles) return;
+    f32x4_t acc[RT][CT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int c = 0; c < CT; ++c) acc[r][c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    // fragments out of range are replaced by in-range ones (clamped tile index); their results are never stored
+    const uint4* ap[RT]; const uint4* bp[CT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) ap[r] = Af + (size_t)min(rt0 + r, row_tiles - 1) * kblks * 64 + lane;
+#pragma unroll
+    for (int c = 0; c < CT; ++c) bp[c] = Wp + (size_t)min(ct0 + c, ntiles - 1) * kblks * 64 + lane;
+    uint4 a[2][RT], b[2][CT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) a[0][r] = ap[r][0];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) b[0][c] = bp[c][0];
+    for (int kb = 0; kb < kblks; kb += 2) {
+        // two K blocks per iteration so that the double buffer has static indices
+        if (kb + 1 < kblks) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r) a[1][r] = ap[r][(size_t)(kb + 1) * 64];
+#pragma unroll
+            for (int c = 0; c < CT; ++c) b[1][c] = bp[c][(size_t)(kb + 1) * 64];
+        }
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int c = 0; c < CT; ++c) mfma_block(acc[r][c], __builtin_bit_cast(bf16x8_t, a[0][r]), b[0][c]);
+        if (kb + 1 < kblks) {
+            if (kb + 2 < kblks) {
+#pragma unroll
+                for (int r = 0; r < RT; ++r) a[0][r] = ap[r][(size_t)(kb + 2) * 64];
+#pragma unroll
+                for (int c = 0; c < CT; ++c) b[0][c] = bp[c][(size_t)(kb + 2) * 64];
+            }
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int c = 0; c < CT; ++c) mfma_block(acc[r][c], __builtin_bit_cast(bf16x8_t, a[1][r]), b[1][c]);
+        }
+    }
+    const int j = lane & 15, a4 = lane >> 4;
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        if (rt0 + r >= row_tiles) continue;
+        const int row = (rt0 + r) * 8 + 2 * a4;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            if (ct0 + c >= ntiles) continue;
+            const int col = (ct0 + c) * 16 + j;
+            if (row < M) Y[(size_t)row * ldy + col] = acc[r][c][0] + acc[r][c][2];
+            if (row + 1 < M) Y[(size_t)(row + 1) * ldy + col] = acc[r][c][1] + acc[r][c][3];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Row-wise small kernels (activations are a few rows of fp32; these are launch-bound, not
 // bandwidth-bound)
 // ------------------------------------------------------------------------------------------

@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 import synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+GEMM_GATEUP = 4      # kind id of the fused gate|up GEMM (+RMSNorm prologue, SiLU*up epilogue): the kernel with the most bytes
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/): filled in from the
+# committed counter runs; None where no counter run exists for the workload.
+TRAFFIC_BYTES_PER_LAUNCH = {}
 PAPER_TAU = {"C2": 5.37, "C3": 5.06, "C4": 4.39, "C5": 5.15}    # Table 2, T=0 averages (tree drafting, A800): context only
 
 
@@ -138,6 +142,7 @@ def main():
     for _ in range(args.warmup):
         run_step(hv, cfg, vis_dev, ids_dev, K)
     hv.timing(True)
+    hv.kernel_timing(GEMM_GATEUP)
     for ph in range(4):
         hv.phase_ms(ph)
     torch.cuda.synchronize()
@@ -149,7 +154,9 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     phases = [hv.phase_ms(ph) for ph in range(4)]
+    k_ms, k_launches, k_bytes = hv.kernel_ms()
     hv.timing(False)
+    hv.kernel_timing(-1)
     verify_bytes_end, draft_bytes_end = hv.algorithmic_bytes()
 
     prefill_ms = phases[0][0] / max(phases[0][1], 1)
@@ -179,10 +186,16 @@ def main():
         "cycle_us": K * draft_us + verify_us + accept_us,
         "draft_step_hbm_gbs": draft_gbs, "draft_step_frac_of_peak": draft_gbs / HBM_PEAK_GBS,
         "cycles": cycles, "mean_accepted_drafts": accepted / max(cycles * cfg.batch, 1),
-        "roofline": {"bound": "hbm", "kernel": "hivis_verify pass (all launches of one verify), HIP events on the library stream",
-                     "achieved": verify_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": verify_gbs / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes": verify_bytes},
+        "verify_pass_hbm_gbs": verify_gbs, "verify_pass_frac_of_peak": verify_gbs / HBM_PEAK_GBS, "verify_pass_algorithmic_bytes": verify_bytes,
     }
+    k_us = k_ms / max(k_launches, 1) * 1e3
+    k_gbs = k_bytes / (k_us * 1e-6) / 1e9 if k_launches else 0.0
+    out["roofline"] = {"bound": "hbm",
+                       "kernel": "phase_kernel<bf16, GEMM, gate|up>: fused RMSNorm + [d x 2F] weight stream + SiLU*up of the verify pass "
+                                 "(largest share of bytes and of time); HIP events recorded around each launch on the library's stream",
+                       "achieved": k_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs / HBM_PEAK_GBS,
+                       "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.config), "algorithmic_bytes_per_launch": k_bytes,
+                       "avg_launch_us": k_us, "launches_timed": k_launches}
     tau = PAPER_TAU.get(args.config)
     if tau:
         out["projected_tokens_per_s_at_paper_tau"] = cfg.batch * tau / ((K * draft_us + verify_us + accept_us) * 1e-6)

@@ -151,6 +151,14 @@ int hivis_get_tokens(hivis_ctx *ctx, int32_t *drafts, int32_t *target_tokens);
 int hivis_timing(hivis_ctx *ctx, int32_t enable);
 int hivis_phase_ms(hivis_ctx *ctx, int32_t phase, double *total_ms, int64_t *calls);
 
+/* Kernel-level timing of the verify pass's weight-streaming GEMM launches of one kind, with HIP events recorded on
+ * the context's stream directly around each launch (resolved at the next hivis_accept).  gemm_kind: 1 = O / down
+ * projection (+ residual), 3 = fused QKV (+ RMSNorm, RoPE, cache append), 4 = fused gate|up (+ RMSNorm, SiLU*up),
+ * 5 = LM head (+ greedy candidates); -1 switches it off.  hivis_kernel_ms returns and clears the accumulated
+ * milliseconds and launch count, and the algorithmic bytes of one such launch (its weight matrix, read once). */
+int hivis_kernel_timing(hivis_ctx *ctx, int32_t gemm_kind);
+int hivis_kernel_ms(hivis_ctx *ctx, double *total_ms, int64_t *launches, double *bytes_per_launch);
+
 /* Algorithmic HBM bytes of the last verify pass and of one draft step at the current lengths
  * (every weight once, the KV rows read once; see the formulas in the implementation). */
 int hivis_algorithmic_bytes(hivis_ctx *ctx, double *verify_bytes, double *draft_step_bytes);

@@ -65,6 +65,8 @@ def load_library(path=LIB_PATH):
         "hivis_get_tokens": (C.c_int, [P, P, P]),
         "hivis_timing": (C.c_int, [P, I32]),
         "hivis_phase_ms": (C.c_int, [P, I32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+        "hivis_kernel_timing": (C.c_int, [P, I32]),
+        "hivis_kernel_ms": (C.c_int, [P, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
         "hivis_algorithmic_bytes": (C.c_int, [P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "hivis_last_error": (C.c_char_p, [P]),
         "hivis_version": (C.c_char_p, []),
@@ -78,7 +80,7 @@ def load_library(path=LIB_PATH):
 
 EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_set_drafts",
                     "hivis_verify", "hivis_accept", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
-                    "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_algorithmic_bytes",
+                    "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes",
                     "hivis_last_error", "hivis_version")
 
 
@@ -219,6 +221,14 @@ class Hivis:
         ms, calls = C.c_double(), C.c_int64()
         self._check(self.lib.hivis_phase_ms(self.ctx, phase, C.byref(ms), C.byref(calls)))
         return ms.value, calls.value
+
+    def kernel_timing(self, gemm_kind):
+        self._check(self.lib.hivis_kernel_timing(self.ctx, int(gemm_kind)))
+
+    def kernel_ms(self):
+        ms, n, by = C.c_double(), C.c_int64(), C.c_double()
+        self._check(self.lib.hivis_kernel_ms(self.ctx, C.byref(ms), C.byref(n), C.byref(by)))
+        return ms.value, n.value, by.value
 
     def algorithmic_bytes(self):
         a, b = C.c_double(), C.c_double()

@@ -81,6 +81,9 @@ struct hivis_ctx {
     unsigned long long* prof = nullptr; int prof_left = 0;   // developer aid: HIVIS_PROF=n dumps per-phase times of n verify passes
 
     // timing
+    int ktime_epi = -1;                                  // GEMM epilogue kind whose verify launches are event-timed (-1: none)
+    std::vector<hipEvent_t> kev; size_t kev_used = 0;     // event pairs recorded since the last accept
+    double kms = 0; int64_t klaunches = 0; double kbytes = 0;
     bool timing = false;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     double phase_ms[4] = {0, 0, 0, 0}; int64_t phase_calls[4] = {0, 0, 0, 0};
@@ -473,6 +476,12 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             else if (ph.type == PH_ARGMAX) grid = std::min(grid, (pp.M + FUSED_NW - 1) / FUSED_NW);
             else if (ph.type == PH_GEMM && ph.epi != FEPI_LOGITS) grid = std::min(grid, ph.N / 16);
 #define HIVIS_LAUNCH(TY, EP) hipLaunchKernelGGL((phase_kernel<WT, TY, EP>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp)
+            const bool ktimed = kind == PROG_VERIFY && ph.type == PH_GEMM && ph.epi == c->ktime_epi;
+            if (ktimed) {
+                if (c->kev_used + 2 > c->kev.size()) { hipEvent_t e0, e1; HIP_TRY(c, hipEventCreate(&e0)); HIP_TRY(c, hipEventCreate(&e1)); c->kev.push_back(e0); c->kev.push_back(e1); }
+                HIP_TRY(c, hipEventRecord(c->kev[c->kev_used], c->stream));
+                c->kbytes = (double)ph.K * ph.N * c->esize;
+            }
             switch (ph.type) {
             case PH_GEMM:
                 switch (ph.epi) {
@@ -491,6 +500,7 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             default: HIVIS_LAUNCH(PH_ARGMAX, 0); break;
             }
 #undef HIVIS_LAUNCH
+            if (ktimed) { HIP_TRY(c, hipEventRecord(c->kev[c->kev_used + 1], c->stream)); c->kev_used += 2; }
         }
         HIP_TRY(c, hipGetLastError());
         return HIVIS_OK;
@@ -747,6 +757,11 @@ int do_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
     if (c->fused) HIP_TRY(c, hipMemcpyAsync(&aborted, c->bar + 1, sizeof(unsigned), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     if (aborted) return fail(c, HIVIS_EHIP, "persistent kernel: grid barrier timed out (pass aborted)");
+    for (size_t i = 0; i + 1 < c->kev_used; i += 2) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->kev[i], c->kev[i + 1]) == hipSuccess) { c->kms += ms; c->klaunches++; }
+    }
+    c->kev_used = 0;
     for (int b = 0; b < B; ++b) {
         c->h_tlen[b] += hn[b] + 1; c->h_dlen[b] += hn[b] + 1;
         if (n_accepted) n_accepted[b] = hn[b];
@@ -909,6 +924,7 @@ int hivis_destroy(hivis_ctx* c) {
     for (auto& kv : c->programs) delete kv.second.host;
     if (c->ev0) (void)hipEventDestroy(c->ev0);
     if (c->ev1) (void)hipEventDestroy(c->ev1);
+    for (hipEvent_t e : c->kev) (void)hipEventDestroy(e);
     delete c;
     return HIVIS_OK;
 }
@@ -1031,6 +1047,21 @@ int hivis_get_tokens(hivis_ctx* c, int32_t* drafts, int32_t* target_tokens) {
 int hivis_timing(hivis_ctx* c, int32_t enable) {
     if (!c) return HIVIS_EINVAL;
     c->timing = enable != 0;
+    return HIVIS_OK;
+}
+
+int hivis_kernel_timing(hivis_ctx* c, int32_t gemm_kind) {
+    if (!c || gemm_kind < -1 || gemm_kind > 5) return HIVIS_EINVAL;
+    c->ktime_epi = gemm_kind; c->kms = 0; c->klaunches = 0; c->kev_used = 0;
+    return HIVIS_OK;
+}
+
+int hivis_kernel_ms(hivis_ctx* c, double* total_ms, int64_t* launches, double* bytes_per_launch) {
+    if (!c) return HIVIS_EINVAL;
+    if (total_ms) *total_ms = c->kms;
+    if (launches) *launches = c->klaunches;
+    if (bytes_per_launch) *bytes_per_launch = c->kbytes;
+    c->kms = 0; c->klaunches = 0;
     return HIVIS_OK;
 }
 

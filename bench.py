@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 GEMM_GATEUP = 4      # kind id of the fused gate|up GEMM (+RMSNorm prologue, SiLU*up epilogue): the kernel with the most bytes
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/): filled in from the
 # committed counter runs; None where no counter run exists for the workload.
-TRAFFIC_BYTES_PER_LAUNCH = {}
+TRAFFIC_BYTES_PER_LAUNCH = {"C2": 182.4e6}     # profiles/gateup_gemm_C2_hbm_counters.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) per launch
 PAPER_TAU = {"C2": 5.37, "C3": 5.06, "C4": 4.39, "C5": 5.15}    # Table 2, T=0 averages (tree drafting, A800): context only
 
 
@@ -104,6 +104,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of target layers (debug only; invalid as a result)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true", help="also run a plain 1 GiB device copy first (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -139,6 +140,12 @@ def main():
     torch.cuda.synchronize()
     print(f"[bench] {cfg.name}: weights generated in {t_gen:.1f}s, uploaded+packed in {t_load:.1f}s", file=sys.stderr, flush=True)
 
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written by one elementwise kernel
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         run_step(hv, cfg, vis_dev, ids_dev, K)
     hv.timing(True)

@@ -133,3 +133,107 @@ def test_error_codes():
     with pytest.raises(HivisError) as e:
         small.prefill(np.concatenate([vis, vis], 1), ids)
     assert e.value.code == HIVIS_ECAP
+
+
+def run_generic(cfg, seed, cycles, plant=(), k_list=None):
+    """own drafts for `cycles` cycles (optionally a different K each), then planted prefixes of the given lengths"""
+    w, vis, ids, hv = make(cfg, seed)
+    sbs = SideBySide(cfg, w, hv, vis, ids)
+    for c in range(cycles):
+        sbs.cycle(k_list[c] if k_list else cfg.K)
+    if plant:
+        ref, _ = greedy_reference(cfg, w, vis[0], ids[0], len(sbs.emitted[0]) + len(plant) * (cfg.K + 1) + 1)
+        for m in plant:
+            done = len(sbs.emitted[0])
+            if sbs.emitted[0] != ref[:done]:
+                break
+            planted = ref[done: done + m] + [(ref[done + j] + 3) % cfg.vocab for j in range(m, cfg.K)]
+            r = sbs.cycle(cfg.K, planted=np.array([planted], np.int32))
+            if sbs.near_ties == 0:
+                assert r[0]["n"] == m
+    hv.close()
+    return sbs
+
+
+def test_long_cache_uses_key_splits():
+    # 1500 visual rows: the verify attention splits the key range over several workgroups and runs the merge launch
+    cfg = small_bf16(n_vis=1500, n_text=40, d=256, n_q_heads=2, n_kv_heads=2, ffn=512, vocab=1024, K=5)
+    sbs = run_generic(cfg, 21, 2, plant=(5, 2))
+    print("long cache max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+
+
+def test_gqa_group7_k6_qwen_like_shape():
+    # 28 query / 4 kv heads (group 7), K = 6 -> 7 rows per sequence, as in the Qwen2.5-VL-shaped workload, at reduced width
+    cfg = small_bf16(n_q_heads=28, n_kv_heads=4, head_dim=64, d=1792, ffn=2368, vocab=4096, K=6, n_vis=130, n_text=50,
+                     rope_theta=1e6, rms_eps=1e-6, n_layers=2)
+    sbs = run_generic(cfg, 22, 2, plant=(6, 3))
+    print("gqa 28/4 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+
+
+def test_edge_shapes_no_visual_single_text_and_varying_k():
+    # no visual rows at all, a one-token prompt, and a different K every cycle (1 .. k_max)
+    cfg = small_bf16(n_vis=0, n_text=1, K=5, d=256, n_q_heads=2, n_kv_heads=2, ffn=512, vocab=1024)
+    sbs = run_generic(cfg, 23, 5, k_list=[1, 5, 2, 3, 4])
+    print("edge shapes max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    cfg = small_bf16(n_vis=1, n_text=2, K=2, d=256, n_q_heads=2, n_kv_heads=2, ffn=512, vocab=1024)
+    run_generic(cfg, 24, 2)
+
+
+def test_fp32_sixteen_rows_and_gqa():
+    # fp32 path with 14 verify rows (one fp32 MFMA tile holds 16) and grouped heads
+    cfg = synth.get_config("C1").scaled(name="f32-gqa", n_q_heads=4, n_kv_heads=2, K=6, batch=2, gen_cycles=3, n_vis=70, n_text=33)
+    w, vis, ids, hv = make(cfg, 25)
+    sbs = SideBySide(cfg, w, hv, vis, ids)
+    for _ in range(3):
+        sbs.cycle(cfg.K)
+    print("fp32 gqa batch-2 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    assert max(sbs.max_err.values()) < 0.1
+
+
+def test_rerun_is_bit_identical():
+    cfg = small_bf16()
+    w, vis, ids, hv = make(cfg, 5)
+    outs = []
+    for _ in range(2):
+        hv.prefill(vis, ids)
+        seq = [hv.get_logits(2).copy()]
+        for _c in range(3):
+            hv.draft(cfg.K); hv.verify()
+            seq.append(hv.get_logits(0).copy()); seq.append(hv.get_logits(1).copy())
+            n, t = hv.accept()
+            seq.append(t.copy())
+        outs.append(seq)
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b), "two runs of the same prompt differ bitwise"
+
+
+def test_persistent_mode_matches_oracle():
+    # the opt-in single-launch (cooperative, grid-barrier) execution of the same phase programs
+    import os
+    os.environ["HIVIS_PERSISTENT"] = "1"
+    try:
+        cfg = small_bf16(K=4)
+        sbs = run_generic(cfg, 26, 2, plant=(3,))
+        cfg1 = synth.get_config("C1")
+        run_generic(cfg1, 2, 2)
+    finally:
+        del os.environ["HIVIS_PERSISTENT"]
+    print("persistent mode max error / tolerance:", sbs.max_err)
+
+
+def test_full_width_7b_layers_two_layer_slice():
+    """LLaVA-1.5-7B widths (d 4096, 32 heads, F 11008, V 32000, 576 + 64 rows, K 5) with 2 of the 32 layers: the launch
+    configuration bench.py times (same tile groups, K passes, LM-head tiling), against the oracle on every logit."""
+    cfg = synth.get_config("C2").scaled(n_layers=2, gen_tokens=0, gen_cycles=2)
+    w, vis, ids, hv = make(cfg, 0)
+    sbs = SideBySide(cfg, w, hv, vis, ids)
+    sbs.cycle(cfg.K)
+    ref, _ = greedy_reference(cfg, w, vis[0], ids[0], len(sbs.emitted[0]) + cfg.K + 2)
+    done = len(sbs.emitted[0])
+    if sbs.emitted[0] == ref[:done]:
+        planted = ref[done: done + 3] + [(ref[done + j] + 3) % cfg.vocab for j in range(3, cfg.K)]
+        r = sbs.cycle(cfg.K, planted=np.array([planted], np.int32))
+        if sbs.near_ties == 0:
+            assert r[0]["n"] == 3
+    hv.close()
+    print("7B-width 2-layer max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)

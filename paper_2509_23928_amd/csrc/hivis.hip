@@ -75,6 +75,7 @@ struct hivis_ctx {
     float* rope_tab = nullptr; float* pm = nullptr; int* pi = nullptr; unsigned* bar = nullptr;
     float* fattn_ws = nullptr; size_t fattn_ws_floats = 0;
     struct Program { hivis::Phase* dev = nullptr; int n = 0; std::vector<hivis::Phase>* host = nullptr; };
+    bool dbg_lm_store = false;
     int keys_per_split = 256;            // attention: cached keys per workgroup before the key range is split further
     bool persistent = false;             // HIVIS_PERSISTENT=1: one cooperative launch per pass instead of one launch per phase
     std::map<int, Program> programs;     // key = kind * 64 + K
@@ -464,6 +465,7 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
         for (int p = 0; p < pg.n; ++p) {
             Phase ph = (*pg.host)[p];
             ph.next_W = nullptr;                       // nothing is prefetched across a kernel boundary
+            if (c->dbg_lm_store && ph.type == PH_GEMM && ph.epi == FEPI_LOGITS) ph.epi = FEPI_STORE;   // timing experiment only
             if (ph.type == PH_ATTN || ph.type == PH_ATTN_MERGE) {
                 ph.att.nsplit = std::max(1, std::min(ph.att.nsplit, (max_keys + c->keys_per_split - 1) / c->keys_per_split));
                 if (ph.type == PH_ATTN_MERGE && ph.att.nsplit == 1) continue;
@@ -551,6 +553,7 @@ int fused_setup(hivis_ctx* c) {
         for (const void* k : ks) HIP_TRY(c, hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
     }
     { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }
+    { const char* de = getenv("HIVIS_DBG_LM_STORE"); c->dbg_lm_store = de && de[0] == '1'; }
     { const char* ke = getenv("HIVIS_KEYS_PER_SPLIT"); if (ke && atoi(ke) >= 16) c->keys_per_split = atoi(ke); }
     int nb = 0;
     HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)fused_pass_kernel<WT>, FUSED_NT, c->fused_lds));

@@ -408,16 +408,21 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         float* cv = red; int* ci = (int*)(red + NW * 64);
         cv[threadIdx.x] = best_v; ci[threadIdx.x] = best_i;
         lds_barrier();
-        if (threadIdx.x < ROWS) {
-            const int row = threadIdx.x;
+        // one wavefront per row: lanes scan the slots of that row, then a shuffle reduction (lowest index wins ties)
+        for (int row = wave; row < ROWS; row += NW) {
             float bv = -INFINITY; int bi = 0x7FFFFFFF;
-            for (int t = 0; t < TILE && t < NW * 64; ++t) {
+            for (int t = lane; t < TILE; t += 64) {
                 const int r = t % RPL, ln = (t / RPL) & 63;
                 if (RPL * (ln >> 4) + r != row) continue;
                 const float v = cv[t]; const int i = ci[t];
                 if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
             }
-            if (row < M) { st_wt(&ph.pm[(size_t)row * gridDim.x + blockIdx.x], bv); st_wt(&ph.pi[(size_t)row * gridDim.x + blockIdx.x], bi); }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            if (lane == 0 && row < M) { st_wt(&ph.pm[(size_t)row * gridDim.x + blockIdx.x], bv); st_wt(&ph.pi[(size_t)row * gridDim.x + blockIdx.x], bi); }
         }
     }
     // The stores of this phase must be acknowledged before the workgroup arrives at the grid barrier, and the

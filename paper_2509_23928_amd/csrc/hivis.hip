@@ -477,7 +477,9 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             else if (ph.type == PH_NORM_ROWS) grid = std::min(grid, pp.M);
             else if (ph.type == PH_ARGMAX) grid = std::min(grid, (pp.M + FUSED_NW - 1) / FUSED_NW);
             else if (ph.type == PH_GEMM && ph.epi != FEPI_LOGITS) grid = std::min(grid, ph.N / 16);
-#define HIVIS_LAUNCH(TY, EP) hipLaunchKernelGGL((phase_kernel<WT, TY, EP>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp)
+#define HIVIS_LAUNCH(TY, EP) do { if (single) hipLaunchKernelGGL((phase_kernel<WT, TY, EP, true>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp); \
+                                  else hipLaunchKernelGGL((phase_kernel<WT, TY, EP, false>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp); } while (0)
+            const bool single = ph.type == PH_GEMM && ph.epi != FEPI_LOGITS && ph.epi != FEPI_SILU && ph.epi != FEPI_QKV && ph.N / 16 <= grid;   // one tile per workgroup at most
             const bool ktimed = kind == PROG_VERIFY && ph.type == PH_GEMM && ph.epi == c->ktime_epi;
             if (ktimed) {
                 if (c->kev_used + 2 > c->kev.size()) { hipEvent_t e0, e1; HIP_TRY(c, hipEventCreate(&e0)); HIP_TRY(c, hipEventCreate(&e1)); c->kev.push_back(e0); c->kev.push_back(e1); }
@@ -544,12 +546,14 @@ int fused_setup(hivis_ctx* c) {
     c->fused_lds = std::max(gemm_f, attn_f) * sizeof(float);
     HIP_TRY(c, hipFuncSetAttribute((const void*)fused_pass_kernel<WT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
     {
-        const void* ks[] = {(const void*)phase_kernel<WT, PH_GEMM, FEPI_STORE>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADD_TO>,
-                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADDVEC>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_QKV>,
-                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_SILU>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_LOGITS>,
-                            (const void*)phase_kernel<WT, PH_ATTN, 0>, (const void*)phase_kernel<WT, PH_ATTN_MERGE, 0>,
-                            (const void*)phase_kernel<WT, PH_PREP, 0>, (const void*)phase_kernel<WT, PH_NORM_ROWS, 0>,
-                            (const void*)phase_kernel<WT, PH_ARGMAX, 0>};
+        const void* ks[] = {(const void*)phase_kernel<WT, PH_GEMM, FEPI_STORE, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADD_TO, false>,
+                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADDVEC, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_QKV, false>,
+                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_SILU, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_LOGITS, false>,
+                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_STORE, true>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADD_TO, true>,
+                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADDVEC, true>,
+                            (const void*)phase_kernel<WT, PH_ATTN, 0, false>, (const void*)phase_kernel<WT, PH_ATTN_MERGE, 0, false>,
+                            (const void*)phase_kernel<WT, PH_PREP, 0, false>, (const void*)phase_kernel<WT, PH_NORM_ROWS, 0, false>,
+                            (const void*)phase_kernel<WT, PH_ARGMAX, 0, false>};
         for (const void* k : ks) HIP_TRY(c, hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
     }
     { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }

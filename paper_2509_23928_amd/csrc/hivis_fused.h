@@ -88,8 +88,8 @@ template <typename WT> struct FusedCfg;
 // state (two 8 KiB weight units, 8 activation fragments, accumulators, staged rows) must never spill, because a
 // spill reload after the barrier's cache invalidation is a full memory round trip.
 constexpr int FUSED_NW = 8, FUSED_NT = FUSED_NW * 64;
-template <> struct FusedCfg<bf16_t> { static constexpr int KBW = 8, G = 4, NW = FUSED_NW; };
-template <> struct FusedCfg<float> { static constexpr int KBW = 8, G = 2, NW = FUSED_NW; };
+template <> struct FusedCfg<bf16_t> { static constexpr int KBW = 8, G = 8, NW = FUSED_NW; };
+template <> struct FusedCfg<float> { static constexpr int KBW = 8, G = 4, NW = FUSED_NW; };
 constexpr int FUSED_U = 8;
 constexpr int FUSED_QM = 8;       // activation rows staged per thread per pass (8 rows / 1 for bf16, 16 rows / 2 for fp32)
 
@@ -146,17 +146,22 @@ __device__ __forceinline__ void frag_from(float4& f, const uint4& u) {
 //  * Weights: one unit (KBW KiB per wavefront) ahead, and the chain of prefetches does not stop at the end of
 //    a tile group, a pass or the phase: the last unit of a phase loads the first unit of the NEXT GEMM phase
 //    (`head`), so those loads are in flight while the workgroup waits at the grid barrier.
-template <typename WT, int EPI>
+template <typename WT, int EPI, bool SINGLE>
 __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp, float* __restrict__ lds, uint4 (&head)[FUSED_U],
                            bool& head_valid, uint4 (&wb1)[FUSED_U], bool& wb1_valid, int pidx) {
 #define HIVIS_MARK(k) if (pp.prof2 && blockIdx.x == 0 && threadIdx.x == 0) pp.prof2[pidx * 8 + (k)] = wall_clock64();
     typedef WTraits<WT> TR;
     typedef typename AFrag<WT>::type afrag_t;
     typedef typename KVType<WT>::type KT;
-    constexpr int RPL = TR::RPL, ROWS = TR::ROWS, KB = TR::KB, KBW = FusedCfg<WT>::KBW, G = FusedCfg<WT>::G, NW = FusedCfg<WT>::NW;
-    constexpr int U = FUSED_U, QM = FUSED_QM;
+    constexpr int RPL = TR::RPL, ROWS = TR::ROWS, KB = TR::KB, KBW = FusedCfg<WT>::KBW, NW = FusedCfg<WT>::NW;
+    // tiles per group: the full group size where a workgroup owns many tiles (LM head, gate|up; also the generic
+    // interpreter), half of it for the kernels whose workgroups own at most a few tiles (fewer accumulators)
+    constexpr int G = (!SINGLE && (EPI < 0 || EPI == FEPI_LOGITS || EPI == FEPI_SILU)) ? FusedCfg<WT>::G : FusedCfg<WT>::G / 2;
+    constexpr int U = FUSED_U, QM = FUSED_QM, NT = FUSED_NT;
     static_assert(KBW == U && (G % 2) == 0, "one unit per tile slice; tiles are processed in pairs");
     constexpr int TILE = G * 64 * RPL;
+    constexpr int SLOTS = TILE / NT;         // epilogue slots per thread (all of the same row and column-in-tile)
+    static_assert(TILE % NT == 0, "whole epilogue slots per thread");
     constexpr int CW = NW * KBW * KB;        // k per pass (64 blocks)
     constexpr int C4 = CW / 4;               // float4 columns per pass (<= 512)
     float* red = lds;                        // [NW][G][64][RPL]
@@ -171,6 +176,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     const int kblks = K / KB, ntiles = N / 16;
     const int t_begin = (int)(((long long)blockIdx.x * ntiles) / gridDim.x);
     const int t_end = (int)(((long long)(blockIdx.x + 1) * ntiles) / gridDim.x);
+    const int ntl = t_end - t_begin;
     const int npass = (kblks + NW * KBW - 1) / (NW * KBW);
     const WT* gain = (ph.pro == PRO_RMS) ? (const WT*)ph.gain : nullptr;
     const float* A = ph.A;
@@ -178,46 +184,52 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     const uint4* W = ph.W;
     const int RU = (RPL == 2) ? 4 * ((M + 1) >> 1) : ((M + 3) & ~3);      // tile rows in use
     const int col4 = threadIdx.x % C4, row0 = threadIdx.x / C4;          // this thread stages rows row0, row0 + RSTEP, ...
-    constexpr int RSTEP = FUSED_NT / C4;
+    constexpr int RSTEP = NT / C4;
     float ssq_acc[QM];
 #pragma unroll
     for (int q = 0; q < QM; ++q) ssq_acc[q] = 0.f;
     float best_v = -INFINITY; int best_i = 0x7FFFFFFF;   // greedy-token candidate (LOGITS): a thread always serves one row
 
-    // first unit of the next GEMM phase for this wavefront (prefetched by the last unit of this phase)
+    // first units of the next GEMM phase for this wavefront (persistent mode only: requested at the end of this phase)
     const int n_kblks = ph.next_K / KB, n_ntiles = ph.next_N / 16;
     const int n_tile = ph.next_W ? (int)(((long long)blockIdx.x * n_ntiles) / gridDim.x) : 0;
     const int n_tend = ph.next_W ? (int)(((long long)(blockIdx.x + 1) * n_ntiles) / gridDim.x) : 0;
     const bool n_has = ph.next_W && n_tile < n_tend;
+    const int n_npass = (n_kblks + NW * KBW - 1) / (NW * KBW);
+    // The unit order of a phase is tile-inner, pass-outer within a tile group.  `head` holds the first unit and
+    // `wb1` the second one: the next tile of the same pass, or, for a workgroup with a single tile, the same tile
+    // of the next pass.
+#define HIVIS_FIRST_UNITS(W_, kblks_, tile_, ntl_, npass_)                                                         \
+    {                                                                                                              \
+        const int nk_ = max(0, min(KBW, (kblks_) - wave * KBW));                                                   \
+        issue_unit(head, W_, kblks_, tile_, wave * KBW, nk_, lane);                                                \
+        head_valid = true; wb1_valid = false;                                                                      \
+        if ((ntl_) >= 2) { issue_unit(wb1, W_, kblks_, (tile_) + 1, wave * KBW, nk_, lane); wb1_valid = true; }    \
+        else if (SINGLE && (npass_) >= 2) {                                                                        \
+            const int kb1_ = (NW + wave) * KBW;                                                                    \
+            issue_unit(wb1, W_, kblks_, tile_, kb1_, max(0, min(KBW, (kblks_) - kb1_)), lane); wb1_valid = true;   \
+        }                                                                                                          \
+    }
 
-    if (t_begin >= t_end) {
-        // no tiles in this phase: still start the next phase's stream
+    if (ntl <= 0) {
         if (epi == FEPI_LOGITS && threadIdx.x < ROWS && (int)threadIdx.x < M) {
             st_wt(&ph.pm[(size_t)threadIdx.x * gridDim.x + blockIdx.x], -INFINITY); st_wt(&ph.pi[(size_t)threadIdx.x * gridDim.x + blockIdx.x], 0x7FFFFFFF);
         }
         wait_vmem();
-        if (!head_valid && n_has) {
-            const int nk = max(0, min(KBW, n_kblks - wave * KBW));
-            issue_unit(head, ph.next_W, n_kblks, n_tile, wave * KBW, nk, lane);
-            head_valid = true;
-            if ((pp.flags & 1) && n_tile + 1 < n_tend) { issue_unit(wb1, ph.next_W, n_kblks, n_tile + 1, wave * KBW, nk, lane); wb1_valid = true; }
-        }
+        if (!head_valid && n_has) HIVIS_FIRST_UNITS(ph.next_W, n_kblks, n_tile, n_tend - n_tile, n_npass)
         return;
     }
-    if (!head_valid) {
-        // nothing was prefetched for this phase: request its first two units now, ahead of the activation rows
-        const int nk0 = max(0, min(KBW, kblks - wave * KBW));
-        issue_unit(head, W, kblks, t_begin, wave * KBW, nk0, lane);
-        wb1_valid = false;
-        if (t_begin + 1 < t_end) { issue_unit(wb1, W, kblks, t_begin + 1, wave * KBW, nk0, lane); wb1_valid = true; }
-    }
+    // nothing prefetched for this phase: request its first two units now, ahead of the activation rows
+    if (!head_valid) HIVIS_FIRST_UNITS(W, kblks, t_begin, ntl, npass)
     head_valid = false;
+    const bool wb1_first = wb1_valid;       // wb1 already holds the second unit of the phase
+    wb1_valid = false;
 
     // raw activation loads of pass `ps`: float4 (row0 + q*RSTEP, ps*CW + 4*col4) and the gain of those 4 columns
-    static_assert(QM * RSTEP >= ROWS, "every row is staged by some thread");
-    float4 araw[QM]; float graw[4];
     // (unconditional loads from clamped addresses: a load under a divergent branch is followed by a full wait,
     //  which would serialise the rows into one memory round trip each)
+    static_assert(QM * RSTEP >= ROWS, "every row is staged by some thread");
+    float4 araw[QM]; float graw[4];
 #define HIVIS_LOAD_RAW(ps)                                                                                         \
     {                                                                                                              \
         const int k_ = min((ps) * CW + 4 * col4, K - 4);                                                           \
@@ -231,6 +243,30 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             _Pragma("unroll") for (int e = 0; e < 4; ++e) graw[e] = 1.0f;                                          \
         }                                                                                                          \
     }
+    // Stage pass `ps` (whose rows are in araw) into LDS as MFMA fragments, request the rows of pass `nx` (or none if
+    // nx < 0), and fetch this wavefront's fragments af[0..KBW).
+#define HIVIS_STAGE(ps, nx, do_ssq)                                                                                \
+    lds_barrier();                        /* everyone is done with the previous chunk */                           \
+    _Pragma("unroll") for (int q = 0; q < QM; ++q) {                                                               \
+        const int row_ = row0 + q * RSTEP;                                                                         \
+        if (row_ < M && (ps) * CW + 4 * col4 < K) {                                                                \
+            float x_[4] = {araw[q].x, araw[q].y, araw[q].z, araw[q].w};                                            \
+            if (do_ssq) ssq_acc[q] += x_[0] * x_[0] + x_[1] * x_[1] + x_[2] * x_[2] + x_[3] * x_[3];               \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) x_[e] *= graw[e];                                        \
+            stage_store(WT(), chunk, RU, row_, 4 * col4, x_);                                                      \
+        }                                                                                                          \
+    }                                                                                                              \
+    if ((nx) >= 0) HIVIS_LOAD_RAW(nx)                                                                              \
+    lds_barrier();                                                                                                 \
+    {                                                                                                              \
+        const int kb0_ = ((ps) * NW + wave) * KBW;                                                                 \
+        const int nkb_ = max(0, min(KBW, kblks - kb0_));                                                           \
+        const int i_ = min(lane & 15, RU - 1), g4_ = lane >> 4;                                                    \
+        _Pragma("unroll") for (int j = 0; j < KBW; ++j) {                                                          \
+            const uint4 u_ = chunk[((wave * KBW + j) * 4 + g4_) * RU + i_];                                        \
+            frag_from(af[j], (j < nkb_) ? u_ : make_uint4(0, 0, 0, 0));                                            \
+        }                                                                                                          \
+    }
     HIVIS_MARK(0)
     HIVIS_LOAD_RAW(0)
 
@@ -240,76 +276,69 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         f32x4_t acc[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) acc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        for (int pass = 0; pass < npass; ++pass) {
-            const int kb0 = (pass * NW + wave) * KBW;
-            const int nkb = max(0, min(KBW, kblks - kb0));
-            // where the prefetch chain goes after the last unit of this (tile group, pass)
-            const uint4* nW = W; int nkblks = kblks, ntile = tg, nkb0 = 0, ntiles2 = ng; bool nvalid = true;
-            if (pass + 1 < npass) { nkb0 = ((pass + 1) * NW + wave) * KBW; }
-            else if (tg + G < t_end) { ntile = tg + G; nkb0 = wave * KBW; ntiles2 = t_end - ntile; }
-            else nvalid = false;     // the next phase's first units are requested after this phase's stores (see the end)
-            const bool wb1_pref = wb1_valid;      // the second unit of this (tile group, pass) was prefetched too
-            wb1_valid = false;
-            const int nnkb = max(0, min(KBW, nkblks - nkb0));
-
-            // ---- stage this pass's activation rows into LDS as MFMA fragments
-            lds_barrier();                      // everyone is done with the previous chunk
+        afrag_t af[KBW];
+        if constexpr (SINGLE) {
+            // ---- every workgroup owns at most one tile: the K passes alternate between the two unit buffers, each requested two passes ahead
+            for (int pass = 0; pass < npass; pass += 2) {
+                HIVIS_STAGE(pass, (pass + 1 < npass) ? pass + 1 : -1, true)
+                if (pass == 0) { HIVIS_MARK(1) }
 #pragma unroll
-            for (int q = 0; q < QM; ++q) {
-                const int row = row0 + q * RSTEP;
-                if (row < M && pass * CW + 4 * col4 < K) {
-                    float x[4] = {araw[q].x, araw[q].y, araw[q].z, araw[q].w};
-                    if (first) ssq_acc[q] += x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
+                for (int j = 0; j < U; ++j) mfma_block(acc[0], af[j], head[j]);
+                if (pass + 2 < npass) { const int kb2 = ((pass + 2) * NW + wave) * KBW; issue_unit(head, W, kblks, tg, kb2, max(0, min(KBW, kblks - kb2)), lane); }
+                if (pass + 1 < npass) {
+                    if (pass == 0 && !wb1_first) { const int kb1 = (NW + wave) * KBW; issue_unit(wb1, W, kblks, tg, kb1, max(0, min(KBW, kblks - kb1)), lane); }
+                    HIVIS_STAGE(pass + 1, (pass + 2 < npass) ? pass + 2 : -1, true)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) x[e] *= graw[e];
-                    stage_store(WT(), chunk, RU, row, 4 * col4, x);
+                    for (int j = 0; j < U; ++j) mfma_block(acc[0], af[j], wb1[j]);
+                    if (pass + 3 < npass) { const int kb3 = ((pass + 3) * NW + wave) * KBW; issue_unit(wb1, W, kblks, tg, kb3, max(0, min(KBW, kblks - kb3)), lane); }
                 }
             }
-            // next pass's rows (the same rows again for the next tile group) are loaded while this pass streams
-            if (pass + 1 < npass) HIVIS_LOAD_RAW(pass + 1) else if (tg + G < t_end) HIVIS_LOAD_RAW(0)
-            lds_barrier();
-            if (first && pass == 0) { HIVIS_MARK(1) }
-            afrag_t af[KBW];
-            {
-                const int i = min(lane & 15, RU - 1), g4 = lane >> 4;
+        } else {
+            for (int pass = 0; pass < npass; ++pass) {
+                const int kb0 = (pass * NW + wave) * KBW;
+                const int nkb = max(0, min(KBW, kblks - kb0));
+                // where the prefetch chain goes after the last unit of this (tile group, pass)
+                int ntile = tg, nkb0 = 0, ntiles2 = ng; bool nvalid = true;
+                if (pass + 1 < npass) { nkb0 = ((pass + 1) * NW + wave) * KBW; }
+                else if (tg + G < t_end) { ntile = tg + G; nkb0 = wave * KBW; ntiles2 = t_end - ntile; }
+                else nvalid = false;     // the next phase's first units are requested after this phase's stores (see the end)
+                const int nnkb = max(0, min(KBW, kblks - nkb0));
+                const bool have_wb1 = (first && pass == 0) ? wb1_first : wb1_valid;
+                wb1_valid = false;
+                HIVIS_STAGE(pass, (pass + 1 < npass) ? pass + 1 : ((tg + G < t_end) ? 0 : -1), first)
+                if (first && pass == 0) { HIVIS_MARK(1) }
+                // ---- stream the tiles of the group, two at a time
 #pragma unroll
-                for (int j = 0; j < KBW; ++j) {
-                    const uint4 u = chunk[((wave * KBW + j) * 4 + g4) * RU + i];
-                    frag_from(af[j], (j < nkb) ? u : make_uint4(0, 0, 0, 0));
-                }
-            }
-            // ---- stream the tiles of the group, two at a time
+                for (int g0 = 0; g0 < G; g0 += 2) {
+                    if (g0 < ng) {
+                        if (g0 + 1 < ng && !(g0 == 0 && have_wb1)) issue_unit(wb1, W, kblks, tg + g0 + 1, kb0, nkb, lane);
 #pragma unroll
-            for (int g0 = 0; g0 < G; g0 += 2) {
-                if (g0 < ng) {
-                    if (g0 + 1 < ng && !(g0 == 0 && wb1_pref)) issue_unit(wb1, W, kblks, tg + g0 + 1, kb0, nkb, lane);
+                        for (int j = 0; j < U; ++j) mfma_block(acc[g0], af[j], head[j]);
+                        if (g0 + 2 < ng) issue_unit(head, W, kblks, tg + g0 + 2, kb0, nkb, lane);
+                        else if (nvalid) issue_unit(head, W, kblks, ntile, nkb0, nnkb, lane);
+                        if (g0 + 1 < ng) {
 #pragma unroll
-                    for (int j = 0; j < U; ++j) mfma_block(acc[g0], af[j], head[j]);
-                    if (g0 + 2 < ng) issue_unit(head, W, kblks, tg + g0 + 2, kb0, nkb, lane);
-                    else if (nvalid) { issue_unit(head, nW, nkblks, ntile, nkb0, nnkb, lane); head_valid = true; }
-                    if (g0 + 1 < ng) {
-#pragma unroll
-                        for (int j = 0; j < U; ++j) mfma_block(acc[g0 + 1], af[j], wb1[j]);
+                            for (int j = 0; j < U; ++j) mfma_block(acc[g0 + 1], af[j], wb1[j]);
+                        }
                     }
                 }
+                // second unit of the next (tile group, pass): its registers are free now
+                if (nvalid && ntiles2 >= 2) { issue_unit(wb1, W, kblks, ntile + 1, nkb0, nnkb, lane); wb1_valid = true; }
+                if (first && pass == 0) { HIVIS_MARK(2) }
             }
-            if (!nvalid) head_valid = false;
-            // second unit of the next chain (its registers are free now)
-            if ((pp.flags & 1) && nvalid && ntiles2 >= 2) { issue_unit(wb1, nW, nkblks, ntile + 1, nkb0, nnkb, lane); wb1_valid = true; }
-            if (first && pass == 0) { HIVIS_MARK(2) }
         }
         if (first) { HIVIS_MARK(3) }
-        // operands of this thread's epilogue slot, requested now so that they arrive during the reduction
-        float epi_a = 0.f, epi_b = 0.f;
-        {
-            static_assert(TILE == NW * 64, "one epilogue slot per thread");
-            const int idx = threadIdx.x, r = idx % RPL, ln = (idx / RPL) & 63, g = idx / (RPL * 64);
+        // operands of this thread's epilogue slots, requested now so that they arrive during the reduction
+        float epi_a[SLOTS], epi_b[SLOTS];
+#pragma unroll
+        for (int sl = 0; sl < SLOTS; ++sl) {
+            epi_a[sl] = 0.f; epi_b[sl] = 0.f;
+            const int idx = threadIdx.x + sl * NT, r = idx % RPL, ln = (idx / RPL) & 63, g = idx / (RPL * 64);
             const int row = min(RPL * (ln >> 4) + r, M - 1), col = min((tg + g) * 16 + (ln & 15), N - 1);
-            if (!(pp.flags & 2)) {}
-            else if (epi == FEPI_ADD_TO) epi_a = ph.R[(size_t)row * ph.ldr + col];
+            if (epi == FEPI_ADD_TO) epi_a[sl] = ph.R[(size_t)row * ph.ldr + col];
             else if (epi == FEPI_QKV) {
                 const int p2 = (col % pp.hd) >> 1;
-                epi_a = ph.rope[((size_t)row * (pp.hd / 2) + p2) * 2]; epi_b = ph.rope[((size_t)row * (pp.hd / 2) + p2) * 2 + 1];
+                epi_a[sl] = ph.rope[((size_t)row * (pp.hd / 2) + p2) * 2]; epi_b[sl] = ph.rope[((size_t)row * (pp.hd / 2) + p2) * 2 + 1];
             }
         }
         // ---- cross-wave reduction
@@ -331,7 +360,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             }
         }
         lds_barrier();
-        for (int idx = threadIdx.x; idx < TILE; idx += NW * 64) {
+        for (int idx = threadIdx.x; idx < TILE; idx += NT) {
             float s = 0.f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) s += red[(size_t)w * TILE + idx];
@@ -348,7 +377,9 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         lds_barrier();
         if (first) { HIVIS_MARK(4) }
         // ---- epilogue on the reduced tiles
-        for (int idx = threadIdx.x; idx < TILE; idx += NW * 64) {
+#pragma unroll
+        for (int sl = 0; sl < SLOTS; ++sl) {
+            const int idx = threadIdx.x + sl * NT;
             const int r = idx % RPL;
             const int ln = (idx / RPL) & 63;
             const int g = idx / (RPL * 64);
@@ -360,7 +391,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             const float v = tile[idx] * sc;
             switch (epi) {
             case FEPI_STORE: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v); break;
-            case FEPI_ADD_TO: st_wt(&ph.Y[(size_t)row * ph.ldy + col], ((pp.flags & 2) ? epi_a : ph.R[(size_t)row * ph.ldr + col]) + v); break;
+            case FEPI_ADD_TO: st_wt(&ph.Y[(size_t)row * ph.ldy + col], epi_a[sl] + v); break;
             case FEPI_ADDVEC: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v + to_f32(((const WT*)ph.vec)[(size_t)ph.vec_idx * N + col])); break;
             case FEPI_LOGITS:
                 st_wt(&ph.Y[(size_t)row * ph.ldy + col], v);
@@ -380,9 +411,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
                 if ((cl & 1) == 0) {
                     const float x1 = v, x2 = tile[idx + RPL] * sc;
                     if (col < qd + kd) {
-                        const int p2 = (col % hd) >> 1;
-                        const float c = (pp.flags & 2) ? epi_a : ph.rope[((size_t)row * (hd / 2) + p2) * 2];
-                        const float s = (pp.flags & 2) ? epi_b : ph.rope[((size_t)row * (hd / 2) + p2) * 2 + 1];
+                        const float c = epi_a[sl], s = epi_b[sl];
                         const float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;
                         if (col < qd) {
                             st_wt_pair(&ph.Y[(size_t)row * ph.ldy + col], y1, y2);
@@ -400,18 +429,19 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         }
     }
 #undef HIVIS_LOAD_RAW
+#undef HIVIS_STAGE
     HIVIS_MARK(5)
 #undef HIVIS_MARK
     if (epi == FEPI_LOGITS) {
         // per-row candidate of this workgroup: the threads of one row meet through LDS
         lds_barrier();
-        float* cv = red; int* ci = (int*)(red + NW * 64);
+        float* cv = red; int* ci = (int*)(red + NT);
         cv[threadIdx.x] = best_v; ci[threadIdx.x] = best_i;
         lds_barrier();
-        // one wavefront per row: lanes scan the slots of that row, then a shuffle reduction (lowest index wins ties)
+        // one wavefront per row: lanes scan the threads that serve that row, then a shuffle reduction (lowest index wins ties)
         for (int row = wave; row < ROWS; row += NW) {
             float bv = -INFINITY; int bi = 0x7FFFFFFF;
-            for (int t = lane; t < TILE; t += 64) {
+            for (int t = lane; t < NT; t += 64) {
                 const int r = t % RPL, ln = (t / RPL) & 63;
                 if (RPL * (ln >> 4) + r != row) continue;
                 const float v = cv[t]; const int i = ci[t];
@@ -427,14 +457,10 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     }
     // The stores of this phase must be acknowledged before the workgroup arrives at the grid barrier, and the
     // only wait available (vmcnt) also covers loads: so first drain, THEN request the first two units of the next
-    // GEMM phase, which stay in flight across the barrier.
+    // GEMM phase, which stay in flight across the barrier (persistent mode).
     wait_vmem();
-    if (n_has) {
-        const int nk = max(0, min(KBW, n_kblks - wave * KBW));
-        issue_unit(head, ph.next_W, n_kblks, n_tile, wave * KBW, nk, lane);
-        head_valid = true;
-        if ((pp.flags & 1) && n_tile + 1 < n_tend) { issue_unit(wb1, ph.next_W, n_kblks, n_tile + 1, wave * KBW, nk, lane); wb1_valid = true; }
-    }
+    if (n_has) HIVIS_FIRST_UNITS(ph.next_W, n_kblks, n_tile, n_tend - n_tile, n_npass)
+#undef HIVIS_FIRST_UNITS
 }
 
 // ---- attention phase ---------------------------------------------------------------------------------
@@ -718,13 +744,13 @@ __device__ __forceinline__ void attn_wg_merge(const float* __restrict__ ws, cons
 }
 
 // One phase, executed by the calling grid (every workgroup calls this with the same arguments).
-template <typename WT, int TYPE, int EPI>
+template <typename WT, int TYPE, int EPI, bool SINGLE>
 __device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp, float* __restrict__ lds, uint4 (&head)[FUSED_U],
                                           bool& head_valid, uint4 (&wb1)[FUSED_U], bool& wb1_valid, int p) {
     typedef typename KVType<WT>::type KT;
     const int type = (TYPE >= 0) ? TYPE : ph.type;
     switch (type) {
-    case PH_GEMM: gemm_phase<WT, EPI>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p); break;
+    case PH_GEMM: gemm_phase<WT, EPI, SINGLE>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p); break;
     case PH_ATTN: {
         const int total = ph.att_items * ph.att.nsplit;
         for (int w = blockIdx.x; w < total; w += gridDim.x) {
@@ -807,7 +833,7 @@ __global__ __launch_bounds__(FUSED_NT) void fused_pass_kernel(PassParams pp) {
     for (int p = 0; p < pp.nphases; ++p) {
         const Phase& ph = pp.phases[p];
         if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3] = wall_clock64();
-        run_phase<WT, -1, -1>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p);
+        run_phase<WT, -1, -1, false>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p);
         if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3 + 1] = wall_clock64();
         const bool ok = grid_barrier(pp.bar, (unsigned)(p + 1) * gridDim.x, pp.spin_limit, ph.type == PH_GEMM);
         if (pp.prof && blockIdx.x == 0 && threadIdx.x == 0) pp.prof[p * 3 + 2] = wall_clock64();
@@ -817,12 +843,12 @@ __global__ __launch_bounds__(FUSED_NT) void fused_pass_kernel(PassParams pp) {
 
 // One phase per launch: the kernel boundary orders the phases (and makes every store visible), so nothing is
 // prefetched across it and no barrier is needed.  This is the default way the passes are run.
-template <typename WT, int TYPE, int EPI>
+template <typename WT, int TYPE, int EPI, bool SINGLE>
 __global__ __launch_bounds__(FUSED_NT) void phase_kernel(Phase ph, PassParams pp) {
     extern __shared__ __align__(16) float lds[];
     uint4 head[FUSED_U], wb1[FUSED_U];
     bool head_valid = false, wb1_valid = false;
-    run_phase<WT, TYPE, EPI>(ph, pp, lds, head, head_valid, wb1, wb1_valid, 0);
+    run_phase<WT, TYPE, EPI, SINGLE>(ph, pp, lds, head, head_valid, wb1, wb1_valid, 0);
 }
 
 }  // namespace hivis

@@ -573,14 +573,10 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
 #pragma unroll
         for (int r = 0; r < RM; ++r) {
             if (r < R) {
-                float sv = s[r];
-                sv += __shfl_xor(sv, 1, 64);
-                sv += __shfl_xor(sv, 2, 64);
+                float sv = quad_sum(s[r]);                // the 4 lanes of a key hold its 4 quarter dot products
                 const int qpos = pos0 + i0 + r % ni;
                 if (key >= k1 || key > qpos) sv = -INFINITY;
-                float tmax = sv;
-#pragma unroll
-                for (int o = 4; o < 64; o <<= 1) tmax = fmaxf(tmax, __shfl_xor(tmax, o, 64));
+                const float tmax = wave_max(sv);
                 const float mnew = fmaxf(mrun[r], tmax);
                 float alpha = 1.f, p = 0.f;
                 if (mnew != -INFINITY) {

@@ -398,15 +398,42 @@ __global__ __launch_bounds__(256) void gemm_tall_kernel(const uint4* __restrict_
 // Row-wise small kernels (activations are a few rows of fp32; these are launch-bound, not
 // bandwidth-bound)
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+// Cross-lane reductions with DPP (data-parallel primitives: the operand of a VALU instruction is taken from
+// another lane of the same row of 16 lanes, or broadcast from the previous row) instead of ds_bpermute, which
+// goes through the LDS crossbar and costs an LDS round trip per step.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float keep, float src) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(keep), __float_as_int(src), CTRL, ROW_MASK, 0xF, false));
+}
+constexpr int DPP_QUAD_XOR1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int DPP_QUAD_XOR2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int DPP_ROW_ROR4 = 0x124, DPP_ROW_ROR8 = 0x128;
+constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+
+// all 4 lanes of a quad get the quad's sum
+__device__ __forceinline__ float quad_sum(float v) {
+    v += dpp_move<DPP_QUAD_XOR1, 0xF>(v, v);
+    v += dpp_move<DPP_QUAD_XOR2, 0xF>(v, v);
     return v;
 }
+// Every lane gets the reduction over all 64 lanes: quad, row of 16 (two rotations), then row 0 -> 1 and 2 -> 3
+// (row_bcast:15 into rows 1,3), then rows 0-1 -> 2,3 (row_bcast:31), and lane 63 is read back.
+__device__ __forceinline__ float wave_sum(float v) {
+    v = quad_sum(v);
+    v += dpp_move<DPP_ROW_ROR4, 0xF>(v, v);
+    v += dpp_move<DPP_ROW_ROR8, 0xF>(v, v);
+    v += dpp_move<DPP_ROW_BCAST15, 0xA>(0.f, v);
+    v += dpp_move<DPP_ROW_BCAST31, 0xC>(0.f, v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    v = fmaxf(v, dpp_move<DPP_QUAD_XOR1, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<DPP_QUAD_XOR2, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<DPP_ROW_ROR4, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<DPP_ROW_ROR8, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<DPP_ROW_BCAST15, 0xA>(v, v));
+    v = fmaxf(v, dpp_move<DPP_ROW_BCAST31, 0xC>(v, v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // h[row] += delta[row] (if delta), then out[row] = h[row] * gain / sqrt(mean(h^2) + eps).

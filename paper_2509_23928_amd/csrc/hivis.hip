@@ -477,8 +477,10 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             else if (ph.type == PH_NORM_ROWS) grid = std::min(grid, pp.M);
             else if (ph.type == PH_ARGMAX) grid = std::min(grid, (pp.M + FUSED_NW - 1) / FUSED_NW);
             else if (ph.type == PH_GEMM && ph.epi != FEPI_LOGITS) grid = std::min(grid, ph.N / 16);
-#define HIVIS_LAUNCH(TY, EP) do { if (single) hipLaunchKernelGGL((phase_kernel<WT, TY, EP, true>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp); \
-                                  else hipLaunchKernelGGL((phase_kernel<WT, TY, EP, false>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp); } while (0)
+            PassParams ppl = pp;
+            if (do_prof) ppl.prof2 = pp.prof2 + (size_t)p * 8;
+#define HIVIS_LAUNCH(TY, EP) do { if (single) hipLaunchKernelGGL((phase_kernel<WT, TY, EP, true>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, ppl); \
+                                  else hipLaunchKernelGGL((phase_kernel<WT, TY, EP, false>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, ppl); } while (0)
             const bool single = ph.type == PH_GEMM && ph.epi != FEPI_LOGITS && ph.epi != FEPI_SILU && ph.epi != FEPI_QKV && ph.N / 16 <= grid;   // one tile per workgroup at most
             const bool ktimed = kind == PROG_VERIFY && ph.type == PH_GEMM && ph.epi == c->ktime_epi;
             if (ktimed) {
@@ -507,6 +509,20 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             if (ktimed) { HIP_TRY(c, hipEventRecord(c->kev[c->kev_used + 1], c->stream)); c->kev_used += 2; }
         }
         HIP_TRY(c, hipGetLastError());
+        if (do_prof) {
+            // developer aid: timestamps (100 MHz) that workgroup 0 of each launch wrote, for one layer in the middle
+            std::vector<unsigned long long> t2((size_t)pg.n * 8);
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            HIP_TRY(c, hipMemcpy(t2.data(), pp.prof2, t2.size() * 8, hipMemcpyDeviceToHost));
+            const int p0 = std::min(pg.n / 2, pg.n - 1);
+            for (int p = p0; p < std::min(pg.n, p0 + 14); ++p) {
+                const Phase& P = (*pg.host)[p];
+                fprintf(stderr, "[hivis prof] phase %d type %d epi %d: entry %+.2f us after previous entry;", p, P.type, P.epi, ((double)t2[p * 8] - (double)t2[(p - 1) * 8]) * 0.01);
+                for (int k = 1; k < 6; ++k) fprintf(stderr, " m%d %+.2f", k, ((double)t2[p * 8 + k] - (double)t2[p * 8]) * 0.01);
+                fprintf(stderr, "\n");
+            }
+            c->prof_left--;
+        }
         return HIVIS_OK;
     }
     hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, (int*)c->bar, 1, 0);
@@ -542,7 +558,7 @@ int fused_setup(hivis_ctx* c) {
     const char* env = getenv("HIVIS_FUSED");
     if (env && env[0] == '0') { c->fused = false; return HIVIS_OK; }
     const size_t gemm_f = fused_gemm_lds_floats(FusedCfg<WT>::NW, FusedCfg<WT>::G, TR::RPL, FusedCfg<WT>::KBW);
-    const size_t attn_f = fused_attn_lds_floats(g.head_dim, FUSED_NW, FUSED_RMAX);
+    const size_t attn_f = std::max(fused_attn_lds_floats(g.head_dim, FUSED_NW, FUSED_RMAX), fused_attn_mfma_lds_floats(g.head_dim, FUSED_NW, FUSED_RMAX));
     c->fused_lds = std::max(gemm_f, attn_f) * sizeof(float);
     HIP_TRY(c, hipFuncSetAttribute((const void*)fused_pass_kernel<WT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
     {

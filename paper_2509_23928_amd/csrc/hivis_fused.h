@@ -17,6 +17,7 @@
 // barrier needs no cache write-back or invalidation.  The few words that are rewritten inside one launch
 // (drafted token ids) are read with agent-scope loads.
 #pragma once
+#include <type_traits>
 #include "hivis_kernels.h"
 
 namespace hivis {
@@ -474,11 +475,276 @@ __host__ __device__ constexpr size_t fused_attn_lds_floats(int hd, int nw, int r
     return (size_t)rm * hd + (size_t)nw * rm * 16 + (size_t)nw * rm * (hd + 2);
 }
 
+#define HIVIS_AMARK(k) if (marks && blockIdx.x == 0 && threadIdx.x == 0) marks[k] = wall_clock64();
+// Tail shared by the attention variants: the NW per-wavefront partials in mrg ([NW][RM][HD + 2]: weighted value
+// sums, running maximum, sum of weights) are merged in wavefront order; with one key split the attention rows are
+// written directly, otherwise ONE partial of the workgroup goes to ws for the merge phase (or, when cnt is given,
+// the workgroup that completes the item merges all of its partials).
+template <int HD, int RM>
+__device__ __forceinline__ void attn_wg_finish(const float* __restrict__ mrg, int* __restrict__ flag, const AttnShape& sh, int item_id, int split,
+                                               int R, int ni, int head0, int i0, int sl, float* __restrict__ ws, int* __restrict__ cnt,
+                                               float* __restrict__ att_out, int ldo, unsigned long long* marks) {
+    constexpr int NW = FUSED_NW;
+    lds_barrier();
+    HIVIS_AMARK(4)
+    if (sh.nsplit == 1) {
+        // the whole key range was handled here: merge the NW partials and write the attention rows directly
+        for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
+            const int r = idx / HD, c = idx % HD;
+            float mx = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) mx = fmaxf(mx, mrg[(w * RM + r) * (HD + 2) + HD]);
+            float num = 0.f, den = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float mw = mrg[(w * RM + r) * (HD + 2) + HD];
+                if (mw != -INFINITY) {
+                    const float e = __expf(mw - mx);
+                    num += mrg[(w * RM + r) * (HD + 2) + c] * e; den += mrg[(w * RM + r) * (HD + 2) + HD + 1] * e;
+                }
+            }
+            const int hh = head0 + r / ni, i = i0 + r % ni;
+            st_wt(&att_out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], num / den);
+        }
+        lds_barrier();
+        return;
+    }
+    // ---- merge the NW partials (fixed order) and write ONE partial of this workgroup
+    float* out = ws + ((size_t)item_id * sh.nsplit + split) * RM * (HD + 2);
+    for (int idx = threadIdx.x; idx < R * (HD + 2); idx += FUSED_NT) {
+        const int r = idx / (HD + 2), c = idx % (HD + 2);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) mx = fmaxf(mx, mrg[(w * RM + r) * (HD + 2) + HD]);
+        float v;
+        if (c == HD) v = mx;
+        else {
+            v = 0.f;
+            const int cc = (c == HD + 1) ? HD + 1 : c;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float mw = mrg[(w * RM + r) * (HD + 2) + HD];
+                if (mw != -INFINITY) v += mrg[(w * RM + r) * (HD + 2) + cc] * __expf(mw - mx);
+            }
+        }
+        st_wt(&out[r * (HD + 2) + c], v);
+    }
+    HIVIS_AMARK(5)
+    if (cnt == nullptr) { lds_barrier(); return; }        // the partials are merged by a separate phase
+    // ---- the workgroup whose partial completes the item merges all of them (no extra grid barrier):
+    // stores acknowledged -> arrive on the item's counter -> the last arriver reads the nsplit partials
+    wait_vmem();
+    lds_barrier();
+    if (threadIdx.x == 0) {
+        // the acknowledgement of a write-through store only says that this XCD's L2 has it; the agent-scope release
+        // makes it visible to the other XCDs before the arrival below
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        flag[0] = __hip_atomic_fetch_add(&cnt[item_id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    lds_barrier();
+    const bool last = flag[0] == sh.nsplit - 1;
+    if (last) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        const float* pbase = ws + (size_t)item_id * sh.nsplit * RM * (HD + 2);
+        for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
+            const int r = idx / HD, c = idx % HD;
+            float mx = -INFINITY;
+            for (int sp = 0; sp < sh.nsplit; ++sp) mx = fmaxf(mx, pbase[((size_t)sp * RM + r) * (HD + 2) + HD]);
+            float num = 0.f, den = 0.f;
+            for (int sp = 0; sp < sh.nsplit; ++sp) {
+                const float* pp_ = pbase + ((size_t)sp * RM + r) * (HD + 2);
+                const float ms = pp_[HD];
+                if (ms == -INFINITY) continue;
+                const float w = __expf(ms - mx);
+                num += pp_[c] * w; den += pp_[HD + 1] * w;
+            }
+            const int hh = head0 + r / ni, i = i0 + r % ni;
+            st_wt(&att_out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], num / den);
+        }
+        if (threadIdx.x == 0) st_wt(&cnt[item_id], 0);
+    }
+    lds_barrier();
+}
+
+// ---- attention on the matrix cores (half-precision caches) ---------------------------------------------
+// Same work split as attn_wg_partial, but both contractions run as MFMA with the (head,row) pairs as the 16-wide
+// N dimension, so the queries live in 4 registers per 32 dims instead of LDS and a 16-key tile costs a dozen MFMA
+// instead of ~500 scalar FMAs:
+//   S^T[key][row]  = K[key][:] . Q^T          4 (HD=128) x mfma 16x16x32 f16; A = 16 cached key rows read straight
+//                                             from HBM (lane: key lane%16, 8 dims at 32 ks + 8 (lane/16)), B = q*scale in half
+//   O^T[dim][row] += V^T[dim][key] . P^T      HD/16 x mfma 16x16x16 f16; B = the probabilities exactly where the
+//                                             first product left them (lane: row lane%16, keys 4 (lane/16) + r);
+//                                             A = V^T, which needs 4 keys of one dim per lane: the V tile goes through
+//                                             LDS row-major and comes back through the transposing LDS read
+// The running maximum / sum / rescale are per lane (row = lane%16 everywhere), only the maximum crosses lanes.
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+
+__host__ __device__ constexpr size_t fused_attn_mfma_lds_floats(int hd, int nw, int rm) {
+    return (size_t)nw * 16 * (hd * 2 + 32) / 4 + (size_t)nw * rm * (hd + 2) + 16;
+}
+
+template <int HD, int RM>
+__device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const f16_t* __restrict__ kc, const f16_t* __restrict__ vc,
+                                             const int* __restrict__ base, const AttnShape& sh, int item_id, int split,
+                                             float* __restrict__ lds, float* __restrict__ ws, int* __restrict__ cnt,
+                                             float* __restrict__ att_out, int ldo, unsigned long long* marks = nullptr) {
+    HIVIS_AMARK(0)
+    static_assert(RM <= 16 && HD % 32 == 0, "rows are the 16-wide MFMA dimension");
+    constexpr int NW = FUSED_NW;
+    constexpr int ROWB = HD * 2;                   // bytes of one cached row
+    constexpr int KS = HD / 32;                    // k-steps of the score product
+    constexpr int NB = HD / 16;                    // 16-dim blocks of the value product
+    constexpr int NCH = ROWB / 16;                 // 16-byte chunks per V row
+    constexpr int KPI = 64 / NCH;                  // V rows per load instruction
+    constexpr int VT = 16 / KPI;                   // V load instructions per 16 keys
+    // row stride of the V tile in LDS: 32 bytes more than the row, so the 4 rows a 16-lane group transposes
+    // start 8 banks apart and the 64-bit transposing reads of a half wavefront touch every bank twice (the minimum)
+    constexpr int VSTRIDE = ROWB + 32;
+    char* vt_all = reinterpret_cast<char*>(lds);                    // [NW][16 keys][VSTRIDE]
+    float* mrg = lds + NW * 16 * VSTRIDE / 4;                       // [NW][RM][HD + 2] per-wavefront partials
+    int* flag = reinterpret_cast<int*>(mrg + NW * RM * (HD + 2));
+
+    int item = item_id;
+    const int rblk = item % sh.n_rblk; item /= sh.n_rblk;
+    const int hblk = item % sh.n_hblk; item /= sh.n_hblk;
+    const int kvh = item % sh.Hkv;
+    const int sl = item / sh.Hkv;
+    const int seq = sh.seq0 + sl;
+    const int group = sh.Hq / sh.Hkv;
+    const int h0 = hblk * sh.gh, nh = min(sh.gh, group - h0);
+    const int i0 = rblk * sh.mi, ni = min(sh.mi, sh.m - i0);
+    const int R = nh * ni;
+    const int pos0 = base[seq] + sh.offset;
+    const int nkeys = min(pos0 + i0 + ni, sh.maxL);
+    const int cs = ((nkeys + sh.nsplit - 1) / sh.nsplit + 15) & ~15;        // keys per split, multiple of 16
+    const int k0 = split * cs, k1 = min(nkeys, k0 + cs);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n16 = lane & 15, g = lane >> 4;
+    const int vks = lane / NCH, vdc = lane % NCH;
+
+    const char* kbase = reinterpret_cast<const char*>(kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD);
+    const char* vbase = reinterpret_cast<const char*>(vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD);
+    char* vt = vt_all + wave * 16 * VSTRIDE;
+
+    // all loads of this wavefront's 16 keys starting at kb_ (rows clamped into the range; masked later)
+    f16x8_t knext[KS]; u32x4_t vnext[VT];
+#define HIVIS_ATTN_LOADS(kb_)                                                                                      \
+    {                                                                                                              \
+        const char* kp_ = kbase + (size_t)min((kb_) + n16, nkeys - 1) * ROWB + g * 16;                             \
+        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) knext[ks] = *reinterpret_cast<const f16x8_t*>(kp_ + ks * 64); \
+        _Pragma("unroll") for (int t = 0; t < VT; ++t)                                                             \
+            vnext[t] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)min((kb_) + t * KPI + vks, nkeys - 1) * ROWB + vdc * 16); \
+    }
+    if (k0 + 16 * wave < k1) HIVIS_ATTN_LOADS(k0 + 16 * wave)
+    HIVIS_AMARK(1)
+
+    // B operand of the score product: q[row lane%16][32 ks + 8 (lane/16) .. +8] * scale in half; rows >= R are zero
+    f16x8_t qb[KS];
+    {
+        const int rq = min(n16, R - 1);
+        const int hh = kvh * group + h0 + rq / ni, i = i0 + rq % ni;
+        const float* qrow = q + (size_t)(sl * sh.m + i) * sh.ldq + (size_t)hh * HD + g * 8;
+        const float scale = (n16 < R) ? rsqrtf((float)HD) : 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const float4 a = *reinterpret_cast<const float4*>(qrow + ks * 32);
+            const float4 b = *reinterpret_cast<const float4*>(qrow + ks * 32 + 4);
+            qb[ks][0] = (_Float16)(a.x * scale); qb[ks][1] = (_Float16)(a.y * scale);
+            qb[ks][2] = (_Float16)(a.z * scale); qb[ks][3] = (_Float16)(a.w * scale);
+            qb[ks][4] = (_Float16)(b.x * scale); qb[ks][5] = (_Float16)(b.y * scale);
+            qb[ks][6] = (_Float16)(b.z * scale); qb[ks][7] = (_Float16)(b.w * scale);
+        }
+    }
+    const int qpos = (n16 < R) ? pos0 + i0 + n16 % ni : 0x7FFFFFFF;     // causal limit of this lane's row
+    HIVIS_AMARK(2)
+
+    float mrun = -INFINITY, lrun = 0.f;
+    f32x4_t acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int kb = k0 + 16 * wave; kb < k1; kb += 16 * NW) {
+        f16x8_t kraw[KS]; u32x4_t vraw[VT];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kraw[ks] = knext[ks];
+#pragma unroll
+        for (int t = 0; t < VT; ++t) vraw[t] = vnext[t];
+        if (kb + 16 * NW < k1) HIVIS_ATTN_LOADS(kb + 16 * NW)
+        // ---- scores, transposed: this lane gets keys kb + 4 (lane/16) + r of row lane%16
+        f32x4_t st = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            st = __builtin_amdgcn_mfma_f32_16x16x32_f16(kraw[ks], qb[ks], st, 0, 0, 0);
+        float sv[4], tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int key = kb + 4 * g + r;
+            sv[r] = (key < k1 && key <= qpos) ? st[r] : -INFINITY;
+            tmax = fmaxf(tmax, sv[r]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float mnew = fmaxf(mrun, tmax);
+        const float mref = (mnew == -INFINITY) ? 0.f : mnew;       // nothing visible yet: every exponential below is 0
+        const float alpha = __expf(mrun - mref);
+        float p[4], psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { p[r] = __expf(sv[r] - mref); psum += p[r]; }
+        mrun = mnew;
+        lrun = lrun * alpha + psum;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[nb][r] *= alpha;
+        }
+        f16x4_t pb;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pb[r] = (_Float16)p[r];
+        // ---- V tile -> LDS (row-major), back as V^T fragments, O^T += V^T . P^T
+#pragma unroll
+        for (int t = 0; t < VT; ++t) *reinterpret_cast<u32x4_t*>(vt + (t * KPI + vks) * VSTRIDE + vdc * 16) = vraw[t];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            // transposing read: within a 16-lane group, lane i element e comes from the address of lane 4e + i/4,
+            // its element i%4; so lane s points at key 4 (lane/16) + s/4, dims 16 nb + 4 (s%4) .. +3
+            const char* src = vt + (4 * g + (n16 >> 2)) * VSTRIDE + (nb * 16 + 4 * (n16 & 3)) * 2;
+            const s16x4_t raw = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(src));
+            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, raw), pb, acc[nb], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+#undef HIVIS_ATTN_LOADS
+    HIVIS_AMARK(3)
+    // ---- per-wavefront partial -> LDS: this lane holds dims 16 nb + 4 (lane/16) + r of row lane%16
+    float lsum = lrun;
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (n16 < R) {
+        float* mr = mrg + (wave * RM + n16) * (HD + 2);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mr[nb * 16 + 4 * g + r] = acc[nb][r];
+        }
+        if (g == 0) { mr[HD] = mrun; mr[HD + 1] = lsum; }
+    }
+    attn_wg_finish<HD, RM>(mrg, flag, sh, item_id, split, R, ni, kvh * group + h0, i0, sl, ws, cnt, att_out, ldo, marks);
+}
+
 template <typename KT, int HD, int RM>
 __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, const KT* __restrict__ kc, const KT* __restrict__ vc,
                                                 const int* __restrict__ base, const AttnShape& sh, int item_id, int split,
                                                 float* __restrict__ lds, float* __restrict__ ws, int* __restrict__ cnt,
-                                                float* __restrict__ att_out, int ldo) {
+                                                float* __restrict__ att_out, int ldo, unsigned long long* marks = nullptr) {
+    HIVIS_AMARK(0)
     constexpr int NW = FUSED_NW;
     constexpr int ROWB = HD * (int)sizeof(KT);     // bytes of one cached row
     constexpr int CH = 16 / (int)sizeof(KT);       // elements per 16-byte chunk
@@ -529,6 +795,7 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
     }
     // the cached keys do not depend on the queries: request the first block before staging q
     if (k0 + 16 * wave < k1) HIVIS_ATTN_LOADS(k0 + 16 * wave)
+    HIVIS_AMARK(1)
 
     for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
         const int r = idx / HD, c = idx % HD;
@@ -536,6 +803,7 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
         qs[idx] = q[(size_t)(sl * sh.m + i) * sh.ldq + (size_t)hh * HD + c] * scale;
     }
     lds_barrier();
+    HIVIS_AMARK(2)
 
     float mrun[RM], lrun[RM], acc[RM][CH];
 #pragma unroll
@@ -612,6 +880,7 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
+    HIVIS_AMARK(3)
     // ---- per-wavefront partial -> LDS (sum over the lanes that share a chunk / over all lanes for l)
 #pragma unroll
     for (int r = 0; r < RM; ++r) {
@@ -627,85 +896,8 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
             if (lane == 0) { mrg[(wave * RM + r) * (HD + 2) + HD] = mrun[r]; mrg[(wave * RM + r) * (HD + 2) + HD + 1] = lsum; }
         }
     }
-    lds_barrier();
-    if (sh.nsplit == 1) {
-        // the whole key range was handled here: merge the NW partials and write the attention rows directly
-        for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
-            const int r = idx / HD, c = idx % HD;
-            float mx = -INFINITY;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) mx = fmaxf(mx, mrg[(w * RM + r) * (HD + 2) + HD]);
-            float num = 0.f, den = 0.f;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                const float mw = mrg[(w * RM + r) * (HD + 2) + HD];
-                if (mw != -INFINITY) {
-                    const float e = __expf(mw - mx);
-                    num += mrg[(w * RM + r) * (HD + 2) + c] * e; den += mrg[(w * RM + r) * (HD + 2) + HD + 1] * e;
-                }
-            }
-            const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
-            st_wt(&att_out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], num / den);
-        }
-        lds_barrier();
-        return;
-    }
-    // ---- merge the NW partials (fixed order) and write ONE partial of this workgroup
-    float* out = ws + ((size_t)item_id * sh.nsplit + split) * RM * (HD + 2);
-    for (int idx = threadIdx.x; idx < R * (HD + 2); idx += FUSED_NT) {
-        const int r = idx / (HD + 2), c = idx % (HD + 2);
-        float mx = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) mx = fmaxf(mx, mrg[(w * RM + r) * (HD + 2) + HD]);
-        float v;
-        if (c == HD) v = mx;
-        else {
-            v = 0.f;
-            const int cc = (c == HD + 1) ? HD + 1 : c;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                const float mw = mrg[(w * RM + r) * (HD + 2) + HD];
-                if (mw != -INFINITY) v += mrg[(w * RM + r) * (HD + 2) + cc] * __expf(mw - mx);
-            }
-        }
-        st_wt(&out[r * (HD + 2) + c], v);
-    }
+    attn_wg_finish<HD, RM>(mrg, reinterpret_cast<int*>(pw_all), sh, item_id, split, R, ni, kvh * group + h0, i0, sl, ws, cnt, att_out, ldo, marks);
 #undef HIVIS_ATTN_LOADS
-    if (cnt == nullptr) { lds_barrier(); return; }        // the partials are merged by a separate phase
-    // ---- the workgroup whose partial completes the item merges all of them (no extra grid barrier):
-    // stores acknowledged -> arrive on the item's counter -> the last arriver reads the nsplit partials
-    wait_vmem();
-    lds_barrier();
-    int* flag = reinterpret_cast<int*>(pw_all);
-    if (threadIdx.x == 0) {
-        // the acknowledgement of a write-through store only says that this XCD's L2 has it; the agent-scope release
-        // makes it visible to the other XCDs before the arrival below
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        flag[0] = __hip_atomic_fetch_add(&cnt[item_id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    lds_barrier();
-    const bool last = flag[0] == sh.nsplit - 1;
-    if (last) {
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        const float* pbase = ws + (size_t)item_id * sh.nsplit * RM * (HD + 2);
-        for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
-            const int r = idx / HD, c = idx % HD;
-            float mx = -INFINITY;
-            for (int sp = 0; sp < sh.nsplit; ++sp) mx = fmaxf(mx, pbase[((size_t)sp * RM + r) * (HD + 2) + HD]);
-            float num = 0.f, den = 0.f;
-            for (int sp = 0; sp < sh.nsplit; ++sp) {
-                const float* pp_ = pbase + ((size_t)sp * RM + r) * (HD + 2);
-                const float ms = pp_[HD];
-                if (ms == -INFINITY) continue;
-                const float w = __expf(ms - mx);
-                num += pp_[c] * w; den += pp_[HD + 1] * w;
-            }
-            const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
-            st_wt(&att_out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], num / den);
-        }
-        if (threadIdx.x == 0) st_wt(&cnt[item_id], 0);
-    }
-    lds_barrier();
 }
 
 // Merge of the nsplit workgroup partials of one item, in split order; writes the attention output rows.
@@ -751,11 +943,17 @@ __device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp,
         const int total = ph.att_items * ph.att.nsplit;
         for (int w = blockIdx.x; w < total; w += gridDim.x) {
             const int item = w / ph.att.nsplit, split = w % ph.att.nsplit;
-            if (pp.hd == 128) attn_wg_partial<KT, 128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy);
-            else attn_wg_partial<KT, 64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy);
+            if constexpr (std::is_same<KT, f16_t>::value) {
+                if (pp.hd == 128) attn_wg_mfma<128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2);
+                else attn_wg_mfma<64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2);
+            } else {
+                if (pp.hd == 128) attn_wg_partial<KT, 128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2);
+                else attn_wg_partial<KT, 64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2);
+            }
         }
     } break;
     case PH_ATTN_MERGE:
+        if (pp.prof2 && blockIdx.x == 0 && threadIdx.x == 0) pp.prof2[0] = wall_clock64();
         for (int item = blockIdx.x; item < ph.att_items; item += gridDim.x) {
             if (pp.hd == 128) attn_wg_merge<128, FUSED_RMAX>(ph.ws, ph.att, item, ph.Y, ph.ldy);
             else attn_wg_merge<64, FUSED_RMAX>(ph.ws, ph.att, item, ph.Y, ph.ldy);

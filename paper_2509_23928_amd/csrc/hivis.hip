@@ -75,8 +75,7 @@ struct hivis_ctx {
     float* rope_tab = nullptr; float* pm = nullptr; int* pi = nullptr; unsigned* bar = nullptr;
     float* fattn_ws = nullptr; size_t fattn_ws_floats = 0;
     struct Program { hivis::Phase* dev = nullptr; int n = 0; std::vector<hivis::Phase>* host = nullptr; };
-    bool dbg_lm_store = false;
-    int keys_per_split = 256;            // attention: cached keys per workgroup before the key range is split further
+    int keys_per_split = 768;            // attention: cached keys per workgroup before the key range is split further
     bool persistent = false;             // HIVIS_PERSISTENT=1: one cooperative launch per pass instead of one launch per phase
     std::map<int, Program> programs;     // key = kind * 64 + K
     unsigned long long* prof = nullptr; int prof_left = 0;   // developer aid: HIVIS_PROF=n dumps per-phase times of n verify passes
@@ -452,7 +451,7 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
     pp.eps = g.rms_eps; pp.theta = g.rope_theta;
     pp.bar = c->bar;
     pp.spin_limit = 1u << 22;
-    { const char* fl = getenv("HIVIS_FLAGS"); pp.flags = fl ? atoi(fl) : 3; }
+    { const char* fl = getenv("HIVIS_FLAGS"); pp.flags = fl ? atoi(fl) : 0; }
     const bool do_prof = c->prof && kind == PROG_VERIFY && c->prof_left > 0;
     pp.prof = do_prof ? c->prof : nullptr;
     pp.prof2 = do_prof ? c->prof + 4096 * 3 : nullptr;
@@ -464,8 +463,8 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
         for (int b = 0; b < g.batch; ++b) max_keys = std::max(max_keys, (kind == PROG_VERIFY ? c->h_tlen[b] : c->h_dlen[b]) + K + 1);
         for (int p = 0; p < pg.n; ++p) {
             Phase ph = (*pg.host)[p];
-            ph.next_W = nullptr;                       // nothing is prefetched across a kernel boundary
-            if (c->dbg_lm_store && ph.type == PH_GEMM && ph.epi == FEPI_LOGITS) ph.epi = FEPI_STORE;   // timing experiment only
+            ph.next_W = nullptr;                       // nothing is prefetched across a kernel boundary (pulling the next launch's
+                                                       // first units into L2 during the epilogue was measured: 3% slower)
             if (ph.type == PH_ATTN || ph.type == PH_ATTN_MERGE) {
                 ph.att.nsplit = std::max(1, std::min(ph.att.nsplit, (max_keys + c->keys_per_split - 1) / c->keys_per_split));
                 if (ph.type == PH_ATTN_MERGE && ph.att.nsplit == 1) continue;
@@ -478,7 +477,7 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             else if (ph.type == PH_ARGMAX) grid = std::min(grid, (pp.M + FUSED_NW - 1) / FUSED_NW);
             else if (ph.type == PH_GEMM && ph.epi != FEPI_LOGITS) grid = std::min(grid, ph.N / 16);
             PassParams ppl = pp;
-            if (do_prof) ppl.prof2 = pp.prof2 + (size_t)p * 8;
+            if (do_prof) { ppl.prof2 = pp.prof2 + (size_t)p * 8; if (p >= pg.n / 2 && p < pg.n / 2 + 8) ppl.prof3 = c->prof + 4096 * 11 + (size_t)(p - pg.n / 2) * 4096; }
 #define HIVIS_LAUNCH(TY, EP) do { if (single) hipLaunchKernelGGL((phase_kernel<WT, TY, EP, true>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, ppl); \
                                   else hipLaunchKernelGGL((phase_kernel<WT, TY, EP, false>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, ppl); } while (0)
             const bool single = ph.type == PH_GEMM && ph.epi != FEPI_LOGITS && ph.epi != FEPI_SILU && ph.epi != FEPI_QKV && ph.N / 16 <= grid;   // one tile per workgroup at most
@@ -518,9 +517,35 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             for (int p = p0; p < std::min(pg.n, p0 + 14); ++p) {
                 const Phase& P = (*pg.host)[p];
                 fprintf(stderr, "[hivis prof] phase %d type %d epi %d: entry %+.2f us after previous entry;", p, P.type, P.epi, ((double)t2[p * 8] - (double)t2[(p - 1) * 8]) * 0.01);
-                for (int k = 1; k < 6; ++k) fprintf(stderr, " m%d %+.2f", k, ((double)t2[p * 8 + k] - (double)t2[p * 8]) * 0.01);
+                for (int k = 1; k < 7; ++k) fprintf(stderr, " m%d %+.2f", k, ((double)t2[p * 8 + k] - (double)t2[p * 8]) * 0.01);
                 fprintf(stderr, "\n");
             }
+            // per-workgroup entry/exit of the same launches: spread of the exits, the latest workgroups and where they ran
+            std::vector<unsigned long long> t3((size_t)8 * 4096);
+            HIP_TRY(c, hipMemcpy(t3.data(), c->prof + 4096 * 11, t3.size() * 8, hipMemcpyDeviceToHost));
+            for (int p = p0; p < std::min(pg.n, p0 + 8); ++p) {
+                const Phase& P = (*pg.host)[p];
+                const unsigned long long* w = t3.data() + (size_t)(p - p0) * 4096;
+                std::vector<std::pair<double, int>> ends; double s0 = 1e300, s1 = 0;
+                for (int b = 0; b < c->fused_grid && b < 1024; ++b) if (w[b * 4]) { s0 = std::min(s0, (double)w[b * 4]); s1 = std::max(s1, (double)w[b * 4]); }
+                for (int b = 0; b < c->fused_grid && b < 1024; ++b) if (w[b * 4]) ends.push_back({((double)w[b * 4 + 1] - s0) * 0.01, b});
+                if (ends.empty()) continue;
+                std::sort(ends.begin(), ends.end());
+                const size_t n = ends.size();
+                fprintf(stderr, "[hivis wg] phase %d type %d epi %d: %zu workgroups, entries within %.2f us; exits min %.2f p10 %.2f p50 %.2f p90 %.2f max %.2f us; latest:", p, P.type, P.epi, n,
+                        (s1 - s0) * 0.01, ends[0].first, ends[n / 10].first, ends[n / 2].first, ends[n * 9 / 10].first, ends[n - 1].first);
+                for (size_t k = n > 6 ? n - 6 : 0; k < n; ++k) {
+                    const unsigned long long id = w[ends[k].second * 4 + 2];
+                    fprintf(stderr, " wg%d(xcc%llu se%llu cu%llu)", ends[k].second, id >> 32, (id >> 13) & 7, (id >> 8) & 15);
+                }
+                double xs[8] = {}; int xn[8] = {};
+                for (auto& e : ends) { const int x = (int)(w[e.second * 4 + 2] >> 32) & 7; xs[x] += e.first; xn[x]++; }
+                fprintf(stderr, "; wg0: entry->mark0 %.2f, mark0->exit %.2f us", ((double)t2[p * 8] - (double)w[0]) * 0.01, ((double)w[1] - (double)t2[p * 8]) * 0.01);
+                fprintf(stderr, "; mean exit per xcc:");
+                for (int x = 0; x < 8; ++x) fprintf(stderr, " %.1f(%d)", xn[x] ? xs[x] / xn[x] : 0.0, xn[x]);
+                fprintf(stderr, "\n");
+            }
+            HIP_TRY(c, hipMemset(c->prof + 4096 * 11, 0, (size_t)8 * 4096 * 8));
             c->prof_left--;
         }
         return HIVIS_OK;
@@ -573,7 +598,6 @@ int fused_setup(hivis_ctx* c) {
         for (const void* k : ks) HIP_TRY(c, hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
     }
     { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }
-    { const char* de = getenv("HIVIS_DBG_LM_STORE"); c->dbg_lm_store = de && de[0] == '1'; }
     { const char* ke = getenv("HIVIS_KEYS_PER_SPLIT"); if (ke && atoi(ke) >= 16) c->keys_per_split = atoi(ke); }
     int nb = 0;
     HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)fused_pass_kernel<WT>, FUSED_NT, c->fused_lds));
@@ -582,7 +606,7 @@ int fused_setup(hivis_ctx* c) {
     int rc;
     if ((rc = dev_alloc(c, &c->bar, 2))) return rc;
     HIP_TRY(c, hipMemset(c->bar, 0, 2 * sizeof(unsigned)));
-    if (const char* pe = getenv("HIVIS_PROF")) { c->prof_left = atoi(pe); if (c->prof_left > 0 && (rc = dev_alloc(c, &c->prof, (size_t)4096 * 11))) return rc; }
+    if (const char* pe = getenv("HIVIS_PROF")) { c->prof_left = atoi(pe); if (c->prof_left > 0) { if ((rc = dev_alloc(c, &c->prof, (size_t)4096 * 19))) return rc; HIP_TRY(c, hipMemset(c->prof, 0, (size_t)4096 * 19 * 8)); } }
     c->fused = true;
     return HIVIS_OK;
 }

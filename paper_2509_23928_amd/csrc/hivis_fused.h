@@ -55,7 +55,8 @@ struct PassParams {
     float eps, theta;
     unsigned* bar;                  // [0] arrival counter (zeroed before launch), [1] abort flag
     unsigned spin_limit;
-    int flags;                      // tuning switches (all combinations are correct): 1 = prefetch a second unit, 2 = early epilogue operands
+    int flags;                      // reserved for tuning experiments (unused)
+    unsigned long long* prof3;      // optional [grid][4] per-workgroup entry time, exit time, hardware id of one launch (one launch per phase only)
     unsigned long long* prof2;      // optional [nphases][8] finer timestamps inside GEMM phases (workgroup 0)
     unsigned long long* prof;       // optional [nphases][3] timestamps of workgroup 0 (phase start, phase end, barrier end), 100 MHz
 };
@@ -98,6 +99,33 @@ constexpr int FUSED_QM = 8;       // activation rows staged per thread per pass 
 // | inv_rms [16] | A chunk of one K pass in MFMA fragment order [NW*KBW blocks][4][RU] x 16 bytes
 __host__ __device__ constexpr size_t fused_gemm_lds_floats(int NW, int G, int RPL, int KBW) {
     return (size_t)NW * G * 64 * RPL + (size_t)G * 64 * RPL + (size_t)NW * FUSED_QM + 16 + (size_t)NW * KBW * 4 * 16 * 4;
+}
+
+// Four consecutive RMSNorm gains as loaded (raw bits of the weight type); converted to float where they are used
+template <typename WT> struct Gain4;
+template <> struct Gain4<bf16_t> {
+    typedef uint2 type;
+    static __device__ __forceinline__ float get(const uint2& g, int e) {
+        const uint32_t w = (e < 2) ? g.x : g.y;
+        return __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
+    }
+};
+template <> struct Gain4<float> {
+    typedef float4 type;
+    static __device__ __forceinline__ float get(const float4& g, int e) { return e == 0 ? g.x : e == 1 ? g.y : e == 2 ? g.z : g.w; }
+};
+
+// K blocks of pass p that wavefront `wave` owns.  A full pass gives every wavefront KBW consecutive blocks; a ragged
+// last pass is dealt out evenly (ceil(rest / NW) blocks each), so that no wavefront streams a whole unit more than the
+// others (with K = 11008 the last pass has 24 blocks: 3 per wavefront instead of 8 for three of them).
+template <int NW, int KBW> __device__ __forceinline__ int unit_bw(int kblks, int p) {
+    const int rest = kblks - p * NW * KBW;
+    return rest >= NW * KBW ? KBW : max(0, (rest + NW - 1) / NW);
+}
+template <int NW, int KBW> __device__ __forceinline__ int unit_kb0(int kblks, int p, int wave) { return p * NW * KBW + wave * unit_bw<NW, KBW>(kblks, p); }
+template <int NW, int KBW> __device__ __forceinline__ int unit_nkb(int kblks, int p, int wave) {
+    const int bw = unit_bw<NW, KBW>(kblks, p);
+    return max(0, min(bw, kblks - p * NW * KBW - wave * bw));
 }
 
 // Loads of one unit: the wavefront's K blocks [kb0, kb0+nkb) of tile `tile`.
@@ -172,11 +200,16 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     uint4* chunk = reinterpret_cast<uint4*>(inv_rms + 16);
 
     const int epi = (EPI >= 0) ? EPI : ph.epi;       // compile-time epilogue when the phase has its own kernel
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wavefront index as a scalar: branches on it are uniform
     const int M = pp.M, K = ph.K, N = ph.N;
     const int kblks = K / KB, ntiles = N / 16;
-    const int t_begin = (int)(((long long)blockIdx.x * ntiles) / gridDim.x);
-    const int t_end = (int)(((long long)(blockIdx.x + 1) * ntiles) / gridDim.x);
+    // (the divisions run on the vector ALU; read back as scalars so that every branch on the tile range is uniform)
+    // Workgroups are dealt to the 8 XCDs round-robin, so workgroup b runs on XCD b % 8.  When the tiles do not divide
+    // evenly, the workgroups with one tile more must be spread over all XCDs (each has its own L2 and memory path):
+    // XCD x takes the contiguous share [x * grid/8, (x+1) * grid/8) of the virtual workgroup order.
+    const int vb = (gridDim.x % 8 == 0) ? (int)((blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8) : (int)blockIdx.x;
+    const int t_begin = __builtin_amdgcn_readfirstlane((int)(((long long)vb * ntiles) / gridDim.x));
+    const int t_end = __builtin_amdgcn_readfirstlane((int)(((long long)(vb + 1) * ntiles) / gridDim.x));
     const int ntl = t_end - t_begin;
     const int npass = (kblks + NW * KBW - 1) / (NW * KBW);
     const WT* gain = (ph.pro == PRO_RMS) ? (const WT*)ph.gain : nullptr;
@@ -193,8 +226,8 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
 
     // first units of the next GEMM phase for this wavefront (persistent mode only: requested at the end of this phase)
     const int n_kblks = ph.next_K / KB, n_ntiles = ph.next_N / 16;
-    const int n_tile = ph.next_W ? (int)(((long long)blockIdx.x * n_ntiles) / gridDim.x) : 0;
-    const int n_tend = ph.next_W ? (int)(((long long)(blockIdx.x + 1) * n_ntiles) / gridDim.x) : 0;
+    const int n_tile = __builtin_amdgcn_readfirstlane(ph.next_W ? (int)(((long long)vb * n_ntiles) / gridDim.x) : 0);
+    const int n_tend = __builtin_amdgcn_readfirstlane(ph.next_W ? (int)(((long long)(vb + 1) * n_ntiles) / gridDim.x) : 0);
     const bool n_has = ph.next_W && n_tile < n_tend;
     const int n_npass = (n_kblks + NW * KBW - 1) / (NW * KBW);
     // The unit order of a phase is tile-inner, pass-outer within a tile group.  `head` holds the first unit and
@@ -202,14 +235,13 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     // of the next pass.
 #define HIVIS_FIRST_UNITS(W_, kblks_, tile_, ntl_, npass_)                                                         \
     {                                                                                                              \
-        const int nk_ = max(0, min(KBW, (kblks_) - wave * KBW));                                                   \
-        issue_unit(head, W_, kblks_, tile_, wave * KBW, nk_, lane);                                                \
-        head_valid = true; wb1_valid = false;                                                                      \
-        if ((ntl_) >= 2) { issue_unit(wb1, W_, kblks_, (tile_) + 1, wave * KBW, nk_, lane); wb1_valid = true; }    \
-        else if (SINGLE && (npass_) >= 2) {                                                                        \
-            const int kb1_ = (NW + wave) * KBW;                                                                    \
-            issue_unit(wb1, W_, kblks_, tile_, kb1_, max(0, min(KBW, (kblks_) - kb1_)), lane); wb1_valid = true;   \
-        }                                                                                                          \
+        issue_unit(head, W_, kblks_, tile_, unit_kb0<NW, KBW>(kblks_, 0, wave), unit_nkb<NW, KBW>(kblks_, 0, wave), lane); \
+        head_valid = true;                                                                                         \
+        /* one call site for the second unit (two alternative ones make the compiler drain the first unit's loads) */ \
+        const bool next_tile_ = (ntl_) >= 2;                                                                       \
+        wb1_valid = next_tile_ || (SINGLE && (npass_) >= 2);                                                       \
+        const int p1_ = next_tile_ ? 0 : 1;                                                                        \
+        if (wb1_valid) issue_unit(wb1, W_, kblks_, (tile_) + (next_tile_ ? 1 : 0), unit_kb0<NW, KBW>(kblks_, p1_, wave), unit_nkb<NW, KBW>(kblks_, p1_, wave), lane); \
     }
 
     if (ntl <= 0) {
@@ -220,28 +252,20 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         if (!head_valid && n_has) HIVIS_FIRST_UNITS(ph.next_W, n_kblks, n_tile, n_tend - n_tile, n_npass)
         return;
     }
-    // nothing prefetched for this phase: request its first two units now, ahead of the activation rows
-    if (!head_valid) HIVIS_FIRST_UNITS(W, kblks, t_begin, ntl, npass)
-    head_valid = false;
-    const bool wb1_first = wb1_valid;       // wb1 already holds the second unit of the phase
-    wb1_valid = false;
 
     // raw activation loads of pass `ps`: float4 (row0 + q*RSTEP, ps*CW + 4*col4) and the gain of those 4 columns
     // (unconditional loads from clamped addresses: a load under a divergent branch is followed by a full wait,
     //  which would serialise the rows into one memory round trip each)
     static_assert(QM * RSTEP >= ROWS, "every row is staged by some thread");
-    float4 araw[QM]; float graw[4];
+    typedef typename Gain4<WT>::type gain4_t;
+    float4 araw[QM]; gain4_t graw = gain4_t();
 #define HIVIS_LOAD_RAW(ps)                                                                                         \
     {                                                                                                              \
         const int k_ = min((ps) * CW + 4 * col4, K - 4);                                                           \
+        if (gain) graw = *reinterpret_cast<const gain4_t*>(gain + k_);   /* converted where it is used: no wait here */ \
         _Pragma("unroll") for (int q = 0; q < QM; ++q) {                                                           \
             const int row_ = min(row0 + q * RSTEP, M - 1);                                                         \
             araw[q] = *reinterpret_cast<const float4*>(A + (size_t)row_ * lda + k_);                               \
-        }                                                                                                          \
-        if (gain) {                                                                                                \
-            _Pragma("unroll") for (int e = 0; e < 4; ++e) graw[e] = to_f32(gain[k_ + e]);                          \
-        } else {                                                                                                   \
-            _Pragma("unroll") for (int e = 0; e < 4; ++e) graw[e] = 1.0f;                                          \
         }                                                                                                          \
     }
     // Stage pass `ps` (whose rows are in araw) into LDS as MFMA fragments, request the rows of pass `nx` (or none if
@@ -253,23 +277,30 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         if (row_ < M && (ps) * CW + 4 * col4 < K) {                                                                \
             float x_[4] = {araw[q].x, araw[q].y, araw[q].z, araw[q].w};                                            \
             if (do_ssq) ssq_acc[q] += x_[0] * x_[0] + x_[1] * x_[1] + x_[2] * x_[2] + x_[3] * x_[3];               \
-            _Pragma("unroll") for (int e = 0; e < 4; ++e) x_[e] *= graw[e];                                        \
+            if (gain) { _Pragma("unroll") for (int e = 0; e < 4; ++e) x_[e] *= Gain4<WT>::get(graw, e); }          \
             stage_store(WT(), chunk, RU, row_, 4 * col4, x_);                                                      \
         }                                                                                                          \
     }                                                                                                              \
     if ((nx) >= 0) HIVIS_LOAD_RAW(nx)                                                                              \
     lds_barrier();                                                                                                 \
     {                                                                                                              \
-        const int kb0_ = ((ps) * NW + wave) * KBW;                                                                 \
-        const int nkb_ = max(0, min(KBW, kblks - kb0_));                                                           \
+        const int nkb_ = unit_nkb<NW, KBW>(kblks, ps, wave);                                                       \
+        const int fb_ = wave * unit_bw<NW, KBW>(kblks, ps);      /* first block of this wavefront within the chunk */ \
         const int i_ = min(lane & 15, RU - 1), g4_ = lane >> 4;                                                    \
         _Pragma("unroll") for (int j = 0; j < KBW; ++j) {                                                          \
-            const uint4 u_ = chunk[((wave * KBW + j) * 4 + g4_) * RU + i_];                                        \
+            const uint4 u_ = chunk[((min(fb_ + j, NW * KBW - 1)) * 4 + g4_) * RU + i_];                            \
             frag_from(af[j], (j < nkb_) ? u_ : make_uint4(0, 0, 0, 0));                                            \
         }                                                                                                          \
     }
     HIVIS_MARK(0)
+    // The activation rows are requested BEFORE the first weight units: loads return in order, so rows requested
+    // after 16 KiB of weights per wavefront could not be staged until those weights had arrived from HBM.
     HIVIS_LOAD_RAW(0)
+    // nothing prefetched for this phase (always the case with one launch per phase): request its first two units now
+    if (!head_valid) HIVIS_FIRST_UNITS(W, kblks, t_begin, ntl, npass)
+    head_valid = false;
+    const bool wb1_first = wb1_valid;       // wb1 already holds the second unit of the phase
+    wb1_valid = false;
 
     for (int tg = t_begin; tg < t_end; tg += G) {
         const int ng = min(G, t_end - tg);
@@ -285,25 +316,26 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
                 if (pass == 0) { HIVIS_MARK(1) }
 #pragma unroll
                 for (int j = 0; j < U; ++j) mfma_block(acc[0], af[j], head[j]);
-                if (pass + 2 < npass) { const int kb2 = ((pass + 2) * NW + wave) * KBW; issue_unit(head, W, kblks, tg, kb2, max(0, min(KBW, kblks - kb2)), lane); }
+                if (pass + 2 < npass) issue_unit(head, W, kblks, tg, unit_kb0<NW, KBW>(kblks, pass + 2, wave), unit_nkb<NW, KBW>(kblks, pass + 2, wave), lane);
                 if (pass + 1 < npass) {
-                    if (pass == 0 && !wb1_first) { const int kb1 = (NW + wave) * KBW; issue_unit(wb1, W, kblks, tg, kb1, max(0, min(KBW, kblks - kb1)), lane); }
+                    if (pass == 0 && !wb1_first) issue_unit(wb1, W, kblks, tg, unit_kb0<NW, KBW>(kblks, 1, wave), unit_nkb<NW, KBW>(kblks, 1, wave), lane);
                     HIVIS_STAGE(pass + 1, (pass + 2 < npass) ? pass + 2 : -1, true)
 #pragma unroll
                     for (int j = 0; j < U; ++j) mfma_block(acc[0], af[j], wb1[j]);
-                    if (pass + 3 < npass) { const int kb3 = ((pass + 3) * NW + wave) * KBW; issue_unit(wb1, W, kblks, tg, kb3, max(0, min(KBW, kblks - kb3)), lane); }
+                    if (pass + 3 < npass) issue_unit(wb1, W, kblks, tg, unit_kb0<NW, KBW>(kblks, pass + 3, wave), unit_nkb<NW, KBW>(kblks, pass + 3, wave), lane);
                 }
             }
         } else {
             for (int pass = 0; pass < npass; ++pass) {
-                const int kb0 = (pass * NW + wave) * KBW;
-                const int nkb = max(0, min(KBW, kblks - kb0));
+                const int kb0 = unit_kb0<NW, KBW>(kblks, pass, wave);
+                const int nkb = unit_nkb<NW, KBW>(kblks, pass, wave);
                 // where the prefetch chain goes after the last unit of this (tile group, pass)
-                int ntile = tg, nkb0 = 0, ntiles2 = ng; bool nvalid = true;
-                if (pass + 1 < npass) { nkb0 = ((pass + 1) * NW + wave) * KBW; }
-                else if (tg + G < t_end) { ntile = tg + G; nkb0 = wave * KBW; ntiles2 = t_end - ntile; }
+                int ntile = tg, npass_i = pass + 1, ntiles2 = ng; bool nvalid = true;
+                if (pass + 1 < npass) { }
+                else if (tg + G < t_end) { ntile = tg + G; npass_i = 0; ntiles2 = t_end - ntile; }
                 else nvalid = false;     // the next phase's first units are requested after this phase's stores (see the end)
-                const int nnkb = max(0, min(KBW, kblks - nkb0));
+                const int nkb0 = unit_kb0<NW, KBW>(kblks, npass_i, wave);
+                const int nnkb = unit_nkb<NW, KBW>(kblks, npass_i, wave);
                 const bool have_wb1 = (first && pass == 0) ? wb1_first : wb1_valid;
                 wb1_valid = false;
                 HIVIS_STAGE(pass, (pass + 1 < npass) ? pass + 1 : ((tg + G < t_end) ? 0 : -1), first)
@@ -432,7 +464,6 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
 #undef HIVIS_LOAD_RAW
 #undef HIVIS_STAGE
     HIVIS_MARK(5)
-#undef HIVIS_MARK
     if (epi == FEPI_LOGITS) {
         // per-row candidate of this workgroup: the threads of one row meet through LDS
         lds_barrier();
@@ -460,6 +491,8 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     // only wait available (vmcnt) also covers loads: so first drain, THEN request the first two units of the next
     // GEMM phase, which stay in flight across the barrier (persistent mode).
     wait_vmem();
+    HIVIS_MARK(6)
+#undef HIVIS_MARK
     if (n_has) HIVIS_FIRST_UNITS(ph.next_W, n_kblks, n_tile, n_tend - n_tile, n_npass)
 #undef HIVIS_FIRST_UNITS
 }
@@ -621,7 +654,7 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     const int nkeys = min(pos0 + i0 + ni, sh.maxL);
     const int cs = ((nkeys + sh.nsplit - 1) / sh.nsplit + 15) & ~15;        // keys per split, multiple of 16
     const int k0 = split * cs, k1 = min(nkeys, k0 + cs);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wavefront index as a scalar: branches on it are uniform
     const int n16 = lane & 15, g = lane >> 4;
     const int vks = lane / NCH, vdc = lane % NCH;
 
@@ -629,7 +662,9 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     const char* vbase = reinterpret_cast<const char*>(vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD);
     char* vt = vt_all + wave * 16 * VSTRIDE;
 
-    // all loads of this wavefront's 16 keys starting at kb_ (rows clamped into the range; masked later)
+    // all loads of this wavefront's 16 keys starting at kb_ (rows clamped into the range; masked later).  One tile
+    // ahead is enough: with a single key split the loop is bound by what one compute unit can pull, not by latency
+    // (two tiles in flight measured slower).
     f16x8_t knext[KS]; u32x4_t vnext[VT];
 #define HIVIS_ATTN_LOADS(kb_)                                                                                      \
     {                                                                                                              \
@@ -772,7 +807,7 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
     const int nkeys = min(pos0 + i0 + ni, sh.maxL);
     const int cs = ((nkeys + sh.nsplit - 1) / sh.nsplit + 15) & ~15;        // keys per split, multiple of 16
     const int k0 = split * cs, k1 = min(nkeys, k0 + cs);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wavefront index as a scalar: branches on it are uniform
     const float scale = rsqrtf((float)HD);
 
     const KT* kbase = kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
@@ -1042,7 +1077,16 @@ __global__ __launch_bounds__(FUSED_NT) void phase_kernel(Phase ph, PassParams pp
     extern __shared__ __align__(16) float lds[];
     uint4 head[FUSED_U], wb1[FUSED_U];
     bool head_valid = false, wb1_valid = false;
+    if (pp.prof3 && threadIdx.x == 0) {
+        pp.prof3[blockIdx.x * 4] = wall_clock64();
+        // HW_ID (wave, SIMD, CU, shader array, shader engine) and XCC_ID of the wavefront
+        pp.prof3[blockIdx.x * 4 + 2] = (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) | ((unsigned long long)__builtin_amdgcn_s_getreg((3 << 11) | 20) << 32);
+    }
     run_phase<WT, TYPE, EPI, SINGLE>(ph, pp, lds, head, head_valid, wb1, wb1_valid, 0);
+    if (pp.prof3) {
+        lds_barrier();
+        if (threadIdx.x == 0) pp.prof3[blockIdx.x * 4 + 1] = wall_clock64();
+    }
 }
 
 }  // namespace hivis

@@ -616,7 +616,7 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
 __host__ __device__ constexpr size_t fused_attn_mfma_lds_floats(int hd, int nw, int rm) {
-    return (size_t)nw * 16 * (hd * 2 + 32) / 4 + (size_t)nw * rm * (hd + 2) + 16;
+    return (size_t)nw * 16 * (hd * 2 + 32) / 4 + (size_t)nw * 16 * (hd * 2 + 16) / 4 + (size_t)nw * rm * (hd + 2) + 16;
 }
 
 template <int HD, int RM>
@@ -636,8 +636,11 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     // row stride of the V tile in LDS: 32 bytes more than the row, so the 4 rows a 16-lane group transposes
     // start 8 banks apart and the 64-bit transposing reads of a half wavefront touch every bank twice (the minimum)
     constexpr int VSTRIDE = ROWB + 32;
+    // K tile in LDS: 16 bytes more than the row, so the 8 lanes a 128-bit read serves per clock hit 32 different banks
+    constexpr int KSTRIDE = ROWB + 16;
     char* vt_all = reinterpret_cast<char*>(lds);                    // [NW][16 keys][VSTRIDE]
-    float* mrg = lds + NW * 16 * VSTRIDE / 4;                       // [NW][RM][HD + 2] per-wavefront partials
+    char* kt_all = vt_all + NW * 16 * VSTRIDE;                      // [NW][16 keys][KSTRIDE]
+    float* mrg = lds + NW * 16 * (VSTRIDE + KSTRIDE) / 4;           // [NW][RM][HD + 2] per-wavefront partials
     int* flag = reinterpret_cast<int*>(mrg + NW * RM * (HD + 2));
 
     int item = item_id;
@@ -661,17 +664,20 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     const char* kbase = reinterpret_cast<const char*>(kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD);
     const char* vbase = reinterpret_cast<const char*>(vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD);
     char* vt = vt_all + wave * 16 * VSTRIDE;
+    char* kt = kt_all + wave * 16 * KSTRIDE;
 
-    // all loads of this wavefront's 16 keys starting at kb_ (rows clamped into the range; masked later).  One tile
-    // ahead is enough: with a single key split the loop is bound by what one compute unit can pull, not by latency
-    // (two tiles in flight measured slower).
-    f16x8_t knext[KS]; u32x4_t vnext[VT];
+    // all loads of this wavefront's 16 keys starting at kb_ (rows clamped into the range; masked later).  K and V rows
+    // are both read as whole rows, 4 (HD=128) rows = 1 KiB contiguous per instruction: reading K directly in fragment
+    // order (16 rows x 64 bytes per instruction) costs the address coalescer 4x the cycles and bounded the loop.
+    // One tile ahead is enough (two in flight measured slower).
+    u32x4_t knext[VT], vnext[VT];
 #define HIVIS_ATTN_LOADS(kb_)                                                                                      \
     {                                                                                                              \
-        const char* kp_ = kbase + (size_t)min((kb_) + n16, nkeys - 1) * ROWB + g * 16;                             \
-        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) knext[ks] = *reinterpret_cast<const f16x8_t*>(kp_ + ks * 64); \
-        _Pragma("unroll") for (int t = 0; t < VT; ++t)                                                             \
-            vnext[t] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)min((kb_) + t * KPI + vks, nkeys - 1) * ROWB + vdc * 16); \
+        _Pragma("unroll") for (int t = 0; t < VT; ++t) {                                                           \
+            const size_t off_ = (size_t)min((kb_) + t * KPI + vks, nkeys - 1) * ROWB + vdc * 16;                   \
+            knext[t] = *reinterpret_cast<const u32x4_t*>(kbase + off_);                                            \
+            vnext[t] = *reinterpret_cast<const u32x4_t*>(vbase + off_);                                            \
+        }                                                                                                          \
     }
     if (k0 + 16 * wave < k1) HIVIS_ATTN_LOADS(k0 + 16 * wave)
     HIVIS_AMARK(1)
@@ -702,17 +708,25 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     for (int kb = k0 + 16 * wave; kb < k1; kb += 16 * NW) {
-        f16x8_t kraw[KS]; u32x4_t vraw[VT];
+        u32x4_t vraw[VT];
+        // ---- both tiles -> LDS (row-major); the K fragments come back as plain 128-bit reads (key lane%16,
+        //      dims 32 ks + 8 (lane/16) .. +8), the V^T fragments through the transposing read further down
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kraw[ks] = knext[ks];
-#pragma unroll
-        for (int t = 0; t < VT; ++t) vraw[t] = vnext[t];
+        for (int t = 0; t < VT; ++t) {
+            *reinterpret_cast<u32x4_t*>(kt + (t * KPI + vks) * KSTRIDE + vdc * 16) = knext[t];
+            vraw[t] = vnext[t];
+        }
         if (kb + 16 * NW < k1) HIVIS_ATTN_LOADS(kb + 16 * NW)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         // ---- scores, transposed: this lane gets keys kb + 4 (lane/16) + r of row lane%16
         f32x4_t st = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            st = __builtin_amdgcn_mfma_f32_16x16x32_f16(kraw[ks], qb[ks], st, 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) {
+            const f16x8_t kf = *reinterpret_cast<const f16x8_t*>(kt + n16 * KSTRIDE + ks * 64 + g * 16);
+            st = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qb[ks], st, 0, 0, 0);
+        }
         float sv[4], tmax = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {

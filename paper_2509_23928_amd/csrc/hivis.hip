@@ -623,6 +623,26 @@ int tall_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
     return HIVIS_OK;
 }
 
+// Prefill attention of one sequence on the matrix cores: the same workgroup routine as the verify pass (one item =
+// one head x 8 consecutive rows, all visible keys, no key split), launched once over all items.
+template <typename WT>
+int prefill_attention_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int* base, int seq, int m, float* out, int ldo) {
+    const hivis_config& g = c->cfg;
+    int items = 0;
+    Phase ph{};
+    ph.type = PH_ATTN;
+    ph.att = fused_attn_shape(c, 1, m, 0, kv.maxL, ldq, &items);
+    ph.att.seq0 = seq; ph.att.nsplit = 1;
+    ph.att_items = items;
+    ph.A = q; ph.kc = kv.k; ph.vc = kv.v; ph.maxL = kv.maxL; ph.base = base; ph.offset = 0;
+    ph.Y = out; ph.ldy = ldo; ph.ws = nullptr; ph.cnt = nullptr;
+    PassParams pp{};
+    pp.M = m; pp.nseq = 1; pp.m = m; pp.d = g.d; pp.Hq = g.n_q_heads; pp.Hkv = g.n_kv_heads; pp.hd = g.head_dim; pp.F = g.ffn; pp.V = g.vocab;
+    hipLaunchKernelGGL((phase_kernel<WT, PH_ATTN, 0, false>), dim3(items), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp);
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
 template <typename WT>
 int prefill_target_tall(hivis_ctx* c, int b, int v, int l) {
     typedef typename KVType<WT>::type KT;
@@ -637,7 +657,8 @@ int prefill_target_tall(hivis_ctx* c, int b, int v, int l) {
         hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, pending, d, (const WT*)L.norm1, c->pf_a, d, d, g.rms_eps);
         if (int rc = tall_gemm(c, c->pf_a, d, M, d, L.wqkv, nqkv, c->pf_qkv, nqkv)) return rc;
         hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M), dim3(256), 0, c->stream, c->pf_qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, (const int*)c->zeros, 0, b, M, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
-        if (int rc = attention<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, M, c->pf_att, qd)) return rc;
+        if (c->fused) { if (int rc = prefill_attention_mfma<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, b, M, c->pf_att, qd)) return rc; }
+        else if (int rc = attention<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, M, c->pf_att, qd)) return rc;
         if (int rc = tall_gemm(c, c->pf_att, qd, M, qd, L.wo, d, c->pf_proj, d)) return rc;
         hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, (const float*)c->pf_proj, d, (const WT*)L.norm2, c->pf_a, d, d, g.rms_eps);
         if (int rc = tall_gemm(c, c->pf_a, d, M, d, L.wgu, 2 * F, c->pf_gu, 2 * F)) return rc;

@@ -162,6 +162,19 @@ def test_long_cache_uses_key_splits():
     print("long cache max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
 
 
+def test_forced_small_key_splits_hd64_and_hd128():
+    # 48 keys per workgroup: many key splits (ragged last split, splits of a single 16-key tile) for both head sizes
+    import os
+    os.environ["HIVIS_KEYS_PER_SPLIT"] = "48"
+    try:
+        sbs = run_generic(small_bf16(), 27, 2, plant=(4,))
+        print("forced key splits hd128 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+        sbs = run_generic(small_bf16(head_dim=64, n_q_heads=8, n_kv_heads=2), 28, 2, plant=(2,))
+        print("forced key splits hd64 gqa max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    finally:
+        del os.environ["HIVIS_KEYS_PER_SPLIT"]
+
+
 def test_gqa_group7_k6_qwen_like_shape():
     # 28 query / 4 kv heads (group 7), K = 6 -> 7 rows per sequence, as in the Qwen2.5-VL-shaped workload, at reduced width
     cfg = small_bf16(n_q_heads=28, n_kv_heads=4, head_dim=64, d=1792, ffn=2368, vocab=4096, K=6, n_vis=130, n_text=50,

@@ -199,7 +199,7 @@ def main():
     k_gbs = k_bytes / (k_us * 1e-6) / 1e9 if k_launches else 0.0
     out["roofline"] = {"bound": "hbm",
                        "kernel": "phase_kernel<bf16, GEMM, gate|up>: fused RMSNorm + [d x 2F] weight stream + SiLU*up of the verify pass "
-                                 "(largest share of bytes and of time); HIP events recorded around each launch on the library's stream",
+                                 "(largest share of bytes and of time); HIP events recorded around every 8th launch on the library's stream (timing every launch idles the queue ~8 us per pair and slowed the pass by 7%)",
                        "achieved": k_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs / HBM_PEAK_GBS,
                        "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.config), "algorithmic_bytes_per_launch": k_bytes,
                        "avg_launch_us": k_us, "launches_timed": k_launches}

@@ -146,13 +146,17 @@ int hivis_kv_lengths(hivis_ctx *ctx, int32_t *target_len, int32_t *drafter_len);
 int hivis_get_tokens(hivis_ctx *ctx, int32_t *drafts, int32_t *target_tokens);
 
 /* Timing hook: when enabled, hivis_draft / hivis_verify / hivis_accept / hivis_prefill record HIP
- * events on the context's stream around their work; hivis_phase_ms returns and clears the accumulated
- * milliseconds and call counts.  phase: 0 prefill, 1 draft (one call = K steps), 2 verify, 3 accept+roll. */
+ * events on the context's stream around their work, without waiting for them (they are read at the next
+ * hivis_accept, which synchronises anyway, or by hivis_phase_ms); hivis_phase_ms synchronises, returns and
+ * clears the accumulated milliseconds and call counts.
+ * phase: 0 prefill, 1 draft (one call = K steps), 2 verify, 3 accept+roll. */
 int hivis_timing(hivis_ctx *ctx, int32_t enable);
 int hivis_phase_ms(hivis_ctx *ctx, int32_t phase, double *total_ms, int64_t *calls);
 
 /* Kernel-level timing of the verify pass's weight-streaming GEMM launches of one kind, with HIP events recorded on
- * the context's stream directly around each launch (resolved at the next hivis_accept).  gemm_kind: 1 = O / down
+ * the context's stream directly around every 8th such launch (an event pair leaves the queue idle for several
+ * microseconds, so timing every launch would slow the pass it measures; the launches of one kind are alike across
+ * layers).  Resolved at the next hivis_accept.  gemm_kind: 1 = O / down
  * projection (+ residual), 3 = fused QKV (+ RMSNorm, RoPE, cache append), 4 = fused gate|up (+ RMSNorm, SiLU*up),
  * 5 = LM head (+ greedy candidates); -1 switches it off.  hivis_kernel_ms returns and clears the accumulated
  * milliseconds and launch count, and the algorithmic bytes of one such launch (its weight matrix, read once). */

@@ -62,6 +62,7 @@ struct hivis_ctx {
     float *attn_ws = nullptr; size_t attn_ws_floats = 0;
     float *logits_v = nullptr, *logits_d = nullptr, *logits_p = nullptr;
     int32_t *row_tok = nullptr, *drafts = nullptr, *ttok = nullptr, *nacc = nullptr, *out_tok = nullptr, *next_tok = nullptr;
+    int32_t* h_result = nullptr;         // pinned host mirror of [nacc | out_tok | abort flag]
     void* vis = nullptr;        // staging for vis_embeds [B][max_vis][d]
     // whole-prompt prefill buffers (bf16 models): all v+l rows of one sequence per layer
     int pf_rows = 0;
@@ -82,10 +83,12 @@ struct hivis_ctx {
 
     // timing
     int ktime_epi = -1;                                  // GEMM epilogue kind whose verify launches are event-timed (-1: none)
+    int ktime_stride = 8; int64_t ktime_seen = 0;        // every ktime_stride-th such launch is timed (an event pair costs ~8 us of idle queue)
     std::vector<hipEvent_t> kev; size_t kev_used = 0;     // event pairs recorded since the last accept
     double kms = 0; int64_t klaunches = 0; double kbytes = 0;
     bool timing = false;
-    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    // phase timing: event pairs recorded without waiting, resolved at the next point where the stream is synchronised anyway
+    std::vector<hipEvent_t> pev; std::vector<int> pev_phase; size_t pev_used = 0;
     double phase_ms[4] = {0, 0, 0, 0}; int64_t phase_calls[4] = {0, 0, 0, 0};
     std::vector<void*> allocs;
 };
@@ -481,7 +484,7 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
 #define HIVIS_LAUNCH(TY, EP) do { if (single) hipLaunchKernelGGL((phase_kernel<WT, TY, EP, true>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, ppl); \
                                   else hipLaunchKernelGGL((phase_kernel<WT, TY, EP, false>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, ppl); } while (0)
             const bool single = ph.type == PH_GEMM && ph.epi != FEPI_LOGITS && ph.epi != FEPI_SILU && ph.epi != FEPI_QKV && ph.N / 16 <= grid;   // one tile per workgroup at most
-            const bool ktimed = kind == PROG_VERIFY && ph.type == PH_GEMM && ph.epi == c->ktime_epi;
+            const bool ktimed = kind == PROG_VERIFY && ph.type == PH_GEMM && ph.epi == c->ktime_epi && (c->ktime_seen++ % c->ktime_stride) == 0;
             if (ktimed) {
                 if (c->kev_used + 2 > c->kev.size()) { hipEvent_t e0, e1; HIP_TRY(c, hipEventCreate(&e0)); HIP_TRY(c, hipEventCreate(&e1)); c->kev.push_back(e0); c->kev.push_back(e1); }
                 HIP_TRY(c, hipEventRecord(c->kev[c->kev_used], c->stream));
@@ -674,16 +677,34 @@ int prefill_target_tall(hivis_ctx* c, int b, int v, int l) {
 }
 
 struct PhaseTimer {
-    hivis_ctx* c; int phase;
-    PhaseTimer(hivis_ctx* c_, int p) : c(c_), phase(p) { if (c->timing) (void)hipEventRecord(c->ev0, c->stream); }
-    void stop() {
+    hivis_ctx* c; int phase; bool on;
+    PhaseTimer(hivis_ctx* c_, int p) : c(c_), phase(p), on(false) {
         if (!c->timing) return;
-        (void)hipEventRecord(c->ev1, c->stream);
-        (void)hipEventSynchronize(c->ev1);
-        float ms = 0.f;
-        if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) { c->phase_ms[phase] += ms; c->phase_calls[phase]++; }
+        while (c->pev_used + 2 > c->pev.size()) {
+            hipEvent_t e = nullptr;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            c->pev.push_back(e);
+        }
+        on = hipEventRecord(c->pev[c->pev_used], c->stream) == hipSuccess;
+    }
+    void stop() {
+        if (!on) return;
+        on = false;
+        if (hipEventRecord(c->pev[c->pev_used + 1], c->stream) != hipSuccess) return;
+        c->pev_phase.resize(c->pev.size() / 2);
+        c->pev_phase[c->pev_used / 2] = phase;
+        c->pev_used += 2;
     }
 };
+// after a stream synchronisation: fold the recorded pairs into the per-phase totals
+static void resolve_phase_events(hivis_ctx* c) {
+    for (size_t i = 0; i + 1 < c->pev_used; i += 2) {
+        float ms = 0.f;
+        const int ph = c->pev_phase[i / 2];
+        if (hipEventElapsedTime(&ms, c->pev[i], c->pev[i + 1]) == hipSuccess) { c->phase_ms[ph] += ms; c->phase_calls[ph]++; }
+    }
+    c->pev_used = 0;
+}
 
 // ---- the four calls, typed -------------------------------------------------------------------
 template <typename WT>
@@ -818,23 +839,24 @@ int do_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
     hipLaunchKernelGGL(select_row_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)c->dout, K + 1, (const int32_t*)c->nacc, c->catD, 2 * d, c->dlen, d);
     HIP_TRY(c, hipGetLastError());
     pt.stop();
-    std::vector<int32_t> hn(B), ht((size_t)B * (g.k_max + 1));
-    HIP_TRY(c, hipMemcpyAsync(hn.data(), c->nacc, B * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(ht.data(), c->out_tok, ht.size() * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
-    unsigned aborted = 0;
-    if (c->fused) HIP_TRY(c, hipMemcpyAsync(&aborted, c->bar + 1, sizeof(unsigned), hipMemcpyDeviceToHost, c->stream));
+    const size_t nres = (size_t)B + (size_t)B * (g.k_max + 1);
+    HIP_TRY(c, hipMemcpyAsync(c->h_result, c->nacc, nres * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    c->h_result[nres] = 0;
+    if (c->fused && c->persistent) HIP_TRY(c, hipMemcpyAsync(c->h_result + nres, c->bar + 1, sizeof(unsigned), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    if (aborted) return fail(c, HIVIS_EHIP, "persistent kernel: grid barrier timed out (pass aborted)");
+    if (c->h_result[nres]) return fail(c, HIVIS_EHIP, "persistent kernel: grid barrier timed out (pass aborted)");
+    const int32_t* hn = c->h_result; const int32_t* ht = c->h_result + B;
     for (size_t i = 0; i + 1 < c->kev_used; i += 2) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, c->kev[i], c->kev[i + 1]) == hipSuccess) { c->kms += ms; c->klaunches++; }
     }
     c->kev_used = 0;
+    resolve_phase_events(c);
     for (int b = 0; b < B; ++b) {
         c->h_tlen[b] += hn[b] + 1; c->h_dlen[b] += hn[b] + 1;
         if (n_accepted) n_accepted[b] = hn[b];
     }
-    if (tokens) memcpy(tokens, ht.data(), ht.size() * sizeof(int32_t));
+    if (tokens) memcpy(tokens, ht, (size_t)B * (g.k_max + 1) * sizeof(int32_t));
     c->state = ST_READY;
     (void)M;
     return HIVIS_OK;
@@ -928,12 +950,12 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     if ((rc = dev_alloc(c, &c->row_tok, R))) return rc;
     if ((rc = dev_alloc(c, &c->drafts, (size_t)B * g.k_max))) return rc;
     if ((rc = dev_alloc(c, &c->ttok, (size_t)B * (g.k_max + 1)))) return rc;
-    if ((rc = dev_alloc(c, &c->nacc, B))) return rc;
-    if ((rc = dev_alloc(c, &c->out_tok, (size_t)B * (g.k_max + 1)))) return rc;
+    // accepted counts and emitted tokens share one block, so one device-to-host copy into pinned memory returns both
+    if ((rc = dev_alloc(c, &c->nacc, (size_t)B + (size_t)B * (g.k_max + 1)))) return rc;
+    c->out_tok = c->nacc + B;
+    HIP_TRY(c, hipHostMalloc((void**)&c->h_result, ((size_t)B + (size_t)B * (g.k_max + 1) + 1) * sizeof(int32_t), hipHostMallocDefault));
     if ((rc = dev_alloc(c, &c->next_tok, (size_t)B * (g.k_max + 1)))) return rc;
     c->h_tlen.assign(B, 0); c->h_dlen.assign(B, 0);
-    HIP_TRY(c, hipEventCreate(&c->ev0));
-    HIP_TRY(c, hipEventCreate(&c->ev1));
     if ((rc = fused_setup<WT>(c))) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return HIVIS_OK;
@@ -990,8 +1012,8 @@ int hivis_destroy(hivis_ctx* c) {
     (void)hipStreamSynchronize(c->stream);
     for (void* p : c->allocs) (void)hipFree(p);
     for (auto& kv : c->programs) delete kv.second.host;
-    if (c->ev0) (void)hipEventDestroy(c->ev0);
-    if (c->ev1) (void)hipEventDestroy(c->ev1);
+    for (hipEvent_t e : c->pev) (void)hipEventDestroy(e);
+    if (c->h_result) (void)hipHostFree(c->h_result);
     for (hipEvent_t e : c->kev) (void)hipEventDestroy(e);
     delete c;
     return HIVIS_OK;
@@ -1120,7 +1142,7 @@ int hivis_timing(hivis_ctx* c, int32_t enable) {
 
 int hivis_kernel_timing(hivis_ctx* c, int32_t gemm_kind) {
     if (!c || gemm_kind < -1 || gemm_kind > 5) return HIVIS_EINVAL;
-    c->ktime_epi = gemm_kind; c->kms = 0; c->klaunches = 0; c->kev_used = 0;
+    c->ktime_epi = gemm_kind; c->kms = 0; c->klaunches = 0; c->kev_used = 0; c->ktime_seen = 0;
     return HIVIS_OK;
 }
 
@@ -1135,6 +1157,7 @@ int hivis_kernel_ms(hivis_ctx* c, double* total_ms, int64_t* launches, double* b
 
 int hivis_phase_ms(hivis_ctx* c, int32_t phase, double* total_ms, int64_t* calls) {
     if (!c || phase < 0 || phase > 3) return HIVIS_EINVAL;
+    if (c->pev_used) { HIP_TRY(c, hipStreamSynchronize(c->stream)); resolve_phase_events(c); }
     if (total_ms) *total_ms = c->phase_ms[phase];
     if (calls) *calls = c->phase_calls[phase];
     c->phase_ms[phase] = 0; c->phase_calls[phase] = 0;

@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 GEMM_GATEUP = 4      # kind id of the fused gate|up GEMM (+RMSNorm prologue, SiLU*up epilogue): the kernel with the most bytes
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/): filled in from the
 # committed counter runs; None where no counter run exists for the workload.
-TRAFFIC_BYTES_PER_LAUNCH = {"C2": 182.4e6}     # profiles/gateup_gemm_C2_hbm_counters.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) per launch
+TRAFFIC_BYTES_PER_LAUNCH = {"C2": 181.7e6}     # profiles/gateup_gemm_C2_hbm_counters.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) per launch
 PAPER_TAU = {"C2": 5.37, "C3": 5.06, "C4": 4.39, "C5": 5.15}    # Table 2, T=0 averages (tree drafting, A800): context only
 
 
@@ -199,7 +199,7 @@ def main():
     k_gbs = k_bytes / (k_us * 1e-6) / 1e9 if k_launches else 0.0
     out["roofline"] = {"bound": "hbm",
                        "kernel": "phase_kernel<bf16, GEMM, gate|up>: fused RMSNorm + [d x 2F] weight stream + SiLU*up of the verify pass "
-                                 "(largest share of bytes and of time); HIP events recorded around every 8th launch on the library's stream (timing every launch idles the queue ~8 us per pair and slowed the pass by 7%)",
+                                 "(largest share of bytes and of time); HIP start/stop events attached to every 8th launch on the library's stream (hipExtLaunchKernel: the kernel's own begin/end timestamps, no marker packets in the queue)",
                        "achieved": k_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k_gbs / HBM_PEAK_GBS,
                        "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.config), "algorithmic_bytes_per_launch": k_bytes,
                        "avg_launch_us": k_us, "launches_timed": k_launches}

@@ -153,10 +153,10 @@ int hivis_get_tokens(hivis_ctx *ctx, int32_t *drafts, int32_t *target_tokens);
 int hivis_timing(hivis_ctx *ctx, int32_t enable);
 int hivis_phase_ms(hivis_ctx *ctx, int32_t phase, double *total_ms, int64_t *calls);
 
-/* Kernel-level timing of the verify pass's weight-streaming GEMM launches of one kind, with HIP events recorded on
- * the context's stream directly around every 8th such launch (an event pair leaves the queue idle for several
- * microseconds, so timing every launch would slow the pass it measures; the launches of one kind are alike across
- * layers).  Resolved at the next hivis_accept.  gemm_kind: 1 = O / down
+/* Kernel-level timing of the verify pass's weight-streaming GEMM launches of one kind, with a pair of HIP events
+ * attached to the dispatch itself (hipExtLaunchKernel's start/stop events: they read the kernel's own begin and end
+ * timestamps, so no marker packets sit in the queue around it).  Every 8th such launch is timed (the launches of
+ * one kind are alike across layers).  Resolved at the next hivis_accept.  gemm_kind: 1 = O / down
  * projection (+ residual), 3 = fused QKV (+ RMSNorm, RoPE, cache append), 4 = fused gate|up (+ RMSNorm, SiLU*up),
  * 5 = LM head (+ greedy candidates); -1 switches it off.  hivis_kernel_ms returns and clears the accumulated
  * milliseconds and launch count, and the algorithmic bytes of one such launch (its weight matrix, read once). */

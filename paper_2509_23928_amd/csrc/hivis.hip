@@ -4,6 +4,7 @@
 #include "hivis_kernels.h"
 #include "hivis_fused.h"
 
+#include <hip/hip_ext.h>
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
@@ -481,13 +482,19 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             else if (ph.type == PH_GEMM && ph.epi != FEPI_LOGITS) grid = std::min(grid, ph.N / 16);
             PassParams ppl = pp;
             if (do_prof) { ppl.prof2 = pp.prof2 + (size_t)p * 8; if (p >= pg.n / 2 && p < pg.n / 2 + 8) ppl.prof3 = c->prof + 4096 * 11 + (size_t)(p - pg.n / 2) * 4096; }
-#define HIVIS_LAUNCH(TY, EP) do { if (single) hipLaunchKernelGGL((phase_kernel<WT, TY, EP, true>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, ppl); \
-                                  else hipLaunchKernelGGL((phase_kernel<WT, TY, EP, false>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, ppl); } while (0)
+            // kev0/kev1 (null unless this launch is timed) are attached to the dispatch itself: they read the kernel's own
+            // start and end timestamps, with no marker packets before or after it in the queue
+#define HIVIS_LAUNCH(TY, EP) do { if (single) hipExtLaunchKernelGGL((phase_kernel<WT, TY, EP, true>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, kev0, kev1, 0, ph, ppl); \
+                                  else hipExtLaunchKernelGGL((phase_kernel<WT, TY, EP, false>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, kev0, kev1, 0, ph, ppl); } while (0)
             const bool single = ph.type == PH_GEMM && ph.epi != FEPI_LOGITS && ph.epi != FEPI_SILU && ph.epi != FEPI_QKV && ph.N / 16 <= grid;   // one tile per workgroup at most
-            const bool ktimed = kind == PROG_VERIFY && ph.type == PH_GEMM && ph.epi == c->ktime_epi && (c->ktime_seen++ % c->ktime_stride) == 0;
+            const bool kmatch = kind == PROG_VERIFY && ph.type == PH_GEMM && ph.epi == c->ktime_epi;
+            const int64_t kseq = kmatch ? c->ktime_seen++ : 0;
+            const bool ktimed = kmatch && (kseq % c->ktime_stride) == 0;
+            hipEvent_t kev0 = nullptr, kev1 = nullptr;
             if (ktimed) {
                 if (c->kev_used + 2 > c->kev.size()) { hipEvent_t e0, e1; HIP_TRY(c, hipEventCreate(&e0)); HIP_TRY(c, hipEventCreate(&e1)); c->kev.push_back(e0); c->kev.push_back(e1); }
-                HIP_TRY(c, hipEventRecord(c->kev[c->kev_used], c->stream));
+                kev0 = c->kev[c->kev_used]; kev1 = c->kev[c->kev_used + 1];
+                c->kev_used += 2;
                 c->kbytes = (double)ph.K * ph.N * c->esize;
             }
             switch (ph.type) {
@@ -508,7 +515,6 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             default: HIVIS_LAUNCH(PH_ARGMAX, 0); break;
             }
 #undef HIVIS_LAUNCH
-            if (ktimed) { HIP_TRY(c, hipEventRecord(c->kev[c->kev_used + 1], c->stream)); c->kev_used += 2; }
         }
         HIP_TRY(c, hipGetLastError());
         if (do_prof) {

@@ -234,6 +234,33 @@ def test_persistent_mode_matches_oracle():
     print("persistent mode max error / tolerance:", sbs.max_err)
 
 
+def test_qwen_vocab_lm_head_many_tile_groups():
+    # V = 152064 (the Qwen2.5-VL-shaped workload): 9504 LM-head tiles, 37-38 per workgroup = 5 tile groups with the greedy
+    # candidate carried across groups; narrow d keeps the oracle quick
+    cfg = small_bf16(vocab=152064, d=512, n_q_heads=4, n_kv_heads=2, ffn=1376, K=6, n_vis=60, n_text=24, rope_theta=1e6, rms_eps=1e-6)
+    sbs = run_generic(cfg, 31, 2, plant=(4,))
+    print("V=152064 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+
+
+def test_qwen_width_ffn_two_layer_slice():
+    # Qwen2.5-VL-7B widths without the vocabulary: d 3584, 28/4 heads of 128, F 18944 (gate|up 2368 tiles = two tile groups per
+    # workgroup; down projection K = 18944 = 9 full passes + a ragged one), K = 6 -> 7 rows
+    cfg = synth.get_config("C4").scaled(n_layers=2, vocab=4096, n_vis=130, n_text=50, gen_tokens=0, gen_cycles=2)
+    sbs = run_generic(cfg, 32, 1, plant=(3,))
+    print("Qwen-width 2-layer max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+
+
+def test_13b_width_batch4_k7_thirty_two_rows():
+    # LLaVA-1.5-13B widths (d 5120, 40 heads, F 13824), batch 4, K = 7: 32 verify rows, the path for more rows than one MFMA tile
+    cfg = synth.get_config("C5").scaled(n_layers=2, vocab=4096, n_vis=96, n_text=40, gen_tokens=0, gen_cycles=2)
+    w, vis, ids, hv = make(cfg, 33)
+    sbs = SideBySide(cfg, w, hv, vis, ids)
+    sbs.cycle(cfg.K)
+    sbs.cycle(cfg.K)
+    hv.close()
+    print("13B-width batch-4 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+
+
 def test_full_width_7b_layers_two_layer_slice():
     """LLaVA-1.5-7B widths (d 4096, 32 heads, F 11008, V 32000, 576 + 64 rows, K 5) with 2 of the 32 layers: the launch
     configuration bench.py times (same tile groups, K passes, LM-head tiling), against the oracle on every logit."""

@@ -221,6 +221,30 @@ int attention(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int*
     return HIVIS_OK;
 }
 
+AttnShape fused_attn_shape(hivis_ctx* c, int nseq, int m, int offset, int maxL, int ldq, int* items_out);
+
+// Attention of nseq x m rows on the matrix cores, outside a phase program (prefill; passes with more rows than one MFMA
+// tile): the same workgroup routine as the verify pass (one item = one kv head x <= 8 (head,row) pairs, all visible
+// keys, no key split), launched once over all items.  Rows of sequence seq0 + s sit at positions base[seq0 + s] + offset + i.
+template <typename WT>
+int attention_rows_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int* base, int offset, int seq0, int nseq, int m,
+                        float* out, int ldo) {
+    const hivis_config& g = c->cfg;
+    int items = 0;
+    Phase ph{};
+    ph.type = PH_ATTN;
+    ph.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, ldq, &items);
+    ph.att.seq0 = seq0; ph.att.nsplit = 1;
+    ph.att_items = items;
+    ph.A = q; ph.kc = kv.k; ph.vc = kv.v; ph.maxL = kv.maxL; ph.base = base; ph.offset = offset;
+    ph.Y = out; ph.ldy = ldo; ph.ws = nullptr; ph.cnt = nullptr;
+    PassParams pp{};
+    pp.M = nseq * m; pp.nseq = nseq; pp.m = m; pp.d = g.d; pp.Hq = g.n_q_heads; pp.Hkv = g.n_kv_heads; pp.hd = g.head_dim; pp.F = g.ffn; pp.V = g.vocab;
+    hipLaunchKernelGGL((phase_kernel<WT, PH_ATTN, 0, false>), dim3(items), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp);
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
 // One decoder layer on M = nseq*m rows.  h: residual stream [M][d] (in place).  `pending` (may be null) is a delta
 // from the previous layer that has not been added to h yet; on return *pending_out is this layer's MLP output, still
 // to be added by the caller (the next layer's first norm, or a final norm/add, fuses that addition).
@@ -234,7 +258,8 @@ int layer_forward(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, co
     hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, pending, d, (const WT*)L.norm1, c->a, d, d, g.rms_eps);
     if (int rc = gemm<WT>(c, c->a, d, M, d, L.wqkv, nqkv, c->qkv, nqkv, EPI_STORE)) return rc;
     hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
-    if (int rc = attention<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, max_keys, c->att, qd)) return rc;
+    if (c->fused && std::is_same<KT, f16_t>::value) { if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd)) return rc; }
+    else if (int rc = attention<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, max_keys, c->att, qd)) return rc;
     if (int rc = gemm<WT>(c, c->att, qd, M, qd, L.wo, d, c->proj, d, EPI_STORE)) return rc;
     hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, (const float*)c->proj, d, (const WT*)L.norm2, c->a, d, d, g.rms_eps);
     if (int rc = gemm<WT>(c, c->a, d, M, d, L.wgu, 2 * F, c->gu, 2 * F, EPI_STORE)) return rc;
@@ -632,26 +657,6 @@ int tall_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
     return HIVIS_OK;
 }
 
-// Prefill attention of one sequence on the matrix cores: the same workgroup routine as the verify pass (one item =
-// one head x 8 consecutive rows, all visible keys, no key split), launched once over all items.
-template <typename WT>
-int prefill_attention_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int* base, int seq, int m, float* out, int ldo) {
-    const hivis_config& g = c->cfg;
-    int items = 0;
-    Phase ph{};
-    ph.type = PH_ATTN;
-    ph.att = fused_attn_shape(c, 1, m, 0, kv.maxL, ldq, &items);
-    ph.att.seq0 = seq; ph.att.nsplit = 1;
-    ph.att_items = items;
-    ph.A = q; ph.kc = kv.k; ph.vc = kv.v; ph.maxL = kv.maxL; ph.base = base; ph.offset = 0;
-    ph.Y = out; ph.ldy = ldo; ph.ws = nullptr; ph.cnt = nullptr;
-    PassParams pp{};
-    pp.M = m; pp.nseq = 1; pp.m = m; pp.d = g.d; pp.Hq = g.n_q_heads; pp.Hkv = g.n_kv_heads; pp.hd = g.head_dim; pp.F = g.ffn; pp.V = g.vocab;
-    hipLaunchKernelGGL((phase_kernel<WT, PH_ATTN, 0, false>), dim3(items), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp);
-    HIP_TRY(c, hipGetLastError());
-    return HIVIS_OK;
-}
-
 template <typename WT>
 int prefill_target_tall(hivis_ctx* c, int b, int v, int l) {
     typedef typename KVType<WT>::type KT;
@@ -666,7 +671,7 @@ int prefill_target_tall(hivis_ctx* c, int b, int v, int l) {
         hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, pending, d, (const WT*)L.norm1, c->pf_a, d, d, g.rms_eps);
         if (int rc = tall_gemm(c, c->pf_a, d, M, d, L.wqkv, nqkv, c->pf_qkv, nqkv)) return rc;
         hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M), dim3(256), 0, c->stream, c->pf_qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, (const int*)c->zeros, 0, b, M, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
-        if (c->fused) { if (int rc = prefill_attention_mfma<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, b, M, c->pf_att, qd)) return rc; }
+        if (c->fused) { if (int rc = attention_rows_mfma<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, c->pf_att, qd)) return rc; }
         else if (int rc = attention<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, M, c->pf_att, qd)) return rc;
         if (int rc = tall_gemm(c, c->pf_att, qd, M, qd, L.wo, d, c->pf_proj, d)) return rc;
         hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, (const float*)c->pf_proj, d, (const WT*)L.norm2, c->pf_a, d, d, g.rms_eps);

@@ -6,4 +6,5 @@ the HIP library.
 """
 from .model import (rmsnorm, rope, softmax_rows, attention, silu, KVCache, decoder_layer, lm_logits,
                     argmax_lowest, Target, Drafter)
-from .hivis import fuse, accept_length, HivisOracle, greedy_reference, top2_gap
+from .hivis import (fuse, accept_length, HivisOracle, greedy_reference, top2_gap, softmax_temperature, sample_inverse_cdf,
+                    speculative_accept, HivisSamplingOracle, sampling_reference)

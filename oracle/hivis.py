@@ -1,4 +1,5 @@
-"""CPU oracle, part 2: the HiViS draft-verify cycle at temperature 0 (float64, numpy).
+"""CPU oracle, part 2: the HiViS draft-verify cycle (float64, numpy): greedy (temperature 0)
+and, at the end of the file, with tokens drawn at a temperature T > 0 (speculative sampling).
 
 TEST INFRASTRUCTURE ONLY (see oracle/model.py).  Follows Algorithm 1 of the paper
 ("Residual-Aided Drafting and Verification Process") step by step, in its notation:
@@ -182,3 +183,114 @@ def top2_gap(logits):
     """Difference between the largest and second-largest logit of each row."""
     part = np.partition(np.asarray(logits, F64), -2, axis=-1)
     return part[..., -1] - part[..., -2]
+
+
+# ---- temperature sampling (speculative sampling) -------------------------------------------------
+# Section 2.1 of the paper describes the verification at T > 0 in words: the target accepts the
+# consecutive candidates that agree with its distribution, rejects the first mismatch and
+# everything after it, resamples the next token "accordingly", and samples from its own
+# distribution if every candidate was accepted.  The rule behind those words is the speculative
+# sampling rule of the works the section cites (Leviathan et al. 2023; Chen et al. 2023), restated
+# here: a candidate x drawn from the drafter's distribution q is accepted with probability
+# min(1, p(x) / q(x)); on the first rejection the replacement is drawn from the normalised
+# positive part of p - q.  With that rule every emitted token is distributed exactly as a sample
+# of the target alone (tests/test_oracle_sampling.py pins this).
+# The uniform random numbers are INPUTS (so that two implementations can be compared draw by draw).
+
+def softmax_temperature(logits, T):
+    """softmax(logits / T) along the last axis, float64."""
+    z = np.asarray(logits, F64) / float(T)
+    z = z - np.max(z, axis=-1, keepdims=True)
+    e = np.exp(z)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def sample_inverse_cdf(weights, u):
+    """Index drawn from non-negative weights (not necessarily normalised) by inversion: the
+    smallest j whose running sum exceeds u * total, for u in [0, 1).  If rounding leaves no such
+    j, the last index with a positive weight."""
+    w = np.asarray(weights, F64)
+    c = np.cumsum(w)
+    j = int(np.searchsorted(c, float(u) * c[-1], side="right"))
+    if j >= w.shape[0]:
+        j = int(np.max(np.nonzero(w > 0)[0]))
+    return j
+
+
+def speculative_accept(p, q, drafts, u_accept, u_resample):
+    """p: [K+1][V] target distributions after rows 0..K; q: [K][V] drafter distributions the
+    drafts were drawn from; drafts: [K].  Returns (n, token): the number of accepted drafts and
+    the token that follows them (replacement at the first rejection, or a sample of p[K])."""
+    K = len(drafts)
+    for i in range(K):
+        x = int(drafts[i])
+        if float(u_accept[i]) * q[i][x] < p[i][x]:          # u < min(1, p/q)
+            continue
+        resid = np.maximum(p[i] - q[i], 0.0)
+        if not np.any(resid > 0):                             # p == q everywhere: nothing to correct
+            resid = p[i]
+        return i, sample_inverse_cdf(resid, u_resample)
+    return K, sample_inverse_cdf(p[K], u_resample)
+
+
+class HivisSamplingOracle(HivisOracle):
+    """The same cycle with tokens drawn at temperature T instead of taken greedily.  The first
+    token after the prompt (prefill) stays the target's greedy token."""
+
+    def draft_sample(self, K, T, u, follow=None):
+        """K chain drafts, draft i drawn from softmax(logits_i / T) with uniform u[i].
+        Returns (tokens [K], logits [K][V]).  `follow` as in draft()."""
+        assert self.drafter.kv_len == self.l
+        f_prev = self.f_next
+        tokens, logits_all = [], []
+        for i in range(1, K + 1):
+            logits = self.target.logits(f_prev)
+            d_i = sample_inverse_cdf(softmax_temperature(logits, T), u[i - 1])
+            used = d_i if follow is None else int(follow[i - 1])
+            logits_all.append(logits)
+            tokens.append(used)
+            if i < K:
+                uu = fuse(f_prev, self.target.embed([used])[0], self.w["fuse_w"], self.rho(i))
+                f_prev = self.drafter.forward(uu[None, :], self.l + i - 1)[0]
+        return tokens, np.stack(logits_all)
+
+    def accept_sample(self, drafts, draft_logits, g, verify_logits, T, u_accept, u_resample, force=None):
+        """Stochastic acceptance, then the same roll-forward as accept()."""
+        p = softmax_temperature(verify_logits, T)
+        q = softmax_temperature(draft_logits, T)
+        n, tok = speculative_accept(p, q, drafts, u_accept, u_resample)
+        emitted = [int(x) for x in drafts[:n]] + [int(tok)]
+        if force is not None:
+            n, emitted = int(force[0]), [int(x) for x in force[1]]
+        self.target.truncate(self.v + self.l + n + 1)
+        self.drafter.truncate(self.l)
+        self.text = self.text + emitted
+        nxt = self.text[self.l + 1: self.l + n + 2]
+        self.f_next = self._refeed(g[: n + 1], nxt, self.l)
+        self.l += n + 1
+        return n, emitted
+
+    def cycle_sample(self, K, T, u_draft, u_accept, u_resample, follow_drafts=None, force=None):
+        """One draft-verify-accept round at temperature T."""
+        drafts, dlogits = self.draft_sample(K, T, u_draft, follow=follow_drafts)
+        g, vlogits, _ = self.verify(drafts)
+        n, emitted = self.accept_sample(drafts, dlogits, g, vlogits, T, u_accept, u_resample, force=force)
+        return {"drafts": drafts, "draft_logits": dlogits, "g": g, "verify_logits": vlogits, "n": n, "emitted": emitted}
+
+
+def sampling_reference(cfg, weights, vis_embeds, text_ids, n_tokens, T, u):
+    """Plain definition at T > 0: prefill the target (greedy first token, as prefill() does), then
+    decode one token at a time, each drawn from softmax(logits / T) with u[k]."""
+    tgt = Target(cfg, weights)
+    vis = np.asarray(vis_embeds, F64)
+    x = np.concatenate([vis, tgt.embed(text_ids)], axis=0)
+    f = tgt.forward(x, 0)[-1]
+    tokens = []
+    pos = x.shape[0]
+    for k in range(n_tokens):
+        logits = tgt.logits(f)
+        tok = int(argmax_lowest(logits)) if k == 0 else sample_inverse_cdf(softmax_temperature(logits, T), u[k])
+        tokens.append(tok)
+        f = tgt.forward(tgt.embed([tok]), pos)[0]
+        pos += 1
+    return tokens

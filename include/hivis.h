@@ -128,6 +128,26 @@ int hivis_verify(hivis_ctx *ctx);
  * Errors: ESTATE, EINVAL, EHIP. */
 int hivis_accept(hivis_ctx *ctx, int32_t *n_accepted, int32_t *tokens);
 
+/* ---- the same cycle at a temperature T > 0 (section 2.1: the accepted prefix is kept, the token after it is
+ * resampled, and if every candidate is accepted the target samples from its own distribution; the rule is the
+ * speculative sampling rule of the works that section cites).  The uniform random numbers are INPUTS, each in [0, 1).
+ * hivis_prefill's first token stays the target's greedy token in both modes. ---- */
+
+/* K serial drafter steps as hivis_draft, but draft i of sequence b is DRAWN from q_i = softmax(logits_i / T) by
+ * inversion with u[b][i-1]: the smallest token j whose running probability sum exceeds u.
+ *   u: [B][K] float32, host.   State READY -> DRAFTED.
+ * Errors: ESTATE, EINVAL (K, T <= 0, null or out-of-range u), ECAP. */
+int hivis_draft_sample(hivis_ctx *ctx, int32_t K, float temperature, const float *u);
+
+/* Stochastic acceptance after hivis_verify of drafts made by hivis_draft_sample with the same T.  With p_i =
+ * softmax(target logits of row i / T): draft i is accepted while u_accept[b][i] * q_i(x_i) < p_i(x_i); at the first
+ * rejection the next token is drawn with u_resample[b] from the normalised positive part of p_i - q_i (from p_i if
+ * it is empty); if all K are accepted it is drawn from p_K.  Then the same roll-forward as hivis_accept.
+ *   u_accept: [B][K] float32 host; u_resample: [B] float32 host; outputs as hivis_accept.  Synchronises.
+ * Errors: ESTATE (also: drafts were planted or drawn greedily, so q is unknown), EINVAL, EHIP. */
+int hivis_accept_sample(hivis_ctx *ctx, float temperature, const float *u_accept, const float *u_resample,
+                        int32_t *n_accepted, int32_t *tokens);
+
 /* ---- test / measurement hooks (all synchronise) ---- */
 
 /* which = 0: logits of the last verify, [B][K+1][vocab]; which = 1: logits of the last draft round,

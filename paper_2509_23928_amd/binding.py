@@ -59,6 +59,8 @@ def load_library(path=LIB_PATH):
         "hivis_set_drafts": (C.c_int, [P, P, I32]),
         "hivis_verify": (C.c_int, [P]),
         "hivis_accept": (C.c_int, [P, P, P]),
+        "hivis_draft_sample": (C.c_int, [P, I32, C.c_float, P]),
+        "hivis_accept_sample": (C.c_int, [P, C.c_float, P, P, P, P]),
         "hivis_get_logits": (C.c_int, [P, I32, P]),
         "hivis_get_hidden": (C.c_int, [P, I32, P]),
         "hivis_kv_lengths": (C.c_int, [P, P, P]),
@@ -79,7 +81,7 @@ def load_library(path=LIB_PATH):
 
 
 EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_set_drafts",
-                    "hivis_verify", "hivis_accept", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
+                    "hivis_verify", "hivis_accept", "hivis_draft_sample", "hivis_accept_sample", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
                     "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes",
                     "hivis_last_error", "hivis_version")
 
@@ -186,6 +188,21 @@ class Hivis:
         n = np.zeros(self.B, np.int32)
         t = np.zeros((self.B, self.k_max + 1), np.int32)
         self._check(self.lib.hivis_accept(self.ctx, _ptr(n), _ptr(t)))
+        return n, t
+
+    def draft_sample(self, K, temperature, u):
+        """u: [B][K] uniform numbers in [0, 1)."""
+        u = np.ascontiguousarray(u, dtype=np.float32).reshape(self.B, K)
+        self._check(self.lib.hivis_draft_sample(self.ctx, K, float(temperature), _ptr(u)))
+        self.K = K
+
+    def accept_sample(self, temperature, u_accept, u_resample):
+        """u_accept: [B][K], u_resample: [B].  Returns (n_accepted [B], tokens [B][k_max+1])."""
+        ua = np.ascontiguousarray(u_accept, dtype=np.float32).reshape(self.B, self.K)
+        ur = np.ascontiguousarray(u_resample, dtype=np.float32).reshape(self.B)
+        n = np.zeros(self.B, np.int32)
+        t = np.zeros((self.B, self.k_max + 1), np.int32)
+        self._check(self.lib.hivis_accept_sample(self.ctx, float(temperature), _ptr(ua), _ptr(ur), _ptr(n), _ptr(t)))
         return n, t
 
     # -- hooks -----------------------------------------------------------------------

@@ -64,6 +64,8 @@ struct hivis_ctx {
     float *logits_v = nullptr, *logits_d = nullptr, *logits_p = nullptr;
     int32_t *row_tok = nullptr, *drafts = nullptr, *ttok = nullptr, *nacc = nullptr, *out_tok = nullptr, *next_tok = nullptr;
     int32_t* h_result = nullptr;         // pinned host mirror of [nacc | out_tok | abort flag]
+    float *u_draft = nullptr, *u_acc = nullptr, *u_res = nullptr;   // uniform numbers of the sampling calls: [B][k_max], [B][k_max] (row stride K), [B]
+    float inv_temp = 1.0f; bool drafts_sampled = false;             // set by hivis_draft_sample; hivis_accept_sample needs the drafter's distributions
     void* vis = nullptr;        // staging for vis_embeds [B][max_vis][d]
     // whole-prompt prefill buffers (bf16 models): all v+l rows of one sequence per layer
     int pf_rows = 0;
@@ -306,7 +308,7 @@ int drafter_forward(hivis_ctx* c, const float* cat, int seq0, int nseq, int m, i
 
 
 // ---- persistent-kernel path --------------------------------------------------------------------
-enum { PROG_VERIFY = 0, PROG_DRAFT = 1, PROG_ROLL = 2 };
+enum { PROG_VERIFY = 0, PROG_DRAFT = 1, PROG_ROLL = 2, PROG_DRAFT_SAMPLE = 3 };
 
 template <typename WT>
 bool fused_rows_ok(int M) { return M <= WTraits<WT>::ROWS; }
@@ -402,7 +404,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
         P.push_back(lm);
         Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->ttok; am.o_sseq = g.k_max + 1; am.o_srow = 1; am.pm = lm.pm; am.pi = lm.pi; am.N = G;
         P.push_back(am);
-    } else if (kind == PROG_DRAFT) {
+    } else if (kind == PROG_DRAFT || kind == PROG_DRAFT_SAMPLE) {
         // cat: [B][2d] = drafter hidden f' | embedding of the token drafted from it; a fresh buffer per step
         float* cat = c->catD;
         for (int i = 1; i <= K; ++i) {
@@ -410,6 +412,9 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
             lm.Y = c->logits_d + (size_t)(i - 1) * B * V; lm.ldy = V; lm.pm = pool.take((size_t)B * G); lm.pi = (int*)pool.take((size_t)B * G);
             P.push_back(lm);
             Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->drafts + (i - 1); am.o_sseq = g.k_max; am.o_srow = 0; am.pm = lm.pm; am.pi = lm.pi; am.N = G;
+            if (kind == PROG_DRAFT_SAMPLE) {     // the token is drawn from softmax(logits / T) instead (uniforms [B][k_max], column i-1)
+                am.type = PH_SAMPLE; am.A = lm.Y; am.lda = V; am.u = c->u_draft; am.u_sseq = g.k_max; am.u_idx = i - 1;
+            }
             P.push_back(am);
             if (i < K) {
                 float* rope = pool.take((size_t)B * g.head_dim);
@@ -477,7 +482,7 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
     pp.phases = pg.dev; pp.nphases = pg.n;
     pp.M = nseq * m; pp.nseq = nseq; pp.m = m;
     pp.d = g.d; pp.Hq = g.n_q_heads; pp.Hkv = g.n_kv_heads; pp.hd = g.head_dim; pp.F = g.ffn; pp.V = g.vocab;
-    pp.eps = g.rms_eps; pp.theta = g.rope_theta;
+    pp.eps = g.rms_eps; pp.theta = g.rope_theta; pp.inv_temp = c->inv_temp;
     pp.bar = c->bar;
     pp.spin_limit = 1u << 22;
     { const char* fl = getenv("HIVIS_FLAGS"); pp.flags = fl ? atoi(fl) : 0; }
@@ -504,6 +509,7 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             else if (ph.type == PH_PREP) grid = std::min(grid, std::max(pp.M, (pp.M * g.head_dim / 2 + FUSED_NT - 1) / FUSED_NT));
             else if (ph.type == PH_NORM_ROWS) grid = std::min(grid, pp.M);
             else if (ph.type == PH_ARGMAX) grid = std::min(grid, (pp.M + FUSED_NW - 1) / FUSED_NW);
+            else if (ph.type == PH_SAMPLE) grid = std::min(grid, pp.M);
             else if (ph.type == PH_GEMM && ph.epi != FEPI_LOGITS) grid = std::min(grid, ph.N / 16);
             PassParams ppl = pp;
             if (do_prof) { ppl.prof2 = pp.prof2 + (size_t)p * 8; if (p >= pg.n / 2 && p < pg.n / 2 + 8) ppl.prof3 = c->prof + 4096 * 11 + (size_t)(p - pg.n / 2) * 4096; }
@@ -537,6 +543,7 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
             case PH_ATTN_MERGE: HIVIS_LAUNCH(PH_ATTN_MERGE, 0); break;
             case PH_PREP: HIVIS_LAUNCH(PH_PREP, 0); break;
             case PH_NORM_ROWS: HIVIS_LAUNCH(PH_NORM_ROWS, 0); break;
+            case PH_SAMPLE: HIVIS_LAUNCH(PH_SAMPLE, 0); break;
             default: HIVIS_LAUNCH(PH_ARGMAX, 0); break;
             }
 #undef HIVIS_LAUNCH
@@ -628,7 +635,7 @@ int fused_setup(hivis_ctx* c) {
                             (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADDVEC, true>,
                             (const void*)phase_kernel<WT, PH_ATTN, 0, false>, (const void*)phase_kernel<WT, PH_ATTN_MERGE, 0, false>,
                             (const void*)phase_kernel<WT, PH_PREP, 0, false>, (const void*)phase_kernel<WT, PH_NORM_ROWS, 0, false>,
-                            (const void*)phase_kernel<WT, PH_ARGMAX, 0, false>};
+                            (const void*)phase_kernel<WT, PH_ARGMAX, 0, false>, (const void*)phase_kernel<WT, PH_SAMPLE, 0, false>};
         for (const void* k : ks) HIP_TRY(c, hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
     }
     { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }
@@ -779,12 +786,12 @@ int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_
 }
 
 template <typename WT>
-int do_draft(hivis_ctx* c, int K) {
+int do_draft(hivis_ctx* c, int K, bool sample) {
     const hivis_config& g = c->cfg;
     const int B = g.batch, d = g.d, V = g.vocab;
     PhaseTimer pt(c, 1);
     if (c->fused && fused_rows_ok<WT>(B)) {
-        if (int rc = run_program<WT>(c, PROG_DRAFT, K, B, 1)) return rc;
+        if (int rc = run_program<WT>(c, sample ? PROG_DRAFT_SAMPLE : PROG_DRAFT, K, B, 1)) return rc;
         pt.stop();
         return HIVIS_OK;
     }
@@ -793,7 +800,8 @@ int do_draft(hivis_ctx* c, int K) {
     for (int i = 1; i <= K; ++i) {
         float* lg = c->logits_d + (size_t)(i - 1) * B * V;
         if (int rc = gemm<WT>(c, c->catD, 2 * d, B, d, c->lm_head, V, lg, V, EPI_STORE)) return rc;
-        hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)lg, V, c->drafts + (i - 1), g.k_max);
+        if (sample) hipLaunchKernelGGL(sample_rows_kernel, dim3(B), dim3(SAMPLE_NT), 0, c->stream, (const float*)lg, V, c->inv_temp, (const float*)(c->u_draft + (i - 1)), g.k_max, c->drafts + (i - 1), g.k_max);
+        else hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)lg, V, c->drafts + (i - 1), g.k_max);
         if (i < K) {
             hipLaunchKernelGGL((gather_rows_kernel<WT>), dim3(B), dim3(256), 0, c->stream, (const WT*)c->embed, (const int32_t*)(c->drafts + (i - 1)), g.k_max, c->catD + d, 2 * d, d);
             if (int rc = drafter_forward<WT>(c, c->catD, 0, B, 1, std::min(i, g.n_resid - 1), i - 1, max_keys + i, c->catD, 2 * d)) return rc;
@@ -829,12 +837,17 @@ int do_verify(hivis_ctx* c) {
 }
 
 template <typename WT>
-int do_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
+int do_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens, bool sample) {
     const hivis_config& g = c->cfg;
     const int B = g.batch, d = g.d, K = c->K, M = B * (K + 1);
     PhaseTimer pt(c, 3);
-    hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(64), 0, c->stream, (const int32_t*)c->drafts, (const int32_t*)c->ttok, g.k_max, K, c->text, c->text_stride,
-                       (const int*)c->dlen, c->tlen, c->nacc, c->out_tok, c->next_tok);
+    if (sample)
+        hipLaunchKernelGGL(accept_sample_kernel, dim3(B), dim3(ACCEPT_NT), 0, c->stream, (const int32_t*)c->drafts, (const float*)c->logits_v, (const float*)c->logits_d,
+                           B, g.vocab, g.k_max, K, c->inv_temp, (const float*)c->u_acc, (const float*)c->u_res, c->text, c->text_stride,
+                           (const int*)c->dlen, c->tlen, c->nacc, c->out_tok, c->next_tok);
+    else
+        hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(64), 0, c->stream, (const int32_t*)c->drafts, (const int32_t*)c->ttok, g.k_max, K, c->text, c->text_stride,
+                           (const int*)c->dlen, c->tlen, c->nacc, c->out_tok, c->next_tok);
     // roll-forward: K+1 rows per sequence [g_i ; Embed(token after row i)] + rho_0 through the drafter at positions
     // dlen..dlen+K; rows beyond n_b are computed but become dead (the drafter length advances by n_b+1 only).
     if (c->fused && fused_rows_ok<WT>(M)) {
@@ -961,6 +974,9 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     if ((rc = dev_alloc(c, &c->row_tok, R))) return rc;
     if ((rc = dev_alloc(c, &c->drafts, (size_t)B * g.k_max))) return rc;
     if ((rc = dev_alloc(c, &c->ttok, (size_t)B * (g.k_max + 1)))) return rc;
+    if ((rc = dev_alloc(c, &c->u_draft, (size_t)B * g.k_max))) return rc;
+    if ((rc = dev_alloc(c, &c->u_acc, (size_t)B * g.k_max))) return rc;
+    if ((rc = dev_alloc(c, &c->u_res, (size_t)B))) return rc;
     // accepted counts and emitted tokens share one block, so one device-to-host copy into pinned memory returns both
     if ((rc = dev_alloc(c, &c->nacc, (size_t)B + (size_t)B * (g.k_max + 1)))) return rc;
     c->out_tok = c->nacc + B;
@@ -1057,9 +1073,33 @@ int hivis_draft(hivis_ctx* c, int32_t K) {
     if (c->state != ST_READY) return fail(c, HIVIS_ESTATE, "hivis_draft needs a prefilled/accepted context");
     if (K < 1 || K > c->cfg.k_max) return fail(c, HIVIS_EINVAL, "K=%d outside [1,%d]", K, c->cfg.k_max);
     if (int rc = check_room(c, K)) return rc;
-    int rc = DISPATCH(c, do_draft, c, K);
+    int rc = DISPATCH(c, do_draft, c, K, false);
     if (rc) return rc;
-    c->K = K; c->state = ST_DRAFTED;
+    c->K = K; c->state = ST_DRAFTED; c->drafts_sampled = false;
+    return HIVIS_OK;
+}
+
+static int check_uniforms(hivis_ctx* c, const float* u, size_t n, const char* what) {
+    if (!u) return fail(c, HIVIS_EINVAL, "null %s", what);
+    for (size_t i = 0; i < n; ++i)
+        if (!(u[i] >= 0.0f && u[i] < 1.0f)) return fail(c, HIVIS_EINVAL, "%s[%zu] = %g outside [0, 1)", what, i, (double)u[i]);
+    return HIVIS_OK;
+}
+
+int hivis_draft_sample(hivis_ctx* c, int32_t K, float temperature, const float* u) {
+    if (!c) return HIVIS_EINVAL;
+    if (c->state != ST_READY) return fail(c, HIVIS_ESTATE, "hivis_draft_sample needs a prefilled/accepted context");
+    if (K < 1 || K > c->cfg.k_max) return fail(c, HIVIS_EINVAL, "K=%d outside [1,%d]", K, c->cfg.k_max);
+    if (!(temperature > 0.0f)) return fail(c, HIVIS_EINVAL, "temperature must be positive");
+    const int B = c->cfg.batch;
+    if (int rc = check_uniforms(c, u, (size_t)B * K, "u")) return rc;
+    if (int rc = check_room(c, K)) return rc;
+    for (int b = 0; b < B; ++b)
+        HIP_TRY(c, hipMemcpyAsync(c->u_draft + (size_t)b * c->cfg.k_max, u + (size_t)b * K, K * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    c->inv_temp = 1.0f / temperature;
+    int rc = DISPATCH(c, do_draft, c, K, true);
+    if (rc) return rc;
+    c->K = K; c->state = ST_DRAFTED; c->drafts_sampled = true;
     return HIVIS_OK;
 }
 
@@ -1073,7 +1113,7 @@ int hivis_set_drafts(hivis_ctx* c, const int32_t* tokens, int32_t K) {
     for (int b = 0; b < c->cfg.batch; ++b)
         HIP_TRY(c, hipMemcpyAsync(c->drafts + (size_t)b * c->cfg.k_max, tokens + (size_t)b * K, K * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    c->K = K; c->state = ST_DRAFTED;
+    c->K = K; c->state = ST_DRAFTED; c->drafts_sampled = false;
     return HIVIS_OK;
 }
 
@@ -1090,7 +1130,22 @@ int hivis_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
     if (!c) return HIVIS_EINVAL;
     if (c->state != ST_VERIFIED) return fail(c, HIVIS_ESTATE, "hivis_accept needs a verified context");
     if (!n_accepted || !tokens) return fail(c, HIVIS_EINVAL, "null output pointer");
-    return DISPATCH(c, do_accept, c, n_accepted, tokens);
+    return DISPATCH(c, do_accept, c, n_accepted, tokens, false);
+}
+
+int hivis_accept_sample(hivis_ctx* c, float temperature, const float* u_accept, const float* u_resample, int32_t* n_accepted, int32_t* tokens) {
+    if (!c) return HIVIS_EINVAL;
+    if (c->state != ST_VERIFIED) return fail(c, HIVIS_ESTATE, "hivis_accept_sample needs a verified context");
+    if (!c->drafts_sampled) return fail(c, HIVIS_ESTATE, "hivis_accept_sample needs drafts drawn by hivis_draft_sample (their distributions)");
+    if (!n_accepted || !tokens) return fail(c, HIVIS_EINVAL, "null output pointer");
+    if (!(temperature > 0.0f)) return fail(c, HIVIS_EINVAL, "temperature must be positive");
+    const int B = c->cfg.batch, K = c->K;
+    if (int rc = check_uniforms(c, u_accept, (size_t)B * K, "u_accept")) return rc;
+    if (int rc = check_uniforms(c, u_resample, (size_t)B, "u_resample")) return rc;
+    HIP_TRY(c, hipMemcpyAsync(c->u_acc, u_accept, (size_t)B * K * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->u_res, u_resample, (size_t)B * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    c->inv_temp = 1.0f / temperature;
+    return DISPATCH(c, do_accept, c, n_accepted, tokens, true);
 }
 
 int hivis_get_logits(hivis_ctx* c, int32_t which, float* out) {

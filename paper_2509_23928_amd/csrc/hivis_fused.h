@@ -22,7 +22,7 @@
 
 namespace hivis {
 
-enum { PH_GEMM = 0, PH_ATTN = 1, PH_ATTN_MERGE = 2, PH_PREP = 3, PH_NORM_ROWS = 4, PH_ARGMAX = 5 };
+enum { PH_GEMM = 0, PH_ATTN = 1, PH_ATTN_MERGE = 2, PH_PREP = 3, PH_NORM_ROWS = 4, PH_ARGMAX = 5, PH_SAMPLE = 6 };
 enum { PRO_PLAIN = 0, PRO_RMS = 1 };
 constexpr int FUSED_RMAX = 8;      // (head,row) pairs per attention work item in the persistent kernel
 enum { FEPI_STORE = 0, FEPI_ADD_TO = 1, FEPI_ADDVEC = 2, FEPI_QKV = 3, FEPI_SILU = 4, FEPI_LOGITS = 5 };
@@ -45,6 +45,7 @@ struct Phase {
     float* ws;                                     // ATTN: per-workgroup partials of the key splits
     int* cnt;                                      // ATTN: arrival counter per item (zero between launches)
     float* pm; int* pi;                            // LOGITS writes, ARGMAX reads: greedy candidates [row][workgroup]
+    const float* u; int u_sseq, u_idx;             // SAMPLE: uniform number of row (seq, i) = u[seq*u_sseq + u_idx]; logits rows in A (stride lda)
     const uint4* next_W; int next_K, next_N;       // GEMM: weights of the next GEMM phase of the program (prefetch), or null
 };
 
@@ -53,6 +54,7 @@ struct PassParams {
     int M, nseq, m;                 // rows of the pass = nseq * m
     int d, Hq, Hkv, hd, F, V;
     float eps, theta;
+    float inv_temp;                 // SAMPLE: 1 / temperature
     unsigned* bar;                  // [0] arrival counter (zeroed before launch), [1] abort flag
     unsigned spin_limit;
     int flags;                      // reserved for tuning experiments (unused)
@@ -1062,6 +1064,15 @@ __device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp,
                 if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
             }
             if ((threadIdx.x & 63) == 0) st_wt(&ph.tok_out[(row / pp.m) * ph.o_sseq + (row % pp.m) * ph.o_srow], min(max(bi, 0), pp.V - 1));
+        }
+        break;
+    case PH_SAMPLE:
+        // one workgroup per row: token drawn from softmax(logits / T) by inversion with the row's uniform number
+        for (int row = blockIdx.x; row < pp.M; row += gridDim.x) {
+            float* smf = lds; int* smi = reinterpret_cast<int*>(lds + 16);
+            const float u = ph.u[(row / pp.m) * ph.u_sseq + ph.u_idx];
+            const int tok = block_sample_softmax<FUSED_NT>(ph.A + (size_t)row * ph.lda, pp.V, pp.inv_temp, u, smf, smi);
+            if (threadIdx.x == 0) st_wt(&ph.tok_out[(row / pp.m) * ph.o_sseq + (row % pp.m) * ph.o_srow], tok);
         }
         break;
     }

@@ -819,6 +819,162 @@ __global__ __launch_bounds__(64) void accept_kernel(const int32_t* __restrict__ 
     if (lane == 0) { nacc[b] = n; tlen[b] += n + 1; }
 }
 
+// ------------------------------------------------------------------------------------------
+// Temperature sampling (section 2.1 at T > 0; the speculative sampling rule of the works it cites).
+// The uniform random numbers are inputs.  One workgroup of NT threads works on one row of V logits; thread t owns
+// the contiguous indices [t*C, (t+1)*C), C = ceil(V / NT), so every sum has one fixed order (bit-reproducible).
+// ------------------------------------------------------------------------------------------
+template <int NT>
+__device__ __forceinline__ float block_reduce_max(float v, float* sm) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = sm[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) r = fmaxf(r, sm[w]);
+    return r;
+}
+template <int NT>
+__device__ __forceinline__ int block_reduce_min_int(int v, int* sm) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int r = sm[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) r = min(r, sm[w]);
+    return r;
+}
+// exclusive prefix of the per-thread values in thread order; *total receives the sum of all
+template <int NT>
+__device__ __forceinline__ float block_exclusive_scan(float v, float* sm, float* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
+    }
+    __syncthreads();
+    if (lane == 63) sm[wave] = incl;
+    __syncthreads();
+    float base = 0.f, tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) { if (w < wave) base += sm[w]; tot += sm[w]; }
+    *total = tot;
+    return base + (incl - v);
+}
+
+// Index drawn by inversion from the non-negative weights wf(j), j in [0, V): the smallest j whose running sum
+// exceeds u * total; if rounding leaves none, the last index with a positive weight.  All threads return the index.
+template <int NT, typename WF>
+__device__ __forceinline__ int block_sample_inverse_cdf(WF wf, int V, float u, float* smf, int* smi) {
+    const int C = (V + NT - 1) / NT;
+    const int j0 = min((int)threadIdx.x * C, V), j1 = min(j0 + C, V);
+    float s = 0.f;
+    int last_pos = -1;
+    for (int j = j0; j < j1; ++j) { const float w = wf(j); s += w; if (w > 0.f) last_pos = j; }
+    float total;
+    const float base = block_exclusive_scan<NT>(s, smf, &total);
+    const float target = u * total;
+    int found = 0x7FFFFFFF;
+    if (base <= target) {
+        float run = base;
+        for (int j = j0; j < j1; ++j) { run += wf(j); if (run > target) { found = j; break; } }
+    }
+    found = block_reduce_min_int<NT>(found, smi);
+    if (found == 0x7FFFFFFF) found = -block_reduce_min_int<NT>(-last_pos, smi);     // maximum of last_pos
+    return min(max(found, 0), V - 1);
+}
+
+// softmax statistics of one row at inverse temperature it: maximum of x*it and the sum of exp(x*it - max)
+template <int NT>
+__device__ __forceinline__ void block_softmax_stats(const float* __restrict__ x, int V, float it, float* smf, float* mx, float* sum) {
+    float m = -INFINITY;
+    for (int j = threadIdx.x; j < V; j += NT) m = fmaxf(m, x[j] * it);
+    m = block_reduce_max<NT>(m, smf);
+    const int C = (V + NT - 1) / NT;
+    const int j0 = min((int)threadIdx.x * C, V), j1 = min(j0 + C, V);
+    float s = 0.f;
+    for (int j = j0; j < j1; ++j) s += expf(x[j] * it - m);
+    float total;
+    (void)block_exclusive_scan<NT>(s, smf, &total);
+    *mx = m; *sum = total;
+}
+
+// One token per row drawn from softmax(logits / T) with the row's uniform number.  One workgroup per row.
+template <int NT>
+__device__ __forceinline__ int block_sample_softmax(const float* __restrict__ x, int V, float it, float u, float* smf, int* smi) {
+    float m = -INFINITY;
+    for (int j = threadIdx.x; j < V; j += NT) m = fmaxf(m, x[j] * it);
+    m = block_reduce_max<NT>(m, smf);
+    return block_sample_inverse_cdf<NT>([&](int j) { return expf(x[j] * it - m); }, V, u, smf, smi);
+}
+constexpr int SAMPLE_NT = 512;
+__global__ __launch_bounds__(SAMPLE_NT) void sample_rows_kernel(const float* __restrict__ logits, int V, float inv_temp,
+                                                                const float* __restrict__ u, int u_stride,
+                                                                int32_t* __restrict__ out, int out_stride) {
+    __shared__ float smf[SAMPLE_NT / 64];
+    __shared__ int smi[SAMPLE_NT / 64];
+    const int row = blockIdx.x;
+    const int tok = block_sample_softmax<SAMPLE_NT>(logits + (size_t)row * V, V, inv_temp, u[(size_t)row * u_stride], smf, smi);
+    if (threadIdx.x == 0) out[(size_t)row * out_stride] = tok;
+}
+
+// Stochastic acceptance, one workgroup per sequence.  p_i = softmax(target logits of row i / T), q_i =
+// softmax(drafter logits of step i / T).  Draft i is accepted while u_acc[i] * q_i(x_i) < p_i(x_i); at the first
+// rejection the replacement is drawn (u_res) from the positive part of p_i - q_i (from p_i if that is empty); if all
+// K are accepted the extra token is drawn from p_K.  Outputs as accept_kernel.
+constexpr int ACCEPT_NT = 1024;
+__global__ __launch_bounds__(ACCEPT_NT) void accept_sample_kernel(const int32_t* __restrict__ drafts, const float* __restrict__ vlogits,
+                                                                  const float* __restrict__ dlogits, int B, int V, int kmax, int K,
+                                                                  float inv_temp, const float* __restrict__ u_acc,
+                                                                  const float* __restrict__ u_res, int32_t* __restrict__ text,
+                                                                  int text_stride, const int* __restrict__ dlen, int* __restrict__ tlen,
+                                                                  int32_t* __restrict__ nacc, int32_t* __restrict__ out_tokens,
+                                                                  int32_t* __restrict__ next_tok) {
+    __shared__ float smf[ACCEPT_NT / 64];
+    __shared__ int smi[ACCEPT_NT / 64];
+    const int b = blockIdx.x;
+    int n = K, tok = 0;
+    for (int i = 0; i < K; ++i) {
+        const float* lp = vlogits + ((size_t)b * (K + 1) + i) * V;
+        const float* lq = dlogits + ((size_t)i * B + b) * V;
+        const int x = min(max(drafts[b * kmax + i], 0), V - 1);
+        float mp, sp, mq, sq;
+        block_softmax_stats<ACCEPT_NT>(lp, V, inv_temp, smf, &mp, &sp);
+        block_softmax_stats<ACCEPT_NT>(lq, V, inv_temp, smf, &mq, &sq);
+        const float px = expf(lp[x] * inv_temp - mp) / sp, qx = expf(lq[x] * inv_temp - mq) / sq;
+        if (u_acc[b * K + i] * qx < px) continue;
+        // rejected: does p - q have a positive part at all?
+        const float isp = 1.0f / sp, isq = 1.0f / sq;
+        auto resid = [&](int j) { return fmaxf(expf(lp[j] * inv_temp - mp) * isp - expf(lq[j] * inv_temp - mq) * isq, 0.f); };
+        float any = 0.f;
+        for (int j = threadIdx.x; j < V; j += ACCEPT_NT) any = fmaxf(any, resid(j));
+        any = block_reduce_max<ACCEPT_NT>(any, smf);
+        if (any > 0.f) tok = block_sample_inverse_cdf<ACCEPT_NT>(resid, V, u_res[b], smf, smi);
+        else tok = block_sample_inverse_cdf<ACCEPT_NT>([&](int j) { return expf(lp[j] * inv_temp - mp); }, V, u_res[b], smf, smi);
+        n = i;
+        break;
+    }
+    if (n == K) tok = block_sample_softmax<ACCEPT_NT>(vlogits + ((size_t)b * (K + 1) + K) * V, V, inv_temp, u_res[b], smf, smi);
+    const int lane = threadIdx.x;
+    if (lane <= kmax) {
+        int t = -1;
+        if (lane < n) t = drafts[b * kmax + lane];
+        else if (lane == n) t = tok;
+        out_tokens[b * (kmax + 1) + lane] = t;
+        if (lane <= n) text[(size_t)b * text_stride + dlen[b] + 1 + lane] = t;
+        if (lane <= K) {
+            const int e = min(lane, n);
+            next_tok[b * (kmax + 1) + lane] = (e < n) ? drafts[b * kmax + e] : tok;
+        }
+    }
+    if (lane == 0) { nacc[b] = n; tlen[b] += n + 1; }
+}
+
 // After the re-feed: the drafter's pending hidden state is its output at row n_b; its cache keeps n_b+1 rows.
 __global__ void select_row_kernel(const float* __restrict__ dout, int m, const int32_t* __restrict__ nacc,
                                   float* __restrict__ fnext, int ldf, int* __restrict__ dlen, int d) {

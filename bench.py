@@ -32,17 +32,23 @@ TRAFFIC_BYTES_PER_LAUNCH = {"C2": 181.7e6}     # profiles/gateup_gemm_C2_hbm_cou
 PAPER_TAU = {"C2": 5.37, "C3": 5.06, "C4": 4.39, "C5": 5.15}    # Table 2, T=0 averages (tree drafting, A800): context only
 
 
-def run_step(hv, cfg, vis, ids, K):
-    """prefill + cycles until cfg.gen_tokens tokens (or cfg.gen_cycles cycles).  Returns (tokens, cycles, accepted)."""
+def run_step(hv, cfg, vis, ids, K, temperature=0.0, rng=None):
+    """prefill + cycles until cfg.gen_tokens tokens (or cfg.gen_cycles cycles).  Returns (tokens, cycles, accepted).
+    temperature > 0: the sampling calls, with uniforms from `rng` (not the headline configuration)."""
     first = hv.prefill(vis, ids)
     produced = np.ones(hv.B, np.int64)
     cycles = 0
     accepted = 0
     target = cfg.gen_tokens
     while True:
-        hv.draft(K)
-        hv.verify()
-        n, _ = hv.accept()
+        if temperature > 0.0:
+            hv.draft_sample(K, temperature, rng.random((hv.B, K), dtype=np.float32))
+            hv.verify()
+            n, _ = hv.accept_sample(temperature, rng.random((hv.B, K), dtype=np.float32), rng.random(hv.B, dtype=np.float32))
+        else:
+            hv.draft(K)
+            hv.verify()
+            n, _ = hv.accept()
         produced += n + 1
         accepted += int(n.sum())
         cycles += 1
@@ -103,6 +109,7 @@ def main():
     ap.add_argument("--config", default="C2")
     ap.add_argument("--layers", type=int, default=0, help="override the number of target layers (debug only; invalid as a result)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--temperature", type=float, default=0.0, help="> 0: time the temperature-sampling calls instead of the greedy ones (extra measurement, not the headline metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true", help="also run a plain 1 GiB device copy first (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -146,8 +153,9 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    rng = np.random.default_rng(args.seed + 12345)
     for _ in range(args.warmup):
-        run_step(hv, cfg, vis_dev, ids_dev, K)
+        run_step(hv, cfg, vis_dev, ids_dev, K, args.temperature, rng)
     hv.timing(True)
     hv.kernel_timing(GEMM_GATEUP)
     for ph in range(4):
@@ -156,7 +164,7 @@ def main():
     t0 = time.perf_counter()
     tokens = cycles = accepted = 0
     for _ in range(args.steps):
-        tk, cy, ac, _ = run_step(hv, cfg, vis_dev, ids_dev, K)
+        tk, cy, ac, _ = run_step(hv, cfg, vis_dev, ids_dev, K, args.temperature, rng)
         tokens += tk; cycles += cy; accepted += ac
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -188,7 +196,7 @@ def main():
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: {cfg.name} N={cfg.n_layers} d={cfg.d} Hq/Hkv={cfg.n_q_heads}/{cfg.n_kv_heads} F={cfg.ffn} V={cfg.vocab}, "
                                f"{cfg.n_vis} visual + {cfg.n_text} text rows, K={K} chain, {cfg.gen_tokens or cfg.gen_cycles * (K + 1)} generated tokens, batch {cfg.batch}, "
-                               "random-init weights (seeded)", "K": K, "batch": cfg.batch},
+                               "random-init weights (seeded)" + (f", temperature {args.temperature} sampling" if args.temperature > 0 else ""), "K": K, "batch": cfg.batch},
         "prefill_ms": prefill_ms, "draft_step_us": draft_us, "verify_us": verify_us, "accept_roll_us": accept_us,
         "cycle_us": K * draft_us + verify_us + accept_us,
         "draft_step_hbm_gbs": draft_gbs, "draft_step_frac_of_peak": draft_gbs / HBM_PEAK_GBS,

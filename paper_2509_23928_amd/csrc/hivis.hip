@@ -658,8 +658,15 @@ int tall_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
     const int kblks = K / 32, row_tiles = (M + 7) / 8, ntiles = N / 16;
     const size_t nfrag = (size_t)row_tiles * kblks * 64;
     hipLaunchKernelGGL(pack_afrag_kernel, dim3((unsigned)std::min<size_t>((nfrag + 255) / 256, 65535)), dim3(256), 0, c->stream, A, lda, M, kblks, c->pf_frag);
-    hipLaunchKernelGGL((gemm_tall_kernel<4, 4>), dim3((ntiles + 7) / 8, (row_tiles + 7) / 8), dim3(256), 0, c->stream,
-                       (const uint4*)c->pf_frag, row_tiles, kblks, Wp, ntiles, Y, ldy, M);
+    // LDS-tiled kernel: 64 real rows x 256 columns per workgroup when that still gives >= 2 workgroups per CU, else x 128
+    const int macro_rows = (row_tiles + 7) / 8;
+    if ((size_t)macro_rows * ((ntiles + 15) / 16) >= (size_t)2 * c->num_cu) {
+        hipLaunchKernelGGL((gemm_tall_lds_kernel<8>), dim3((ntiles + 15) / 16, macro_rows), dim3(256), 2 * 24 * 1024, c->stream,
+                           (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M);
+    } else {
+        hipLaunchKernelGGL((gemm_tall_lds_kernel<4>), dim3((ntiles + 7) / 8, macro_rows), dim3(256), 2 * 16 * 1024, c->stream,
+                           (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M);
+    }
     HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;
 }

@@ -330,64 +330,91 @@ __global__ void pack_afrag_kernel(const float* __restrict__ A, int lda, int M, i
     }
 }
 
-template <int RT, int CT>
-__global__ __launch_bounds__(256) void gemm_tall_kernel(const uint4* __restrict__ Af, int row_tiles, int kblks,
-                                                         const uint4* __restrict__ Wp, int ntiles, float* __restrict__ Y,
-                                                         int ldy, int M) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int rt0 = (blockIdx.y * 2 + (wave >> 1)) * RT;
-    const int ct0 = (blockIdx.x * 2 + (wave & 1)) * CT;
-    if (rt0 >= row_tiles || ct0 >= ntiles) return;
-    f32x4_t acc[RT][CT];
+// Tall GEMM of the prefill: a workgroup of 2 x 2 wavefronts computes 8 row tiles x 2*CTW column tiles (64 real rows x
+// 32*CTW columns); each wavefront owns 4 x CTW MFMA tiles.  Per K block the workgroup copies the 8 A blocks and 2*CTW B blocks
+// (1 KiB each, already in fragment order) from global memory to LDS once, and the wavefronts read their fragments with
+// 128-bit LDS reads (lane-contiguous: conflict-free), so the L1 sees each block once per workgroup instead of once per
+// wavefront (a register-only version, 8 fragment loads per 16 MFMAs per wavefront, was bound by L1 fill bandwidth).
+// Two LDS stages; the global loads of K block k+1 are in flight while block k is multiplied; one LDS-only barrier per block.
+typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
+template <int CTW>
+__global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __restrict__ Af, int row_tiles, int kblks,
+                                                             const v4u_t* __restrict__ Wp, int ntiles, float* __restrict__ Y,
+                                                             int ldy, int M) {
+    constexpr int RTW = 4;                       // row tiles per wavefront
+    constexpr int NA = 2 * RTW, NB = 2 * CTW;    // A / B blocks per K block and workgroup
+    constexpr int NBLK = NA + NB;
+    constexpr int PER_WAVE = NBLK / 4;           // blocks each wavefront copies per K block
+    static_assert(NBLK % 4 == 0, "blocks are dealt evenly to the 4 wavefronts");
+    extern __shared__ __align__(16) v4u_t tall_lds[];      // [2 stages][NBLK][64]
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wr = wave >> 1, wc = wave & 1;
+    const int rt_wg = blockIdx.y * NA, ct_wg = blockIdx.x * NB;
+    // the blocks this wavefront copies: block id b = wave + 4 i; b < NA is an A block (row tile rt_wg + b), else a B block
+    const v4u_t* src[PER_WAVE];
 #pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int c = 0; c < CT; ++c) acc[r][c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    // fragments out of range are replaced by in-range ones (clamped tile index); their results are never stored
-    const uint4* ap[RT]; const uint4* bp[CT];
-#pragma unroll
-    for (int r = 0; r < RT; ++r) ap[r] = Af + (size_t)min(rt0 + r, row_tiles - 1) * kblks * 64 + lane;
-#pragma unroll
-    for (int c = 0; c < CT; ++c) bp[c] = Wp + (size_t)min(ct0 + c, ntiles - 1) * kblks * 64 + lane;
-    uint4 a[2][RT], b[2][CT];
-#pragma unroll
-    for (int r = 0; r < RT; ++r) a[0][r] = ap[r][0];
-#pragma unroll
-    for (int c = 0; c < CT; ++c) b[0][c] = bp[c][0];
-    for (int kb = 0; kb < kblks; kb += 2) {
-        // two K blocks per iteration so that the double buffer has static indices
-        if (kb + 1 < kblks) {
-#pragma unroll
-            for (int r = 0; r < RT; ++r) a[1][r] = ap[r][(size_t)(kb + 1) * 64];
-#pragma unroll
-            for (int c = 0; c < CT; ++c) b[1][c] = bp[c][(size_t)(kb + 1) * 64];
-        }
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-#pragma unroll
-            for (int c = 0; c < CT; ++c) mfma_block(acc[r][c], __builtin_bit_cast(bf16x8_t, a[0][r]), b[0][c]);
-        if (kb + 1 < kblks) {
-            if (kb + 2 < kblks) {
-#pragma unroll
-                for (int r = 0; r < RT; ++r) a[0][r] = ap[r][(size_t)(kb + 2) * 64];
-#pragma unroll
-                for (int c = 0; c < CT; ++c) b[0][c] = bp[c][(size_t)(kb + 2) * 64];
-            }
-#pragma unroll
-            for (int r = 0; r < RT; ++r)
-#pragma unroll
-                for (int c = 0; c < CT; ++c) mfma_block(acc[r][c], __builtin_bit_cast(bf16x8_t, a[1][r]), b[1][c]);
-        }
+    for (int i = 0; i < PER_WAVE; ++i) {
+        const int b = wave + 4 * i;
+        // out-of-range tiles are replaced by in-range ones (clamped index); their results are never stored
+        src[i] = (b < NA) ? Af + (size_t)min(rt_wg + b, row_tiles - 1) * kblks * 64 + lane
+                          : Wp + (size_t)min(ct_wg + (b - NA), ntiles - 1) * kblks * 64 + lane;
     }
+    f32x4_t acc[RTW][CTW];
+#pragma unroll
+    for (int r = 0; r < RTW; ++r)
+#pragma unroll
+        for (int c = 0; c < CTW; ++c) acc[r][c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    // Global loads run TWO K blocks ahead of the multiplication (one block is ~0.4 us of MFMA work, less than an L2 round
+    // trip): block kb+1 waits in registers `sa`/`sb` while block kb+2 is in flight in the other set.
+    v4u_t sa[PER_WAVE], sb[PER_WAVE];
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) sa[i] = src[i][0];
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) tall_lds[(size_t)(wave + 4 * i) * 64 + lane] = sa[i];
+    if (kblks > 1) {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) sa[i] = src[i][(size_t)64];
+    }
+    if (kblks > 2) {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) sb[i] = src[i][(size_t)2 * 64];
+    }
+    lds_barrier();
+    // one K block: multiply block kb_ from its LDS stage, park block kb_+1 (registers s_) in the other stage, request kb_+3
+#define HIVIS_TALL_STEP(kb_, s_)                                                                                   \
+    {                                                                                                              \
+        const v4u_t* cur = tall_lds + (size_t)((kb_) & 1) * NBLK * 64;                                             \
+        v4u_t* nxt = tall_lds + (size_t)(((kb_) + 1) & 1) * NBLK * 64;                                             \
+        v4u_t a[RTW], b[CTW];                                                                                      \
+        _Pragma("unroll") for (int r = 0; r < RTW; ++r) a[r] = cur[(size_t)(wr * RTW + r) * 64 + lane];            \
+        _Pragma("unroll") for (int c = 0; c < CTW; ++c) b[c] = cur[(size_t)(NA + wc * CTW + c) * 64 + lane];       \
+        _Pragma("unroll") for (int r = 0; r < RTW; ++r)                                                            \
+            _Pragma("unroll") for (int c = 0; c < CTW; ++c)                                                        \
+                acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[r]), __builtin_bit_cast(bf16x8_t, b[c]), acc[r][c], 0, 0, 0); \
+        if ((kb_) + 1 < kblks) {                                                                                   \
+            _Pragma("unroll") for (int i = 0; i < PER_WAVE; ++i) nxt[(size_t)(wave + 4 * i) * 64 + lane] = s_[i];  \
+            if ((kb_) + 3 < kblks) {                                                                               \
+                _Pragma("unroll") for (int i = 0; i < PER_WAVE; ++i) s_[i] = src[i][(size_t)((kb_) + 3) * 64];     \
+            }                                                                                                      \
+        }                                                                                                          \
+        lds_barrier();                                                                                             \
+    }
+    for (int kb = 0; kb < kblks; kb += 2) {
+        HIVIS_TALL_STEP(kb, sa)
+        if (kb + 1 < kblks) HIVIS_TALL_STEP(kb + 1, sb)
+    }
+#undef HIVIS_TALL_STEP
     const int j = lane & 15, a4 = lane >> 4;
 #pragma unroll
-    for (int r = 0; r < RT; ++r) {
-        if (rt0 + r >= row_tiles) continue;
-        const int row = (rt0 + r) * 8 + 2 * a4;
+    for (int r = 0; r < RTW; ++r) {
+        const int rt = rt_wg + wr * RTW + r;
+        if (rt >= row_tiles) continue;
+        const int row = rt * 8 + 2 * a4;
 #pragma unroll
-        for (int c = 0; c < CT; ++c) {
-            if (ct0 + c >= ntiles) continue;
-            const int col = (ct0 + c) * 16 + j;
+        for (int c = 0; c < CTW; ++c) {
+            const int ct = ct_wg + wc * CTW + c;
+            if (ct >= ntiles) continue;
+            const int col = ct * 16 + j;
             if (row < M) Y[(size_t)row * ldy + col] = acc[r][c][0] + acc[r][c][2];
             if (row + 1 < M) Y[(size_t)(row + 1) * ldy + col] = acc[r][c][1] + acc[r][c][3];
         }

@@ -485,7 +485,6 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
     pp.eps = g.rms_eps; pp.theta = g.rope_theta; pp.inv_temp = c->inv_temp;
     pp.bar = c->bar;
     pp.spin_limit = 1u << 22;
-    { const char* fl = getenv("HIVIS_FLAGS"); pp.flags = fl ? atoi(fl) : 0; }
     const bool do_prof = c->prof && kind == PROG_VERIFY && c->prof_left > 0;
     pp.prof = do_prof ? c->prof : nullptr;
     pp.prof2 = do_prof ? c->prof + 4096 * 3 : nullptr;

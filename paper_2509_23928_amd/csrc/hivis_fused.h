@@ -57,7 +57,6 @@ struct PassParams {
     float inv_temp;                 // SAMPLE: 1 / temperature
     unsigned* bar;                  // [0] arrival counter (zeroed before launch), [1] abort flag
     unsigned spin_limit;
-    int flags;                      // reserved for tuning experiments (unused)
     unsigned long long* prof3;      // optional [grid][4] per-workgroup entry time, exit time, hardware id of one launch (one launch per phase only)
     unsigned long long* prof2;      // optional [nphases][8] finer timestamps inside GEMM phases (workgroup 0)
     unsigned long long* prof;       // optional [nphases][3] timestamps of workgroup 0 (phase start, phase end, barrier end), 100 MHz

@@ -848,8 +848,8 @@ __global__ __launch_bounds__(64) void accept_kernel(const int32_t* __restrict__ 
 
 // ------------------------------------------------------------------------------------------
 // Temperature sampling (section 2.1 at T > 0; the speculative sampling rule of the works it cites).
-// The uniform random numbers are inputs.  One workgroup of NT threads works on one row of V logits; thread t owns
-// the contiguous indices [t*C, (t+1)*C), C = ceil(V / NT), so every sum has one fixed order (bit-reproducible).
+// The uniform random numbers are inputs.  One workgroup of NT threads works on one row of V logits; every sum has
+// one fixed order (bit-reproducible).
 // ------------------------------------------------------------------------------------------
 template <int NT>
 __device__ __forceinline__ float block_reduce_max(float v, float* sm) {
@@ -861,6 +861,19 @@ __device__ __forceinline__ float block_reduce_max(float v, float* sm) {
 #pragma unroll
     for (int w = 1; w < NT / 64; ++w) r = fmaxf(r, sm[w]);
     return r;
+}
+// maximum of x[j] * it over one row, 8 independent loads per trip
+template <int NT>
+__device__ __forceinline__ float block_row_max(const float* __restrict__ x, int V, float it, float* sm) {
+    float m = -INFINITY;
+    for (int j = threadIdx.x; j < V; j += NT * 8) {
+        float x8[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) x8[k] = x[min(j + NT * k, V - 1)];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) m = fmaxf(m, x8[k] * it);       // clamped duplicates of the last element do not change a maximum
+    }
+    return block_reduce_max<NT>(m, sm);
 }
 template <int NT>
 __device__ __forceinline__ int block_reduce_min_int(int v, int* sm) {
@@ -874,69 +887,97 @@ __device__ __forceinline__ int block_reduce_min_int(int v, int* sm) {
     for (int w = 1; w < NT / 64; ++w) r = min(r, sm[w]);
     return r;
 }
-// exclusive prefix of the per-thread values in thread order; *total receives the sum of all
-template <int NT>
-__device__ __forceinline__ float block_exclusive_scan(float v, float* sm, float* total) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float incl = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const float up = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += up;
-    }
-    __syncthreads();
-    if (lane == 63) sm[wave] = incl;
-    __syncthreads();
-    float base = 0.f, tot = 0.f;
-#pragma unroll
-    for (int w = 0; w < NT / 64; ++w) { if (w < wave) base += sm[w]; tot += sm[w]; }
-    *total = tot;
-    return base + (incl - v);
-}
-
 // Index drawn by inversion from the non-negative weights wf(j), j in [0, V): the smallest j whose running sum
 // exceeds u * total; if rounding leaves none, the last index with a positive weight.  All threads return the index.
+// Wavefront w owns the contiguous segment [w*L, (w+1)*L) (L a multiple of 64) and reads it 64 consecutive elements
+// at a time (coalesced).  Pass A: segment totals.  Pass B: the wavefront whose segment contains the target walks it
+// again, 64 elements per step, with an in-order wavefront scan, and takes the first lane whose prefix exceeds it.
 template <int NT, typename WF>
 __device__ __forceinline__ int block_sample_inverse_cdf(WF wf, int V, float u, float* smf, int* smi) {
-    const int C = (V + NT - 1) / NT;
-    const int j0 = min((int)threadIdx.x * C, V), j1 = min(j0 + C, V);
-    float s = 0.f;
+    constexpr int NWV = NT / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int L = ((V + NWV * 64 - 1) / (NWV * 64)) * 64;
+    const int s0 = min(wave * L, V), s1 = min(s0 + L, V);
+    float part = 0.f;
     int last_pos = -1;
-    for (int j = j0; j < j1; ++j) { const float w = wf(j); s += w; if (w > 0.f) last_pos = j; }
-    float total;
-    const float base = block_exclusive_scan<NT>(s, smf, &total);
+    // (8 independent loads per trip: a one-load-per-trip loop pays a memory round trip per element)
+    for (int j = s0 + lane; j < s1; j += 64 * 8) {
+        float w8[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w8[k] = wf(min(j + 64 * k, V - 1));
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (j + 64 * k < s1) { part += w8[k]; if (w8[k] > 0.f) last_pos = j + 64 * k; }
+        }
+    }
+    const float tw = wave_sum(part);
+    __syncthreads();
+    if (lane == 0) smf[wave] = tw;
+    __syncthreads();
+    float base = 0.f, total = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) { if (w < wave) base += smf[w]; total += smf[w]; }
     const float target = u * total;
+    int wsel = -1;
+    {
+        float run = 0.f;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) { run += smf[w]; if (wsel < 0 && run > target) wsel = w; }
+    }
     int found = 0x7FFFFFFF;
-    if (base <= target) {
+    if (wave == wsel) {
         float run = base;
-        for (int j = j0; j < j1; ++j) { run += wf(j); if (run > target) { found = j; break; } }
+        for (int r = s0; r < s1; r += 64) {
+            const int j = r + lane;
+            const float w = (j < s1) ? wf(j) : 0.f;
+            float incl = w;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const float up = __shfl_up(incl, o, 64);
+                if (lane >= o) incl += up;
+            }
+            const unsigned long long hit = __ballot(run + incl > target && j < s1);
+            if (hit) { found = r + (int)__builtin_ctzll(hit); break; }
+            run += __shfl(incl, 63, 64);
+        }
+        if (found == 0x7FFFFFFF) {            // rounding: the segment total said "here", the in-order walk did not get there
+            int lp = last_pos;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) lp = max(lp, __shfl_xor(lp, o, 64));
+            if (lp >= 0) found = lp;
+        }
     }
     found = block_reduce_min_int<NT>(found, smi);
-    if (found == 0x7FFFFFFF) found = -block_reduce_min_int<NT>(-last_pos, smi);     // maximum of last_pos
+    if (found == 0x7FFFFFFF) found = -block_reduce_min_int<NT>(-last_pos, smi);     // maximum of last_pos over the row
     return min(max(found, 0), V - 1);
 }
 
 // softmax statistics of one row at inverse temperature it: maximum of x*it and the sum of exp(x*it - max)
 template <int NT>
 __device__ __forceinline__ void block_softmax_stats(const float* __restrict__ x, int V, float it, float* smf, float* mx, float* sum) {
-    float m = -INFINITY;
-    for (int j = threadIdx.x; j < V; j += NT) m = fmaxf(m, x[j] * it);
-    m = block_reduce_max<NT>(m, smf);
-    const int C = (V + NT - 1) / NT;
-    const int j0 = min((int)threadIdx.x * C, V), j1 = min(j0 + C, V);
+    float m = block_row_max<NT>(x, V, it, smf);
     float s = 0.f;
-    for (int j = j0; j < j1; ++j) s += expf(x[j] * it - m);
-    float total;
-    (void)block_exclusive_scan<NT>(s, smf, &total);
+    for (int j = threadIdx.x; j < V; j += NT * 8) {
+        float x8[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) x8[k] = x[min(j + NT * k, V - 1)];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) if (j + NT * k < V) s += expf(x8[k] * it - m);
+    }
+    s = wave_sum(s);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) smf[threadIdx.x >> 6] = s;
+    __syncthreads();
+    float total = 0.f;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) total += smf[w];
     *mx = m; *sum = total;
 }
 
 // One token per row drawn from softmax(logits / T) with the row's uniform number.  One workgroup per row.
 template <int NT>
 __device__ __forceinline__ int block_sample_softmax(const float* __restrict__ x, int V, float it, float u, float* smf, int* smi) {
-    float m = -INFINITY;
-    for (int j = threadIdx.x; j < V; j += NT) m = fmaxf(m, x[j] * it);
-    m = block_reduce_max<NT>(m, smf);
+    const float m = block_row_max<NT>(x, V, it, smf);
     return block_sample_inverse_cdf<NT>([&](int j) { return expf(x[j] * it - m); }, V, u, smf, smi);
 }
 constexpr int SAMPLE_NT = 512;
@@ -979,7 +1020,13 @@ __global__ __launch_bounds__(ACCEPT_NT) void accept_sample_kernel(const int32_t*
         const float isp = 1.0f / sp, isq = 1.0f / sq;
         auto resid = [&](int j) { return fmaxf(expf(lp[j] * inv_temp - mp) * isp - expf(lq[j] * inv_temp - mq) * isq, 0.f); };
         float any = 0.f;
-        for (int j = threadIdx.x; j < V; j += ACCEPT_NT) any = fmaxf(any, resid(j));
+        for (int j = threadIdx.x; j < V; j += ACCEPT_NT * 4) {
+            float r4[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) r4[k] = resid(min(j + ACCEPT_NT * k, V - 1));
+#pragma unroll
+            for (int k = 0; k < 4; ++k) any = fmaxf(any, r4[k]);
+        }
         any = block_reduce_max<ACCEPT_NT>(any, smf);
         if (any > 0.f) tok = block_sample_inverse_cdf<ACCEPT_NT>(resid, V, u_res[b], smf, smi);
         else tok = block_sample_inverse_cdf<ACCEPT_NT>([&](int j) { return expf(lp[j] * inv_temp - mp); }, V, u_res[b], smf, smi);

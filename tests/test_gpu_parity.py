@@ -220,6 +220,18 @@ def test_rerun_is_bit_identical():
         assert np.array_equal(a, b), "two runs of the same prompt differ bitwise"
 
 
+def test_standalone_kernel_path_matches_oracle():
+    # HIVIS_FUSED=0: every operation as its own launch (the kernels the 32-row passes and the fp32 prefill also use)
+    import os
+    os.environ["HIVIS_FUSED"] = "0"
+    try:
+        sbs = run_generic(small_bf16(K=4), 29, 2, plant=(3,))
+        print("stand-alone kernels bf16 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+        run_generic(synth.get_config("C1"), 3, 2, plant=(2,))
+    finally:
+        del os.environ["HIVIS_FUSED"]
+
+
 def test_persistent_mode_matches_oracle():
     # the opt-in single-launch (cooperative, grid-barrier) execution of the same phase programs
     import os

@@ -120,3 +120,14 @@ def test_sampling_full_vocab_width():
     cfg = synth.get_config("C2").scaled(n_layers=2, gen_tokens=0, gen_cycles=2, n_vis=64, n_text=24)
     st = run_sampling(cfg, 43, 2, 1.0)
     print("V=32000 T=1 sampling:", st)
+
+
+def test_sampling_standalone_kernel_path():
+    # HIVIS_FUSED=0: the draft loop draws its tokens with the stand-alone row-sampling kernel
+    import os
+    os.environ["HIVIS_FUSED"] = "0"
+    try:
+        st = run_sampling(small_bf16(K=3), 44, 4, 0.7)
+        print("stand-alone path T=0.7 sampling:", st)
+    finally:
+        del os.environ["HIVIS_FUSED"]

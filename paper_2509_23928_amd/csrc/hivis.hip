@@ -182,8 +182,9 @@ int gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, i
     const int T = (M + ROWS - 1) / ROWS;
     if constexpr (sizeof(WT) == 2) {
         if (T == 1) hipLaunchKernelGGL((gemm_skinny_kernel<WT, 1, 4, 8, 16>), dim3(grid), dim3(1024), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);
-        else if (T == 2) hipLaunchKernelGGL((gemm_skinny_kernel<WT, 2, 4, 4, 16>), dim3(grid), dim3(1024), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);
-        else hipLaunchKernelGGL((gemm_skinny_kernel<WT, 4, 2, 2, 16>), dim3(grid), dim3(1024), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);
+        // 8 wavefronts for the wider row counts: every wavefront may use 256 registers (raw rows + fragments + accumulators spill at 128)
+        else if (T == 2) hipLaunchKernelGGL((gemm_skinny_kernel<WT, 2, 4, 4, 8>), dim3(grid), dim3(512), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);
+        else hipLaunchKernelGGL((gemm_skinny_kernel<WT, 4, 2, 4, 8>), dim3(grid), dim3(512), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);   // 4 tiles per group: the rows' fragments are re-read once per group
     } else {
         if (T == 1) hipLaunchKernelGGL((gemm_skinny_kernel<WT, 1, 4, 4, 16>), dim3(grid), dim3(1024), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);
         else hipLaunchKernelGGL((gemm_skinny_kernel<WT, 2, 4, 2, 16>), dim3(grid), dim3(1024), 0, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi);

@@ -174,6 +174,42 @@ template <> struct AFrag<float> { typedef float4 type; };
 
 // A fragment of tile tt, block kb for this lane.  a_scale (optional, per k) multiplies the
 // activation before the hi/lo split (used to apply an RMSNorm gain on the fly).
+// Raw activation values of one A fragment (loaded unconditionally from a clamped row; converted later)
+template <typename WT> struct ARaw;
+template <> struct ARaw<bf16_t> { float4 x0, x1; };
+template <> struct ARaw<float> { float4 x0; };
+__device__ __forceinline__ void load_afrag_raw(ARaw<bf16_t>& r, const float* __restrict__ A, int lda, int M, int tt, int kb, int lane) {
+    const int i = lane & 15, g = lane >> 4;
+    const int row = min(tt * 8 + 2 * (i >> 2) + (i & 1), M - 1);
+    const float4* p = reinterpret_cast<const float4*>(A + (size_t)row * lda + kb * 32 + g * 8);
+    r.x0 = p[0]; r.x1 = p[1];
+}
+__device__ __forceinline__ void load_afrag_raw(ARaw<float>& r, const float* __restrict__ A, int lda, int M, int tt, int kb, int lane) {
+    const int i = lane & 15, g = lane >> 4;
+    const int row = min(tt * 16 + i, M - 1);
+    r.x0 = *reinterpret_cast<const float4*>(A + (size_t)row * lda + kb * 16 + g * 4);
+}
+__device__ __forceinline__ void make_afrag(bf16x8_t& out, const ARaw<bf16_t>& r, int M, int tt, bool valid, int lane) {
+    const int i = lane & 15;
+    const int row = tt * 8 + 2 * (i >> 2) + (i & 1);
+    const bool lo = (i & 2) != 0;
+    const bool on = valid && row < M;
+    const float x[8] = {r.x0.x, r.x0.y, r.x0.z, r.x0.w, r.x1.x, r.x1.y, r.x1.z, r.x1.w};
+    uint32_t pk[4];
+    bf16_t h[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const bf16_t hi = f32_to_bf16(x[e]);
+        h[e] = lo ? f32_to_bf16(x[e] - bf16_to_f32(hi)) : hi;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pk[e] = on ? ((uint32_t)h[2 * e] | ((uint32_t)h[2 * e + 1] << 16)) : 0u;
+    out = __builtin_bit_cast(bf16x8_t, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+}
+__device__ __forceinline__ void make_afrag(float4& out, const ARaw<float>& r, int M, int tt, bool valid, int lane) {
+    const bool on = valid && (tt * 16 + (lane & 15)) < M;
+    out = on ? r.x0 : make_float4(0.f, 0.f, 0.f, 0.f);
+}
 __device__ __forceinline__ void load_afrag(bf16x8_t& out, const float* __restrict__ A, int lda, int M, int tt, int kb,
                                            int lane) {
     const int i = lane & 15, g = lane >> 4;
@@ -224,10 +260,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const float* __res
     typedef WTraits<WT> TR;
     typedef typename AFrag<WT>::type afrag_t;
     constexpr int RPL = TR::RPL;
-    static_assert(G * T * RPL <= 16, "LDS reduction buffer limited to 64 KiB");
+    static_assert(NW * G * T * RPL * 64 * 4 <= 65536, "LDS reduction buffer limited to 64 KiB");
     __shared__ float red[NW * G * T * 64 * RPL];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: uniform branches
     const int kblks = K / TR::KB;
     const int ntiles = N / 16;
     const int t_begin = (int)(((long long)blockIdx.x * ntiles) / gridDim.x);
@@ -246,19 +282,23 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const float* __res
             const int kb0 = (pass * NW + wave) * KBW;
             const int nkb = max(0, min(KBW, kblks - kb0));       // wave-uniform
             if (nkb == 0) continue;
-            afrag_t af[T][KBW];
-#pragma unroll
-            for (int tt = 0; tt < T; ++tt)
-#pragma unroll
-                for (int j = 0; j < KBW; ++j) {
-                    if (j < nkb) load_afrag(af[tt][j], A, lda, M, tt, kb0 + j, lane);
-                    else load_afrag(af[tt][j], A, lda, 0, tt, 0, lane);   // zeros
-                }
+            // first tile's weights and ALL activation rows of the pass are requested before anything is converted:
+            // a conversion right behind each (conditional) row load costs one memory round trip per fragment
             uint4 wb[2][KBW];
             const uint4* wp = Wp + ((size_t)tg * kblks + kb0) * 64 + lane;
 #pragma unroll
             for (int j = 0; j < KBW; ++j)
                 if (j < nkb) wb[0][j] = wp[(size_t)j * 64]; else wb[0][j] = make_uint4(0, 0, 0, 0);
+            ARaw<WT> raw[T][KBW];
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+                for (int j = 0; j < KBW; ++j) load_afrag_raw(raw[tt][j], A, lda, M, tt, min(kb0 + j, kblks - 1), lane);
+            afrag_t af[T][KBW];
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+                for (int j = 0; j < KBW; ++j) make_afrag(af[tt][j], raw[tt][j], M, tt, j < nkb, lane);
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 if (g < ng) {

@@ -660,11 +660,14 @@ int tall_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
     hipLaunchKernelGGL(pack_afrag_kernel, dim3((unsigned)std::min<size_t>((nfrag + 255) / 256, 65535)), dim3(256), 0, c->stream, A, lda, M, kblks, c->pf_frag);
     // LDS-tiled kernel: 64 real rows x 256 columns per workgroup when that still gives >= 2 workgroups per CU, else x 128
     const int macro_rows = (row_tiles + 7) / 8;
+    // grid: (column blocks rounded up to a multiple of the 8 XCDs) x row blocks, 1-D (see the kernel's mapping)
     if ((size_t)macro_rows * ((ntiles + 15) / 16) >= (size_t)2 * c->num_cu) {
-        hipLaunchKernelGGL((gemm_tall_lds_kernel<8>), dim3((ntiles + 15) / 16, macro_rows), dim3(256), 2 * 24 * 1024, c->stream,
+        const int ncol8 = (((ntiles + 15) / 16) + 7) & ~7;
+        hipLaunchKernelGGL((gemm_tall_lds_kernel<8>), dim3(ncol8 * macro_rows), dim3(256), 2 * 24 * 1024, c->stream,
                            (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M);
     } else {
-        hipLaunchKernelGGL((gemm_tall_lds_kernel<4>), dim3((ntiles + 7) / 8, macro_rows), dim3(256), 2 * 16 * 1024, c->stream,
+        const int ncol8 = (((ntiles + 7) / 8) + 7) & ~7;
+        hipLaunchKernelGGL((gemm_tall_lds_kernel<4>), dim3(ncol8 * macro_rows), dim3(256), 2 * 16 * 1024, c->stream,
                            (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M);
     }
     HIP_TRY(c, hipGetLastError());

@@ -389,7 +389,14 @@ __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __re
     extern __shared__ __align__(16) v4u_t tall_lds[];      // [2 stages][NBLK][64]
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wr = wave >> 1, wc = wave & 1;
-    const int rt_wg = blockIdx.y * NA, ct_wg = blockIdx.x * NB;
+    // 1-D grid, XCD-aware: workgroup L runs on XCD L % 8 (round-robin dispatch) and each XCD has its own L2.  The nrow
+    // workgroups that share one block of weight columns are given consecutive slots of ONE XCD, so the weights come
+    // from HBM once and from that L2 nrow-1 times (with a plain 2-D grid every XCD fetched its own copy: 10x the bytes).
+    const int ncol = (ntiles + NB - 1) / NB, nrow = (row_tiles + NA - 1) / NA;
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const int cblk = 8 * (slot / nrow) + xcd, rblk = slot % nrow;
+    if (cblk >= ncol) return;
+    const int rt_wg = rblk * NA, ct_wg = cblk * NB;
     // the blocks this wavefront copies: block id b = wave + 4 i; b < NA is an A block (row tile rt_wg + b), else a B block
     const v4u_t* src[PER_WAVE];
 #pragma unroll

@@ -220,6 +220,39 @@ def test_rerun_is_bit_identical():
         assert np.array_equal(a, b), "two runs of the same prompt differ bitwise"
 
 
+@pytest.mark.parametrize("seed", list(range(100, 112)))
+def test_random_shape_sweep(seed):
+    """Seeded random small shapes inside the documented limits: odd tile counts (grids smaller than the chip, ragged K
+    passes, partial tile groups), both head sizes, grouped heads, batches, K from 1 to 7, caches from a few keys to several
+    key tiles, and row counts on both sides of one MFMA tile."""
+    rng = np.random.default_rng(seed)
+    hd = int(rng.choice([64, 128]))
+    n_kv = int(rng.choice([1, 2, 4]))
+    group = int(rng.choice([1, 2, 3]))
+    n_q = n_kv * group
+    d = 32 * int(rng.integers(4, 20))
+    ffn = 32 * int(rng.integers(5, 60))
+    vocab = 32 * int(rng.integers(8, 200))
+    K = int(rng.integers(1, 8))
+    batch = int(rng.choice([1, 1, 2, 3, 4]))
+    while batch * (K + 1) > 32:
+        batch -= 1
+    cfg = small_bf16(name=f"sweep-{seed}", d=d, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=hd, ffn=ffn, vocab=vocab, K=K, batch=batch,
+                     n_vis=int(rng.integers(0, 300)), n_text=int(rng.integers(1, 60)), n_layers=int(rng.integers(1, 4)))
+    w, vis, ids, hv = make(cfg, seed)
+    try:
+        sbs = SideBySide(cfg, w, hv, vis, ids)
+    except AssertionError as e:
+        if "near-tie at the first token" in str(e):
+            pytest.skip("near-tie at the first token for this seed")
+        raise
+    sbs.cycle(K)
+    sbs.cycle(max(1, K - 1))
+    hv.close()
+    print(f"sweep {seed}: d={d} Hq/Hkv={n_q}/{n_kv} hd={hd} F={ffn} V={vocab} K={K} B={batch} v={cfg.n_vis} l={cfg.n_text} N={cfg.n_layers}",
+          "max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+
+
 def test_standalone_kernel_path_matches_oracle():
     # HIVIS_FUSED=0: every operation as its own launch (the kernels the 32-row passes and the fp32 prefill also use)
     import os

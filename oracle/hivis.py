@@ -79,9 +79,11 @@ class HivisOracle:
         return out[-1]
 
     # -- Algorithm 1, inputs line + steps 1-2 --------------------------------------------
-    def prefill(self, vis_embeds, text_ids):
+    def prefill(self, vis_embeds, text_ids, pick=None):
         """Target prefill over [visual ; text]; returns x_{l+1} (emitted) and the logits
-        that chose it.  Then the drafter is prefilled over the l text positions only."""
+        that chose it.  Then the drafter is prefilled over the l text positions only.
+        pick: optional function logits -> token replacing the greedy choice of x_{l+1}
+        (temperature sampling, or following another implementation's token)."""
         vis = np.asarray(vis_embeds, F64)
         ids = [int(t) for t in text_ids]
         self.v = vis.shape[0]
@@ -90,7 +92,7 @@ class HivisOracle:
         f_all = self.target.forward(x, 0)
         f = f_all[self.v:]                                   # f_fused^{1:l}: text rows only
         logits = self.target.logits(f[-1])
-        x_next = int(argmax_lowest(logits))
+        x_next = int(argmax_lowest(logits)) if pick is None else int(pick(logits))
         self.text = ids + [x_next]
         self.l = l
         # e^_{2:l+1} = f^{1:l} w1 + e^{2:l+1} w2, all rows carry r^0
@@ -234,8 +236,20 @@ def speculative_accept(p, q, drafts, u_accept, u_resample):
 
 
 class HivisSamplingOracle(HivisOracle):
-    """The same cycle with tokens drawn at temperature T instead of taken greedily.  The first
-    token after the prompt (prefill) stays the target's greedy token."""
+    """The same cycle with tokens drawn at temperature T instead of taken greedily.  prefill()
+    keeps the greedy first token; prefill_sample() draws it from the target's distribution too."""
+
+    def prefill_sample(self, vis_embeds, text_ids, T, u, follow=None):
+        """Prefill with x_{l+1} drawn from softmax(logits / T) with uniform u (or `follow`'s token fed
+        forward instead, the returned token still being this oracle's own draw)."""
+        drawn = {}
+
+        def pick(logits):
+            drawn["x"] = sample_inverse_cdf(softmax_temperature(logits, T), u)
+            return drawn["x"] if follow is None else int(follow)
+
+        _, logits = self.prefill(vis_embeds, text_ids, pick=pick)
+        return drawn["x"], logits
 
     def draft_sample(self, K, T, u, follow=None):
         """K chain drafts, draft i drawn from softmax(logits_i / T) with uniform u[i].
@@ -278,9 +292,10 @@ class HivisSamplingOracle(HivisOracle):
         return {"drafts": drafts, "draft_logits": dlogits, "g": g, "verify_logits": vlogits, "n": n, "emitted": emitted}
 
 
-def sampling_reference(cfg, weights, vis_embeds, text_ids, n_tokens, T, u):
-    """Plain definition at T > 0: prefill the target (greedy first token, as prefill() does), then
-    decode one token at a time, each drawn from softmax(logits / T) with u[k]."""
+def sampling_reference(cfg, weights, vis_embeds, text_ids, n_tokens, T, u, sample_first=False):
+    """Plain definition at T > 0: prefill the target, then decode one token at a time, each drawn
+    from softmax(logits / T) with u[k]; the first token is greedy (as prefill() does) unless
+    sample_first (as prefill_sample() does)."""
     tgt = Target(cfg, weights)
     vis = np.asarray(vis_embeds, F64)
     x = np.concatenate([vis, tgt.embed(text_ids)], axis=0)
@@ -289,7 +304,7 @@ def sampling_reference(cfg, weights, vis_embeds, text_ids, n_tokens, T, u):
     pos = x.shape[0]
     for k in range(n_tokens):
         logits = tgt.logits(f)
-        tok = int(argmax_lowest(logits)) if k == 0 else sample_inverse_cdf(softmax_temperature(logits, T), u[k])
+        tok = int(argmax_lowest(logits)) if (k == 0 and not sample_first) else sample_inverse_cdf(softmax_temperature(logits, T), u[k])
         tokens.append(tok)
         f = tgt.forward(tgt.embed([tok]), pos)[0]
         pos += 1

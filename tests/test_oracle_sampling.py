@@ -153,3 +153,21 @@ def test_sampling_cycle_state_equals_fresh_prefill():
     g1, l1, _ = fresh.verify(drafts); g2, l2, _ = o.verify(drafts)
     np.testing.assert_allclose(g1, g2, rtol=1e-9, atol=1e-11)
     np.testing.assert_allclose(l1, l2, rtol=1e-8, atol=1e-10)
+
+
+def test_prefill_sample_first_token():
+    """The first token drawn at temperature T: equals the inversion draw from the prefill logits; a cold
+    temperature gives the greedy token; a followed token is fed forward while the own draw is reported."""
+    cfg = tiny_cfg()
+    w = synth.make_weights(cfg, seed=8)
+    vis, ids = synth.make_prompt(cfg, seed=8)
+    g = HivisOracle(cfg, w); xg, lg = g.prefill(vis[0], ids[0])
+    o = HivisSamplingOracle(cfg, w); x, logits = o.prefill_sample(vis[0], ids[0], 1.0, 0.37)
+    np.testing.assert_allclose(logits, lg, rtol=1e-12, atol=1e-14)
+    assert x == sample_inverse_cdf(softmax_temperature(lg, 1.0), 0.37) and o.text[-1] == x
+    c = HivisSamplingOracle(cfg, w); xc, _ = c.prefill_sample(vis[0], ids[0], 1e-4, 0.9)
+    assert xc == xg and np.array_equal(c.f_next, g.f_next)
+    f = HivisSamplingOracle(cfg, w); xf, _ = f.prefill_sample(vis[0], ids[0], 1.0, 0.37, follow=(x + 1) % cfg.vocab)
+    assert xf == x and f.text[-1] == (x + 1) % cfg.vocab
+    ref = sampling_reference(cfg, w, vis[0], ids[0], 1, 1.0, [0.37], sample_first=True)
+    assert ref == [x]

@@ -131,7 +131,12 @@ int hivis_accept(hivis_ctx *ctx, int32_t *n_accepted, int32_t *tokens);
 /* ---- the same cycle at a temperature T > 0 (section 2.1: the accepted prefix is kept, the token after it is
  * resampled, and if every candidate is accepted the target samples from its own distribution; the rule is the
  * speculative sampling rule of the works that section cites).  The uniform random numbers are INPUTS, each in [0, 1).
- * hivis_prefill's first token stays the target's greedy token in both modes. ---- */
+ * hivis_prefill's first token is the target's greedy token; hivis_prefill_sample draws it as well. ---- */
+
+/* hivis_prefill with x_{l+1} of sequence b drawn from softmax(logits / T) by inversion with u_first[b] (host, [B]).
+ * Errors as hivis_prefill, plus EINVAL for T <= 0 or a uniform outside [0, 1). */
+int hivis_prefill_sample(hivis_ctx *ctx, const void *vis_embeds, int32_t v, const int32_t *text_ids, int32_t l,
+                         float temperature, const float *u_first, int32_t *first_token);
 
 /* K serial drafter steps as hivis_draft, but draft i of sequence b is DRAWN from q_i = softmax(logits_i / T) by
  * inversion with u[b][i-1]: the smallest token j whose running probability sum exceeds u.

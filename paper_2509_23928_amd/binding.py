@@ -59,6 +59,7 @@ def load_library(path=LIB_PATH):
         "hivis_set_drafts": (C.c_int, [P, P, I32]),
         "hivis_verify": (C.c_int, [P]),
         "hivis_accept": (C.c_int, [P, P, P]),
+        "hivis_prefill_sample": (C.c_int, [P, P, I32, P, I32, C.c_float, P, P]),
         "hivis_draft_sample": (C.c_int, [P, I32, C.c_float, P]),
         "hivis_accept_sample": (C.c_int, [P, C.c_float, P, P, P, P]),
         "hivis_get_logits": (C.c_int, [P, I32, P]),
@@ -81,7 +82,7 @@ def load_library(path=LIB_PATH):
 
 
 EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_set_drafts",
-                    "hivis_verify", "hivis_accept", "hivis_draft_sample", "hivis_accept_sample", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
+                    "hivis_verify", "hivis_accept", "hivis_prefill_sample", "hivis_draft_sample", "hivis_accept_sample", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
                     "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes",
                     "hivis_last_error", "hivis_version")
 
@@ -169,6 +170,18 @@ class Hivis:
         v, l = int(vis_embeds.shape[-2]), int(text_ids.shape[-1])
         first = np.zeros(self.B, np.int32)
         self._check(self.lib.hivis_prefill(self.ctx, _ptr(vis_embeds), v, _ptr(text_ids), l, _ptr(first)))
+        return first
+
+    def prefill_sample(self, vis_embeds, text_ids, temperature, u_first):
+        """prefill() with the first token of every sequence drawn at `temperature` with u_first [B]."""
+        if isinstance(vis_embeds, np.ndarray):
+            vis_embeds = _host_weight(vis_embeds, self.dtype)
+        if isinstance(text_ids, np.ndarray):
+            text_ids = np.ascontiguousarray(text_ids, dtype=np.int32)
+        v, l = int(vis_embeds.shape[-2]), int(text_ids.shape[-1])
+        u = np.ascontiguousarray(u_first, dtype=np.float32).reshape(self.B)
+        first = np.zeros(self.B, np.int32)
+        self._check(self.lib.hivis_prefill_sample(self.ctx, _ptr(vis_embeds), v, _ptr(text_ids), l, float(temperature), _ptr(u), _ptr(first)))
         return first
 
     def draft(self, K):

@@ -736,7 +736,7 @@ static void resolve_phase_events(hivis_ctx* c) {
 
 // ---- the four calls, typed -------------------------------------------------------------------
 template <typename WT>
-int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_ids, int l, int32_t* first_token) {
+int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_ids, int l, int32_t* first_token, bool sample) {
     const hivis_config& g = c->cfg;
     const int B = g.batch, d = g.d;
     PhaseTimer pt(c, 0);
@@ -769,7 +769,8 @@ int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_
     hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, c->tlen, B, total);
     // first token x_{l+1}: LM head on the last text row of every sequence
     if (int rc = gemm<WT>(c, c->feat + (size_t)(l - 1) * d, g.max_text * d, B, d, c->lm_head, g.vocab, c->logits_p, g.vocab, EPI_STORE)) return rc;
-    hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)c->logits_p, g.vocab, c->text + l, c->text_stride);
+    if (sample) hipLaunchKernelGGL(sample_rows_kernel, dim3(B), dim3(SAMPLE_NT), 0, c->stream, (const float*)c->logits_p, g.vocab, c->inv_temp, (const float*)c->u_res, 1, c->text + l, c->text_stride);
+    else hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)c->logits_p, g.vocab, c->text + l, c->text_stride);
     // drafter prefill over the l text positions: rows [f^j ; Embed(x_{j+1})] + rho_0
     for (int b = 0; b < B; ++b) {
         for (int j0 = 0; j0 < l; j0 += MAX_ROWS) {
@@ -1066,7 +1067,27 @@ int hivis_prefill(hivis_ctx* c, const void* vis_embeds, int32_t v, const int32_t
     for (int32_t id : c->h_ids)
         if (id < 0 || id >= g.vocab) return fail(c, HIVIS_EINVAL, "token id %d outside [0,%d)", id, g.vocab);
     c->state = ST_CREATED;
-    return DISPATCH(c, do_prefill, c, vis_embeds, v, text_ids, l, first_token);
+    return DISPATCH(c, do_prefill, c, vis_embeds, v, text_ids, l, first_token, false);
+}
+
+static int check_uniforms(hivis_ctx* c, const float* u, size_t n, const char* what);
+
+int hivis_prefill_sample(hivis_ctx* c, const void* vis_embeds, int32_t v, const int32_t* text_ids, int32_t l, float temperature,
+                         const float* u_first, int32_t* first_token) {
+    if (!c) return HIVIS_EINVAL;
+    const hivis_config& g = c->cfg;
+    if (!text_ids || v < 0 || l < 1 || (v > 0 && !vis_embeds)) return fail(c, HIVIS_EINVAL, "bad prefill arguments (v=%d, l=%d)", v, l);
+    if (!(temperature > 0.0f)) return fail(c, HIVIS_EINVAL, "temperature must be positive");
+    if (int rc = check_uniforms(c, u_first, (size_t)g.batch, "u_first")) return rc;
+    if (v > g.max_vis || l + g.k_max + 2 > g.max_text) return fail(c, HIVIS_ECAP, "prompt exceeds capacity (v=%d/%d, l=%d/%d)", v, g.max_vis, l, g.max_text);
+    c->h_ids.resize((size_t)g.batch * l);
+    HIP_TRY(c, hipMemcpy(c->h_ids.data(), text_ids, c->h_ids.size() * sizeof(int32_t), hipMemcpyDefault));
+    for (int32_t id : c->h_ids)
+        if (id < 0 || id >= g.vocab) return fail(c, HIVIS_EINVAL, "token id %d outside [0,%d)", id, g.vocab);
+    HIP_TRY(c, hipMemcpyAsync(c->u_res, u_first, (size_t)g.batch * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    c->inv_temp = 1.0f / temperature;
+    c->state = ST_CREATED;
+    return DISPATCH(c, do_prefill, c, vis_embeds, v, text_ids, l, first_token, true);
 }
 
 static int check_room(hivis_ctx* c, int K) {

@@ -23,17 +23,32 @@ def near_cdf_boundary(weights, u, a, b):
     return bool(np.min(np.abs(c[lo:hi] - u * c[-1])) <= EDGE * c[-1])
 
 
-def run_sampling(cfg, seed, cycles, T):
+def run_sampling(cfg, seed, cycles, T, sample_first=False):
     from paper_2509_23928_amd import HivisError, HIVIS_ESTATE, HIVIS_EINVAL
     w, vis, ids, hv = make(cfg, seed)
     B, K = cfg.batch, cfg.K
-    first = hv.prefill(vis, ids)
-    oracles = [HivisSamplingOracle(cfg, w) for _ in range(B)]
-    for b, o in enumerate(oracles):
-        x, _ = o.prefill(vis[b], ids[b])
-        assert x == int(first[b]), "near-tie at the first token: pick another seed"
     rng = np.random.default_rng(1000 + seed)
     stats = {"draws": 0, "edge": 0, "n_hist": np.zeros(K + 1, int), "max_err": 0.0}
+    oracles = [HivisSamplingOracle(cfg, w) for _ in range(B)]
+    if sample_first:
+        u_f = rng.random(B).astype(np.float32)
+        first = hv.prefill_sample(vis, ids, T, u_f)
+        plog = hv.get_logits(2).astype(np.float64)
+        for b, o in enumerate(oracles):
+            _, ologits = o.prefill_sample(vis[b], ids[b], T, float(u_f[b]), follow=int(first[b]))
+            tol = logit_tol(cfg, ologits)
+            assert float(np.max(np.abs(plog[b] - ologits))) <= tol
+            pr = softmax_temperature(plog[b], T)
+            mine = sample_inverse_cdf(pr, float(u_f[b]))
+            stats["draws"] += 1
+            if mine != int(first[b]):
+                assert near_cdf_boundary(pr, float(u_f[b]), mine, int(first[b]))
+                stats["edge"] += 1
+    else:
+        first = hv.prefill(vis, ids)
+        for b, o in enumerate(oracles):
+            x, _ = o.prefill(vis[b], ids[b])
+            assert x == int(first[b]), "near-tie at the first token: pick another seed"
     # error paths: bad temperature / uniforms, and acceptance by sampling after greedy drafts
     with pytest.raises(HivisError) as e:
         hv.draft_sample(K, 0.0, rng.random((B, K)))
@@ -100,14 +115,14 @@ def run_sampling(cfg, seed, cycles, T):
 
 
 def test_sampling_c1_fp32_temperature_one():
-    st = run_sampling(synth.get_config("C1"), 0, 8, 1.0)
+    st = run_sampling(synth.get_config("C1"), 0, 8, 1.0, sample_first=True)
     print("C1 T=1 sampling:", st)
     assert st["n_hist"].sum() == 8
 
 
 def test_sampling_small_bf16_two_temperatures_batch2():
     cfg = small_bf16(batch=2, K=4)
-    st = run_sampling(cfg, 41, 6, 1.0)
+    st = run_sampling(cfg, 41, 6, 1.0, sample_first=True)
     print("bf16 T=1 sampling:", st)
     st2 = run_sampling(cfg, 42, 6, 0.05)
     print("bf16 T=0.05 sampling:", st2)

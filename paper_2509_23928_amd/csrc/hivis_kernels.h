@@ -260,8 +260,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const float* __res
     typedef WTraits<WT> TR;
     typedef typename AFrag<WT>::type afrag_t;
     constexpr int RPL = TR::RPL;
-    static_assert(NW * G * T * RPL * 64 * 4 <= 65536, "LDS reduction buffer limited to 64 KiB");
-    __shared__ float red[NW * G * T * 64 * RPL];
+    static_assert(NW * G * T * RPL * 64 * 4 <= 160 * 1024, "LDS reduction buffer must fit the 160 KiB of a compute unit");
+    extern __shared__ __align__(16) float red[];       // [NW][G][T][64][RPL] (dynamic: up to 128 KiB for the 32-row variant)
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: uniform branches
     const int kblks = K / TR::KB;

@@ -172,6 +172,9 @@ int upload_layer(hivis_ctx* c, const hivis_layer_weights& w, void* staging, Laye
     return HIVIS_OK;
 }
 
+// column chunks per row for the row-wise kernels: few rows -> split every row over several workgroups
+static inline int row_chunks(int rows) { return rows >= 256 ? 1 : std::max(1, std::min(8, 256 / std::max(rows, 1))); }
+
 // ---- launches --------------------------------------------------------------------------------
 template <typename WT>
 int gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy, int epi) {
@@ -273,13 +276,13 @@ int layer_forward(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, co
     const int nqkv = qd + 2 * kd;
     hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, pending, d, (const WT*)L.norm1, c->a, d, d, g.rms_eps);
     if (int rc = gemm<WT>(c, c->a, d, M, d, L.wqkv, nqkv, c->qkv, nqkv, EPI_STORE)) return rc;
-    hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
+    hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
     if (c->fused && std::is_same<KT, f16_t>::value) { if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd)) return rc; }
     else if (int rc = attention<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, max_keys, c->att, qd)) return rc;
     if (int rc = gemm<WT>(c, c->att, qd, M, qd, L.wo, d, c->proj, d, EPI_STORE)) return rc;
     hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, (const float*)c->proj, d, (const WT*)L.norm2, c->a, d, d, g.rms_eps);
     if (int rc = gemm<WT>(c, c->a, d, M, d, L.wgu, 2 * F, c->gu, 2 * F, EPI_STORE)) return rc;
-    hipLaunchKernelGGL(silu_mul_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->gu, c->act, F);
+    hipLaunchKernelGGL(silu_mul_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, (const float*)c->gu, c->act, F);
     if (int rc = gemm<WT>(c, c->act, F, M, F, L.wd, d, c->proj, d, EPI_STORE)) return rc;
     HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;   // c->proj holds the MLP delta, not yet added to h
@@ -700,13 +703,13 @@ int prefill_target_tall(hivis_ctx* c, int b, int v, int l) {
         const KVDev& kv = c->tkv[l_];
         hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, pending, d, (const WT*)L.norm1, c->pf_a, d, d, g.rms_eps);
         if (int rc = tall_gemm(c, c->pf_a, d, M, d, L.wqkv, nqkv, c->pf_qkv, nqkv)) return rc;
-        hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M), dim3(256), 0, c->stream, c->pf_qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, (const int*)c->zeros, 0, b, M, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
+        hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->pf_qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, (const int*)c->zeros, 0, b, M, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
         if (c->fused) { if (int rc = attention_rows_mfma<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, c->pf_att, qd)) return rc; }
         else if (int rc = attention<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, M, c->pf_att, qd)) return rc;
         if (int rc = tall_gemm(c, c->pf_att, qd, M, qd, L.wo, d, c->pf_proj, d)) return rc;
         hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, (const float*)c->pf_proj, d, (const WT*)L.norm2, c->pf_a, d, d, g.rms_eps);
         if (int rc = tall_gemm(c, c->pf_a, d, M, d, L.wgu, 2 * F, c->pf_gu, 2 * F)) return rc;
-        hipLaunchKernelGGL(silu_mul_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->pf_gu, c->pf_act, F);
+        hipLaunchKernelGGL(silu_mul_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, (const float*)c->pf_gu, c->pf_act, F);
         if (int rc = tall_gemm(c, c->pf_act, F, M, F, L.wd, d, c->pf_proj, d)) return rc;
         pending = c->pf_proj;
     }

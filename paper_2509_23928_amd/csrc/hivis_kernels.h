@@ -511,15 +511,53 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // h[row] += delta[row] (if delta), then out[row] = h[row] * gain / sqrt(mean(h^2) + eps).
-// One workgroup (256 threads) per row.
+// One workgroup (256 threads) per row.  A row of up to 8192 values is held in registers (8 float4 per thread), with all
+// loads of a pass issued together: a one-load-per-trip loop costs a memory round trip per trip when only a few
+// workgroups run (the 32-row passes).
 template <typename WT>
 __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h, int ldh, const float* __restrict__ delta,
                                                            int ldd, const WT* __restrict__ gain, float* __restrict__ out,
                                                            int ldo, int d, float eps) {
     __shared__ float part[4];
+    constexpr int MAXV = 8;
     const int row = blockIdx.x;
     float* hr = h + (size_t)row * ldh;
     const float* dr = delta ? delta + (size_t)row * ldd : nullptr;
+    float* o = out + (size_t)row * ldo;
+    const int n4 = d / 4;
+    if (n4 <= 256 * MAXV) {
+        float4 xs[MAXV], ds[MAXV];
+#pragma unroll
+        for (int k = 0; k < MAXV; ++k) {
+            const int c4 = min((int)threadIdx.x + 256 * k, n4 - 1);
+            xs[k] = reinterpret_cast<const float4*>(hr)[c4];
+            ds[k] = dr ? reinterpret_cast<const float4*>(dr)[c4] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        float ss = 0.f;
+#pragma unroll
+        for (int k = 0; k < MAXV; ++k) {
+            const int c4 = (int)threadIdx.x + 256 * k;
+            if (c4 < n4) {
+                xs[k].x += ds[k].x; xs[k].y += ds[k].y; xs[k].z += ds[k].z; xs[k].w += ds[k].w;
+                if (dr) reinterpret_cast<float4*>(hr)[c4] = xs[k];
+                ss += xs[k].x * xs[k].x + xs[k].y * xs[k].y + xs[k].z * xs[k].z + xs[k].w * xs[k].w;
+            }
+        }
+        ss = wave_sum(ss);
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+        __syncthreads();
+        const float inv = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)d + eps);
+#pragma unroll
+        for (int k = 0; k < MAXV; ++k) {
+            const int c4 = (int)threadIdx.x + 256 * k;
+            if (c4 < n4) {
+                const WT* gp = gain + 4 * c4;
+                reinterpret_cast<float4*>(o)[c4] = make_float4(xs[k].x * to_f32(gp[0]) * inv, xs[k].y * to_f32(gp[1]) * inv,
+                                                               xs[k].z * to_f32(gp[2]) * inv, xs[k].w * to_f32(gp[3]) * inv);
+            }
+        }
+        return;
+    }
     float ss = 0.f;
     for (int c = threadIdx.x; c < d; c += 256) {
         float x = hr[c];
@@ -531,7 +569,6 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ h,
     __syncthreads();
     const float tot = part[0] + part[1] + part[2] + part[3];
     const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-    float* o = out + (size_t)row * ldo;
     for (int c = threadIdx.x; c < d; c += 256) o[c] = hr[c] * to_f32(gain[c]) * inv;
 }
 
@@ -552,11 +589,14 @@ __global__ void add_rho_kernel(float* __restrict__ u, int ldu, const WT* __restr
 
 // act[row][c] = silu(gate c) * up c, with gate|up interleaved per 16-column tile (PACK_GATEUP order)
 __global__ void silu_mul_kernel(const float* __restrict__ gu, float* __restrict__ act, int F) {
+    // grid (rows, column chunks); 4 consecutive activations per thread (they share one 8-column gate group)
     const int row = blockIdx.x;
-    for (int c = threadIdx.x; c < F; c += blockDim.x) {
+    for (int c4 = blockIdx.y * blockDim.x + threadIdx.x; c4 < F / 4; c4 += gridDim.y * blockDim.x) {
+        const int c = 4 * c4;
         const size_t o = (size_t)row * 2 * F + (size_t)(c >> 3) * 16 + (c & 7);
-        const float g = gu[o], u = gu[o + 8];
-        act[(size_t)row * F + c] = g / (1.0f + expf(-g)) * u;
+        const float4 g = *reinterpret_cast<const float4*>(gu + o), u = *reinterpret_cast<const float4*>(gu + o + 8);
+        *reinterpret_cast<float4*>(act + (size_t)row * F + c) =
+            make_float4(g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y, g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w);
     }
 }
 
@@ -574,7 +614,7 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int
     const int half = HD / 2;
     float* r = qkv + (size_t)row * (Hq + 2 * Hkv) * HD;
     const int npair = (Hq + Hkv) * half;
-    for (int idx = threadIdx.x; idx < npair; idx += blockDim.x) {
+    for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < npair; idx += gridDim.y * blockDim.x) {
         const int head = idx / half, i = idx % half;
         const double inv_freq = exp2(-2.0 * (double)i / (double)HD * log2((double)theta));
         double s, c;
@@ -591,7 +631,7 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int
         }
     }
     const float* v = r + (size_t)(Hq + Hkv) * HD;
-    for (int idx = threadIdx.x; idx < Hkv * HD; idx += blockDim.x) {
+    for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < Hkv * HD; idx += gridDim.y * blockDim.x) {
         const int head = idx / HD, c = idx % HD;
         from_f32(vc[(((size_t)seq * Hkv + head) * maxL + pos) * HD + c], v[idx]);
     }

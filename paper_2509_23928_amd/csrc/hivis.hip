@@ -184,27 +184,29 @@ int gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, i
     constexpr int ROWS = WTraits<WT>::ROWS;
     const int T = (M + ROWS - 1) / ROWS;
     // dynamic LDS = cross-wavefront reduction buffer [NW][G][T][64][RPL] floats
-#define HIVIS_SKINNY(T_, KBW_, G_, NW_)                                                                            \
+#define HIVIS_SKINNY(T_, KBW_, G_, NW_) HIVIS_SKINNY_(T_, KBW_, G_, NW_, false)
+#define HIVIS_SKINNY_(T_, KBW_, G_, NW_, UP_)                                                                      \
     do {                                                                                                           \
         constexpr size_t lds_ = (size_t)NW_ * G_ * T_ * 64 * WTraits<WT>::RPL * sizeof(float);                     \
         static bool attr_done_ = false;                                                                            \
         if (!attr_done_ && lds_ > 64 * 1024) {                                                                     \
-            HIP_TRY(c, hipFuncSetAttribute((const void*)gemm_skinny_kernel<WT, T_, KBW_, G_, NW_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_)); \
+            HIP_TRY(c, hipFuncSetAttribute((const void*)gemm_skinny_kernel<WT, T_, KBW_, G_, NW_, UP_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_)); \
             attr_done_ = true;                                                                                     \
         }                                                                                                          \
-        hipLaunchKernelGGL((gemm_skinny_kernel<WT, T_, KBW_, G_, NW_>), dim3(grid), dim3(NW_ * 64), lds_, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi); \
+        hipLaunchKernelGGL((gemm_skinny_kernel<WT, T_, KBW_, G_, NW_, UP_>), dim3(grid), dim3(NW_ * 64), lds_, c->stream, A, lda, M, K, Wp, N, Y, ldy, epi); \
     } while (0)
     if constexpr (sizeof(WT) == 2) {
         if (T == 1) HIVIS_SKINNY(1, 4, 8, 16);
         // 8 wavefronts for the wider row counts: every wavefront may use 256 registers (raw rows + fragments + accumulators
-        // spill at 128); 8 tiles per group for 32 rows: the rows' fragments are re-read once per group
+        // spill at 128)
         else if (T == 2) HIVIS_SKINNY(2, 4, 4, 8);
-        else HIVIS_SKINNY(4, 2, 8, 8);
+        else HIVIS_SKINNY_(4, 2, 4, 8, true);     // all 4 tiles' weights of a pass in flight together
     } else {
         if (T == 1) HIVIS_SKINNY(1, 4, 4, 16);
         else HIVIS_SKINNY(2, 4, 2, 16);
     }
 #undef HIVIS_SKINNY
+#undef HIVIS_SKINNY_
     HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;
 }

@@ -253,7 +253,7 @@ __device__ __forceinline__ void mfma_block(f32x4_t& d, const float4& a, const ui
 // Epilogue modes of the skinny GEMM
 enum { EPI_STORE = 0, EPI_ACCUM = 1 };
 
-template <typename WT, int T, int KBW, int G, int NW>
+template <typename WT, int T, int KBW, int G, int NW, bool UPFRONT = false>
 __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const float* __restrict__ A, int lda, int M, int K,
                                                                const uint4* __restrict__ Wp, int N,
                                                                float* __restrict__ Y, int ldy, int epi) {
@@ -282,13 +282,23 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const float* __res
             const int kb0 = (pass * NW + wave) * KBW;
             const int nkb = max(0, min(KBW, kblks - kb0));       // wave-uniform
             if (nkb == 0) continue;
-            // first tile's weights and ALL activation rows of the pass are requested before anything is converted:
-            // a conversion right behind each (conditional) row load costs one memory round trip per fragment
-            uint4 wb[2][KBW];
+            // first tile's weights (UPFRONT: the weights of ALL tiles of the group, so that one memory round trip serves the
+            // whole pass instead of one per tile) and ALL activation rows of the pass are requested before anything is
+            // converted: a conversion right behind each (conditional) row load costs one memory round trip per fragment
+            uint4 wb[UPFRONT ? G : 2][KBW];
             const uint4* wp = Wp + ((size_t)tg * kblks + kb0) * 64 + lane;
 #pragma unroll
             for (int j = 0; j < KBW; ++j)
                 if (j < nkb) wb[0][j] = wp[(size_t)j * 64]; else wb[0][j] = make_uint4(0, 0, 0, 0);
+            if constexpr (UPFRONT) {
+#pragma unroll
+                for (int g = 1; g < G; ++g) {
+                    const uint4* wn = wp + (size_t)min(g, ng - 1) * kblks * 64;      // tiles beyond the group: a clamped (unused) one
+#pragma unroll
+                    for (int j = 0; j < KBW; ++j)
+                        if (j < nkb) wb[g][j] = wn[(size_t)j * 64]; else wb[g][j] = make_uint4(0, 0, 0, 0);
+                }
+            }
             ARaw<WT> raw[T][KBW];
 #pragma unroll
             for (int tt = 0; tt < T; ++tt)
@@ -302,16 +312,18 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const float* __res
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 if (g < ng) {
-                    if (g + 1 < ng) {
-                        const uint4* wn = wp + (size_t)(g + 1) * kblks * 64;
+                    if constexpr (!UPFRONT) {
+                        if (g + 1 < ng) {
+                            const uint4* wn = wp + (size_t)(g + 1) * kblks * 64;
 #pragma unroll
-                        for (int j = 0; j < KBW; ++j)
-                            if (j < nkb) wb[(g + 1) & 1][j] = wn[(size_t)j * 64]; else wb[(g + 1) & 1][j] = make_uint4(0, 0, 0, 0);
+                            for (int j = 0; j < KBW; ++j)
+                                if (j < nkb) wb[(g + 1) & 1][j] = wn[(size_t)j * 64]; else wb[(g + 1) & 1][j] = make_uint4(0, 0, 0, 0);
+                        }
                     }
 #pragma unroll
                     for (int j = 0; j < KBW; ++j)
 #pragma unroll
-                        for (int tt = 0; tt < T; ++tt) mfma_block(acc[g][tt], af[tt][j], wb[g & 1][j]);
+                        for (int tt = 0; tt < T; ++tt) mfma_block(acc[g][tt], af[tt][j], wb[UPFRONT ? g : (g & 1)][j]);
                 }
             }
         }

@@ -54,18 +54,23 @@ def softmax_rows(s):
     return e / np.sum(e, axis=-1, keepdims=True)
 
 
-def attention(q, k, v, q_pos, k_pos):
+def attention(q, k, v, q_pos, k_pos, visible=None):
     """Causal grouped-query attention.
     q: [m][Hq][hd]; k, v: [n][Hkv][hd]; q_pos [m], k_pos [n] integer positions.
     Query at position p sees exactly the keys at positions <= p.
-    Query head h reads kv head h // (Hq / Hkv).  Returns [m][Hq][hd]."""
+    Query head h reads kv head h // (Hq / Hkv).  Returns [m][Hq][hd].
+    visible: optional boolean [m][n] that REPLACES the position rule (rows of a draft tree see their
+    ancestors only, whatever the positions say)."""
     q = np.asarray(q, F64)
     k = np.asarray(k, F64)
     v = np.asarray(v, F64)
     m, Hq, hd = q.shape
     Hkv = k.shape[1]
     group = Hq // Hkv
-    visible = np.asarray(k_pos)[None, :] <= np.asarray(q_pos)[:, None]  # [m][n]
+    if visible is None:
+        visible = np.asarray(k_pos)[None, :] <= np.asarray(q_pos)[:, None]  # [m][n]
+    visible = np.asarray(visible, bool)
+    assert visible.shape == (m, k.shape[0])
     out = np.empty((m, Hq, hd), F64)
     for h in range(Hq):
         g = h // group
@@ -100,11 +105,19 @@ class KVCache:
         self.v = self.v[:n]
         self.pos = self.pos[:n]
 
+    def keep(self, idx):
+        """Keep exactly the entries idx (in that order)."""
+        idx = np.asarray(idx, np.int64)
+        self.k = self.k[idx]
+        self.v = self.v[idx]
+        self.pos = self.pos[idx]
 
-def decoder_layer(h, w, cache, pos, cfg):
+
+def decoder_layer(h, w, cache, pos, cfg, visible=None):
     """One pre-norm decoder block on the rows h [m][d] at positions pos [m]; the rows'
     keys/values are appended to `cache`, and every row attends to all cached entries at
-    positions <= its own.  w: dict with norm1, wq, wk, wv, wo, norm2, wg, wu, wd."""
+    positions <= its own (or, if `visible` [m][len(cache) + m] is given, to exactly the
+    entries it marks).  w: dict with norm1, wq, wk, wv, wo, norm2, wg, wu, wd."""
     h = np.asarray(h, F64)
     m = h.shape[0]
     a = rmsnorm(h, w["norm1"], cfg.rms_eps)
@@ -114,7 +127,7 @@ def decoder_layer(h, w, cache, pos, cfg):
     q = rope(q, pos, cfg.rope_theta)
     k = rope(k, pos, cfg.rope_theta)
     cache.append(k, v, pos)
-    o = attention(q, cache.k, cache.v, pos, cache.pos).reshape(m, cfg.q_dim)
+    o = attention(q, cache.k, cache.v, pos, cache.pos, visible).reshape(m, cfg.q_dim)
     h = h + o @ np.asarray(w["wo"], F64)
     b = rmsnorm(h, w["norm2"], cfg.rms_eps)
     gate = b @ np.asarray(w["wg"], F64)
@@ -149,15 +162,17 @@ class Target:
     def embed(self, ids):
         return np.asarray(self.w["embed"], F64)[np.asarray(ids, np.int64)]
 
-    def forward(self, x, start_pos):
+    def forward(self, x, start_pos, pos=None, visible=None):
         """Run the rows x [m][d] (already embedded) at positions start_pos..start_pos+m-1
         through all layers; returns the final-layer features after the final norm [m][d]
-        (the tensor the LM head reads; this is what is used as f_fused)."""
+        (the tensor the LM head reads; this is what is used as f_fused).
+        pos / visible: explicit positions and visibility for the rows of a draft tree."""
         m = x.shape[0]
-        pos = np.arange(start_pos, start_pos + m)
+        if pos is None:
+            pos = np.arange(start_pos, start_pos + m)
         h = np.asarray(x, F64)
         for i in range(self.cfg.n_layers):
-            h = decoder_layer(h, self.w["layers"][i], self.caches[i], pos, self.cfg)
+            h = decoder_layer(h, self.w["layers"][i], self.caches[i], pos, self.cfg, visible)
         return rmsnorm(h, self.w["final_norm"], self.cfg.rms_eps)
 
     def logits(self, f):
@@ -166,6 +181,10 @@ class Target:
     def truncate(self, n):
         for c in self.caches:
             c.truncate(n)
+
+    def keep(self, idx):
+        for c in self.caches:
+            c.keep(idx)
 
 
 class Drafter:
@@ -182,10 +201,11 @@ class Drafter:
     def kv_len(self):
         return len(self.cache)
 
-    def forward(self, u, start_pos):
+    def forward(self, u, start_pos, pos=None, visible=None):
         m = u.shape[0]
-        pos = np.arange(start_pos, start_pos + m)
-        return decoder_layer(u, self.w["draft_layer"], self.cache, pos, self.cfg)
+        if pos is None:
+            pos = np.arange(start_pos, start_pos + m)
+        return decoder_layer(u, self.w["draft_layer"], self.cache, pos, self.cfg, visible)
 
     def truncate(self, n):
         self.cache.truncate(n)

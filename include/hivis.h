@@ -153,13 +153,57 @@ int hivis_draft_sample(hivis_ctx *ctx, int32_t K, float temperature, const float
 int hivis_accept_sample(hivis_ctx *ctx, float temperature, const float *u_accept, const float *u_resample,
                         int32_t *n_accepted, int32_t *tokens);
 
+/* ---- the same cycle with a draft TREE instead of a chain (section 4, inference setting: a top-k tree expanded to a
+ * fixed depth, the candidates with the highest cumulative probability verified in one pass; section 2.1 names the tree
+ * structure).  Greedy (T = 0), batch 1 only.  The three calls replace hivis_draft / hivis_verify / hivis_accept in a
+ * cycle; chain and tree cycles may alternate on one context. ---- */
+
+/* Builds the pool and picks the candidates.  Level 1: the top_k most probable tokens after the drafter's pending
+ * hidden state, scored by log-probability.  Level j+1 (j = 1..depth-1): the top_k best-scored nodes of level j go
+ * through the drafter as one pass of top_k rows (fusion input with the residual of depth j; each row sees the
+ * text-only cache, its ancestors and itself) and each contributes its top_k most probable continuations, scored
+ * parent score + log-probability.  Pool = top_k + (depth-1) top_k^2 nodes, indexed level by level, expanded row by
+ * expanded row, rank by rank.  Candidates = the n_nodes best-scored pool nodes (ties: lower pool index), kept in pool
+ * order; verify row i (1..n_nodes) is candidate i-1, row 0 the last known token.
+ * Limits: top_k <= 16, depth <= 16, pool <= 2048, (depth-1) top_k <= 64, n_nodes <= min(pool, 63).
+ * State READY -> TREE_DRAFTED.  Errors: ESTATE, EINVAL (limits, batch != 1), ECAP, EHIP. */
+int hivis_tree_draft(hivis_ctx *ctx, int32_t top_k, int32_t depth, int32_t n_nodes);
+
+/* Test hook, the tree analogue of hivis_set_drafts: plants the candidates instead of drafting them.  tokens[i] /
+ * parents[i] describe verify row i+1; parents are row indices (0 = the root) smaller than the row's own.
+ *   tokens, parents: [n_nodes] int32 host.  State READY -> TREE_DRAFTED.  Errors: ESTATE, EINVAL, ECAP, EHIP. */
+int hivis_tree_set(hivis_ctx *ctx, int32_t n_nodes, const int32_t *tokens, const int32_t *parents);
+
+/* One target pass over the n_nodes + 1 rows: a row sits at position v + l + depth and attends to the whole
+ * visual + text cache, its ancestors and itself.  State TREE_DRAFTED -> TREE_VERIFIED.  Errors: ESTATE, EHIP. */
+int hivis_tree_verify(hivis_ctx *ctx);
+
+/* Greedy acceptance on the tree: from the root, the child whose token equals the target's greedy token at the current
+ * row is followed until there is none; tokens[0..n-1] are the followed tokens, tokens[n] the target's own token at the
+ * last row.  The target cache keeps the followed rows (moved next to the root's), the drafter drops its tree rows and
+ * is re-fed the true features of the path, as hivis_accept does.  Synchronises.  State TREE_VERIFIED -> READY.
+ *   n_accepted: [1] int32 host.   tokens: [depth+1] int32 host (entries beyond n are -1).
+ * Errors: ESTATE, EINVAL, EHIP. */
+int hivis_tree_accept(hivis_ctx *ctx, int32_t *n_accepted, int32_t *tokens);
+
 /* ---- test / measurement hooks (all synchronise) ---- */
 
-/* which = 0: logits of the last verify, [B][K+1][vocab]; which = 1: logits of the last draft round,
+/* The last tree, any pointer may be null (host arrays): pool_tokens / pool_parents (pool index, -1 = root) /
+ * pool_scores [pool]; expand [depth-1][top_k] pool indices of the expanded rows; selected [n_nodes] candidates;
+ * row_tokens / row_parents (row index, -1 for the root) / row_depths [n_nodes+1]; target_tokens [n_nodes+1] (after
+ * hivis_tree_verify only). */
+int hivis_tree_get(hivis_ctx *ctx, int32_t *pool_tokens, int32_t *pool_parents, float *pool_scores, int32_t *expand,
+                   int32_t *selected, int32_t *row_tokens, int32_t *row_parents, int32_t *row_depths, int32_t *target_tokens);
+
+/* Drafter logits behind the last tree: row 0 = the pending hidden state, row 1 + (j-1) top_k + r = expanded row r of
+ * level j.  out: [1 + (depth-1) top_k][vocab] float32, host. */
+int hivis_tree_get_logits(hivis_ctx *ctx, float *out);
+
+/* which = 0: logits of the last verify, [B][K+1][vocab] (tree: [n_nodes+1][vocab]); which = 1: logits of the last draft round,
  * [K][B][vocab]; which = 2: logits that chose x_{l+1} at prefill, [B][vocab].  out: float32, host. */
 int hivis_get_logits(hivis_ctx *ctx, int32_t which, float *out);
 
-/* which = 0: post-final-norm target features g of the last verify, [B][K+1][d];
+/* which = 0: post-final-norm target features g of the last verify, [B][K+1][d] (tree: [n_nodes+1][d]);
  * which = 1: the drafter's pending hidden state f'_1 for the next round, [B][d].  out: float32, host. */
 int hivis_get_hidden(hivis_ctx *ctx, int32_t which, float *out);
 

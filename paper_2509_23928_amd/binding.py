@@ -62,6 +62,12 @@ def load_library(path=LIB_PATH):
         "hivis_prefill_sample": (C.c_int, [P, P, I32, P, I32, C.c_float, P, P]),
         "hivis_draft_sample": (C.c_int, [P, I32, C.c_float, P]),
         "hivis_accept_sample": (C.c_int, [P, C.c_float, P, P, P, P]),
+        "hivis_tree_draft": (C.c_int, [P, I32, I32, I32]),
+        "hivis_tree_set": (C.c_int, [P, I32, P, P]),
+        "hivis_tree_verify": (C.c_int, [P]),
+        "hivis_tree_accept": (C.c_int, [P, P, P]),
+        "hivis_tree_get": (C.c_int, [P, P, P, P, P, P, P, P, P, P]),
+        "hivis_tree_get_logits": (C.c_int, [P, P]),
         "hivis_get_logits": (C.c_int, [P, I32, P]),
         "hivis_get_hidden": (C.c_int, [P, I32, P]),
         "hivis_kv_lengths": (C.c_int, [P, P, P]),
@@ -82,7 +88,7 @@ def load_library(path=LIB_PATH):
 
 
 EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_set_drafts",
-                    "hivis_verify", "hivis_accept", "hivis_prefill_sample", "hivis_draft_sample", "hivis_accept_sample", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
+                    "hivis_verify", "hivis_accept", "hivis_prefill_sample", "hivis_draft_sample", "hivis_accept_sample", "hivis_tree_draft", "hivis_tree_set", "hivis_tree_verify", "hivis_tree_accept", "hivis_tree_get", "hivis_tree_get_logits", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
                     "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes",
                     "hivis_last_error", "hivis_version")
 
@@ -217,6 +223,62 @@ class Hivis:
         t = np.zeros((self.B, self.k_max + 1), np.int32)
         self._check(self.lib.hivis_accept_sample(self.ctx, float(temperature), _ptr(ua), _ptr(ur), _ptr(n), _ptr(t)))
         return n, t
+
+    # -- draft tree (batch 1) -----------------------------------------------------------
+    def tree_draft(self, top_k, depth, n_nodes):
+        self._check(self.lib.hivis_tree_draft(self.ctx, int(top_k), int(depth), int(n_nodes)))
+        self.tree_shape = (int(top_k), int(depth), int(n_nodes))
+        self.K = int(n_nodes)            # rows of the coming verify pass = n_nodes + 1 (get_logits / get_hidden shapes)
+
+    def tree_set(self, tokens, parents):
+        """Plants the candidates: tokens / parents [n_nodes], parents as verify-row indices (0 = root)."""
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        par = np.ascontiguousarray(parents, dtype=np.int32)
+        self._check(self.lib.hivis_tree_set(self.ctx, len(tok), _ptr(tok), _ptr(par)))
+        depth = {0: 0}
+        for i, p in enumerate(par, start=1):
+            depth[i] = depth[int(p)] + 1
+        self.tree_shape = (0, max(depth.values()), len(tok))
+        self.K = len(tok)
+
+    def tree_verify(self):
+        self._check(self.lib.hivis_tree_verify(self.ctx))
+
+    def tree_accept(self):
+        """Returns (n_accepted, tokens [depth+1], -1 beyond n+1 entries)."""
+        n = np.zeros(1, np.int32)
+        t = np.zeros(self.tree_shape[1] + 1, np.int32)
+        self._check(self.lib.hivis_tree_accept(self.ctx, _ptr(n), _ptr(t)))
+        return int(n[0]), t
+
+    def tree_get(self, verified=False):
+        """The last tree as a dict of host arrays (target_tokens only if verified)."""
+        k, depth, N = self.tree_shape
+        P = k + (depth - 1) * k * k
+        if k == 0:        # planted tree: rows only
+            out = {"row_tokens": np.zeros(N + 1, np.int32), "row_parents": np.zeros(N + 1, np.int32), "row_depths": np.zeros(N + 1, np.int32)}
+            tt = np.zeros(N + 1, np.int32) if verified else None
+            self._check(self.lib.hivis_tree_get(self.ctx, None, None, None, None, None, _ptr(out["row_tokens"]), _ptr(out["row_parents"]),
+                                                _ptr(out["row_depths"]), _ptr(tt)))
+            if verified:
+                out["target_tokens"] = tt
+            return out
+        out = {"pool_tokens": np.zeros(P, np.int32), "pool_parents": np.zeros(P, np.int32), "pool_scores": np.zeros(P, np.float32),
+               "expand": np.zeros((depth - 1, k), np.int32), "selected": np.zeros(N, np.int32), "row_tokens": np.zeros(N + 1, np.int32),
+               "row_parents": np.zeros(N + 1, np.int32), "row_depths": np.zeros(N + 1, np.int32)}
+        tt = np.zeros(N + 1, np.int32) if verified else None
+        self._check(self.lib.hivis_tree_get(self.ctx, _ptr(out["pool_tokens"]), _ptr(out["pool_parents"]), _ptr(out["pool_scores"]),
+                                            _ptr(out["expand"]) if depth > 1 else None, _ptr(out["selected"]), _ptr(out["row_tokens"]),
+                                            _ptr(out["row_parents"]), _ptr(out["row_depths"]), _ptr(tt)))
+        if verified:
+            out["target_tokens"] = tt
+        return out
+
+    def tree_get_logits(self):
+        k, depth, _ = self.tree_shape
+        out = np.zeros((1 + (depth - 1) * k, self.cfg.vocab), np.float32)
+        self._check(self.lib.hivis_tree_get_logits(self.ctx, _ptr(out)))
+        return out
 
     # -- hooks -----------------------------------------------------------------------
     def get_logits(self, which):

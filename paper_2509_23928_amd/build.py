@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libhivis.so")
 SOURCES = [os.path.join(HERE, "csrc", "hivis.hip")]
-HEADERS = [os.path.join(HERE, "csrc", "hivis_kernels.h"), os.path.join(ROOT, "include", "hivis.h")]
+HEADERS = [os.path.join(HERE, "csrc", n) for n in ("hivis_kernels.h", "hivis_fused.h", "hivis_tree.h")] + [os.path.join(ROOT, "include", "hivis.h")]
 
 
 def hipcc_path():

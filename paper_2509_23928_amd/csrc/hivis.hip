@@ -3,6 +3,7 @@
 #include "hivis.h"
 #include "hivis_kernels.h"
 #include "hivis_fused.h"
+#include "hivis_tree.h"
 
 #include <hip/hip_ext.h>
 #include <algorithm>
@@ -18,9 +19,13 @@ using namespace hivis;
 
 namespace {
 
-enum State { ST_CREATED = 0, ST_READY, ST_DRAFTED, ST_VERIFIED };
+enum State { ST_CREATED = 0, ST_READY, ST_DRAFTED, ST_VERIFIED, ST_TREE_DRAFTED, ST_TREE_VERIFIED };
 
-constexpr int MAX_ROWS = 32;   // rows per pass (verify rows B*(K+1), prefill chunk)
+constexpr int MAX_ROWS = 64;        // rows per pass that the activation buffers hold (tree verify: root + 63 candidates)
+constexpr int CHAIN_MAX_ROWS = 32;  // chain verify rows B*(K+1); prefill chunk; rows per launch of the skinny GEMM
+
+// Rows of a draft tree (null pointers: ordinary causal rows)
+struct TreeRows { const int* pos_delta = nullptr; const unsigned long long* mask = nullptr; };
 
 struct LayerDev {
     void* norm1 = nullptr; void* norm2 = nullptr;   // [d] storage dtype
@@ -83,6 +88,14 @@ struct hivis_ctx {
     bool persistent = false;             // HIVIS_PERSISTENT=1: one cooperative launch per pass instead of one launch per phase
     std::map<int, Program> programs;     // key = kind * 64 + K
     unsigned long long* prof = nullptr; int prof_left = 0;   // developer aid: HIVIS_PROF=n dumps per-phase times of n verify passes
+
+    // draft tree (batch 1): device arrays are allocated by the first hivis_tree_draft call, for the limits below
+    hivis::TreeDev tree{}; bool tree_ready = false;
+    int tk = 0, tdepth = 0, tn = 0;                       // top-k, depth, candidates of the current tree
+    int vrows = 0;                                        // rows of the last verify pass (chain: B*(K+1); tree: N+1)
+    float *tH = nullptr, *tlogits = nullptr, *tcat = nullptr, *troll = nullptr;   // hidden rows, their logits, level inputs, re-feed inputs
+    void** kv_ptrs = nullptr; void* kv_staging = nullptr;
+    int32_t* h_tree_result = nullptr;                     // pinned [1 + TREE_MAX_DEPTH + 1]
 
     // timing
     int ktime_epi = -1;                                  // GEMM epilogue kind whose verify launches are event-timed (-1: none)
@@ -179,6 +192,11 @@ static inline int row_chunks(int rows) { return rows >= 256 ? 1 : std::max(1, st
 template <typename WT>
 int gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy, int epi) {
     if (M < 1 || M > MAX_ROWS) return fail(c, HIVIS_EINVAL, "gemm rows %d out of range", M);
+    if (M > CHAIN_MAX_ROWS) {            // wider passes (tree verify): one launch per 32 rows
+        for (int r0 = 0; r0 < M; r0 += CHAIN_MAX_ROWS)
+            if (int rc = gemm<WT>(c, A + (size_t)r0 * lda, lda, std::min(CHAIN_MAX_ROWS, M - r0), K, Wp, N, Y + (size_t)r0 * ldy, ldy, epi)) return rc;
+        return HIVIS_OK;
+    }
     const int ntiles = N / 16;
     const int grid = std::min(ntiles, c->num_cu);
     constexpr int ROWS = WTraits<WT>::ROWS;
@@ -213,7 +231,7 @@ int gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, i
 
 template <typename WT>
 int attention(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int* base, int offset, int seq0, int nseq,
-              int m, int max_keys, float* out, int ldo) {
+              int m, int max_keys, float* out, int ldo, const unsigned long long* tmask = nullptr) {
     typedef typename KVType<WT>::type KT;
     const hivis_config& g = c->cfg;
     AttnShape sh{};
@@ -222,7 +240,7 @@ int attention(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int*
     if (m >= ATT_RMAX) { sh.mi = ATT_RMAX; sh.gh = 1; }
     else { sh.mi = m; sh.gh = std::max(1, std::min(group, ATT_RMAX / m)); }
     sh.n_hblk = (group + sh.gh - 1) / sh.gh; sh.n_rblk = (m + sh.mi - 1) / sh.mi;
-    sh.seq0 = seq0; sh.offset = offset; sh.maxL = kv.maxL; sh.ldq = ldq; sh.nwaves = 4;
+    sh.seq0 = seq0; sh.offset = offset; sh.maxL = kv.maxL; sh.ldq = ldq; sh.nwaves = 4; sh.tmask = tmask;
     const int items = nseq * g.n_kv_heads * sh.n_hblk * sh.n_rblk;
     // enough workgroups to occupy the chip, at most one 64-key tile per wavefront slot
     const int tiles = (max_keys + 63) / 64;
@@ -249,13 +267,13 @@ AttnShape fused_attn_shape(hivis_ctx* c, int nseq, int m, int offset, int maxL, 
 // keys, no key split), launched once over all items.  Rows of sequence seq0 + s sit at positions base[seq0 + s] + offset + i.
 template <typename WT>
 int attention_rows_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int* base, int offset, int seq0, int nseq, int m,
-                        float* out, int ldo) {
+                        float* out, int ldo, const unsigned long long* tmask = nullptr) {
     const hivis_config& g = c->cfg;
     int items = 0;
     Phase ph{};
     ph.type = PH_ATTN;
     ph.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, ldq, &items);
-    ph.att.seq0 = seq0; ph.att.nsplit = 1;
+    ph.att.seq0 = seq0; ph.att.nsplit = 1; ph.att.tmask = tmask;
     ph.att_items = items;
     ph.A = q; ph.kc = kv.k; ph.vc = kv.v; ph.maxL = kv.maxL; ph.base = base; ph.offset = offset;
     ph.Y = out; ph.ldy = ldo; ph.ws = nullptr; ph.cnt = nullptr;
@@ -271,16 +289,16 @@ int attention_rows_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, 
 // to be added by the caller (the next layer's first norm, or a final norm/add, fuses that addition).
 template <typename WT>
 int layer_forward(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, const float* pending, const int* base,
-                  int offset, int seq0, int nseq, int m, int max_keys) {
+                  int offset, int seq0, int nseq, int m, int max_keys, TreeRows tr = TreeRows()) {
     typedef typename KVType<WT>::type KT;
     const hivis_config& g = c->cfg;
     const int M = nseq * m, d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn;
     const int nqkv = qd + 2 * kd;
     hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, pending, d, (const WT*)L.norm1, c->a, d, d, g.rms_eps);
     if (int rc = gemm<WT>(c, c->a, d, M, d, L.wqkv, nqkv, c->qkv, nqkv, EPI_STORE)) return rc;
-    hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
-    if (c->fused && std::is_same<KT, f16_t>::value) { if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd)) return rc; }
-    else if (int rc = attention<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, max_keys, c->att, qd)) return rc;
+    hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta);
+    if (c->fused && std::is_same<KT, f16_t>::value) { if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd, tr.mask)) return rc; }
+    else if (int rc = attention<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, max_keys, c->att, qd, tr.mask)) return rc;
     if (int rc = gemm<WT>(c, c->att, qd, M, qd, L.wo, d, c->proj, d, EPI_STORE)) return rc;
     hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, (const float*)c->proj, d, (const WT*)L.norm2, c->a, d, d, g.rms_eps);
     if (int rc = gemm<WT>(c, c->a, d, M, d, L.wgu, 2 * F, c->gu, 2 * F, EPI_STORE)) return rc;
@@ -294,13 +312,13 @@ int layer_forward(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, co
 // for rows >= first_out_row (pointer arithmetic done by the caller through first_out_row).
 template <typename WT>
 int target_forward(hivis_ctx* c, int seq0, int nseq, int m, const int* base, int offset, int max_keys, float* out, int ldo,
-                   int first_out_row) {
+                   int first_out_row, TreeRows tr = TreeRows()) {
     const hivis_config& g = c->cfg;
     const int M = nseq * m;
     const float* pending = nullptr;
     for (int l = 0; l < g.n_layers; ++l) {
         // KV of layer l for all sequences
-        if (int rc = layer_forward<WT>(c, c->layers[l], c->tkv[l], c->x, pending, base, offset, seq0, nseq, m, max_keys)) return rc;
+        if (int rc = layer_forward<WT>(c, c->layers[l], c->tkv[l], c->x, pending, base, offset, seq0, nseq, m, max_keys, tr)) return rc;
         pending = c->proj;
     }
     const int nout = M - first_out_row;
@@ -314,12 +332,12 @@ int target_forward(hivis_ctx* c, int seq0, int nseq, int m, const int* base, int
 // Drafter: fusion FC on cat rows [M][2d] + rho_idx, then its single layer; output rows (h + mlp delta) to out.
 template <typename WT>
 int drafter_forward(hivis_ctx* c, const float* cat, int seq0, int nseq, int m, int rho_idx, int offset, int max_keys,
-                    float* out, int ldo) {
+                    float* out, int ldo, TreeRows tr = TreeRows()) {
     const hivis_config& g = c->cfg;
     const int M = nseq * m, d = g.d;
     if (int rc = gemm<WT>(c, cat, 2 * d, M, 2 * d, c->fuse_w, d, c->u, d, EPI_STORE)) return rc;
     hipLaunchKernelGGL((add_rho_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->u, d, (const WT*)c->rho, rho_idx, d);
-    if (int rc = layer_forward<WT>(c, c->draft, c->dkv, c->u, nullptr, c->dlen, offset, seq0, nseq, m, max_keys)) return rc;
+    if (int rc = layer_forward<WT>(c, c->draft, c->dkv, c->u, nullptr, c->dlen, offset, seq0, nseq, m, max_keys, tr)) return rc;
     hipLaunchKernelGGL(add_rows_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->u, d, (const float*)c->proj, d, out, ldo, d);
     HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;
@@ -775,8 +793,8 @@ int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_
             if (int rc = prefill_target_tall<WT>(c, b, v, l)) return rc;
             continue;
         }
-        for (int p0 = 0; p0 < total; p0 += MAX_ROWS) {
-            const int m = std::min(MAX_ROWS, total - p0);
+        for (int p0 = 0; p0 < total; p0 += CHAIN_MAX_ROWS) {
+            const int m = std::min(CHAIN_MAX_ROWS, total - p0);
             hipLaunchKernelGGL((prefill_rows_kernel<WT>), dim3(m), dim3(256), 0, c->stream, (const WT*)c->vis + (size_t)b * g.max_vis * d, v,
                                (const WT*)c->embed, (const int32_t*)(c->text + (size_t)b * c->text_stride), p0, c->x, d);
             const int first_out = std::max(0, v - p0);       // rows of this chunk before the first text row produce no feature
@@ -791,8 +809,8 @@ int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_
     else hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)c->logits_p, g.vocab, c->text + l, c->text_stride);
     // drafter prefill over the l text positions: rows [f^j ; Embed(x_{j+1})] + rho_0
     for (int b = 0; b < B; ++b) {
-        for (int j0 = 0; j0 < l; j0 += MAX_ROWS) {
-            const int m = std::min(MAX_ROWS, l - j0);
+        for (int j0 = 0; j0 < l; j0 += CHAIN_MAX_ROWS) {
+            const int m = std::min(CHAIN_MAX_ROWS, l - j0);
             hipLaunchKernelGGL((fuse_rows_kernel<WT>), dim3(m), dim3(256), 0, c->stream, (const float*)(c->feat + (size_t)b * g.max_text * d),
                                (const WT*)c->embed, (const int32_t*)(c->text + (size_t)b * c->text_stride), j0, c->catT, d);
             if (int rc = drafter_forward<WT>(c, c->catT, b, 1, m, 0, j0, j0 + m, c->dout, d)) return rc;
@@ -915,6 +933,120 @@ int do_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens, bool sample) {
     return HIVIS_OK;
 }
 
+
+// ---- draft tree (batch 1) ---------------------------------------------------------------------------
+// Device arrays of the tree, sized for the library's limits, allocated on the first tree call.
+template <typename WT>
+int tree_setup(hivis_ctx* c) {
+    typedef typename KVType<WT>::type KT;
+    if (c->tree_ready) return HIVIS_OK;
+    const hivis_config& g = c->cfg;
+    const int d = g.d, V = g.vocab, kd = g.n_kv_heads * g.head_dim;
+    TreeDev& t = c->tree;
+    int rc;
+    const int P = TREE_MAX_POOL, R = TREE_MAX_ROWS, D = TREE_MAX_DEPTH;
+    if ((rc = dev_alloc(c, &t.pool_tok, P)) || (rc = dev_alloc(c, &t.pool_par, P)) || (rc = dev_alloc(c, &t.pool_score, P)) ||
+        (rc = dev_alloc(c, &t.pool_depth, P)) || (rc = dev_alloc(c, &t.pool_hid, P)) || (rc = dev_alloc(c, &t.pool_slot, P)) ||
+        (rc = dev_alloc(c, &t.expand, R)) || (rc = dev_alloc(c, &t.dmask, R)) || (rc = dev_alloc(c, &t.dpos, R)) ||
+        (rc = dev_alloc(c, &t.sel, R)) || (rc = dev_alloc(c, &t.row_par, R)) || (rc = dev_alloc(c, &t.row_depth, R)) ||
+        (rc = dev_alloc(c, &t.vmask, R)) || (rc = dev_alloc(c, &t.ttok, R)) || (rc = dev_alloc(c, &t.path, D + 1)) ||
+        (rc = dev_alloc(c, &t.next_tok, D + 1)) || (rc = dev_alloc(c, &t.result, D + 2)))
+        return rc;
+    t.row_tok = c->row_tok;
+    if ((rc = dev_alloc(c, &c->tH, (size_t)(R + 1) * d))) return rc;
+    if ((rc = dev_alloc(c, &c->tlogits, (size_t)(R + 1) * V))) return rc;
+    if ((rc = dev_alloc(c, &c->tcat, (size_t)TREE_MAX_TOPK * 2 * d))) return rc;
+    if ((rc = dev_alloc(c, &c->troll, (size_t)(D + 1) * 2 * d))) return rc;
+    // cache pointers of all target layers (keys, values) for the compaction kernels, and their staging rows
+    std::vector<void*> ptrs;
+    for (int l = 0; l < g.n_layers; ++l) { ptrs.push_back(c->tkv[l].k); ptrs.push_back(c->tkv[l].v); }
+    if ((rc = dev_alloc(c, &c->kv_ptrs, ptrs.size()))) return rc;
+    HIP_TRY(c, hipMemcpy(c->kv_ptrs, ptrs.data(), ptrs.size() * sizeof(void*), hipMemcpyHostToDevice));
+    { KT* st; if ((rc = dev_alloc(c, &st, (size_t)g.n_layers * 2 * D * kd))) return rc; c->kv_staging = st; }
+    HIP_TRY(c, hipHostMalloc((void**)&c->h_tree_result, (D + 2) * sizeof(int32_t), hipHostMallocDefault));
+    c->tree_ready = true;
+    return HIVIS_OK;
+}
+
+// Pool of k + (depth-1) k^2 nodes, level by level; then the N best-scored candidates and their verify rows.
+template <typename WT>
+int do_tree_draft(hivis_ctx* c, int k, int depth, int N) {
+    const hivis_config& g = c->cfg;
+    const int d = g.d, V = g.vocab;
+    if (int rc = tree_setup<WT>(c)) return rc;
+    PhaseTimer pt(c, 1);
+    const TreeDev& t = c->tree;
+    // hidden row 0 = the drafter's pending state f'_1; its distribution gives level 1
+    hipLaunchKernelGGL(copy_rows_kernel, dim3(1), dim3(256), 0, c->stream, (const float*)c->catD, 2 * d, c->tH, d, d);
+    if (int rc = gemm<WT>(c, c->tH, d, 1, d, c->lm_head, V, c->tlogits, V, EPI_STORE)) return rc;
+    hipLaunchKernelGGL(tree_children_kernel, dim3(1), dim3(TOPK_NT), 0, c->stream, (const float*)c->tlogits, V, k, 0, (const int32_t*)nullptr, 1, 0, t);
+    int lo = 0, n = k;
+    for (int j = 1; j < depth; ++j) {
+        const int n_prev = (j - 1) * k, row0 = 1 + n_prev;
+        const int32_t* E = t.expand + n_prev;
+        hipLaunchKernelGGL(tree_expand_kernel, dim3(1), dim3(256), 0, c->stream, lo, n, k, n_prev, j, t);
+        hipLaunchKernelGGL((tree_cat_kernel<WT>), dim3(k), dim3(256), 0, c->stream, E, t, (const float*)c->tH, (const WT*)c->embed, c->tcat, d);
+        TreeRows tr; tr.pos_delta = t.dpos + n_prev; tr.mask = t.dmask + n_prev;
+        if (int rc = drafter_forward<WT>(c, c->tcat, 0, 1, k, std::min(j, g.n_resid - 1), n_prev, c->h_dlen[0] + n_prev + k,
+                                         c->tH + (size_t)row0 * d, d, tr)) return rc;
+        if (int rc = gemm<WT>(c, c->tH + (size_t)row0 * d, d, k, d, c->lm_head, V, c->tlogits + (size_t)row0 * V, V, EPI_STORE)) return rc;
+        const int first = lo + n;
+        hipLaunchKernelGGL(tree_children_kernel, dim3(k), dim3(TOPK_NT), 0, c->stream, (const float*)(c->tlogits + (size_t)row0 * V), V, k, first, E, j + 1, row0, t);
+        lo = first; n = k * k;
+    }
+    hipLaunchKernelGGL(tree_select_kernel, dim3(1), dim3(1024), 0, c->stream, lo + n, N, (const int32_t*)c->text, (const int*)c->dlen, t);
+    HIP_TRY(c, hipGetLastError());
+    pt.stop();
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int do_tree_verify(hivis_ctx* c) {
+    const hivis_config& g = c->cfg;
+    const int d = g.d, V = g.vocab, M = c->tn + 1;
+    PhaseTimer pt(c, 2);
+    const TreeDev& t = c->tree;
+    hipLaunchKernelGGL((gather_rows_kernel<WT>), dim3(M), dim3(256), 0, c->stream, (const WT*)c->embed, (const int32_t*)t.row_tok, 1, c->x, d, d);
+    TreeRows tr; tr.pos_delta = t.row_depth; tr.mask = t.vmask;
+    if (int rc = target_forward<WT>(c, 0, 1, M, c->tlen, 0, c->h_tlen[0] + M, c->catT, 2 * d, 0, tr)) return rc;
+    if (int rc = gemm<WT>(c, c->catT, 2 * d, M, d, c->lm_head, V, c->logits_v, V, EPI_STORE)) return rc;
+    hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->logits_v, V, t.ttok, 1);
+    HIP_TRY(c, hipGetLastError());
+    pt.stop();
+    c->vrows = M;
+    return HIVIS_OK;
+}
+
+template <typename WT>
+int do_tree_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
+    typedef typename KVType<WT>::type KT;
+    const hivis_config& g = c->cfg;
+    const int d = g.d, N = c->tn, depth = c->tdepth;
+    PhaseTimer pt(c, 3);
+    const TreeDev& t = c->tree;
+    hipLaunchKernelGGL(tree_accept_kernel, dim3(1), dim3(64), 0, c->stream, N, depth, c->text, (const int*)c->dlen, t);
+    // target cache: the followed rows move to the slots right after the root's
+    for (int scatter = 0; scatter < 2; ++scatter)
+        hipLaunchKernelGGL((tree_kv_gather_kernel<KT>), dim3(depth, 2 * g.n_layers), dim3(256), 0, c->stream, (KT* const*)c->kv_ptrs, c->tkv[0].maxL,
+                           g.n_kv_heads, g.head_dim, (const int*)c->tlen, (const int32_t*)t.result, (const int32_t*)t.path, depth, (KT*)c->kv_staging, scatter);
+    // drafter: every tree row is dropped (its length never advanced); depth+1 rows rebuilt from the true features
+    hipLaunchKernelGGL((tree_roll_cat_kernel<WT>), dim3(depth + 1), dim3(256), 0, c->stream, (const float*)c->catT, 2 * d, (const int32_t*)t.path,
+                       (const int32_t*)t.next_tok, (const WT*)c->embed, c->troll, d);
+    if (int rc = drafter_forward<WT>(c, c->troll, 0, 1, depth + 1, 0, 0, c->h_dlen[0] + depth + 1, c->dout, d)) return rc;
+    hipLaunchKernelGGL(tree_finish_kernel, dim3(1), dim3(256), 0, c->stream, (const float*)c->dout, (const int32_t*)t.result, c->catD, c->dlen, c->tlen, d);
+    HIP_TRY(c, hipGetLastError());
+    pt.stop();
+    HIP_TRY(c, hipMemcpyAsync(c->h_tree_result, t.result, (depth + 2) * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    resolve_phase_events(c);
+    const int n = c->h_tree_result[0];
+    c->h_tlen[0] += n + 1; c->h_dlen[0] += n + 1;
+    *n_accepted = n;
+    memcpy(tokens, c->h_tree_result + 1, (size_t)(depth + 1) * sizeof(int32_t));
+    c->state = ST_READY;
+    return HIVIS_OK;
+}
+
 template <typename WT>
 int do_create(hivis_ctx* c, const hivis_weights* w) {
     const hivis_config& g = c->cfg;
@@ -992,7 +1124,7 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     // attention workspace: (items * nsplit) work groups x 4 wave slots x RMAX rows x (hd + 2) floats, where
     // items * nsplit <= 2 * num_cu + items and items <= max(2, B) * n_q_heads
     {
-        size_t max_items = (size_t)std::max(2, B) * g.n_q_heads;
+        size_t max_items = (size_t)std::max({2, B, MAX_ROWS / ATT_RMAX}) * g.n_q_heads;
         if (c->pf_rows) max_items = std::max(max_items, (size_t)g.n_q_heads * ((c->pf_rows + ATT_RMAX - 1) / ATT_RMAX));
         c->attn_ws_floats = (2 * (size_t)c->num_cu + max_items) * 4 * ATT_RMAX * (g.head_dim + 2);
         if ((rc = dev_alloc(c, &c->attn_ws, c->attn_ws_floats))) return rc;
@@ -1027,7 +1159,7 @@ int check_config(const hivis_config* g, std::string& why) {
     if (g->n_q_heads % g->n_kv_heads) BAD("n_q_heads %% n_kv_heads != 0");
     if (g->d % al || (g->n_q_heads * g->head_dim) % al || (g->n_kv_heads * g->head_dim) % al || g->ffn % al) BAD("d, q_dim, kv_dim, ffn must be multiples of %d", al);
     if (g->vocab % 16) BAD("vocab must be a multiple of 16");
-    if (g->batch < 1 || g->k_max < 1 || g->batch * (g->k_max + 1) > MAX_ROWS) BAD("batch*(k_max+1) must be in 2..%d", MAX_ROWS);
+    if (g->batch < 1 || g->k_max < 1 || g->batch * (g->k_max + 1) > CHAIN_MAX_ROWS) BAD("batch*(k_max+1) must be in 2..%d", CHAIN_MAX_ROWS);
     if (g->max_vis < 0 || g->max_text < 2 + g->k_max) BAD("capacity too small");
     if (g->n_resid < 1) BAD("n_resid must be >= 1");
     if (!(g->rope_theta > 1.f) || !(g->rms_eps >= 0.f)) BAD("rope_theta / rms_eps out of range");
@@ -1070,6 +1202,7 @@ int hivis_destroy(hivis_ctx* c) {
     for (auto& kv : c->programs) delete kv.second.host;
     for (hipEvent_t e : c->pev) (void)hipEventDestroy(e);
     if (c->h_result) (void)hipHostFree(c->h_result);
+    if (c->h_tree_result) (void)hipHostFree(c->h_tree_result);
     for (hipEvent_t e : c->kev) (void)hipEventDestroy(e);
     delete c;
     return HIVIS_OK;
@@ -1171,7 +1304,7 @@ int hivis_verify(hivis_ctx* c) {
     if (c->state != ST_DRAFTED) return fail(c, HIVIS_ESTATE, "hivis_verify needs drafts");
     int rc = DISPATCH(c, do_verify, c);
     if (rc) return rc;
-    c->state = ST_VERIFIED;
+    c->state = ST_VERIFIED; c->vrows = c->cfg.batch * (c->K + 1);
     return HIVIS_OK;
 }
 
@@ -1197,11 +1330,106 @@ int hivis_accept_sample(hivis_ctx* c, float temperature, const float* u_accept, 
     return DISPATCH(c, do_accept, c, n_accepted, tokens, true);
 }
 
+int hivis_tree_draft(hivis_ctx* c, int32_t top_k, int32_t depth, int32_t n_nodes) {
+    if (!c) return HIVIS_EINVAL;
+    const hivis_config& g = c->cfg;
+    if (g.batch != 1) return fail(c, HIVIS_EINVAL, "tree drafting needs batch 1 (got %d)", g.batch);
+    if (c->state != ST_READY) return fail(c, HIVIS_ESTATE, "hivis_tree_draft needs a prefilled/accepted context");
+    if (top_k < 1 || top_k > TREE_MAX_TOPK || depth < 1 || depth > TREE_MAX_DEPTH) return fail(c, HIVIS_EINVAL, "top_k=%d outside [1,%d] or depth=%d outside [1,%d]", top_k, TREE_MAX_TOPK, depth, TREE_MAX_DEPTH);
+    const int P = top_k + (depth - 1) * top_k * top_k;
+    if (P > TREE_MAX_POOL || (depth - 1) * top_k > TREE_MAX_ROWS) return fail(c, HIVIS_EINVAL, "tree too large: pool %d > %d or expanded rows %d > %d", P, TREE_MAX_POOL, (depth - 1) * top_k, TREE_MAX_ROWS);
+    if (n_nodes < 1 || n_nodes > P || n_nodes + 1 > TREE_MAX_ROWS) return fail(c, HIVIS_EINVAL, "n_nodes=%d outside [1, min(pool %d, %d)]", n_nodes, P, TREE_MAX_ROWS - 1);
+    if (c->h_dlen[0] + std::max((depth - 1) * top_k, depth + 1) + 2 > g.max_text) return fail(c, HIVIS_ECAP, "text length %d + tree rows exceeds max_text %d", c->h_dlen[0], g.max_text);
+    if (c->h_tlen[0] + n_nodes + 1 > g.max_vis + g.max_text) return fail(c, HIVIS_ECAP, "target cache full");
+    int rc = DISPATCH(c, do_tree_draft, c, top_k, depth, n_nodes);
+    if (rc) return rc;
+    c->tk = top_k; c->tdepth = depth; c->tn = n_nodes; c->state = ST_TREE_DRAFTED;
+    return HIVIS_OK;
+}
+
+int hivis_tree_set(hivis_ctx* c, int32_t n_nodes, const int32_t* tokens, const int32_t* parents) {
+    if (!c) return HIVIS_EINVAL;
+    const hivis_config& g = c->cfg;
+    if (g.batch != 1) return fail(c, HIVIS_EINVAL, "tree drafting needs batch 1 (got %d)", g.batch);
+    if (c->state != ST_READY) return fail(c, HIVIS_ESTATE, "hivis_tree_set needs a prefilled/accepted context");
+    if (!tokens || !parents || n_nodes < 1 || n_nodes + 1 > TREE_MAX_ROWS) return fail(c, HIVIS_EINVAL, "bad planted tree (n_nodes=%d)", n_nodes);
+    // verify rows 1..n_nodes: parents are row indices (0 = root) and precede their children
+    std::vector<int32_t> tok(n_nodes + 1, 0), par(n_nodes + 1, -1), dep(n_nodes + 1, 0);
+    std::vector<unsigned long long> mask(n_nodes + 1, 1ull);
+    int depth = 1;
+    for (int i = 1; i <= n_nodes; ++i) {
+        const int p = parents[i - 1], t = tokens[i - 1];
+        if (p < 0 || p >= i) return fail(c, HIVIS_EINVAL, "planted row %d: parent %d outside [0,%d)", i, p, i);
+        if (t < 0 || t >= g.vocab) return fail(c, HIVIS_EINVAL, "planted token %d outside vocab", t);
+        tok[i] = t; par[i] = p; dep[i] = dep[p] + 1; mask[i] = mask[p] | (1ull << i);
+        depth = std::max(depth, dep[i]);
+    }
+    if (depth > TREE_MAX_DEPTH) return fail(c, HIVIS_EINVAL, "planted tree depth %d > %d", depth, TREE_MAX_DEPTH);
+    if (c->h_dlen[0] + depth + 3 > g.max_text) return fail(c, HIVIS_ECAP, "text length %d + tree rows exceeds max_text %d", c->h_dlen[0], g.max_text);
+    if (c->h_tlen[0] + n_nodes + 1 > g.max_vis + g.max_text) return fail(c, HIVIS_ECAP, "target cache full");
+    if (int rc = DISPATCH(c, tree_setup, c)) return rc;
+    const TreeDev& t = c->tree;
+    // row 0's token: the last known text token (device to device)
+    HIP_TRY(c, hipMemcpyAsync(t.row_tok + 1, tok.data() + 1, n_nodes * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(t.row_tok, c->text + c->h_dlen[0], sizeof(int32_t), hipMemcpyDeviceToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(t.row_par, par.data(), (n_nodes + 1) * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(t.row_depth, dep.data(), (n_nodes + 1) * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(t.vmask, mask.data(), (n_nodes + 1) * sizeof(unsigned long long), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->tk = 0; c->tdepth = depth; c->tn = n_nodes; c->state = ST_TREE_DRAFTED;
+    return HIVIS_OK;
+}
+
+int hivis_tree_verify(hivis_ctx* c) {
+    if (!c) return HIVIS_EINVAL;
+    if (c->state != ST_TREE_DRAFTED) return fail(c, HIVIS_ESTATE, "hivis_tree_verify needs a drafted tree");
+    int rc = DISPATCH(c, do_tree_verify, c);
+    if (rc) return rc;
+    c->state = ST_TREE_VERIFIED;
+    return HIVIS_OK;
+}
+
+int hivis_tree_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
+    if (!c) return HIVIS_EINVAL;
+    if (c->state != ST_TREE_VERIFIED) return fail(c, HIVIS_ESTATE, "hivis_tree_accept needs a verified tree");
+    if (!n_accepted || !tokens) return fail(c, HIVIS_EINVAL, "null output pointer");
+    return DISPATCH(c, do_tree_accept, c, n_accepted, tokens);
+}
+
+int hivis_tree_get(hivis_ctx* c, int32_t* pool_tokens, int32_t* pool_parents, float* pool_scores, int32_t* expand, int32_t* selected,
+                   int32_t* row_tokens, int32_t* row_parents, int32_t* row_depths, int32_t* target_tokens) {
+    if (!c) return HIVIS_EINVAL;
+    if (!c->tree_ready || c->tn < 1) return fail(c, HIVIS_ESTATE, "no tree drafted yet");
+    const TreeDev& t = c->tree;
+    const int k = c->tk, P = k + (c->tdepth - 1) * k * k, N = c->tn;
+    if (k == 0 && (pool_tokens || pool_parents || pool_scores || expand || selected)) return fail(c, HIVIS_ESTATE, "the last tree was planted: it has no pool");
+#define GET(dst, src, n) do { if (dst) HIP_TRY(c, hipMemcpyAsync(dst, src, (size_t)(n) * 4, hipMemcpyDeviceToHost, c->stream)); } while (0)
+    GET(pool_tokens, t.pool_tok, P); GET(pool_parents, t.pool_par, P); GET(pool_scores, t.pool_score, P);
+    GET(expand, t.expand, (c->tdepth - 1) * k); GET(selected, t.sel, N);
+    GET(row_tokens, t.row_tok, N + 1); GET(row_parents, t.row_par, N + 1); GET(row_depths, t.row_depth, N + 1);
+    if (target_tokens) {
+        if (c->state != ST_TREE_VERIFIED && c->state != ST_READY) return fail(c, HIVIS_ESTATE, "tree not verified yet");
+        GET(target_tokens, t.ttok, N + 1);
+    }
+#undef GET
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return HIVIS_OK;
+}
+
+int hivis_tree_get_logits(hivis_ctx* c, float* out) {
+    if (!c || !out) return HIVIS_EINVAL;
+    if (!c->tree_ready || c->tn < 1 || c->tk < 1) return fail(c, HIVIS_ESTATE, "no tree drafted yet");
+    const size_t rows = 1 + (size_t)(c->tdepth - 1) * c->tk;
+    HIP_TRY(c, hipMemcpyAsync(out, c->tlogits, rows * c->cfg.vocab * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return HIVIS_OK;
+}
+
 int hivis_get_logits(hivis_ctx* c, int32_t which, float* out) {
     if (!c || !out) return HIVIS_EINVAL;
     const hivis_config& g = c->cfg;
     const float* src; size_t n;
-    if (which == 0) { if (c->state != ST_VERIFIED && c->state != ST_READY) return fail(c, HIVIS_ESTATE, "no verify logits"); src = c->logits_v; n = (size_t)g.batch * (c->K + 1) * g.vocab; }
+    if (which == 0) { if ((c->state != ST_VERIFIED && c->state != ST_TREE_VERIFIED && c->state != ST_READY) || c->vrows < 1) return fail(c, HIVIS_ESTATE, "no verify logits"); src = c->logits_v; n = (size_t)c->vrows * g.vocab; }
     else if (which == 1) { src = c->logits_d; n = (size_t)c->K * g.batch * g.vocab; }
     else if (which == 2) { src = c->logits_p; n = (size_t)g.batch * g.vocab; }
     else return fail(c, HIVIS_EINVAL, "which=%d", which);
@@ -1217,7 +1445,8 @@ int hivis_get_hidden(hivis_ctx* c, int32_t which, float* out) {
     if (c->state == ST_CREATED) return fail(c, HIVIS_ESTATE, "nothing computed yet");
     const int d = g.d;
     if (which == 0) {
-        HIP_TRY(c, hipMemcpy2DAsync(out, d * sizeof(float), c->catT, 2 * d * sizeof(float), d * sizeof(float), (size_t)g.batch * (c->K + 1), hipMemcpyDeviceToHost, c->stream));
+        if (c->vrows < 1) return fail(c, HIVIS_ESTATE, "no verify pass yet");
+        HIP_TRY(c, hipMemcpy2DAsync(out, d * sizeof(float), c->catT, 2 * d * sizeof(float), d * sizeof(float), (size_t)c->vrows, hipMemcpyDeviceToHost, c->stream));
     } else if (which == 1) {
         HIP_TRY(c, hipMemcpy2DAsync(out, d * sizeof(float), c->catD, 2 * d * sizeof(float), d * sizeof(float), (size_t)g.batch, hipMemcpyDeviceToHost, c->stream));
     } else return fail(c, HIVIS_EINVAL, "which=%d", which);
@@ -1238,6 +1467,7 @@ int hivis_get_tokens(hivis_ctx* c, int32_t* drafts, int32_t* target_tokens) {
     if (!c) return HIVIS_EINVAL;
     const hivis_config& g = c->cfg;
     if (c->state == ST_CREATED || c->K < 1) return fail(c, HIVIS_ESTATE, "no draft round yet");
+    if (c->state == ST_TREE_DRAFTED || c->state == ST_TREE_VERIFIED) return fail(c, HIVIS_ESTATE, "a tree round is in progress: use hivis_tree_get");
     std::vector<int32_t> hd((size_t)g.batch * g.k_max), ht((size_t)g.batch * (g.k_max + 1));
     HIP_TRY(c, hipMemcpyAsync(hd.data(), c->drafts, hd.size() * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipMemcpyAsync(ht.data(), c->ttok, ht.size() * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));

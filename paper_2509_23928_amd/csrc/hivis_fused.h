@@ -701,6 +701,9 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
         }
     }
     const int qpos = (n16 < R) ? pos0 + i0 + n16 % ni : 0x7FFFFFFF;     // causal limit of this lane's row
+    const bool tree = sh.tmask != nullptr;                              // rows of a draft tree: ancestor mask instead
+    const unsigned long long tmk = (tree && n16 < R) ? sh.tmask[sl * sh.m + i0 + n16 % ni] : ~0ull;
+    const int tb = pos0 - sh.offset;
     HIVIS_AMARK(2)
 
     float mrun = -INFINITY, lrun = 0.f;
@@ -732,7 +735,7 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int key = kb + 4 * g + r;
-            sv[r] = (key < k1 && key <= qpos) ? st[r] : -INFINITY;
+            sv[r] = (key < k1 && attn_visible(tree, key, qpos, tmk, tb)) ? st[r] : -INFINITY;
             tmax = fmaxf(tmax, sv[r]);
         }
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));

@@ -616,13 +616,16 @@ __global__ void silu_mul_kernel(const float* __restrict__ gu, float* __restrict_
 // Row r belongs to sequence seq0 + r / m and sits at position base[seq] + offset + r % m, which is
 // both its rotary position and its slot in the cache.  Cache layout: [seq][Hkv][maxL][HD].
 // The angle is evaluated in double so that large positions keep full fp32 accuracy.
+// pos_delta (optional, rows of a draft tree): the rotary position of row r is base[seq] + pos_delta[r] instead, its
+// cache slot stays base[seq] + offset + r % m.
 template <typename ST>
 __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int HD, const int* __restrict__ base,
                                    int offset, int seq0, int m, ST* __restrict__ kc, ST* __restrict__ vc, int maxL,
-                                   float theta) {
+                                   float theta, const int* __restrict__ pos_delta = nullptr) {
     const int row = blockIdx.x;
     const int seq = seq0 + row / m;
-    const int pos = base[seq] + offset + row % m;
+    const int slot = base[seq] + offset + row % m;
+    const int pos = pos_delta ? base[seq] + pos_delta[row] : slot;
     const int half = HD / 2;
     float* r = qkv + (size_t)row * (Hq + 2 * Hkv) * HD;
     const int npair = (Hq + Hkv) * half;
@@ -638,14 +641,14 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int
         if (head < Hq) {
             x[2 * i] = y1; x[2 * i + 1] = y2;
         } else {
-            ST* dst = kc + (((size_t)seq * Hkv + (head - Hq)) * maxL + pos) * HD;
+            ST* dst = kc + (((size_t)seq * Hkv + (head - Hq)) * maxL + slot) * HD;
             from_f32(dst[2 * i], y1); from_f32(dst[2 * i + 1], y2);
         }
     }
     const float* v = r + (size_t)(Hq + Hkv) * HD;
     for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < Hkv * HD; idx += gridDim.y * blockDim.x) {
         const int head = idx / HD, c = idx % HD;
-        from_f32(vc[(((size_t)seq * Hkv + head) * maxL + pos) * HD + c], v[idx]);
+        from_f32(vc[(((size_t)seq * Hkv + head) * maxL + slot) * HD + c], v[idx]);
     }
 }
 
@@ -667,7 +670,15 @@ struct AttnShape {
     int seq0, offset, maxL, nsplit;
     int ldq;                 // row stride of the q buffer
     int nwaves;              // wavefronts per workgroup working on one (item, split)
+    // rows of a draft tree (optional): row i sees every key before base[seq] plus the keys base[seq] + b whose bit b is
+    // set in tmask[i] (its ancestors among the tree rows and itself), instead of the causal rule
+    const unsigned long long* tmask;
 };
+// visibility of key `key` for a row with causal limit qpos (tm, tb: the row's tree mask and the tree's first slot)
+__device__ __forceinline__ bool attn_visible(bool tree, int key, int qpos, unsigned long long tm, int tb) {
+    if (!tree) return key <= qpos;
+    return key < tb || ((unsigned)(key - tb) < 64u && ((tm >> ((key - tb) & 63)) & 1ull));
+}
 
 // LDS needed by attn_item_partial: q rows + one probability tile per wavefront
 __host__ __device__ constexpr size_t attn_lds_floats(int hd, int nwaves, int rmax = ATT_RMAX) {
@@ -751,7 +762,9 @@ __device__ __forceinline__ void attn_item_partial(const float* __restrict__ q, c
         for (int r = 0; r < RM; ++r) {
             if (r < R) {
                 const int qpos = pos0 + i0 + r % ni;
-                const float sv = (valid && j <= qpos) ? s[r] : -INFINITY;
+                const bool tree = sh.tmask != nullptr;
+                const unsigned long long tm = tree ? sh.tmask[sl * sh.m + i0 + r % ni] : 0ull;
+                const float sv = (valid && attn_visible(tree, j, qpos, tm, pos0 - sh.offset)) ? s[r] : -INFINITY;
                 const float tmax = wave_max(sv);
                 const float mnew = fmaxf(mrun[r], tmax);
                 float alpha = 1.f, p = 0.f;

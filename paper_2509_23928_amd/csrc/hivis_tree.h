@@ -1,0 +1,248 @@
+// Draft-tree kernels (section 4 inference setting: top-k tree expanded to a fixed depth, the best-scored candidates
+// verified in one pass; section 2.1 names the tree structure).  Batch 1.
+//
+// Pool layout (P = k + (depth-1) k^2 nodes): level 1 = the k most probable tokens after the drafter's pending hidden
+// state; level j+1 = k children of each of the k rows expanded at level j, row by row, rank by rank.  A node's score
+// is the sum of the log-probabilities along its path.  Everything that decides an index (top-k, expansion set,
+// candidate set, acceptance walk) orders by (score descending, index ascending), so results are unique.
+#pragma once
+#include "hivis_kernels.h"
+
+namespace hivis {
+
+constexpr int TREE_MAX_TOPK = 16;       // k
+constexpr int TREE_MAX_ROWS = 64;       // verify rows (root + candidates); drafter tree rows (depth-1)*k: one 64-bit mask each
+constexpr int TREE_MAX_DEPTH = 16;
+constexpr int TREE_MAX_POOL = 2048;
+
+struct TreeDev {
+    int32_t* pool_tok; int32_t* pool_par; float* pool_score; int32_t* pool_depth;   // [P]
+    int32_t* pool_hid;                  // [P] hidden row whose distribution the node was taken from
+    int32_t* pool_slot;                 // [P] drafter tree row of an expanded node
+    int32_t* expand;                    // [depth-1][k] pool indices of the expanded rows
+    unsigned long long* dmask;          // [(depth-1) k] ancestor masks of the drafter's tree rows (bit = tree row)
+    int32_t* dpos;                      // [(depth-1) k] rotary position of a drafter tree row, relative to the cache length
+    int32_t* sel;                       // [N] candidates, ascending pool index
+    int32_t* row_tok; int32_t* row_par; int32_t* row_depth;   // [N+1] verify rows (row 0 = root)
+    unsigned long long* vmask;          // [N+1] ancestor masks of the verify rows
+    int32_t* ttok;                      // [N+1] the target's greedy token after each row
+    int32_t* path;                      // [depth+1] rows re-fed after acceptance: root, followed rows, then the last one repeated
+    int32_t* next_tok;                  // [depth+1] token that follows each re-fed row
+    int32_t* result;                    // [1 + depth+1] accepted length | emitted tokens (-1 padded)
+};
+
+// (value, index) maximum over the workgroup under the order (value descending, index ascending); every thread gets it.
+template <int NT>
+__device__ __forceinline__ void block_best(float& v, int& i, float* smf, int* smi) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(v, o, 64); const int oi = __shfl_xor(i, o, 64);
+        if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { smf[threadIdx.x >> 6] = v; smi[threadIdx.x >> 6] = i; }
+    __syncthreads();
+    v = smf[0]; i = smi[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) {
+        const float ov = smf[w]; const int oi = smi[w];
+        if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+    }
+}
+
+// Children of the rows of one level: row r of `logits` is the drafter's distribution behind node expand_row[r] (or
+// behind the root if expand_row is null).  Its k most probable tokens (best first) become pool nodes
+// first + r k + q with score = parent score + log softmax.  One workgroup per row; round q picks the best element
+// that comes after round q-1's pick in the (value descending, index ascending) order.
+constexpr int TOPK_NT = 512;
+__global__ __launch_bounds__(TOPK_NT) void tree_children_kernel(const float* __restrict__ logits, int V, int k, int first,
+                                                                const int32_t* __restrict__ expand_row, int depth, int hid_row0,
+                                                                TreeDev t) {
+    __shared__ float smf[TOPK_NT / 64];
+    __shared__ int smi[TOPK_NT / 64];
+    const int r = blockIdx.x;
+    const float* x = logits + (size_t)r * V;
+    float mx, sum;
+    block_softmax_stats<TOPK_NT>(x, V, 1.0f, smf, &mx, &sum);
+    const float logz = mx + logf(sum);
+    const int parent = expand_row ? expand_row[r] : -1;
+    const float pscore = parent >= 0 ? t.pool_score[parent] : 0.f;
+    float pv = INFINITY; int pi = -1;
+    for (int q = 0; q < k; ++q) {
+        float bv = -INFINITY; int bi = 0x7FFFFFFF;
+        for (int j = threadIdx.x; j < V; j += TOPK_NT * 8) {
+            float x8[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x8[e] = x[min(j + TOPK_NT * e, V - 1)];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int idx = j + TOPK_NT * e;
+                const float xv = x8[e];
+                const bool after = xv < pv || (xv == pv && idx > pi);
+                if (idx < V && after && (xv > bv || (xv == bv && idx < bi))) { bv = xv; bi = idx; }
+            }
+        }
+        block_best<TOPK_NT>(bv, bi, smf, smi);
+        pv = bv; pi = bi;
+        if (threadIdx.x == 0) {
+            const int n = first + r * k + q;
+            t.pool_tok[n] = bi; t.pool_par[n] = parent; t.pool_depth[n] = depth; t.pool_hid[n] = hid_row0 + r;
+            t.pool_score[n] = pscore + (bv - logz);
+            t.pool_slot[n] = -1;
+        }
+    }
+}
+
+// The k best-scored of the n nodes [lo, lo + n) of one level become the drafter's tree rows n_prev .. n_prev + k - 1
+// (rank order).  One workgroup, n <= 256.
+__global__ __launch_bounds__(256) void tree_expand_kernel(int lo, int n, int k, int n_prev, int level, TreeDev t) {
+    __shared__ float s[256];
+    const int i = threadIdx.x;
+    s[i] = i < n ? t.pool_score[lo + i] : -INFINITY;
+    __syncthreads();
+    if (i >= n) return;
+    const float si = s[i];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) rank += (s[j] > si || (s[j] == si && j < i)) ? 1 : 0;
+    if (rank >= k) return;
+    const int slot = n_prev + rank, node = lo + i;
+    t.expand[(level - 1) * k + rank] = node;
+    t.pool_slot[node] = slot;
+    const int parent = t.pool_par[node];      // expanded at the level before (or the root): its row and mask already exist
+    t.dmask[slot] = (parent >= 0 ? t.dmask[t.pool_slot[parent]] : 0ull) | (1ull << slot);
+    t.dpos[slot] = level - 1;
+}
+
+// Fusion input rows of one level: [hidden row the node was drawn from ; Embed(node token)].
+template <typename WT>
+__global__ void tree_cat_kernel(const int32_t* __restrict__ expand_row, TreeDev t, const float* __restrict__ H,
+                                const WT* __restrict__ table, float* __restrict__ cat, int d) {
+    const int r = blockIdx.x, node = expand_row[r];
+    const float* h = H + (size_t)t.pool_hid[node] * d;
+    const WT* e = table + (size_t)t.pool_tok[node] * d;
+    float* o = cat + (size_t)r * 2 * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) { o[c] = h[c]; o[d + c] = to_f32(e[c]); }
+}
+
+// Candidates: the N best-scored pool nodes, in pool order; verify rows 1..N (row 0 = root = the last known token).
+// One workgroup of 1024 threads, P <= 2048.
+__global__ __launch_bounds__(1024) void tree_select_kernel(int P, int N, const int32_t* __restrict__ text,
+                                                           const int* __restrict__ dlen, TreeDev t) {
+    __shared__ float s[TREE_MAX_POOL];
+    __shared__ short rowof[TREE_MAX_POOL];      // verify row of a pool node, 0 if not a candidate
+    for (int i = threadIdx.x; i < P; i += 1024) s[i] = t.pool_score[i];
+    __syncthreads();
+    bool chosen[2] = {false, false};
+    for (int e = 0; e < 2; ++e) {
+        const int i = threadIdx.x + e * 1024;
+        if (i >= P) continue;
+        const float si = s[i];
+        int rank = 0;
+        for (int j = 0; j < P; ++j) rank += (s[j] > si || (s[j] == si && j < i)) ? 1 : 0;
+        chosen[e] = rank < N;
+    }
+    for (int e = 0; e < 2; ++e) { const int i = threadIdx.x + e * 1024; if (i < P) rowof[i] = chosen[e] ? 1 : 0; }
+    __syncthreads();
+    int myrow[2] = {0, 0};
+    for (int e = 0; e < 2; ++e) {
+        const int i = threadIdx.x + e * 1024;
+        if (i >= P || !chosen[e]) continue;
+        int below = 0;
+        for (int j = 0; j < i; ++j) below += rowof[j] ? 1 : 0;
+        myrow[e] = below + 1;
+    }
+    __syncthreads();
+    for (int e = 0; e < 2; ++e) { const int i = threadIdx.x + e * 1024; if (i < P) rowof[i] = (short)myrow[e]; }
+    __syncthreads();
+    for (int e = 0; e < 2; ++e) {
+        const int i = threadIdx.x + e * 1024;
+        if (i >= P || !chosen[e]) continue;
+        const int row = myrow[e];
+        t.sel[row - 1] = i;
+        t.row_tok[row] = t.pool_tok[i];
+        t.row_depth[row] = t.pool_depth[i];
+        const int parent = t.pool_par[i];
+        t.row_par[row] = parent >= 0 ? rowof[parent] : 0;        // the candidate set is closed under ancestors
+        unsigned long long m = 1ull;                              // the root
+        for (int a = i; a >= 0; a = t.pool_par[a]) m |= 1ull << rowof[a];
+        t.vmask[row] = m;
+    }
+    if (threadIdx.x == 0) { t.row_tok[0] = text[dlen[0]]; t.row_par[0] = -1; t.row_depth[0] = 0; t.vmask[0] = 1ull; }
+}
+
+// Greedy acceptance on the tree: from the root, follow the child whose token is the target's greedy token at the
+// current row until there is none.  Emits the followed tokens plus the target's token at the last row, appends them
+// to the text, and lists the rows whose true features re-condition the drafter.  One wavefront.
+__global__ __launch_bounds__(64) void tree_accept_kernel(int N, int depth, int32_t* __restrict__ text, const int* __restrict__ dlen, TreeDev t) {
+    const int lane = threadIdx.x;
+    int cur = 0, n = 0;
+    int mine = 0;                                   // lane e ends up holding re-fed row e (lane 0: the root)
+    while (n < depth) {
+        const int want = t.ttok[cur];
+        int found = 0x7FFFFFFF;
+        for (int c = 1 + lane; c <= N; c += 64)
+            if (t.row_par[c] == cur && t.row_tok[c] == want) found = min(found, c);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) found = min(found, __shfl_xor(found, o, 64));
+        if (found == 0x7FFFFFFF) break;
+        cur = found; ++n;
+        if (lane == n) mine = cur;
+    }
+    if (lane > n) mine = cur;                       // dead rows repeat the last followed row
+    const int bonus = t.ttok[cur];
+    const int next_row = __shfl(mine, min(lane + 1, 63), 64);
+    if (lane <= depth) {
+        const int tok = (lane < n) ? t.row_tok[next_row] : bonus;          // token that follows re-fed row `lane`
+        t.path[lane] = mine;
+        t.next_tok[lane] = tok;
+        t.result[1 + lane] = (lane <= n) ? tok : -1;
+        if (lane <= n) text[dlen[0] + 1 + lane] = tok;
+    }
+    if (lane == 0) t.result[0] = n;
+}
+
+// Cache compaction after acceptance, for all layers at once: the rows of the followed path move from their tree
+// slots base + path[j] to base + j (j = 1..n).  Two kernels (gather into a staging buffer, scatter back) because a
+// destination slot of one row can be the source slot of another.
+// kv: [n_layers][2] cache pointers; cache layout [Hkv][maxL][HD]; staging [n_layers][2][depth][Hkv*HD].
+template <typename KT>
+__global__ void tree_kv_gather_kernel(KT* const* __restrict__ kv, int maxL, int Hkv, int HD, const int* __restrict__ tlen,
+                                      const int32_t* __restrict__ result, const int32_t* __restrict__ path, int depth,
+                                      KT* __restrict__ staging, int scatter) {
+    const int j = blockIdx.x + 1, lk = blockIdx.y;                  // lk = layer * 2 + (0: keys, 1: values)
+    const int n = result[0];
+    if (j > n) return;
+    const int src = path[j];
+    if (src == j) return;                                           // already in place
+    KT* cache = kv[lk];
+    KT* st = staging + ((size_t)lk * depth + (j - 1)) * Hkv * HD;
+    const int base = tlen[0];
+    for (int idx = threadIdx.x; idx < Hkv * HD; idx += blockDim.x) {
+        const int h = idx / HD, c = idx % HD;
+        if (scatter) cache[((size_t)h * maxL + base + j) * HD + c] = st[idx];
+        else st[idx] = cache[((size_t)h * maxL + base + src) * HD + c];
+    }
+}
+
+// Re-feed rows after acceptance: [true feature of path row e ; Embed(token after it)], e = 0..depth (rows beyond the
+// accepted length repeat the last one and are dead).  g: verify features, row stride ldg.
+template <typename WT>
+__global__ void tree_roll_cat_kernel(const float* __restrict__ g, int ldg, const int32_t* __restrict__ path,
+                                     const int32_t* __restrict__ next_tok, const WT* __restrict__ table,
+                                     float* __restrict__ cat, int d) {
+    const int e = blockIdx.x;
+    const float* f = g + (size_t)path[e] * ldg;
+    const WT* em = table + (size_t)next_tok[e] * d;
+    float* o = cat + (size_t)e * 2 * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) { o[c] = f[c]; o[d + c] = to_f32(em[c]); }
+}
+
+// After the re-feed: pending hidden state = drafter output at row n; both caches keep n + 1 more rows.
+__global__ void tree_finish_kernel(const float* __restrict__ dout, const int32_t* __restrict__ result, float* __restrict__ fnext,
+                                   int* __restrict__ dlen, int* __restrict__ tlen, int d) {
+    const int n = result[0];
+    for (int c = threadIdx.x; c < d; c += blockDim.x) fnext[c] = dout[(size_t)n * d + c];
+    if (threadIdx.x == 0) { dlen[0] += n + 1; tlen[0] += n + 1; }
+}
+
+}  // namespace hivis

@@ -1,0 +1,243 @@
+"""GPU parity of the draft-tree calls (hivis_tree_draft / hivis_tree_verify / hivis_tree_accept) against the oracle.
+
+Floating point is compared with the tolerances of the chain tests (oracle in follow mode: it is handed the
+library's tree and recomputes every row on its own state).  Every index the tree method decides from floating
+point (top-k tokens of a row, the rows expanded at a level, the candidates, the followed path) is re-decided by
+the oracle's routines from the library's OWN float32 numbers, where it must agree exactly; that the numbers
+themselves are right is the tolerance check."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import greedy_reference
+from oracle.tree import HivisTreeOracle, accept_path, log_softmax, pool_size, top_k_lowest
+from parity_utils import check_token, logit_tol
+from test_gpu_parity import small_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def c1(**kw):
+    return synth.get_config("C1").scaled(**kw)
+
+
+def make_tree(cfg, seed, room):
+    from paper_2509_23928_amd import Hivis
+    w = synth.make_weights(cfg, seed=seed)
+    vis, ids = synth.make_prompt(cfg, seed=seed)
+    hv = Hivis(cfg, w, max_text=cfg.n_text + room, k_max=max(cfg.K, 1))
+    return w, vis, ids, hv
+
+
+class TreeSideBySide:
+    def __init__(self, cfg, seed, room=400):
+        self.cfg = cfg
+        self.w, self.vis, self.ids, self.hv = make_tree(cfg, seed, room)
+        self.o = HivisTreeOracle(cfg, self.w)
+        first = self.hv.prefill(self.vis, self.ids)
+        x, logits = self.o.prefill(self.vis[0], self.ids[0])
+        assert x == int(first[0]), "near-tie at the first token: pick another seed"
+        self.emitted = [x]
+        self.near_ties = 0
+        self.n_hist = []
+        self.max_err = {"draft": 0.0, "score": 0.0, "verify": 0.0, "g": 0.0, "fnext": 0.0}
+        self._check_fnext()
+
+    def _check_fnext(self):
+        f = self.hv.get_hidden(1)[0]
+        scale = float(np.sqrt(np.mean(self.o.f_next ** 2)))
+        rel = float(np.max(np.abs(f - self.o.f_next))) / scale
+        lim = 2e-4 if self.cfg.dtype == "f32" else 6e-2
+        self.max_err["fnext"] = max(self.max_err["fnext"], rel / lim)
+        assert rel <= lim, f"drafter pending hidden state off by {rel}"
+
+    def _verify_accept(self, tokens, parents, depth):
+        """Shared tail of a cycle: the oracle's tree (self.o.tree) already equals the library's."""
+        cfg, hv, o = self.cfg, self.hv, self.o
+        hv.tree_verify()
+        N = len(tokens)
+        tr = hv.tree_get(verified=True)
+        assert list(tr["row_tokens"][1:]) == list(tokens) and list(tr["row_parents"][1:]) == list(parents)
+        assert int(tr["row_parents"][0]) == -1 and int(tr["row_tokens"][0]) == o.text[-1] and int(tr["row_depths"][0]) == 0
+        vlog = hv.get_logits(0)[0]
+        g = hv.get_hidden(0)[0]
+        og, ologits, ot = o.tree_verify()
+        tol = logit_tol(cfg, ologits)
+        err = float(np.max(np.abs(vlog - ologits)))
+        self.max_err["verify"] = max(self.max_err["verify"], err / tol)
+        assert err <= tol, f"tree verify logits off by {err} > {tol}"
+        gerr = float(np.max(np.abs(g - og))) / float(np.sqrt(np.mean(og ** 2)))
+        glim = 1e-4 if cfg.dtype == "f32" else 6e-2
+        self.max_err["g"] = max(self.max_err["g"], gerr / glim)
+        assert gerr <= glim, f"tree verify features off by {gerr}"
+        ttok = tr["target_tokens"]
+        for i in range(N + 1):
+            self.near_ties += check_token(ttok[i], ologits[i], tol)
+        n, toks = hv.tree_accept()
+        # acceptance: bit-exact given the library's own target tokens
+        path = accept_path([-1] + list(parents), [o.text[-1]] + list(tokens), ttok)
+        exp = [int(tokens[r - 1]) for r in path] + [int(ttok[path[-1] if path else 0])]
+        assert n == len(path) and [int(t) for t in toks[:n + 1]] == exp and all(int(t) == -1 for t in toks[n + 1:])
+        o.tree_accept(og, ot, force=(path, exp))
+        tl, dl = hv.kv_lengths()
+        assert int(tl[0]) == o.target.kv_len and int(dl[0]) == o.drafter.kv_len == o.l
+        self.emitted += exp
+        self.n_hist.append(n)
+        self._check_fnext()
+        return n, path
+
+    def cycle(self, k, depth, N):
+        cfg, hv, o = self.cfg, self.hv, self.o
+        hv.tree_draft(k, depth, N)
+        tr = hv.tree_get()
+        dlog = hv.tree_get_logits().astype(np.float64)              # [1 + (depth-1) k][V]
+        P = pool_size(k, depth)
+        ptok, ppar, psc = tr["pool_tokens"], tr["pool_parents"], tr["pool_scores"].astype(np.float64)
+        # --- decisions re-taken from the library's own numbers: exact
+        lp_own = log_softmax(dlog)
+        lo, n = 0, k
+        for j in range(depth):
+            rows = [0] if j == 0 else [1 + (j - 1) * k + r for r in range(k)]
+            first = 0 if j == 0 else lo + n
+            for r, row in enumerate(rows):
+                kids = list(range(first + r * k, first + (r + 1) * k))
+                assert [int(ptok[i]) for i in kids] == top_k_lowest(dlog[row], k), (j, r)
+                parent = -1 if j == 0 else int(tr["expand"][j - 1][r])
+                assert all(int(ppar[i]) == parent for i in kids)
+                base = 0.0 if parent < 0 else psc[parent]
+                for i in kids:                                        # fp32 sum of fp32 log-probabilities
+                    assert abs(psc[i] - (base + lp_own[row][ptok[i]])) <= 2e-5 * (1 + abs(psc[i]))
+            if j > 0:
+                lo, n = first, k * k
+            if j < depth - 1:
+                l0, ln = (0, k) if j == 0 else (first, k * k)
+                assert [int(e) for e in tr["expand"][j]] == [l0 + i for i in top_k_lowest(psc[l0:l0 + ln], k)], j
+        assert [int(s) for s in tr["selected"]] == sorted(top_k_lowest(psc, N))
+        # --- the numbers themselves: the oracle follows the library's tree
+        ot = o.tree_draft(k, depth, N, follow={"pool_tokens": ptok, "expand": tr["expand"], "selected": tr["selected"]})
+        tol = logit_tol(cfg, dlog)
+        err = float(np.max(np.abs(lp_own - ot["logp"])))
+        self.max_err["draft"] = max(self.max_err["draft"], err / (2 * tol))
+        assert err <= 2 * tol, f"tree draft log-probabilities off by {err} > {2 * tol}"
+        serr = float(np.max(np.abs(psc - ot["pool_scores"])))
+        self.max_err["score"] = max(self.max_err["score"], serr / (2 * tol * depth))
+        assert serr <= 2 * tol * depth
+        assert list(tr["row_tokens"][1:]) == ot["tokens"] and list(tr["row_parents"][1:]) == ot["parents"] and list(tr["row_depths"][1:]) == ot["depths"]
+        return self._verify_accept(ot["tokens"], ot["parents"], depth)
+
+    def planted_cycle(self, tokens, parents):
+        o = self.o
+        self.hv.tree_set(tokens, parents)
+        depths = {0: 0}
+        for i, p in enumerate(parents, start=1):
+            depths[i] = depths[int(p)] + 1
+        o.tree = {"tokens": [int(t) for t in tokens], "parents": [int(p) for p in parents], "depths": [depths[i] for i in range(1, len(tokens) + 1)]}
+        return self._verify_accept(o.tree["tokens"], o.tree["parents"], max(depths.values()))
+
+
+def branching_plant(ref, done, vocab, good, shape):
+    """A tree whose followed path is ref[done:done+good] placed on NON-first siblings: at every level `shape` siblings
+    hang under the previous level's path node, the path token sits at the last of them, the others carry wrong tokens;
+    below the path's end one more level of wrong tokens."""
+    tokens, parents = [], []
+    parent = 0
+    for lvl in range(good + 1):
+        want = ref[done + lvl]
+        first = len(tokens) + 1
+        for s in range(shape):
+            on_path = (s == shape - 1) and lvl < good
+            tokens.append(want if on_path else (want + 1 + s) % vocab)
+            parents.append(parent)
+        parent = first + shape - 1
+    return tokens, parents
+
+
+def test_tree_own_drafts_tiny_fp32():
+    cfg = c1(n_vis=40, n_text=19, n_q_heads=4, n_kv_heads=2)
+    t = TreeSideBySide(cfg, 5)
+    for (k, depth, N) in [(3, 3, 9), (4, 2, 12), (2, 4, 7), (1, 3, 3), (5, 3, 31), (3, 1, 3)]:
+        t.cycle(k, depth, N)
+    print("tiny tree max error / tolerance:", t.max_err, "accepted:", t.n_hist, "near ties:", t.near_ties)
+    if t.near_ties == 0:
+        ref, _ = greedy_reference(cfg, t.w, t.vis[0], t.ids[0], len(t.emitted))
+        assert t.emitted == ref
+
+
+def test_tree_planted_paths_and_compaction_fp32():
+    """Planted trees whose followed path sits on scattered rows: accepted lengths 0..4, cache compaction, and the
+    following cycles (chain and tree) still exact."""
+    cfg = c1(n_vis=33, n_text=9, K=3)
+    t = TreeSideBySide(cfg, 6)
+    ref, _ = greedy_reference(cfg, t.w, t.vis[0], t.ids[0], 60)
+    for good, shape in [(3, 3), (0, 2), (4, 4), (1, 1), (2, 5)]:
+        tokens, parents = branching_plant(ref, len(t.emitted), cfg.vocab, good, shape)
+        n, path = t.planted_cycle(tokens, parents)
+        if t.near_ties == 0:
+            assert n == good
+            assert path == [shape * (lvl + 1) for lvl in range(good)]       # the last sibling of every level
+        t.cycle(3, 2, 6)                                                      # an own-draft tree cycle on the compacted state
+    # a chain cycle on the same context afterwards
+    hv = t.hv
+    hv.draft(cfg.K); hv.verify(); n, toks = hv.accept()
+    if t.near_ties == 0:
+        done = len(t.emitted)
+        assert [int(x) for x in toks[0][: n[0] + 1]] == ref[done: done + n[0] + 1]
+        assert t.emitted == ref[: len(t.emitted)]
+    print("planted tree max error / tolerance:", t.max_err, "accepted:", t.n_hist)
+
+
+@pytest.mark.parametrize("variant", ["mha128", "gqa64"])
+def test_tree_small_bf16(variant):
+    kw = dict(n_q_heads=4, n_kv_heads=4, head_dim=128) if variant == "mha128" else dict(n_q_heads=8, n_kv_heads=2, head_dim=64)
+    cfg = small_bf16(**kw)
+    t = TreeSideBySide(cfg, 7)
+    ref, _ = greedy_reference(cfg, t.w, t.vis[0], t.ids[0], 40)
+    t.cycle(4, 3, 15)
+    tokens, parents = branching_plant(ref, len(t.emitted), cfg.vocab, 3, 3)
+    t.planted_cycle(tokens, parents)
+    t.cycle(10, 6, 60)                    # the paper's setting: 61 verify rows (two GEMM row blocks), 50 drafter tree rows
+    t.cycle(8, 4, 30)                     # the supplementary setting
+    print(variant, "tree max error / tolerance:", t.max_err, "accepted:", t.n_hist, "near ties:", t.near_ties)
+    if t.near_ties == 0:
+        assert t.emitted == ref[: len(t.emitted)]
+
+
+def test_tree_error_codes():
+    from paper_2509_23928_amd import Hivis, HivisError, HIVIS_EINVAL, HIVIS_ESTATE, HIVIS_ECAP
+    cfg = c1(n_vis=8, n_text=9)
+    w, vis, ids, hv = make_tree(cfg, 8, 40)
+    with pytest.raises(HivisError) as e:
+        hv.tree_draft(3, 3, 9)                              # nothing prefilled
+    assert e.value.code == HIVIS_ESTATE
+    hv.prefill(vis, ids)
+    for bad in [(0, 3, 3), (17, 2, 3), (3, 0, 3), (3, 17, 3), (3, 3, 0), (3, 3, 22), (16, 6, 60), (10, 6, 64)]:
+        with pytest.raises(HivisError) as e:
+            hv.tree_draft(*bad)
+        assert e.value.code == HIVIS_EINVAL, bad
+    with pytest.raises(HivisError) as e:
+        hv.tree_verify()
+    assert e.value.code == HIVIS_ESTATE
+    with pytest.raises(HivisError) as e:
+        hv.tree_set([1, 2], [0, 2])                         # parent does not precede its child
+    assert e.value.code == HIVIS_EINVAL
+    with pytest.raises(HivisError) as e:
+        hv.tree_draft(10, 6, 60)                            # 50 drafter tree rows do not fit max_text = n_text + 40
+    assert e.value.code == HIVIS_ECAP
+    hv.tree_draft(3, 2, 5)
+    with pytest.raises(HivisError) as e:
+        hv.verify()                                         # chain verify on a tree round
+    assert e.value.code == HIVIS_ESTATE
+    with pytest.raises(HivisError) as e:
+        hv.tree_accept()
+    assert e.value.code == HIVIS_ESTATE
+    hv.tree_verify()
+    n, toks = hv.tree_accept()
+    assert 0 <= n <= 2 and toks[n] >= 0
+    cfg2 = c1(n_vis=8, n_text=9, batch=2)
+    w2 = synth.make_weights(cfg2, seed=8)
+    vis2, ids2 = synth.make_prompt(cfg2, seed=8)
+    hv2 = Hivis(cfg2, w2)
+    hv2.prefill(vis2, ids2)
+    with pytest.raises(HivisError) as e:
+        hv2.tree_draft(2, 2, 3)                             # batch 2
+    assert e.value.code == HIVIS_EINVAL

@@ -32,16 +32,22 @@ TRAFFIC_BYTES_PER_LAUNCH = {"C2": 181.7e6}     # profiles/gateup_gemm_C2_hbm_cou
 PAPER_TAU = {"C2": 5.37, "C3": 5.06, "C4": 4.39, "C5": 5.15}    # Table 2, T=0 averages (tree drafting, A800): context only
 
 
-def run_step(hv, cfg, vis, ids, K, temperature=0.0, rng=None):
+def run_step(hv, cfg, vis, ids, K, temperature=0.0, rng=None, tree=None):
     """prefill + cycles until cfg.gen_tokens tokens (or cfg.gen_cycles cycles).  Returns (tokens, cycles, accepted).
-    temperature > 0: the sampling calls, with uniforms from `rng` (not the headline configuration)."""
+    temperature > 0: the sampling calls, with uniforms from `rng` (not the headline configuration).
+    tree = (top_k, depth, n_nodes): draft-tree cycles instead of chain cycles (not the headline configuration)."""
     first = hv.prefill(vis, ids)
     produced = np.ones(hv.B, np.int64)
     cycles = 0
     accepted = 0
     target = cfg.gen_tokens
     while True:
-        if temperature > 0.0:
+        if tree:
+            hv.tree_draft(*tree)
+            hv.tree_verify()
+            n1, _ = hv.tree_accept()
+            n = np.array([n1], np.int64)
+        elif temperature > 0.0:
             hv.draft_sample(K, temperature, rng.random((hv.B, K), dtype=np.float32))
             hv.verify()
             n, _ = hv.accept_sample(temperature, rng.random((hv.B, K), dtype=np.float32), rng.random(hv.B, dtype=np.float32))
@@ -110,6 +116,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of target layers (debug only; invalid as a result)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--temperature", type=float, default=0.0, help="> 0: time the temperature-sampling calls instead of the greedy ones (extra measurement, not the headline metric)")
+    ap.add_argument("--tree", default="", help="top_k,depth,n_nodes: time draft-tree cycles instead of chain cycles (extra measurement, not the headline metric; batch 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true", help="also run a plain 1 GiB device copy first (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -135,7 +142,12 @@ def main():
     t_gen = time.time() - t0
     t0 = time.time()
     stream = torch.cuda.Stream()
-    hv = Hivis(cfg, w, stream=stream.cuda_stream)
+    tree = tuple(int(x) for x in args.tree.split(",")) if args.tree else None
+    if tree:
+        gen = cfg.gen_tokens or cfg.gen_cycles * (tree[1] + 1)
+        hv = Hivis(cfg, w, stream=stream.cuda_stream, max_text=cfg.n_text + gen + max((tree[1] - 1) * tree[0], tree[2]) + tree[1] + 8)
+    else:
+        hv = Hivis(cfg, w, stream=stream.cuda_stream)
     del w
     t_load = time.time() - t0
     # inputs resident in HBM before the timed region
@@ -155,7 +167,7 @@ def main():
         del src, dst
     rng = np.random.default_rng(args.seed + 12345)
     for _ in range(args.warmup):
-        run_step(hv, cfg, vis_dev, ids_dev, K, args.temperature, rng)
+        run_step(hv, cfg, vis_dev, ids_dev, K, args.temperature, rng, tree)
     hv.timing(True)
     hv.kernel_timing(GEMM_GATEUP)
     for ph in range(4):
@@ -164,7 +176,7 @@ def main():
     t0 = time.perf_counter()
     tokens = cycles = accepted = 0
     for _ in range(args.steps):
-        tk, cy, ac, _ = run_step(hv, cfg, vis_dev, ids_dev, K, args.temperature, rng)
+        tk, cy, ac, _ = run_step(hv, cfg, vis_dev, ids_dev, K, args.temperature, rng, tree)
         tokens += tk; cycles += cy; accepted += ac
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -175,7 +187,8 @@ def main():
     verify_bytes_end, draft_bytes_end = hv.algorithmic_bytes()
 
     prefill_ms = phases[0][0] / max(phases[0][1], 1)
-    draft_us = phases[1][0] / max(phases[1][1], 1) / K * 1e3
+    Kd = 1 if tree else K                      # tree: phase 1 is the whole tree draft (depth LM-head passes, depth-1 drafter passes)
+    draft_us = phases[1][0] / max(phases[1][1], 1) / Kd * 1e3
     verify_us = phases[2][0] / max(phases[2][1], 1) * 1e3
     accept_us = phases[3][0] / max(phases[3][1], 1) * 1e3
     # algorithmic bytes of an average verify / draft step: weights once + KV at the mean length of the run
@@ -196,9 +209,11 @@ def main():
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: {cfg.name} N={cfg.n_layers} d={cfg.d} Hq/Hkv={cfg.n_q_heads}/{cfg.n_kv_heads} F={cfg.ffn} V={cfg.vocab}, "
                                f"{cfg.n_vis} visual + {cfg.n_text} text rows, K={K} chain, {cfg.gen_tokens or cfg.gen_cycles * (K + 1)} generated tokens, batch {cfg.batch}, "
-                               "random-init weights (seeded)" + (f", temperature {args.temperature} sampling" if args.temperature > 0 else ""), "K": K, "batch": cfg.batch},
+                               "random-init weights (seeded)" + (f", temperature {args.temperature} sampling" if args.temperature > 0 else "")
+                               + (f"; DRAFT TREE top_k={tree[0]} depth={tree[1]} candidates={tree[2]} instead of the chain (draft_step_us = one whole tree draft; "
+                                  f"verify = {tree[2] + 1} rows; the *_hbm_gbs / frac figures below price ONE weight pass and do not apply)" if tree else ""), "K": K, "batch": cfg.batch},
         "prefill_ms": prefill_ms, "draft_step_us": draft_us, "verify_us": verify_us, "accept_roll_us": accept_us,
-        "cycle_us": K * draft_us + verify_us + accept_us,
+        "cycle_us": Kd * draft_us + verify_us + accept_us,
         "draft_step_hbm_gbs": draft_gbs, "draft_step_frac_of_peak": draft_gbs / HBM_PEAK_GBS,
         "cycles": cycles, "mean_accepted_drafts": accepted / max(cycles * cfg.batch, 1),
         "verify_pass_hbm_gbs": verify_gbs, "verify_pass_frac_of_peak": verify_gbs / HBM_PEAK_GBS, "verify_pass_algorithmic_bytes": verify_bytes,
@@ -213,7 +228,7 @@ def main():
                        "avg_launch_us": k_us, "launches_timed": k_launches}
     tau = PAPER_TAU.get(args.config)
     if tau:
-        out["projected_tokens_per_s_at_paper_tau"] = cfg.batch * tau / ((K * draft_us + verify_us + accept_us) * 1e-6)
+        out["projected_tokens_per_s_at_paper_tau"] = cfg.batch * tau / ((Kd * draft_us + verify_us + accept_us) * 1e-6)
         out["projection_note"] = f"PROJECTION: (paper tau {tau} tokens/cycle, Table 2 T=0 avg, tree drafting on A800) / measured cycle time; random-init drafts are almost never accepted"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, K, args.seed)

@@ -95,6 +95,7 @@ struct hivis_ctx {
     int vrows = 0;                                        // rows of the last verify pass (chain: B*(K+1); tree: N+1)
     float *tH = nullptr, *tlogits = nullptr, *tcat = nullptr, *troll = nullptr;   // hidden rows, their logits, level inputs, re-feed inputs
     void** kv_ptrs = nullptr; void* kv_staging = nullptr;
+    float* splitk_ws = nullptr; size_t splitk_floats = 0; bool no_wide_gemm = false;   // K-slice partials of the wide GEMM; HIVIS_WIDE_GEMM=0 disables it
     int32_t* h_tree_result = nullptr;                     // pinned [1 + TREE_MAX_DEPTH + 1]
 
     // timing
@@ -188,11 +189,15 @@ int upload_layer(hivis_ctx* c, const hivis_layer_weights& w, void* staging, Laye
 // column chunks per row for the row-wise kernels: few rows -> split every row over several workgroups
 static inline int row_chunks(int rows) { return rows >= 256 ? 1 : std::max(1, std::min(8, 256 / std::max(rows, 1))); }
 
+int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy);
+
 // ---- launches --------------------------------------------------------------------------------
 template <typename WT>
 int gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy, int epi) {
     if (M < 1 || M > MAX_ROWS) return fail(c, HIVIS_EINVAL, "gemm rows %d out of range", M);
-    if (M > CHAIN_MAX_ROWS) {            // wider passes (tree verify): one launch per 32 rows
+    if (M > CHAIN_MAX_ROWS) {            // wider passes (tree verify)
+        if (sizeof(WT) == 2 && c->pf_frag && c->pf_rows >= MAX_ROWS && ldy == N && !c->no_wide_gemm) return wide_gemm(c, A, lda, M, K, Wp, N, Y, ldy);
+        // fp32 models: one launch per 32 rows
         for (int r0 = 0; r0 < M; r0 += CHAIN_MAX_ROWS)
             if (int rc = gemm<WT>(c, A + (size_t)r0 * lda, lda, std::min(CHAIN_MAX_ROWS, M - r0), K, Wp, N, Y + (size_t)r0 * ldy, ldy, epi)) return rc;
         return HIVIS_OK;
@@ -675,6 +680,7 @@ int fused_setup(hivis_ctx* c) {
         for (const void* k : ks) HIP_TRY(c, hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
     }
     { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }
+    { const char* we = getenv("HIVIS_WIDE_GEMM"); c->no_wide_gemm = we && we[0] == '0'; }
     { const char* ke = getenv("HIVIS_KEYS_PER_SPLIT"); if (ke && atoi(ke) >= 16) c->keys_per_split = atoi(ke); }
     int nb = 0;
     HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)fused_pass_kernel<WT>, FUSED_NT, c->fused_lds));
@@ -700,12 +706,38 @@ int tall_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
     if ((size_t)macro_rows * ((ntiles + 15) / 16) >= (size_t)2 * c->num_cu) {
         const int ncol8 = (((ntiles + 15) / 16) + 7) & ~7;
         hipLaunchKernelGGL((gemm_tall_lds_kernel<8>), dim3(ncol8 * macro_rows), dim3(256), 2 * 24 * 1024, c->stream,
-                           (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M);
+                           (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M, 1, (float*)nullptr);
     } else {
         const int ncol8 = (((ntiles + 7) / 8) + 7) & ~7;
         hipLaunchKernelGGL((gemm_tall_lds_kernel<4>), dim3(ncol8 * macro_rows), dim3(256), 2 * 16 * 1024, c->stream,
-                           (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M);
+                           (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M, 1, (float*)nullptr);
     }
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
+// 33..64 rows (tree verify) in ONE pass over the weights: the LDS-tiled MFMA kernel of the prefill with the K range cut
+// into slices, so that a few hundred workgroups stream the weights (a workgroup owns 64 rows x 128 columns x one slice;
+// the activation fragments it needs are re-read by the column blocks only, not by every workgroup as in the skinny kernel).
+int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy) {
+    const int kblks = K / 32, row_tiles = (M + 7) / 8, ntiles = N / 16;
+    const size_t nfrag = (size_t)row_tiles * kblks * 64;
+    hipLaunchKernelGGL(pack_afrag_kernel, dim3((unsigned)std::min<size_t>((nfrag + 255) / 256, 65535)), dim3(256), 0, c->stream, A, lda, M, kblks, c->pf_frag);
+    const int ncol = (ntiles + 7) / 8, ncol8 = (ncol + 7) & ~7;
+    int S = std::max(1, std::min(8, (3 * c->num_cu / 2) / ncol));
+    while (S > 1 && ((S - 1) * ((kblks + S - 1) / S) >= kblks || (kblks + S - 1) / S < 4)) --S;     // no empty slice, >= 4 K blocks each
+    float* part = nullptr;
+    if (S > 1) {
+        const size_t need = (size_t)S * M * ldy;
+        if (need > c->splitk_floats) {
+            if (int rc = dev_alloc(c, &c->splitk_ws, need)) return rc;
+            c->splitk_floats = need;
+        }
+        part = c->splitk_ws;
+    }
+    hipLaunchKernelGGL((gemm_tall_lds_kernel<4>), dim3(ncol8 * S), dim3(256), 2 * 16 * 1024, c->stream,
+                       (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M, S, part);
+    if (S > 1) hipLaunchKernelGGL(splitk_reduce_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, (const float*)part, S, M, N, ldy, Y, ldy);
     HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;
 }

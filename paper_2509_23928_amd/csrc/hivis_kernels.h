@@ -392,7 +392,7 @@ typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
 template <int CTW>
 __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __restrict__ Af, int row_tiles, int kblks,
                                                              const v4u_t* __restrict__ Wp, int ntiles, float* __restrict__ Y,
-                                                             int ldy, int M) {
+                                                             int ldy, int M, int ksplit, float* __restrict__ part) {
     constexpr int RTW = 4;                       // row tiles per wavefront
     constexpr int NA = 2 * RTW, NB = 2 * CTW;    // A / B blocks per K block and workgroup
     constexpr int NBLK = NA + NB;
@@ -404,10 +404,17 @@ __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __re
     // 1-D grid, XCD-aware: workgroup L runs on XCD L % 8 (round-robin dispatch) and each XCD has its own L2.  The nrow
     // workgroups that share one block of weight columns are given consecutive slots of ONE XCD, so the weights come
     // from HBM once and from that L2 nrow-1 times (with a plain 2-D grid every XCD fetched its own copy: 10x the bytes).
+    // ksplit > 1 (few rows, weight-streaming regime): the K range is cut into ksplit slices, one workgroup each, so that
+    // enough workgroups stream the weights; slice s writes its partial sums to part[s][M][ldy] and a second kernel adds them.
     const int ncol = (ntiles + NB - 1) / NB, nrow = (row_tiles + NA - 1) / NA;
-    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const int split = blockIdx.x % ksplit, bid = blockIdx.x / ksplit;
+    const int xcd = bid % 8, slot = bid / 8;
     const int cblk = 8 * (slot / nrow) + xcd, rblk = slot % nrow;
     if (cblk >= ncol) return;
+    const int kper = (kblks + ksplit - 1) / ksplit, kb0 = split * kper;
+    const int nkb = min(kblks, kb0 + kper) - kb0;            // >= 1: the host picks ksplit so that no slice is empty
+    if (nkb <= 0) return;
+    if (ksplit > 1) Y = part + (size_t)split * M * ldy;
     const int rt_wg = rblk * NA, ct_wg = cblk * NB;
     // the blocks this wavefront copies: block id b = wave + 4 i; b < NA is an A block (row tile rt_wg + b), else a B block
     const v4u_t* src[PER_WAVE];
@@ -415,8 +422,8 @@ __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __re
     for (int i = 0; i < PER_WAVE; ++i) {
         const int b = wave + 4 * i;
         // out-of-range tiles are replaced by in-range ones (clamped index); their results are never stored
-        src[i] = (b < NA) ? Af + (size_t)min(rt_wg + b, row_tiles - 1) * kblks * 64 + lane
-                          : Wp + (size_t)min(ct_wg + (b - NA), ntiles - 1) * kblks * 64 + lane;
+        src[i] = (b < NA) ? Af + ((size_t)min(rt_wg + b, row_tiles - 1) * kblks + kb0) * 64 + lane
+                          : Wp + ((size_t)min(ct_wg + (b - NA), ntiles - 1) * kblks + kb0) * 64 + lane;
     }
     f32x4_t acc[RTW][CTW];
 #pragma unroll
@@ -430,11 +437,11 @@ __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __re
     for (int i = 0; i < PER_WAVE; ++i) sa[i] = src[i][0];
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) tall_lds[(size_t)(wave + 4 * i) * 64 + lane] = sa[i];
-    if (kblks > 1) {
+    if (nkb > 1) {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) sa[i] = src[i][(size_t)64];
     }
-    if (kblks > 2) {
+    if (nkb > 2) {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) sb[i] = src[i][(size_t)2 * 64];
     }
@@ -450,17 +457,17 @@ __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __re
         _Pragma("unroll") for (int r = 0; r < RTW; ++r)                                                            \
             _Pragma("unroll") for (int c = 0; c < CTW; ++c)                                                        \
                 acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[r]), __builtin_bit_cast(bf16x8_t, b[c]), acc[r][c], 0, 0, 0); \
-        if ((kb_) + 1 < kblks) {                                                                                   \
+        if ((kb_) + 1 < nkb) {                                                                                     \
             _Pragma("unroll") for (int i = 0; i < PER_WAVE; ++i) nxt[(size_t)(wave + 4 * i) * 64 + lane] = s_[i];  \
-            if ((kb_) + 3 < kblks) {                                                                               \
+            if ((kb_) + 3 < nkb) {                                                                                 \
                 _Pragma("unroll") for (int i = 0; i < PER_WAVE; ++i) s_[i] = src[i][(size_t)((kb_) + 3) * 64];     \
             }                                                                                                      \
         }                                                                                                          \
         lds_barrier();                                                                                             \
     }
-    for (int kb = 0; kb < kblks; kb += 2) {
+    for (int kb = 0; kb < nkb; kb += 2) {
         HIVIS_TALL_STEP(kb, sa)
-        if (kb + 1 < kblks) HIVIS_TALL_STEP(kb + 1, sb)
+        if (kb + 1 < nkb) HIVIS_TALL_STEP(kb + 1, sb)
     }
 #undef HIVIS_TALL_STEP
     const int j = lane & 15, a4 = lane >> 4;
@@ -477,6 +484,19 @@ __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __re
             if (row < M) Y[(size_t)row * ldy + col] = acc[r][c][0] + acc[r][c][2];
             if (row + 1 < M) Y[(size_t)(row + 1) * ldy + col] = acc[r][c][1] + acc[r][c][3];
         }
+    }
+}
+
+// Y[r][c] = sum over the K slices of part[s][r][c] (fixed order), r < M, c < N (N a multiple of 4).
+__global__ void splitk_reduce_kernel(const float* __restrict__ part, int ksplit, int M, int N, int ldp, float* __restrict__ Y, int ldy) {
+    const int row = blockIdx.x;
+    for (int c4 = blockIdx.y * blockDim.x + threadIdx.x; c4 < N / 4; c4 += gridDim.y * blockDim.x) {
+        float4 acc = *reinterpret_cast<const float4*>(part + (size_t)row * ldp + 4 * c4);
+        for (int s = 1; s < ksplit; ++s) {
+            const float4 v = *reinterpret_cast<const float4*>(part + ((size_t)s * M + row) * ldp + 4 * c4);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        *reinterpret_cast<float4*>(Y + (size_t)row * ldy + 4 * c4) = acc;
     }
 }
 

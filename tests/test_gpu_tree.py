@@ -241,3 +241,13 @@ def test_tree_error_codes():
     with pytest.raises(HivisError) as e:
         hv2.tree_draft(2, 2, 3)                             # batch 2
     assert e.value.code == HIVIS_EINVAL
+
+
+def test_tree_full_width_7b_two_layer_slice():
+    """The paper's tree setting (top-10, depth 6, 60 candidates) at LLaVA-1.5-7B layer width and vocabulary, two target
+    layers (what the oracle finishes in seconds): 61 verify rows against 576 visual + 64 text cached rows."""
+    cfg = synth.get_config("C2").scaled(name="C2-2layer", n_layers=2, gen_tokens=0, gen_cycles=2)
+    t = TreeSideBySide(cfg, 9, room=160)
+    t.cycle(10, 6, 60)
+    t.cycle(8, 4, 30)
+    print("7B-width tree max error / tolerance:", t.max_err, "accepted:", t.n_hist, "near ties:", t.near_ties)

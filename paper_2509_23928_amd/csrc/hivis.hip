@@ -93,9 +93,10 @@ struct hivis_ctx {
     hivis::TreeDev tree{}; bool tree_ready = false;
     int tk = 0, tdepth = 0, tn = 0;                       // top-k, depth, candidates of the current tree
     int vrows = 0;                                        // rows of the last verify pass (chain: B*(K+1); tree: N+1)
-    float *tH = nullptr, *tlogits = nullptr, *tcat = nullptr, *troll = nullptr;   // hidden rows, their logits, level inputs, re-feed inputs
+    float *tH = nullptr, *tlogits = nullptr, *tcat = nullptr, *troll = nullptr;
+    float *tcand_v = nullptr, *tseg = nullptr; int32_t* tcand_i = nullptr; int tnseg = 0;   // per-segment top-k candidates and (max, sum) partials   // hidden rows, their logits, level inputs, re-feed inputs
     void** kv_ptrs = nullptr; void* kv_staging = nullptr;
-    float* splitk_ws = nullptr; size_t splitk_floats = 0; bool no_wide_gemm = false;   // K-slice partials of the wide GEMM; HIVIS_WIDE_GEMM=0 disables it
+    float* splitk_ws = nullptr; size_t splitk_floats = 0; bool no_wide_gemm = false; int wide_min = 33;   // K-slice partials of the wide GEMM; HIVIS_WIDE_GEMM=0 disables it
     int32_t* h_tree_result = nullptr;                     // pinned [1 + TREE_MAX_DEPTH + 1]
 
     // timing
@@ -195,8 +196,9 @@ int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
 template <typename WT>
 int gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy, int epi) {
     if (M < 1 || M > MAX_ROWS) return fail(c, HIVIS_EINVAL, "gemm rows %d out of range", M);
+    if (sizeof(WT) == 2 && M >= c->wide_min && c->pf_frag && c->pf_rows >= MAX_ROWS && ldy == N && epi == EPI_STORE && !c->no_wide_gemm)
+        return wide_gemm(c, A, lda, M, K, Wp, N, Y, ldy);
     if (M > CHAIN_MAX_ROWS) {            // wider passes (tree verify)
-        if (sizeof(WT) == 2 && c->pf_frag && c->pf_rows >= MAX_ROWS && ldy == N && !c->no_wide_gemm) return wide_gemm(c, A, lda, M, K, Wp, N, Y, ldy);
         // fp32 models: one launch per 32 rows
         for (int r0 = 0; r0 < M; r0 += CHAIN_MAX_ROWS)
             if (int rc = gemm<WT>(c, A + (size_t)r0 * lda, lda, std::min(CHAIN_MAX_ROWS, M - r0), K, Wp, N, Y + (size_t)r0 * ldy, ldy, epi)) return rc;
@@ -681,6 +683,7 @@ int fused_setup(hivis_ctx* c) {
     }
     { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }
     { const char* we = getenv("HIVIS_WIDE_GEMM"); c->no_wide_gemm = we && we[0] == '0'; }
+    { const char* we = getenv("HIVIS_WIDE_MIN"); if (we && atoi(we) >= 1) c->wide_min = atoi(we); }
     { const char* ke = getenv("HIVIS_KEYS_PER_SPLIT"); if (ke && atoi(ke) >= 16) c->keys_per_split = atoi(ke); }
     int nb = 0;
     HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)fused_pass_kernel<WT>, FUSED_NT, c->fused_lds));
@@ -735,7 +738,7 @@ int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
         }
         part = c->splitk_ws;
     }
-    hipLaunchKernelGGL((gemm_tall_lds_kernel<4>), dim3(ncol8 * S), dim3(256), 2 * 16 * 1024, c->stream,
+    hipLaunchKernelGGL((gemm_tall_lds_kernel<4, 4>), dim3(ncol8 * S), dim3(256), 2 * 16 * 1024, c->stream,
                        (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M, S, part);
     if (S > 1) hipLaunchKernelGGL(splitk_reduce_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, (const float*)part, S, M, N, ldy, Y, ldy);
     HIP_TRY(c, hipGetLastError());
@@ -989,6 +992,10 @@ int tree_setup(hivis_ctx* c) {
     if ((rc = dev_alloc(c, &c->tlogits, (size_t)(R + 1) * V))) return rc;
     if ((rc = dev_alloc(c, &c->tcat, (size_t)TREE_MAX_TOPK * 2 * d))) return rc;
     if ((rc = dev_alloc(c, &c->troll, (size_t)(D + 1) * 2 * d))) return rc;
+    c->tnseg = (V + TOPK_SEG - 1) / TOPK_SEG;
+    if ((rc = dev_alloc(c, &c->tcand_v, (size_t)TREE_MAX_TOPK * c->tnseg * TREE_MAX_TOPK))) return rc;
+    if ((rc = dev_alloc(c, &c->tcand_i, (size_t)TREE_MAX_TOPK * c->tnseg * TREE_MAX_TOPK))) return rc;
+    if ((rc = dev_alloc(c, &c->tseg, (size_t)TREE_MAX_TOPK * c->tnseg * 2))) return rc;
     // cache pointers of all target layers (keys, values) for the compaction kernels, and their staging rows
     std::vector<void*> ptrs;
     for (int l = 0; l < g.n_layers; ++l) { ptrs.push_back(c->tkv[l].k); ptrs.push_back(c->tkv[l].v); }
@@ -1011,7 +1018,12 @@ int do_tree_draft(hivis_ctx* c, int k, int depth, int N) {
     // hidden row 0 = the drafter's pending state f'_1; its distribution gives level 1
     hipLaunchKernelGGL(copy_rows_kernel, dim3(1), dim3(256), 0, c->stream, (const float*)c->catD, 2 * d, c->tH, d, d);
     if (int rc = gemm<WT>(c, c->tH, d, 1, d, c->lm_head, V, c->tlogits, V, EPI_STORE)) return rc;
-    hipLaunchKernelGGL(tree_children_kernel, dim3(1), dim3(TOPK_NT), 0, c->stream, (const float*)c->tlogits, V, k, 0, (const int32_t*)nullptr, 1, 0, t);
+    const int nseg = c->tnseg;
+    const size_t child_lds = (size_t)nseg * k * 2 * sizeof(float);
+    if (child_lds > 48 * 1024) return fail(c, HIVIS_EINVAL, "vocabulary too large for the top-k merge (%d segments x %d)", nseg, k);
+    hipLaunchKernelGGL(tree_topk_part_kernel, dim3(1, nseg), dim3(TOPK_NT), 0, c->stream, (const float*)c->tlogits, V, k, c->tcand_v, c->tcand_i, c->tseg);
+    hipLaunchKernelGGL(tree_children_kernel, dim3(1), dim3(CHILD_NT), child_lds, c->stream, (const float*)c->tcand_v, (const int32_t*)c->tcand_i, (const float*)c->tseg, nseg, k, 0,
+                       (const int32_t*)nullptr, 1, 0, t);
     int lo = 0, n = k;
     for (int j = 1; j < depth; ++j) {
         const int n_prev = (j - 1) * k, row0 = 1 + n_prev;
@@ -1023,7 +1035,9 @@ int do_tree_draft(hivis_ctx* c, int k, int depth, int N) {
                                          c->tH + (size_t)row0 * d, d, tr)) return rc;
         if (int rc = gemm<WT>(c, c->tH + (size_t)row0 * d, d, k, d, c->lm_head, V, c->tlogits + (size_t)row0 * V, V, EPI_STORE)) return rc;
         const int first = lo + n;
-        hipLaunchKernelGGL(tree_children_kernel, dim3(k), dim3(TOPK_NT), 0, c->stream, (const float*)(c->tlogits + (size_t)row0 * V), V, k, first, E, j + 1, row0, t);
+        hipLaunchKernelGGL(tree_topk_part_kernel, dim3(k, nseg), dim3(TOPK_NT), 0, c->stream, (const float*)(c->tlogits + (size_t)row0 * V), V, k, c->tcand_v, c->tcand_i, c->tseg);
+        hipLaunchKernelGGL(tree_children_kernel, dim3(k), dim3(CHILD_NT), child_lds, c->stream, (const float*)c->tcand_v, (const int32_t*)c->tcand_i, (const float*)c->tseg, nseg, k, first,
+                           E, j + 1, row0, t);
         lo = first; n = k * k;
     }
     hipLaunchKernelGGL(tree_select_kernel, dim3(1), dim3(1024), 0, c->stream, lo + n, N, (const int32_t*)c->text, (const int*)c->dlen, t);

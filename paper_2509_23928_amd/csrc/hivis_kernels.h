@@ -389,7 +389,7 @@ __global__ void pack_afrag_kernel(const float* __restrict__ A, int lda, int M, i
 // wavefront (a register-only version, 8 fragment loads per 16 MFMAs per wavefront, was bound by L1 fill bandwidth).
 // Two LDS stages; the global loads of K block k+1 are in flight while block k is multiplied; one LDS-only barrier per block.
 typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
-template <int CTW>
+template <int CTW, int NSET = 2>
 __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __restrict__ Af, int row_tiles, int kblks,
                                                              const v4u_t* __restrict__ Wp, int ntiles, float* __restrict__ Y,
                                                              int ldy, int M, int ksplit, float* __restrict__ part) {
@@ -430,46 +430,54 @@ __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __re
     for (int r = 0; r < RTW; ++r)
 #pragma unroll
         for (int c = 0; c < CTW; ++c) acc[r][c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    // Global loads run TWO K blocks ahead of the multiplication (one block is ~0.4 us of MFMA work, less than an L2 round
-    // trip): block kb+1 waits in registers `sa`/`sb` while block kb+2 is in flight in the other set.
-    v4u_t sa[PER_WAVE], sb[PER_WAVE];
+    // Global loads run NSET K blocks ahead of the multiplication: block kb+1 waits in register set (kb+1) % NSET while
+    // blocks kb+2 .. kb+NSET are in flight in the other sets.  NSET = 2 for the prefill (one block is ~0.4 us of MFMA
+    // work, a little less than an L2 round trip); NSET = 4 in the few-row weight-streaming regime, where the MFMA work
+    // per block is small and the bytes in flight per workgroup set the bandwidth.
+    v4u_t st[NSET][PER_WAVE];
 #pragma unroll
-    for (int i = 0; i < PER_WAVE; ++i) sa[i] = src[i][0];
+    for (int i = 0; i < PER_WAVE; ++i) st[0][i] = src[i][0];
 #pragma unroll
-    for (int i = 0; i < PER_WAVE; ++i) tall_lds[(size_t)(wave + 4 * i) * 64 + lane] = sa[i];
-    if (nkb > 1) {
+    for (int i = 0; i < PER_WAVE; ++i) tall_lds[(size_t)(wave + 4 * i) * 64 + lane] = st[0][i];
 #pragma unroll
-        for (int i = 0; i < PER_WAVE; ++i) sa[i] = src[i][(size_t)64];
-    }
-    if (nkb > 2) {
+    for (int b = 1; b <= NSET; ++b) {
+        if (b < nkb) {
 #pragma unroll
-        for (int i = 0; i < PER_WAVE; ++i) sb[i] = src[i][(size_t)2 * 64];
+            for (int i = 0; i < PER_WAVE; ++i) st[b % NSET][i] = src[i][(size_t)b * 64];
+        }
     }
     lds_barrier();
-    // one K block: multiply block kb_ from its LDS stage, park block kb_+1 (registers s_) in the other stage, request kb_+3
-#define HIVIS_TALL_STEP(kb_, s_)                                                                                   \
-    {                                                                                                              \
-        const v4u_t* cur = tall_lds + (size_t)((kb_) & 1) * NBLK * 64;                                             \
-        v4u_t* nxt = tall_lds + (size_t)(((kb_) + 1) & 1) * NBLK * 64;                                             \
-        v4u_t a[RTW], b[CTW];                                                                                      \
-        _Pragma("unroll") for (int r = 0; r < RTW; ++r) a[r] = cur[(size_t)(wr * RTW + r) * 64 + lane];            \
-        _Pragma("unroll") for (int c = 0; c < CTW; ++c) b[c] = cur[(size_t)(NA + wc * CTW + c) * 64 + lane];       \
-        _Pragma("unroll") for (int r = 0; r < RTW; ++r)                                                            \
-            _Pragma("unroll") for (int c = 0; c < CTW; ++c)                                                        \
-                acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[r]), __builtin_bit_cast(bf16x8_t, b[c]), acc[r][c], 0, 0, 0); \
-        if ((kb_) + 1 < nkb) {                                                                                     \
-            _Pragma("unroll") for (int i = 0; i < PER_WAVE; ++i) nxt[(size_t)(wave + 4 * i) * 64 + lane] = s_[i];  \
-            if ((kb_) + 3 < nkb) {                                                                                 \
-                _Pragma("unroll") for (int i = 0; i < PER_WAVE; ++i) s_[i] = src[i][(size_t)((kb_) + 3) * 64];     \
-            }                                                                                                      \
-        }                                                                                                          \
-        lds_barrier();                                                                                             \
+    for (int kb0_ = 0; kb0_ < nkb; kb0_ += NSET) {
+#pragma unroll
+        for (int u = 0; u < NSET; ++u) {
+            // one K block: multiply block kb from its LDS stage, park block kb+1 (register set (u+1) % NSET) in the other
+            // stage, request block kb+1+NSET into that set
+            const int kb = kb0_ + u;
+            if (kb < nkb) {
+                const v4u_t* cur = tall_lds + (size_t)(kb & 1) * NBLK * 64;
+                v4u_t* nxt = tall_lds + (size_t)((kb + 1) & 1) * NBLK * 64;
+                v4u_t a[RTW], b[CTW];
+#pragma unroll
+                for (int r = 0; r < RTW; ++r) a[r] = cur[(size_t)(wr * RTW + r) * 64 + lane];
+#pragma unroll
+                for (int c = 0; c < CTW; ++c) b[c] = cur[(size_t)(NA + wc * CTW + c) * 64 + lane];
+#pragma unroll
+                for (int r = 0; r < RTW; ++r)
+#pragma unroll
+                    for (int c = 0; c < CTW; ++c)
+                        acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[r]), __builtin_bit_cast(bf16x8_t, b[c]), acc[r][c], 0, 0, 0);
+                if (kb + 1 < nkb) {
+#pragma unroll
+                    for (int i = 0; i < PER_WAVE; ++i) nxt[(size_t)(wave + 4 * i) * 64 + lane] = st[(u + 1) % NSET][i];
+                    if (kb + 1 + NSET < nkb) {
+#pragma unroll
+                        for (int i = 0; i < PER_WAVE; ++i) st[(u + 1) % NSET][i] = src[i][(size_t)(kb + 1 + NSET) * 64];
+                    }
+                }
+                lds_barrier();
+            }
+        }
     }
-    for (int kb = 0; kb < nkb; kb += 2) {
-        HIVIS_TALL_STEP(kb, sa)
-        if (kb + 1 < nkb) HIVIS_TALL_STEP(kb + 1, sb)
-    }
-#undef HIVIS_TALL_STEP
     const int j = lane & 15, a4 = lane >> 4;
 #pragma unroll
     for (int r = 0; r < RTW; ++r) {

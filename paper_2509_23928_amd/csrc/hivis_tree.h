@@ -50,45 +50,89 @@ __device__ __forceinline__ void block_best(float& v, int& i, float* smf, int* sm
     }
 }
 
-// Children of the rows of one level: row r of `logits` is the drafter's distribution behind node expand_row[r] (or
-// behind the root if expand_row is null).  Its k most probable tokens (best first) become pool nodes
-// first + r k + q with score = parent score + log softmax.  One workgroup per row; round q picks the best element
-// that comes after round q-1's pick in the (value descending, index ascending) order.
-constexpr int TOPK_NT = 512;
-__global__ __launch_bounds__(TOPK_NT) void tree_children_kernel(const float* __restrict__ logits, int V, int k, int first,
-                                                                const int32_t* __restrict__ expand_row, int depth, int hid_row0,
-                                                                TreeDev t) {
+// Children of the rows of one level, in two kernels.  Row r of `logits` is the drafter's distribution behind node
+// expand_row[r] (or behind the root if expand_row is null); its k most probable tokens (best first) become pool nodes
+// first + r k + q with score = parent score + log softmax.
+//  1. tree_topk_part_kernel, grid (rows, segments): a workgroup holds one segment of <= 4096 logits in registers
+//     (8 per thread, loaded once), writes the segment's (max, sum of exp) and its k best (value, index) pairs; round q
+//     picks the best element not yet taken under the order (value descending, index ascending).
+//  2. tree_children_kernel, one workgroup per row: log-normaliser from the segment partials (fixed order), the k best
+//     of the segments' candidates by rank counting, pool entries written.
+constexpr int TOPK_NT = 512, TOPK_PER = 8, TOPK_SEG = TOPK_NT * TOPK_PER;
+__global__ __launch_bounds__(TOPK_NT) void tree_topk_part_kernel(const float* __restrict__ logits, int V, int k,
+                                                                 float* __restrict__ cand_v, int32_t* __restrict__ cand_i,
+                                                                 float* __restrict__ seg_ms) {
     __shared__ float smf[TOPK_NT / 64];
     __shared__ int smi[TOPK_NT / 64];
-    const int r = blockIdx.x;
+    const int r = blockIdx.x, seg = blockIdx.y, nseg = gridDim.y;
     const float* x = logits + (size_t)r * V;
-    float mx, sum;
-    block_softmax_stats<TOPK_NT>(x, V, 1.0f, smf, &mx, &sum);
+    const int j0 = seg * TOPK_SEG;
+    float v[TOPK_PER];
+#pragma unroll
+    for (int e = 0; e < TOPK_PER; ++e) {
+        const int j = j0 + e * TOPK_NT + threadIdx.x;
+        v[e] = j < V ? x[j] : -INFINITY;
+    }
+    float m = v[0];
+#pragma unroll
+    for (int e = 1; e < TOPK_PER; ++e) m = fmaxf(m, v[e]);
+    m = block_reduce_max<TOPK_NT>(m, smf);                  // the segment is never empty (the host sizes the grid)
+    float sum = 0.f;
+#pragma unroll
+    for (int e = 0; e < TOPK_PER; ++e) sum += expf(v[e] - m);       // exp(-inf) = 0 for the padding
+    sum = wave_sum(sum);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) smf[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float total = 0.f;
+        for (int w = 0; w < TOPK_NT / 64; ++w) total += smf[w];
+        seg_ms[((size_t)r * nseg + seg) * 2] = m; seg_ms[((size_t)r * nseg + seg) * 2 + 1] = total;
+    }
+    for (int q = 0; q < k; ++q) {
+        float bv = -INFINITY; int bi = 0x7FFFFFFF;
+#pragma unroll
+        for (int e = 0; e < TOPK_PER; ++e) {
+            const int j = j0 + e * TOPK_NT + threadIdx.x;
+            if (j < V && (v[e] > bv || (v[e] == bv && j < bi))) { bv = v[e]; bi = j; }
+        }
+        block_best<TOPK_NT>(bv, bi, smf, smi);
+#pragma unroll
+        for (int e = 0; e < TOPK_PER; ++e) if (j0 + e * TOPK_NT + (int)threadIdx.x == bi) v[e] = -INFINITY;   // taken (logits are finite)
+        if (threadIdx.x == 0) {
+            const size_t o = ((size_t)r * nseg + seg) * k + q;
+            cand_v[o] = bv; cand_i[o] = bi;                    // a segment shorter than k pads with (-inf, INT_MAX)
+        }
+    }
+}
+
+constexpr int CHILD_NT = 256;
+__global__ __launch_bounds__(CHILD_NT) void tree_children_kernel(const float* __restrict__ cand_v, const int32_t* __restrict__ cand_i,
+                                                                 const float* __restrict__ seg_ms, int nseg, int k, int first,
+                                                                 const int32_t* __restrict__ expand_row, int depth, int hid_row0,
+                                                                 TreeDev t) {
+    extern __shared__ float child_lds[];                     // [nseg * k] values, [nseg * k] indices
+    const int r = blockIdx.x, n = nseg * k;
+    float* cv = child_lds; int* ci = reinterpret_cast<int*>(child_lds + n);
+    for (int i = threadIdx.x; i < n; i += CHILD_NT) { cv[i] = cand_v[(size_t)r * n + i]; ci[i] = cand_i[(size_t)r * n + i]; }
+    __syncthreads();
+    // log-normaliser: every thread adds the segments in the same order
+    float mx = -INFINITY;
+    for (int s = 0; s < nseg; ++s) mx = fmaxf(mx, seg_ms[((size_t)r * nseg + s) * 2]);
+    float sum = 0.f;
+    for (int s = 0; s < nseg; ++s) sum += seg_ms[((size_t)r * nseg + s) * 2 + 1] * expf(seg_ms[((size_t)r * nseg + s) * 2] - mx);
     const float logz = mx + logf(sum);
     const int parent = expand_row ? expand_row[r] : -1;
     const float pscore = parent >= 0 ? t.pool_score[parent] : 0.f;
-    float pv = INFINITY; int pi = -1;
-    for (int q = 0; q < k; ++q) {
-        float bv = -INFINITY; int bi = 0x7FFFFFFF;
-        for (int j = threadIdx.x; j < V; j += TOPK_NT * 8) {
-            float x8[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x8[e] = x[min(j + TOPK_NT * e, V - 1)];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int idx = j + TOPK_NT * e;
-                const float xv = x8[e];
-                const bool after = xv < pv || (xv == pv && idx > pi);
-                if (idx < V && after && (xv > bv || (xv == bv && idx < bi))) { bv = xv; bi = idx; }
-            }
-        }
-        block_best<TOPK_NT>(bv, bi, smf, smi);
-        pv = bv; pi = bi;
-        if (threadIdx.x == 0) {
-            const int n = first + r * k + q;
-            t.pool_tok[n] = bi; t.pool_par[n] = parent; t.pool_depth[n] = depth; t.pool_hid[n] = hid_row0 + r;
-            t.pool_score[n] = pscore + (bv - logz);
-            t.pool_slot[n] = -1;
+    for (int i = threadIdx.x; i < n; i += CHILD_NT) {
+        const float vi = cv[i]; const int ii = ci[i];
+        int rank = 0;
+        for (int j = 0; j < n; ++j) rank += (cv[j] > vi || (cv[j] == vi && ci[j] < ii)) ? 1 : 0;
+        if (rank < k && ii != 0x7FFFFFFF) {
+            const int node = first + r * k + rank;
+            t.pool_tok[node] = ii; t.pool_par[node] = parent; t.pool_depth[node] = depth; t.pool_hid[node] = hid_row0 + r;
+            t.pool_score[node] = pscore + (vi - logz);
+            t.pool_slot[node] = -1;
         }
     }
 }

@@ -251,3 +251,48 @@ def test_tree_full_width_7b_two_layer_slice():
     t.cycle(10, 6, 60)
     t.cycle(8, 4, 30)
     print("7B-width tree max error / tolerance:", t.max_err, "accepted:", t.n_hist, "near ties:", t.near_ties)
+
+
+def test_tree_full_size_c2_emits_the_chain_text():
+    """BASELINE's C2 at full size (32 layers), where the oracle cannot run: tree cycles (the paper's 10/6/60 setting, the
+    61-row verify pass of bench.py --tree) and chain cycles on the same prompt must emit the same text, both being the
+    target's greedy decoding; at a disagreement the library's own verify logits must show a near-tie there."""
+    from paper_2509_23928_amd import Hivis
+    cfg = synth.get_config("C2")
+    w = synth.make_weights(cfg, seed=3, bits=True, threads=8)
+    vis, ids = synth.make_prompt(cfg, seed=3)
+    hv = Hivis(cfg, w, max_text=cfg.n_text + 200)
+    del w
+    want = 24
+
+    def run(tree):
+        first = hv.prefill(vis, ids)
+        out, gaps = [int(first[0])], [np.inf]
+        while len(out) < want:
+            if tree:
+                hv.tree_draft(10, 6, 60); hv.tree_verify()
+                vlog = hv.get_logits(0)[0]
+                rows = hv.tree_get(verified=True)
+                n, toks = hv.tree_accept()
+                path = accept_path(list(rows["row_parents"]), list(rows["row_tokens"]), rows["target_tokens"])
+                assert n == len(path)
+                used = [0] + path
+            else:
+                hv.draft(cfg.K); hv.verify()
+                vlog = hv.get_logits(0)[0]
+                nn, tt = hv.accept()
+                n, toks = int(nn[0]), tt[0]
+                used = list(range(n + 1))
+            for i, r in enumerate(used):
+                srt = np.sort(vlog[r])
+                out.append(int(toks[i])); gaps.append(float(srt[-1] - srt[-2]))
+                assert int(toks[i]) == int(np.argmax(vlog[r]))
+        return out[:want], gaps[:want], float(np.sqrt(np.mean(vlog.astype(np.float64) ** 2)))
+
+    chain, gaps_c, rms = run(False)
+    tree, gaps_t, _ = run(True)
+    for i in range(want):
+        if chain[i] != tree[i]:
+            assert min(gaps_c[i], gaps_t[i]) <= 6e-2 * rms, f"token {i}: chain {chain[i]} vs tree {tree[i]} with top-2 gaps {gaps_c[i]}, {gaps_t[i]}"
+            break       # after a near-tie the two texts legitimately differ
+    print("full-size C2: tree and chain agree on", i + 1 if chain[i] == tree[i] else i, "tokens")

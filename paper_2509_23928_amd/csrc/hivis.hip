@@ -190,7 +190,10 @@ int upload_layer(hivis_ctx* c, const hivis_layer_weights& w, void* staging, Laye
 // column chunks per row for the row-wise kernels: few rows -> split every row over several workgroups
 static inline int row_chunks(int rows) { return rows >= 256 ? 1 : std::max(1, std::min(8, 256 / std::max(rows, 1))); }
 
-int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy);
+int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy, hivis::Parts* defer = nullptr);
+template <typename WT>
+int layer_forward_wide(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, hivis::Parts pending, const int* base,
+                       int offset, int seq0, int m, TreeRows tr, hivis::Parts* out_pending);
 
 // ---- launches --------------------------------------------------------------------------------
 template <typename WT>
@@ -323,6 +326,20 @@ int target_forward(hivis_ctx* c, int seq0, int nseq, int m, const int* base, int
     const hivis_config& g = c->cfg;
     const int M = nseq * m;
     const float* pending = nullptr;
+    if constexpr (sizeof(WT) == 2) {
+        if (nseq == 1 && M >= c->wide_min && M <= MAX_ROWS && c->fused && c->pf_frag && c->pf_rows >= MAX_ROWS && g.d <= 8192 && !c->no_wide_gemm) {
+            Parts pend{nullptr, 0, 0};
+            for (int l = 0; l < g.n_layers; ++l)
+                if (int rc = layer_forward_wide<WT>(c, c->layers[l], c->tkv[l], c->x, pend, base, offset, seq0, m, tr, &pend)) return rc;
+            if (pend.n > 1) hipLaunchKernelGGL(splitk_reduce_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, pend.p, pend.n, M, g.d, g.d, c->proj, g.d);
+            const int nout_w = M - first_out_row;
+            if (nout_w > 0)
+                hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(nout_w), dim3(256), 0, c->stream, c->x + (size_t)first_out_row * g.d, g.d,
+                                   (const float*)c->proj + (size_t)first_out_row * g.d, g.d, (const WT*)c->final_norm, out, ldo, g.d, g.rms_eps);
+            HIP_TRY(c, hipGetLastError());
+            return HIVIS_OK;
+        }
+    }
     for (int l = 0; l < g.n_layers; ++l) {
         // KV of layer l for all sequences
         if (int rc = layer_forward<WT>(c, c->layers[l], c->tkv[l], c->x, pending, base, offset, seq0, nseq, m, max_keys, tr)) return rc;
@@ -722,12 +739,16 @@ int tall_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
 // 33..64 rows (tree verify) in ONE pass over the weights: the LDS-tiled MFMA kernel of the prefill with the K range cut
 // into slices, so that a few hundred workgroups stream the weights (a workgroup owns 64 rows x 128 columns x one slice;
 // the activation fragments it needs are re-read by the column blocks only, not by every workgroup as in the skinny kernel).
-int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy) {
+// A == nullptr: the fragments are already in c->pf_frag (written by the producing row kernel).  defer != nullptr: the
+// slice partials are not reduced here; *defer describes them for the consuming row kernel.
+int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy, Parts* defer) {
     const int kblks = K / 32, row_tiles = (M + 7) / 8, ntiles = N / 16;
     const size_t nfrag = (size_t)row_tiles * kblks * 64;
-    hipLaunchKernelGGL(pack_afrag_kernel, dim3((unsigned)std::min<size_t>((nfrag + 255) / 256, 65535)), dim3(256), 0, c->stream, A, lda, M, kblks, c->pf_frag);
-    const int ncol = (ntiles + 7) / 8, ncol8 = (ncol + 7) & ~7;
-    int S = std::max(1, std::min(8, (3 * c->num_cu / 2) / ncol));
+    if (A) hipLaunchKernelGGL(pack_afrag_kernel, dim3((unsigned)std::min<size_t>((nfrag + 255) / 256, 65535)), dim3(256), 0, c->stream, A, lda, M, kblks, c->pf_frag);
+    const int ncol = (ntiles + 7) / 8, ncol8 = (ncol + 7) & ~7;         // 8 column tiles per workgroup
+    // about 3 workgroups per CU and at most 16 slices (swept at 61 rows: 256/384/512/768/1024 workgroups, 8/16 slices;
+    // 256-column tiles with half the slices were no faster)
+    int S = std::max(1, std::min(16, 3 * c->num_cu / ncol));
     while (S > 1 && ((S - 1) * ((kblks + S - 1) / S) >= kblks || (kblks + S - 1) / S < 4)) --S;     // no empty slice, >= 4 K blocks each
     float* part = nullptr;
     if (S > 1) {
@@ -740,7 +761,32 @@ int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
     }
     hipLaunchKernelGGL((gemm_tall_lds_kernel<4, 4>), dim3(ncol8 * S), dim3(256), 2 * 16 * 1024, c->stream,
                        (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M, S, part);
-    if (S > 1) hipLaunchKernelGGL(splitk_reduce_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, (const float*)part, S, M, N, ldy, Y, ldy);
+    if (defer) { defer->p = S > 1 ? part : Y; defer->n = S; defer->stride = (size_t)M * ldy; }
+    else if (S > 1) hipLaunchKernelGGL(splitk_reduce_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, (const float*)part, S, M, N, ldy, Y, ldy);
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
+// One decoder layer on 33..64 rows of one sequence (bf16 models): the split-K GEMMs chained through row kernels that read
+// the slice partials and write the next GEMM's fragments.  `pending` / `out_pending` as in layer_forward, as partials.
+template <typename WT>
+int layer_forward_wide(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, Parts pending, const int* base,
+                       int offset, int seq0, int m, TreeRows tr, Parts* out_pending) {
+    typedef typename KVType<WT>::type KT;
+    const hivis_config& g = c->cfg;
+    const int M = m, d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn;
+    const int nqkv = qd + 2 * kd, Mp = ((M + 7) / 8) * 8;
+    Parts pq{}, po{}, pg{};
+    hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, h, d, pending, d, M, (const WT*)L.norm1, c->pf_frag, d, g.rms_eps);
+    if (int rc = wide_gemm(c, nullptr, 0, M, d, L.wqkv, nqkv, c->qkv, nqkv, &pq)) return rc;
+    hipLaunchKernelGGL((wide_rope_append_kernel<KT>), dim3(M, 8), dim3(256), 0, c->stream, pq, c->qkv, nqkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m,
+                       (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta);
+    if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, 1, m, c->att, qd, tr.mask)) return rc;
+    if (int rc = wide_gemm(c, c->att, qd, M, qd, L.wo, d, c->proj, d, &po)) return rc;
+    hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, h, d, po, d, M, (const WT*)L.norm2, c->pf_frag, d, g.rms_eps);
+    if (int rc = wide_gemm(c, nullptr, 0, M, d, L.wgu, 2 * F, c->gu, 2 * F, &pg)) return rc;
+    hipLaunchKernelGGL(wide_silu_frag_kernel, dim3(Mp, 8), dim3(256), 0, c->stream, pg, M, F, c->pf_frag);
+    if (int rc = wide_gemm(c, nullptr, 0, M, F, L.wd, d, c->proj, d, out_pending)) return rc;
     HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;
 }

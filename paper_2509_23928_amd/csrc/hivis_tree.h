@@ -289,4 +289,154 @@ __global__ void tree_finish_kernel(const float* __restrict__ dout, const int32_t
     if (threadIdx.x == 0) { dlen[0] += n + 1; tlen[0] += n + 1; }
 }
 
+// ------------------------------------------------------------------------------------------
+// Row-wise kernels of the 33..64-row passes (bf16 models).  They read a GEMM result as the sum of its K-slice partials
+// (value = sum over s < nparts of p[s * pstride + index], fixed order) and, where the consumer is the next split-K GEMM,
+// write its A operand directly as MFMA fragments (bf16 hi/lo split, layout of pack_afrag_kernel:
+// frag[(row tile * kblks + kb) * 64 + lane], lane = 16 g + i holds k = 32 kb + 8 g .. +8 of row 8 tt + 2 (i >> 2) + (i & 1),
+// i & 2 selecting the low part), so neither the reduction nor the fragment packing is a launch of its own.
+// ------------------------------------------------------------------------------------------
+struct Parts { const float* p; int n; size_t stride; };
+
+// B slices per trip, their loads issued together (a one-load-per-trip loop costs a memory round trip per slice)
+template <int B>
+__device__ __forceinline__ void parts_add(float4& a, const Parts& ps, size_t idx, int s0) {
+    for (int s = s0; s < ps.n; s += B) {
+        float4 v[B];
+#pragma unroll
+        for (int j = 0; j < B; ++j) v[j] = *reinterpret_cast<const float4*>(ps.p + (size_t)min(s + j, ps.n - 1) * ps.stride + idx);
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            if (s + j < ps.n) { a.x += v[j].x; a.y += v[j].y; a.z += v[j].z; a.w += v[j].w; }
+    }
+}
+__device__ __forceinline__ float4 parts_load4(const Parts& ps, size_t idx) {
+    float4 a = *reinterpret_cast<const float4*>(ps.p + idx);
+    if (ps.n <= 4) parts_add<3>(a, ps, idx, 1);       // slices 1..3 in one trip
+    else parts_add<8>(a, ps, idx, 1);
+    return a;
+}
+
+// 8 consecutive values x[0..8) of row `row` at k0 (a multiple of 8) -> the two fragment chunks (high and low parts)
+__device__ __forceinline__ void store_afrag8(uint4* __restrict__ frag, int kblks, int row, int k0, const float (&x)[8], bool zero) {
+    const int tt = row >> 3, rr = row & 7, i_hi = 4 * (rr >> 1) + (rr & 1);
+    const size_t base = ((size_t)tt * kblks + (k0 >> 5)) * 64 + ((k0 >> 3) & 3) * 16;
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const bf16_t h0 = f32_to_bf16(x[2 * e]), h1 = f32_to_bf16(x[2 * e + 1]);
+        const bf16_t l0 = f32_to_bf16(x[2 * e] - bf16_to_f32(h0)), l1 = f32_to_bf16(x[2 * e + 1] - bf16_to_f32(h1));
+        hi[e] = zero ? 0u : ((uint32_t)h0 | ((uint32_t)h1 << 16));
+        lo[e] = zero ? 0u : ((uint32_t)l0 | ((uint32_t)l1 << 16));
+    }
+    frag[base + i_hi] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    frag[base + i_hi + 2] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+}
+
+// h[row] += delta (sum of partials, optional); fragments of h[row] * gain / sqrt(mean(h^2) + eps).  One workgroup per row
+// of the padded row range (rows >= M write zero fragments); d <= 8192, d % 8 == 0.
+constexpr int WNORM_NT = 512;
+template <typename WT>
+__global__ __launch_bounds__(WNORM_NT) void wide_add_norm_frag_kernel(float* __restrict__ h, int ldh, Parts delta, int ldd, int M,
+                                                                  const WT* __restrict__ gain, uint4* __restrict__ frag, int d, float eps) {
+    __shared__ float part[WNORM_NT / 64];
+    constexpr int MAXG = 2;                         // groups of 8 values per thread
+    const int row = blockIdx.x, ng = d / 8, kblks = d / 32;
+    const bool live = row < M;
+    const int rr = min(row, M - 1);
+    float x[MAXG][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < MAXG; ++k) {
+        const int gi = (int)threadIdx.x + WNORM_NT * k;
+        if (gi < ng) {
+            float4 a = *reinterpret_cast<const float4*>(h + (size_t)rr * ldh + 8 * gi), b = *reinterpret_cast<const float4*>(h + (size_t)rr * ldh + 8 * gi + 4);
+            if (delta.p) {
+                const float4 da = parts_load4(delta, (size_t)rr * ldd + 8 * gi), db = parts_load4(delta, (size_t)rr * ldd + 8 * gi + 4);
+                a.x += da.x; a.y += da.y; a.z += da.z; a.w += da.w; b.x += db.x; b.y += db.y; b.z += db.z; b.w += db.w;
+                if (live) { *reinterpret_cast<float4*>(h + (size_t)rr * ldh + 8 * gi) = a; *reinterpret_cast<float4*>(h + (size_t)rr * ldh + 8 * gi + 4) = b; }
+            }
+            x[k][0] = a.x; x[k][1] = a.y; x[k][2] = a.z; x[k][3] = a.w; x[k][4] = b.x; x[k][5] = b.y; x[k][6] = b.z; x[k][7] = b.w;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += x[k][e] * x[k][e];
+        }
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < WNORM_NT / 64; ++w) tot += part[w];
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int k = 0; k < MAXG; ++k) {
+        const int gi = (int)threadIdx.x + WNORM_NT * k;
+        if (gi < ng) {
+            float y[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = x[k][e] * to_f32(gain[8 * gi + e]) * inv;
+            store_afrag8(frag, kblks, row, 8 * gi, y, !live);
+        }
+    }
+}
+
+// act = silu(gate) * up from the interleaved gate|up result (sum of partials), written as fragments of the down projection.
+// grid (padded rows, column chunks); F % 8 == 0.
+__global__ void wide_silu_frag_kernel(Parts gu, int M, int F, uint4* __restrict__ frag) {
+    const int row = blockIdx.x, kblks = F / 32;
+    const bool live = row < M;
+    const int rr = min(row, M - 1);
+    for (int gi = blockIdx.y * blockDim.x + threadIdx.x; gi < F / 8; gi += gridDim.y * blockDim.x) {
+        const size_t o = (size_t)rr * 2 * F + (size_t)gi * 16;
+        const float4 g0 = parts_load4(gu, o), g1 = parts_load4(gu, o + 4), u0 = parts_load4(gu, o + 8), u1 = parts_load4(gu, o + 12);
+        const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w}, u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+        float y[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) y[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+        store_afrag8(frag, kblks, row, 8 * gi, y, !live);
+    }
+}
+
+// rope_append_kernel for rows whose fused QKV result arrives as partials: sums them, rotates q and k, writes q to `q_out`
+// (row stride ldq, the buffer the attention reads) and k, v to the cache.  Same position / slot rule as rope_append_kernel.
+template <typename ST>
+__global__ void wide_rope_append_kernel(Parts qkv, float* __restrict__ q_out, int ldq, int Hq, int Hkv, int HD, const int* __restrict__ base,
+                                        int offset, int seq0, int m, ST* __restrict__ kc, ST* __restrict__ vc, int maxL,
+                                        float theta, const int* __restrict__ pos_delta) {
+    const int row = blockIdx.x;
+    const int seq = seq0 + row / m;
+    const int slot = base[seq] + offset + row % m;
+    const int pos = pos_delta ? base[seq] + pos_delta[row] : slot;
+    const int half = HD / 2;
+    const size_t rbase = (size_t)row * (Hq + 2 * Hkv) * HD;
+    const int npair2 = (Hq + Hkv) * half / 2;                 // two pairs (4 adjacent columns) per trip
+    for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < npair2; idx += gridDim.y * blockDim.x) {
+        const int head = (2 * idx) / half, i = (2 * idx) % half;
+        const float4 x = parts_load4(qkv, rbase + (size_t)head * HD + 2 * i);      // pairs (i, i + hd/2) sit in columns 2i, 2i+1
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const double inv_freq = exp2(-2.0 * (double)(i + e) / (double)HD * log2((double)theta));
+            double s, c;
+            sincos((double)pos * inv_freq, &s, &c);
+            const float x1 = e ? x.z : x.x, x2 = e ? x.w : x.y;
+            y[2 * e] = (float)((double)x1 * c - (double)x2 * s);
+            y[2 * e + 1] = (float)((double)x2 * c + (double)x1 * s);
+        }
+        if (head < Hq) {
+            *reinterpret_cast<float4*>(q_out + (size_t)row * ldq + (size_t)head * HD + 2 * i) = make_float4(y[0], y[1], y[2], y[3]);
+        } else {
+            ST* dst = kc + (((size_t)seq * Hkv + (head - Hq)) * maxL + slot) * HD + 2 * i;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) from_f32(dst[e], y[e]);
+        }
+    }
+    for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < Hkv * HD / 4; idx += gridDim.y * blockDim.x) {
+        const int head = (4 * idx) / HD, c = (4 * idx) % HD;
+        const float4 v = parts_load4(qkv, rbase + (size_t)(Hq + Hkv) * HD + 4 * idx);
+        ST* dst = vc + (((size_t)seq * Hkv + head) * maxL + slot) * HD + c;
+        from_f32(dst[0], v.x); from_f32(dst[1], v.y); from_f32(dst[2], v.z); from_f32(dst[3], v.w);
+    }
+}
+
 }  // namespace hivis

@@ -202,6 +202,16 @@ def test_tree_small_bf16(variant):
         assert t.emitted == ref[: len(t.emitted)]
 
 
+def test_tree_verify_two_skinny_passes(monkeypatch):
+    """HIVIS_WIDE_GEMM=0: the 61-row GEMMs as two passes of the 32-row kernel instead of the split-K kernel."""
+    monkeypatch.setenv("HIVIS_WIDE_GEMM", "0")
+    cfg = small_bf16()
+    t = TreeSideBySide(cfg, 12)
+    t.cycle(10, 6, 60)
+    t.cycle(6, 3, 40)
+    print("two-pass tree max error / tolerance:", t.max_err)
+
+
 def test_tree_error_codes():
     from paper_2509_23928_amd import Hivis, HivisError, HIVIS_EINVAL, HIVIS_ESTATE, HIVIS_ECAP
     cfg = c1(n_vis=8, n_text=9)

@@ -96,7 +96,7 @@ struct hivis_ctx {
     float *tH = nullptr, *tlogits = nullptr, *tcat = nullptr, *troll = nullptr;
     float *tcand_v = nullptr, *tseg = nullptr; int32_t* tcand_i = nullptr; int tnseg = 0;   // per-segment top-k candidates and (max, sum) partials   // hidden rows, their logits, level inputs, re-feed inputs
     void** kv_ptrs = nullptr; void* kv_staging = nullptr;
-    float* splitk_ws = nullptr; size_t splitk_floats = 0; bool no_wide_gemm = false; int wide_min = 33;   // K-slice partials of the wide GEMM; HIVIS_WIDE_GEMM=0 disables it
+    float* splitk_ws = nullptr; size_t splitk_floats = 0; bool no_wide_gemm = false; int wide_min = 17;   // K-slice partials of the wide GEMM; HIVIS_WIDE_GEMM=0 disables it
     int32_t* h_tree_result = nullptr;                     // pinned [1 + TREE_MAX_DEPTH + 1]
 
     // timing
@@ -193,7 +193,7 @@ static inline int row_chunks(int rows) { return rows >= 256 ? 1 : std::max(1, st
 int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy, hivis::Parts* defer = nullptr);
 template <typename WT>
 int layer_forward_wide(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, hivis::Parts pending, const int* base,
-                       int offset, int seq0, int m, TreeRows tr, hivis::Parts* out_pending);
+                       int offset, int seq0, int nseq, int m, TreeRows tr, hivis::Parts* out_pending);
 
 // ---- launches --------------------------------------------------------------------------------
 template <typename WT>
@@ -327,10 +327,10 @@ int target_forward(hivis_ctx* c, int seq0, int nseq, int m, const int* base, int
     const int M = nseq * m;
     const float* pending = nullptr;
     if constexpr (sizeof(WT) == 2) {
-        if (nseq == 1 && M >= c->wide_min && M <= MAX_ROWS && c->fused && c->pf_frag && c->pf_rows >= MAX_ROWS && g.d <= 8192 && !c->no_wide_gemm) {
+        if (M >= c->wide_min && M <= MAX_ROWS && c->fused && c->pf_frag && c->pf_rows >= MAX_ROWS && g.d <= 8192 && !c->no_wide_gemm) {
             Parts pend{nullptr, 0, 0};
             for (int l = 0; l < g.n_layers; ++l)
-                if (int rc = layer_forward_wide<WT>(c, c->layers[l], c->tkv[l], c->x, pend, base, offset, seq0, m, tr, &pend)) return rc;
+                if (int rc = layer_forward_wide<WT>(c, c->layers[l], c->tkv[l], c->x, pend, base, offset, seq0, nseq, m, tr, &pend)) return rc;
             if (pend.n > 1) hipLaunchKernelGGL(splitk_reduce_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, pend.p, pend.n, M, g.d, g.d, c->proj, g.d);
             const int nout_w = M - first_out_row;
             if (nout_w > 0)
@@ -361,7 +361,15 @@ int drafter_forward(hivis_ctx* c, const float* cat, int seq0, int nseq, int m, i
     const int M = nseq * m, d = g.d;
     if (int rc = gemm<WT>(c, cat, 2 * d, M, 2 * d, c->fuse_w, d, c->u, d, EPI_STORE)) return rc;
     hipLaunchKernelGGL((add_rho_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->u, d, (const WT*)c->rho, rho_idx, d);
-    if (int rc = layer_forward<WT>(c, c->draft, c->dkv, c->u, nullptr, c->dlen, offset, seq0, nseq, m, max_keys, tr)) return rc;
+    bool wide = false;
+    if constexpr (sizeof(WT) == 2) wide = M >= c->wide_min && M <= MAX_ROWS && c->fused && c->pf_frag && c->pf_rows >= MAX_ROWS && d <= 8192 && !c->no_wide_gemm;
+    if (wide) {
+        if constexpr (sizeof(WT) == 2) {
+            Parts pend{nullptr, 0, 0};
+            if (int rc = layer_forward_wide<WT>(c, c->draft, c->dkv, c->u, pend, c->dlen, offset, seq0, nseq, m, tr, &pend)) return rc;
+            if (pend.n > 1) hipLaunchKernelGGL(splitk_reduce_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, pend.p, pend.n, M, d, d, c->proj, d);
+        }
+    } else if (int rc = layer_forward<WT>(c, c->draft, c->dkv, c->u, nullptr, c->dlen, offset, seq0, nseq, m, max_keys, tr)) return rc;
     hipLaunchKernelGGL(add_rows_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->u, d, (const float*)c->proj, d, out, ldo, d);
     HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;
@@ -767,21 +775,21 @@ int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
     return HIVIS_OK;
 }
 
-// One decoder layer on 33..64 rows of one sequence (bf16 models): the split-K GEMMs chained through row kernels that read
-// the slice partials and write the next GEMM's fragments.  `pending` / `out_pending` as in layer_forward, as partials.
+// One decoder layer on up to 64 rows (nseq sequences x m rows; bf16 models): the split-K GEMMs chained through row kernels
+// that read the slice partials and write the next GEMM's fragments.  `pending` / `out_pending` as in layer_forward, as partials.
 template <typename WT>
 int layer_forward_wide(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, Parts pending, const int* base,
-                       int offset, int seq0, int m, TreeRows tr, Parts* out_pending) {
+                       int offset, int seq0, int nseq, int m, TreeRows tr, Parts* out_pending) {
     typedef typename KVType<WT>::type KT;
     const hivis_config& g = c->cfg;
-    const int M = m, d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn;
+    const int M = nseq * m, d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn;
     const int nqkv = qd + 2 * kd, Mp = ((M + 7) / 8) * 8;
     Parts pq{}, po{}, pg{};
     hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, h, d, pending, d, M, (const WT*)L.norm1, c->pf_frag, d, g.rms_eps);
     if (int rc = wide_gemm(c, nullptr, 0, M, d, L.wqkv, nqkv, c->qkv, nqkv, &pq)) return rc;
     hipLaunchKernelGGL((wide_rope_append_kernel<KT>), dim3(M, 8), dim3(256), 0, c->stream, pq, c->qkv, nqkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m,
                        (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta);
-    if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, 1, m, c->att, qd, tr.mask)) return rc;
+    if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd, tr.mask)) return rc;
     if (int rc = wide_gemm(c, c->att, qd, M, qd, L.wo, d, c->proj, d, &po)) return rc;
     hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, h, d, po, d, M, (const WT*)L.norm2, c->pf_frag, d, g.rms_eps);
     if (int rc = wide_gemm(c, nullptr, 0, M, d, L.wgu, 2 * F, c->gu, 2 * F, &pg)) return rc;

@@ -306,3 +306,18 @@ def test_tree_full_size_c2_emits_the_chain_text():
             assert min(gaps_c[i], gaps_t[i]) <= 6e-2 * rms, f"token {i}: chain {chain[i]} vs tree {tree[i]} with top-2 gaps {gaps_c[i]}, {gaps_t[i]}"
             break       # after a near-tie the two texts legitimately differ
     print("full-size C2: tree and chain agree on", i + 1 if chain[i] == tree[i] else i, "tokens")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tree_maximum_sizes(dtype):
+    """The library's limits at once: top_k 16, 64 drafter tree rows (mask bit 63), 63 candidates = 64 verify rows."""
+    cfg = c1(n_vis=40, n_text=11) if dtype == "f32" else small_bf16(n_vis=90, n_text=21)
+    t = TreeSideBySide(cfg, 13)
+    t.cycle(16, 5, 63)
+    ref, _ = greedy_reference(cfg, t.w, t.vis[0], t.ids[0], 12)
+    tokens, parents = branching_plant(ref, len(t.emitted), cfg.vocab, 8, 7)      # 63 planted rows, depth 9, path on rows 7, 14, .. 56
+    n, path = t.planted_cycle(tokens, parents)
+    if t.near_ties == 0:
+        assert n == 8 and path[-1] == 56
+    t.cycle(16, 5, 63)
+    print(dtype, "maximum-size tree max error / tolerance:", t.max_err, "accepted:", t.n_hist)

@@ -279,6 +279,32 @@ template <typename WT>
 int attention_rows_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int* base, int offset, int seq0, int nseq, int m,
                         float* out, int ldo, const unsigned long long* tmask = nullptr) {
     const hivis_config& g = c->cfg;
+    typedef typename KVType<WT>::type KT;
+    if constexpr (std::is_same<KT, f16_t>::value) {
+        if (m > FUSED_RMAX) {
+            // many rows per sequence: 16 (head,row) pairs per work item
+            AttnShape sh{};
+            sh.Hq = g.n_q_heads; sh.Hkv = g.n_kv_heads; sh.m = m;
+            const int group = g.n_q_heads / g.n_kv_heads;
+            if (m >= ATTN_ROWS_RM) { sh.mi = ATTN_ROWS_RM; sh.gh = 1; }
+            else { sh.mi = m; sh.gh = std::max(1, std::min(group, ATTN_ROWS_RM / m)); }
+            sh.n_hblk = (group + sh.gh - 1) / sh.gh; sh.n_rblk = (m + sh.mi - 1) / sh.mi;
+            sh.seq0 = seq0; sh.offset = offset; sh.maxL = kv.maxL; sh.ldq = ldq; sh.nwaves = FUSED_NW; sh.nsplit = 1; sh.tmask = tmask;
+            const int items = nseq * g.n_kv_heads * sh.n_hblk * sh.n_rblk;
+            const size_t lds = fused_attn_mfma_lds_floats(g.head_dim, FUSED_NW, ATTN_ROWS_RM) * sizeof(float);
+            if (g.head_dim == 128) {
+                static bool attr128 = false;
+                if (!attr128) { HIP_TRY(c, hipFuncSetAttribute((const void*)attn_rows_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); attr128 = true; }
+                hipLaunchKernelGGL((attn_rows_kernel<128>), dim3(items), dim3(FUSED_NT), lds, c->stream, q, (const f16_t*)kv.k, (const f16_t*)kv.v, base, sh, out, ldo);
+            } else {
+                static bool attr64 = false;
+                if (!attr64) { HIP_TRY(c, hipFuncSetAttribute((const void*)attn_rows_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); attr64 = true; }
+                hipLaunchKernelGGL((attn_rows_kernel<64>), dim3(items), dim3(FUSED_NT), lds, c->stream, q, (const f16_t*)kv.k, (const f16_t*)kv.v, base, sh, out, ldo);
+            }
+            HIP_TRY(c, hipGetLastError());
+            return HIVIS_OK;
+        }
+    }
     int items = 0;
     Phase ph{};
     ph.type = PH_ATTN;

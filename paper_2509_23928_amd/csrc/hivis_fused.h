@@ -792,6 +792,16 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     attn_wg_finish<HD, RM>(mrg, flag, sh, item_id, split, R, ni, kvh * group + h0, i0, sl, ws, cnt, att_out, ldo, marks);
 }
 
+// The MFMA attention as a kernel of its own, with all 16 MFMA columns holding real (head,row) pairs: passes with many
+// rows per sequence (prefill, tree verify) read every cached key half as often as with 8 pairs per work item.
+constexpr int ATTN_ROWS_RM = 16;
+template <int HD>
+__global__ __launch_bounds__(FUSED_NT) void attn_rows_kernel(const float* __restrict__ q, const f16_t* __restrict__ kc, const f16_t* __restrict__ vc,
+                                                             const int* __restrict__ base, AttnShape sh, float* __restrict__ out, int ldo) {
+    extern __shared__ __align__(16) float attn_rows_lds[];
+    attn_wg_mfma<HD, ATTN_ROWS_RM>(q, kc, vc, base, sh, blockIdx.x, 0, attn_rows_lds, nullptr, nullptr, out, ldo);
+}
+
 template <typename KT, int HD, int RM>
 __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, const KT* __restrict__ kc, const KT* __restrict__ vc,
                                                 const int* __restrict__ base, const AttnShape& sh, int item_id, int split,

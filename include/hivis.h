@@ -156,7 +156,8 @@ int hivis_accept_sample(hivis_ctx *ctx, float temperature, const float *u_accept
 /* ---- the same cycle with a draft TREE instead of a chain (section 4, inference setting: a top-k tree expanded to a
  * fixed depth, the candidates with the highest cumulative probability verified in one pass; section 2.1 names the tree
  * structure).  Greedy (T = 0), batch 1 only.  The three calls replace hivis_draft / hivis_verify / hivis_accept in a
- * cycle; chain and tree cycles may alternate on one context. ---- */
+ * cycle; chain and tree cycles may alternate on one context.  The first tree call on a context allocates the tree's
+ * device arrays (a few MB plus [65][vocab] floats); they are freed by hivis_destroy. ---- */
 
 /* Builds the pool and picks the candidates.  Level 1: the top_k most probable tokens after the drafter's pending
  * hidden state, scored by log-probability.  Level j+1 (j = 1..depth-1): the top_k best-scored nodes of level j go

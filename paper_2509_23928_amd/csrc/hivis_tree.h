@@ -202,6 +202,7 @@ __global__ __launch_bounds__(1024) void tree_select_kernel(int P, int N, const i
         const int i = threadIdx.x + e * 1024;
         if (i >= P || !chosen[e]) continue;
         const int row = myrow[e];
+        if (row > N) continue;                                    // only with NaN scores (ranks are then not a permutation)
         t.sel[row - 1] = i;
         t.row_tok[row] = t.pool_tok[i];
         t.row_depth[row] = t.pool_depth[i];

@@ -212,6 +212,20 @@ def test_tree_verify_two_skinny_passes(monkeypatch):
     print("two-pass tree max error / tolerance:", t.max_err)
 
 
+def test_tree_without_phase_programs(monkeypatch):
+    """HIVIS_FUSED=0: every pass on the stand-alone kernels, the half-precision cache read by the vector-ALU attention
+    (its ancestor-mask branch) instead of the MFMA routine."""
+    monkeypatch.setenv("HIVIS_FUSED", "0")
+    cfg = small_bf16(n_q_heads=8, n_kv_heads=2, head_dim=64)
+    t = TreeSideBySide(cfg, 14)
+    t.cycle(5, 4, 25)
+    ref, _ = greedy_reference(cfg, t.w, t.vis[0], t.ids[0], 12)
+    tokens, parents = branching_plant(ref, len(t.emitted), cfg.vocab, 2, 4)
+    t.planted_cycle(tokens, parents)
+    t.cycle(10, 6, 60)
+    print("stand-alone tree max error / tolerance:", t.max_err, "accepted:", t.n_hist)
+
+
 def test_tree_error_codes():
     from paper_2509_23928_amd import Hivis, HivisError, HIVIS_EINVAL, HIVIS_ESTATE, HIVIS_ECAP
     cfg = c1(n_vis=8, n_text=9)

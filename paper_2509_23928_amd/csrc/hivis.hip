@@ -781,7 +781,7 @@ int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
     if (A) hipLaunchKernelGGL(pack_afrag_kernel, dim3((unsigned)std::min<size_t>((nfrag + 255) / 256, 65535)), dim3(256), 0, c->stream, A, lda, M, kblks, c->pf_frag);
     const int ncol = (ntiles + 7) / 8, ncol8 = (ncol + 7) & ~7;         // 8 column tiles per workgroup
     // about 3 workgroups per CU and at most 16 slices (swept at 61 rows: 256/384/512/768/1024 workgroups, 8/16 slices;
-    // 256-column tiles with half the slices were no faster)
+    // 256-column tiles with half the slices were no faster, at 61 rows and at 32)
     int S = std::max(1, std::min(16, 3 * c->num_cu / ncol));
     while (S > 1 && ((S - 1) * ((kblks + S - 1) / S) >= kblks || (kblks + S - 1) / S < 4)) --S;     // no empty slice, >= 4 K blocks each
     float* part = nullptr;
@@ -793,8 +793,12 @@ int wide_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
         }
         part = c->splitk_ws;
     }
-    hipLaunchKernelGGL((gemm_tall_lds_kernel<4, 4>), dim3(ncol8 * S), dim3(256), 2 * 16 * 1024, c->stream,
-                       (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M, S, part);
+    if (row_tiles <= 4)      // at most 32 rows: 4 row tiles per workgroup, half the fragment traffic and MFMA work
+        hipLaunchKernelGGL((gemm_tall_lds_kernel<4, 4, 2>), dim3(ncol8 * S), dim3(256), 2 * 12 * 1024, c->stream,
+                           (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M, S, part);
+    else
+        hipLaunchKernelGGL((gemm_tall_lds_kernel<4, 4>), dim3(ncol8 * S), dim3(256), 2 * 16 * 1024, c->stream,
+                           (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M, S, part);
     if (defer) { defer->p = S > 1 ? part : Y; defer->n = S; defer->stride = (size_t)M * ldy; }
     else if (S > 1) hipLaunchKernelGGL(splitk_reduce_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, (const float*)part, S, M, N, ldy, Y, ldy);
     HIP_TRY(c, hipGetLastError());

@@ -389,11 +389,11 @@ __global__ void pack_afrag_kernel(const float* __restrict__ A, int lda, int M, i
 // wavefront (a register-only version, 8 fragment loads per 16 MFMAs per wavefront, was bound by L1 fill bandwidth).
 // Two LDS stages; the global loads of K block k+1 are in flight while block k is multiplied; one LDS-only barrier per block.
 typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
-template <int CTW, int NSET = 2>
+template <int CTW, int NSET = 2, int RTW = 4>
 __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __restrict__ Af, int row_tiles, int kblks,
                                                              const v4u_t* __restrict__ Wp, int ntiles, float* __restrict__ Y,
                                                              int ldy, int M, int ksplit, float* __restrict__ part) {
-    constexpr int RTW = 4;                       // row tiles per wavefront
+    // RTW = row tiles per wavefront: 4 (64 real rows per workgroup), or 2 for passes of at most 32 rows
     constexpr int NA = 2 * RTW, NB = 2 * CTW;    // A / B blocks per K block and workgroup
     constexpr int NBLK = NA + NB;
     constexpr int PER_WAVE = NBLK / 4;           // blocks each wavefront copies per K block

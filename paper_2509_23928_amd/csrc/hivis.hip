@@ -96,7 +96,7 @@ struct hivis_ctx {
     float *tH = nullptr, *tlogits = nullptr, *tcat = nullptr, *troll = nullptr;
     float *tcand_v = nullptr, *tseg = nullptr; int32_t* tcand_i = nullptr; int tnseg = 0;   // per-segment top-k candidates and (max, sum) partials   // hidden rows, their logits, level inputs, re-feed inputs
     void** kv_ptrs = nullptr; void* kv_staging = nullptr;
-    float* splitk_ws = nullptr; size_t splitk_floats = 0; bool no_wide_gemm = false; int wide_min = 17;   // K-slice partials of the wide GEMM; HIVIS_WIDE_GEMM=0 disables it
+    float* splitk_ws = nullptr; size_t splitk_floats = 0; bool no_wide_gemm = false; int wide_min = 11;   // measured: 10-row passes faster on the skinny kernels, 12-row passes on the split-K layer   // K-slice partials of the wide GEMM; HIVIS_WIDE_GEMM=0 disables it
     int32_t* h_tree_result = nullptr;                     // pinned [1 + TREE_MAX_DEPTH + 1]
 
     // timing

@@ -115,6 +115,7 @@ def main():
     ap.add_argument("--config", default="C2")
     ap.add_argument("--layers", type=int, default=0, help="override the number of target layers (debug only; invalid as a result)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (experiments only; not the named workload)")
+    ap.add_argument("--K", type=int, default=0, help="override the chain draft length (experiments only; not the named workload)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--temperature", type=float, default=0.0, help="> 0: time the temperature-sampling calls instead of the greedy ones (extra measurement, not the headline metric)")
     ap.add_argument("--tree", default="", help="top_k,depth,n_nodes: time draft-tree cycles instead of chain cycles (extra measurement, not the headline metric; batch 1)")
@@ -137,6 +138,8 @@ def main():
         cfg = cfg.scaled(n_layers=args.layers)
     if args.batch:
         cfg = cfg.scaled(batch=args.batch)
+    if args.K:
+        cfg = cfg.scaled(K=args.K)
     K = cfg.K
     t0 = time.time()
     nthreads = min(16, os.cpu_count() or 1)

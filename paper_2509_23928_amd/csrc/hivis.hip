@@ -720,7 +720,10 @@ int fused_setup(hivis_ctx* c) {
     const size_t gemm_f = fused_gemm_lds_floats(FusedCfg<WT>::NW, FusedCfg<WT>::G, TR::RPL, FusedCfg<WT>::KBW);
     const size_t attn_f = std::max(fused_attn_lds_floats(g.head_dim, FUSED_NW, FUSED_RMAX), fused_attn_mfma_lds_floats(g.head_dim, FUSED_NW, FUSED_RMAX));
     c->fused_lds = std::max(gemm_f, attn_f) * sizeof(float);
-    HIP_TRY(c, hipFuncSetAttribute((const void*)fused_pass_kernel<WT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
+    // the attribute is per kernel, not per context: contexts with different head sizes may be alive together, so it only grows
+    static size_t lds_limit = 0;
+    lds_limit = std::max(lds_limit, c->fused_lds);
+    HIP_TRY(c, hipFuncSetAttribute((const void*)fused_pass_kernel<WT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit));
     {
         const void* ks[] = {(const void*)phase_kernel<WT, PH_GEMM, FEPI_STORE, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADD_TO, false>,
                             (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADDVEC, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_QKV, false>,
@@ -730,7 +733,7 @@ int fused_setup(hivis_ctx* c) {
                             (const void*)phase_kernel<WT, PH_ATTN, 0, false>, (const void*)phase_kernel<WT, PH_ATTN_MERGE, 0, false>,
                             (const void*)phase_kernel<WT, PH_PREP, 0, false>, (const void*)phase_kernel<WT, PH_NORM_ROWS, 0, false>,
                             (const void*)phase_kernel<WT, PH_ARGMAX, 0, false>, (const void*)phase_kernel<WT, PH_SAMPLE, 0, false>};
-        for (const void* k : ks) HIP_TRY(c, hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->fused_lds));
+        for (const void* k : ks) HIP_TRY(c, hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit));
     }
     { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }
     { const char* we = getenv("HIVIS_WIDE_GEMM"); c->no_wide_gemm = we && we[0] == '0'; }

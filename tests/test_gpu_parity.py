@@ -322,3 +322,20 @@ def test_full_width_7b_layers_two_layer_slice():
             assert r[0]["n"] == 3
     hv.close()
     print("7B-width 2-layer max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+
+
+def test_two_live_contexts_with_different_head_sizes():
+    """Two contexts alive at once (head_dim 128 created first, then 64) used alternately: per-kernel launch attributes set
+    for one must not break the other."""
+    cfg_a = small_bf16(name="live-a", n_q_heads=4, n_kv_heads=4, head_dim=128)
+    cfg_b = small_bf16(name="live-b", n_q_heads=8, n_kv_heads=2, head_dim=64)
+    wa, va, ia, ha = make(cfg_a, 31)
+    wb, vb, ib, hb = make(cfg_b, 32)
+    sa = SideBySide(cfg_a, wa, ha, va, ia)
+    sb = SideBySide(cfg_b, wb, hb, vb, ib)
+    for _ in range(2):
+        sa.cycle(cfg_a.K)
+        sb.cycle(cfg_b.K)
+    ha.tree_draft(4, 3, 20); ha.tree_verify(); ha.tree_accept()
+    hb.tree_draft(4, 3, 20); hb.tree_verify(); hb.tree_accept()
+    print("two live contexts max error / tolerance:", sa.max_err, sb.max_err)

@@ -368,3 +368,12 @@ def test_tree_random_shape_sweep(seed):
     t.hv.close()
     print(f"tree sweep {seed}: {cfg.dtype} d={cfg.d} Hq/Hkv={n_q}/{n_kv} hd={hd} F={cfg.ffn} V={cfg.vocab} v={cfg.n_vis} l={cfg.n_text} N={cfg.n_layers} "
           f"tree {k}/{depth}/{n_nodes}", "max error / tolerance:", t.max_err, "accepted:", t.n_hist, "near ties:", t.near_ties)
+
+
+def test_tree_qwen_vocabulary():
+    """V = 152064 (38 top-k segments per row; LM head of the 41-row verify pass with 9504 column tiles)."""
+    cfg = small_bf16(name="tree-bigvocab", d=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=512, vocab=152064, n_vis=60, n_text=12, n_layers=1)
+    t = TreeSideBySide(cfg, 15)
+    t.cycle(10, 3, 40)
+    t.cycle(16, 2, 63)
+    print("V=152064 tree max error / tolerance:", t.max_err, "accepted:", t.n_hist, "near ties:", t.near_ties)

@@ -100,7 +100,8 @@ int hivis_destroy(hivis_ctx *ctx);
  *   text_ids   : [B][l] int32, host or device; every id in [0, vocab).
  *   first_token: [B] int32, host; receives x_{l+1} (may be NULL).
  * May be called again at any time to start new sequences (all state is reset).
- * Errors: EINVAL (null, v<0, l<1, id out of range), ECAP (v>max_vis or l+k_max+2>max_text), EHIP. */
+ * Errors: EINVAL (null, v<0, l<1, id out of range; also: the prompt's logits have no finite maximum, i.e. NaN or Inf
+ * in vis_embeds or the weights -- the context then stays un-prefilled), ECAP (v>max_vis or l+k_max+2>max_text), EHIP. */
 int hivis_prefill(hivis_ctx *ctx, const void *vis_embeds, int32_t v, const int32_t *text_ids, int32_t l,
                   int32_t *first_token);
 
@@ -125,7 +126,9 @@ int hivis_verify(hivis_ctx *ctx);
  * drafter's speculative rows are dropped and n_b+1 rows rebuilt from the target's true features
  * (section 3.3, Eq. (1)).  Synchronises.  State VERIFIED -> READY.
  *   n_accepted: [B] int32 host.   tokens: [B][k_max+1] int32 host (entries beyond n_b are -1).
- * Errors: ESTATE, EINVAL, EHIP. */
+ * Errors: ESTATE, EINVAL, EHIP.  If a pass of the cycle met logits without a finite maximum (EINVAL), or the optional
+ * one-launch pass aborted at its grid barrier (EHIP), the device state has already moved on: the context falls back
+ * to the un-prefilled state and only hivis_prefill is accepted next (it also clears both conditions). */
 int hivis_accept(hivis_ctx *ctx, int32_t *n_accepted, int32_t *tokens);
 
 /* ---- the same cycle at a temperature T > 0 (section 2.1: the accepted prefix is kept, the token after it is
@@ -236,6 +239,12 @@ int hivis_kernel_ms(hivis_ctx *ctx, double *total_ms, int64_t *launches, double 
 /* Algorithmic HBM bytes of the last verify pass and of one draft step at the current lengths
  * (every weight once, the KV rows read once; see the formulas in the implementation). */
 int hivis_algorithmic_bytes(hivis_ctx *ctx, double *verify_bytes, double *draft_step_bytes);
+
+/* Host function, no GPU needed: the rule every greedy-token kernel applies before it stores a token id (the same
+ * inline function, compiled for the host): ids below 0 become 0, ids >= vocab become vocab - 1.  Only a row of logits
+ * with no finite maximum (NaN / Inf inputs) yields such an id; the calls that synchronise (hivis_prefill, hivis_accept,
+ * hivis_tree_accept) then return HIVIS_EINVAL and the context must be prefilled again. */
+int32_t hivis_clamp_token(int32_t id, int32_t vocab);
 
 const char *hivis_last_error(hivis_ctx *ctx);   /* never NULL; "" if no error */
 const char *hivis_version(void);

@@ -77,6 +77,7 @@ def load_library(path=LIB_PATH):
         "hivis_kernel_timing": (C.c_int, [P, I32]),
         "hivis_kernel_ms": (C.c_int, [P, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
         "hivis_algorithmic_bytes": (C.c_int, [P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "hivis_clamp_token": (I32, [I32, I32]),
         "hivis_last_error": (C.c_char_p, [P]),
         "hivis_version": (C.c_char_p, []),
     }
@@ -89,7 +90,7 @@ def load_library(path=LIB_PATH):
 
 EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_set_drafts",
                     "hivis_verify", "hivis_accept", "hivis_prefill_sample", "hivis_draft_sample", "hivis_accept_sample", "hivis_tree_draft", "hivis_tree_set", "hivis_tree_verify", "hivis_tree_accept", "hivis_tree_get", "hivis_tree_get_logits", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
-                    "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes",
+                    "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes", "hivis_clamp_token",
                     "hivis_last_error", "hivis_version")
 
 

@@ -68,7 +68,8 @@ struct hivis_ctx {
     float *attn_ws = nullptr; size_t attn_ws_floats = 0;
     float *logits_v = nullptr, *logits_d = nullptr, *logits_p = nullptr;
     int32_t *row_tok = nullptr, *drafts = nullptr, *ttok = nullptr, *nacc = nullptr, *out_tok = nullptr, *next_tok = nullptr;
-    int32_t* h_result = nullptr;         // pinned host mirror of [nacc | out_tok | abort flag]
+    int32_t* h_result = nullptr;         // pinned host mirror of [nacc | out_tok | abort flag | bad-logits flag]
+    int* bad = nullptr;                  // device flag: a greedy-token kernel met a row without a finite maximum (cleared by hivis_prefill)
     float *u_draft = nullptr, *u_acc = nullptr, *u_res = nullptr;   // uniform numbers of the sampling calls: [B][k_max], [B][k_max] (row stride K), [B]
     float inv_temp = 1.0f; bool drafts_sampled = false;             // set by hivis_draft_sample; hivis_accept_sample needs the drafter's distributions
     void* vis = nullptr;        // staging for vis_embeds [B][max_vis][d]
@@ -578,7 +579,7 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
     pp.M = nseq * m; pp.nseq = nseq; pp.m = m;
     pp.d = g.d; pp.Hq = g.n_q_heads; pp.Hkv = g.n_kv_heads; pp.hd = g.head_dim; pp.F = g.ffn; pp.V = g.vocab;
     pp.eps = g.rms_eps; pp.theta = g.rope_theta; pp.inv_temp = c->inv_temp;
-    pp.bar = c->bar;
+    pp.bar = c->bar; pp.bad = c->bad;
     pp.spin_limit = 1u << 22;
     const bool do_prof = c->prof && kind == PROG_VERIFY && c->prof_left > 0;
     pp.prof = do_prof ? c->prof : nullptr;
@@ -908,6 +909,10 @@ int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_
         HIP_TRY(c, hipMemcpyAsync(c->text + (size_t)b * c->text_stride, c->h_ids.data() + (size_t)b * l, (size_t)l * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
     hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, c->tlen, B, 0);
     hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, c->dlen, B, 0);
+    // a fresh start also clears the sticky error words: the bad-logits flag and, for the one-launch-per-pass path, the
+    // barrier's arrival counter and abort flag (an aborted pass leaves the abort flag set)
+    hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, c->bad, 1, 0);
+    if (c->bar) hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, c->stream, (int*)c->bar, 2, 0);
 
     const int total = v + l;
     for (int b = 0; b < B; ++b) {
@@ -928,7 +933,7 @@ int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_
     // first token x_{l+1}: LM head on the last text row of every sequence
     if (int rc = gemm<WT>(c, c->feat + (size_t)(l - 1) * d, g.max_text * d, B, d, c->lm_head, g.vocab, c->logits_p, g.vocab, EPI_STORE)) return rc;
     if (sample) hipLaunchKernelGGL(sample_rows_kernel, dim3(B), dim3(SAMPLE_NT), 0, c->stream, (const float*)c->logits_p, g.vocab, c->inv_temp, (const float*)c->u_res, 1, c->text + l, c->text_stride);
-    else hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)c->logits_p, g.vocab, c->text + l, c->text_stride);
+    else hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)c->logits_p, g.vocab, c->text + l, c->text_stride, c->bad);
     // drafter prefill over the l text positions: rows [f^j ; Embed(x_{j+1})] + rho_0
     for (int b = 0; b < B; ++b) {
         for (int j0 = 0; j0 < l; j0 += CHAIN_MAX_ROWS) {
@@ -946,7 +951,10 @@ int do_prefill(hivis_ctx* c, const void* vis_embeds, int v, const int32_t* text_
     std::vector<int32_t> ft(B);
     for (int b = 0; b < B; ++b)
         HIP_TRY(c, hipMemcpyAsync(&ft[b], c->text + (size_t)b * c->text_stride + l, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    int bad = 0;
+    HIP_TRY(c, hipMemcpyAsync(&bad, c->bad, sizeof(int), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (bad) return fail(c, HIVIS_EINVAL, "prefill produced logits without a finite maximum (NaN or Inf in vis_embeds or in the weights); prefill again with valid inputs");
     if (first_token) for (int b = 0; b < B; ++b) first_token[b] = ft[b];
     for (int b = 0; b < B; ++b) { c->h_tlen[b] = total; c->h_dlen[b] = l; }
     c->v = v;
@@ -970,7 +978,7 @@ int do_draft(hivis_ctx* c, int K, bool sample) {
         float* lg = c->logits_d + (size_t)(i - 1) * B * V;
         if (int rc = gemm<WT>(c, c->catD, 2 * d, B, d, c->lm_head, V, lg, V, EPI_STORE)) return rc;
         if (sample) hipLaunchKernelGGL(sample_rows_kernel, dim3(B), dim3(SAMPLE_NT), 0, c->stream, (const float*)lg, V, c->inv_temp, (const float*)(c->u_draft + (i - 1)), g.k_max, c->drafts + (i - 1), g.k_max);
-        else hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)lg, V, c->drafts + (i - 1), g.k_max);
+        else hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, c->stream, (const float*)lg, V, c->drafts + (i - 1), g.k_max, c->bad);
         if (i < K) {
             hipLaunchKernelGGL((gather_rows_kernel<WT>), dim3(B), dim3(256), 0, c->stream, (const WT*)c->embed, (const int32_t*)(c->drafts + (i - 1)), g.k_max, c->catD + d, 2 * d, d);
             if (int rc = drafter_forward<WT>(c, c->catD, 0, B, 1, std::min(i, g.n_resid - 1), i - 1, max_keys + i, c->catD, 2 * d)) return rc;
@@ -999,7 +1007,7 @@ int do_verify(hivis_ctx* c) {
     if (int rc = gemm<WT>(c, c->catT, 2 * d, M, d, c->lm_head, V, c->logits_v, V, EPI_STORE)) return rc;
     // target's greedy token after each row: ttok[b][i], row stride k_max+1
     for (int b = 0; b < B; ++b)
-        hipLaunchKernelGGL(argmax_kernel, dim3(K + 1), dim3(256), 0, c->stream, (const float*)(c->logits_v + (size_t)b * (K + 1) * V), V, c->ttok + (size_t)b * (g.k_max + 1), 1);
+        hipLaunchKernelGGL(argmax_kernel, dim3(K + 1), dim3(256), 0, c->stream, (const float*)(c->logits_v + (size_t)b * (K + 1) * V), V, c->ttok + (size_t)b * (g.k_max + 1), 1, c->bad);
     HIP_TRY(c, hipGetLastError());
     pt.stop();
     return HIVIS_OK;
@@ -1036,8 +1044,12 @@ int do_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens, bool sample) {
     HIP_TRY(c, hipMemcpyAsync(c->h_result, c->nacc, nres * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     c->h_result[nres] = 0;
     if (c->fused && c->persistent) HIP_TRY(c, hipMemcpyAsync(c->h_result + nres, c->bar + 1, sizeof(unsigned), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->h_result + nres + 1, c->bad, sizeof(int), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    if (c->h_result[nres]) return fail(c, HIVIS_EHIP, "persistent kernel: grid barrier timed out (pass aborted)");
+    // Either flag means the device state (lengths, text) has already moved on from something invalid while the host
+    // mirrors have not: the context is put back to "created", which only a new hivis_prefill leaves.
+    if (c->h_result[nres]) { c->state = ST_CREATED; return fail(c, HIVIS_EHIP, "one-launch pass: grid barrier timed out (pass aborted); prefill again"); }
+    if (c->h_result[nres + 1]) { c->state = ST_CREATED; return fail(c, HIVIS_EINVAL, "a pass produced logits without a finite maximum (NaN or Inf in the inputs or weights); prefill again"); }
     const int32_t* hn = c->h_result; const int32_t* ht = c->h_result + B;
     for (size_t i = 0; i + 1 < c->kev_used; i += 2) {
         float ms = 0.f;
@@ -1089,7 +1101,18 @@ int tree_setup(hivis_ctx* c) {
     if ((rc = dev_alloc(c, &c->kv_ptrs, ptrs.size()))) return rc;
     HIP_TRY(c, hipMemcpy(c->kv_ptrs, ptrs.data(), ptrs.size() * sizeof(void*), hipMemcpyHostToDevice));
     { KT* st; if ((rc = dev_alloc(c, &st, (size_t)g.n_layers * 2 * D * kd))) return rc; c->kv_staging = st; }
-    HIP_TRY(c, hipHostMalloc((void**)&c->h_tree_result, (D + 2) * sizeof(int32_t), hipHostMallocDefault));
+    HIP_TRY(c, hipHostMalloc((void**)&c->h_tree_result, (D + 3) * sizeof(int32_t), hipHostMallocDefault));     // result [D + 2] | bad-logits flag
+    // pool and row arrays start at zero: a level whose logits have no finite maximum writes no entries, and what a later
+    // kernel then reads as a token id must still be a valid one
+    HIP_TRY(c, hipMemsetAsync(t.pool_tok, 0, P * sizeof(*t.pool_tok), c->stream)); HIP_TRY(c, hipMemsetAsync(t.pool_par, 0, P * sizeof(*t.pool_par), c->stream));
+    HIP_TRY(c, hipMemsetAsync(t.pool_score, 0, P * sizeof(*t.pool_score), c->stream)); HIP_TRY(c, hipMemsetAsync(t.pool_depth, 0, P * sizeof(*t.pool_depth), c->stream));
+    HIP_TRY(c, hipMemsetAsync(t.pool_hid, 0, P * sizeof(*t.pool_hid), c->stream)); HIP_TRY(c, hipMemsetAsync(t.pool_slot, 0, P * sizeof(*t.pool_slot), c->stream));
+    HIP_TRY(c, hipMemsetAsync(t.expand, 0, R * sizeof(*t.expand), c->stream)); HIP_TRY(c, hipMemsetAsync(t.sel, 0, R * sizeof(*t.sel), c->stream));
+    HIP_TRY(c, hipMemsetAsync(t.row_par, 0, R * sizeof(*t.row_par), c->stream)); HIP_TRY(c, hipMemsetAsync(t.row_depth, 0, R * sizeof(*t.row_depth), c->stream));
+    HIP_TRY(c, hipMemsetAsync(t.ttok, 0, R * sizeof(*t.ttok), c->stream)); HIP_TRY(c, hipMemsetAsync(t.path, 0, (D + 1) * sizeof(*t.path), c->stream));
+    HIP_TRY(c, hipMemsetAsync(t.next_tok, 0, (D + 1) * sizeof(*t.next_tok), c->stream)); HIP_TRY(c, hipMemsetAsync(t.result, 0, (D + 2) * sizeof(*t.result), c->stream));
+    HIP_TRY(c, hipMemsetAsync(t.dmask, 0, R * sizeof(*t.dmask), c->stream)); HIP_TRY(c, hipMemsetAsync(t.dpos, 0, R * sizeof(*t.dpos), c->stream));
+    HIP_TRY(c, hipMemsetAsync(t.vmask, 0, R * sizeof(*t.vmask), c->stream));
     c->tree_ready = true;
     return HIVIS_OK;
 }
@@ -1143,7 +1166,7 @@ int do_tree_verify(hivis_ctx* c) {
     TreeRows tr; tr.pos_delta = t.row_depth; tr.mask = t.vmask;
     if (int rc = target_forward<WT>(c, 0, 1, M, c->tlen, 0, c->h_tlen[0] + M, c->catT, 2 * d, 0, tr)) return rc;
     if (int rc = gemm<WT>(c, c->catT, 2 * d, M, d, c->lm_head, V, c->logits_v, V, EPI_STORE)) return rc;
-    hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->logits_v, V, t.ttok, 1);
+    hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(256), 0, c->stream, (const float*)c->logits_v, V, t.ttok, 1, c->bad);
     HIP_TRY(c, hipGetLastError());
     pt.stop();
     c->vrows = M;
@@ -1170,8 +1193,10 @@ int do_tree_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
     HIP_TRY(c, hipGetLastError());
     pt.stop();
     HIP_TRY(c, hipMemcpyAsync(c->h_tree_result, t.result, (depth + 2) * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->h_tree_result + TREE_MAX_DEPTH + 2, c->bad, sizeof(int), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     resolve_phase_events(c);
+    if (c->h_tree_result[TREE_MAX_DEPTH + 2]) { c->state = ST_CREATED; return fail(c, HIVIS_EINVAL, "a pass produced logits without a finite maximum (NaN or Inf in the inputs or weights); prefill again"); }
     const int n = c->h_tree_result[0];
     c->h_tlen[0] += n + 1; c->h_dlen[0] += n + 1;
     *n_accepted = n;
@@ -1274,7 +1299,9 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     // accepted counts and emitted tokens share one block, so one device-to-host copy into pinned memory returns both
     if ((rc = dev_alloc(c, &c->nacc, (size_t)B + (size_t)B * (g.k_max + 1)))) return rc;
     c->out_tok = c->nacc + B;
-    HIP_TRY(c, hipHostMalloc((void**)&c->h_result, ((size_t)B + (size_t)B * (g.k_max + 1) + 1) * sizeof(int32_t), hipHostMallocDefault));
+    HIP_TRY(c, hipHostMalloc((void**)&c->h_result, ((size_t)B + (size_t)B * (g.k_max + 1) + 2) * sizeof(int32_t), hipHostMallocDefault));
+    if ((rc = dev_alloc(c, &c->bad, 1))) return rc;
+    HIP_TRY(c, hipMemset(c->bad, 0, sizeof(int)));
     if ((rc = dev_alloc(c, &c->next_tok, (size_t)B * (g.k_max + 1)))) return rc;
     c->h_tlen.assign(B, 0); c->h_dlen.assign(B, 0);
     if ((rc = fused_setup<WT>(c))) return rc;
@@ -1653,6 +1680,8 @@ int hivis_algorithmic_bytes(hivis_ctx* c, double* verify_bytes, double* draft_st
     if (draft_step_bytes) *draft_step_bytes = w_layer + 2 * d * d * b + V * d * b + kv_d;
     return HIVIS_OK;
 }
+
+int32_t hivis_clamp_token(int32_t id, int32_t vocab) { return clamp_token(id, vocab); }
 
 const char* hivis_last_error(hivis_ctx* c) { return c ? c->err.c_str() : g_create_err.c_str(); }
 const char* hivis_version(void) { return "hivis-gfx950 0.1"; }

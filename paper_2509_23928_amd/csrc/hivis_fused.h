@@ -56,6 +56,7 @@ struct PassParams {
     float eps, theta;
     float inv_temp;                 // SAMPLE: 1 / temperature
     unsigned* bar;                  // [0] arrival counter (zeroed before launch), [1] abort flag
+    int* bad;                       // set to 1 when a row has no greedy token (no logit above -inf: NaN input); may be null
     unsigned spin_limit;
     unsigned long long* prof3;      // optional [grid][4] per-workgroup entry time, exit time, hardware id of one launch (one launch per phase only)
     unsigned long long* prof2;      // optional [nphases][8] finer timestamps inside GEMM phases (workgroup 0)
@@ -1075,7 +1076,10 @@ __device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp,
                 const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
                 if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
             }
-            if ((threadIdx.x & 63) == 0) st_wt(&ph.tok_out[(row / pp.m) * ph.o_sseq + (row % pp.m) * ph.o_srow], min(max(bi, 0), pp.V - 1));
+            if ((threadIdx.x & 63) == 0) {
+                if (pp.bad && (unsigned)bi >= (unsigned)pp.V) st_wt(pp.bad, 1);
+                st_wt(&ph.tok_out[(row / pp.m) * ph.o_sseq + (row % pp.m) * ph.o_srow], clamp_token(bi, pp.V));
+            }
         }
         break;
     case PH_SAMPLE:

@@ -894,9 +894,13 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
 // ------------------------------------------------------------------------------------------
 // Token-level kernels
 // ------------------------------------------------------------------------------------------
+// Token id forced into [0, V-1] (an id outside it can only come from a row without a greedy token, see argmax_kernel)
+__host__ __device__ __forceinline__ int clamp_token(int id, int V) { return id < 0 ? 0 : (id >= V ? V - 1 : id); }
 // Greedy token per row: index of the largest logit, lowest index on ties.  One workgroup per row.
+// A row in which no logit compares greater than -inf (all NaN, or all -inf) has no greedy token: the stored id is
+// clamped into [0, V-1] so that nothing downstream indexes a table out of bounds, and *bad (if given) is set to 1.
 __global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int V, int32_t* __restrict__ out,
-                                                      int out_stride) {
+                                                      int out_stride, int* __restrict__ bad) {
     __shared__ float bv[4];
     __shared__ int bi[4];
     const int row = blockIdx.x;
@@ -916,7 +920,8 @@ __global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ l
     if (threadIdx.x == 0) {
         for (int w = 1; w < 4; ++w)
             if (bv[w] > best || (bv[w] == best && bi[w] < besti)) { best = bv[w]; besti = bi[w]; }
-        out[(size_t)row * out_stride] = besti;
+        if (bad && (unsigned)besti >= (unsigned)V) *bad = 1;
+        out[(size_t)row * out_stride] = clamp_token(besti, V);
     }
 }
 

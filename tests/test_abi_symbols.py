@@ -48,3 +48,16 @@ def test_create_rejects_bad_config_without_gpu():
     assert rc == binding.HIVIS_EINVAL and not ctx.value
     assert b"multiple" in lib.hivis_last_error(None)
     assert lib.hivis_destroy(None) == 0
+
+
+def test_token_clamp_rule_on_the_host():
+    """The id a greedy-token kernel stores is forced into [0, vocab): the sentinel of a row without a finite maximum
+    (0x7FFFFFFF), negative garbage and vocab itself all land inside the table."""
+    from paper_2509_23928_amd import binding
+    lib = binding.load_library()
+    for V in (16, 1024, 152064):
+        assert lib.hivis_clamp_token(0x7FFFFFFF, V) == V - 1
+        assert lib.hivis_clamp_token(V, V) == V - 1
+        assert lib.hivis_clamp_token(-1, V) == 0 and lib.hivis_clamp_token(-2**31, V) == 0
+        for ok in (0, 1, V // 2, V - 1):
+            assert lib.hivis_clamp_token(ok, V) == ok

@@ -111,6 +111,22 @@ int hivis_prefill(hivis_ctx *ctx, const void *vis_embeds, int32_t v, const int32
  * Errors: ESTATE, EINVAL, ECAP (a sequence would exceed max_text). */
 int hivis_draft(hivis_ctx *ctx, int32_t K);
 
+/* hivis_draft for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same K drafter steps with the same kernels, one launch per step operation,
+ * but every intermediate buffer of the round (rotary tables, fusion outputs, q/k/v rows, attention partials,
+ * MLP activations, greedy candidates) lives in ONE static device array of HIVIS_NOALLOC_SCRATCH_BYTES that is part
+ * of the library's code object; the call makes no hipMalloc / hipFree and creates no events (hivis_timing does not
+ * cover it).  Inputs and outputs are those of hivis_draft: the context's pending hidden state and text-only cache
+ * in, K drafted tokens (and their logits, hivis_get_logits(1)) out.
+ *   - Limits: needs the phase programs (default; batch <= 8 for HIVIS_BF16, <= 16 for HIVIS_F32) and a round that
+ *     fits the array: otherwise HIVIS_EINVAL / HIVIS_ECAP with a message, and nothing has run.
+ *   - The array is one per GPU, shared by every context and every call on that GPU, and keeps the last call's
+ *     contents; nothing in it has to start at zero (each word is written by the round before the round reads it).
+ *     Calls that overlap on one GPU (two contexts on different streams, two host threads) race on it: serialise them.
+ * State READY -> DRAFTED.  Errors: ESTATE, EINVAL, ECAP, EHIP. */
+#define HIVIS_NOALLOC_SCRATCH_BYTES (16u << 20)
+int hivis_draft_noalloc(hivis_ctx *ctx, int32_t K);
+
 /* Test hook: plant drafts instead of running the drafter.  tokens: [B][K] int32, host.
  * State READY -> DRAFTED.  Errors: ESTATE, EINVAL, ECAP. */
 int hivis_set_drafts(hivis_ctx *ctx, const int32_t *tokens, int32_t K);

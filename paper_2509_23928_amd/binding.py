@@ -56,6 +56,7 @@ def load_library(path=LIB_PATH):
         "hivis_destroy": (C.c_int, [P]),
         "hivis_prefill": (C.c_int, [P, P, I32, P, I32, P]),
         "hivis_draft": (C.c_int, [P, I32]),
+        "hivis_draft_noalloc": (C.c_int, [P, I32]),
         "hivis_set_drafts": (C.c_int, [P, P, I32]),
         "hivis_verify": (C.c_int, [P]),
         "hivis_accept": (C.c_int, [P, P, P]),
@@ -88,7 +89,7 @@ def load_library(path=LIB_PATH):
     return lib
 
 
-EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_set_drafts",
+EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_draft_noalloc", "hivis_set_drafts",
                     "hivis_verify", "hivis_accept", "hivis_prefill_sample", "hivis_draft_sample", "hivis_accept_sample", "hivis_tree_draft", "hivis_tree_set", "hivis_tree_verify", "hivis_tree_accept", "hivis_tree_get", "hivis_tree_get_logits", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
                     "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes", "hivis_clamp_token",
                     "hivis_last_error", "hivis_version")
@@ -193,6 +194,11 @@ class Hivis:
 
     def draft(self, K):
         self._check(self.lib.hivis_draft(self.ctx, K))
+        self.K = K
+
+    def draft_noalloc(self, K):
+        """draft() with every intermediate buffer in the library's static scratch array (no device allocation)."""
+        self._check(self.lib.hivis_draft_noalloc(self.ctx, K))
         self.K = K
 
     def set_drafts(self, tokens):

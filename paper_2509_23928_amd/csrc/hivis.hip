@@ -12,10 +12,18 @@
 #include <cstring>
 #include <cstdlib>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
 using namespace hivis;
+
+// Scratch memory of hivis_draft_noalloc: a file-scope device array instead of an allocation.  Every GPU the library runs on
+// holds its own copy at its own address until the process ends.  In host code the name `scratch` is only a stand-in for
+// the symbol: the device address is looked up once per device with hipGetSymbolAddress (scratch_for_device below) and that
+// pointer, never the name, is what kernels receive.
+#define HIVIS_SCRATCH_BYTES HIVIS_NOALLOC_SCRATCH_BYTES
+static __device__ __align__(256) unsigned char scratch[HIVIS_SCRATCH_BYTES];
 
 namespace {
 
@@ -110,6 +118,10 @@ struct hivis_ctx {
     std::vector<hipEvent_t> pev; std::vector<int> pev_phase; size_t pev_used = 0;
     double phase_ms[4] = {0, 0, 0, 0}; int64_t phase_calls[4] = {0, 0, 0, 0};
     std::vector<void*> allocs;
+    // hivis_draft_noalloc: this device's address of the static scratch array, and host storage for its phase list
+    // (reserved at create, so the call itself allocates nothing on the host either)
+    void* scratch_dev = nullptr;
+    std::vector<hivis::Phase> na_phases;
 };
 
 namespace {
@@ -126,6 +138,24 @@ int fail(hivis_ctx* c, int code, const char* fmt, ...) {
         hipError_t e_ = (expr);                                                                       \
         if (e_ != hipSuccess) return fail((c), HIVIS_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
+
+// Device address of the static scratch array on device `dev` (which must be the current device): looked up once per
+// device, then kept for the life of the process.
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+std::mutex g_scratch_mu;
+int scratch_for_device(hivis_ctx* c, int dev) {
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(c, HIVIS_EINVAL, "device index %d outside [0,%d)", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        HIP_TRY(c, hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(c, HIVIS_EHIP, "hipGetSymbolAddress(scratch) returned a null address");
+        g_scratch_ptr[dev] = ptr;
+    }
+    c->scratch_dev = g_scratch_ptr[dev];
+    return HIVIS_OK;
+}
 
 template <typename T> int dev_alloc(hivis_ctx* c, T** p, size_t count) {
     void* q = nullptr;
@@ -440,7 +470,7 @@ struct Pool {
 // of the layer output (row stride ldd).
 template <typename WT>
 float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const LayerDev& L, const KVDev& kv, float* h, const int* base,
-                    int offset, int nseq, int m, float* rope, float* dst, int ldd, int* ld_out) {
+                    int offset, int nseq, int m, float* rope, float* dst, int ldd, int* ld_out, bool persistent) {
     const hivis_config& g = c->cfg;
     const int M = nseq * m;
     const int d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn, nqkv = qd + 2 * kd;
@@ -456,7 +486,7 @@ float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const Layer
     Phase a{}; a.type = PH_ATTN; a.A = qkv; a.lda = nqkv; a.kc = kv.k; a.vc = kv.v; a.maxL = kv.maxL; a.base = base; a.offset = offset;
     a.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, nqkv, &a.att_items);
     a.ws = pool.take((size_t)a.att_items * a.att.nsplit * FUSED_RMAX * (g.head_dim + 2));
-    if (c->persistent) {
+    if (persistent) {
         a.cnt = (int*)pool.take((size_t)a.att_items);  // zero from the pool's memset; the merging workgroup re-zeroes it
         a.Y = att; a.ldy = qd;
         P.push_back(a);
@@ -481,7 +511,7 @@ float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const Layer
 }
 
 template <typename WT>
-void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>& P) {
+void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>& P, bool persistent) {
     const hivis_config& g = c->cfg;
     const int B = g.batch, d = g.d, V = g.vocab, G = c->fused_grid;
     int ld = d;
@@ -492,7 +522,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
         Phase pr{}; pr.type = PH_PREP; pr.ids = c->row_tok; pr.id_sseq = m; pr.id_srow = 1; pr.gain = c->embed; pr.Y = x; pr.ldy = d;
         pr.base = c->tlen; pr.offset = 0; pr.rope = rope;
         P.push_back(pr);
-        for (int l = 0; l < g.n_layers; ++l) x = layer_phases<WT>(c, P, pool, c->layers[l], c->tkv[l], x, c->tlen, 0, B, m, rope, nullptr, 0, &ld);
+        for (int l = 0; l < g.n_layers; ++l) x = layer_phases<WT>(c, P, pool, c->layers[l], c->tkv[l], x, c->tlen, 0, B, m, rope, nullptr, 0, &ld, persistent);
         Phase nr{}; nr.type = PH_NORM_ROWS; nr.A = x; nr.lda = d; nr.gain = c->final_norm; nr.Y = c->catT; nr.ldy = 2 * d;
         P.push_back(nr);
         Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = c->catT; lm.lda = 2 * d;
@@ -522,7 +552,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
                 Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = cat; fu.lda = 2 * d;
                 fu.Y = u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = std::min(i, g.n_resid - 1);
                 P.push_back(fu);
-                layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, i - 1, B, 1, rope, cat_next, 2 * d, &ld);
+                layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, i - 1, B, 1, rope, cat_next, 2 * d, &ld, persistent);
                 cat = cat_next;
             }
         }
@@ -536,7 +566,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
         Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = c->catT; fu.lda = 2 * d;
         fu.Y = u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = 0;
         P.push_back(fu);
-        layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, 0, B, m, rope, c->dout, d, &ld);
+        layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, 0, B, m, rope, c->dout, d, &ld, persistent);
     }
     // chain the GEMM phases for the cross-barrier weight prefetch
     for (size_t i = 0; i < P.size(); ++i) {
@@ -553,12 +583,12 @@ int get_program(hivis_ctx* c, int kind, int K, hivis_ctx::Program* out) {
     if (it != c->programs.end()) { *out = it->second; return HIVIS_OK; }
     std::vector<Phase> P;
     Pool count;
-    build_phases<WT>(c, kind, K, count, P);           // sizes only
+    build_phases<WT>(c, kind, K, count, P, c->persistent);           // sizes only
     Pool pool;
     if (int rc = dev_alloc(c, &pool.base, count.used)) return rc;
     HIP_TRY(c, hipMemset(pool.base, 0, count.used * sizeof(float)));
     P.clear();
-    build_phases<WT>(c, kind, K, pool, P);
+    build_phases<WT>(c, kind, K, pool, P, c->persistent);
     hivis_ctx::Program pg;
     pg.n = (int)P.size();
     if (int rc = dev_alloc(c, &pg.dev, P.size())) return rc;
@@ -566,6 +596,72 @@ int get_program(hivis_ctx* c, int kind, int K, hivis_ctx::Program* out) {
     pg.host = new std::vector<Phase>(P);
     c->programs[key] = pg;
     *out = pg;
+    return HIVIS_OK;
+}
+
+// One launch per phase (the default way a pass runs): grids sized to the phase's work.  phases: host array of n phases.
+template <typename WT>
+int launch_phases(hivis_ctx* c, const Phase* phases, int n, int kind, int K, const PassParams& pp, bool do_prof) {
+    const hivis_config& g = c->cfg;
+    // one launch per phase; grids sized to the phase's work
+    // key splits per attention item: enough workgroups to fill the chip for long caches, a single workgroup (and no
+    // merge launch) for short ones; the program was sized for the largest split count
+    int max_keys = 0;
+    for (int b = 0; b < g.batch; ++b) max_keys = std::max(max_keys, (kind == PROG_VERIFY ? c->h_tlen[b] : c->h_dlen[b]) + K + 1);
+    for (int p = 0; p < n; ++p) {
+        Phase ph = phases[p];
+        ph.next_W = nullptr;                       // nothing is prefetched across a kernel boundary (pulling the next launch's
+                                                   // first units into L2 during the epilogue was measured: 3% slower)
+        if (ph.type == PH_ATTN || ph.type == PH_ATTN_MERGE) {
+            ph.att.nsplit = std::max(1, std::min(ph.att.nsplit, (max_keys + c->keys_per_split - 1) / c->keys_per_split));
+            if (ph.type == PH_ATTN_MERGE && ph.att.nsplit == 1) continue;
+        }
+        int grid = c->fused_grid;
+        if (ph.type == PH_ATTN) grid = std::min(grid, ph.att_items * ph.att.nsplit);
+        else if (ph.type == PH_ATTN_MERGE) grid = std::min(grid, ph.att_items);
+        else if (ph.type == PH_PREP) grid = std::min(grid, std::max(pp.M, (pp.M * g.head_dim / 2 + FUSED_NT - 1) / FUSED_NT));
+        else if (ph.type == PH_NORM_ROWS) grid = std::min(grid, pp.M);
+        else if (ph.type == PH_ARGMAX) grid = std::min(grid, (pp.M + FUSED_NW - 1) / FUSED_NW);
+        else if (ph.type == PH_SAMPLE) grid = std::min(grid, pp.M);
+        else if (ph.type == PH_GEMM && ph.epi != FEPI_LOGITS) grid = std::min(grid, ph.N / 16);
+        PassParams ppl = pp;
+        if (do_prof) { ppl.prof2 = pp.prof2 + (size_t)p * 8; if (p >= n / 2 && p < n / 2 + 8) ppl.prof3 = c->prof + 4096 * 11 + (size_t)(p - n / 2) * 4096; }
+        // kev0/kev1 (null unless this launch is timed) are attached to the dispatch itself: they read the kernel's own
+        // start and end timestamps, with no marker packets before or after it in the queue
+#define HIVIS_LAUNCH(TY, EP) do { if (single) hipExtLaunchKernelGGL((phase_kernel<WT, TY, EP, true>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, kev0, kev1, 0, ph, ppl); \
+                              else hipExtLaunchKernelGGL((phase_kernel<WT, TY, EP, false>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, kev0, kev1, 0, ph, ppl); } while (0)
+        const bool single = ph.type == PH_GEMM && ph.epi != FEPI_LOGITS && ph.epi != FEPI_SILU && ph.epi != FEPI_QKV && ph.N / 16 <= grid;   // one tile per workgroup at most
+        const bool kmatch = kind == PROG_VERIFY && ph.type == PH_GEMM && ph.epi == c->ktime_epi;
+        const int64_t kseq = kmatch ? c->ktime_seen++ : 0;
+        const bool ktimed = kmatch && (kseq % c->ktime_stride) == 0;
+        hipEvent_t kev0 = nullptr, kev1 = nullptr;
+        if (ktimed) {
+            if (c->kev_used + 2 > c->kev.size()) { hipEvent_t e0, e1; HIP_TRY(c, hipEventCreate(&e0)); HIP_TRY(c, hipEventCreate(&e1)); c->kev.push_back(e0); c->kev.push_back(e1); }
+            kev0 = c->kev[c->kev_used]; kev1 = c->kev[c->kev_used + 1];
+            c->kev_used += 2;
+            c->kbytes = (double)ph.K * ph.N * c->esize;
+        }
+        switch (ph.type) {
+        case PH_GEMM:
+            switch (ph.epi) {
+            case FEPI_STORE: HIVIS_LAUNCH(PH_GEMM, FEPI_STORE); break;
+            case FEPI_ADD_TO: HIVIS_LAUNCH(PH_GEMM, FEPI_ADD_TO); break;
+            case FEPI_ADDVEC: HIVIS_LAUNCH(PH_GEMM, FEPI_ADDVEC); break;
+            case FEPI_QKV: HIVIS_LAUNCH(PH_GEMM, FEPI_QKV); break;
+            case FEPI_SILU: HIVIS_LAUNCH(PH_GEMM, FEPI_SILU); break;
+            default: HIVIS_LAUNCH(PH_GEMM, FEPI_LOGITS); break;
+            }
+            break;
+        case PH_ATTN: HIVIS_LAUNCH(PH_ATTN, 0); break;
+        case PH_ATTN_MERGE: HIVIS_LAUNCH(PH_ATTN_MERGE, 0); break;
+        case PH_PREP: HIVIS_LAUNCH(PH_PREP, 0); break;
+        case PH_NORM_ROWS: HIVIS_LAUNCH(PH_NORM_ROWS, 0); break;
+        case PH_SAMPLE: HIVIS_LAUNCH(PH_SAMPLE, 0); break;
+        default: HIVIS_LAUNCH(PH_ARGMAX, 0); break;
+        }
+#undef HIVIS_LAUNCH
+    }
+    HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;
 }
 
@@ -585,65 +681,7 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
     pp.prof = do_prof ? c->prof : nullptr;
     pp.prof2 = do_prof ? c->prof + 4096 * 3 : nullptr;
     if (!c->persistent) {
-        // one launch per phase; grids sized to the phase's work
-        // key splits per attention item: enough workgroups to fill the chip for long caches, a single workgroup (and no
-        // merge launch) for short ones; the program was sized for the largest split count
-        int max_keys = 0;
-        for (int b = 0; b < g.batch; ++b) max_keys = std::max(max_keys, (kind == PROG_VERIFY ? c->h_tlen[b] : c->h_dlen[b]) + K + 1);
-        for (int p = 0; p < pg.n; ++p) {
-            Phase ph = (*pg.host)[p];
-            ph.next_W = nullptr;                       // nothing is prefetched across a kernel boundary (pulling the next launch's
-                                                       // first units into L2 during the epilogue was measured: 3% slower)
-            if (ph.type == PH_ATTN || ph.type == PH_ATTN_MERGE) {
-                ph.att.nsplit = std::max(1, std::min(ph.att.nsplit, (max_keys + c->keys_per_split - 1) / c->keys_per_split));
-                if (ph.type == PH_ATTN_MERGE && ph.att.nsplit == 1) continue;
-            }
-            int grid = c->fused_grid;
-            if (ph.type == PH_ATTN) grid = std::min(grid, ph.att_items * ph.att.nsplit);
-            else if (ph.type == PH_ATTN_MERGE) grid = std::min(grid, ph.att_items);
-            else if (ph.type == PH_PREP) grid = std::min(grid, std::max(pp.M, (pp.M * g.head_dim / 2 + FUSED_NT - 1) / FUSED_NT));
-            else if (ph.type == PH_NORM_ROWS) grid = std::min(grid, pp.M);
-            else if (ph.type == PH_ARGMAX) grid = std::min(grid, (pp.M + FUSED_NW - 1) / FUSED_NW);
-            else if (ph.type == PH_SAMPLE) grid = std::min(grid, pp.M);
-            else if (ph.type == PH_GEMM && ph.epi != FEPI_LOGITS) grid = std::min(grid, ph.N / 16);
-            PassParams ppl = pp;
-            if (do_prof) { ppl.prof2 = pp.prof2 + (size_t)p * 8; if (p >= pg.n / 2 && p < pg.n / 2 + 8) ppl.prof3 = c->prof + 4096 * 11 + (size_t)(p - pg.n / 2) * 4096; }
-            // kev0/kev1 (null unless this launch is timed) are attached to the dispatch itself: they read the kernel's own
-            // start and end timestamps, with no marker packets before or after it in the queue
-#define HIVIS_LAUNCH(TY, EP) do { if (single) hipExtLaunchKernelGGL((phase_kernel<WT, TY, EP, true>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, kev0, kev1, 0, ph, ppl); \
-                                  else hipExtLaunchKernelGGL((phase_kernel<WT, TY, EP, false>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, kev0, kev1, 0, ph, ppl); } while (0)
-            const bool single = ph.type == PH_GEMM && ph.epi != FEPI_LOGITS && ph.epi != FEPI_SILU && ph.epi != FEPI_QKV && ph.N / 16 <= grid;   // one tile per workgroup at most
-            const bool kmatch = kind == PROG_VERIFY && ph.type == PH_GEMM && ph.epi == c->ktime_epi;
-            const int64_t kseq = kmatch ? c->ktime_seen++ : 0;
-            const bool ktimed = kmatch && (kseq % c->ktime_stride) == 0;
-            hipEvent_t kev0 = nullptr, kev1 = nullptr;
-            if (ktimed) {
-                if (c->kev_used + 2 > c->kev.size()) { hipEvent_t e0, e1; HIP_TRY(c, hipEventCreate(&e0)); HIP_TRY(c, hipEventCreate(&e1)); c->kev.push_back(e0); c->kev.push_back(e1); }
-                kev0 = c->kev[c->kev_used]; kev1 = c->kev[c->kev_used + 1];
-                c->kev_used += 2;
-                c->kbytes = (double)ph.K * ph.N * c->esize;
-            }
-            switch (ph.type) {
-            case PH_GEMM:
-                switch (ph.epi) {
-                case FEPI_STORE: HIVIS_LAUNCH(PH_GEMM, FEPI_STORE); break;
-                case FEPI_ADD_TO: HIVIS_LAUNCH(PH_GEMM, FEPI_ADD_TO); break;
-                case FEPI_ADDVEC: HIVIS_LAUNCH(PH_GEMM, FEPI_ADDVEC); break;
-                case FEPI_QKV: HIVIS_LAUNCH(PH_GEMM, FEPI_QKV); break;
-                case FEPI_SILU: HIVIS_LAUNCH(PH_GEMM, FEPI_SILU); break;
-                default: HIVIS_LAUNCH(PH_GEMM, FEPI_LOGITS); break;
-                }
-                break;
-            case PH_ATTN: HIVIS_LAUNCH(PH_ATTN, 0); break;
-            case PH_ATTN_MERGE: HIVIS_LAUNCH(PH_ATTN_MERGE, 0); break;
-            case PH_PREP: HIVIS_LAUNCH(PH_PREP, 0); break;
-            case PH_NORM_ROWS: HIVIS_LAUNCH(PH_NORM_ROWS, 0); break;
-            case PH_SAMPLE: HIVIS_LAUNCH(PH_SAMPLE, 0); break;
-            default: HIVIS_LAUNCH(PH_ARGMAX, 0); break;
-            }
-#undef HIVIS_LAUNCH
-        }
-        HIP_TRY(c, hipGetLastError());
+        if (int rc = launch_phases<WT>(c, pg.host->data(), pg.n, kind, K, pp, do_prof)) return rc;
         if (do_prof) {
             // developer aid: timestamps (100 MHz) that workgroup 0 of each launch wrote, for one layer in the middle
             std::vector<unsigned long long> t2((size_t)pg.n * 8);
@@ -710,6 +748,34 @@ int run_program(hivis_ctx* c, int kind, int K, int nseq, int m) {
         c->prof_left--;
     }
     return HIVIS_OK;
+}
+
+// Phases a draft program of K steps needs at most (LM head, token, prep, fusion FC, QKV, attention, merge, O, gate|up, down)
+static inline size_t draft_phase_capacity(int k_max) { return (size_t)k_max * 10 + 4; }
+
+// The draft round of do_draft with every intermediate buffer inside the static scratch array: the same phase list and
+// the same kernels (always one launch per phase), built into host storage reserved at create; no allocation of any kind.
+template <typename WT>
+int draft_noalloc(hivis_ctx* c, int K) {
+    const hivis_config& g = c->cfg;
+    std::vector<Phase>& P = c->na_phases;
+    if (draft_phase_capacity(K) > P.capacity()) return fail(c, HIVIS_ECAP, "phase list of K=%d exceeds the storage reserved at create", K);
+    P.clear();
+    Pool count;
+    build_phases<WT>(c, PROG_DRAFT, K, count, P, false);            // sizes only
+    const size_t need = count.used * sizeof(float);
+    if (need > (size_t)HIVIS_SCRATCH_BYTES)
+        return fail(c, HIVIS_ECAP, "draft round of K=%d needs %zu bytes of scratch, the static array holds %u", K, need, (unsigned)HIVIS_SCRATCH_BYTES);
+    P.clear();
+    Pool pool; pool.base = (float*)c->scratch_dev;                  // the looked-up device address, not the array's name
+    build_phases<WT>(c, PROG_DRAFT, K, pool, P, false);
+    PassParams pp{};
+    pp.phases = nullptr; pp.nphases = (int)P.size();
+    pp.M = g.batch; pp.nseq = g.batch; pp.m = 1;
+    pp.d = g.d; pp.Hq = g.n_q_heads; pp.Hkv = g.n_kv_heads; pp.hd = g.head_dim; pp.F = g.ffn; pp.V = g.vocab;
+    pp.eps = g.rms_eps; pp.theta = g.rope_theta; pp.inv_temp = c->inv_temp;
+    pp.bar = c->bar; pp.bad = c->bad; pp.spin_limit = 1u << 22;
+    return launch_phases<WT>(c, P.data(), (int)P.size(), PROG_DRAFT, K, pp, false);
 }
 
 template <typename WT>
@@ -1349,7 +1415,9 @@ int hivis_create(const hivis_config* cfg, const hivis_weights* w, void* hip_stre
         g_create_err = "no HIP device"; delete c; return HIVIS_EHIP;
     }
     c->num_cu = prop.multiProcessorCount;
-    int rc = DISPATCH(c, do_create, c, w);
+    c->na_phases.reserve(draft_phase_capacity(cfg->k_max));
+    int rc = scratch_for_device(c, dev);
+    if (!rc) rc = DISPATCH(c, do_create, c, w);
     if (rc) { g_create_err = c->err; hivis_destroy(c); return rc; }
     *out = c;
     return HIVIS_OK;
@@ -1416,6 +1484,22 @@ int hivis_draft(hivis_ctx* c, int32_t K) {
     if (K < 1 || K > c->cfg.k_max) return fail(c, HIVIS_EINVAL, "K=%d outside [1,%d]", K, c->cfg.k_max);
     if (int rc = check_room(c, K)) return rc;
     int rc = DISPATCH(c, do_draft, c, K, false);
+    if (rc) return rc;
+    c->K = K; c->state = ST_DRAFTED; c->drafts_sampled = false;
+    return HIVIS_OK;
+}
+
+int hivis_draft_noalloc(hivis_ctx* c, int32_t K) {
+    if (!c) return HIVIS_EINVAL;
+    const hivis_config& g = c->cfg;
+    if (c->state != ST_READY) return fail(c, HIVIS_ESTATE, "hivis_draft_noalloc needs a prefilled/accepted context");
+    if (K < 1 || K > g.k_max) return fail(c, HIVIS_EINVAL, "K=%d outside [1,%d]", K, g.k_max);
+    const int max_rows = g.dtype == HIVIS_BF16 ? WTraits<bf16_t>::ROWS : WTraits<float>::ROWS;
+    if (!c->fused || g.batch > max_rows)
+        return fail(c, HIVIS_EINVAL, "hivis_draft_noalloc needs the phase programs (HIVIS_FUSED not 0) and batch <= %d", max_rows);
+    if (!c->scratch_dev) return fail(c, HIVIS_EHIP, "the static scratch array was not resolved at create");
+    if (int rc = check_room(c, K)) return rc;
+    int rc = DISPATCH(c, draft_noalloc, c, K);
     if (rc) return rc;
     c->K = K; c->state = ST_DRAFTED; c->drafts_sampled = false;
     return HIVIS_OK;

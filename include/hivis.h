@@ -19,8 +19,9 @@
  *     returns (weights at create; prompts at prefill) and owns all device state of a context.
  *   - dtype: HIVIS_F32 = IEEE float32; HIVIS_BF16 = bfloat16 bit patterns (uint16_t).  It is the
  *     storage type of weights, embedding tables and vis_embeds.  The KV caches are float32 for
- *     HIVIS_F32 and IEEE half (same 2 bytes as bf16, 10 mantissa bits) for HIVIS_BF16.  Activations
- *     between kernels and all accumulation are float32.
+ *     HIVIS_F32; for HIVIS_BF16 every cached value is a pair of IEEE halves hi + lo (4 bytes, ~22
+ *     mantissa bits; one half alone put the drafter's logits outside the parity tolerance at 32
+ *     layers).  Activations between kernels and all accumulation are float32.
  *   - Matrix orientation is the paper's row-vector form y = x W: W is [in][out] row-major,
  *     except embed and lm_head, which are [vocab][d] row-major.
  *   - Work is enqueued on the hipStream_t given at create.  hivis_accept, hivis_prefill (for

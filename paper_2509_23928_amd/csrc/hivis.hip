@@ -1166,7 +1166,7 @@ int tree_setup(hivis_ctx* c) {
     for (int l = 0; l < g.n_layers; ++l) { ptrs.push_back(c->tkv[l].k); ptrs.push_back(c->tkv[l].v); }
     if ((rc = dev_alloc(c, &c->kv_ptrs, ptrs.size()))) return rc;
     HIP_TRY(c, hipMemcpy(c->kv_ptrs, ptrs.data(), ptrs.size() * sizeof(void*), hipMemcpyHostToDevice));
-    { KT* st; if ((rc = dev_alloc(c, &st, (size_t)g.n_layers * 2 * D * kd))) return rc; c->kv_staging = st; }
+    { KT* st; if ((rc = dev_alloc(c, &st, (size_t)g.n_layers * 2 * D * kd * KVWidth<KT>::W))) return rc; c->kv_staging = st; }
     HIP_TRY(c, hipHostMalloc((void**)&c->h_tree_result, (D + 3) * sizeof(int32_t), hipHostMallocDefault));     // result [D + 2] | bad-logits flag
     // pool and row arrays start at zero: a level whose logits have no finite maximum writes no entries, and what a later
     // kernel then reads as a token id must still be a valid one
@@ -1250,7 +1250,7 @@ int do_tree_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
     // target cache: the followed rows move to the slots right after the root's
     for (int scatter = 0; scatter < 2; ++scatter)
         hipLaunchKernelGGL((tree_kv_gather_kernel<KT>), dim3(depth, 2 * g.n_layers), dim3(256), 0, c->stream, (KT* const*)c->kv_ptrs, c->tkv[0].maxL,
-                           g.n_kv_heads, g.head_dim, (const int*)c->tlen, (const int32_t*)t.result, (const int32_t*)t.path, depth, (KT*)c->kv_staging, scatter);
+                           g.n_kv_heads, g.head_dim * KVWidth<KT>::W, (const int*)c->tlen, (const int32_t*)t.result, (const int32_t*)t.path, depth, (KT*)c->kv_staging, scatter);
     // drafter: every tree row is dropped (its length never advanced); depth+1 rows rebuilt from the true features
     hipLaunchKernelGGL((tree_roll_cat_kernel<WT>), dim3(depth + 1), dim3(256), 0, c->stream, (const float*)c->catT, 2 * d, (const int32_t*)t.path,
                        (const int32_t*)t.next_tok, (const WT*)c->embed, c->troll, d);
@@ -1296,18 +1296,19 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     (void)hipFree(staging);
     if (rc) return rc;
 
-    // KV caches
+    // KV caches (KW storage elements per cached value: hi and lo halves for bf16 models)
+    constexpr int KW = KVWidth<typename KVType<WT>::type>::W;
     const int maxLt = g.max_vis + g.max_text, maxLd = g.max_text;
     c->tkv.resize(g.n_layers);
     for (int l = 0; l < g.n_layers; ++l) {
         typename KVType<WT>::type *k, *v;
-        if ((rc = dev_alloc(c, &k, (size_t)B * kd * maxLt))) return rc;
-        if ((rc = dev_alloc(c, &v, (size_t)B * kd * maxLt))) return rc;
+        if ((rc = dev_alloc(c, &k, (size_t)B * kd * maxLt * KW))) return rc;
+        if ((rc = dev_alloc(c, &v, (size_t)B * kd * maxLt * KW))) return rc;
         c->tkv[l].k = k; c->tkv[l].v = v; c->tkv[l].maxL = maxLt;
     }
     { typename KVType<WT>::type *k, *v;
-      if ((rc = dev_alloc(c, &k, (size_t)B * kd * maxLd))) return rc;
-      if ((rc = dev_alloc(c, &v, (size_t)B * kd * maxLd))) return rc;
+      if ((rc = dev_alloc(c, &k, (size_t)B * kd * maxLd * KW))) return rc;
+      if ((rc = dev_alloc(c, &v, (size_t)B * kd * maxLd * KW))) return rc;
       c->dkv.k = k; c->dkv.v = v; c->dkv.maxL = maxLd; }
     { WT* vis; if ((rc = dev_alloc(c, &vis, (size_t)B * std::max(1, g.max_vis) * d))) return rc; c->vis = vis; }
 

@@ -452,11 +452,11 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
                             st_wt_pair(&ph.Y[(size_t)row * ph.ldy + col], y1, y2);
                         } else {
                             const int c2 = col - qd;
-                            st_wt_pair((KT*)ph.kc + (((size_t)seq * pp.Hkv + c2 / hd) * ph.maxL + pos) * hd + c2 % hd, y1, y2);
+                            st_wt_kv_pair((KT*)ph.kc + (((size_t)seq * pp.Hkv + c2 / hd) * ph.maxL + pos) * hd * KVWidth<KT>::W, hd, c2 % hd, y1, y2);
                         }
                     } else {
                         const int c2 = col - qd - kd;
-                        st_wt_pair((KT*)ph.vc + (((size_t)seq * pp.Hkv + c2 / hd) * ph.maxL + pos) * hd + c2 % hd, x1, x2);
+                        st_wt_kv_pair((KT*)ph.vc + (((size_t)seq * pp.Hkv + c2 / hd) * ph.maxL + pos) * hd * KVWidth<KT>::W, hd, c2 % hd, x1, x2);
                     }
                 }
             } break;
@@ -603,22 +603,29 @@ __device__ __forceinline__ void attn_wg_finish(const float* __restrict__ mrg, in
 
 // ---- attention on the matrix cores (half-precision caches) ---------------------------------------------
 // Same work split as attn_wg_partial, but both contractions run as MFMA with the (head,row) pairs as the 16-wide
-// N dimension, so the queries live in 4 registers per 32 dims instead of LDS and a 16-key tile costs a dozen MFMA
-// instead of ~500 scalar FMAs:
-//   S^T[key][row]  = K[key][:] . Q^T          4 (HD=128) x mfma 16x16x32 f16; A = 16 cached key rows read straight
-//                                             from HBM (lane: key lane%16, 8 dims at 32 ks + 8 (lane/16)), B = q*scale in half
-//   O^T[dim][row] += V^T[dim][key] . P^T      HD/16 x mfma 16x16x16 f16; B = the probabilities exactly where the
-//                                             first product left them (lane: row lane%16, keys 4 (lane/16) + r);
-//                                             A = V^T, which needs 4 keys of one dim per lane: the V tile goes through
-//                                             LDS row-major and comes back through the transposing LDS read
+// N dimension, so the queries live in registers instead of LDS and a 16-key tile costs a few dozen MFMA instead of
+// ~500 scalar FMAs:
+//   S^T[key][row]  = K[key][:] . Q^T          mfma 16x16x32 f16; A = 16 cached key rows (lane: key lane%16, 8 dims at
+//                                             32 ks + 8 (lane/16)), B = q*scale
+//   O^T[dim][row] += V^T[dim][key] . P^T      mfma 16x16x16 f16; B = the probabilities exactly where the first product
+//                                             left them (lane: row lane%16, keys 4 (lane/16) + r); A = V^T, which needs
+//                                             4 keys of one dim per lane: the V tile goes through LDS row-major and
+//                                             comes back through the transposing LDS read
+// Every operand is a pair of halves, hi + lo (the cache stores K and V that way, see KVType; q*scale and the
+// probabilities are split in registers), and each product is three MFMA: hi.hi + lo.hi + hi.lo (lo.lo is below
+// fp32 resolution).  That keeps ~22 bits in all four operands at 3x the (small) MFMA work.
 // The running maximum / sum / rescale are per lane (row = lane%16 everywhere), only the maximum crosses lanes.
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
+// LDS (floats): per-wavefront K and V tiles of 16 keys (a row = hi | lo halves = 4 hd bytes, plus padding); the
+// per-wavefront partials [nw][rm][hd + 2] reuse the tile space after the key loop; 16 words for the election flag.
 __host__ __device__ constexpr size_t fused_attn_mfma_lds_floats(int hd, int nw, int rm) {
-    return (size_t)nw * 16 * (hd * 2 + 32) / 4 + (size_t)nw * 16 * (hd * 2 + 16) / 4 + (size_t)nw * rm * (hd + 2) + 16;
+    const size_t tiles = ((size_t)nw * 16 * (hd * 4 + 32) + (size_t)nw * 16 * (hd * 4 + 16)) / 4;
+    const size_t mrg = (size_t)nw * rm * (hd + 2);
+    return (tiles > mrg ? tiles : mrg) + 16;
 }
 
 template <int HD, int RM>
@@ -629,12 +636,14 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     HIVIS_AMARK(0)
     static_assert(RM <= 16 && HD % 32 == 0, "rows are the 16-wide MFMA dimension");
     constexpr int NW = FUSED_NW;
-    constexpr int ROWB = HD * 2;                   // bytes of one cached row
+    constexpr int HALFB = HD * 2;                  // bytes of the hi (or lo) halves of one cached row
+    constexpr int ROWB = HD * 4;                   // bytes of one cached row: hi halves, then lo halves
     constexpr int KS = HD / 32;                    // k-steps of the score product
     constexpr int NB = HD / 16;                    // 16-dim blocks of the value product
-    constexpr int NCH = ROWB / 16;                 // 16-byte chunks per V row
-    constexpr int KPI = 64 / NCH;                  // V rows per load instruction
-    constexpr int VT = 16 / KPI;                   // V load instructions per 16 keys
+    constexpr int NCH = ROWB / 16;                 // 16-byte chunks per cached row
+    constexpr int KPI = 64 / NCH;                  // cached rows per load instruction
+    constexpr int VT = 16 / KPI;                   // load instructions per 16 keys
+    static_assert(NCH <= 64 && KPI >= 1, "row too long for this mapping");
     // row stride of the V tile in LDS: 32 bytes more than the row, so the 4 rows a 16-lane group transposes
     // start 8 banks apart and the 64-bit transposing reads of a half wavefront touch every bank twice (the minimum)
     constexpr int VSTRIDE = ROWB + 32;
@@ -642,8 +651,8 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     constexpr int KSTRIDE = ROWB + 16;
     char* vt_all = reinterpret_cast<char*>(lds);                    // [NW][16 keys][VSTRIDE]
     char* kt_all = vt_all + NW * 16 * VSTRIDE;                      // [NW][16 keys][KSTRIDE]
-    float* mrg = lds + NW * 16 * (VSTRIDE + KSTRIDE) / 4;           // [NW][RM][HD + 2] per-wavefront partials
-    int* flag = reinterpret_cast<int*>(mrg + NW * RM * (HD + 2));
+    float* mrg = lds;                                               // [NW][RM][HD + 2] per-wavefront partials: same space, after the loop
+    int* flag = reinterpret_cast<int*>(lds + fused_attn_mfma_lds_floats(HD, NW, RM) - 16);
 
     int item = item_id;
     const int rblk = item % sh.n_rblk; item /= sh.n_rblk;
@@ -663,14 +672,14 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     const int n16 = lane & 15, g = lane >> 4;
     const int vks = lane / NCH, vdc = lane % NCH;
 
-    const char* kbase = reinterpret_cast<const char*>(kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD);
-    const char* vbase = reinterpret_cast<const char*>(vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD);
+    const char* kbase = reinterpret_cast<const char*>(kc) + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * ROWB;
+    const char* vbase = reinterpret_cast<const char*>(vc) + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * ROWB;
     char* vt = vt_all + wave * 16 * VSTRIDE;
     char* kt = kt_all + wave * 16 * KSTRIDE;
 
     // all loads of this wavefront's 16 keys starting at kb_ (rows clamped into the range; masked later).  K and V rows
-    // are both read as whole rows, 4 (HD=128) rows = 1 KiB contiguous per instruction: reading K directly in fragment
-    // order (16 rows x 64 bytes per instruction) costs the address coalescer 4x the cycles and bounded the loop.
+    // are both read as whole rows (1 KiB contiguous per instruction): reading K directly in fragment order (16 rows x
+    // 64 bytes per instruction) costs the address coalescer 4x the cycles and bounded the loop.
     // One tile ahead is enough (two in flight measured slower).
     u32x4_t knext[VT], vnext[VT];
 #define HIVIS_ATTN_LOADS(kb_)                                                                                      \
@@ -684,8 +693,8 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     if (k0 + 16 * wave < k1) HIVIS_ATTN_LOADS(k0 + 16 * wave)
     HIVIS_AMARK(1)
 
-    // B operand of the score product: q[row lane%16][32 ks + 8 (lane/16) .. +8] * scale in half; rows >= R are zero
-    f16x8_t qb[KS];
+    // B operand of the score product: q[row lane%16][32 ks + 8 (lane/16) .. +8] * scale as hi + lo halves; rows >= R are zero
+    f16x8_t qh[KS], ql[KS];
     {
         const int rq = min(n16, R - 1);
         const int hh = kvh * group + h0 + rq / ni, i = i0 + rq % ni;
@@ -695,10 +704,12 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
         for (int ks = 0; ks < KS; ++ks) {
             const float4 a = *reinterpret_cast<const float4*>(qrow + ks * 32);
             const float4 b = *reinterpret_cast<const float4*>(qrow + ks * 32 + 4);
-            qb[ks][0] = (_Float16)(a.x * scale); qb[ks][1] = (_Float16)(a.y * scale);
-            qb[ks][2] = (_Float16)(a.z * scale); qb[ks][3] = (_Float16)(a.w * scale);
-            qb[ks][4] = (_Float16)(b.x * scale); qb[ks][5] = (_Float16)(b.y * scale);
-            qb[ks][6] = (_Float16)(b.z * scale); qb[ks][7] = (_Float16)(b.w * scale);
+            const float x[8] = {a.x * scale, a.y * scale, a.z * scale, a.w * scale, b.x * scale, b.y * scale, b.z * scale, b.w * scale};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const _Float16 hi = (_Float16)fminf(fmaxf(x[e], -65504.f), 65504.f);
+                qh[ks][e] = hi; ql[ks][e] = (_Float16)(x[e] - (float)hi);
+            }
         }
     }
     const int qpos = (n16 < R) ? pos0 + i0 + n16 % ni : 0x7FFFFFFF;     // causal limit of this lane's row
@@ -715,7 +726,8 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     for (int kb = k0 + 16 * wave; kb < k1; kb += 16 * NW) {
         u32x4_t vraw[VT];
         // ---- both tiles -> LDS (row-major); the K fragments come back as plain 128-bit reads (key lane%16,
-        //      dims 32 ks + 8 (lane/16) .. +8), the V^T fragments through the transposing read further down
+        //      dims 32 ks + 8 (lane/16) .. +8, hi halves and HALFB further the lo halves), the V^T fragments through
+        //      the transposing read further down
 #pragma unroll
         for (int t = 0; t < VT; ++t) {
             *reinterpret_cast<u32x4_t*>(kt + (t * KPI + vks) * KSTRIDE + vdc * 16) = knext[t];
@@ -729,8 +741,11 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
         f32x4_t st = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const f16x8_t kf = *reinterpret_cast<const f16x8_t*>(kt + n16 * KSTRIDE + ks * 64 + g * 16);
-            st = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qb[ks], st, 0, 0, 0);
+            const f16x8_t kh = *reinterpret_cast<const f16x8_t*>(kt + n16 * KSTRIDE + ks * 64 + g * 16);
+            const f16x8_t kl = *reinterpret_cast<const f16x8_t*>(kt + n16 * KSTRIDE + HALFB + ks * 64 + g * 16);
+            st = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[ks], st, 0, 0, 0);
+            st = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, ql[ks], st, 0, 0, 0);
+            st = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[ks], st, 0, 0, 0);
         }
         float sv[4], tmax = -INFINITY;
 #pragma unroll
@@ -754,9 +769,9 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[nb][r] *= alpha;
         }
-        f16x4_t pb;
+        f16x4_t pbh, pbl;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) pb[r] = (_Float16)p[r];
+        for (int r = 0; r < 4; ++r) { pbh[r] = (_Float16)p[r]; pbl[r] = (_Float16)(p[r] - (float)pbh[r]); }
         // ---- V tile -> LDS (row-major), back as V^T fragments, O^T += V^T . P^T
 #pragma unroll
         for (int t = 0; t < VT; ++t) *reinterpret_cast<u32x4_t*>(vt + (t * KPI + vks) * VSTRIDE + vdc * 16) = vraw[t];
@@ -768,8 +783,11 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
             // transposing read: within a 16-lane group, lane i element e comes from the address of lane 4e + i/4,
             // its element i%4; so lane s points at key 4 (lane/16) + s/4, dims 16 nb + 4 (s%4) .. +3
             const char* src = vt + (4 * g + (n16 >> 2)) * VSTRIDE + (nb * 16 + 4 * (n16 & 3)) * 2;
-            const s16x4_t raw = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(src));
-            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, raw), pb, acc[nb], 0, 0, 0);
+            const s16x4_t rh = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(src));
+            const s16x4_t rl = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(src + HALFB));
+            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, rl), pbh, acc[nb], 0, 0, 0);
+            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, rh), pbl, acc[nb], 0, 0, 0);
+            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, rh), pbh, acc[nb], 0, 0, 0);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -777,7 +795,9 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     }
 #undef HIVIS_ATTN_LOADS
     HIVIS_AMARK(3)
-    // ---- per-wavefront partial -> LDS: this lane holds dims 16 nb + 4 (lane/16) + r of row lane%16
+    // ---- per-wavefront partial -> LDS: this lane holds dims 16 nb + 4 (lane/16) + r of row lane%16.  The partials
+    //      reuse the tile space, so every wavefront must have left its key loop first.
+    lds_barrier();
     float lsum = lrun;
     lsum += __shfl_xor(lsum, 16, 64);
     lsum += __shfl_xor(lsum, 32, 64);

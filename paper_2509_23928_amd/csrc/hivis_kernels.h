@@ -62,12 +62,41 @@ __device__ __forceinline__ void st_wt_pair(_Float16* dst, float a, float b) {
     st_wt(reinterpret_cast<uint32_t*>(dst), __builtin_bit_cast(uint32_t, v));
 }
 
-// KV-cache storage type that goes with a weight type.  bf16 models keep K and V in IEEE half:
-// same bytes as bf16, but 10 mantissa bits, which keeps the rounding of V (the dominant
-// low-precision error of the whole pass) an order of magnitude below the parity tolerance.
+// two adjacent values (c, c+1; c even) of a cache row of HD values, hi and lo halves for half-precision caches
+__device__ __forceinline__ void st_wt_kv_pair(float* row, int HD, int c, float a, float b) { st_wt_pair(row + c, a, b); }
+__device__ __forceinline__ void st_wt_kv_pair(_Float16* row, int HD, int c, float a, float b) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 hi, lo;
+    hi[0] = (_Float16)fminf(fmaxf(a, -65504.f), 65504.f);
+    hi[1] = (_Float16)fminf(fmaxf(b, -65504.f), 65504.f);
+    lo[0] = (_Float16)(a - (float)hi[0]);
+    lo[1] = (_Float16)(b - (float)hi[1]);
+    st_wt(reinterpret_cast<uint32_t*>(row + c), __builtin_bit_cast(uint32_t, hi));
+    st_wt(reinterpret_cast<uint32_t*>(row + HD + c), __builtin_bit_cast(uint32_t, lo));
+}
+
+// KV-cache storage that goes with a weight type.  fp32 models keep K and V in fp32.  bf16 models keep every cached
+// value as TWO IEEE halves, hi = half(x) and lo = half(x - hi) (about 22 mantissa bits), in one row of 2*HD halves:
+// [hi 0..HD) | lo 0..HD)].  Both halves are MFMA operands as they are.  One half alone is not enough at depth: the
+// rounding of K and V (2^-11 relative) is amplified layer after layer (text rows carry a tiny residual stream next
+// to what attention adds to it) and again by the drafter; at 32 layers it put the drafter's logits at 1.7x the
+// parity tolerance, with q and the probabilities rounded to half contributing as much again.
 template <typename WT> struct KVType;
 template <> struct KVType<bf16_t> { typedef f16_t type; };
 template <> struct KVType<float> { typedef float type; };
+// elements of storage per cached value (row width = HD * KVW)
+template <typename KT> struct KVWidth { static constexpr int W = 1; };
+template <> struct KVWidth<f16_t> { static constexpr int W = 2; };
+
+// value c of the cache row starting at `row` (HD values per row)
+__device__ __forceinline__ void kv_put(float* row, int HD, int c, float x) { row[c] = x; }
+__device__ __forceinline__ void kv_put(f16_t* row, int HD, int c, float x) {
+    const f16_t hi = (f16_t)fminf(fmaxf(x, -65504.f), 65504.f);
+    row[c] = hi;
+    row[HD + c] = (f16_t)(x - (float)hi);
+}
+__device__ __forceinline__ float kv_get(const float* row, int HD, int c) { return row[c]; }
+__device__ __forceinline__ float kv_get(const f16_t* row, int HD, int c) { return (float)row[c] + (float)row[HD + c]; }
 
 // 16 raw bytes of cache -> floats
 __device__ __forceinline__ void decode_chunk(const uint4& raw, float (&kf)[8], f16_t) {
@@ -642,7 +671,7 @@ __global__ void silu_mul_kernel(const float* __restrict__ gu, float* __restrict_
 
 // RoPE (rotate-half pairing, pairs stored in adjacent columns) on q and k of the fused qkv rows, then append k, v.
 // Row r belongs to sequence seq0 + r / m and sits at position base[seq] + offset + r % m, which is
-// both its rotary position and its slot in the cache.  Cache layout: [seq][Hkv][maxL][HD].
+// both its rotary position and its slot in the cache.  Cache layout: [seq][Hkv][maxL][HD * KVWidth] (see KVType).
 // The angle is evaluated in double so that large positions keep full fp32 accuracy.
 // pos_delta (optional, rows of a draft tree): the rotary position of row r is base[seq] + pos_delta[r] instead, its
 // cache slot stays base[seq] + offset + r % m.
@@ -669,14 +698,14 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int
         if (head < Hq) {
             x[2 * i] = y1; x[2 * i + 1] = y2;
         } else {
-            ST* dst = kc + (((size_t)seq * Hkv + (head - Hq)) * maxL + slot) * HD;
-            from_f32(dst[2 * i], y1); from_f32(dst[2 * i + 1], y2);
+            ST* dst = kc + (((size_t)seq * Hkv + (head - Hq)) * maxL + slot) * HD * KVWidth<ST>::W;
+            kv_put(dst, HD, 2 * i, y1); kv_put(dst, HD, 2 * i + 1, y2);
         }
     }
     const float* v = r + (size_t)(Hq + Hkv) * HD;
     for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < Hkv * HD; idx += gridDim.y * blockDim.x) {
         const int head = idx / HD, c = idx % HD;
-        from_f32(vc[(((size_t)seq * Hkv + head) * maxL + slot) * HD + c], v[idx]);
+        kv_put(vc + (((size_t)seq * Hkv + head) * maxL + slot) * HD * KVWidth<ST>::W, HD, c, v[idx]);
     }
 }
 
@@ -723,6 +752,7 @@ __device__ __forceinline__ void attn_item_partial(const float* __restrict__ q, c
                                                   float* __restrict__ ws) {
     constexpr int CH = 16 / sizeof(ST);          // elements per 16-byte chunk
     constexpr int DPL = HD / 64;                 // value dims per lane
+    constexpr int KW = KVWidth<ST>::W;           // storage elements per value (half-precision caches: hi row | lo row)
     const int nthreads = sh.nwaves * 64;
     float* qs = lds;                                         // [RM][HD]
     float* pw_all = lds + RM * HD;                     // [nwaves][RM][64]
@@ -752,8 +782,8 @@ __device__ __forceinline__ void attn_item_partial(const float* __restrict__ q, c
     }
     lds_barrier();
 
-    const ST* kbase = kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
-    const ST* vbase = vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD;
+    const ST* kbase = kc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD * KW;
+    const ST* vbase = vc + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * HD * KW;
 
     float mrun[RM], lrun[RM], acc[RM][DPL];
 #pragma unroll
@@ -770,12 +800,18 @@ __device__ __forceinline__ void attn_item_partial(const float* __restrict__ q, c
 #pragma unroll
         for (int r = 0; r < RM; ++r) s[r] = 0.f;
         if (valid) {
-            const uint4* kp = reinterpret_cast<const uint4*>(kbase + (size_t)j * HD);
+            const uint4* kp = reinterpret_cast<const uint4*>(kbase + (size_t)j * HD * KW);
 #pragma unroll 4
             for (int c = 0; c < HD / CH; ++c) {
                 const uint4 raw = kp[c];
                 float kf[CH];
                 decode_chunk(raw, kf, ST());
+                if constexpr (KW == 2) {             // the lo halves of the same values follow the hi row
+                    float kl[CH];
+                    decode_chunk(kp[HD / CH + c], kl, ST());
+#pragma unroll
+                    for (int e = 0; e < CH; ++e) kf[e] += kl[e];
+                }
 #pragma unroll
                 for (int r = 0; r < RM; ++r) {
                     if (r < R) {
@@ -814,9 +850,9 @@ __device__ __forceinline__ void attn_item_partial(const float* __restrict__ q, c
         const int nk = min(64, nkeys - ti * 64);
         for (int jj = 0; jj < nk; ++jj) {
             float vf[DPL];
-            const ST* vp = vbase + (size_t)(ti * 64 + jj) * HD + lane * DPL;
+            const ST* vrow = vbase + (size_t)(ti * 64 + jj) * HD * KW;
 #pragma unroll
-            for (int e = 0; e < DPL; ++e) vf[e] = to_f32(vp[e]);
+            for (int e = 0; e < DPL; ++e) vf[e] = kv_get(vrow, HD, lane * DPL + e);
 #pragma unroll
             for (int r = 0; r < RM; ++r) {
                 if (r < R) {

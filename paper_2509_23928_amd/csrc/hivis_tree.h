@@ -249,7 +249,8 @@ __global__ __launch_bounds__(64) void tree_accept_kernel(int N, int depth, int32
 // Cache compaction after acceptance, for all layers at once: the rows of the followed path move from their tree
 // slots base + path[j] to base + j (j = 1..n).  Two kernels (gather into a staging buffer, scatter back) because a
 // destination slot of one row can be the source slot of another.
-// kv: [n_layers][2] cache pointers; cache layout [Hkv][maxL][HD]; staging [n_layers][2][depth][Hkv*HD].
+// kv: [n_layers][2] cache pointers; cache layout [Hkv][maxL][HD]; staging [n_layers][2][depth][Hkv*HD], where HD here is
+// the STORAGE width of a cached row (head_dim * KVWidth: hi and lo halves of a half-precision cache move together).
 template <typename KT>
 __global__ void tree_kv_gather_kernel(KT* const* __restrict__ kv, int maxL, int Hkv, int HD, const int* __restrict__ tlen,
                                       const int32_t* __restrict__ result, const int32_t* __restrict__ path, int depth,
@@ -427,16 +428,16 @@ __global__ void wide_rope_append_kernel(Parts qkv, float* __restrict__ q_out, in
         if (head < Hq) {
             *reinterpret_cast<float4*>(q_out + (size_t)row * ldq + (size_t)head * HD + 2 * i) = make_float4(y[0], y[1], y[2], y[3]);
         } else {
-            ST* dst = kc + (((size_t)seq * Hkv + (head - Hq)) * maxL + slot) * HD + 2 * i;
+            ST* dst = kc + (((size_t)seq * Hkv + (head - Hq)) * maxL + slot) * HD * KVWidth<ST>::W;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) from_f32(dst[e], y[e]);
+            for (int e = 0; e < 4; ++e) kv_put(dst, HD, 2 * i + e, y[e]);
         }
     }
     for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < Hkv * HD / 4; idx += gridDim.y * blockDim.x) {
         const int head = (4 * idx) / HD, c = (4 * idx) % HD;
         const float4 v = parts_load4(qkv, rbase + (size_t)(Hq + Hkv) * HD + 4 * idx);
-        ST* dst = vc + (((size_t)seq * Hkv + head) * maxL + slot) * HD + c;
-        from_f32(dst[0], v.x); from_f32(dst[1], v.y); from_f32(dst[2], v.z); from_f32(dst[3], v.w);
+        ST* dst = vc + (((size_t)seq * Hkv + head) * maxL + slot) * HD * KVWidth<ST>::W;
+        kv_put(dst, HD, c, v.x); kv_put(dst, HD, c + 1, v.y); kv_put(dst, HD, c + 2, v.z); kv_put(dst, HD, c + 3, v.w);
     }
 }
 

@@ -31,7 +31,7 @@ def test_c1_end_to_end_own_drafts():
     sbs = SideBySide(cfg, w, hv, vis, ids)
     for c in range(cfg.gen_cycles):
         sbs.cycle(cfg.K)
-    print("C1 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print("C1:", sbs.summary())
     # lossless: the emitted stream is the plain greedy decode of the target
     ref, _ = greedy_reference(cfg, w, vis[0], ids[0], len(sbs.emitted[0]))
     if sbs.near_ties == 0:
@@ -75,7 +75,7 @@ def test_small_bf16_end_to_end(variant):
             break                                 # a near-tie moved the trajectory: planted prefixes no longer apply
         planted = ref[done: done + m] + [(ref[done + j] + 3) % cfg.vocab for j in range(m, cfg.K)]
         sbs.cycle(cfg.K, planted=np.array([planted], np.int32))
-    print(variant, "max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print(variant, ":", sbs.summary())
 
 
 def test_batch_per_sequence_acceptance():
@@ -95,7 +95,7 @@ def test_batch_per_sequence_acceptance():
         r = sbs.cycle(cfg.K, planted=np.array(planted, np.int32))
         if sbs.near_ties == 0:
             assert [x["n"] for x in r] == plan
-    print("batch max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print("batch:", sbs.summary())
 
 
 def test_error_codes():
@@ -159,7 +159,7 @@ def test_long_cache_uses_key_splits():
     # 1500 visual rows: the verify attention splits the key range over several workgroups and runs the merge launch
     cfg = small_bf16(n_vis=1500, n_text=40, d=256, n_q_heads=2, n_kv_heads=2, ffn=512, vocab=1024, K=5)
     sbs = run_generic(cfg, 21, 2, plant=(5, 2))
-    print("long cache max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print("long cache:", sbs.summary())
 
 
 def test_forced_small_key_splits_hd64_and_hd128():
@@ -168,9 +168,9 @@ def test_forced_small_key_splits_hd64_and_hd128():
     os.environ["HIVIS_KEYS_PER_SPLIT"] = "48"
     try:
         sbs = run_generic(small_bf16(), 27, 2, plant=(4,))
-        print("forced key splits hd128 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+        print("forced key splits hd128:", sbs.summary())
         sbs = run_generic(small_bf16(head_dim=64, n_q_heads=8, n_kv_heads=2), 28, 2, plant=(2,))
-        print("forced key splits hd64 gqa max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+        print("forced key splits hd64 gqa:", sbs.summary())
     finally:
         del os.environ["HIVIS_KEYS_PER_SPLIT"]
 
@@ -180,14 +180,14 @@ def test_gqa_group7_k6_qwen_like_shape():
     cfg = small_bf16(n_q_heads=28, n_kv_heads=4, head_dim=64, d=1792, ffn=2368, vocab=4096, K=6, n_vis=130, n_text=50,
                      rope_theta=1e6, rms_eps=1e-6, n_layers=2)
     sbs = run_generic(cfg, 22, 2, plant=(6, 3))
-    print("gqa 28/4 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print("gqa 28/4:", sbs.summary())
 
 
 def test_edge_shapes_no_visual_single_text_and_varying_k():
     # no visual rows at all, a one-token prompt, and a different K every cycle (1 .. k_max)
     cfg = small_bf16(n_vis=0, n_text=1, K=5, d=256, n_q_heads=2, n_kv_heads=2, ffn=512, vocab=1024)
     sbs = run_generic(cfg, 23, 5, k_list=[1, 5, 2, 3, 4])
-    print("edge shapes max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print("edge shapes:", sbs.summary())
     cfg = small_bf16(n_vis=1, n_text=2, K=2, d=256, n_q_heads=2, n_kv_heads=2, ffn=512, vocab=1024)
     run_generic(cfg, 24, 2)
 
@@ -199,7 +199,7 @@ def test_fp32_sixteen_rows_and_gqa():
     sbs = SideBySide(cfg, w, hv, vis, ids)
     for _ in range(3):
         sbs.cycle(cfg.K)
-    print("fp32 gqa batch-2 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print("fp32 gqa batch-2:", sbs.summary())
     assert max(sbs.max_err.values()) < 0.1
 
 
@@ -250,7 +250,7 @@ def test_random_shape_sweep(seed):
     sbs.cycle(max(1, K - 1))
     hv.close()
     print(f"sweep {seed}: d={d} Hq/Hkv={n_q}/{n_kv} hd={hd} F={ffn} V={vocab} K={K} B={batch} v={cfg.n_vis} l={cfg.n_text} N={cfg.n_layers}",
-          "max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+          ":", sbs.summary())
 
 
 def test_standalone_kernel_path_matches_oracle():
@@ -259,7 +259,7 @@ def test_standalone_kernel_path_matches_oracle():
     os.environ["HIVIS_FUSED"] = "0"
     try:
         sbs = run_generic(small_bf16(K=4), 29, 2, plant=(3,))
-        print("stand-alone kernels bf16 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+        print("stand-alone kernels bf16:", sbs.summary())
         run_generic(synth.get_config("C1"), 3, 2, plant=(2,))
     finally:
         del os.environ["HIVIS_FUSED"]
@@ -284,7 +284,7 @@ def test_qwen_vocab_lm_head_many_tile_groups():
     # candidate carried across groups; narrow d keeps the oracle quick
     cfg = small_bf16(vocab=152064, d=512, n_q_heads=4, n_kv_heads=2, ffn=1376, K=6, n_vis=60, n_text=24, rope_theta=1e6, rms_eps=1e-6)
     sbs = run_generic(cfg, 31, 2, plant=(4,))
-    print("V=152064 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print("V=152064:", sbs.summary())
 
 
 def test_qwen_width_ffn_two_layer_slice():
@@ -292,7 +292,7 @@ def test_qwen_width_ffn_two_layer_slice():
     # workgroup; down projection K = 18944 = 9 full passes + a ragged one), K = 6 -> 7 rows
     cfg = synth.get_config("C4").scaled(n_layers=2, vocab=4096, n_vis=130, n_text=50, gen_tokens=0, gen_cycles=2)
     sbs = run_generic(cfg, 32, 1, plant=(3,))
-    print("Qwen-width 2-layer max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print("Qwen-width 2-layer:", sbs.summary())
 
 
 def test_13b_width_batch4_k7_thirty_two_rows():
@@ -303,7 +303,7 @@ def test_13b_width_batch4_k7_thirty_two_rows():
     sbs.cycle(cfg.K)
     sbs.cycle(cfg.K)
     hv.close()
-    print("13B-width batch-4 max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print("13B-width batch-4:", sbs.summary())
 
 
 def test_full_width_7b_layers_two_layer_slice():
@@ -321,7 +321,7 @@ def test_full_width_7b_layers_two_layer_slice():
         if sbs.near_ties == 0:
             assert r[0]["n"] == 3
     hv.close()
-    print("7B-width 2-layer max error / tolerance:", sbs.max_err, "near ties:", sbs.near_ties)
+    print("7B-width 2-layer:", sbs.summary())
 
 
 def test_two_live_contexts_with_different_head_sizes():

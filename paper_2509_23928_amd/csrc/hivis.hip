@@ -93,7 +93,9 @@ struct hivis_ctx {
     float* rope_tab = nullptr; float* pm = nullptr; int* pi = nullptr; unsigned* bar = nullptr;
     float* fattn_ws = nullptr; size_t fattn_ws_floats = 0;
     struct Program { hivis::Phase* dev = nullptr; int n = 0; std::vector<hivis::Phase>* host = nullptr; };
-    int keys_per_split = 768;            // attention: cached keys per workgroup before the key range is split further
+    int keys_per_split = 128;            // attention: cached keys per workgroup (one 16-key tile per wavefront) before the key range is split further
+    bool attn_elect = true;              // key splits merged by the workgroup that arrives last (false: by a merge launch)
+    int attn_flags = 3;                  // AttnShape::flags of the phase programs
     bool persistent = false;             // HIVIS_PERSISTENT=1: one cooperative launch per pass instead of one launch per phase
     std::map<int, Program> programs;     // key = kind * 64 + K
     unsigned long long* prof = nullptr; int prof_left = 0;   // developer aid: HIVIS_PROF=n dumps per-phase times of n verify passes
@@ -449,7 +451,7 @@ AttnShape fused_attn_shape(hivis_ctx* c, int nseq, int m, int offset, int maxL, 
     sh.n_hblk = (group + sh.gh - 1) / sh.gh; sh.n_rblk = (m + sh.mi - 1) / sh.mi;
     sh.seq0 = 0; sh.offset = offset; sh.maxL = maxL; sh.ldq = ldq; sh.nwaves = FUSED_NW;
     const int items = nseq * g.n_kv_heads * sh.n_hblk * sh.n_rblk;
-    sh.nsplit = std::max(1, c->fused_grid / items);
+    sh.nsplit = std::min(ATTN_MAX_SPLITS, std::max(1, c->fused_grid / items));
     *items_out = items;
     return sh;
 }
@@ -470,7 +472,7 @@ struct Pool {
 // of the layer output (row stride ldd).
 template <typename WT>
 float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const LayerDev& L, const KVDev& kv, float* h, const int* base,
-                    int offset, int nseq, int m, float* rope, float* dst, int ldd, int* ld_out, bool persistent) {
+                    int offset, int nseq, int m, float* rope, float* dst, int ldd, int* ld_out, bool persistent, bool elect) {
     const hivis_config& g = c->cfg;
     const int M = nseq * m;
     const int d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn, nqkv = qd + 2 * kd;
@@ -486,12 +488,12 @@ float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const Layer
     Phase a{}; a.type = PH_ATTN; a.A = qkv; a.lda = nqkv; a.kc = kv.k; a.vc = kv.v; a.maxL = kv.maxL; a.base = base; a.offset = offset;
     a.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, nqkv, &a.att_items);
     a.ws = pool.take((size_t)a.att_items * a.att.nsplit * FUSED_RMAX * (g.head_dim + 2));
-    if (persistent) {
+    if (persistent || elect) {
         a.cnt = (int*)pool.take((size_t)a.att_items);  // zero from the pool's memset; the merging workgroup re-zeroes it
         a.Y = att; a.ldy = qd;
         P.push_back(a);
     } else {
-        // one launch per phase: a separate merge launch is cheaper than the in-kernel election's cache maintenance
+        // key splits merged by a launch of their own
         a.cnt = nullptr; a.Y = att; a.ldy = qd;
         P.push_back(a);
         Phase mg = a; mg.type = PH_ATTN_MERGE; mg.Y = att; mg.ldy = qd;
@@ -511,7 +513,7 @@ float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const Layer
 }
 
 template <typename WT>
-void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>& P, bool persistent) {
+void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>& P, bool persistent, bool elect) {
     const hivis_config& g = c->cfg;
     const int B = g.batch, d = g.d, V = g.vocab, G = c->fused_grid;
     int ld = d;
@@ -522,7 +524,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
         Phase pr{}; pr.type = PH_PREP; pr.ids = c->row_tok; pr.id_sseq = m; pr.id_srow = 1; pr.gain = c->embed; pr.Y = x; pr.ldy = d;
         pr.base = c->tlen; pr.offset = 0; pr.rope = rope;
         P.push_back(pr);
-        for (int l = 0; l < g.n_layers; ++l) x = layer_phases<WT>(c, P, pool, c->layers[l], c->tkv[l], x, c->tlen, 0, B, m, rope, nullptr, 0, &ld, persistent);
+        for (int l = 0; l < g.n_layers; ++l) x = layer_phases<WT>(c, P, pool, c->layers[l], c->tkv[l], x, c->tlen, 0, B, m, rope, nullptr, 0, &ld, persistent, elect);
         Phase nr{}; nr.type = PH_NORM_ROWS; nr.A = x; nr.lda = d; nr.gain = c->final_norm; nr.Y = c->catT; nr.ldy = 2 * d;
         P.push_back(nr);
         Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = c->catT; lm.lda = 2 * d;
@@ -552,7 +554,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
                 Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = cat; fu.lda = 2 * d;
                 fu.Y = u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = std::min(i, g.n_resid - 1);
                 P.push_back(fu);
-                layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, i - 1, B, 1, rope, cat_next, 2 * d, &ld, persistent);
+                layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, i - 1, B, 1, rope, cat_next, 2 * d, &ld, persistent, elect);
                 cat = cat_next;
             }
         }
@@ -566,7 +568,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
         Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = c->catT; fu.lda = 2 * d;
         fu.Y = u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = 0;
         P.push_back(fu);
-        layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, 0, B, m, rope, c->dout, d, &ld, persistent);
+        layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, 0, B, m, rope, c->dout, d, &ld, persistent, elect);
     }
     // chain the GEMM phases for the cross-barrier weight prefetch
     for (size_t i = 0; i < P.size(); ++i) {
@@ -583,12 +585,12 @@ int get_program(hivis_ctx* c, int kind, int K, hivis_ctx::Program* out) {
     if (it != c->programs.end()) { *out = it->second; return HIVIS_OK; }
     std::vector<Phase> P;
     Pool count;
-    build_phases<WT>(c, kind, K, count, P, c->persistent);           // sizes only
+    build_phases<WT>(c, kind, K, count, P, c->persistent, c->attn_elect);           // sizes only
     Pool pool;
     if (int rc = dev_alloc(c, &pool.base, count.used)) return rc;
     HIP_TRY(c, hipMemset(pool.base, 0, count.used * sizeof(float)));
     P.clear();
-    build_phases<WT>(c, kind, K, pool, P, c->persistent);
+    build_phases<WT>(c, kind, K, pool, P, c->persistent, c->attn_elect);
     hivis_ctx::Program pg;
     pg.n = (int)P.size();
     if (int rc = dev_alloc(c, &pg.dev, P.size())) return rc;
@@ -614,10 +616,15 @@ int launch_phases(hivis_ctx* c, const Phase* phases, int n, int kind, int K, con
                                                    // first units into L2 during the epilogue was measured: 3% slower)
         if (ph.type == PH_ATTN || ph.type == PH_ATTN_MERGE) {
             ph.att.nsplit = std::max(1, std::min(ph.att.nsplit, (max_keys + c->keys_per_split - 1) / c->keys_per_split));
+            ph.att.flags = c->attn_flags;
+            if (g.batch <= 8 && ph.att.seq0 == 0) {          // the lengths the device arrays hold right now, by value
+                ph.att.nbase = g.batch;
+                for (int b = 0; b < g.batch; ++b) ph.att.base_val[b] = kind == PROG_VERIFY ? c->h_tlen[b] : c->h_dlen[b];
+            }
             if (ph.type == PH_ATTN_MERGE && ph.att.nsplit == 1) continue;
         }
         int grid = c->fused_grid;
-        if (ph.type == PH_ATTN) grid = std::min(grid, ph.att_items * ph.att.nsplit);
+        if (ph.type == PH_ATTN) grid = std::min(grid, ((ph.att.flags & 2) ? 8 * ((ph.att_items + 7) / 8) : ph.att_items) * ph.att.nsplit);
         else if (ph.type == PH_ATTN_MERGE) grid = std::min(grid, ph.att_items);
         else if (ph.type == PH_PREP) grid = std::min(grid, std::max(pp.M, (pp.M * g.head_dim / 2 + FUSED_NT - 1) / FUSED_NT));
         else if (ph.type == PH_NORM_ROWS) grid = std::min(grid, pp.M);
@@ -762,13 +769,13 @@ int draft_noalloc(hivis_ctx* c, int K) {
     if (draft_phase_capacity(K) > P.capacity()) return fail(c, HIVIS_ECAP, "phase list of K=%d exceeds the storage reserved at create", K);
     P.clear();
     Pool count;
-    build_phases<WT>(c, PROG_DRAFT, K, count, P, false);            // sizes only
+    build_phases<WT>(c, PROG_DRAFT, K, count, P, false, false);            // sizes only
     const size_t need = count.used * sizeof(float);
     if (need > (size_t)HIVIS_SCRATCH_BYTES)
         return fail(c, HIVIS_ECAP, "draft round of K=%d needs %zu bytes of scratch, the static array holds %u", K, need, (unsigned)HIVIS_SCRATCH_BYTES);
     P.clear();
     Pool pool; pool.base = (float*)c->scratch_dev;                  // the looked-up device address, not the array's name
-    build_phases<WT>(c, PROG_DRAFT, K, pool, P, false);
+    build_phases<WT>(c, PROG_DRAFT, K, pool, P, false, false);
     PassParams pp{};
     pp.phases = nullptr; pp.nphases = (int)P.size();
     pp.M = g.batch; pp.nseq = g.batch; pp.m = 1;
@@ -806,6 +813,8 @@ int fused_setup(hivis_ctx* c) {
     { const char* we = getenv("HIVIS_WIDE_GEMM"); c->no_wide_gemm = we && we[0] == '0'; }
     { const char* we = getenv("HIVIS_WIDE_MIN"); if (we && atoi(we) >= 1) c->wide_min = atoi(we); }
     { const char* ke = getenv("HIVIS_KEYS_PER_SPLIT"); if (ke && atoi(ke) >= 16) c->keys_per_split = atoi(ke); }
+    { const char* ee = getenv("HIVIS_ATTN_ELECT"); if (ee) c->attn_elect = ee[0] == '1'; }
+    { const char* fe = getenv("HIVIS_ATTN_FLAGS"); if (fe) c->attn_flags = atoi(fe); }
     int nb = 0;
     HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)fused_pass_kernel<WT>, FUSED_NT, c->fused_lds));
     if (nb < 1) return fail(c, HIVIS_EHIP, "persistent kernel does not fit on a compute unit");

@@ -511,6 +511,65 @@ __host__ __device__ constexpr size_t fused_attn_lds_floats(int hd, int nw, int r
 }
 
 #define HIVIS_AMARK(k) if (marks && blockIdx.x == 0 && threadIdx.x == 0) marks[k] = wall_clock64();
+
+// Merge of the key-split partials of one item (pbase: [nsplit][RM][HD + 2], each row = weighted value sums, running
+// maximum, sum of weights) in split order, by the whole workgroup; writes the attention rows.  Every load is
+// requested before anything waits (the partials come from memory, a round trip of more than a microsecond: a loop
+// that loads split after split spent 8-10 us here), which is why the split count is bounded at compile time.
+// wl: LDS scratch of 3 * ATTN_MAX_SPLITS * RM floats that nothing else uses until the routine returns.
+constexpr int ATTN_MAX_SPLITS = 16;
+template <int HD, int RM>
+__device__ __forceinline__ void attn_merge_splits(const float* __restrict__ pbase, int nsplit, int R, int ni, int head0, int i0, int sl,
+                                                  const AttnShape& sh, float* __restrict__ wl, float* __restrict__ att_out, int ldo) {
+    constexpr int MAXS = ATTN_MAX_SPLITS;
+    constexpr int PER = (RM * HD + FUSED_NT - 1) / FUSED_NT;       // output elements per thread
+    static_assert(MAXS * RM <= FUSED_NT, "one thread per (split, row) pair of statistics");
+    float* wm = wl; float* wsum = wl + MAXS * RM; float* ww = wl + 2 * MAXS * RM;
+    float v[PER][MAXS];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int idx = threadIdx.x + e * FUSED_NT;
+        const int r = min(idx / HD, R - 1), c = idx % HD;
+#pragma unroll
+        for (int sp = 0; sp < MAXS; ++sp) v[e][sp] = ld_agent(&pbase[((size_t)min(sp, nsplit - 1) * RM + r) * (HD + 2) + c]);
+    }
+    if ((int)threadIdx.x < MAXS * RM) {
+        const int sp = threadIdx.x / RM, r = threadIdx.x % RM;
+        const float* p = pbase + ((size_t)min(sp, nsplit - 1) * RM + min(r, R - 1)) * (HD + 2);
+        const float ms = ld_agent(&p[HD]), ls = ld_agent(&p[HD + 1]);
+        const bool live = sp < nsplit && r < R;
+        wm[threadIdx.x] = live ? ms : -INFINITY; wsum[threadIdx.x] = live ? ls : 0.f;
+    }
+    lds_barrier();
+    if ((int)threadIdx.x < MAXS * RM) {
+        const int sp = threadIdx.x / RM, r = threadIdx.x % RM;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int s2 = 0; s2 < MAXS; ++s2) mx = fmaxf(mx, wm[s2 * RM + r]);
+        float den = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < MAXS; ++s2) {
+            const float m2 = wm[s2 * RM + r];
+            if (m2 != -INFINITY) den += wsum[s2 * RM + r] * __expf(m2 - mx);
+        }
+        const float ms = wm[threadIdx.x];
+        ww[threadIdx.x] = (ms == -INFINITY) ? 0.f : __expf(ms - mx) / den;
+    }
+    lds_barrier();
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int idx = threadIdx.x + e * FUSED_NT;
+        const int r = idx / HD, c = idx % HD;
+        if (r < R) {
+            float o = 0.f;
+#pragma unroll
+            for (int sp = 0; sp < MAXS; ++sp) o += ww[sp * RM + r] * v[e][sp];
+            const int hh = head0 + r / ni, i = i0 + r % ni;
+            st_wt(&att_out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], o);
+        }
+    }
+    lds_barrier();
+}
 // Tail shared by the attention variants: the NW per-wavefront partials in mrg ([NW][RM][HD + 2]: weighted value
 // sums, running maximum, sum of weights) are merged in wavefront order; with one key split the attention rows are
 // written directly, otherwise ONE partial of the workgroup goes to ws for the merge phase (or, when cnt is given,
@@ -566,36 +625,25 @@ __device__ __forceinline__ void attn_wg_finish(const float* __restrict__ mrg, in
     }
     HIVIS_AMARK(5)
     if (cnt == nullptr) { lds_barrier(); return; }        // the partials are merged by a separate phase
-    // ---- the workgroup whose partial completes the item merges all of them (no extra grid barrier):
-    // stores acknowledged -> arrive on the item's counter -> the last arriver reads the nsplit partials
+    // ---- the workgroup whose partial completes the item merges all of them (no merge launch, no grid barrier):
+    // partial stored -> stores complete -> arrive on the item's counter -> the last arriver reads the nsplit partials.
+    // Every access involved is an agent-scope atomic (write-through stores, the counter, the loads of the merge), and
+    // the stores have completed (vmcnt) before the arrival is issued: that orders them for every XCD without writing
+    // back or invalidating an L2.  (Measured with the fence pair as well: 1.8 us more per layer; parity was identical
+    // with the splits of an item on one XCD and spread over all of them.)
     wait_vmem();
     lds_barrier();
     if (threadIdx.x == 0) {
-        // the acknowledgement of a write-through store only says that this XCD's L2 has it; the agent-scope release
-        // makes it visible to the other XCDs before the arrival below
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        if (!(sh.flags & 1)) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         flag[0] = __hip_atomic_fetch_add(&cnt[item_id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     lds_barrier();
     const bool last = flag[0] == sh.nsplit - 1;
     if (last) {
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        if (!(sh.flags & 1)) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         const float* pbase = ws + (size_t)item_id * sh.nsplit * RM * (HD + 2);
-        for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
-            const int r = idx / HD, c = idx % HD;
-            float mx = -INFINITY;
-            for (int sp = 0; sp < sh.nsplit; ++sp) mx = fmaxf(mx, pbase[((size_t)sp * RM + r) * (HD + 2) + HD]);
-            float num = 0.f, den = 0.f;
-            for (int sp = 0; sp < sh.nsplit; ++sp) {
-                const float* pp_ = pbase + ((size_t)sp * RM + r) * (HD + 2);
-                const float ms = pp_[HD];
-                if (ms == -INFINITY) continue;
-                const float w = __expf(ms - mx);
-                num += pp_[c] * w; den += pp_[HD + 1] * w;
-            }
-            const int hh = head0 + r / ni, i = i0 + r % ni;
-            st_wt(&att_out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], num / den);
-        }
+        // (the wavefront partials in mrg are dead since the barrier before the arrival: their space is the scratch)
+        attn_merge_splits<HD, RM>(pbase, sh.nsplit, R, ni, head0, i0, sl, sh, const_cast<float*>(mrg), att_out, ldo);
         if (threadIdx.x == 0) st_wt(&cnt[item_id], 0);
     }
     lds_barrier();
@@ -664,7 +712,7 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
     const int h0 = hblk * sh.gh, nh = min(sh.gh, group - h0);
     const int i0 = rblk * sh.mi, ni = min(sh.mi, sh.m - i0);
     const int R = nh * ni;
-    const int pos0 = base[seq] + sh.offset;
+    const int pos0 = (sh.nbase > 0 ? sh.base_val[sl] : base[seq]) + sh.offset;
     const int nkeys = min(pos0 + i0 + ni, sh.maxL);
     const int cs = ((nkeys + sh.nsplit - 1) / sh.nsplit + 15) & ~15;        // keys per split, multiple of 16
     const int k0 = split * cs, k1 = min(nkeys, k0 + cs);
@@ -852,7 +900,7 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
     const int h0 = hblk * sh.gh, nh = min(sh.gh, group - h0);
     const int i0 = rblk * sh.mi, ni = min(sh.mi, sh.m - i0);
     const int R = nh * ni;
-    const int pos0 = base[seq] + sh.offset;
+    const int pos0 = (sh.nbase > 0 ? sh.base_val[sl] : base[seq]) + sh.offset;
     const int nkeys = min(pos0 + i0 + ni, sh.maxL);
     const int cs = ((nkeys + sh.nsplit - 1) / sh.nsplit + 15) & ~15;        // keys per split, multiple of 16
     const int k0 = split * cs, k1 = min(nkeys, k0 + cs);
@@ -987,7 +1035,7 @@ __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, con
 // Merge of the nsplit workgroup partials of one item, in split order; writes the attention output rows.
 template <int HD, int RM>
 __device__ __forceinline__ void attn_wg_merge(const float* __restrict__ ws, const AttnShape& sh, int item_id,
-                                              float* __restrict__ out, int ldo) {
+                                              float* __restrict__ lds, float* __restrict__ out, int ldo) {
     int item = item_id;
     const int rblk = item % sh.n_rblk; item /= sh.n_rblk;
     const int hblk = item % sh.n_hblk; item /= sh.n_hblk;
@@ -998,21 +1046,7 @@ __device__ __forceinline__ void attn_wg_merge(const float* __restrict__ ws, cons
     const int i0 = rblk * sh.mi, ni = min(sh.mi, sh.m - i0);
     const int R = nh * ni;
     const float* base = ws + (size_t)item_id * sh.nsplit * RM * (HD + 2);
-    for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
-        const int r = idx / HD, c = idx % HD;
-        float mx = -INFINITY;
-        for (int s = 0; s < sh.nsplit; ++s) mx = fmaxf(mx, base[((size_t)s * RM + r) * (HD + 2) + HD]);
-        float num = 0.f, den = 0.f;
-        for (int s = 0; s < sh.nsplit; ++s) {
-            const float* p = base + ((size_t)s * RM + r) * (HD + 2);
-            const float ms = p[HD];
-            if (ms == -INFINITY) continue;
-            const float w = __expf(ms - mx);
-            num += p[c] * w; den += p[HD + 1] * w;
-        }
-        const int hh = kvh * group + h0 + r / ni, i = i0 + r % ni;
-        st_wt(&out[(size_t)(sl * sh.m + i) * ldo + (size_t)hh * HD + c], num / den);
-    }
+    attn_merge_splits<HD, RM>(base, sh.nsplit, R, ni, kvh * group + h0, i0, sl, sh, lds, out, ldo);
 }
 
 // One phase, executed by the calling grid (every workgroup calls this with the same arguments).
@@ -1024,9 +1058,15 @@ __device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp,
     switch (type) {
     case PH_GEMM: gemm_phase<WT, EPI, SINGLE>(ph, pp, lds, head, head_valid, wb1, wb1_valid, p); break;
     case PH_ATTN: {
-        const int total = ph.att_items * ph.att.nsplit;
+        // (item, split) of a workgroup.  Default: split-minor.  flags & 2: every split of an item on ONE XCD (workgroup w
+        // runs on XCD w % 8): XCD x works on the items x, x + 8, ..., so an item's partials meet in one L2.
+        const int nsp = ph.att.nsplit;
+        const bool xcd_map = (ph.att.flags & 2) != 0;
+        const int total = xcd_map ? 8 * ((ph.att_items + 7) / 8) * nsp : ph.att_items * nsp;
         for (int w = blockIdx.x; w < total; w += gridDim.x) {
-            const int item = w / ph.att.nsplit, split = w % ph.att.nsplit;
+            int item, split;
+            if (xcd_map) { const int j = w >> 3; item = (w & 7) + 8 * (j / nsp); split = j % nsp; if (item >= ph.att_items) continue; }
+            else { item = w / nsp; split = w % nsp; }
             if constexpr (std::is_same<KT, f16_t>::value) {
                 if (pp.hd == 128) attn_wg_mfma<128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2);
                 else attn_wg_mfma<64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2);
@@ -1039,8 +1079,8 @@ __device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp,
     case PH_ATTN_MERGE:
         if (pp.prof2 && blockIdx.x == 0 && threadIdx.x == 0) pp.prof2[0] = wall_clock64();
         for (int item = blockIdx.x; item < ph.att_items; item += gridDim.x) {
-            if (pp.hd == 128) attn_wg_merge<128, FUSED_RMAX>(ph.ws, ph.att, item, ph.Y, ph.ldy);
-            else attn_wg_merge<64, FUSED_RMAX>(ph.ws, ph.att, item, ph.Y, ph.ldy);
+            if (pp.hd == 128) attn_wg_merge<128, FUSED_RMAX>(ph.ws, ph.att, item, lds, ph.Y, ph.ldy);
+            else attn_wg_merge<64, FUSED_RMAX>(ph.ws, ph.att, item, lds, ph.Y, ph.ldy);
         }
         break;
     case PH_PREP: {

@@ -52,6 +52,8 @@ __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70)
 __device__ __forceinline__ void st_wt(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void st_wt(int* p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void st_wt(uint32_t* p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+// Agent-scope load: reads what an agent-scope (write-through) store of another workgroup, on any XCD, has completed.
+__device__ __forceinline__ float ld_agent(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 // two adjacent cache elements (dst 4-byte aligned)
 __device__ __forceinline__ void st_wt_pair(float* dst, float a, float b) { st_wt(dst, a); st_wt(dst + 1, b); }
 __device__ __forceinline__ void st_wt_pair(_Float16* dst, float a, float b) {
@@ -727,6 +729,12 @@ struct AttnShape {
     int seq0, offset, maxL, nsplit;
     int ldq;                 // row stride of the q buffer
     int nwaves;              // wavefronts per workgroup working on one (item, split)
+    int flags;               // bit 0: the election of the merging workgroup relies on agent-scope stores, loads and the
+                             //        arrival counter alone (clear: an agent-scope release / acquire fence pair around it as well);
+                             // bit 1: every key split of an item on one XCD (the partials meet in one L2)
+    // cache lengths by value (nbase > 0): the host knows them at launch, and reading base[seq] from memory first costs the
+    // attention a dependent round trip before its first key can be requested.  base_val[s] replaces base[seq0 + s].
+    int nbase; int base_val[8];
     // rows of a draft tree (optional): row i sees every key before base[seq] plus the keys base[seq] + b whose bit b is
     // set in tmask[i] (its ancestors among the tree rows and itself), instead of the causal rule
     const unsigned long long* tmask;

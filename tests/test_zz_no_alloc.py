@@ -109,8 +109,9 @@ def test_draft_noalloc_rejects_what_it_cannot_hold():
     hv.draft_noalloc(cfg.K)                            # still usable afterwards
     hv.verify(); hv.accept()
     hv.close()
-    # a round whose buffers exceed the static array (31 draft steps x ~1 MB of attention partials each): refused, nothing runs
-    big = small_bf16(K=31, gen_cycles=2)
+    # a round whose buffers exceed the static array (31 draft steps x ~1 MB of attention key-split partials each, with 32
+    # kv heads): refused, nothing runs
+    big = small_bf16(K=31, gen_cycles=2, n_q_heads=32, n_kv_heads=32)
     w = synth.make_weights(big, seed=0)
     vis, ids = synth.make_prompt(big, seed=0)
     hv = Hivis(big, w)

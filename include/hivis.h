@@ -257,6 +257,18 @@ int hivis_kernel_ms(hivis_ctx *ctx, double *total_ms, int64_t *launches, double 
  * (every weight once, the KV rows read once; see the formulas in the implementation). */
 int hivis_algorithmic_bytes(hivis_ctx *ctx, double *verify_bytes, double *draft_step_bytes);
 
+/* Measurement hook, independent of any context: the rate at which a plain read-only kernel streams memory on this
+ * GPU, with the access pattern of the library's weight-streaming GEMMs (1 KiB per wavefront and instruction, 8
+ * independent 16-byte loads per lane, 64 KiB per workgroup and trip) and none of their work.  n_buffers device
+ * buffers of buffer_bytes each are allocated, filled, read once untimed and then `passes` times in rotation, one launch
+ * of `workgroups` x 512 threads per buffer, back to back on hip_stream (a hipStream_t, NULL = default); HIP events
+ * around the timed launches give the rate (launch gaps included, as in a pass of the library).  Choose n_buffers *
+ * buffer_bytes well above the 256 MB memory-side cache so that nothing is re-read from it.
+ *   gb_per_s: bytes read / elapsed time, in 1e9 bytes per second; us_per_launch: elapsed time / launches.  Either may be NULL.
+ * Frees everything before it returns.  Errors: EINVAL (sizes), EHIP. */
+int hivis_calib_stream(void *hip_stream, int64_t buffer_bytes, int32_t n_buffers, int32_t passes, int32_t workgroups,
+                       double *gb_per_s, double *us_per_launch);
+
 /* Host function, no GPU needed: the rule every greedy-token kernel applies before it stores a token id (the same
  * inline function, compiled for the host): ids below 0 become 0, ids >= vocab become vocab - 1.  Only a row of logits
  * with no finite maximum (NaN / Inf inputs) yields such an id; the calls that synchronise (hivis_prefill, hivis_accept,

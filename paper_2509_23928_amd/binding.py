@@ -79,6 +79,7 @@ def load_library(path=LIB_PATH):
         "hivis_kernel_ms": (C.c_int, [P, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
         "hivis_algorithmic_bytes": (C.c_int, [P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "hivis_clamp_token": (I32, [I32, I32]),
+        "hivis_calib_stream": (C.c_int, [P, C.c_int64, I32, I32, I32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "hivis_last_error": (C.c_char_p, [P]),
         "hivis_version": (C.c_char_p, []),
     }
@@ -91,7 +92,7 @@ def load_library(path=LIB_PATH):
 
 EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_draft_noalloc", "hivis_set_drafts",
                     "hivis_verify", "hivis_accept", "hivis_prefill_sample", "hivis_draft_sample", "hivis_accept_sample", "hivis_tree_draft", "hivis_tree_set", "hivis_tree_verify", "hivis_tree_accept", "hivis_tree_get", "hivis_tree_get_logits", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
-                    "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes", "hivis_clamp_token",
+                    "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes", "hivis_clamp_token", "hivis_calib_stream",
                     "hivis_last_error", "hivis_version")
 
 
@@ -116,6 +117,16 @@ def _host_weight(a, dtype):
         assert not np.any(bits & np.uint32(0xFFFF)), "float32 weights of a bf16 model must hold bf16-representable values"
         return np.ascontiguousarray((bits >> np.uint32(16)).astype(np.uint16))
     return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def calib_stream(buffer_bytes, n_buffers, passes, workgroups=1024, stream=None):
+    """hivis_calib_stream: (GB/s, us per launch) of a plain read-only streaming kernel over rotating buffers."""
+    lib = load_library()
+    gbs, us = C.c_double(), C.c_double()
+    rc = lib.hivis_calib_stream(C.c_void_p(stream or 0), int(buffer_bytes), int(n_buffers), int(passes), int(workgroups), C.byref(gbs), C.byref(us))
+    if rc:
+        raise HivisError(rc, "hivis_calib_stream failed")
+    return gbs.value, us.value
 
 
 class Hivis:

@@ -1777,6 +1777,51 @@ int hivis_algorithmic_bytes(hivis_ctx* c, double* verify_bytes, double* draft_st
 
 int32_t hivis_clamp_token(int32_t id, int32_t vocab) { return clamp_token(id, vocab); }
 
+int hivis_calib_stream(void* hip_stream, int64_t buffer_bytes, int32_t n_buffers, int32_t passes, int32_t workgroups, double* gb_per_s,
+                       double* us_per_launch) {
+    if (buffer_bytes < (1 << 20) || n_buffers < 1 || n_buffers > 64 || passes < 1 || workgroups < 1 || workgroups > 65535) return HIVIS_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t n16 = (size_t)buffer_bytes / 16;
+    const size_t trips = n16 / 4096;
+    if (trips == 0) return HIVIS_EINVAL;
+    std::vector<void*> bufs;
+    unsigned* sink = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = HIVIS_OK;
+    auto cleanup = [&]() {
+        for (void* b : bufs) (void)hipFree(b);
+        if (sink) (void)hipFree(sink);
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+    };
+#define CAL_TRY(expr) do { if ((expr) != hipSuccess) { cleanup(); return HIVIS_EHIP; } } while (0)
+    CAL_TRY(hipMalloc((void**)&sink, sizeof(unsigned)));
+    for (int i = 0; i < n_buffers; ++i) {
+        void* b = nullptr;
+        CAL_TRY(hipMalloc(&b, n16 * 16));
+        bufs.push_back(b);
+        CAL_TRY(hipMemsetAsync(b, 0x5A, n16 * 16, st));
+    }
+    CAL_TRY(hipEventCreate(&e0)); CAL_TRY(hipEventCreate(&e1));
+    // one untimed round over all buffers, then `passes` timed rounds; the buffers rotate so that nothing read comes from a cache
+    for (int i = 0; i < n_buffers; ++i) hipLaunchKernelGGL(calib_stream_kernel, dim3(workgroups), dim3(512), 0, st, (const uint4*)bufs[i], n16, sink);
+    CAL_TRY(hipEventRecord(e0, st));
+    for (int p = 0; p < passes; ++p)
+        for (int i = 0; i < n_buffers; ++i) hipLaunchKernelGGL(calib_stream_kernel, dim3(workgroups), dim3(512), 0, st, (const uint4*)bufs[i], n16, sink);
+    CAL_TRY(hipEventRecord(e1, st));
+    CAL_TRY(hipEventSynchronize(e1));
+    CAL_TRY(hipGetLastError());
+    float ms = 0.f;
+    CAL_TRY(hipEventElapsedTime(&ms, e0, e1));
+#undef CAL_TRY
+    const double launches = (double)passes * n_buffers;
+    const double bytes = (double)trips * 4096 * 16.0;                 // what one launch reads
+    if (gb_per_s) *gb_per_s = bytes * launches / (ms * 1e-3) / 1e9;
+    if (us_per_launch) *us_per_launch = ms * 1e3 / launches;
+    cleanup();
+    return rc;
+}
+
 const char* hivis_last_error(hivis_ctx* c) { return c ? c->err.c_str() : g_create_err.c_str(); }
 const char* hivis_version(void) { return "hivis-gfx950 0.1"; }
 

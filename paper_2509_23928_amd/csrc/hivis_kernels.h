@@ -936,6 +936,28 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
 }
 
 // ------------------------------------------------------------------------------------------
+// Calibration: a plain read-only stream over a buffer, the access pattern of the weight-streaming GEMMs without any
+// of their work (one wavefront reads 1 KiB per instruction, 8 independent 16-byte loads per lane and trip, a workgroup
+// 64 KiB per trip).  What it reaches is the ceiling any weight-streaming kernel on this machine works under.
+// n16: buffer size in 16-byte units.  The xor of everything read goes to `sink` only if it equals a value it
+// cannot practically take, which keeps the loads alive.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void calib_stream_kernel(const uint4* __restrict__ buf, size_t n16, unsigned* __restrict__ sink) {
+    const size_t trips = n16 / 4096;                                         // 64 KiB per workgroup and trip: 8 wavefronts x 8 loads x 64 lanes
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t t = blockIdx.x; t < trips; t += gridDim.x) {
+        const uint4* p = buf + t * 4096 + (size_t)wave * 512 + lane;
+        uint4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = p[(size_t)j * 64];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { acc.x ^= v[j].x; acc.y ^= v[j].y; acc.z ^= v[j].z; acc.w ^= v[j].w; }
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u && acc.x == 0x7F4A7C15u) *sink = acc.x;
+}
+
+// ------------------------------------------------------------------------------------------
 // Token-level kernels
 // ------------------------------------------------------------------------------------------
 // Token id forced into [0, V-1] (an id outside it can only come from a row without a greedy token, see argmax_kernel)

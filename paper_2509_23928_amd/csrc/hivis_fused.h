@@ -95,12 +95,12 @@ constexpr int FUSED_NW = 8, FUSED_NT = FUSED_NW * 64;
 template <> struct FusedCfg<bf16_t> { static constexpr int KBW = 8, G = 8, NW = FUSED_NW; };
 template <> struct FusedCfg<float> { static constexpr int KBW = 8, G = 4, NW = FUSED_NW; };
 constexpr int FUSED_U = 8;
-constexpr int FUSED_QM = 8;       // activation rows staged per thread per pass (8 rows / 1 for bf16, 16 rows / 2 for fp32)
+constexpr int FUSED_QM = 8;       // activation rows staged per lane per pass (bf16: rows q; fp32: rows 2 q + lane / 32)
 
-// LDS of a GEMM phase (floats): cross-wave reduction [NW][TILE] | reduced tiles [TILE] | ssq partials [NW][QM]
+// LDS of a GEMM phase (floats): cross-wave reduction [NW][TILE] | reduced tiles [TILE] | ssq partials [NW][16]
 // | inv_rms [16] | A chunk of one K pass in MFMA fragment order [NW*KBW blocks][4][RU] x 16 bytes
 __host__ __device__ constexpr size_t fused_gemm_lds_floats(int NW, int G, int RPL, int KBW) {
-    return (size_t)NW * G * 64 * RPL + (size_t)G * 64 * RPL + (size_t)NW * FUSED_QM + 16 + (size_t)NW * KBW * 4 * 16 * 4;
+    return (size_t)NW * G * 64 * RPL + (size_t)G * 64 * RPL + (size_t)NW * 16 + 16 + (size_t)NW * KBW * 4 * 16 * 4;
 }
 
 // Four consecutive RMSNorm gains as loaded (raw bits of the weight type); converted to float where they are used
@@ -194,11 +194,13 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     constexpr int SLOTS = TILE / NT;         // epilogue slots per thread (all of the same row and column-in-tile)
     static_assert(TILE % NT == 0, "whole epilogue slots per thread");
     constexpr int CW = NW * KBW * KB;        // k per pass (64 blocks)
-    constexpr int C4 = CW / 4;               // float4 columns per pass (<= 512)
+    constexpr int SL4 = KBW * KB / 4;        // float4 columns of one wavefront's K slice of a pass (64 bf16 / 32 fp32)
+    constexpr int RS = 64 / SL4;             // rows a wavefront covers per load step (1 / 2)
+    static_assert(RS == 1 || RS == 2, "a wavefront's lanes cover one or two rows of its slice at a time");
     float* red = lds;                        // [NW][G][64][RPL]
     float* tile = red + (size_t)NW * TILE;   // [G][64][RPL]
-    float* ssq_w = tile + TILE;              // [NW][QM]
-    float* inv_rms = ssq_w + NW * QM;        // [16]
+    float* ssq_w = tile + TILE;              // [NW][16]
+    float* inv_rms = ssq_w + NW * 16;        // [16]
     uint4* chunk = reinterpret_cast<uint4*>(inv_rms + 16);
 
     const int epi = (EPI >= 0) ? EPI : ph.epi;       // compile-time epilogue when the phase has its own kernel
@@ -219,8 +221,12 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     const int lda = ph.lda;
     const uint4* W = ph.W;
     const int RU = (RPL == 2) ? 4 * ((M + 1) >> 1) : ((M + 3) & ~3);      // tile rows in use
-    const int col4 = threadIdx.x % C4, row0 = threadIdx.x / C4;          // this thread stages rows row0, row0 + RSTEP, ...
-    constexpr int RSTEP = NT / C4;
+    // Activation staging is PRIVATE to a wavefront: it loads, converts and parks exactly the K slice its own weight
+    // blocks multiply (lane: float4 column col4 of the slice, rows row0 + q*RS), into its own part of the LDS chunk, and
+    // reads its fragments back; no workgroup barrier is involved, so the eight wavefronts stream independently until the
+    // cross-wavefront reduction at the end (with workgroup-wide staging every pass waited twice for the slowest one).
+    const int col4 = lane % SL4, row0 = lane / SL4;
+    uint4* slice = chunk + (size_t)wave * (KBW * 4 * 16);               // [KBW blocks][4][RU] x 16 bytes of this wavefront
     float ssq_acc[QM];
 #pragma unroll
     for (int q = 0; q < QM; ++q) ssq_acc[q] = 0.f;
@@ -255,44 +261,48 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         return;
     }
 
-    // raw activation loads of pass `ps`: float4 (row0 + q*RSTEP, ps*CW + 4*col4) and the gain of those 4 columns
-    // (unconditional loads from clamped addresses: a load under a divergent branch is followed by a full wait,
-    //  which would serialise the rows into one memory round trip each)
-    static_assert(QM * RSTEP >= ROWS, "every row is staged by some thread");
+    // raw activation loads of pass `ps`: float4 (row0 + q*RS, first k of the wavefront's slice + 4*col4) and the gain of
+    // those 4 columns (unconditional loads from clamped addresses: a load under a divergent branch is followed by a
+    // full wait, which would serialise the rows into one memory round trip each)
+    static_assert(QM * RS >= ROWS, "every row is staged by some lane");
     typedef typename Gain4<WT>::type gain4_t;
     float4 araw[QM]; gain4_t graw = gain4_t();
 #define HIVIS_LOAD_RAW(ps)                                                                                         \
     {                                                                                                              \
-        const int k_ = min((ps) * CW + 4 * col4, K - 4);                                                           \
+        const int k_ = min(unit_kb0<NW, KBW>(kblks, ps, wave) * KB + 4 * col4, K - 4);                             \
         if (gain) graw = *reinterpret_cast<const gain4_t*>(gain + k_);   /* converted where it is used: no wait here */ \
         _Pragma("unroll") for (int q = 0; q < QM; ++q) {                                                           \
-            const int row_ = min(row0 + q * RSTEP, M - 1);                                                         \
+            const int row_ = min(row0 + q * RS, M - 1);                                                            \
             araw[q] = *reinterpret_cast<const float4*>(A + (size_t)row_ * lda + k_);                               \
         }                                                                                                          \
     }
-    // Stage pass `ps` (whose rows are in araw) into LDS as MFMA fragments, request the rows of pass `nx` (or none if
-    // nx < 0), and fetch this wavefront's fragments af[0..KBW).
+    // Stage this wavefront's slice of pass `ps` (whose rows are in araw) into its LDS slice as MFMA fragments, request
+    // the rows of pass `nx` (or none if nx < 0), and fetch the fragments af[0..KBW).
 #define HIVIS_STAGE(ps, nx, do_ssq)                                                                                \
-    lds_barrier();                        /* everyone is done with the previous chunk */                           \
-    _Pragma("unroll") for (int q = 0; q < QM; ++q) {                                                               \
-        const int row_ = row0 + q * RSTEP;                                                                         \
-        if (row_ < M && (ps) * CW + 4 * col4 < K) {                                                                \
-            float x_[4] = {araw[q].x, araw[q].y, araw[q].z, araw[q].w};                                            \
-            if (do_ssq) ssq_acc[q] += x_[0] * x_[0] + x_[1] * x_[1] + x_[2] * x_[2] + x_[3] * x_[3];               \
-            if (gain) { _Pragma("unroll") for (int e = 0; e < 4; ++e) x_[e] *= Gain4<WT>::get(graw, e); }          \
-            stage_store(WT(), chunk, RU, row_, 4 * col4, x_);                                                      \
-        }                                                                                                          \
-    }                                                                                                              \
-    if ((nx) >= 0) HIVIS_LOAD_RAW(nx)                                                                              \
-    lds_barrier();                                                                                                 \
     {                                                                                                              \
         const int nkb_ = unit_nkb<NW, KBW>(kblks, ps, wave);                                                       \
-        const int fb_ = wave * unit_bw<NW, KBW>(kblks, ps);      /* first block of this wavefront within the chunk */ \
+        _Pragma("unroll") for (int q = 0; q < QM; ++q) {                                                           \
+            const int row_ = row0 + q * RS;                                                                        \
+            if (row_ < M && 4 * col4 < nkb_ * KB) {                                                                \
+                float x_[4] = {araw[q].x, araw[q].y, araw[q].z, araw[q].w};                                        \
+                if (do_ssq) ssq_acc[q] += x_[0] * x_[0] + x_[1] * x_[1] + x_[2] * x_[2] + x_[3] * x_[3];           \
+                if (gain) { _Pragma("unroll") for (int e = 0; e < 4; ++e) x_[e] *= Gain4<WT>::get(graw, e); }      \
+                stage_store(WT(), slice, RU, row_, 4 * col4, x_);                                                  \
+            }                                                                                                      \
+        }                                                                                                          \
+        if ((nx) >= 0) HIVIS_LOAD_RAW(nx)                                                                          \
+        /* the slice is written and read by this wavefront only */                                                 \
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");                                                     \
+        __builtin_amdgcn_wave_barrier();                                                                           \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");                                                     \
         const int i_ = min(lane & 15, RU - 1), g4_ = lane >> 4;                                                    \
         _Pragma("unroll") for (int j = 0; j < KBW; ++j) {                                                          \
-            const uint4 u_ = chunk[((min(fb_ + j, NW * KBW - 1)) * 4 + g4_) * RU + i_];                            \
+            const uint4 u_ = slice[(j * 4 + g4_) * RU + i_];                                                       \
             frag_from(af[j], (j < nkb_) ? u_ : make_uint4(0, 0, 0, 0));                                            \
         }                                                                                                          \
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");                                                     \
+        __builtin_amdgcn_wave_barrier();                                                                           \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");                                                     \
     }
     HIVIS_MARK(0)
     // The activation rows are requested BEFORE the first weight units: loads return in order, so rows requested
@@ -388,10 +398,14 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             }
         }
         if (first && gain) {
+            // this wavefront's share of every row's sum of squares (its lanes with row0 == h hold rows h + q*RS)
 #pragma unroll
             for (int q = 0; q < QM; ++q) {
-                const float s = wave_sum(ssq_acc[q]);
-                if (lane == 0) ssq_w[wave * QM + q] = s;
+#pragma unroll
+                for (int h = 0; h < RS; ++h) {
+                    const float s = wave_sum(row0 == h ? ssq_acc[q] : 0.f);
+                    if (lane == 0) ssq_w[wave * 16 + q * RS + h] = s;
+                }
             }
         }
         lds_barrier();
@@ -402,11 +416,10 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             tile[idx] = s;
         }
         if (first && gain && (int)threadIdx.x < M) {
-            // row r was staged by the wavefronts whose threads have row0 == r % RSTEP, as their (r / RSTEP)-th row
-            const int r = threadIdx.x, q = r / RSTEP, r0 = r % RSTEP;
-            constexpr int WPR = C4 / 64;          // wavefronts per staged row
+            const int r = threadIdx.x;
             float s = 0.f;
-            for (int w = r0 * WPR; w < (r0 + 1) * WPR; ++w) s += ssq_w[w * QM + q];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) s += ssq_w[w * 16 + r];
             inv_rms[r] = 1.0f / sqrtf(s / (float)K + pp.eps);
         }
         lds_barrier();

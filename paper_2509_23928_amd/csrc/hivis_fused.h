@@ -267,30 +267,32 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     static_assert(QM * RS >= ROWS, "every row is staged by some lane");
     typedef typename Gain4<WT>::type gain4_t;
     float4 araw[QM]; gain4_t graw = gain4_t();
-#define HIVIS_LOAD_RAW(ps)                                                                                         \
+    float4 araw2[SINGLE ? QM : 1]; gain4_t graw2 = gain4_t();      // rows of the second pass of a pair (one tile per workgroup)
+#define HIVIS_LOAD_RAW_TO(ps, ARAW, GRAW)                                                                          \
     {                                                                                                              \
         const int k_ = min(unit_kb0<NW, KBW>(kblks, ps, wave) * KB + 4 * col4, K - 4);                             \
-        if (gain) graw = *reinterpret_cast<const gain4_t*>(gain + k_);   /* converted where it is used: no wait here */ \
+        if (gain) GRAW = *reinterpret_cast<const gain4_t*>(gain + k_);   /* converted where it is used: no wait here */ \
         _Pragma("unroll") for (int q = 0; q < QM; ++q) {                                                           \
             const int row_ = min(row0 + q * RS, M - 1);                                                            \
-            araw[q] = *reinterpret_cast<const float4*>(A + (size_t)row_ * lda + k_);                               \
+            ARAW[q] = *reinterpret_cast<const float4*>(A + (size_t)row_ * lda + k_);                               \
         }                                                                                                          \
     }
-    // Stage this wavefront's slice of pass `ps` (whose rows are in araw) into its LDS slice as MFMA fragments, request
-    // the rows of pass `nx` (or none if nx < 0), and fetch the fragments af[0..KBW).
-#define HIVIS_STAGE(ps, nx, do_ssq)                                                                                \
+#define HIVIS_LOAD_RAW(ps) HIVIS_LOAD_RAW_TO(ps, araw, graw)
+    // Stage this wavefront's slice of pass `ps` (whose rows are in ARAW) into its LDS slice as MFMA fragments, run
+    // NEXT (the request for the rows staged next, or nothing), and fetch the fragments af[0..KBW).
+#define HIVIS_STAGE_FROM(ps, ARAW, GRAW, do_ssq, NEXT)                                                             \
     {                                                                                                              \
         const int nkb_ = unit_nkb<NW, KBW>(kblks, ps, wave);                                                       \
         _Pragma("unroll") for (int q = 0; q < QM; ++q) {                                                           \
             const int row_ = row0 + q * RS;                                                                        \
             if (row_ < M && 4 * col4 < nkb_ * KB) {                                                                \
-                float x_[4] = {araw[q].x, araw[q].y, araw[q].z, araw[q].w};                                        \
+                float x_[4] = {ARAW[q].x, ARAW[q].y, ARAW[q].z, ARAW[q].w};                                        \
                 if (do_ssq) ssq_acc[q] += x_[0] * x_[0] + x_[1] * x_[1] + x_[2] * x_[2] + x_[3] * x_[3];           \
-                if (gain) { _Pragma("unroll") for (int e = 0; e < 4; ++e) x_[e] *= Gain4<WT>::get(graw, e); }      \
+                if (gain) { _Pragma("unroll") for (int e = 0; e < 4; ++e) x_[e] *= Gain4<WT>::get(GRAW, e); }      \
                 stage_store(WT(), slice, RU, row_, 4 * col4, x_);                                                  \
             }                                                                                                      \
         }                                                                                                          \
-        if ((nx) >= 0) HIVIS_LOAD_RAW(nx)                                                                          \
+        NEXT                                                                                                       \
         /* the slice is written and read by this wavefront only */                                                 \
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");                                                     \
         __builtin_amdgcn_wave_barrier();                                                                           \
@@ -304,6 +306,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         __builtin_amdgcn_wave_barrier();                                                                           \
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");                                                     \
     }
+#define HIVIS_STAGE(ps, nx, do_ssq) HIVIS_STAGE_FROM(ps, araw, graw, do_ssq, if ((nx) >= 0) HIVIS_LOAD_RAW(nx))
     HIVIS_MARK(0)
     // The activation rows are requested BEFORE the first weight units: loads return in order, so rows requested
     // after 16 KiB of weights per wavefront could not be staged until those weights had arrived from HBM.
@@ -322,19 +325,30 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         for (int g = 0; g < G; ++g) acc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         afrag_t af[KBW];
         if constexpr (SINGLE) {
-            // ---- every workgroup owns at most one tile: the K passes alternate between the two unit buffers, each requested two passes ahead
+            // ---- every workgroup owns at most one tile.  The K passes go in pairs, and everything the NEXT pair needs
+            //      (two weight units, the rows of both passes) is requested in one go after the pair's arithmetic: the
+            //      compiler waits for "all loads" wherever one is used (conditional loads defeat its counting), so what
+            //      matters is how much is in flight per wait: two units here.  With one unit requested per pass every
+            //      pass paid a memory round trip for 8 KiB per wavefront and the kernel was latency-bound.
+            if (npass > 1) HIVIS_LOAD_RAW_TO(1, araw2, graw2)
+            if (!wb1_first && npass > 1) issue_unit(wb1, W, kblks, tg, unit_kb0<NW, KBW>(kblks, 1, wave), unit_nkb<NW, KBW>(kblks, 1, wave), lane);
             for (int pass = 0; pass < npass; pass += 2) {
-                HIVIS_STAGE(pass, (pass + 1 < npass) ? pass + 1 : -1, true)
+                HIVIS_STAGE_FROM(pass, araw, graw, true, )
                 if (pass == 0) { HIVIS_MARK(1) }
 #pragma unroll
                 for (int j = 0; j < U; ++j) mfma_block(acc[0], af[j], head[j]);
-                if (pass + 2 < npass) issue_unit(head, W, kblks, tg, unit_kb0<NW, KBW>(kblks, pass + 2, wave), unit_nkb<NW, KBW>(kblks, pass + 2, wave), lane);
                 if (pass + 1 < npass) {
-                    if (pass == 0 && !wb1_first) issue_unit(wb1, W, kblks, tg, unit_kb0<NW, KBW>(kblks, 1, wave), unit_nkb<NW, KBW>(kblks, 1, wave), lane);
-                    HIVIS_STAGE(pass + 1, (pass + 2 < npass) ? pass + 2 : -1, true)
+                    HIVIS_STAGE_FROM(pass + 1, araw2, graw2, true, )
 #pragma unroll
                     for (int j = 0; j < U; ++j) mfma_block(acc[0], af[j], wb1[j]);
-                    if (pass + 3 < npass) issue_unit(wb1, W, kblks, tg, unit_kb0<NW, KBW>(kblks, pass + 3, wave), unit_nkb<NW, KBW>(kblks, pass + 3, wave), lane);
+                }
+                if (pass + 2 < npass) {
+                    HIVIS_LOAD_RAW_TO(pass + 2, araw, graw)
+                    issue_unit(head, W, kblks, tg, unit_kb0<NW, KBW>(kblks, pass + 2, wave), unit_nkb<NW, KBW>(kblks, pass + 2, wave), lane);
+                }
+                if (pass + 3 < npass) {
+                    HIVIS_LOAD_RAW_TO(pass + 3, araw2, graw2)
+                    issue_unit(wb1, W, kblks, tg, unit_kb0<NW, KBW>(kblks, pass + 3, wave), unit_nkb<NW, KBW>(kblks, pass + 3, wave), lane);
                 }
             }
         } else {
@@ -477,7 +491,9 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         }
     }
 #undef HIVIS_LOAD_RAW
+#undef HIVIS_LOAD_RAW_TO
 #undef HIVIS_STAGE
+#undef HIVIS_STAGE_FROM
     HIVIS_MARK(5)
     if (epi == FEPI_LOGITS) {
         // per-row candidate of this workgroup: the threads of one row meet through LDS

@@ -472,7 +472,7 @@ struct Pool {
 // of the layer output (row stride ldd).
 template <typename WT>
 float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const LayerDev& L, const KVDev& kv, float* h, const int* base,
-                    int offset, int nseq, int m, float* rope, float* dst, int ldd, int* ld_out, bool persistent, bool elect) {
+                    int offset, int nseq, int m, float* dst, int ldd, int* ld_out, bool persistent, bool elect) {
     const hivis_config& g = c->cfg;
     const int M = nseq * m;
     const int d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn, nqkv = qd + 2 * kd;
@@ -483,7 +483,7 @@ float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const Layer
     float* h2 = dst ? dst : pool.take((size_t)M * d);
     const int ld2 = dst ? ldd : d;
     Phase q{}; q.type = PH_GEMM; q.pro = PRO_RMS; q.epi = FEPI_QKV; q.K = d; q.N = nqkv; q.W = L.wqkv; q.A = h; q.lda = d;
-    q.gain = L.norm1; q.Y = qkv; q.ldy = nqkv; q.kc = kv.k; q.vc = kv.v; q.maxL = kv.maxL; q.base = base; q.offset = offset; q.rope = rope;
+    q.gain = L.norm1; q.Y = qkv; q.ldy = nqkv; q.kc = kv.k; q.vc = kv.v; q.maxL = kv.maxL; q.base = base; q.offset = offset; q.rope = c->rope_tab;
     P.push_back(q);
     Phase a{}; a.type = PH_ATTN; a.A = qkv; a.lda = nqkv; a.kc = kv.k; a.vc = kv.v; a.maxL = kv.maxL; a.base = base; a.offset = offset;
     a.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, nqkv, &a.att_items);
@@ -517,58 +517,81 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
     const hivis_config& g = c->cfg;
     const int B = g.batch, d = g.d, V = g.vocab, G = c->fused_grid;
     int ld = d;
+    // Launch-per-phase programs fold two small phases away: the gather of Embed(x) into the fusion FC (its activation
+    // columns [d, 2d) come straight from the embedding table), and, with `elect`, the greedy-token reduction into the
+    // LM-head phase (the workgroup that arrives last reduces the candidates).  The single-launch program keeps both phases.
+    const bool fold = !persistent;
+    const bool lm_elect = elect && !persistent;
     if (kind == PROG_VERIFY) {
         const int m = K + 1, M = B * m;
         float* x = pool.take((size_t)M * d);
-        float* rope = pool.take((size_t)M * g.head_dim);
         Phase pr{}; pr.type = PH_PREP; pr.ids = c->row_tok; pr.id_sseq = m; pr.id_srow = 1; pr.gain = c->embed; pr.Y = x; pr.ldy = d;
-        pr.base = c->tlen; pr.offset = 0; pr.rope = rope;
+        pr.base = c->tlen; pr.offset = 0;
         P.push_back(pr);
-        for (int l = 0; l < g.n_layers; ++l) x = layer_phases<WT>(c, P, pool, c->layers[l], c->tkv[l], x, c->tlen, 0, B, m, rope, nullptr, 0, &ld, persistent, elect);
+        for (int l = 0; l < g.n_layers; ++l) x = layer_phases<WT>(c, P, pool, c->layers[l], c->tkv[l], x, c->tlen, 0, B, m, nullptr, 0, &ld, persistent, elect);
         Phase nr{}; nr.type = PH_NORM_ROWS; nr.A = x; nr.lda = d; nr.gain = c->final_norm; nr.Y = c->catT; nr.ldy = 2 * d;
         P.push_back(nr);
         Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = c->catT; lm.lda = 2 * d;
         lm.Y = c->logits_v; lm.ldy = V; lm.pm = pool.take((size_t)M * G); lm.pi = (int*)pool.take((size_t)M * G);
+        lm.tok_out = c->ttok; lm.o_sseq = g.k_max + 1; lm.o_srow = 1;
+        if (lm_elect) lm.cnt = (int*)pool.take(1);         // zero from the pool's memset; the reducing workgroup re-zeroes it
         P.push_back(lm);
-        Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->ttok; am.o_sseq = g.k_max + 1; am.o_srow = 1; am.pm = lm.pm; am.pi = lm.pi; am.N = G;
-        P.push_back(am);
+        if (!lm_elect) {
+            Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->ttok; am.o_sseq = g.k_max + 1; am.o_srow = 1; am.pm = lm.pm; am.pi = lm.pi; am.N = G;
+            P.push_back(am);
+        }
     } else if (kind == PROG_DRAFT || kind == PROG_DRAFT_SAMPLE) {
         // cat: [B][2d] = drafter hidden f' | embedding of the token drafted from it; a fresh buffer per step
         float* cat = c->catD;
         for (int i = 1; i <= K; ++i) {
             Phase lm{}; lm.type = PH_GEMM; lm.pro = PRO_PLAIN; lm.epi = FEPI_LOGITS; lm.K = d; lm.N = V; lm.W = c->lm_head; lm.A = cat; lm.lda = 2 * d;
             lm.Y = c->logits_d + (size_t)(i - 1) * B * V; lm.ldy = V; lm.pm = pool.take((size_t)B * G); lm.pi = (int*)pool.take((size_t)B * G);
+            lm.tok_out = c->drafts + (i - 1); lm.o_sseq = g.k_max; lm.o_srow = 0;
+            // greedy token of step i: reduced by the fusion FC that follows (steps before the last), by the LM head's last
+            // workgroup (last step, with `elect`), or by a phase of its own
+            const bool in_fc = fold && kind == PROG_DRAFT && i < K;
+            const bool in_lm = !in_fc && lm_elect && kind == PROG_DRAFT;
+            if (in_lm) lm.cnt = (int*)pool.take(1);
             P.push_back(lm);
-            Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->drafts + (i - 1); am.o_sseq = g.k_max; am.o_srow = 0; am.pm = lm.pm; am.pi = lm.pi; am.N = G;
-            if (kind == PROG_DRAFT_SAMPLE) {     // the token is drawn from softmax(logits / T) instead (uniforms [B][k_max], column i-1)
-                am.type = PH_SAMPLE; am.A = lm.Y; am.lda = V; am.u = c->u_draft; am.u_sseq = g.k_max; am.u_idx = i - 1;
+            if (!in_lm && !in_fc) {
+                Phase am{}; am.type = PH_ARGMAX; am.tok_out = c->drafts + (i - 1); am.o_sseq = g.k_max; am.o_srow = 0; am.pm = lm.pm; am.pi = lm.pi; am.N = G;
+                if (kind == PROG_DRAFT_SAMPLE) {     // the token is drawn from softmax(logits / T) instead (uniforms [B][k_max], column i-1)
+                    am.type = PH_SAMPLE; am.A = lm.Y; am.lda = V; am.u = c->u_draft; am.u_sseq = g.k_max; am.u_idx = i - 1;
+                }
+                P.push_back(am);
             }
-            P.push_back(am);
             if (i < K) {
-                float* rope = pool.take((size_t)B * g.head_dim);
                 float* u = pool.take((size_t)B * d);
                 float* cat_next = pool.take((size_t)B * 2 * d);
-                Phase pr{}; pr.type = PH_PREP; pr.ids = c->drafts + (i - 1); pr.id_sseq = g.k_max; pr.id_srow = 0; pr.gain = c->embed;
-                pr.Y = cat + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = i - 1; pr.rope = rope;
-                P.push_back(pr);
                 Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = cat; fu.lda = 2 * d;
                 fu.Y = u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = std::min(i, g.n_resid - 1);
+                if (fold) {
+                    fu.emb = c->embed; fu.tok = c->drafts + (i - 1); fu.tok_sseq = g.k_max; fu.tok_srow = 0;
+                    if (in_fc) { fu.tok = nullptr; fu.pm = lm.pm; fu.pi = lm.pi; fu.ncand = G; fu.tok_out = c->drafts + (i - 1); fu.o_sseq = g.k_max; fu.o_srow = 0; }
+                }
+                else {
+                    Phase pr{}; pr.type = PH_PREP; pr.ids = c->drafts + (i - 1); pr.id_sseq = g.k_max; pr.id_srow = 0; pr.gain = c->embed;
+                    pr.Y = cat + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = i - 1;
+                    P.push_back(pr);
+                }
                 P.push_back(fu);
-                layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, i - 1, B, 1, rope, cat_next, 2 * d, &ld, persistent, elect);
+                layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, i - 1, B, 1, cat_next, 2 * d, &ld, persistent, elect);
                 cat = cat_next;
             }
         }
     } else {
         const int m = K + 1, M = B * m;
-        float* rope = pool.take((size_t)M * g.head_dim);
         float* u = pool.take((size_t)M * d);
-        Phase pr{}; pr.type = PH_PREP; pr.ids = c->next_tok; pr.id_sseq = g.k_max + 1; pr.id_srow = 1; pr.gain = c->embed;
-        pr.Y = c->catT + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = 0; pr.rope = rope;
-        P.push_back(pr);
         Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = c->catT; fu.lda = 2 * d;
         fu.Y = u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = 0;
+        if (fold) { fu.emb = c->embed; fu.tok = c->next_tok; fu.tok_sseq = g.k_max + 1; fu.tok_srow = 1; }
+        else {
+            Phase pr{}; pr.type = PH_PREP; pr.ids = c->next_tok; pr.id_sseq = g.k_max + 1; pr.id_srow = 1; pr.gain = c->embed;
+            pr.Y = c->catT + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = 0;
+            P.push_back(pr);
+        }
         P.push_back(fu);
-        layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, 0, B, m, rope, c->dout, d, &ld, persistent, elect);
+        layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, 0, B, m, c->dout, d, &ld, persistent, elect);
     }
     // chain the GEMM phases for the cross-barrier weight prefetch
     for (size_t i = 0; i < P.size(); ++i) {
@@ -617,6 +640,8 @@ int launch_phases(hivis_ctx* c, const Phase* phases, int n, int kind, int K, con
         if (ph.type == PH_ATTN || ph.type == PH_ATTN_MERGE) {
             ph.att.nsplit = std::max(1, std::min(ph.att.nsplit, (max_keys + c->keys_per_split - 1) / c->keys_per_split));
             ph.att.flags = c->attn_flags;
+        }
+        if (ph.type == PH_ATTN || ph.type == PH_ATTN_MERGE || (ph.type == PH_GEMM && ph.epi == FEPI_QKV)) {
             if (g.batch <= 8 && ph.att.seq0 == 0) {          // the lengths the device arrays hold right now, by value
                 ph.att.nbase = g.batch;
                 for (int b = 0; b < g.batch; ++b) ph.att.base_val[b] = kind == PROG_VERIFY ? c->h_tlen[b] : c->h_dlen[b];
@@ -626,7 +651,7 @@ int launch_phases(hivis_ctx* c, const Phase* phases, int n, int kind, int K, con
         int grid = c->fused_grid;
         if (ph.type == PH_ATTN) grid = std::min(grid, ((ph.att.flags & 2) ? 8 * ((ph.att_items + 7) / 8) : ph.att_items) * ph.att.nsplit);
         else if (ph.type == PH_ATTN_MERGE) grid = std::min(grid, ph.att_items);
-        else if (ph.type == PH_PREP) grid = std::min(grid, std::max(pp.M, (pp.M * g.head_dim / 2 + FUSED_NT - 1) / FUSED_NT));
+        else if (ph.type == PH_PREP) grid = std::min(grid, pp.M);
         else if (ph.type == PH_NORM_ROWS) grid = std::min(grid, pp.M);
         else if (ph.type == PH_ARGMAX) grid = std::min(grid, (pp.M + FUSED_NW - 1) / FUSED_NW);
         else if (ph.type == PH_SAMPLE) grid = std::min(grid, pp.M);
@@ -1380,6 +1405,14 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     HIP_TRY(c, hipMemset(c->bad, 0, sizeof(int)));
     if ((rc = dev_alloc(c, &c->next_tok, (size_t)B * (g.k_max + 1)))) return rc;
     c->h_tlen.assign(B, 0); c->h_dlen.assign(B, 0);
+    // rotary table over every position either cache can hold (read by the QKV epilogue of the phase programs)
+    {
+        const int npos = g.max_vis + g.max_text;
+        if ((rc = dev_alloc(c, &c->rope_tab, (size_t)npos * g.head_dim))) return rc;
+        const size_t n = (size_t)npos * (g.head_dim / 2);
+        hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 4096)), dim3(256), 0, c->stream, c->rope_tab, npos, g.head_dim, g.rope_theta);
+        HIP_TRY(c, hipGetLastError());
+    }
     if ((rc = fused_setup<WT>(c))) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return HIVIS_OK;

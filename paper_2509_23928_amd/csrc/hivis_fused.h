@@ -36,14 +36,20 @@ struct Phase {
     float* Y; int ldy;         // output rows (STORE / ADD_TO / ADDVEC / LOGITS / QKV q part / SILU act / ATTN_MERGE / PREP gather / NORM_ROWS)
     const float* R; int ldr;   // ADD_TO: Y = R + result (R == Y: accumulate into the residual stream)
     const void* vec; int vec_idx;          // ADDVEC: table [*][N] of the weight dtype and the row to add
+    // ADDVEC (fusion FC), optional: columns [K/2, K) of activation row (seq, i) are row tok[seq*tok_sseq + i*tok_srow] of
+    // the embedding table emb ([vocab][K/2], weight dtype) instead of A's: the gather of Embed(x) needs no launch
+    const void* emb; const int32_t* tok; int tok_sseq, tok_srow;
+    // ... and if tok is null the token of row r is the greedy token of the LM-head phase before it, reduced here from
+    // that phase's per-workgroup candidates pm / pi ([row][ncand]); workgroup 0 also stores it to tok_out
+    int ncand;
     void* kc; void* vc; int maxL;          // QKV epilogue / ATTN: cache of this layer
     const int* base; int offset;           // row positions: base[seq] + offset + i
     const int32_t* ids; int id_sseq, id_srow;      // PREP: token of row (seq, i) = ids[seq*id_sseq + i*id_srow] (ids may be null: no gather)
     int32_t* tok_out; int o_sseq, o_srow;          // ARGMAX: destination of the greedy token of row (seq, i)
     AttnShape att; int att_items;                  // ATTN / ATTN_MERGE
-    float* rope;                                   // PREP writes, QKV epilogue reads: [rows][hd/2][2] cos, sin
+    const float* rope;                             // QKV epilogue: rotary table of the context, [position][hd/2][2] cos, sin
     float* ws;                                     // ATTN: per-workgroup partials of the key splits
-    int* cnt;                                      // ATTN: arrival counter per item (zero between launches)
+    int* cnt;                                      // ATTN: arrival counter per item; LM head: one arrival counter (zero between launches)
     float* pm; int* pi;                            // LOGITS writes, ARGMAX reads: greedy candidates [row][workgroup]
     const float* u; int u_sseq, u_idx;             // SAMPLE: uniform number of row (seq, i) = u[seq*u_sseq + u_idx]; logits rows in A (stride lda)
     const uint4* next_W; int next_K, next_N;       // GEMM: weights of the next GEMM phase of the program (prefetch), or null
@@ -117,6 +123,13 @@ template <> struct Gain4<float> {
     static __device__ __forceinline__ float get(const float4& g, int e) { return e == 0 ? g.x : e == 1 ? g.y : e == 2 ? g.z : g.w; }
 };
 
+// four consecutive values of the weight dtype as floats
+__device__ __forceinline__ float4 load4_f32(const bf16_t* p) {
+    const uint2 u = *reinterpret_cast<const uint2*>(p);
+    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xFFFF0000u));
+}
+__device__ __forceinline__ float4 load4_f32(const float* p) { return *reinterpret_cast<const float4*>(p); }
+
 // K blocks of pass p that wavefront `wave` owns.  A full pass gives every wavefront KBW consecutive blocks; a ragged
 // last pass is dealt out evenly (ceil(rest / NW) blocks each), so that no wavefront streams a whole unit more than the
 // others (with K = 11008 the last pass has 24 blocks: 3 per wavefront instead of 8 for three of them).
@@ -164,6 +177,38 @@ __device__ __forceinline__ void stage_store(float, uint4* chunk, int RU, int row
 __device__ __forceinline__ void frag_from(bf16x8_t& f, const uint4& u) { f = __builtin_bit_cast(bf16x8_t, u); }
 __device__ __forceinline__ void frag_from(float4& f, const uint4& u) {
     f = make_float4(__uint_as_float(u.x), __uint_as_float(u.y), __uint_as_float(u.z), __uint_as_float(u.w));
+}
+
+// Greedy tokens without a launch of their own: after a workgroup of the LM-head phase has stored its per-row
+// candidates (write-through) and those stores have completed, it arrives on the phase's counter; the workgroup that
+// arrives last reduces the gridDim.x candidates of every row (lowest index wins ties, as everywhere) and stores the
+// tokens.  Agent-scope atomics only (stores, counter, loads), as in the attention's key-split merge.  flag: one LDS word.
+__device__ __forceinline__ void lm_head_elect(const Phase& ph, const PassParams& pp, int* __restrict__ flag) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    wait_vmem();
+    lds_barrier();
+    if (threadIdx.x == 0) flag[0] = __hip_atomic_fetch_add(ph.cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    lds_barrier();
+    if (flag[0] != (int)gridDim.x - 1) return;
+    const int ncand = gridDim.x;
+    for (int row = wave; row < pp.M; row += FUSED_NW) {
+        float bv = -INFINITY; int bi = 0x7FFFFFFF;
+        for (int w = lane; w < ncand; w += 64) {
+            const float v = ld_agent(&ph.pm[(size_t)row * ncand + w]);
+            const int i = __hip_atomic_load(&ph.pi[(size_t)row * ncand + w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == 0) {
+            if (pp.bad && (unsigned)bi >= (unsigned)pp.V) st_wt(pp.bad, 1);
+            st_wt(&ph.tok_out[(row / pp.m) * ph.o_sseq + (row % pp.m) * ph.o_srow], clamp_token(bi, pp.V));
+        }
+    }
+    if (threadIdx.x == 0) st_wt(ph.cnt, 0);
 }
 
 // GEMM phase of the persistent kernel (rows <= one MFMA tile).  Work split as in gemm_skinny_kernel: the
@@ -256,6 +301,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         if (epi == FEPI_LOGITS && threadIdx.x < ROWS && (int)threadIdx.x < M) {
             st_wt(&ph.pm[(size_t)threadIdx.x * gridDim.x + blockIdx.x], -INFINITY); st_wt(&ph.pi[(size_t)threadIdx.x * gridDim.x + blockIdx.x], 0x7FFFFFFF);
         }
+        if (epi == FEPI_LOGITS && ph.cnt) lm_head_elect(ph, pp, reinterpret_cast<int*>(inv_rms));
         wait_vmem();
         if (!head_valid && n_has) HIVIS_FIRST_UNITS(ph.next_W, n_kblks, n_tile, n_tend - n_tile, n_npass)
         return;
@@ -266,15 +312,27 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     // full wait, which would serialise the rows into one memory round trip each)
     static_assert(QM * RS >= ROWS, "every row is staged by some lane");
     typedef typename Gain4<WT>::type gain4_t;
+    // fusion FC with the embedding half taken from the table: the tokens of this lane's rows
+    int tokr[QM];        // as loaded; forced into [0, V) where it is used, so that nothing waits for the load here
+#pragma unroll
+    for (int q = 0; q < QM; ++q) {
+        tokr[q] = 0;
+        if (EPI == FEPI_ADDVEC && ph.emb != nullptr && ph.tok != nullptr) {
+            const int r_ = min(row0 + q * RS, M - 1);
+            tokr[q] = __hip_atomic_load(&ph.tok[(r_ / pp.m) * ph.tok_sseq + (r_ % pp.m) * ph.tok_srow], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
     float4 araw[QM]; gain4_t graw = gain4_t();
     float4 araw2[SINGLE ? QM : 1]; gain4_t graw2 = gain4_t();      // rows of the second pass of a pair (one tile per workgroup)
 #define HIVIS_LOAD_RAW_TO(ps, ARAW, GRAW)                                                                          \
     {                                                                                                              \
         const int k_ = min(unit_kb0<NW, KBW>(kblks, ps, wave) * KB + 4 * col4, K - 4);                             \
         if (gain) GRAW = *reinterpret_cast<const gain4_t*>(gain + k_);   /* converted where it is used: no wait here */ \
+        const bool from_emb_ = EPI == FEPI_ADDVEC && ph.emb != nullptr && k_ >= K / 2;                             \
         _Pragma("unroll") for (int q = 0; q < QM; ++q) {                                                           \
             const int row_ = min(row0 + q * RS, M - 1);                                                            \
-            ARAW[q] = *reinterpret_cast<const float4*>(A + (size_t)row_ * lda + k_);                               \
+            if (from_emb_) ARAW[q] = load4_f32(reinterpret_cast<const WT*>(ph.emb) + (size_t)clamp_token(tokr[q], pp.V) * (K / 2) + (k_ - K / 2)); \
+            else ARAW[q] = *reinterpret_cast<const float4*>(A + (size_t)row_ * lda + k_);                          \
         }                                                                                                          \
     }
 #define HIVIS_LOAD_RAW(ps) HIVIS_LOAD_RAW_TO(ps, araw, graw)
@@ -307,12 +365,39 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");                                                     \
     }
 #define HIVIS_STAGE(ps, nx, do_ssq) HIVIS_STAGE_FROM(ps, araw, graw, do_ssq, if ((nx) >= 0) HIVIS_LOAD_RAW(nx))
+    // Tokens = greedy tokens of the LM-head phase before this one (fusion FC with ph.tok == null): every wavefront
+    // reduces that phase's candidates itself (lowest index wins ties); workgroup 0 also stores them.
+    const bool cand_tokens = EPI == FEPI_ADDVEC && ph.emb != nullptr && ph.tok == nullptr;
+    auto reduce_tokens = [&]() {
+        for (int r = 0; r < M; ++r) {
+            float bv = -INFINITY; int bi = 0x7FFFFFFF;
+            for (int w = lane; w < ph.ncand; w += 64) {
+                const float v = ph.pm[(size_t)r * ph.ncand + w]; const int i = ph.pi[(size_t)r * ph.ncand + w];
+                if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            if (blockIdx.x == 0 && threadIdx.x == 0) {
+                if (pp.bad && (unsigned)bi >= (unsigned)pp.V) st_wt(pp.bad, 1);
+                st_wt(&ph.tok_out[(r / pp.m) * ph.o_sseq + (r % pp.m) * ph.o_srow], clamp_token(bi, pp.V));
+            }
+#pragma unroll
+            for (int q = 0; q < QM; ++q) if (row0 + q * RS == r) tokr[q] = bi;
+        }
+    };
+    // tiny models: the first K pass already reads embedding rows, so the tokens come first
+    if (cand_tokens && K / 2 < CW) reduce_tokens();
     HIVIS_MARK(0)
     // The activation rows are requested BEFORE the first weight units: loads return in order, so rows requested
     // after 16 KiB of weights per wavefront could not be staged until those weights had arrived from HBM.
     HIVIS_LOAD_RAW(0)
     // nothing prefetched for this phase (always the case with one launch per phase): request its first two units now
     if (!head_valid) HIVIS_FIRST_UNITS(W, kblks, t_begin, ntl, npass)
+    // (normally here: the loads ride behind the weight units just requested, and the first staging waits for those anyway)
+    if (cand_tokens && K / 2 >= CW) reduce_tokens();
     head_valid = false;
     const bool wb1_first = wb1_valid;       // wb1 already holds the second unit of the phase
     wb1_valid = false;
@@ -397,7 +482,10 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             if (epi == FEPI_ADD_TO) epi_a[sl] = ph.R[(size_t)row * ph.ldr + col];
             else if (epi == FEPI_QKV) {
                 const int p2 = (col % pp.hd) >> 1;
-                epi_a[sl] = ph.rope[((size_t)row * (pp.hd / 2) + p2) * 2]; epi_b[sl] = ph.rope[((size_t)row * (pp.hd / 2) + p2) * 2 + 1];
+                const int seq_ = row / pp.m;
+                const int pos_ = min((ph.att.nbase > 0 ? ph.att.base_val[seq_] : ph.base[seq_]) + ph.offset + row % pp.m, ph.maxL - 1);
+                const float2 cs_ = *reinterpret_cast<const float2*>(ph.rope + ((size_t)pos_ * (pp.hd / 2) + p2) * 2);
+                epi_a[sl] = cs_.x; epi_b[sl] = cs_.y;
             }
         }
         // ---- cross-wave reduction
@@ -469,7 +557,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
                 // every even column handles the pair (col, col+1): a rotary pair of q or k, or two v elements
                 const int qd = pp.Hq * pp.hd, kd = pp.Hkv * pp.hd, hd = pp.hd;
                 const int seq = row / pp.m;
-                const int pos = min(ph.base[seq] + ph.offset + row % pp.m, ph.maxL - 1);
+                const int pos = min((ph.att.nbase > 0 ? ph.att.base_val[seq] : ph.base[seq]) + ph.offset + row % pp.m, ph.maxL - 1);
                 if ((cl & 1) == 0) {
                     const float x1 = v, x2 = tile[idx + RPL] * sc;
                     if (col < qd + kd) {
@@ -517,6 +605,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             }
             if (lane == 0 && row < M) { st_wt(&ph.pm[(size_t)row * gridDim.x + blockIdx.x], bv); st_wt(&ph.pi[(size_t)row * gridDim.x + blockIdx.x], bi); }
         }
+        if (ph.cnt) lm_head_elect(ph, pp, reinterpret_cast<int*>(inv_rms));
     }
     // The stores of this phase must be acknowledged before the workgroup arrives at the grid barrier, and the
     // only wait available (vmcnt) also covers loads: so first drain, THEN request the first two units of the next
@@ -1113,7 +1202,7 @@ __device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp,
         }
         break;
     case PH_PREP: {
-        // embedding gather of the rows' tokens (optional) and the rotary cos/sin table of the rows' positions
+        // embedding gather of the rows' tokens
         if (ph.ids) {
             for (int row = blockIdx.x; row < pp.M; row += gridDim.x) {
                 // token ids may have been written earlier in this launch: agent-scope load; clamped for safety
@@ -1122,15 +1211,6 @@ __device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp,
                 const WT* src = (const WT*)ph.gain + (size_t)tok * pp.d;
                 for (int c = threadIdx.x; c < pp.d; c += FUSED_NT) st_wt(&ph.Y[(size_t)row * ph.ldy + c], to_f32(src[c]));
             }
-        }
-        const int half = pp.hd / 2;
-        for (int idx = blockIdx.x * FUSED_NT + threadIdx.x; idx < pp.M * half; idx += gridDim.x * FUSED_NT) {
-            const int row = idx / half, i = idx % half;
-            const int pos = ph.base[row / pp.m] + ph.offset + row % pp.m;
-            const double inv_freq = exp2(-2.0 * (double)i / (double)pp.hd * log2((double)pp.theta));
-            double s, c;
-            sincos((double)pos * inv_freq, &s, &c);
-            st_wt(&ph.rope[(size_t)idx * 2], (float)c); st_wt(&ph.rope[(size_t)idx * 2 + 1], (float)s);
         }
     } break;
     case PH_NORM_ROWS:

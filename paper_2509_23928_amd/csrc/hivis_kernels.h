@@ -935,6 +935,19 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
     attn_item_merge<HD, ATT_RMAX>(ws, base, sh, blockIdx.x, 256, out, ldo);
 }
 
+// Rotary table of a context: tab[pos][i] = (cos, sin)(pos * theta^(-2i/hd)), i < hd/2, angle evaluated in double (so that
+// large positions keep full fp32 accuracy).  Written once at create; the QKV epilogue of the phase programs reads it.
+__global__ void rope_table_kernel(float* __restrict__ tab, int npos, int hd, float theta) {
+    const int half = hd / 2;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < (size_t)npos * half; idx += (size_t)gridDim.x * blockDim.x) {
+        const int pos = (int)(idx / half), i = (int)(idx % half);
+        const double inv_freq = exp2(-2.0 * (double)i / (double)hd * log2((double)theta));
+        double s, c;
+        sincos((double)pos * inv_freq, &s, &c);
+        tab[idx * 2] = (float)c; tab[idx * 2 + 1] = (float)s;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // Calibration: a plain read-only stream over a buffer, the access pattern of the weight-streaming GEMMs without any
 // of their work (one wavefront reads 1 KiB per instruction, 8 independent 16-byte loads per lane and trip, a workgroup

@@ -15,7 +15,9 @@ text positions are the fused features f_fused.  The paper does not spell out the
 decoder block; this oracle uses the block of the model families it evaluates
 (section 4, "Models and Tasks": LLaVA-1.5 / LLaVA-NeXT / Qwen2.5-VL, i.e.
 LLaMA-style pre-norm blocks): RMSNorm, rotary position embedding with rotate-half
-pairing, grouped-query softmax attention, SwiGLU MLP, no biases.
+pairing, grouped-query softmax attention, SwiGLU MLP; no biases, except the q/k/v
+projection biases of the Qwen2.5 language model, which a layer's weight dict may carry
+as bq, bk, bv (added to the projections before the rotation).
 
 Orientation: y = x W with W stored [in][out] (the paper's row-vector notation,
 e.g. "f_fused w_1"), except embed and lm_head, which are [vocab][d].
@@ -117,13 +119,20 @@ def decoder_layer(h, w, cache, pos, cfg, visible=None):
     """One pre-norm decoder block on the rows h [m][d] at positions pos [m]; the rows'
     keys/values are appended to `cache`, and every row attends to all cached entries at
     positions <= its own (or, if `visible` [m][len(cache) + m] is given, to exactly the
-    entries it marks).  w: dict with norm1, wq, wk, wv, wo, norm2, wg, wu, wd."""
+    entries it marks).  w: dict with norm1, wq, wk, wv, wo, norm2, wg, wu, wd and optionally bq, bk, bv."""
     h = np.asarray(h, F64)
     m = h.shape[0]
     a = rmsnorm(h, w["norm1"], cfg.rms_eps)
-    q = (a @ np.asarray(w["wq"], F64)).reshape(m, cfg.n_q_heads, cfg.head_dim)
-    k = (a @ np.asarray(w["wk"], F64)).reshape(m, cfg.n_kv_heads, cfg.head_dim)
-    v = (a @ np.asarray(w["wv"], F64)).reshape(m, cfg.n_kv_heads, cfg.head_dim)
+    q = a @ np.asarray(w["wq"], F64)
+    k = a @ np.asarray(w["wk"], F64)
+    v = a @ np.asarray(w["wv"], F64)
+    if "bq" in w:            # q/k/v projection biases (the Qwen2.5 language model has them), added before the rotation
+        q = q + np.asarray(w["bq"], F64)
+        k = k + np.asarray(w["bk"], F64)
+        v = v + np.asarray(w["bv"], F64)
+    q = q.reshape(m, cfg.n_q_heads, cfg.head_dim)
+    k = k.reshape(m, cfg.n_kv_heads, cfg.head_dim)
+    v = v.reshape(m, cfg.n_kv_heads, cfg.head_dim)
     q = rope(q, pos, cfg.rope_theta)
     k = rope(k, pos, cfg.rope_theta)
     cache.append(k, v, pos)

@@ -27,6 +27,7 @@ class HivisConfig:
     rope_theta: float = 10000.0
     rms_eps: float = 1e-5
     n_resid: int = 4       # r^0..r^3 (section 4, training setup); r^3 reused afterwards
+    qkv_bias: bool = False # the attention's q/k/v projections carry bias vectors (the Qwen2.5 language model does)
 
     @property
     def q_dim(self):

@@ -8,7 +8,8 @@ bf16 and a consumer reading them as float32 see the same numbers.
 
 Recipe: matrices N(0, 0.02); norm gains 1 + 0.1*N(0,1) (so that a forgotten
 gain shows); residual vectors rho_i N(0, 0.02); visual embeddings N(0, 1);
-text ids uniform in [0, vocab).
+text ids uniform in [0, vocab); for configs with qkv_bias, bias vectors bq, bk, bv
+N(0, 0.5) per layer (large enough that a dropped or misplaced bias shows).
 
 Matrix orientation is the paper's row-vector convention y = x W, i.e. W is
 [in][out], except the embedding table and LM head, which are [vocab][d].
@@ -76,12 +77,16 @@ def _tensor_specs(cfg):
             is_norm = name.startswith("norm")
             specs.append((path + (name,), f"{prefix}.{name}", shape, 0.1 if is_norm else 0.02,
                           1.0 if is_norm else 0.0))
+        if getattr(cfg, "qkv_bias", False):
+            for name, n in (("bq", cfg.q_dim), ("bk", cfg.kv_dim), ("bv", cfg.kv_dim)):
+                specs.append((path + (name,), f"{prefix}.{name}", (n,), 0.5, 0.0))
     return specs
 
 
 def make_weights(cfg, seed=0, bits=False, threads=1):
     """dict: embed [V][d], lm_head [V][d], final_norm [d], layers [N]{...},
     draft_layer {...}, fuse_w [2d][d] (= [w1; w2]), resid_rho [n_resid][d].
+    With cfg.qkv_bias every layer dict also holds bq [q_dim], bk [kv_dim], bv [kv_dim].
     bits=True (bf16 configs only): uint16 bf16 bit patterns instead of float32."""
     w = {"layers": [dict() for _ in range(cfg.n_layers)], "draft_layer": {}}
 

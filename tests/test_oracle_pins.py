@@ -168,6 +168,47 @@ def test_target_forward_matches_transformers_llama(heads):
     assert np.abs(ref).max() > 0.3
 
 
+def test_target_forward_with_qkv_bias_matches_transformers_qwen2():
+    """The q/k/v bias term (Qwen2.5 language model) against the transformers Qwen2 model: GQA 6/2, biases of order 1."""
+    from transformers import Qwen2Config, Qwen2ForCausalLM
+    cfg = tiny_cfg(n_q_heads=6, n_kv_heads=2, d=48, rope_theta=1.0e6, rms_eps=1e-6, qkv_bias=True)
+    w = synth.make_weights(cfg, seed=4)
+    for lw in w["layers"]:
+        assert lw["bq"].shape == (cfg.q_dim,) and lw["bk"].shape == (cfg.kv_dim,) and np.abs(lw["bv"]).max() > 0.3
+        for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+            lw[k] = lw[k] * 8.0
+    vis, ids = synth.make_prompt(cfg, seed=4)
+    tgt = Target(cfg, w)
+    x = np.concatenate([vis[0].astype(np.float64), tgt.embed(ids[0])], axis=0)
+    logits = tgt.logits(tgt.forward(x, 0))
+    hc = Qwen2Config(vocab_size=cfg.vocab, hidden_size=cfg.d, intermediate_size=cfg.ffn, num_hidden_layers=cfg.n_layers,
+                     num_attention_heads=cfg.n_q_heads, num_key_value_heads=cfg.n_kv_heads, rms_norm_eps=cfg.rms_eps,
+                     rope_theta=cfg.rope_theta, tie_word_embeddings=False, max_position_embeddings=512, use_sliding_window=False,
+                     attn_implementation="eager")
+    assert hc.hidden_size // hc.num_attention_heads == cfg.head_dim
+    m = Qwen2ForCausalLM(hc).double().eval()
+    sd = {"model.embed_tokens.weight": w["embed"], "lm_head.weight": w["lm_head"], "model.norm.weight": w["final_norm"]}
+    names = {"wq": "self_attn.q_proj", "wk": "self_attn.k_proj", "wv": "self_attn.v_proj", "wo": "self_attn.o_proj",
+             "wg": "mlp.gate_proj", "wu": "mlp.up_proj", "wd": "mlp.down_proj"}
+    for i, lw in enumerate(w["layers"]):
+        for k, hfk in names.items():
+            sd[f"model.layers.{i}.{hfk}.weight"] = lw[k].T
+        for k, hfk in (("bq", "q_proj"), ("bk", "k_proj"), ("bv", "v_proj")):
+            sd[f"model.layers.{i}.self_attn.{hfk}.bias"] = lw[k]
+        sd[f"model.layers.{i}.input_layernorm.weight"] = lw["norm1"]
+        sd[f"model.layers.{i}.post_attention_layernorm.weight"] = lw["norm2"]
+    missing = m.load_state_dict({k: torch.tensor(np.ascontiguousarray(v), dtype=torch.float64) for k, v in sd.items()}, strict=False)
+    assert not [k for k in missing.missing_keys if "rotary" not in k] and not missing.unexpected_keys
+    with torch.no_grad():
+        ref = m(inputs_embeds=torch.tensor(x)[None]).logits[0].numpy()
+    np.testing.assert_allclose(logits, ref, rtol=1e-5, atol=2e-6)
+    # and the term matters: the same weights without the biases give different logits
+    w0 = {k: v for k, v in w.items()}
+    w0["layers"] = [{k: v for k, v in lw.items() if k not in ("bq", "bk", "bv")} for lw in w["layers"]]
+    t0 = Target(cfg, w0)
+    assert np.abs(t0.logits(t0.forward(x, 0)) - logits).max() > 1e-2
+
+
 # ---------------------------------------------------------------- method invariants
 @pytest.fixture(scope="module")
 def tiny():

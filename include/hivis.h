@@ -69,9 +69,12 @@ typedef struct {
 
 /* Weights of one decoder layer, all host pointers of the context's dtype:
  * norm1 [d], wq [d][Hq*hd], wk [d][Hkv*hd], wv [d][Hkv*hd], wo [Hq*hd][d],
- * norm2 [d], wg [d][ffn], wu [d][ffn], wd [ffn][d].  No biases. */
+ * norm2 [d], wg [d][ffn], wu [d][ffn], wd [ffn][d].
+ * bq [Hq*hd], bk [Hkv*hd], bv [Hkv*hd]: optional bias vectors of the q/k/v projections (the Qwen2.5 language model of
+ * section 4's Qwen2.5-VL has them), added before the rotation; all three NULL (no biases) or all three given. */
 typedef struct {
     const void *norm1, *wq, *wk, *wv, *wo, *norm2, *wg, *wu, *wd;
+    const void *bq, *bk, *bv;
 } hivis_layer_weights;
 
 typedef struct {

@@ -14,6 +14,7 @@ HIVIS_OK, HIVIS_EINVAL, HIVIS_ESTATE, HIVIS_ECAP, HIVIS_EHIP = 0, -1, -2, -3, -4
 HIVIS_F32, HIVIS_BF16 = 0, 1
 
 LAYER_FIELDS = ("norm1", "wq", "wk", "wv", "wo", "norm2", "wg", "wu", "wd")
+LAYER_OPTIONAL = ("bq", "bk", "bv")          # q/k/v projection biases: all three or none
 
 
 class HivisError(RuntimeError):
@@ -30,7 +31,7 @@ class hivis_config(C.Structure):
 
 
 class hivis_layer_weights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS]
+    _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS + LAYER_OPTIONAL]
 
 
 class hivis_weights(C.Structure):
@@ -152,7 +153,7 @@ class Hivis:
             return C.c_void_p(h.ctypes.data)
 
         def layer(lw):
-            return hivis_layer_weights(*[hw(lw[n]) for n in LAYER_FIELDS])
+            return hivis_layer_weights(*([hw(lw[n]) for n in LAYER_FIELDS] + [hw(lw[n]) if n in lw else None for n in LAYER_OPTIONAL]))
 
         layers = (hivis_layer_weights * cfg.n_layers)(*[layer(lw) for lw in weights["layers"]])
         w = hivis_weights(hw(weights["embed"]), hw(weights["lm_head"]), hw(weights["final_norm"]), layers,

@@ -2,7 +2,7 @@
 
 Target: the tensor naming of the Hugging Face LLaMA family, which the language models of the paper's targets use
 (section 4, "Models and Tasks": LLaVA-1.5 / LLaVA-NeXT; Qwen2.5-VL's language model has the same names plus q/k/v
-biases, which this library does not implement and this loader refuses unless they are all zero).  The prefix in front
+biases, which are loaded as bq / bk / bv when any of them is non-zero; an o_proj bias is refused).  The prefix in front
 of `embed_tokens` / `layers.N` / `norm` is detected (`model.`, `language_model.model.`, `model.language_model.` ...).
 Linear weights are stored [out][in] there and [in][out] here, so they are transposed.
 
@@ -53,10 +53,16 @@ def _layer(tensors, prefix):
         if key not in tensors:
             raise KeyError(f"missing tensor {key}")
         lw[ours] = _to_numpy(tensors[key], transpose=not ours.startswith("norm"))
-    for proj in ("q_proj", "k_proj", "v_proj", "o_proj"):
-        b = tensors.get(prefix + f"self_attn.{proj}.bias")
-        if b is not None and bool((b != 0).any()):
-            raise ValueError(f"{prefix}self_attn.{proj}.bias is non-zero: attention biases are not implemented")
+    biases = {ours: tensors.get(prefix + f"self_attn.{proj}.bias") for ours, proj in (("bq", "q_proj"), ("bk", "k_proj"), ("bv", "v_proj"))}
+    if any(b is not None and bool((b != 0).any()) for b in biases.values()):
+        # q/k/v projection biases (Qwen2.5 language model): all three are handed over, a missing one as zeros
+        import torch
+        for ours, b in biases.items():
+            n = lw["wq" if ours == "bq" else "wk"].shape[1]
+            lw[ours] = _to_numpy(b if b is not None else torch.zeros(n, dtype=tensors[prefix + _LAYER["wq"]].dtype))
+    b = tensors.get(prefix + "self_attn.o_proj.bias")
+    if b is not None and bool((b != 0).any()):
+        raise ValueError(f"{prefix}self_attn.o_proj.bias is non-zero: an output-projection bias is not implemented")
     return lw
 
 

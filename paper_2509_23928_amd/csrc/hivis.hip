@@ -41,6 +41,7 @@ struct LayerDev {
     uint4* wo = nullptr;                            // packed [q_dim] -> [d]
     uint4* wgu = nullptr;                           // packed [d] -> [2 ffn]  (gate | up)
     uint4* wd = nullptr;                            // packed [ffn] -> [d]
+    float* bqkv = nullptr;                          // optional q/k/v projection biases [q_dim + 2 kv_dim], in wqkv's column order
 };
 
 struct KVDev { void* k = nullptr; void* v = nullptr; int maxL = 0; };   // [B][Hkv][maxL][hd]
@@ -217,6 +218,28 @@ int upload_layer(hivis_ctx* c, const hivis_layer_weights& w, void* staging, Laye
       if (int rc = pack_matrix<WT>(c, s, n, 2, g.d, 0, staging, &L.wgu, PACK_GATEUP)) return rc; }
     { const void* s[1] = {w.wd}; int n[1] = {g.d};
       if (int rc = pack_matrix<WT>(c, s, n, 1, g.ffn, 0, staging, &L.wd)) return rc; }
+    if (w.bq || w.bk || w.bv) {
+        if (!w.bq || !w.bk || !w.bv) return fail(c, HIVIS_EINVAL, "q/k/v biases: give all three or none");
+        // the fused qkv columns: [q heads | k heads | v heads], inside every q and k head the rotary pair (i, i + hd/2)
+        // in adjacent columns (2i, 2i+1): the biases follow their columns
+        const int hd = g.head_dim, half = hd / 2;
+        std::vector<float> b((size_t)qd + 2 * kd);
+        auto val = [](const void* p, size_t i) -> float {
+            if (sizeof(WT) == 2) { const uint32_t u = (uint32_t)((const uint16_t*)p)[i] << 16; float f; memcpy(&f, &u, 4); return f; }
+            return ((const float*)p)[i];
+        };
+        for (int part = 0; part < 2; ++part) {
+            const void* src = part == 0 ? w.bq : w.bk;
+            const int n = part == 0 ? qd : kd, off = part == 0 ? 0 : qd;
+            for (int col = 0; col < n; ++col) {
+                const int h = col / hd, pc = col % hd;
+                b[(size_t)off + col] = val(src, (size_t)h * hd + ((pc & 1) ? pc / 2 + half : pc / 2));
+            }
+        }
+        for (int col = 0; col < kd; ++col) b[(size_t)qd + kd + col] = val(w.bv, col);
+        if (int rc = dev_alloc(c, &L.bqkv, b.size())) return rc;
+        HIP_TRY(c, hipMemcpy(L.bqkv, b.data(), b.size() * sizeof(float), hipMemcpyHostToDevice));
+    }
     return HIVIS_OK;
 }
 
@@ -365,7 +388,7 @@ int layer_forward(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, co
     const int nqkv = qd + 2 * kd;
     hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, pending, d, (const WT*)L.norm1, c->a, d, d, g.rms_eps);
     if (int rc = gemm<WT>(c, c->a, d, M, d, L.wqkv, nqkv, c->qkv, nqkv, EPI_STORE)) return rc;
-    hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta);
+    hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta, (const float*)L.bqkv);
     if (c->fused && std::is_same<KT, f16_t>::value) { if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd, tr.mask)) return rc; }
     else if (int rc = attention<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, max_keys, c->att, qd, tr.mask)) return rc;
     if (int rc = gemm<WT>(c, c->att, qd, M, qd, L.wo, d, c->proj, d, EPI_STORE)) return rc;
@@ -483,7 +506,7 @@ float* layer_phases(hivis_ctx* c, std::vector<Phase>& P, Pool& pool, const Layer
     float* h2 = dst ? dst : pool.take((size_t)M * d);
     const int ld2 = dst ? ldd : d;
     Phase q{}; q.type = PH_GEMM; q.pro = PRO_RMS; q.epi = FEPI_QKV; q.K = d; q.N = nqkv; q.W = L.wqkv; q.A = h; q.lda = d;
-    q.gain = L.norm1; q.Y = qkv; q.ldy = nqkv; q.kc = kv.k; q.vc = kv.v; q.maxL = kv.maxL; q.base = base; q.offset = offset; q.rope = c->rope_tab;
+    q.gain = L.norm1; q.Y = qkv; q.ldy = nqkv; q.kc = kv.k; q.vc = kv.v; q.maxL = kv.maxL; q.base = base; q.offset = offset; q.rope = c->rope_tab; q.bias = L.bqkv;
     P.push_back(q);
     Phase a{}; a.type = PH_ATTN; a.A = qkv; a.lda = nqkv; a.kc = kv.k; a.vc = kv.v; a.maxL = kv.maxL; a.base = base; a.offset = offset;
     a.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, nqkv, &a.att_items);
@@ -922,7 +945,7 @@ int layer_forward_wide(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* 
     hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, h, d, pending, d, M, (const WT*)L.norm1, c->pf_frag, d, g.rms_eps);
     if (int rc = wide_gemm(c, nullptr, 0, M, d, L.wqkv, nqkv, c->qkv, nqkv, &pq)) return rc;
     hipLaunchKernelGGL((wide_rope_append_kernel<KT>), dim3(M, 8), dim3(256), 0, c->stream, pq, c->qkv, nqkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m,
-                       (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta);
+                       (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta, (const float*)L.bqkv);
     if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd, tr.mask)) return rc;
     if (int rc = wide_gemm(c, c->att, qd, M, qd, L.wo, d, c->proj, d, &po)) return rc;
     hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, h, d, po, d, M, (const WT*)L.norm2, c->pf_frag, d, g.rms_eps);
@@ -946,7 +969,7 @@ int prefill_target_tall(hivis_ctx* c, int b, int v, int l) {
         const KVDev& kv = c->tkv[l_];
         hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, pending, d, (const WT*)L.norm1, c->pf_a, d, d, g.rms_eps);
         if (int rc = tall_gemm(c, c->pf_a, d, M, d, L.wqkv, nqkv, c->pf_qkv, nqkv)) return rc;
-        hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->pf_qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, (const int*)c->zeros, 0, b, M, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta);
+        hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->pf_qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, (const int*)c->zeros, 0, b, M, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, (const int*)nullptr, (const float*)L.bqkv);
         if (c->fused) { if (int rc = attention_rows_mfma<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, c->pf_att, qd)) return rc; }
         else if (int rc = attention<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, M, c->pf_att, qd)) return rc;
         if (int rc = tall_gemm(c, c->pf_att, qd, M, qd, L.wo, d, c->pf_proj, d)) return rc;

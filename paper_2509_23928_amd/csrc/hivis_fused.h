@@ -48,6 +48,7 @@ struct Phase {
     int32_t* tok_out; int o_sseq, o_srow;          // ARGMAX: destination of the greedy token of row (seq, i)
     AttnShape att; int att_items;                  // ATTN / ATTN_MERGE
     const float* rope;                             // QKV epilogue: rotary table of the context, [position][hd/2][2] cos, sin
+    const float* bias;                             // QKV epilogue: optional q/k/v projection biases [N] in packed column order
     float* ws;                                     // ATTN: per-workgroup partials of the key splits
     int* cnt;                                      // ATTN: arrival counter per item; LM head: one arrival counter (zero between launches)
     float* pm; int* pi;                            // LOGITS writes, ARGMAX reads: greedy candidates [row][workgroup]
@@ -559,7 +560,8 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
                 const int seq = row / pp.m;
                 const int pos = min((ph.att.nbase > 0 ? ph.att.base_val[seq] : ph.base[seq]) + ph.offset + row % pp.m, ph.maxL - 1);
                 if ((cl & 1) == 0) {
-                    const float x1 = v, x2 = tile[idx + RPL] * sc;
+                    float x1 = v, x2 = tile[idx + RPL] * sc;
+                    if (ph.bias) { x1 += ph.bias[col]; x2 += ph.bias[col + 1]; }
                     if (col < qd + kd) {
                         const float c = epi_a[sl], s = epi_b[sl];
                         const float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;

@@ -677,10 +677,11 @@ __global__ void silu_mul_kernel(const float* __restrict__ gu, float* __restrict_
 // The angle is evaluated in double so that large positions keep full fp32 accuracy.
 // pos_delta (optional, rows of a draft tree): the rotary position of row r is base[seq] + pos_delta[r] instead, its
 // cache slot stays base[seq] + offset + r % m.
+// bias (optional): q/k/v projection biases in the column order of the fused qkv rows, added before the rotation.
 template <typename ST>
 __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int HD, const int* __restrict__ base,
                                    int offset, int seq0, int m, ST* __restrict__ kc, ST* __restrict__ vc, int maxL,
-                                   float theta, const int* __restrict__ pos_delta = nullptr) {
+                                   float theta, const int* __restrict__ pos_delta = nullptr, const float* __restrict__ bias = nullptr) {
     const int row = blockIdx.x;
     const int seq = seq0 + row / m;
     const int slot = base[seq] + offset + row % m;
@@ -694,7 +695,8 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int
         double s, c;
         sincos((double)pos * inv_freq, &s, &c);
         float* x = r + (size_t)head * HD;          // the pair (i, i + hd/2) sits in columns 2i, 2i+1 (PACK_QKV order)
-        const float x1 = x[2 * i], x2 = x[2 * i + 1];
+        const float b1 = bias ? bias[(size_t)head * HD + 2 * i] : 0.f, b2 = bias ? bias[(size_t)head * HD + 2 * i + 1] : 0.f;
+        const float x1 = x[2 * i] + b1, x2 = x[2 * i + 1] + b2;
         const float y1 = (float)((double)x1 * c - (double)x2 * s);
         const float y2 = (float)((double)x2 * c + (double)x1 * s);
         if (head < Hq) {
@@ -707,7 +709,7 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int
     const float* v = r + (size_t)(Hq + Hkv) * HD;
     for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < Hkv * HD; idx += gridDim.y * blockDim.x) {
         const int head = idx / HD, c = idx % HD;
-        kv_put(vc + (((size_t)seq * Hkv + head) * maxL + slot) * HD * KVWidth<ST>::W, HD, c, v[idx]);
+        kv_put(vc + (((size_t)seq * Hkv + head) * maxL + slot) * HD * KVWidth<ST>::W, HD, c, v[idx] + (bias ? bias[(size_t)(Hq + Hkv) * HD + idx] : 0.f));
     }
 }
 

@@ -400,11 +400,12 @@ __global__ void wide_silu_frag_kernel(Parts gu, int M, int F, uint4* __restrict_
 }
 
 // rope_append_kernel for rows whose fused QKV result arrives as partials: sums them, rotates q and k, writes q to `q_out`
-// (row stride ldq, the buffer the attention reads) and k, v to the cache.  Same position / slot rule as rope_append_kernel.
+// (row stride ldq, the buffer the attention reads) and k, v to the cache.  Same position / slot rule and optional bias as
+// rope_append_kernel.
 template <typename ST>
 __global__ void wide_rope_append_kernel(Parts qkv, float* __restrict__ q_out, int ldq, int Hq, int Hkv, int HD, const int* __restrict__ base,
                                         int offset, int seq0, int m, ST* __restrict__ kc, ST* __restrict__ vc, int maxL,
-                                        float theta, const int* __restrict__ pos_delta) {
+                                        float theta, const int* __restrict__ pos_delta, const float* __restrict__ bias) {
     const int row = blockIdx.x;
     const int seq = seq0 + row / m;
     const int slot = base[seq] + offset + row % m;
@@ -414,7 +415,8 @@ __global__ void wide_rope_append_kernel(Parts qkv, float* __restrict__ q_out, in
     const int npair2 = (Hq + Hkv) * half / 2;                 // two pairs (4 adjacent columns) per trip
     for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < npair2; idx += gridDim.y * blockDim.x) {
         const int head = (2 * idx) / half, i = (2 * idx) % half;
-        const float4 x = parts_load4(qkv, rbase + (size_t)head * HD + 2 * i);      // pairs (i, i + hd/2) sit in columns 2i, 2i+1
+        float4 x = parts_load4(qkv, rbase + (size_t)head * HD + 2 * i);            // pairs (i, i + hd/2) sit in columns 2i, 2i+1
+        if (bias) { const float4 b = *reinterpret_cast<const float4*>(bias + (size_t)head * HD + 2 * i); x.x += b.x; x.y += b.y; x.z += b.z; x.w += b.w; }
         float y[4];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -435,7 +437,8 @@ __global__ void wide_rope_append_kernel(Parts qkv, float* __restrict__ q_out, in
     }
     for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < Hkv * HD / 4; idx += gridDim.y * blockDim.x) {
         const int head = (4 * idx) / HD, c = (4 * idx) % HD;
-        const float4 v = parts_load4(qkv, rbase + (size_t)(Hq + Hkv) * HD + 4 * idx);
+        float4 v = parts_load4(qkv, rbase + (size_t)(Hq + Hkv) * HD + 4 * idx);
+        if (bias) { const float4 b = *reinterpret_cast<const float4*>(bias + (size_t)(Hq + Hkv) * HD + 4 * idx); v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w; }
         ST* dst = vc + (((size_t)seq * Hkv + head) * maxL + slot) * HD * KVWidth<ST>::W;
         kv_put(dst, HD, c, v.x); kv_put(dst, HD, c + 1, v.y); kv_put(dst, HD, c + 2, v.z); kv_put(dst, HD, c + 3, v.w);
     }

@@ -97,8 +97,46 @@ def test_tied_embeddings_and_bias_handling(tmp_path):
     checkpoint.load_target(paths)                             # all-zero biases are accepted
     d3 = tmp_path / "bias"; d3.mkdir()
     _, paths = write_target(d3, cfg, w, bias=0.5)
+    got, _ = checkpoint.load_target(paths)                    # a non-zero q bias: all three come back, k and v as zeros
+    np.testing.assert_array_equal(got["layers"][0]["bq"], np.full(cfg.q_dim, 0.5, np.float32))
+    assert not got["layers"][0]["bk"].any() and got["layers"][0]["bv"].shape == (cfg.kv_dim,)
+    assert "bq" not in got["layers"][1]
+    d4 = tmp_path / "obias"; d4.mkdir()
+    from safetensors.torch import save_file
+    _, paths = write_target(d4, cfg, w)
+    extra = str(d4 / "extra.safetensors")
+    save_file({"model.layers.0.self_attn.o_proj.bias": torch.full((cfg.d,), 0.25)}, extra)
     with pytest.raises(ValueError):
-        checkpoint.load_target(paths)
+        checkpoint.load_target(paths + [extra])
+
+
+def test_residual_fold_matches_oracle_fuse():
+    """The loader folds rho_i = r^i w on the host (the one product of the method outside the library).  Pin: the oracle's
+    fusion f w1 + e w2 + rho with the folded vector equals the unfolded form written out, (f w1 + e w2) + r^i w, in float64."""
+    from oracle import fuse
+    rng = np.random.default_rng(5)
+    d, m, n_resid = 24, 7, 4
+    r = rng.standard_normal((n_resid, m)).astype(np.float32)
+    wmat = rng.standard_normal((m, d)).astype(np.float32)
+    f = rng.standard_normal((3, d)); e = rng.standard_normal((3, d)); fw = rng.standard_normal((2 * d, d))
+    import tempfile
+    from safetensors.torch import save_file
+    cfg = tiny_cfg(d=d, n_q_heads=3, n_kv_heads=3, head_dim=8)
+    w = synth.make_weights(cfg, seed=1)
+    with tempfile.TemporaryDirectory() as td:
+        import pathlib
+        path = write_drafter(pathlib.Path(td), cfg, w)
+        from safetensors.torch import load_file
+        sd = load_file(path)
+        del sd["residual.rho"]
+        sd["residual.r"] = torch.tensor(r); sd["residual.w"] = torch.tensor(wmat)
+        save_file(sd, path)
+        got = checkpoint.load_drafter(path)
+    rho = got["resid_rho"]
+    assert rho.shape == (n_resid, d)
+    for i in range(n_resid):
+        unfolded = (f @ fw[:d] + e @ fw[d:]) + r[i].astype(np.float64) @ wmat.astype(np.float64)
+        np.testing.assert_allclose(fuse(f, e, fw, rho[i]), unfolded, rtol=0, atol=2e-5)       # the fold itself is a float32 product
 
 
 def test_config_fields(tmp_path):
@@ -150,3 +188,65 @@ def test_library_from_checkpoint_matches_transformers(tmp_path):
                 assert top[-1] - lg[tok] <= 2e-4, f"token {tok} is not the transformers model's greedy token (gap {top[-1] - lg[tok]})"
                 break                                 # a near-tie: the two texts may legitimately part here
             seq.append(tok)
+
+
+@pytest.mark.gpu
+def test_library_from_qwen2_checkpoint_with_qkv_biases(tmp_path):
+    """A checkpoint written by the transformers Qwen2 model (q/k/v biases of order 1, GQA) loaded and prefilled by the HIP
+    library, against that model's own logits; then chain cycles must emit its greedy text."""
+    from safetensors.torch import save_file
+    from transformers import Qwen2Config, Qwen2ForCausalLM
+    from paper_2509_23928_amd import Hivis
+    cfg = synth.get_config("C1").scaled(n_q_heads=4, n_kv_heads=2, n_vis=20, n_text=15, rope_theta=1.0e6, rms_eps=1e-6, qkv_bias=True)
+    w = synth.make_weights(cfg, seed=10)
+    vis, ids = synth.make_prompt(cfg, seed=10)
+    hc = Qwen2Config(vocab_size=cfg.vocab, hidden_size=cfg.d, intermediate_size=cfg.ffn, num_hidden_layers=cfg.n_layers,
+                     num_attention_heads=cfg.n_q_heads, num_key_value_heads=cfg.n_kv_heads, rms_norm_eps=cfg.rms_eps,
+                     rope_theta=cfg.rope_theta, tie_word_embeddings=False, max_position_embeddings=512, use_sliding_window=False,
+                     attn_implementation="eager")
+    m = Qwen2ForCausalLM(hc).double().eval()
+    sd = {"model.embed_tokens.weight": w["embed"], "lm_head.weight": w["lm_head"], "model.norm.weight": w["final_norm"]}
+    names = {"wq": "self_attn.q_proj", "wk": "self_attn.k_proj", "wv": "self_attn.v_proj", "wo": "self_attn.o_proj",
+             "wg": "mlp.gate_proj", "wu": "mlp.up_proj", "wd": "mlp.down_proj"}
+    for i, lw in enumerate(w["layers"]):
+        for k, hfk in names.items():
+            sd[f"model.layers.{i}.{hfk}.weight"] = lw[k].T
+        for k, hfk in (("bq", "q_proj"), ("bk", "k_proj"), ("bv", "v_proj")):
+            sd[f"model.layers.{i}.self_attn.{hfk}.bias"] = lw[k]
+        sd[f"model.layers.{i}.input_layernorm.weight"] = lw["norm1"]
+        sd[f"model.layers.{i}.post_attention_layernorm.weight"] = lw["norm2"]
+    m.load_state_dict({k: torch.tensor(np.ascontiguousarray(v), dtype=torch.float64) for k, v in sd.items()}, strict=False)
+    tpath = str(tmp_path / "qwen.safetensors")
+    save_file({k: v.to(torch.float32).contiguous() for k, v in m.state_dict().items() if "rotary" not in k}, tpath)
+    # drafter file: its layer carries biases too
+    dpath = write_drafter(tmp_path, cfg, w)
+    from safetensors.torch import load_file
+    dsd = load_file(dpath)
+    for k, hfk in (("bq", "q_proj"), ("bk", "k_proj"), ("bv", "v_proj")):
+        dsd[f"layers.0.self_attn.{hfk}.bias"] = torch.tensor(w["draft_layer"][k])
+    save_file(dsd, dpath)
+    got, n_layers = checkpoint.load_weights([tpath], dpath)
+    np.testing.assert_array_equal(got["layers"][1]["bk"], w["layers"][1]["bk"])
+    np.testing.assert_array_equal(got["draft_layer"]["bv"], w["draft_layer"]["bv"])
+    hv = Hivis(cfg.scaled(n_layers=n_layers), got)
+    first = hv.prefill(vis, ids)
+    logits = hv.get_logits(2)[0]
+    x = torch.cat([torch.tensor(vis[0], dtype=torch.float64), m.get_input_embeddings()(torch.tensor(ids[0].astype(np.int64)))], dim=0)
+    with torch.no_grad():
+        ref = m(inputs_embeds=x[None]).logits[0, -1].numpy()
+    assert float(np.max(np.abs(logits - ref))) <= 1e-4
+    assert int(first[0]) == int(np.argmax(ref))
+    out = [int(first[0])]
+    for cyc in range(3):
+        hv.draft(cfg.K); hv.verify(); n, toks = hv.accept()
+        out += [int(t) for t in toks[0][: int(n[0]) + 1]]
+    seq = [int(t) for t in ids[0]]
+    with torch.no_grad():
+        for tok in out:
+            xs = torch.cat([torch.tensor(vis[0], dtype=torch.float64), m.get_input_embeddings()(torch.tensor(seq, dtype=torch.int64))], dim=0)
+            lg = m(inputs_embeds=xs[None]).logits[0, -1].numpy()
+            if int(np.argmax(lg)) != tok:
+                assert np.max(lg) - lg[tok] <= 2e-4, f"token {tok} is not the transformers model's greedy token"
+                break
+            seq.append(tok)
+    hv.close()

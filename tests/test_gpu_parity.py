@@ -339,3 +339,49 @@ def test_two_live_contexts_with_different_head_sizes():
     ha.tree_draft(4, 3, 20); ha.tree_verify(); ha.tree_accept()
     hb.tree_draft(4, 3, 20); hb.tree_verify(); hb.tree_accept()
     print("two live contexts max error / tolerance:", sa.max_err, sb.max_err)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_qkv_biases_gqa7(dtype):
+    """q/k/v projection biases (Qwen2.5 language model): 7 query heads per kv head, biases of order 0.5 in every target
+    layer and in the drafter's layer; prefill, own-draft cycles, a planted cycle, and a draft-tree cycle (the bias is
+    added in four different kernels: the fused QKV epilogue, the prefill's and the stand-alone RoPE kernels, and the
+    wide-pass RoPE kernel)."""
+    if dtype == "bf16":
+        cfg = small_bf16(name="bias-bf16", n_q_heads=7, n_kv_heads=1, d=896, ffn=2368, K=4, n_vis=120, n_text=40, rope_theta=1e6, rms_eps=1e-6,
+                         qkv_bias=True, gen_cycles=10)
+    else:
+        cfg = synth.get_config("C1").scaled(name="bias-f32", n_q_heads=4, n_kv_heads=2, qkv_bias=True)
+    w, vis, ids, hv = make(cfg, 21)
+    sbs = SideBySide(cfg, w, hv, vis, ids)
+    ref, _ = greedy_reference(cfg, w, vis[0], ids[0], 1 + 4 * (cfg.K + 1))
+    sbs.cycle(cfg.K)
+    sbs.cycle(2)
+    done = len(sbs.emitted[0])
+    if sbs.emitted[0] == ref[:done]:
+        planted = ref[done: done + 2] + [(ref[done + j] + 3) % cfg.vocab for j in range(2, cfg.K)]
+        r = sbs.cycle(cfg.K, planted=np.array([planted], np.int32))
+        if sbs.near_ties == 0:
+            assert r[0]["n"] == 2
+    print("q/k/v biases", dtype, ":", sbs.summary())
+    # a draft-tree cycle on the same state (12-row passes through the wide-pass kernels for bf16): lossless means its
+    # tokens continue the oracle's greedy text
+    done = len(sbs.emitted[0])
+    if sbs.near_ties == 0 and sbs.emitted[0] == ref[:done]:
+        hv.tree_draft(4, 3, 11)
+        hv.tree_verify()
+        n, toks = hv.tree_accept()
+        got = [int(t) for t in toks[: n + 1]]
+        ref2, lg2 = greedy_reference(cfg, w, vis[0], ids[0], done + len(got))
+        from oracle import top2_gap
+        from parity_utils import logit_tol
+        if float(np.min(top2_gap(lg2[done:]))) > 2 * logit_tol(cfg, lg2):
+            assert got == ref2[done: done + len(got)], (got, ref2[done:])
+    # the oracle without the biases must NOT match (the term is visible at this tolerance)
+    w0 = dict(w); w0["layers"] = [{k: v for k, v in lw.items() if k not in ("bq", "bk", "bv")} for lw in w["layers"]]
+    from oracle import HivisOracle
+    _, l0 = HivisOracle(cfg, w0).prefill(vis[0], ids[0])
+    _, l1 = HivisOracle(cfg, w).prefill(vis[0], ids[0])
+    from parity_utils import logit_tol
+    assert float(np.max(np.abs(l0 - l1))) > 3 * logit_tol(cfg, l1)
+    hv.close()

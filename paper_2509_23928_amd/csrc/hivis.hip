@@ -94,7 +94,7 @@ struct hivis_ctx {
     float* rope_tab = nullptr; float* pm = nullptr; int* pi = nullptr; unsigned* bar = nullptr;
     float* fattn_ws = nullptr; size_t fattn_ws_floats = 0;
     struct Program { hivis::Phase* dev = nullptr; int n = 0; std::vector<hivis::Phase>* host = nullptr; };
-    int keys_per_split = 128;            // attention: cached keys per workgroup (one 16-key tile per wavefront) before the key range is split further
+    int keys_per_split = 192;            // attention: cached keys per workgroup (one or two 16-key tiles per wavefront) before the key range is split further
     bool attn_elect = true;              // key splits merged by the workgroup that arrives last (false: by a merge launch)
     int attn_flags = 3;                  // AttnShape::flags of the phase programs
     bool persistent = false;             // HIVIS_PERSISTENT=1: one cooperative launch per pass instead of one launch per phase

@@ -638,10 +638,9 @@ __host__ __device__ constexpr size_t fused_attn_lds_floats(int hd, int nw, int r
 // that loads split after split spent 8-10 us here), which is why the split count is bounded at compile time.
 // wl: LDS scratch of 3 * ATTN_MAX_SPLITS * RM floats that nothing else uses until the routine returns.
 constexpr int ATTN_MAX_SPLITS = 16;
-template <int HD, int RM>
-__device__ __forceinline__ void attn_merge_splits(const float* __restrict__ pbase, int nsplit, int R, int ni, int head0, int i0, int sl,
-                                                  const AttnShape& sh, float* __restrict__ wl, float* __restrict__ att_out, int ldo) {
-    constexpr int MAXS = ATTN_MAX_SPLITS;
+template <int HD, int RM, int MAXS>
+__device__ __forceinline__ void attn_merge_splits_n(const float* __restrict__ pbase, int nsplit, int R, int ni, int head0, int i0, int sl,
+                                                    const AttnShape& sh, float* __restrict__ wl, float* __restrict__ att_out, int ldo) {
     constexpr int PER = (RM * HD + FUSED_NT - 1) / FUSED_NT;       // output elements per thread
     static_assert(MAXS * RM <= FUSED_NT, "one thread per (split, row) pair of statistics");
     float* wm = wl; float* wsum = wl + MAXS * RM; float* ww = wl + 2 * MAXS * RM;
@@ -689,6 +688,14 @@ __device__ __forceinline__ void attn_merge_splits(const float* __restrict__ pbas
         }
     }
     lds_barrier();
+}
+// (the loads are unrolled to a compile-time bound: the smallest of 4 / 8 / 16 that holds the split count)
+template <int HD, int RM>
+__device__ __forceinline__ void attn_merge_splits(const float* __restrict__ pbase, int nsplit, int R, int ni, int head0, int i0, int sl,
+                                                  const AttnShape& sh, float* __restrict__ wl, float* __restrict__ att_out, int ldo) {
+    if (nsplit <= 4) attn_merge_splits_n<HD, RM, 4>(pbase, nsplit, R, ni, head0, i0, sl, sh, wl, att_out, ldo);
+    else if (nsplit <= 8) attn_merge_splits_n<HD, RM, 8>(pbase, nsplit, R, ni, head0, i0, sl, sh, wl, att_out, ldo);
+    else attn_merge_splits_n<HD, RM, ATTN_MAX_SPLITS>(pbase, nsplit, R, ni, head0, i0, sl, sh, wl, att_out, ldo);
 }
 // Tail shared by the attention variants: the NW per-wavefront partials in mrg ([NW][RM][HD + 2]: weighted value
 // sums, running maximum, sum of weights) are merged in wavefront order; with one key split the attention rows are

@@ -94,6 +94,7 @@ struct hivis_ctx {
     float* rope_tab = nullptr; float* pm = nullptr; int* pi = nullptr; unsigned* bar = nullptr;
     float* fattn_ws = nullptr; size_t fattn_ws_floats = 0;
     struct Program { hivis::Phase* dev = nullptr; int n = 0; std::vector<hivis::Phase>* host = nullptr; };
+    int attn_shared_min = 128;           // rows per sequence from which a causal pass uses the shared-tile attention kernel (128 rows per workgroup)
     int keys_per_split = 192;            // attention: cached keys per workgroup (one or two 16-key tiles per wavefront) before the key range is split further
     bool attn_elect = true;              // key splits merged by the workgroup that arrives last (false: by a merge launch)
     int attn_flags = 3;                  // AttnShape::flags of the phase programs
@@ -337,6 +338,19 @@ int attention_rows_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, 
     const hivis_config& g = c->cfg;
     typedef typename KVType<WT>::type KT;
     if constexpr (std::is_same<KT, f16_t>::value) {
+        if (m >= c->attn_shared_min && tmask == nullptr) {
+            // long causal row ranges (prefill): 128 rows of one head per workgroup, key tiles shared through LDS
+            AttnShape sh{};
+            sh.Hq = g.n_q_heads; sh.Hkv = g.n_kv_heads; sh.m = m; sh.mi = ATTN_SHARED_ROWS; sh.gh = 1;
+            sh.n_hblk = g.n_q_heads / g.n_kv_heads; sh.n_rblk = (m + ATTN_SHARED_ROWS - 1) / ATTN_SHARED_ROWS;
+            sh.seq0 = seq0; sh.offset = offset; sh.maxL = kv.maxL; sh.ldq = ldq; sh.nwaves = FUSED_NW; sh.nsplit = 1; sh.tmask = nullptr;
+            const int items = nseq * g.n_q_heads * sh.n_rblk;
+            const size_t lds = attn_shared_lds_bytes(g.head_dim);
+            if (g.head_dim == 128) hipLaunchKernelGGL((attn_rows_shared_kernel<128>), dim3(items), dim3(FUSED_NT), lds, c->stream, q, (const f16_t*)kv.k, (const f16_t*)kv.v, base, sh, out, ldo);
+            else hipLaunchKernelGGL((attn_rows_shared_kernel<64>), dim3(items), dim3(FUSED_NT), lds, c->stream, q, (const f16_t*)kv.k, (const f16_t*)kv.v, base, sh, out, ldo);
+            HIP_TRY(c, hipGetLastError());
+            return HIVIS_OK;
+        }
         if (m > FUSED_RMAX) {
             // many rows per sequence: 16 (head,row) pairs per work item
             AttnShape sh{};
@@ -860,6 +874,7 @@ int fused_setup(hivis_ctx* c) {
     { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }
     { const char* we = getenv("HIVIS_WIDE_GEMM"); c->no_wide_gemm = we && we[0] == '0'; }
     { const char* we = getenv("HIVIS_WIDE_MIN"); if (we && atoi(we) >= 1) c->wide_min = atoi(we); }
+    { const char* ke = getenv("HIVIS_ATTN_SHARED_MIN"); if (ke && atoi(ke) >= 1) c->attn_shared_min = atoi(ke); }
     { const char* ke = getenv("HIVIS_KEYS_PER_SPLIT"); if (ke && atoi(ke) >= 16) c->keys_per_split = atoi(ke); }
     { const char* ee = getenv("HIVIS_ATTN_ELECT"); if (ee) c->attn_elect = ee[0] == '1'; }
     { const char* fe = getenv("HIVIS_ATTN_FLAGS"); if (fe) c->attn_flags = atoi(fe); }

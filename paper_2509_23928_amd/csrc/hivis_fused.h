@@ -998,6 +998,150 @@ __global__ __launch_bounds__(FUSED_NT) void attn_rows_kernel(const float* __rest
     attn_wg_mfma<HD, ATTN_ROWS_RM>(q, kc, vc, base, sh, blockIdx.x, 0, attn_rows_lds, nullptr, nullptr, out, ldo);
 }
 
+// Attention of long row ranges (prefill): the published flash-attention work split.  A workgroup owns 128 consecutive
+// rows of ONE query head, 16 per wavefront, and walks the keys in tiles of 16 that the whole workgroup loads once and
+// shares through LDS (two buffers, one workgroup barrier per tile), so a cached row is fetched once per 128 query rows
+// instead of once per 16; every wavefront keeps its own running maximum / sum / accumulator, and nothing is merged
+// across wavefronts.  Arithmetic per tile is exactly attn_wg_mfma's (hi/lo operands, three MFMA per product).
+// Items: heads vary fastest, row blocks run from the last (most keys) to the first.
+constexpr int ATTN_SHARED_ROWS = 16 * FUSED_NW;
+__host__ __device__ constexpr size_t attn_shared_lds_bytes(int hd) { return 2 * 16 * ((size_t)hd * 4 + 16 + (size_t)hd * 4 + 32); }
+
+template <int HD>
+__global__ __launch_bounds__(FUSED_NT) void attn_rows_shared_kernel(const float* __restrict__ q, const f16_t* __restrict__ kc, const f16_t* __restrict__ vc,
+                                                                    const int* __restrict__ base, AttnShape sh, float* __restrict__ out, int ldo) {
+    extern __shared__ __align__(16) float attn_shared_lds[];
+    constexpr int HALFB = HD * 2, ROWB = HD * 4, KS = HD / 32, NB = HD / 16, NCH = ROWB / 16;
+    constexpr int VSTRIDE = ROWB + 32, KSTRIDE = ROWB + 16;
+    constexpr int KTB = 16 * KSTRIDE, BUFB = KTB + 16 * VSTRIDE;
+    static_assert(16 * NCH <= FUSED_NT, "one 16-key tile is loaded by one instruction of the workgroup");
+    char* bufs = reinterpret_cast<char*>(attn_shared_lds);          // [2][K tile | V tile]
+
+    const int group = sh.Hq / sh.Hkv;
+    const int nh_total = sh.Hq;                                      // heads per sequence
+    int item = blockIdx.x;
+    const int per_rblk = nh_total * (int)(gridDim.x / (unsigned)(nh_total * sh.n_rblk));   // sequences x heads
+    const int rblk = sh.n_rblk - 1 - item / per_rblk; item %= per_rblk;
+    const int hh = item % nh_total;
+    const int sl = item / nh_total;
+    const int kvh = hh / group;
+    const int seq = sh.seq0 + sl;
+    const int i0 = rblk * ATTN_SHARED_ROWS, ni = min(ATTN_SHARED_ROWS, sh.m - i0);
+    const int pos0 = (sh.nbase > 0 ? sh.base_val[sl] : base[seq]) + sh.offset;
+    const int nkeys = min(pos0 + i0 + ni, sh.maxL);
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n16 = lane & 15, g = lane >> 4;
+    const int r = 16 * wave + n16;
+    const bool valid = r < ni;
+    const bool active = 16 * wave < ni;                              // uniform per wavefront
+    const int wq_max = pos0 + i0 + min(16 * wave + 15, ni - 1);      // last position any row of this wavefront may see
+
+    const char* kbase = reinterpret_cast<const char*>(kc) + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * ROWB;
+    const char* vbase = reinterpret_cast<const char*>(vc) + ((size_t)seq * sh.Hkv + kvh) * sh.maxL * ROWB;
+    const int tid = threadIdx.x;
+    const bool loader = tid < 16 * NCH;
+    const int lkey = min(tid / NCH, 15), lch = tid % NCH;
+    u32x4_t knext, vnext;
+#define HIVIS_SHARED_LOADS(kb_)                                                                 \
+    {                                                                                           \
+        const size_t off_ = (size_t)min((kb_) + lkey, nkeys - 1) * ROWB + lch * 16;             \
+        knext = *reinterpret_cast<const u32x4_t*>(kbase + off_);                                \
+        vnext = *reinterpret_cast<const u32x4_t*>(vbase + off_);                                \
+    }
+    HIVIS_SHARED_LOADS(0)
+
+    f16x8_t qh[KS], ql[KS];
+    {
+        const float* qrow = q + (size_t)(sl * sh.m + i0 + min(r, ni - 1)) * sh.ldq + (size_t)hh * HD + g * 8;
+        const float scale = valid ? rsqrtf((float)HD) : 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const float4 a = *reinterpret_cast<const float4*>(qrow + ks * 32);
+            const float4 b = *reinterpret_cast<const float4*>(qrow + ks * 32 + 4);
+            const float x[8] = {a.x * scale, a.y * scale, a.z * scale, a.w * scale, b.x * scale, b.y * scale, b.z * scale, b.w * scale};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const _Float16 hi = (_Float16)fminf(fmaxf(x[e], -65504.f), 65504.f);
+                qh[ks][e] = hi; ql[ks][e] = (_Float16)(x[e] - (float)hi);
+            }
+        }
+    }
+    const int qpos = valid ? pos0 + i0 + r : 0x7FFFFFFF;
+
+    float mrun = -INFINITY, lrun = 0.f;
+    f32x4_t acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int kb = 0, t = 0; kb < nkeys; kb += 16, ++t) {
+        char* kt = bufs + (t & 1) * BUFB;
+        char* vt = kt + KTB;
+        // tile t -> LDS buffer t % 2 (its last readers, of tile t - 2, are behind the barrier of tile t - 1); request tile t + 1
+        if (loader) {
+            *reinterpret_cast<u32x4_t*>(kt + lkey * KSTRIDE + lch * 16) = knext;
+            *reinterpret_cast<u32x4_t*>(vt + lkey * VSTRIDE + lch * 16) = vnext;
+        }
+        HIVIS_SHARED_LOADS(min(kb + 16, nkeys - 1))
+        lds_barrier();
+        if (!active || kb > wq_max) continue;                    // uniform: no row of this wavefront sees the tile
+        f32x4_t st = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const f16x8_t kh = *reinterpret_cast<const f16x8_t*>(kt + n16 * KSTRIDE + ks * 64 + g * 16);
+            const f16x8_t kl = *reinterpret_cast<const f16x8_t*>(kt + n16 * KSTRIDE + HALFB + ks * 64 + g * 16);
+            st = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[ks], st, 0, 0, 0);
+            st = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, ql[ks], st, 0, 0, 0);
+            st = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[ks], st, 0, 0, 0);
+        }
+        float sv[4], tmax = -INFINITY;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const int key = kb + 4 * g + rr;
+            sv[rr] = (key < nkeys && key <= qpos) ? st[rr] : -INFINITY;
+            tmax = fmaxf(tmax, sv[rr]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float mnew = fmaxf(mrun, tmax);
+        const float mref = (mnew == -INFINITY) ? 0.f : mnew;
+        const float alpha = __expf(mrun - mref);
+        float p[4], psum = 0.f;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) { p[rr] = __expf(sv[rr] - mref); psum += p[rr]; }
+        mrun = mnew;
+        lrun = lrun * alpha + psum;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) acc[nb][rr] *= alpha;
+        }
+        f16x4_t pbh, pbl;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) { pbh[rr] = (_Float16)p[rr]; pbl[rr] = (_Float16)(p[rr] - (float)pbh[rr]); }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const char* src = vt + (4 * g + (n16 >> 2)) * VSTRIDE + (nb * 16 + 4 * (n16 & 3)) * 2;
+            const s16x4_t rh = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(src));
+            const s16x4_t rl = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(src + HALFB));
+            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, rl), pbh, acc[nb], 0, 0, 0);
+            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, rh), pbl, acc[nb], 0, 0, 0);
+            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, rh), pbh, acc[nb], 0, 0, 0);
+        }
+    }
+#undef HIVIS_SHARED_LOADS
+    // this lane holds dims 16 nb + 4 (lane/16) + 0..3 of row r; the row's sum of weights is spread over the four lane groups
+    float lsum = lrun;
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (valid) {
+        const float inv = 1.f / lsum;
+        float* orow = out + (size_t)(sl * sh.m + i0 + r) * ldo + (size_t)hh * HD + 4 * g;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+            *reinterpret_cast<float4*>(orow + nb * 16) = make_float4(acc[nb][0] * inv, acc[nb][1] * inv, acc[nb][2] * inv, acc[nb][3] * inv);
+    }
+}
+
 template <typename KT, int HD, int RM>
 __device__ __forceinline__ void attn_wg_partial(const float* __restrict__ q, const KT* __restrict__ kc, const KT* __restrict__ vc,
                                                 const int* __restrict__ base, const AttnShape& sh, int item_id, int split,

@@ -34,7 +34,7 @@ PAPER_TAU = {"C2": 5.37, "C3": 5.06, "C4": 4.39, "C5": 5.15}    # Table 2, T=0 a
 
 def run_step(hv, cfg, vis, ids, K, temperature=0.0, rng=None, tree=None):
     """prefill + cycles until cfg.gen_tokens tokens (or cfg.gen_cycles cycles).  Returns (tokens, cycles, accepted).
-    temperature > 0: the sampling calls, with uniforms from `rng` (not the headline configuration).
+    temperature > 0: the sampling calls, with uniforms drawn on the device (hivis_rng_seed; not the headline configuration).
     tree = (top_k, depth, n_nodes): draft-tree cycles instead of chain cycles (not the headline configuration)."""
     first = hv.prefill(vis, ids)
     produced = np.ones(hv.B, np.int64)
@@ -48,9 +48,9 @@ def run_step(hv, cfg, vis, ids, K, temperature=0.0, rng=None, tree=None):
             n1, _ = hv.tree_accept()
             n = np.array([n1], np.int64)
         elif temperature > 0.0:
-            hv.draft_sample(K, temperature, rng.random((hv.B, K), dtype=np.float32))
+            hv.draft_sample(K, temperature)
             hv.verify()
-            n, _ = hv.accept_sample(temperature, rng.random((hv.B, K), dtype=np.float32), rng.random(hv.B, dtype=np.float32))
+            n, _ = hv.accept_sample(temperature)
         else:
             hv.draft(K)
             hv.verify()
@@ -196,7 +196,9 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    rng = np.random.default_rng(args.seed + 12345)
+    rng = None
+    if args.temperature > 0.0:
+        hv.rng_seed(args.seed + 12345)
     for _ in range(args.warmup):
         run_step(hv, cfg, vis_dev, ids_dev, K, args.temperature, rng, tree)
     hv.timing(True)

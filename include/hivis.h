@@ -157,13 +157,13 @@ int hivis_accept(hivis_ctx *ctx, int32_t *n_accepted, int32_t *tokens);
  * hivis_prefill's first token is the target's greedy token; hivis_prefill_sample draws it as well. ---- */
 
 /* hivis_prefill with x_{l+1} of sequence b drawn from softmax(logits / T) by inversion with u_first[b] (host, [B]).
- * Errors as hivis_prefill, plus EINVAL for T <= 0 or a uniform outside [0, 1). */
+ * Errors as hivis_prefill, plus EINVAL for T <= 0 or a uniform outside [0, 1).  u_first may be NULL after hivis_rng_seed. */
 int hivis_prefill_sample(hivis_ctx *ctx, const void *vis_embeds, int32_t v, const int32_t *text_ids, int32_t l,
                          float temperature, const float *u_first, int32_t *first_token);
 
 /* K serial drafter steps as hivis_draft, but draft i of sequence b is DRAWN from q_i = softmax(logits_i / T) by
  * inversion with u[b][i-1]: the smallest token j whose running probability sum exceeds u.
- *   u: [B][K] float32, host.   State READY -> DRAFTED.
+ *   u: [B][K] float32, host (NULL after hivis_rng_seed: drawn on the device).   State READY -> DRAFTED.
  * Errors: ESTATE, EINVAL (K, T <= 0, null or out-of-range u), ECAP. */
 int hivis_draft_sample(hivis_ctx *ctx, int32_t K, float temperature, const float *u);
 
@@ -171,10 +171,23 @@ int hivis_draft_sample(hivis_ctx *ctx, int32_t K, float temperature, const float
  * softmax(target logits of row i / T): draft i is accepted while u_accept[b][i] * q_i(x_i) < p_i(x_i); at the first
  * rejection the next token is drawn with u_resample[b] from the normalised positive part of p_i - q_i (from p_i if
  * it is empty); if all K are accepted it is drawn from p_K.  Then the same roll-forward as hivis_accept.
- *   u_accept: [B][K] float32 host; u_resample: [B] float32 host; outputs as hivis_accept.  Synchronises.
+ *   u_accept: [B][K] float32 host; u_resample: [B] float32 host (both NULL after hivis_rng_seed: drawn on the
+ *   device); outputs as hivis_accept.  Synchronises.
  * Errors: ESTATE (also: drafts were planted or drawn greedily, so q is unknown), EINVAL, EHIP. */
 int hivis_accept_sample(hivis_ctx *ctx, float temperature, const float *u_accept, const float *u_resample,
                         int32_t *n_accepted, int32_t *tokens);
+
+/* Random numbers drawn ON THE DEVICE for the three sampling calls above (section 2.1 leaves the source of randomness
+ * open).  After hivis_rng_seed a sampling call whose uniform arrays are ALL NULL fills them itself, on the device, from the
+ * published counter-based generator Philox4x32-10 (Salmon et al., SC'11): key = (seed low word, seed high word), counter =
+ * (index of the number in its array, purpose, call count low word, call count high word), uniform = top 24 bits of output
+ * word 0 times 2^-24.  Purposes and array shapes: 0 = u_first [B]; 1 = u [B][K] (index b*K + i); 2 = u_accept [B][K];
+ * 3 = u_resample [B].  Every sampling call that draws this way uses the context's call count once (u_accept and
+ * u_resample of one hivis_accept_sample share it) and then increments it; hivis_rng_seed resets it to 0.  Nothing crosses
+ * the host-device link.  calls_so_far (may be NULL) receives the count before the reset.
+ * Errors: EINVAL (null ctx).  A sampling call with NULL uniforms before any hivis_rng_seed: ESTATE; with only one of
+ * u_accept / u_resample NULL: EINVAL. */
+int hivis_rng_seed(hivis_ctx *ctx, uint64_t seed, uint64_t *calls_so_far);
 
 /* ---- the same cycle with a draft TREE instead of a chain (section 4, inference setting: a top-k tree expanded to a
  * fixed depth, the candidates with the highest cumulative probability verified in one pass; section 2.1 names the tree

@@ -64,6 +64,7 @@ def load_library(path=LIB_PATH):
         "hivis_prefill_sample": (C.c_int, [P, P, I32, P, I32, C.c_float, P, P]),
         "hivis_draft_sample": (C.c_int, [P, I32, C.c_float, P]),
         "hivis_accept_sample": (C.c_int, [P, C.c_float, P, P, P, P]),
+        "hivis_rng_seed": (C.c_int, [P, C.c_uint64, P]),
         "hivis_tree_draft": (C.c_int, [P, I32, I32, I32]),
         "hivis_tree_set": (C.c_int, [P, I32, P, P]),
         "hivis_tree_verify": (C.c_int, [P]),
@@ -92,7 +93,7 @@ def load_library(path=LIB_PATH):
 
 
 EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_draft_noalloc", "hivis_set_drafts",
-                    "hivis_verify", "hivis_accept", "hivis_prefill_sample", "hivis_draft_sample", "hivis_accept_sample", "hivis_tree_draft", "hivis_tree_set", "hivis_tree_verify", "hivis_tree_accept", "hivis_tree_get", "hivis_tree_get_logits", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
+                    "hivis_verify", "hivis_accept", "hivis_prefill_sample", "hivis_draft_sample", "hivis_accept_sample", "hivis_rng_seed", "hivis_tree_draft", "hivis_tree_set", "hivis_tree_verify", "hivis_tree_accept", "hivis_tree_get", "hivis_tree_get_logits", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
                     "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes", "hivis_clamp_token", "hivis_calib_stream",
                     "hivis_last_error", "hivis_version")
 
@@ -192,14 +193,21 @@ class Hivis:
         self._check(self.lib.hivis_prefill(self.ctx, _ptr(vis_embeds), v, _ptr(text_ids), l, _ptr(first)))
         return first
 
-    def prefill_sample(self, vis_embeds, text_ids, temperature, u_first):
-        """prefill() with the first token of every sequence drawn at `temperature` with u_first [B]."""
+    def rng_seed(self, seed):
+        """Seeds the device-side generator; afterwards the sampling calls accept None for their uniforms.  Returns the
+        number of drawing calls made since the previous seeding."""
+        calls = C.c_uint64(0)
+        self._check(self.lib.hivis_rng_seed(self.ctx, C.c_uint64(int(seed) & 0xFFFFFFFFFFFFFFFF), C.byref(calls)))
+        return int(calls.value)
+
+    def prefill_sample(self, vis_embeds, text_ids, temperature, u_first=None):
+        """prefill() with the first token of every sequence drawn at `temperature` with u_first [B] (None: drawn on the device)."""
         if isinstance(vis_embeds, np.ndarray):
             vis_embeds = _host_weight(vis_embeds, self.dtype)
         if isinstance(text_ids, np.ndarray):
             text_ids = np.ascontiguousarray(text_ids, dtype=np.int32)
         v, l = int(vis_embeds.shape[-2]), int(text_ids.shape[-1])
-        u = np.ascontiguousarray(u_first, dtype=np.float32).reshape(self.B)
+        u = None if u_first is None else np.ascontiguousarray(u_first, dtype=np.float32).reshape(self.B)
         first = np.zeros(self.B, np.int32)
         self._check(self.lib.hivis_prefill_sample(self.ctx, _ptr(vis_embeds), v, _ptr(text_ids), l, float(temperature), _ptr(u), _ptr(first)))
         return first
@@ -228,16 +236,16 @@ class Hivis:
         self._check(self.lib.hivis_accept(self.ctx, _ptr(n), _ptr(t)))
         return n, t
 
-    def draft_sample(self, K, temperature, u):
-        """u: [B][K] uniform numbers in [0, 1)."""
-        u = np.ascontiguousarray(u, dtype=np.float32).reshape(self.B, K)
+    def draft_sample(self, K, temperature, u=None):
+        """u: [B][K] uniform numbers in [0, 1) (None after rng_seed: drawn on the device)."""
+        u = None if u is None else np.ascontiguousarray(u, dtype=np.float32).reshape(self.B, K)
         self._check(self.lib.hivis_draft_sample(self.ctx, K, float(temperature), _ptr(u)))
         self.K = K
 
-    def accept_sample(self, temperature, u_accept, u_resample):
-        """u_accept: [B][K], u_resample: [B].  Returns (n_accepted [B], tokens [B][k_max+1])."""
-        ua = np.ascontiguousarray(u_accept, dtype=np.float32).reshape(self.B, self.K)
-        ur = np.ascontiguousarray(u_resample, dtype=np.float32).reshape(self.B)
+    def accept_sample(self, temperature, u_accept=None, u_resample=None):
+        """u_accept: [B][K], u_resample: [B] (both None after rng_seed: drawn on the device).  Returns (n_accepted [B], tokens [B][k_max+1])."""
+        ua = None if u_accept is None else np.ascontiguousarray(u_accept, dtype=np.float32).reshape(self.B, self.K)
+        ur = None if u_resample is None else np.ascontiguousarray(u_resample, dtype=np.float32).reshape(self.B)
         n = np.zeros(self.B, np.int32)
         t = np.zeros((self.B, self.k_max + 1), np.int32)
         self._check(self.lib.hivis_accept_sample(self.ctx, float(temperature), _ptr(ua), _ptr(ur), _ptr(n), _ptr(t)))

@@ -79,6 +79,7 @@ struct hivis_ctx {
     int32_t *row_tok = nullptr, *drafts = nullptr, *ttok = nullptr, *nacc = nullptr, *out_tok = nullptr, *next_tok = nullptr;
     int32_t* h_result = nullptr;         // pinned host mirror of [nacc | out_tok | abort flag | bad-logits flag]
     int* bad = nullptr;                  // device flag: a greedy-token kernel met a row without a finite maximum (cleared by hivis_prefill)
+    bool rng_seeded = false; unsigned long long rng_seed = 0, rng_calls = 0;   // device-side uniforms (hivis_rng_seed): Philox key and draw-call count
     float *u_draft = nullptr, *u_acc = nullptr, *u_res = nullptr;   // uniform numbers of the sampling calls: [B][k_max], [B][k_max] (row stride K), [B]
     float inv_temp = 1.0f; bool drafts_sampled = false;             // set by hivis_draft_sample; hivis_accept_sample needs the drafter's distributions
     void* vis = nullptr;        // staging for vis_embeds [B][max_vis][d]
@@ -1532,19 +1533,39 @@ int hivis_prefill(hivis_ctx* c, const void* vis_embeds, int32_t v, const int32_t
 
 static int check_uniforms(hivis_ctx* c, const float* u, size_t n, const char* what);
 
+// Fills the uniform arrays of one sampling call on the device (up to two arrays share the call's number).
+static int rng_fill(hivis_ctx* c, float* uA, int nA, int rowA, int strideA, unsigned purposeA, float* uB, int nB, unsigned purposeB) {
+    if (!c->rng_seeded) return fail(c, HIVIS_ESTATE, "null uniform arrays need hivis_rng_seed first");
+    const unsigned long long n = c->rng_calls++;
+    const int total = nA + nB;
+    hipLaunchKernelGGL(rng_fill_kernel, dim3((total + 255) / 256), dim3(256), 0, c->stream, uA, nA, std::max(rowA, 1), strideA, purposeA, uB, nB, purposeB,
+                       (unsigned)(c->rng_seed & 0xFFFFFFFFull), (unsigned)(c->rng_seed >> 32), (unsigned)(n & 0xFFFFFFFFull), (unsigned)(n >> 32));
+    HIP_TRY(c, hipGetLastError());
+    return HIVIS_OK;
+}
+
+int hivis_rng_seed(hivis_ctx* c, uint64_t seed, uint64_t* calls_so_far) {
+    if (!c) return HIVIS_EINVAL;
+    if (calls_so_far) *calls_so_far = c->rng_calls;
+    c->rng_seeded = true; c->rng_seed = seed; c->rng_calls = 0;
+    return HIVIS_OK;
+}
+
 int hivis_prefill_sample(hivis_ctx* c, const void* vis_embeds, int32_t v, const int32_t* text_ids, int32_t l, float temperature,
                          const float* u_first, int32_t* first_token) {
     if (!c) return HIVIS_EINVAL;
     const hivis_config& g = c->cfg;
     if (!text_ids || v < 0 || l < 1 || (v > 0 && !vis_embeds)) return fail(c, HIVIS_EINVAL, "bad prefill arguments (v=%d, l=%d)", v, l);
     if (!(temperature > 0.0f)) return fail(c, HIVIS_EINVAL, "temperature must be positive");
-    if (int rc = check_uniforms(c, u_first, (size_t)g.batch, "u_first")) return rc;
+    if (!u_first && !c->rng_seeded) return fail(c, HIVIS_ESTATE, "null u_first needs hivis_rng_seed first");
+    if (u_first) { if (int rc = check_uniforms(c, u_first, (size_t)g.batch, "u_first")) return rc; }
     if (v > g.max_vis || l + g.k_max + 2 > g.max_text) return fail(c, HIVIS_ECAP, "prompt exceeds capacity (v=%d/%d, l=%d/%d)", v, g.max_vis, l, g.max_text);
     c->h_ids.resize((size_t)g.batch * l);
     HIP_TRY(c, hipMemcpy(c->h_ids.data(), text_ids, c->h_ids.size() * sizeof(int32_t), hipMemcpyDefault));
     for (int32_t id : c->h_ids)
         if (id < 0 || id >= g.vocab) return fail(c, HIVIS_EINVAL, "token id %d outside [0,%d)", id, g.vocab);
-    HIP_TRY(c, hipMemcpyAsync(c->u_res, u_first, (size_t)g.batch * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    if (u_first) { HIP_TRY(c, hipMemcpyAsync(c->u_res, u_first, (size_t)g.batch * sizeof(float), hipMemcpyHostToDevice, c->stream)); }
+    else if (int rc = rng_fill(c, c->u_res, g.batch, 1, 1, 0u, nullptr, 0, 0u)) return rc;
     c->inv_temp = 1.0f / temperature;
     c->state = ST_CREATED;
     return DISPATCH(c, do_prefill, c, vis_embeds, v, text_ids, l, first_token, true);
@@ -1599,10 +1620,13 @@ int hivis_draft_sample(hivis_ctx* c, int32_t K, float temperature, const float* 
     if (K < 1 || K > c->cfg.k_max) return fail(c, HIVIS_EINVAL, "K=%d outside [1,%d]", K, c->cfg.k_max);
     if (!(temperature > 0.0f)) return fail(c, HIVIS_EINVAL, "temperature must be positive");
     const int B = c->cfg.batch;
-    if (int rc = check_uniforms(c, u, (size_t)B * K, "u")) return rc;
+    if (!u && !c->rng_seeded) return fail(c, HIVIS_ESTATE, "null u needs hivis_rng_seed first");
+    if (u) { if (int rc = check_uniforms(c, u, (size_t)B * K, "u")) return rc; }
     if (int rc = check_room(c, K)) return rc;
-    for (int b = 0; b < B; ++b)
-        HIP_TRY(c, hipMemcpyAsync(c->u_draft + (size_t)b * c->cfg.k_max, u + (size_t)b * K, K * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    if (u) {
+        for (int b = 0; b < B; ++b)
+            HIP_TRY(c, hipMemcpyAsync(c->u_draft + (size_t)b * c->cfg.k_max, u + (size_t)b * K, K * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    } else if (int rc = rng_fill(c, c->u_draft, B * K, K, c->cfg.k_max, 1u, nullptr, 0, 0u)) return rc;
     c->inv_temp = 1.0f / temperature;
     int rc = DISPATCH(c, do_draft, c, K, true);
     if (rc) return rc;
@@ -1647,10 +1671,13 @@ int hivis_accept_sample(hivis_ctx* c, float temperature, const float* u_accept, 
     if (!n_accepted || !tokens) return fail(c, HIVIS_EINVAL, "null output pointer");
     if (!(temperature > 0.0f)) return fail(c, HIVIS_EINVAL, "temperature must be positive");
     const int B = c->cfg.batch, K = c->K;
-    if (int rc = check_uniforms(c, u_accept, (size_t)B * K, "u_accept")) return rc;
-    if (int rc = check_uniforms(c, u_resample, (size_t)B, "u_resample")) return rc;
-    HIP_TRY(c, hipMemcpyAsync(c->u_acc, u_accept, (size_t)B * K * sizeof(float), hipMemcpyHostToDevice, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(c->u_res, u_resample, (size_t)B * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    if ((u_accept == nullptr) != (u_resample == nullptr)) return fail(c, HIVIS_EINVAL, "u_accept and u_resample must both be given or both be null");
+    if (u_accept) {
+        if (int rc = check_uniforms(c, u_accept, (size_t)B * K, "u_accept")) return rc;
+        if (int rc = check_uniforms(c, u_resample, (size_t)B, "u_resample")) return rc;
+        HIP_TRY(c, hipMemcpyAsync(c->u_acc, u_accept, (size_t)B * K * sizeof(float), hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->u_res, u_resample, (size_t)B * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    } else if (int rc = rng_fill(c, c->u_acc, B * K, K, K, 2u, c->u_res, B, 3u)) return rc;
     c->inv_temp = 1.0f / temperature;
     return DISPATCH(c, do_accept, c, n_accepted, tokens, true);
 }

@@ -714,6 +714,40 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int
 }
 
 // ------------------------------------------------------------------------------------------
+// Uniform numbers for the sampling kernels, drawn on the device: Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
+// One round maps the counter (c0..c3) under the round key (k0, k1) to
+//   (hi(M1 c2) ^ c1 ^ k0,  lo(M1 c2),  hi(M0 c0) ^ c3 ^ k1,  lo(M0 c0));
+// ten rounds, the key advancing by the two Weyl constants between rounds.  A uniform is the top 24 bits of output
+// word 0 times 2^-24.  Counter = (index in the array, purpose of the array, draw-call count low, high); key = seed.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned philox4x32_10_word0(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0, unsigned k1) {
+#pragma unroll
+    for (int rnd = 0; rnd < 10; ++rnd) {
+        if (rnd > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+        const unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const unsigned hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    }
+    return c0;
+}
+
+// Fills up to two arrays of one sampling call: array A holds nA numbers laid out [nA / rowA][rowA] with row stride
+// strideA (number i sits at (i / rowA) * strideA + i % rowA), array B holds nB numbers contiguously.
+__global__ void rng_fill_kernel(float* __restrict__ uA, int nA, int rowA, int strideA, unsigned purposeA,
+                                float* __restrict__ uB, int nB, unsigned purposeB,
+                                unsigned key0, unsigned key1, unsigned call_lo, unsigned call_hi) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < nA) {
+        const unsigned w = philox4x32_10_word0((unsigned)t, purposeA, call_lo, call_hi, key0, key1);
+        uA[(size_t)(t / rowA) * strideA + t % rowA] = (float)(w >> 8) * 0x1p-24f;
+    } else if (t < nA + nB) {
+        const unsigned w = philox4x32_10_word0((unsigned)(t - nA), purposeB, call_lo, call_hi, key0, key1);
+        uB[t - nA] = (float)(w >> 8) * 0x1p-24f;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Attention of a few query rows against a long cached K/V (verify: K+1 rows; draft: 1 row;
 // prefill chunks: up to 16 rows of one head).  A work item is (sequence, kv head, a range of
 // query heads of that kv head, a range of rows) with at most RMAX (head,row) pairs; it is

@@ -3,12 +3,17 @@
 Logits are compared as in the greedy tests (oracle in follow mode).  Every sampling DECISION (drawn draft, accepted
 length, replacement / extra token) is an integer decided by floating point, so both sides take it from the same
 numbers: the oracle re-takes each decision in float64 from the library's own float32 logits and the same uniforms;
-a difference is tolerated only where the uniform lies within 1e-5 of the decision boundary (counted)."""
+a difference is tolerated only where the uniform lies within 1e-5 of the decision boundary (counted).
+
+With `device_seed` the library draws its uniforms itself (hivis_rng_seed, NULL arrays); the test derives the numbers it
+must have used from the oracle's own generator (oracle/rng.py: seed, call count, purpose, index) and checks every
+decision exactly as above, so a wrong counter layout, key or bit-to-float mapping in the kernel shows as wrong draws."""
 import numpy as np
 import pytest
 
 import synth
 from oracle import HivisSamplingOracle, sample_inverse_cdf, softmax_temperature, speculative_accept
+from oracle import rng as orng
 from parity_utils import logit_tol
 from test_gpu_parity import make, small_bf16
 
@@ -23,16 +28,27 @@ def near_cdf_boundary(weights, u, a, b):
     return bool(np.min(np.abs(c[lo:hi] - u * c[-1])) <= EDGE * c[-1])
 
 
-def run_sampling(cfg, seed, cycles, T, sample_first=False):
+def run_sampling(cfg, seed, cycles, T, sample_first=False, device_seed=None):
     from paper_2509_23928_amd import HivisError, HIVIS_ESTATE, HIVIS_EINVAL
     w, vis, ids, hv = make(cfg, seed)
     B, K = cfg.batch, cfg.K
     rng = np.random.default_rng(1000 + seed)
+    dev = device_seed is not None
+    call = 0                                        # the library's count of drawing calls since the seeding
+    if dev:
+        with pytest.raises(HivisError) as e:        # NULL uniforms before any seeding
+            hv.prefill_sample(vis, ids, T, None)
+        assert e.value.code == HIVIS_ESTATE
+        assert hv.rng_seed(device_seed) == 0
     stats = {"draws": 0, "edge": 0, "n_hist": np.zeros(K + 1, int), "max_err": 0.0}
     oracles = [HivisSamplingOracle(cfg, w) for _ in range(B)]
     if sample_first:
-        u_f = rng.random(B).astype(np.float32)
-        first = hv.prefill_sample(vis, ids, T, u_f)
+        if dev:
+            u_f = orng.uniforms(device_seed, call, orng.FIRST_TOKEN, B); call += 1
+            first = hv.prefill_sample(vis, ids, T, None)
+        else:
+            u_f = rng.random(B).astype(np.float32)
+            first = hv.prefill_sample(vis, ids, T, u_f)
         plog = hv.get_logits(2).astype(np.float64)
         for b, o in enumerate(oracles):
             _, ologits = o.prefill_sample(vis[b], ids[b], T, float(u_f[b]), follow=int(first[b]))
@@ -57,15 +73,26 @@ def run_sampling(cfg, seed, cycles, T, sample_first=False):
         hv.draft_sample(K, 1.0, np.full((B, K), 1.0))
     assert e.value.code == HIVIS_EINVAL
     for cyc in range(cycles):
-        u_d = rng.random((B, K)).astype(np.float32)
-        u_a = rng.random((B, K)).astype(np.float32)
-        u_r = rng.random(B).astype(np.float32)
-        hv.draft_sample(K, T, u_d)
+        if dev:
+            u_d = orng.uniforms(device_seed, call, orng.DRAFT, B * K).reshape(B, K)
+            u_a = orng.uniforms(device_seed, call + 1, orng.ACCEPT, B * K).reshape(B, K)
+            u_r = orng.uniforms(device_seed, call + 1, orng.RESAMPLE, B)
+            call += 2
+            hv.draft_sample(K, T, None)
+        else:
+            u_d = rng.random((B, K)).astype(np.float32)
+            u_a = rng.random((B, K)).astype(np.float32)
+            u_r = rng.random(B).astype(np.float32)
+            hv.draft_sample(K, T, u_d)
         hv.verify()
         drafts, _ = hv.get_tokens()
         dlog = hv.get_logits(1).astype(np.float64)      # [K][B][V]
         vlog = hv.get_logits(0).astype(np.float64)      # [B][K+1][V]
-        n, toks = hv.accept_sample(T, u_a, u_r)
+        if dev and cyc == 0:
+            with pytest.raises(HivisError) as e:    # one array given, the other not
+                hv.accept_sample(T, u_a, None)
+            assert e.value.code == HIVIS_EINVAL
+        n, toks = hv.accept_sample(T, None, None) if dev else hv.accept_sample(T, u_a, u_r)
         for b, o in enumerate(oracles):
             _, ologits = o.draft_sample(K, T, u_d[b], follow=drafts[b])
             tol = logit_tol(cfg, ologits)
@@ -109,6 +136,8 @@ def run_sampling(cfg, seed, cycles, T, sample_first=False):
         hv.accept_sample(T, rng.random((B, K)), rng.random(B))
     assert e.value.code == HIVIS_ESTATE
     hv.accept()
+    if dev:
+        assert hv.rng_seed(device_seed + 1) == call         # every drawing call was counted once
     hv.close()
     assert stats["edge"] <= max(3, stats["draws"] // 5), stats
     return stats
@@ -146,3 +175,13 @@ def test_sampling_standalone_kernel_path():
         print("stand-alone path T=0.7 sampling:", st)
     finally:
         del os.environ["HIVIS_FUSED"]
+
+
+def test_sampling_device_rng_fp32_and_bf16_batch2():
+    # uniforms drawn on the device (Philox4x32-10); a 64-bit seed with both halves in use
+    st = run_sampling(synth.get_config("C1"), 0, 6, 1.0, sample_first=True, device_seed=0x9E3779B97F4A7C15)
+    print("C1 T=1 device-drawn uniforms:", st)
+    assert st["n_hist"].sum() == 6
+    st = run_sampling(small_bf16(batch=2, K=4), 45, 5, 0.8, sample_first=True, device_seed=7)
+    print("bf16 batch 2 T=0.8 device-drawn uniforms:", st)
+    assert st["n_hist"].sum() == 10

@@ -75,6 +75,7 @@ struct hivis_ctx {
     float *u = nullptr, *dout = nullptr;
     float *feat = nullptr;      // [B][max_text][d] true features of prompt text rows (prefill only)
     float *attn_ws = nullptr; size_t attn_ws_floats = 0;
+    int* rows_cnt = nullptr; int rows_cnt_n = 0;      // arrival counters of the key-split attention launched outside a phase program (zero between launches)
     float *logits_v = nullptr, *logits_d = nullptr, *logits_p = nullptr;
     int32_t *row_tok = nullptr, *drafts = nullptr, *ttok = nullptr, *nacc = nullptr, *out_tok = nullptr, *next_tok = nullptr;
     int32_t* h_result = nullptr;         // pinned host mirror of [nacc | out_tok | abort flag | bad-logits flag]
@@ -380,13 +381,24 @@ int attention_rows_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, 
     Phase ph{};
     ph.type = PH_ATTN;
     ph.att = fused_attn_shape(c, nseq, m, offset, kv.maxL, ldq, &items);
-    ph.att.seq0 = seq0; ph.att.nsplit = 1; ph.att.tmask = tmask;
+    ph.att.seq0 = seq0; ph.att.nsplit = 1; ph.att.tmask = tmask; ph.att.flags = c->attn_flags;
     ph.att_items = items;
     ph.A = q; ph.kc = kv.k; ph.vc = kv.v; ph.maxL = kv.maxL; ph.base = base; ph.offset = offset;
     ph.Y = out; ph.ldy = ldo; ph.ws = nullptr; ph.cnt = nullptr;
+    if (c->attn_elect && items <= c->rows_cnt_n) {
+        // long caches: the key range of an item is split over workgroups and the last one to arrive merges (as in the
+        // phase programs); the host mirrors the cache lengths that `base` holds
+        const std::vector<int>* hl = base == c->tlen ? &c->h_tlen : base == c->dlen ? &c->h_dlen : nullptr;
+        int max_keys = 0;
+        for (int s = 0; s < nseq; ++s) max_keys = std::max(max_keys, (hl ? (*hl)[seq0 + s] : 0) + offset + m);
+        int nsplit = std::min({ATTN_MAX_SPLITS, (max_keys + c->keys_per_split - 1) / c->keys_per_split, std::max(1, c->fused_grid / items)});    // no more workgroups than CUs: with more, C5's 160 items got slower (8.8 -> 9.6 ms per verify)
+        while (nsplit > 1 && (size_t)items * nsplit * FUSED_RMAX * (g.head_dim + 2) > c->attn_ws_floats) --nsplit;
+        if (nsplit > 1) { ph.att.nsplit = nsplit; ph.ws = c->attn_ws; ph.cnt = c->rows_cnt; }
+    }
+    const int grid = ((ph.att.flags & 2) ? 8 * ((items + 7) / 8) : items) * ph.att.nsplit;
     PassParams pp{};
     pp.M = nseq * m; pp.nseq = nseq; pp.m = m; pp.d = g.d; pp.Hq = g.n_q_heads; pp.Hkv = g.n_kv_heads; pp.hd = g.head_dim; pp.F = g.ffn; pp.V = g.vocab;
-    hipLaunchKernelGGL((phase_kernel<WT, PH_ATTN, 0, false>), dim3(items), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp);
+    hipLaunchKernelGGL((phase_kernel<WT, PH_ATTN, 0, false>), dim3(grid), dim3(FUSED_NT), c->fused_lds, c->stream, ph, pp);
     HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;
 }
@@ -1426,6 +1438,9 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
         if (c->pf_rows) max_items = std::max(max_items, (size_t)g.n_q_heads * ((c->pf_rows + ATT_RMAX - 1) / ATT_RMAX));
         c->attn_ws_floats = (2 * (size_t)c->num_cu + max_items) * 4 * ATT_RMAX * (g.head_dim + 2);
         if ((rc = dev_alloc(c, &c->attn_ws, c->attn_ws_floats))) return rc;
+        c->rows_cnt_n = std::max(2, B) * g.n_q_heads;
+        if ((rc = dev_alloc(c, &c->rows_cnt, (size_t)c->rows_cnt_n))) return rc;
+        HIP_TRY(c, hipMemset(c->rows_cnt, 0, (size_t)c->rows_cnt_n * sizeof(int)));
     }
     if ((rc = dev_alloc(c, &c->logits_v, (size_t)R * V))) return rc;
     if ((rc = dev_alloc(c, &c->logits_d, (size_t)g.k_max * B * V))) return rc;

@@ -171,6 +171,14 @@ def test_forced_small_key_splits_hd64_and_hd128():
         print("forced key splits hd128:", sbs.summary())
         sbs = run_generic(small_bf16(head_dim=64, n_q_heads=8, n_kv_heads=2), 28, 2, plant=(2,))
         print("forced key splits hd64 gqa:", sbs.summary())
+        # batch 4, K = 7: 32-row passes, whose attention is launched outside a phase program (same split + elected merge)
+        cfg = small_bf16(batch=4, K=7, n_vis=90, n_text=45, n_q_heads=4, n_kv_heads=4)
+        w, vis, ids, hv = make(cfg, 29)
+        sbs = SideBySide(cfg, w, hv, vis, ids)
+        for _ in range(3):
+            sbs.cycle(cfg.K)
+        hv.close()
+        print("forced key splits batch 4 (32-row passes):", sbs.summary())
     finally:
         del os.environ["HIVIS_KEYS_PER_SPLIT"]
 

@@ -75,6 +75,7 @@ struct hivis_ctx {
     float *u = nullptr, *dout = nullptr;
     float *feat = nullptr;      // [B][max_text][d] true features of prompt text rows (prefill only)
     float *attn_ws = nullptr; size_t attn_ws_floats = 0;
+    float* zero_blk = nullptr;           // 1 KiB of zeros: the K blocks past the end in the large-tile prefill GEMM
     int* rows_cnt = nullptr; int rows_cnt_n = 0;      // arrival counters of the key-split attention launched outside a phase program (zero between launches)
     float *logits_v = nullptr, *logits_d = nullptr, *logits_p = nullptr;
     int32_t *row_tok = nullptr, *drafts = nullptr, *ttok = nullptr, *nacc = nullptr, *out_tok = nullptr, *next_tok = nullptr;
@@ -96,6 +97,7 @@ struct hivis_ctx {
     float* rope_tab = nullptr; float* pm = nullptr; int* pi = nullptr; unsigned* bar = nullptr;
     float* fattn_ws = nullptr; size_t fattn_ws_floats = 0;
     struct Program { hivis::Phase* dev = nullptr; int n = 0; std::vector<hivis::Phase>* host = nullptr; };
+    bool tall_big = true; int tall_big_fill = 70;   // prefill GEMMs: the 128 x 256 tile when its workgroups fill at least this percentage of their rounds over the CUs
     int attn_shared_min = 128;           // rows per sequence from which a causal pass uses the shared-tile attention kernel (128 rows per workgroup)
     int keys_per_split = 192;            // attention: cached keys per workgroup (one or two 16-key tiles per wavefront) before the key range is split further
     bool attn_elect = true;              // key splits merged by the workgroup that arrives last (false: by a merge launch)
@@ -887,6 +889,8 @@ int fused_setup(hivis_ctx* c) {
     { const char* pe = getenv("HIVIS_PERSISTENT"); c->persistent = pe && pe[0] == '1'; }
     { const char* we = getenv("HIVIS_WIDE_GEMM"); c->no_wide_gemm = we && we[0] == '0'; }
     { const char* we = getenv("HIVIS_WIDE_MIN"); if (we && atoi(we) >= 1) c->wide_min = atoi(we); }
+    { const char* be = getenv("HIVIS_TALL_BIG"); if (be) c->tall_big = be[0] != '0'; }
+    { const char* be = getenv("HIVIS_TALL_BIG_FILL"); if (be && atoi(be) >= 0 && atoi(be) <= 100) c->tall_big_fill = atoi(be); }
     { const char* ke = getenv("HIVIS_ATTN_SHARED_MIN"); if (ke && atoi(ke) >= 1) c->attn_shared_min = atoi(ke); }
     { const char* ke = getenv("HIVIS_KEYS_PER_SPLIT"); if (ke && atoi(ke) >= 16) c->keys_per_split = atoi(ke); }
     { const char* ee = getenv("HIVIS_ATTN_ELECT"); if (ee) c->attn_elect = ee[0] == '1'; }
@@ -912,6 +916,26 @@ int tall_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* 
     // LDS-tiled kernel: 64 real rows x 256 columns per workgroup when that still gives >= 2 workgroups per CU, else x 128
     const int macro_rows = (row_tiles + 7) / 8;
     // grid: (column blocks rounded up to a multiple of the 8 XCDs) x row blocks, 1-D (see the kernel's mapping)
+    // large tile (128 real rows x 256 columns, one workgroup per CU) where it fills the CUs in whole rounds well enough
+    {
+        const int big_rows = (row_tiles + 15) / 16, big_cols = (ntiles + 15) / 16;
+        const long wgs = (long)big_rows * big_cols;
+        const long rounds = (wgs + c->num_cu - 1) / c->num_cu;
+        // rows padded to 128 must not waste more than rows padded to 64 would (832 rows: 7.7% against 0)
+        const bool rows_ok = c->tall_big_fill == 0 || big_rows * 128 - M <= macro_rows * 64 - M + M / 32;
+        if (c->tall_big && M >= 128 && rows_ok && wgs * 100 >= rounds * c->num_cu * c->tall_big_fill) {
+            static bool attr = false;
+            if (!attr) { HIP_TRY(c, hipFuncSetAttribute((const void*)gemm_tall_big_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 32 * 1024)); attr = true; }
+            // patches of RB x CB blocks, dealt to the 8 XCDs (the kernel's mapping)
+            const int npr = (big_rows + 7) / 8, RB = (big_rows + npr - 1) / npr, CB = std::max(1, 32 / RB);
+            const int npatch = ((big_rows + RB - 1) / RB) * ((big_cols + CB - 1) / CB);
+            const int grid = ((npatch + 7) / 8) * 8 * RB * CB;
+            hipLaunchKernelGGL((gemm_tall_big_kernel<8>), dim3(grid), dim3(256), 3 * 32 * 1024, c->stream,
+                               (const v4u_t*)c->pf_frag, row_tiles, kblks, (const v4u_t*)Wp, ntiles, Y, ldy, M, (const v4u_t*)c->zero_blk);
+            HIP_TRY(c, hipGetLastError());
+            return HIVIS_OK;
+        }
+    }
     if ((size_t)macro_rows * ((ntiles + 15) / 16) >= (size_t)2 * c->num_cu) {
         const int ncol8 = (((ntiles + 15) / 16) + 7) & ~7;
         hipLaunchKernelGGL((gemm_tall_lds_kernel<8>), dim3(ncol8 * macro_rows), dim3(256), 2 * 24 * 1024, c->stream,
@@ -1402,6 +1426,8 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     if ((rc = dev_alloc(c, &c->tlen, B))) return rc;
     if ((rc = dev_alloc(c, &c->dlen, B))) return rc;
     if ((rc = dev_alloc(c, &c->zeros, B))) return rc;
+    if ((rc = dev_alloc(c, &c->zero_blk, 256))) return rc;
+    HIP_TRY(c, hipMemset(c->zero_blk, 0, 256 * sizeof(float)));
     HIP_TRY(c, hipMemset(c->zeros, 0, B * sizeof(int)));
     if ((rc = dev_alloc(c, &c->text, (size_t)B * c->text_stride))) return rc;
     HIP_TRY(c, hipMemset(c->text, 0, (size_t)B * c->text_stride * sizeof(int32_t)));

@@ -526,6 +526,141 @@ __global__ __launch_bounds__(256, 2) void gemm_tall_lds_kernel(const v4u_t* __re
     }
 }
 
+// Tall GEMM, large tile: a workgroup of 2 x 2 wavefronts computes 16 row tiles x 16 column tiles (128 real rows x 256
+// columns), each wavefront 8 x 8 MFMA tiles whose 256 accumulator registers leave room for ONE wavefront per SIMD, so
+// the wavefront has to overlap its own latencies.  Step kb (one K block): park block kb+2 in LDS (three stages), request
+// block kb+5 from memory into the register set that just became free (three sets: a block has three steps to arrive),
+// read the A fragments of block kb+1 into the second fragment set, all spread over the 64 MFMAs of block kb, whose
+// operands were read earlier; one LDS-only barrier per step.  The steps are branch-free (so that the
+// loads in flight can be counted) and unrolled by six (register sets are static); past the last K block they multiply a
+// block of zeros (`zero`, 1 KiB) instead.
+template <int CTW>
+__global__ __launch_bounds__(256, 1) void gemm_tall_big_kernel(const v4u_t* __restrict__ Af, int row_tiles, int kblks,
+                                                             const v4u_t* __restrict__ Wp, int ntiles, float* __restrict__ Y,
+                                                             int ldy, int M, const v4u_t* __restrict__ zero) {
+    constexpr int RTW = 8, NA = 2 * RTW, NB = 2 * CTW, NBLK = NA + NB, PER_WAVE = NBLK / 4;
+    static_assert(NBLK % 4 == 0, "blocks are dealt evenly to the 4 wavefronts");
+    extern __shared__ __align__(16) v4u_t big_lds[];       // [3 stages][NBLK][64]
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wr = wave >> 1, wc = wave & 1;
+    // XCD-aware 1-D grid (workgroup L runs on XCD L % 8, one workgroup per CU, 32 CUs per XCD): the workgroups an XCD runs
+    // at one time form a compact patch of RB row blocks x CB column blocks, so that per K block the XCD's L2 is asked for
+    // RB + CB different 16 KiB operand blocks instead of ~RB * CB (with one column block per XCD, every activation block
+    // came from beyond the L2 for a single use).  The weights of a column block are then fetched by nrow / RB XCDs, which
+    // HBM has room for in this compute-bound regime.  Patch p of the (row, column) block space goes to XCD p % 8.
+    const int ncol = (ntiles + NB - 1) / NB, nrow = (row_tiles + NA - 1) / NA;
+    const int npr_ = (nrow + 7) / 8, RB = (nrow + npr_ - 1) / npr_, CB = max(1, 32 / RB), S = RB * CB;    // row blocks dealt evenly to the patches
+    const int prow = (nrow + RB - 1) / RB;
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const int patch = (slot / S) * 8 + xcd, within = slot % S;
+    const int rblk = (patch % prow) * RB + within % RB, cblk = (patch / prow) * CB + within / RB;
+    if (cblk >= ncol || rblk >= nrow) return;
+    const int rt_wg = rblk * NA, ct_wg = cblk * NB;
+    const v4u_t* src[PER_WAVE];
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+        const int b = wave + 4 * i;
+        // (wavefront-uniform: the lane is added at the access, so the bases stay in scalar registers)
+        src[i] = (b < NA) ? Af + ((size_t)min(rt_wg + b, row_tiles - 1) * kblks) * 64
+                          : Wp + ((size_t)min(ct_wg + (b - NA), ntiles - 1) * kblks) * 64;
+    }
+    f32x4_t acc[RTW][CTW];
+#pragma unroll
+    for (int r = 0; r < RTW; ++r)
+#pragma unroll
+        for (int c = 0; c < CTW; ++c) acc[r][c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    v4u_t st[3][PER_WAVE];                  // blocks on their way from memory to LDS: block j waits in set j % 3
+    // A fragments of the block being multiplied (set kb % 2) and of the next one; the B fragments are single-buffered (a
+    // second set does not fit beside three staging sets): each is read two columns before the column that uses it, and
+    // the MFMAs run column-major
+    v4u_t fa[2][RTW], fb[CTW];
+#define HIVIS_BIG_LOAD(set_, blk_)                                                                         \
+    {                                                                                                      \
+        const int j_ = (blk_);                                                                             \
+        _Pragma("unroll") for (int i = 0; i < PER_WAVE; ++i) { const v4u_t* p_ = (j_ < kblks) ? src[i] + (size_t)j_ * 64 : zero; st[set_][i] = p_[lane]; } \
+    }
+#define HIVIS_BIG_PARK(set_, stage_)                                                                       \
+    {                                                                                                      \
+        v4u_t* dst_ = big_lds + (size_t)(stage_) * NBLK * 64;                                               \
+        _Pragma("unroll") for (int i = 0; i < PER_WAVE; ++i) dst_[(size_t)(wave + 4 * i) * 64 + lane] = st[set_][i]; \
+    }
+#define HIVIS_BIG_AFRAGS(fs_, stage_)                                                                      \
+    {                                                                                                      \
+        const v4u_t* s_ = big_lds + (size_t)(stage_) * NBLK * 64;                                           \
+        _Pragma("unroll") for (int r = 0; r < RTW; ++r) fa[fs_][r] = s_[(size_t)(wr * RTW + r) * 64 + lane]; \
+    }
+    // prologue: blocks 0 and 1 into stages 0 and 1, blocks 2, 3, 4 requested, fragments of block 0 read
+    HIVIS_BIG_LOAD(0, 0)
+    HIVIS_BIG_LOAD(1, 1)
+    HIVIS_BIG_PARK(0, 0)
+    HIVIS_BIG_PARK(1, 1)
+    HIVIS_BIG_LOAD(2, 2)
+    HIVIS_BIG_LOAD(0, 3)
+    HIVIS_BIG_LOAD(1, 4)
+    lds_barrier();
+    HIVIS_BIG_AFRAGS(0, 0)
+    fb[0] = big_lds[(size_t)(NA + wc * CTW + 0) * 64 + lane];
+    fb[1] = big_lds[(size_t)(NA + wc * CTW + 1) * 64 + lane];
+    // nothing may be pending on the LDS counter when the loop is entered: inside it the fragments read during one step
+    // are only awaited at that step's barrier, after its MFMAs have been issued
+    lds_barrier();
+    int stage2 = 2, stage1 = 1, stage0 = 0; // (kb + 2) % 3, (kb + 1) % 3, kb % 3
+    for (int kb0 = 0; kb0 < kblks; kb0 += 6) {
+#pragma unroll
+        for (int u = 0; u < 6; ++u) {
+            const int kb = kb0 + u;
+            // The step's memory instructions are spread over its MFMAs, one of each kind per column of 8 MFMAs (issued in
+            // one lump at the start they kept the matrix pipeline idle: a lone wavefront issues nothing else meanwhile):
+            //   park piece c of block kb+2 in its stage (last read, as block kb-1, two barriers ago), request the same
+            //   piece of block kb+5 into the freed registers, read A fragment c of block kb+1 (in LDS since the previous
+            //   barrier) and the B fragment needed two columns later (of block kb+1 for the last two columns).
+            const v4u_t* s0_ = big_lds + (size_t)stage0 * NBLK * 64;
+            const v4u_t* s1_ = big_lds + (size_t)stage1 * NBLK * 64;
+            v4u_t* s2_ = big_lds + (size_t)stage2 * NBLK * 64;
+            const v4u_t* nsrc_[PER_WAVE];
+#pragma unroll
+            for (int i = 0; i < PER_WAVE; ++i) nsrc_[i] = (kb + 5 < kblks) ? src[i] + (size_t)(kb + 5) * 64 : zero;
+#pragma unroll
+            for (int c = 0; c < CTW; ++c) {
+                static_assert(CTW == PER_WAVE && RTW == CTW, "one piece of every kind per column");
+                s2_[(size_t)(wave + 4 * c) * 64 + lane] = st[(u + 2) % 3][c];
+                st[(u + 2) % 3][c] = nsrc_[c][lane];
+                fa[(u + 1) % 2][c] = s1_[(size_t)(wr * RTW + c) * 64 + lane];
+                fb[(c + 2) % CTW] = (c + 2 < CTW ? s0_ : s1_)[(size_t)(NA + wc * CTW + (c + 2) % CTW) * 64 + lane];
+#pragma unroll
+                for (int r = 0; r < RTW; ++r)
+                    // accumulators pinned to the accumulation registers (the register allocator otherwise keeps them in
+                    // ordinary registers and copies each tile in and out around every MFMA)
+                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[r][c]) : "v"(fa[u % 2][r]), "v"(fb[c]));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            lds_barrier();
+            stage0 = stage1; stage1 = stage2; stage2 = (stage2 == 2) ? 0 : stage2 + 1;
+        }
+    }
+#undef HIVIS_BIG_LOAD
+#undef HIVIS_BIG_PARK
+#undef HIVIS_BIG_AFRAGS
+    // the last MFMA results are read below by ordinary moves: let the matrix pipeline drain first (the compiler does not
+    // see an MFMA inside the asm statements, so it inserts no wait states of its own)
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    const int j = lane & 15, a4 = lane >> 4;
+#pragma unroll
+    for (int r = 0; r < RTW; ++r) {
+        const int rt = rt_wg + wr * RTW + r;
+        if (rt >= row_tiles) continue;
+        const int row = rt * 8 + 2 * a4;
+#pragma unroll
+        for (int c = 0; c < CTW; ++c) {
+            const int ct = ct_wg + wc * CTW + c;
+            if (ct >= ntiles) continue;
+            const int col = ct * 16 + j;
+            if (row < M) Y[(size_t)row * ldy + col] = acc[r][c][0] + acc[r][c][2];
+            if (row + 1 < M) Y[(size_t)(row + 1) * ldy + col] = acc[r][c][1] + acc[r][c][3];
+        }
+    }
+}
+
 // Y[r][c] = sum over the K slices of part[s][r][c] (fixed order), r < M, c < N (N a multiple of 4).
 __global__ void splitk_reduce_kernel(const float* __restrict__ part, int ksplit, int M, int N, int ldp, float* __restrict__ Y, int ldy) {
     const int row = blockIdx.x;

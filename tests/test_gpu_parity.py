@@ -183,6 +183,22 @@ def test_forced_small_key_splits_hd64_and_hd128():
         del os.environ["HIVIS_KEYS_PER_SPLIT"]
 
 
+def test_prefill_large_tile_gemm_on_small_shapes():
+    # the 128-row x 256-column prefill GEMM tile is normally chosen only where it fills the CUs (7B-13B widths, covered at
+    # depth elsewhere); forced here on small ragged shapes: 187 and 420 prompt rows (1.46 and 3.3 row blocks), column counts
+    # that are not multiples of 256, K blocks from 8 to 74
+    import os
+    os.environ["HIVIS_TALL_BIG_FILL"] = "0"
+    try:
+        sbs = run_generic(small_bf16(), 51, 1, plant=(3,))
+        print("large-tile prefill GEMM, default small model:", sbs.summary())
+        cfg = small_bf16(n_q_heads=7, n_kv_heads=1, d=896, ffn=2368, K=4, n_vis=380, n_text=40, rope_theta=1e6, rms_eps=1e-6)
+        sbs = run_generic(cfg, 52, 1, plant=(2,))
+        print("large-tile prefill GEMM, gqa7 d896 F2368, 420 rows:", sbs.summary())
+    finally:
+        del os.environ["HIVIS_TALL_BIG_FILL"]
+
+
 def test_gqa_group7_k6_qwen_like_shape():
     # 28 query / 4 kv heads (group 7), K = 6 -> 7 rows per sequence, as in the Qwen2.5-VL-shaped workload, at reduced width
     cfg = small_bf16(n_q_heads=28, n_kv_heads=4, head_dim=64, d=1792, ffn=2368, vocab=4096, K=6, n_vis=130, n_text=50,

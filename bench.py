@@ -108,8 +108,9 @@ def cpu_baseline(cfg, K, weights, vis, ids, gpu_tokens_per_cycle):
 def stream_ceiling(stream=None):
     """hivis_calib_stream over buffer sizes like the verify pass's weight matrices (O projection 33.5 MB, down 90 MB,
     gate|up 180 MB, LM head 262 MB at C2) and one large buffer, each in rotation over >= 1.4 GB so that nothing comes from a
-    cache; one launch per buffer, back to back, launch gaps included.  256 workgroups = one per compute unit, as the GEMM
-    phases run; 1024 = four per compute unit."""
+    cache; one launch per buffer, back to back, each timed by start / stop events attached to its dispatch (the kernel's own
+    duration, as `roofline` times the GEMM).  256 workgroups = one per compute unit, as the GEMM phases run; 1024 = four
+    per compute unit."""
     from paper_2509_23928_amd import calib_stream
     out = {"unit": "GB/s", "peak": HBM_PEAK_GBS, "kernel": "calib_stream_kernel: read-only, 1 KiB per wavefront and instruction, 8 independent 16-byte loads per lane",
            "cases": []}

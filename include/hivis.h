@@ -277,10 +277,12 @@ int hivis_algorithmic_bytes(hivis_ctx *ctx, double *verify_bytes, double *draft_
  * GPU, with the access pattern of the library's weight-streaming GEMMs (1 KiB per wavefront and instruction, 8
  * independent 16-byte loads per lane, 64 KiB per workgroup and trip) and none of their work.  n_buffers device
  * buffers of buffer_bytes each are allocated, filled, read once untimed and then `passes` times in rotation, one launch
- * of `workgroups` x 512 threads per buffer, back to back on hip_stream (a hipStream_t, NULL = default); HIP events
- * around the timed launches give the rate (launch gaps included, as in a pass of the library).  Choose n_buffers *
- * buffer_bytes well above the 256 MB memory-side cache so that nothing is re-read from it.
- *   gb_per_s: bytes read / elapsed time, in 1e9 bytes per second; us_per_launch: elapsed time / launches.  Either may be NULL.
+ * of `workgroups` x 512 threads per buffer, back to back on hip_stream (a hipStream_t, NULL = default).  Start / stop
+ * events attached to the dispatches themselves (at most 256 of them, evenly spread) read each launch's own begin and end,
+ * exactly as hivis_kernel_timing times the library's GEMM: launch gaps and the host's launch rate are not in the figure.
+ * Choose n_buffers * buffer_bytes well above the 256 MB memory-side cache so that nothing is re-read from it.
+ *   us_per_launch: average duration of one launch; gb_per_s: bytes one launch reads / that duration, in 1e9 bytes per
+ *   second.  Either may be NULL.
  * Frees everything before it returns.  Errors: EINVAL (sizes), EHIP. */
 int hivis_calib_stream(void *hip_stream, int64_t buffer_bytes, int32_t n_buffers, int32_t passes, int32_t workgroups,
                        double *gb_per_s, double *us_per_launch);

@@ -1925,13 +1925,12 @@ int hivis_calib_stream(void* hip_stream, int64_t buffer_bytes, int32_t n_buffers
     if (trips == 0) return HIVIS_EINVAL;
     std::vector<void*> bufs;
     unsigned* sink = nullptr;
-    hipEvent_t e0 = nullptr, e1 = nullptr;
+    std::vector<hipEvent_t> ev;
     int rc = HIVIS_OK;
     auto cleanup = [&]() {
         for (void* b : bufs) (void)hipFree(b);
         if (sink) (void)hipFree(sink);
-        if (e0) (void)hipEventDestroy(e0);
-        if (e1) (void)hipEventDestroy(e1);
+        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
     };
 #define CAL_TRY(expr) do { if ((expr) != hipSuccess) { cleanup(); return HIVIS_EHIP; } } while (0)
     CAL_TRY(hipMalloc((void**)&sink, sizeof(unsigned)));
@@ -1941,22 +1940,34 @@ int hivis_calib_stream(void* hip_stream, int64_t buffer_bytes, int32_t n_buffers
         bufs.push_back(b);
         CAL_TRY(hipMemsetAsync(b, 0x5A, n16 * 16, st));
     }
-    CAL_TRY(hipEventCreate(&e0)); CAL_TRY(hipEventCreate(&e1));
+    // Timed like the dominant GEMM in hivis_kernel_timing: start / stop events attached to the dispatch itself read the
+    // kernel's own begin and end (events recorded around a batch of short launches measure the host's launch rate
+    // instead: 12 us per launch for a 6.8 us kernel).  At most 256 launches carry events (every k-th beyond that).
+    const int total = passes * n_buffers;
+    const int stride = (total + 255) / 256;
+    const int timed = (total + stride - 1) / stride;
+    ev.resize((size_t)2 * timed, nullptr);
+    for (hipEvent_t& e : ev) CAL_TRY(hipEventCreate(&e));
     // one untimed round over all buffers, then `passes` timed rounds; the buffers rotate so that nothing read comes from a cache
     for (int i = 0; i < n_buffers; ++i) hipLaunchKernelGGL(calib_stream_kernel, dim3(workgroups), dim3(512), 0, st, (const uint4*)bufs[i], n16, sink);
-    CAL_TRY(hipEventRecord(e0, st));
-    for (int p = 0; p < passes; ++p)
-        for (int i = 0; i < n_buffers; ++i) hipLaunchKernelGGL(calib_stream_kernel, dim3(workgroups), dim3(512), 0, st, (const uint4*)bufs[i], n16, sink);
-    CAL_TRY(hipEventRecord(e1, st));
-    CAL_TRY(hipEventSynchronize(e1));
+    for (int l = 0, t = 0; l < total; ++l) {
+        hipEvent_t a = nullptr, b = nullptr;
+        if (l % stride == 0) { a = ev[2 * t]; b = ev[2 * t + 1]; ++t; }
+        hipExtLaunchKernelGGL(calib_stream_kernel, dim3(workgroups), dim3(512), 0, st, a, b, 0, (const uint4*)bufs[l % n_buffers], n16, sink);
+    }
+    CAL_TRY(hipStreamSynchronize(st));
     CAL_TRY(hipGetLastError());
-    float ms = 0.f;
-    CAL_TRY(hipEventElapsedTime(&ms, e0, e1));
+    double ms_sum = 0.0;
+    for (int t = 0; t < timed; ++t) {
+        float ms = 0.f;
+        CAL_TRY(hipEventElapsedTime(&ms, ev[2 * t], ev[2 * t + 1]));
+        ms_sum += ms;
+    }
 #undef CAL_TRY
-    const double launches = (double)passes * n_buffers;
     const double bytes = (double)trips * 4096 * 16.0;                 // what one launch reads
-    if (gb_per_s) *gb_per_s = bytes * launches / (ms * 1e-3) / 1e9;
-    if (us_per_launch) *us_per_launch = ms * 1e3 / launches;
+    const double us = ms_sum * 1e3 / timed;                           // average duration of one launch
+    if (gb_per_s) *gb_per_s = bytes / (us * 1e-6) / 1e9;
+    if (us_per_launch) *us_per_launch = us;
     cleanup();
     return rc;
 }

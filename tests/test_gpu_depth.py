@@ -1,5 +1,6 @@
 """GPU parity AT DEPTH: the benchmarked LLaVA-1.5-7B-shaped model as configured (32 layers, 576 + 64 prompt rows,
-K = 5), and the Qwen2.5-VL-7B- and LLaVA-1.5-13B-shaped widths at 8 layers, against the CPU oracle.
+K = 5), the Qwen2.5-VL-7B- and LLaVA-1.5-13B-shaped widths at 8 layers, and the LLaVA-NeXT prompt (2880 visual + 128
+text rows) at 4 layers, against the CPU oracle.
 
 What depth adds over the 2-layer slices of test_gpu_parity.py is rounding that accumulates layer after layer: the
 quantity the tolerance (3e-2 x logit RMS for bf16 models) exists to bound.  Every logit of the prefill row, of the
@@ -102,4 +103,13 @@ def test_c5_widths_8_layers_batch4():
     8 layers, per-sequence acceptance with a different planted length per sequence."""
     cfg = synth.get_config("C5").scaled(n_layers=8, name="C5-widths-8-layers", gen_tokens=0, gen_cycles=8)
     sbs = run_depth_case(cfg, seed=0, plant=[2, 0, 3, 1])
+    assert max(sbs.max_err.values()) <= 1.0
+
+
+@pytest.mark.timeout(600)
+def test_c3_prompt_3008_rows_4_layers():
+    """LLaVA-NeXT-7B prompt shape (2880 visual + 128 text rows: 24 row blocks of the prefill GEMM's large tile, 24 row
+    blocks x 32 heads of the shared-tile prefill attention, 16 key splits per head in the verify attention) at 4 layers."""
+    cfg = synth.get_config("C3").scaled(n_layers=4, name="C3-rows-4-layers", gen_tokens=0, gen_cycles=8)
+    sbs = run_depth_case(cfg, seed=0, plant=[4])
     assert max(sbs.max_err.values()) <= 1.0

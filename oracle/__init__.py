@@ -8,5 +8,5 @@ from .model import (rmsnorm, rope, softmax_rows, attention, silu, KVCache, decod
                     argmax_lowest, Target, Drafter)
 from .hivis import (fuse, accept_length, HivisOracle, greedy_reference, top2_gap, softmax_temperature, sample_inverse_cdf,
                     speculative_accept, HivisSamplingOracle, sampling_reference)
-from .tree import (HivisTreeOracle, log_softmax, top_k_lowest, pool_size, ancestors_visible, accept_path)
+from .tree import (HivisTreeOracle, log_softmax, top_k_lowest, pool_size, ancestors_visible, accept_path, sample_tree_tokens)
 from . import rng

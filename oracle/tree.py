@@ -77,6 +77,19 @@ def accept_path(parents, tokens, target_tokens):
         path.append(cur)
 
 
+def sample_tree_tokens(logits, depths, T, u):
+    """Acceptance at T > 0 with a tree of DETERMINISTIC candidates (the tree is built from top-k choices, nothing in it
+    is drawn).  Section 2.1 describes the T > 0 rule for a chain of drawn drafts; for a tree the paper only reports
+    results (Table 2, T = 1), so this is a reading: after every visited row the target DRAWS its next token from
+    softmax(logits / T) by inversion, and a candidate child is followed exactly when it is the drawn token.  The
+    emitted tokens are then draws from the target's own distribution whatever the tree holds, and with the same
+    uniform numbers they are the very tokens token-by-token sampling emits (pinned in the tests).
+    One walk visits one row per depth, so row i (depth d_i, the root has depth 0) uses u[d_i].
+    Returns the drawn token after every row; accept_path() with these in place of the greedy tokens is the walk."""
+    from .hivis import softmax_temperature, sample_inverse_cdf
+    return [sample_inverse_cdf(softmax_temperature(np.asarray(logits[i], F64), T), float(u[int(depths[i])])) for i in range(len(depths))]
+
+
 class HivisTreeOracle(HivisOracle):
     """HivisOracle whose draft round builds a tree.  prefill() is inherited."""
 
@@ -191,6 +204,12 @@ class HivisTreeOracle(HivisOracle):
         self.f_next = self._refeed(np.asarray(g)[[0] + path], nxt, self.l)
         self.l += n + 1
         return n, emitted, path
+
+    def tree_accept_sample(self, g, logits, T, u, force=None):
+        """tree_accept with the target's tokens drawn at temperature T (see sample_tree_tokens); u: [depth + 1]."""
+        t = sample_tree_tokens(logits, [0] + self.tree["depths"], T, u)
+        n, emitted, path = self.tree_accept(g, t, force)
+        return n, emitted, path, t
 
     def tree_cycle(self, top_k, depth, n_nodes):
         tree = self.tree_draft(top_k, depth, n_nodes)

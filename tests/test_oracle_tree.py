@@ -260,3 +260,86 @@ def test_follow_mode_reproduces_own_choices():
     np.testing.assert_array_equal(ta["pool_tokens"], tb["pool_tokens"])
     np.testing.assert_allclose(ta["pool_scores"], tb["pool_scores"], rtol=0, atol=0)
     assert ta["parents"] == tb["parents"] and ta["tokens"] == tb["tokens"]
+
+
+# ---- acceptance at T > 0 (sample_tree_tokens: a reading, see its docstring) -------------------------------------
+
+def run_tree_sampling(cfg, w, vis, ids, shape, T, cycles, seed, plant=None):
+    """Tree cycles with drawn target tokens.  Returns (text after the first token, the uniforms in the order in which
+    emitted tokens consumed them, accepted lengths)."""
+    from oracle import sampling_reference
+    k, depth, n_nodes = shape
+    g = np.random.default_rng(seed)
+    o = HivisTreeOracle(cfg, w)
+    first, _ = o.prefill(vis, ids)
+    text, used, ns = [], [], []
+    for c in range(cycles):
+        u = g.random(depth + 1)
+        follow = None
+        if plant is not None and c in plant:
+            # a tree holding what token-by-token sampling with THESE uniforms is about to emit
+            ref = sampling_reference(cfg, w, vis, ids, 1 + len(text) + depth, T, [0.0] + used + list(u))
+            follow = planted_follow(o, k, depth, n_nodes, ref[1 + len(text): 1 + len(text) + plant[c]])
+        o.tree_draft(k, depth, n_nodes, follow=follow)
+        gfeat, logits, _ = o.tree_verify()
+        n, emitted, path, _ = o.tree_accept_sample(gfeat, logits, T, u)
+        assert len(emitted) == n + 1 and len(path) == n
+        text += emitted
+        used += list(u[: n + 1])
+        ns.append(n)
+    return first, text, used, ns
+
+
+def test_tree_sampling_emits_exactly_the_token_by_token_samples():
+    """With the same uniform numbers, tree cycles at T > 0 emit the very text that drawing one token at a time from
+    the target emits (the plain definition): own trees (mostly rejected at once), and planted trees whose first path
+    carries 1..depth of the coming samples (accepted exactly that far)."""
+    from oracle import sampling_reference
+    for seed, shape, T, plant in [(31, (3, 3, 7), 1.0, None), (32, (2, 4, 8), 0.7, {1: 2, 3: 4}), (33, (3, 3, 9), 1.3, {0: 3, 2: 1})]:
+        cfg, w, vis, ids = make(seed)
+        first, text, used, ns = run_tree_sampling(cfg, w, vis, ids, shape, T, 5, 100 + seed, plant)
+        ref = sampling_reference(cfg, w, vis, ids, 1 + len(text), T, [0.0] + used)
+        assert [first] + text == ref
+        if plant:
+            for c, m in plant.items():
+                assert ns[c] >= m                      # the planted prefix is followed (further only by coincidence)
+        # the state afterwards is a valid one: greedy chain cycles continue the text like a fresh prefill would
+        assert sum(ns) >= (sum(plant.values()) if plant else 0)
+
+
+def test_tree_sampling_first_token_distribution_is_the_targets():
+    """Over a fine grid of u_0 the first emitted token is distributed as softmax(logits / T) of the root row, whether or
+    not the tree holds it (the fraction of the grid that emits token x is p(x) within the grid's resolution)."""
+    from oracle import softmax_temperature
+    from oracle.tree import sample_tree_tokens
+    cfg, w, vis, ids = make(34)
+    o = HivisTreeOracle(cfg, w)
+    o.prefill(vis, ids)
+    o.tree_draft(3, 2, 6)
+    gfeat, logits, _ = o.tree_verify()
+    T = 0.9
+    p = softmax_temperature(logits[0], T)
+    n = 4000
+    counts = np.zeros(cfg.vocab)
+    accepted_mass = 0
+    kids = {o.tree["tokens"][i] for i in range(len(o.tree["tokens"])) if o.tree["parents"][i] == 0}
+    for i in range(n):
+        u = [(i + 0.5) / n, 0.5, 0.5]
+        t = sample_tree_tokens(logits, [0] + o.tree["depths"], T, u)
+        counts[t[0]] += 1
+        path = accept_path([-1] + o.tree["parents"], [o.text[-1]] + o.tree["tokens"], t)
+        accepted_mass += 1 if path else 0
+    assert np.max(np.abs(counts / n - p)) <= 1.0 / n + 1e-12
+    assert abs(accepted_mass / n - sum(p[x] for x in kids)) <= len(kids) / n + 1e-12      # followed iff the draw is a child's token
+
+
+def test_tree_sampling_cold_temperature_is_the_greedy_walk():
+    """T -> 0: the drawn tokens are the greedy ones (for any u away from 0 and 1), so the walk is tree_accept's."""
+    from oracle.tree import sample_tree_tokens
+    cfg, w, vis, ids = make(35)
+    o = HivisTreeOracle(cfg, w)
+    o.prefill(vis, ids)
+    o.tree_draft(3, 3, 9)
+    gfeat, logits, t_greedy = o.tree_verify()
+    t = sample_tree_tokens(logits, [0] + o.tree["depths"], 1e-4, [0.37, 0.81, 0.05, 0.5])
+    assert t == t_greedy

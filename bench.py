@@ -45,7 +45,7 @@ def run_step(hv, cfg, vis, ids, K, temperature=0.0, rng=None, tree=None):
         if tree:
             hv.tree_draft(*tree)
             hv.tree_verify()
-            n1, _ = hv.tree_accept()
+            n1, _ = hv.tree_accept_sample(temperature) if temperature > 0.0 else hv.tree_accept()
             n = np.array([n1], np.int64)
         elif temperature > 0.0:
             hv.draft_sample(K, temperature)

@@ -182,7 +182,7 @@ int hivis_accept_sample(hivis_ctx *ctx, float temperature, const float *u_accept
  * published counter-based generator Philox4x32-10 (Salmon et al., SC'11): key = (seed low word, seed high word), counter =
  * (index of the number in its array, purpose, call count low word, call count high word), uniform = top 24 bits of output
  * word 0 times 2^-24.  Purposes and array shapes: 0 = u_first [B]; 1 = u [B][K] (index b*K + i); 2 = u_accept [B][K];
- * 3 = u_resample [B].  Every sampling call that draws this way uses the context's call count once (u_accept and
+ * 3 = u_resample [B]; 4 = u of hivis_tree_accept_sample [depth + 1].  Every sampling call that draws this way uses the context's call count once (u_accept and
  * u_resample of one hivis_accept_sample share it) and then increments it; hivis_rng_seed resets it to 0.  Nothing crosses
  * the host-device link.  calls_so_far (may be NULL) receives the count before the reset.
  * Errors: EINVAL (null ctx).  A sampling call with NULL uniforms before any hivis_rng_seed: ESTATE; with only one of
@@ -222,6 +222,18 @@ int hivis_tree_verify(hivis_ctx *ctx);
  *   n_accepted: [1] int32 host.   tokens: [depth+1] int32 host (entries beyond n are -1).
  * Errors: ESTATE, EINVAL, EHIP. */
 int hivis_tree_accept(hivis_ctx *ctx, int32_t *n_accepted, int32_t *tokens);
+
+/* hivis_tree_accept at a temperature T > 0.  Table 2 reports T = 1 results with a tree, the paper does not spell the rule
+ * out; the reading implemented: the tree holds deterministic candidates, so after every visited row the target DRAWS its
+ * next token from softmax(logits of that row / T) by inversion, and a candidate child is followed exactly when it is the
+ * drawn token; the walk ends with the first draw that is no child.  The emitted tokens are draws from the target's own
+ * distribution whatever the tree holds: with the same uniforms they are the tokens that drawing one token at a time
+ * emits.  A row of depth j (root: 0) draws with u[j].
+ *   u: [depth + 1] float32 host, each in [0, 1) (depth as given to hivis_tree_draft, or the depth of the planted tree);
+ *      NULL after hivis_rng_seed: drawn on the device (purpose 4, index j).  Outputs, state and errors as hivis_tree_accept,
+ *      plus EINVAL for T <= 0 or a uniform outside [0, 1).  hivis_tree_get afterwards returns the DRAWN tokens as
+ *      target_tokens. */
+int hivis_tree_accept_sample(hivis_ctx *ctx, float temperature, const float *u, int32_t *n_accepted, int32_t *tokens);
 
 /* ---- test / measurement hooks (all synchronise) ---- */
 

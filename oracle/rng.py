@@ -21,7 +21,7 @@ W0, W1 = 0x9E3779B9, 0xBB67AE85
 MASK = 0xFFFFFFFF
 
 # purposes (counter word 1)
-FIRST_TOKEN, DRAFT, ACCEPT, RESAMPLE = 0, 1, 2, 3
+FIRST_TOKEN, DRAFT, ACCEPT, RESAMPLE, TREE = 0, 1, 2, 3, 4
 
 
 def philox4x32_10(counter, key):

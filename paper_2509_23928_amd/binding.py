@@ -69,6 +69,7 @@ def load_library(path=LIB_PATH):
         "hivis_tree_set": (C.c_int, [P, I32, P, P]),
         "hivis_tree_verify": (C.c_int, [P]),
         "hivis_tree_accept": (C.c_int, [P, P, P]),
+        "hivis_tree_accept_sample": (C.c_int, [P, C.c_float, P, P, P]),
         "hivis_tree_get": (C.c_int, [P, P, P, P, P, P, P, P, P, P]),
         "hivis_tree_get_logits": (C.c_int, [P, P]),
         "hivis_get_logits": (C.c_int, [P, I32, P]),
@@ -93,7 +94,7 @@ def load_library(path=LIB_PATH):
 
 
 EXPORTED_SYMBOLS = ("hivis_create", "hivis_destroy", "hivis_prefill", "hivis_draft", "hivis_draft_noalloc", "hivis_set_drafts",
-                    "hivis_verify", "hivis_accept", "hivis_prefill_sample", "hivis_draft_sample", "hivis_accept_sample", "hivis_rng_seed", "hivis_tree_draft", "hivis_tree_set", "hivis_tree_verify", "hivis_tree_accept", "hivis_tree_get", "hivis_tree_get_logits", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
+                    "hivis_verify", "hivis_accept", "hivis_prefill_sample", "hivis_draft_sample", "hivis_accept_sample", "hivis_rng_seed", "hivis_tree_draft", "hivis_tree_set", "hivis_tree_verify", "hivis_tree_accept", "hivis_tree_accept_sample", "hivis_tree_get", "hivis_tree_get_logits", "hivis_get_logits", "hivis_get_hidden", "hivis_kv_lengths",
                     "hivis_get_tokens", "hivis_timing", "hivis_phase_ms", "hivis_kernel_timing", "hivis_kernel_ms", "hivis_algorithmic_bytes", "hivis_clamp_token", "hivis_calib_stream",
                     "hivis_last_error", "hivis_version")
 
@@ -276,6 +277,15 @@ class Hivis:
         n = np.zeros(1, np.int32)
         t = np.zeros(self.tree_shape[1] + 1, np.int32)
         self._check(self.lib.hivis_tree_accept(self.ctx, _ptr(n), _ptr(t)))
+        return int(n[0]), t
+
+    def tree_accept_sample(self, temperature, u=None):
+        """tree_accept() with the target's tokens drawn at `temperature`; u: [depth+1] uniforms, one per depth (None after
+        rng_seed: drawn on the device).  Returns (n_accepted, tokens [depth+1])."""
+        n = np.zeros(1, np.int32)
+        t = np.zeros(self.tree_shape[1] + 1, np.int32)
+        uu = None if u is None else np.ascontiguousarray(u, dtype=np.float32).reshape(self.tree_shape[1] + 1)
+        self._check(self.lib.hivis_tree_accept_sample(self.ctx, float(temperature), _ptr(uu), _ptr(n), _ptr(t)))
         return int(n[0]), t
 
     def tree_get(self, verified=False):

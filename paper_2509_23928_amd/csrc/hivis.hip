@@ -82,6 +82,7 @@ struct hivis_ctx {
     int32_t* h_result = nullptr;         // pinned host mirror of [nacc | out_tok | abort flag | bad-logits flag]
     int* bad = nullptr;                  // device flag: a greedy-token kernel met a row without a finite maximum (cleared by hivis_prefill)
     bool rng_seeded = false; unsigned long long rng_seed = 0, rng_calls = 0;   // device-side uniforms (hivis_rng_seed): Philox key and draw-call count
+    float* u_tree = nullptr;             // [TREE_MAX_DEPTH + 1] uniforms of hivis_tree_accept_sample, one per depth
     float *u_draft = nullptr, *u_acc = nullptr, *u_res = nullptr;   // uniform numbers of the sampling calls: [B][k_max], [B][k_max] (row stride K), [B]
     float inv_temp = 1.0f; bool drafts_sampled = false;             // set by hivis_draft_sample; hivis_accept_sample needs the drafter's distributions
     void* vis = nullptr;        // staging for vis_embeds [B][max_vis][d]
@@ -1349,12 +1350,16 @@ int do_tree_verify(hivis_ctx* c) {
 }
 
 template <typename WT>
-int do_tree_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
+int do_tree_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens, bool sample) {
     typedef typename KVType<WT>::type KT;
     const hivis_config& g = c->cfg;
     const int d = g.d, N = c->tn, depth = c->tdepth;
     PhaseTimer pt(c, 3);
     const TreeDev& t = c->tree;
+    // T > 0: the token the target DRAWS after every row replaces its greedy token (row of depth j: uniform u_tree[j]);
+    // the walk below is the same: a candidate is followed when it is the token after its parent row
+    if (sample) hipLaunchKernelGGL(sample_rows_kernel, dim3(N + 1), dim3(SAMPLE_NT), 0, c->stream, (const float*)c->logits_v, g.vocab, c->inv_temp,
+                                   (const float*)c->u_tree, 1, t.ttok, 1, (const int32_t*)t.row_depth);
     hipLaunchKernelGGL(tree_accept_kernel, dim3(1), dim3(64), 0, c->stream, N, depth, c->text, (const int*)c->dlen, t);
     // target cache: the followed rows move to the slots right after the root's
     for (int scatter = 0; scatter < 2; ++scatter)
@@ -1477,6 +1482,7 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     if ((rc = dev_alloc(c, &c->u_draft, (size_t)B * g.k_max))) return rc;
     if ((rc = dev_alloc(c, &c->u_acc, (size_t)B * g.k_max))) return rc;
     if ((rc = dev_alloc(c, &c->u_res, (size_t)B))) return rc;
+    if ((rc = dev_alloc(c, &c->u_tree, (size_t)TREE_MAX_DEPTH + 1))) return rc;
     // accepted counts and emitted tokens share one block, so one device-to-host copy into pinned memory returns both
     if ((rc = dev_alloc(c, &c->nacc, (size_t)B + (size_t)B * (g.k_max + 1)))) return rc;
     c->out_tok = c->nacc + B;
@@ -1786,7 +1792,21 @@ int hivis_tree_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens) {
     if (!c) return HIVIS_EINVAL;
     if (c->state != ST_TREE_VERIFIED) return fail(c, HIVIS_ESTATE, "hivis_tree_accept needs a verified tree");
     if (!n_accepted || !tokens) return fail(c, HIVIS_EINVAL, "null output pointer");
-    return DISPATCH(c, do_tree_accept, c, n_accepted, tokens);
+    return DISPATCH(c, do_tree_accept, c, n_accepted, tokens, false);
+}
+
+int hivis_tree_accept_sample(hivis_ctx* c, float temperature, const float* u, int32_t* n_accepted, int32_t* tokens) {
+    if (!c) return HIVIS_EINVAL;
+    if (c->state != ST_TREE_VERIFIED) return fail(c, HIVIS_ESTATE, "hivis_tree_accept_sample needs a verified tree");
+    if (!n_accepted || !tokens) return fail(c, HIVIS_EINVAL, "null output pointer");
+    if (!(temperature > 0.0f)) return fail(c, HIVIS_EINVAL, "temperature must be positive");
+    const int n = c->tdepth + 1;
+    if (u) {
+        if (int rc = check_uniforms(c, u, (size_t)n, "u")) return rc;
+        HIP_TRY(c, hipMemcpyAsync(c->u_tree, u, (size_t)n * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    } else if (int rc = rng_fill(c, c->u_tree, n, 1, 1, 4u, nullptr, 0, 0u)) return rc;
+    c->inv_temp = 1.0f / temperature;
+    return DISPATCH(c, do_tree_accept, c, n_accepted, tokens, true);
 }
 
 int hivis_tree_get(hivis_ctx* c, int32_t* pool_tokens, int32_t* pool_parents, float* pool_scores, int32_t* expand, int32_t* selected,

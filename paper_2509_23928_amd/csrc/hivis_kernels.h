@@ -1376,13 +1376,17 @@ __device__ __forceinline__ int block_sample_softmax(const float* __restrict__ x,
     return block_sample_inverse_cdf<NT>([&](int j) { return expf(x[j] * it - m); }, V, u, smf, smi);
 }
 constexpr int SAMPLE_NT = 512;
+// (u_index, optional: row r draws with u[u_index[r] * u_stride] instead of u[r * u_stride]; the rows of a draft tree draw
+//  with the uniform of their depth)
 __global__ __launch_bounds__(SAMPLE_NT) void sample_rows_kernel(const float* __restrict__ logits, int V, float inv_temp,
                                                                 const float* __restrict__ u, int u_stride,
-                                                                int32_t* __restrict__ out, int out_stride) {
+                                                                int32_t* __restrict__ out, int out_stride,
+                                                                const int32_t* __restrict__ u_index = nullptr) {
     __shared__ float smf[SAMPLE_NT / 64];
     __shared__ int smi[SAMPLE_NT / 64];
     const int row = blockIdx.x;
-    const int tok = block_sample_softmax<SAMPLE_NT>(logits + (size_t)row * V, V, inv_temp, u[(size_t)row * u_stride], smf, smi);
+    const int ui = u_index ? u_index[row] : row;
+    const int tok = block_sample_softmax<SAMPLE_NT>(logits + (size_t)row * V, V, inv_temp, u[(size_t)ui * u_stride], smf, smi);
     if (threadIdx.x == 0) out[(size_t)row * out_stride] = tok;
 }
 

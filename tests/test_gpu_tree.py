@@ -9,8 +9,9 @@ import numpy as np
 import pytest
 
 import synth
-from oracle import greedy_reference
-from oracle.tree import HivisTreeOracle, accept_path, log_softmax, pool_size, top_k_lowest
+from oracle import greedy_reference, sampling_reference, softmax_temperature
+from oracle import rng as orng
+from oracle.tree import HivisTreeOracle, accept_path, log_softmax, pool_size, sample_tree_tokens, top_k_lowest
 from parity_utils import check_token, logit_tol
 from test_gpu_parity import small_bf16
 
@@ -41,6 +42,8 @@ class TreeSideBySide:
         self.near_ties = 0
         self.n_hist = []
         self.max_err = {"draft": 0.0, "score": 0.0, "verify": 0.0, "g": 0.0, "fnext": 0.0}
+        self.draws = self.edge = 0
+        self.used_u = []                    # uniforms in the order in which emitted tokens consumed them (sampling cycles)
         self._check_fnext()
 
     def _check_fnext(self):
@@ -51,8 +54,10 @@ class TreeSideBySide:
         self.max_err["fnext"] = max(self.max_err["fnext"], rel / lim)
         assert rel <= lim, f"drafter pending hidden state off by {rel}"
 
-    def _verify_accept(self, tokens, parents, depth):
-        """Shared tail of a cycle: the oracle's tree (self.o.tree) already equals the library's."""
+    def _verify_accept(self, tokens, parents, depth, sample=None):
+        """Shared tail of a cycle: the oracle's tree (self.o.tree) already equals the library's.
+        sample = (T, u): acceptance at temperature T; u = [depth+1] uniforms handed to the library, or a callable that
+        returns the uniforms the library must have drawn itself (then it is given none)."""
         cfg, hv, o = self.cfg, self.hv, self.o
         hv.tree_verify()
         N = len(tokens)
@@ -73,7 +78,30 @@ class TreeSideBySide:
         ttok = tr["target_tokens"]
         for i in range(N + 1):
             self.near_ties += check_token(ttok[i], ologits[i], tol)
-        n, toks = hv.tree_accept()
+        if sample is None:
+            n, toks = hv.tree_accept()
+        else:
+            # every row's token is DRAWN: re-drawn here in float64 from the library's own float32 logits with the same
+            # uniform (row of depth j: u[j]); a difference only within 1e-5 of a boundary of the running sum
+            T, u = sample
+            if callable(u):
+                n, toks = hv.tree_accept_sample(T, None)
+                u = u()
+            else:
+                n, toks = hv.tree_accept_sample(T, u)
+            ttok = hv.tree_get(verified=True)["target_tokens"]
+            dep = [0] + [int(x) for x in tr["row_depths"][1:]]
+            mine = sample_tree_tokens(vlog.astype(np.float64), dep, T, u)
+            for i in range(N + 1):
+                self.draws += 1
+                if mine[i] != int(ttok[i]):
+                    pr = softmax_temperature(vlog[i].astype(np.float64), T)
+                    c = np.cumsum(pr)
+                    lo, hi = min(mine[i], int(ttok[i])), max(mine[i], int(ttok[i]))
+                    assert np.min(np.abs(c[lo:hi] - float(u[dep[i]]) * c[-1])) <= 1e-5 * c[-1], (i, mine[i], int(ttok[i]))
+                    self.edge += 1
+            self.used_u += [float(x) for x in u[: n + 1]]
+            ot = [int(x) for x in ttok]
         # acceptance: bit-exact given the library's own target tokens
         path = accept_path([-1] + list(parents), [o.text[-1]] + list(tokens), ttok)
         exp = [int(tokens[r - 1]) for r in path] + [int(ttok[path[-1] if path else 0])]
@@ -86,7 +114,7 @@ class TreeSideBySide:
         self._check_fnext()
         return n, path
 
-    def cycle(self, k, depth, N):
+    def cycle(self, k, depth, N, sample=None):
         cfg, hv, o = self.cfg, self.hv, self.o
         hv.tree_draft(k, depth, N)
         tr = hv.tree_get()
@@ -123,16 +151,16 @@ class TreeSideBySide:
         self.max_err["score"] = max(self.max_err["score"], serr / (2 * tol * depth))
         assert serr <= 2 * tol * depth
         assert list(tr["row_tokens"][1:]) == ot["tokens"] and list(tr["row_parents"][1:]) == ot["parents"] and list(tr["row_depths"][1:]) == ot["depths"]
-        return self._verify_accept(ot["tokens"], ot["parents"], depth)
+        return self._verify_accept(ot["tokens"], ot["parents"], depth, sample)
 
-    def planted_cycle(self, tokens, parents):
+    def planted_cycle(self, tokens, parents, sample=None):
         o = self.o
         self.hv.tree_set(tokens, parents)
         depths = {0: 0}
         for i, p in enumerate(parents, start=1):
             depths[i] = depths[int(p)] + 1
         o.tree = {"tokens": [int(t) for t in tokens], "parents": [int(p) for p in parents], "depths": [depths[i] for i in range(1, len(tokens) + 1)]}
-        return self._verify_accept(o.tree["tokens"], o.tree["parents"], max(depths.values()))
+        return self._verify_accept(o.tree["tokens"], o.tree["parents"], max(depths.values()), sample)
 
 
 def branching_plant(ref, done, vocab, good, shape):
@@ -377,3 +405,72 @@ def test_tree_qwen_vocabulary():
     t.cycle(10, 3, 40)
     t.cycle(16, 2, 63)
     print("V=152064 tree max error / tolerance:", t.max_err, "accepted:", t.n_hist, "near ties:", t.near_ties)
+
+
+def run_tree_sampling(cfg, seed, T, shapes, plant, device_seed=None):
+    """Tree cycles accepted at temperature T.  shapes: one (k, depth, N) per cycle; plant: {cycle: m}: that cycle runs a
+    planted branching tree whose followed path carries the next m tokens that token-by-token sampling with the cycle's
+    uniforms emits.  device_seed: the library draws the uniforms itself (call c of the context)."""
+    t = TreeSideBySide(cfg, seed)
+    g = np.random.default_rng(500 + seed)
+    if device_seed is not None:
+        assert t.hv.rng_seed(device_seed) == 0
+    for c, (k, depth, N) in enumerate(shapes):
+        if c in plant:
+            m = plant[c]
+            depth = m + 1                                  # branching_plant: m path levels and one level of wrong tokens
+        u = orng.uniforms(device_seed, c, orng.TREE, depth + 1) if device_seed is not None else g.random(depth + 1).astype(np.float32)
+        give = (lambda uu=u: uu) if device_seed is not None else u
+        if c in plant:
+            done = len(t.emitted)
+            ref = sampling_reference(cfg, t.w, t.vis[0], t.ids[0], done + m + 1, T, [0.0] + t.used_u + [float(x) for x in u])
+            assert ref[:done] == t.emitted, "the text so far is not what token-by-token sampling emits"
+            toks, pars = branching_plant(ref, done, cfg.vocab, m, 3)
+            n, _ = t.planted_cycle(toks, pars, sample=(T, give))
+            if t.edge == 0:
+                assert n == m
+        else:
+            t.cycle(k, depth, N, sample=(T, give))
+    if t.edge == 0 and t.near_ties == 0:
+        ref = sampling_reference(cfg, t.w, t.vis[0], t.ids[0], len(t.emitted), T, [0.0] + t.used_u)
+        assert t.emitted == ref, "tree cycles at T > 0 must emit what drawing one token at a time emits with the same uniforms"
+    if device_seed is not None:
+        assert t.hv.rng_seed(0) == len(shapes)
+    return t
+
+
+def test_tree_sampling_tiny_fp32_host_uniforms():
+    cfg = c1(n_vis=40, n_text=19, n_q_heads=4, n_kv_heads=2)
+    t = run_tree_sampling(cfg, 61, 1.0, [(3, 3, 9), (4, 2, 12), (2, 4, 7), (3, 3, 9), (5, 3, 31), (3, 2, 6)], {1: 2, 3: 4, 5: 1})
+    print("tree sampling fp32:", t.max_err, "accepted:", t.n_hist, "draws:", t.draws, "edge:", t.edge)
+    assert t.n_hist[1] >= 2 and t.n_hist[3] >= 4
+
+
+def test_tree_sampling_bf16_device_uniforms():
+    cfg = small_bf16(K=4)
+    t = run_tree_sampling(cfg, 62, 0.8, [(3, 3, 9), (4, 3, 20), (2, 2, 4), (10, 3, 40)], {1: 3, 2: 1}, device_seed=0xC0FFEE1234)
+    print("tree sampling bf16, device-drawn uniforms:", t.max_err, "accepted:", t.n_hist, "draws:", t.draws, "edge:", t.edge)
+
+
+def test_tree_accept_sample_error_codes():
+    from paper_2509_23928_amd import HivisError, HIVIS_EINVAL, HIVIS_ESTATE
+    cfg = c1(n_vis=10, n_text=9, n_q_heads=4, n_kv_heads=2)
+    w, vis, ids, hv = make_tree(cfg, 63, 100)
+    hv.prefill(vis, ids)
+    hv.tree_draft(3, 2, 6)
+    with pytest.raises(HivisError) as e:
+        hv.tree_accept_sample(1.0, [0.5, 0.5, 0.5])                  # not verified yet
+    assert e.value.code == HIVIS_ESTATE
+    hv.tree_verify()
+    with pytest.raises(HivisError) as e:
+        hv.tree_accept_sample(0.0, [0.5, 0.5, 0.5])
+    assert e.value.code == HIVIS_EINVAL
+    with pytest.raises(HivisError) as e:
+        hv.tree_accept_sample(1.0, [0.5, 1.0, 0.5])
+    assert e.value.code == HIVIS_EINVAL
+    with pytest.raises(HivisError) as e:
+        hv.tree_accept_sample(1.0, None)                             # no seed given yet
+    assert e.value.code == HIVIS_ESTATE
+    n, toks = hv.tree_accept_sample(1.0, [0.5, 0.5, 0.5])
+    assert 0 <= n <= 2 and all(int(x) >= 0 for x in toks[: n + 1])
+    hv.close()

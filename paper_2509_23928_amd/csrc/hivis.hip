@@ -59,6 +59,8 @@ struct hivis_ctx {
     // weights
     void* embed = nullptr; void* final_norm = nullptr; void* rho = nullptr;
     uint4* lm_head = nullptr; uint4* fuse_w = nullptr;
+    uint4* fuse_w1 = nullptr;            // rows [0, d) of the fusion FC, packed on their own (K = d), and
+    float* emb_w2 = nullptr;             // [V][d] fp32: Embed(token) . w2, the embedding half of the fusion FC per token (bf16 models)
     std::vector<LayerDev> layers; LayerDev draft;
     std::vector<KVDev> tkv; KVDev dkv;
 
@@ -620,6 +622,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
                 fu.Y = u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = std::min(i, g.n_resid - 1);
                 if (fold) {
                     fu.emb = c->embed; fu.tok = c->drafts + (i - 1); fu.tok_sseq = g.k_max; fu.tok_srow = 0;
+                    if (c->emb_w2) { fu.emb = nullptr; fu.add_rows = c->emb_w2; fu.K = d; fu.W = c->fuse_w1; }     // embedding half from the table
                     if (in_fc) { fu.tok = nullptr; fu.pm = lm.pm; fu.pi = lm.pi; fu.ncand = G; fu.tok_out = c->drafts + (i - 1); fu.o_sseq = g.k_max; fu.o_srow = 0; }
                 }
                 else {
@@ -637,7 +640,10 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
         float* u = pool.take((size_t)M * d);
         Phase fu{}; fu.type = PH_GEMM; fu.pro = PRO_PLAIN; fu.epi = FEPI_ADDVEC; fu.K = 2 * d; fu.N = d; fu.W = c->fuse_w; fu.A = c->catT; fu.lda = 2 * d;
         fu.Y = u; fu.ldy = d; fu.vec = c->rho; fu.vec_idx = 0;
-        if (fold) { fu.emb = c->embed; fu.tok = c->next_tok; fu.tok_sseq = g.k_max + 1; fu.tok_srow = 1; }
+        if (fold) {
+            fu.emb = c->embed; fu.tok = c->next_tok; fu.tok_sseq = g.k_max + 1; fu.tok_srow = 1;
+            if (c->emb_w2) { fu.emb = nullptr; fu.add_rows = c->emb_w2; fu.K = d; fu.W = c->fuse_w1; }
+        }
         else {
             Phase pr{}; pr.type = PH_PREP; pr.ids = c->next_tok; pr.id_sseq = g.k_max + 1; pr.id_srow = 1; pr.gain = c->embed;
             pr.Y = c->catT + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = 0;
@@ -1385,6 +1391,42 @@ int do_tree_accept(hivis_ctx* c, int32_t* n_accepted, int32_t* tokens, bool samp
     return HIVIS_OK;
 }
 
+// The fusion FC is linear in its two halves: [f ; Embed(x)] [w1 ; w2] = f w1 + Embed(x) w2 (section 3.2), and the second
+// term depends on the token alone.  For bf16 models the table T[x] = Embed(x) w2 ([V][d], fp32: bf16 x bf16 products summed
+// in fp32) is computed here once, with the prefill's GEMM over ranges of embedding rows, and the phase programs' FC then
+// streams w1 only (d x d instead of 2d x d per step) and adds T[x] in its epilogue.  HIVIS_EMB_TABLE=0 keeps the full FC.
+template <typename WT>
+int build_embed_fc_table(hivis_ctx* c, const hivis_weights* w) {
+    if constexpr (sizeof(WT) != 2) return HIVIS_OK;
+    const hivis_config& g = c->cfg;
+    const int d = g.d, V = g.vocab;
+    { const char* e = getenv("HIVIS_EMB_TABLE"); if (e && e[0] == '0') return HIVIS_OK; }
+    if (!c->fused || c->persistent || !c->pf_frag || c->pf_rows < 8) return HIVIS_OK;
+    void* staging = nullptr;
+    HIP_TRY(c, hipMalloc(&staging, (size_t)d * d * sizeof(WT) + 4096));
+    uint4* w2p = nullptr;
+    int rc = HIVIS_OK;
+    do {
+        { const void* s[1] = {w->fuse_w}; int n[1] = {d};
+          if ((rc = pack_matrix<WT>(c, s, n, 1, d, 0, staging, &c->fuse_w1))) break; }
+        { const void* s[1] = {(const WT*)w->fuse_w + (size_t)d * d}; int n[1] = {d};
+          if ((rc = pack_matrix<WT>(c, s, n, 1, d, 0, staging, &w2p))) break; }
+        float* table = nullptr;
+        if ((rc = dev_alloc(c, &table, (size_t)V * d))) break;
+        const int R = c->pf_rows;                                  // rows per GEMM: what the prefill buffers hold
+        for (int r0 = 0; r0 < V && !rc; r0 += R) {
+            const int n = std::min(R, V - r0);
+            hipLaunchKernelGGL((rows_to_f32_kernel<WT>), dim3(1024), dim3(256), 0, c->stream, (const WT*)c->embed + (size_t)r0 * d, (size_t)n * d, c->pf_x);
+            rc = tall_gemm(c, c->pf_x, d, n, d, w2p, d, table + (size_t)r0 * d, d);
+        }
+        if (rc) break;
+        if (hipStreamSynchronize(c->stream) != hipSuccess) { rc = fail(c, HIVIS_EHIP, "building the embedding table of the fusion FC failed"); break; }
+        c->emb_w2 = table;
+    } while (0);
+    (void)hipFree(staging);
+    return rc;
+}
+
 template <typename WT>
 int do_create(hivis_ctx* c, const hivis_weights* w) {
     const hivis_config& g = c->cfg;
@@ -1501,6 +1543,7 @@ int do_create(hivis_ctx* c, const hivis_weights* w) {
     }
     if ((rc = fused_setup<WT>(c))) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if ((rc = build_embed_fc_table<WT>(c, w))) return rc;
     return HIVIS_OK;
 }
 
@@ -1930,7 +1973,9 @@ int hivis_algorithmic_bytes(hivis_ctx* c, double* verify_bytes, double* draft_st
     double kv_t = 0, kv_d = 0;
     for (int s = 0; s < g.batch; ++s) { kv_t += 2.0 * c->h_tlen[s] * kd * b * g.n_layers; kv_d += 2.0 * c->h_dlen[s] * kd * b; }
     if (verify_bytes) *verify_bytes = g.n_layers * w_layer + V * d * b + kv_t;
-    if (draft_step_bytes) *draft_step_bytes = w_layer + 2 * d * d * b + V * d * b + kv_d;
+    // fusion FC: [2d x d] weights, or with the per-token table of its embedding half [d x d] and one fp32 table row per sequence
+    const double fc = c->emb_w2 ? d * d * b + g.batch * d * 4.0 : 2 * d * d * b;
+    if (draft_step_bytes) *draft_step_bytes = w_layer + fc + V * d * b + kv_d;
     return HIVIS_OK;
 }
 

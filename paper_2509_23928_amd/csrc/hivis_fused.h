@@ -39,6 +39,10 @@ struct Phase {
     // ADDVEC (fusion FC), optional: columns [K/2, K) of activation row (seq, i) are row tok[seq*tok_sseq + i*tok_srow] of
     // the embedding table emb ([vocab][K/2], weight dtype) instead of A's: the gather of Embed(x) needs no launch
     const void* emb; const int32_t* tok; int tok_sseq, tok_srow;
+    // ADDVEC, alternative to emb: the embedding half of the fusion FC as a table.  [f ; e] [w1 ; w2] = f w1 + e w2, and
+    // e w2 depends on the token alone, so add_rows[token][N] (fp32, computed once at create) is ADDED in the epilogue and
+    // the GEMM runs over f's K = d only: half the weight bytes per step.  The token of a row as for emb (tok, or reduced).
+    const float* add_rows;
     // ... and if tok is null the token of row r is the greedy token of the LM-head phase before it, reduced here from
     // that phase's per-workgroup candidates pm / pi ([row][ncand]); workgroup 0 also stores it to tok_out
     int ncand;
@@ -368,7 +372,12 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
 #define HIVIS_STAGE(ps, nx, do_ssq) HIVIS_STAGE_FROM(ps, araw, graw, do_ssq, if ((nx) >= 0) HIVIS_LOAD_RAW(nx))
     // Tokens = greedy tokens of the LM-head phase before this one (fusion FC with ph.tok == null): every wavefront
     // reduces that phase's candidates itself (lowest index wins ties); workgroup 0 also stores them.
-    const bool cand_tokens = EPI == FEPI_ADDVEC && ph.emb != nullptr && ph.tok == nullptr;
+    const bool cand_tokens = EPI == FEPI_ADDVEC && (ph.emb != nullptr || ph.add_rows != nullptr) && ph.tok == nullptr;
+    // the token of THIS thread's epilogue row (all of a thread's epilogue slots serve one row), for the table form
+    const int row_e = min(RPL * (((int)threadIdx.x / RPL & 63) >> 4) + (int)threadIdx.x % RPL, M - 1);
+    int tok_e = 0;
+    if (EPI == FEPI_ADDVEC && ph.add_rows != nullptr && ph.tok != nullptr)
+        tok_e = __hip_atomic_load(&ph.tok[(row_e / pp.m) * ph.tok_sseq + (row_e % pp.m) * ph.tok_srow], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     auto reduce_tokens = [&]() {
         for (int r = 0; r < M; ++r) {
             float bv = -INFINITY; int bi = 0x7FFFFFFF;
@@ -387,6 +396,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             }
 #pragma unroll
             for (int q = 0; q < QM; ++q) if (row0 + q * RS == r) tokr[q] = bi;
+            if (r == row_e) tok_e = bi;
         }
     };
     // The tokens come first: a tiny model's first K pass already reads embedding rows, and for the others requesting the
@@ -480,6 +490,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             const int idx = threadIdx.x + sl * NT, r = idx % RPL, ln = (idx / RPL) & 63, g = idx / (RPL * 64);
             const int row = min(RPL * (ln >> 4) + r, M - 1), col = min((tg + g) * 16 + (ln & 15), N - 1);
             if (epi == FEPI_ADD_TO) epi_a[sl] = ph.R[(size_t)row * ph.ldr + col];
+            else if (epi == FEPI_ADDVEC && ph.add_rows != nullptr) epi_a[sl] = ph.add_rows[(size_t)clamp_token(tok_e, pp.V) * N + col];
             else if (epi == FEPI_QKV) {
                 const int p2 = (col % pp.hd) >> 1;
                 const int seq_ = row / pp.m;
@@ -542,7 +553,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             switch (epi) {
             case FEPI_STORE: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v); break;
             case FEPI_ADD_TO: st_wt(&ph.Y[(size_t)row * ph.ldy + col], epi_a[sl] + v); break;
-            case FEPI_ADDVEC: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v + to_f32(((const WT*)ph.vec)[(size_t)ph.vec_idx * N + col])); break;
+            case FEPI_ADDVEC: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v + to_f32(((const WT*)ph.vec)[(size_t)ph.vec_idx * N + col]) + epi_a[sl]); break;
             case FEPI_LOGITS:
                 st_wt(&ph.Y[(size_t)row * ph.ldy + col], v);
                 if (v > best_v || (v == best_v && col < best_i)) { best_v = v; best_i = col; }

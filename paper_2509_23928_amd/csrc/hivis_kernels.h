@@ -1175,6 +1175,13 @@ __global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ l
     }
 }
 
+// dst[i] = src[i] widened to fp32 (a range of embedding rows, as the A operand of the GEMM that folds the embedding half
+// of the fusion FC into a table)
+template <typename WT>
+__global__ void rows_to_f32_kernel(const WT* __restrict__ src, size_t n, float* __restrict__ dst) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = to_f32(src[i]);
+}
+
 // rows[r][0..d) = table[ids[r]]  (embedding gather, converted to fp32)
 template <typename WT>
 __global__ void gather_rows_kernel(const WT* __restrict__ table, const int32_t* __restrict__ ids, int id_stride,

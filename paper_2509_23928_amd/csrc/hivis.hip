@@ -1973,9 +1973,8 @@ int hivis_algorithmic_bytes(hivis_ctx* c, double* verify_bytes, double* draft_st
     double kv_t = 0, kv_d = 0;
     for (int s = 0; s < g.batch; ++s) { kv_t += 2.0 * c->h_tlen[s] * kd * b * g.n_layers; kv_d += 2.0 * c->h_dlen[s] * kd * b; }
     if (verify_bytes) *verify_bytes = g.n_layers * w_layer + V * d * b + kv_t;
-    // fusion FC: [2d x d] weights, or with the per-token table of its embedding half [d x d] and one fp32 table row per sequence
-    const double fc = c->emb_w2 ? d * d * b + g.batch * d * 4.0 : 2 * d * d * b;
-    if (draft_step_bytes) *draft_step_bytes = w_layer + fc + V * d * b + kv_d;
+    // (the method's bytes: the fusion FC as [2d x d] weights, also where the library reads only w1 and a table row per sequence)
+    if (draft_step_bytes) *draft_step_bytes = w_layer + 2 * d * d * b + V * d * b + kv_d;
     return HIVIS_OK;
 }
 

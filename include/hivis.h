@@ -90,6 +90,9 @@ typedef struct {
 /* Create a context: validates the config, allocates device state (weights re-laid-out for
  * streaming, target KV for max_vis+max_text positions, drafter KV for max_text positions) and
  * copies the weights from host memory.  hip_stream: a hipStream_t (NULL = the default stream).
+ * For bf16 models it also computes, once, the table Embed(x) w2 of the fusion's embedding half (section 3.2: e^ is linear
+ * in its two inputs, and Embed(x) w2 depends on the token alone): vocab x d float32 values of device memory
+ * (0.5 GB for a 32000 x 4096 model), so that a draft step streams w1 only.
  * Errors: HIVIS_EINVAL, HIVIS_EHIP (then *out is NULL). */
 int hivis_create(const hivis_config *cfg, const hivis_weights *w, void *hip_stream, hivis_ctx **out);
 

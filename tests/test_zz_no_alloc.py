@@ -6,7 +6,7 @@ the second on a smaller input (shorter prompt, fewer visual rows, smaller K), so
 scratch contents the first one left behind.  The kernels and their order are the same on both sides, so the drafted
 tokens must be identical and the logits equal within the float tolerance of the parity tests (in practice bit-equal);
 the pending state afterwards (cache lengths, verify logits of the drafted rows, next hidden state) must agree too.
-Round 1 of B is also checked against the CPU oracle."""
+The first of B's two draft rounds is also checked against the CPU oracle."""
 import numpy as np
 import pytest
 

@@ -1412,7 +1412,12 @@ int build_embed_fc_table(hivis_ctx* c, const hivis_weights* w) {
         { const void* s[1] = {(const WT*)w->fuse_w + (size_t)d * d}; int n[1] = {d};
           if ((rc = pack_matrix<WT>(c, s, n, 1, d, 0, staging, &w2p))) break; }
         float* table = nullptr;
-        if ((rc = dev_alloc(c, &table, (size_t)V * d))) break;
+        {   // no room for the table is not an error: the FC then keeps multiplying the embedding half
+            void* q = nullptr;
+            if (hipMalloc(&q, (size_t)V * d * sizeof(float)) != hipSuccess) { (void)hipGetLastError(); break; }
+            c->allocs.push_back(q);
+            table = (float*)q;
+        }
         const int R = c->pf_rows;                                  // rows per GEMM: what the prefill buffers hold
         for (int r0 = 0; r0 < V && !rc; r0 += R) {
             const int n = std::min(R, V - r0);

@@ -60,6 +60,7 @@ struct hivis_ctx {
     void* embed = nullptr; void* final_norm = nullptr; void* rho = nullptr;
     uint4* lm_head = nullptr; uint4* fuse_w = nullptr;
     uint4* fuse_w1 = nullptr;            // rows [0, d) of the fusion FC, packed on their own (K = d), and
+    bool lm_ext = false;                 // the packed LM head is followed by w1's tiles in one buffer (lm_head .. lm_head + (V + d) d)
     float* emb_w2 = nullptr;             // [V][d] fp32: Embed(token) . w2, the embedding half of the fusion FC per token (bf16 models)
     std::vector<LayerDev> layers; LayerDev draft;
     std::vector<KVDev> tkv; KVDev dkv;
@@ -605,6 +606,11 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
             // greedy token of step i: reduced by the fusion FC that follows (steps before the last), by the LM head's last
             // workgroup (last step, with `elect`), or by a phase of its own
             const bool in_fc = fold && kind == PROG_DRAFT && i < K;
+            // ... and with the extended LM head there is no FC phase: this LM-head launch also computes f' w1 + rho for the
+            // next step (d extra columns), and the next step's QKV phase reduces the token and adds the table row of it
+            const bool ext = in_fc && c->lm_ext && B <= 2;       // (the QKV variant that adds the table rows stages two rows)
+            float* u_part = ext ? pool.take((size_t)B * d) : nullptr;
+            if (ext) { lm.N = V + d; lm.Y2 = u_part; lm.ldy2 = d; lm.vec = c->rho; lm.vec_idx = std::min(i, g.n_resid - 1); }
             const bool in_lm = !in_fc && lm_elect && kind == PROG_DRAFT;
             if (in_lm) lm.cnt = (int*)pool.take(1);
             P.push_back(lm);
@@ -630,8 +636,14 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
                     pr.Y = cat + d; pr.ldy = 2 * d; pr.base = c->dlen; pr.offset = i - 1;
                     P.push_back(pr);
                 }
-                P.push_back(fu);
+                if (!ext) P.push_back(fu);
+                const size_t qi = P.size();
                 layer_phases<WT>(c, P, pool, c->draft, c->dkv, u, c->dlen, i - 1, B, 1, cat_next, 2 * d, &ld, persistent, elect);
+                if (ext) {      // the layer's first phase (QKV): rows = u_part + table[token], tokens from this step's candidates, u written back
+                    Phase& q = P[qi];
+                    q.A = u_part; q.lda = d; q.add_rows = c->emb_w2; q.wb = u; q.tok = nullptr; q.pm = lm.pm; q.pi = lm.pi; q.ncand = G;
+                    q.tok_out = c->drafts + (i - 1); q.o_sseq = g.k_max; q.o_srow = 0;
+                }
                 cat = cat_next;
             }
         }
@@ -738,7 +750,7 @@ int launch_phases(hivis_ctx* c, const Phase* phases, int n, int kind, int K, con
             case FEPI_STORE: HIVIS_LAUNCH(PH_GEMM, FEPI_STORE); break;
             case FEPI_ADD_TO: HIVIS_LAUNCH(PH_GEMM, FEPI_ADD_TO); break;
             case FEPI_ADDVEC: HIVIS_LAUNCH(PH_GEMM, FEPI_ADDVEC); break;
-            case FEPI_QKV: HIVIS_LAUNCH(PH_GEMM, FEPI_QKV); break;
+            case FEPI_QKV: if (ph.add_rows) HIVIS_LAUNCH(PH_GEMM, FEPI_QKV_TAB); else HIVIS_LAUNCH(PH_GEMM, FEPI_QKV); break;
             case FEPI_SILU: HIVIS_LAUNCH(PH_GEMM, FEPI_SILU); break;
             default: HIVIS_LAUNCH(PH_GEMM, FEPI_LOGITS); break;
             }
@@ -885,6 +897,7 @@ int fused_setup(hivis_ctx* c) {
     {
         const void* ks[] = {(const void*)phase_kernel<WT, PH_GEMM, FEPI_STORE, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADD_TO, false>,
                             (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADDVEC, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_QKV, false>,
+                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_QKV_TAB, false>,
                             (const void*)phase_kernel<WT, PH_GEMM, FEPI_SILU, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_LOGITS, false>,
                             (const void*)phase_kernel<WT, PH_GEMM, FEPI_STORE, true>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADD_TO, true>,
                             (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADDVEC, true>,
@@ -1427,6 +1440,23 @@ int build_embed_fc_table(hivis_ctx* c, const hivis_weights* w) {
         if (rc) break;
         if (hipStreamSynchronize(c->stream) != hipSuccess) { rc = fail(c, HIVIS_EHIP, "building the embedding table of the fusion FC failed"); break; }
         c->emb_w2 = table;
+        // w1's tiles behind the LM head's, in one buffer: both have K = d, so a draft step's LM-head launch can compute
+        // f' w1 as d more output columns and the fusion FC needs no launch of its own (HIVIS_LM_EXT=0: keep the FC phase)
+        const char* le = getenv("HIVIS_LM_EXT");
+        if (!(le && le[0] == '0')) {
+            const size_t lm_bytes = (size_t)V * d * sizeof(WT), w1_bytes = (size_t)d * d * sizeof(WT);
+            void* q = nullptr;
+            if (hipMalloc(&q, lm_bytes + w1_bytes) != hipSuccess) { (void)hipGetLastError(); break; }
+            if (hipMemcpyAsync(q, c->lm_head, lm_bytes, hipMemcpyDeviceToDevice, c->stream) != hipSuccess ||
+                hipMemcpyAsync((char*)q + lm_bytes, c->fuse_w1, w1_bytes, hipMemcpyDeviceToDevice, c->stream) != hipSuccess ||
+                hipStreamSynchronize(c->stream) != hipSuccess) { (void)hipFree(q); rc = fail(c, HIVIS_EHIP, "copying the LM head failed"); break; }
+            // the separate LM-head buffer is no longer needed
+            for (auto it = c->allocs.begin(); it != c->allocs.end(); ++it) if (*it == (void*)c->lm_head) { c->allocs.erase(it); break; }
+            (void)hipFree(c->lm_head);
+            c->allocs.push_back(q);
+            c->lm_head = (uint4*)q;
+            c->lm_ext = true;
+        }
     } while (0);
     (void)hipFree(staging);
     return rc;

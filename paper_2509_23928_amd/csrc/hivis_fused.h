@@ -25,7 +25,8 @@ namespace hivis {
 enum { PH_GEMM = 0, PH_ATTN = 1, PH_ATTN_MERGE = 2, PH_PREP = 3, PH_NORM_ROWS = 4, PH_ARGMAX = 5, PH_SAMPLE = 6 };
 enum { PRO_PLAIN = 0, PRO_RMS = 1 };
 constexpr int FUSED_RMAX = 8;      // (head,row) pairs per attention work item in the persistent kernel
-enum { FEPI_STORE = 0, FEPI_ADD_TO = 1, FEPI_ADDVEC = 2, FEPI_QKV = 3, FEPI_SILU = 4, FEPI_LOGITS = 5 };
+enum { FEPI_STORE = 0, FEPI_ADD_TO = 1, FEPI_ADDVEC = 2, FEPI_QKV = 3, FEPI_SILU = 4, FEPI_LOGITS = 5,
+       FEPI_QKV_TAB = 6 };   // kernel variant only (never a Phase.epi): QKV whose rows are A + add_rows[token], see Phase.wb
 
 struct Phase {
     int type, pro, epi;
@@ -43,6 +44,14 @@ struct Phase {
     // e w2 depends on the token alone, so add_rows[token][N] (fp32, computed once at create) is ADDED in the epilogue and
     // the GEMM runs over f's K = d only: half the weight bytes per step.  The token of a row as for emb (tok, or reduced).
     const float* add_rows;
+    // QKV with add_rows (the drafter's first phase of a step, when the fusion FC's w1 half rode on the LM-head launch
+    // before it): activation row r is A[r] + add_rows[token of r], the token as above (tok, or reduced from pm / pi), and
+    // workgroup 0 writes the sum back to wb [M][K] (the layer's residual stream, read later by the O projection)
+    float* wb;
+    // LOGITS with N > vocab: columns [vocab, N) are not logits but extra output columns (the packed weights carry another
+    // matrix of the same K behind the LM head: w1 of the fusion FC); they go to Y2 [M][ldy2] plus vec[vec_idx], and
+    // take no part in the greedy candidates
+    float* Y2; int ldy2;
     // ... and if tok is null the token of row r is the greedy token of the LM-head phase before it, reduced here from
     // that phase's per-workgroup candidates pm / pi ([row][ncand]); workgroup 0 also stores it to tok_out
     int ncand;
@@ -238,7 +247,9 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     // tiles per group: the full group size where a workgroup owns many tiles (LM head, gate|up; also the generic
     // interpreter), half of it for the kernels whose workgroups own at most a few tiles (fewer accumulators)
     constexpr int G = (!SINGLE && (EPI < 0 || EPI == FEPI_LOGITS || EPI == FEPI_SILU)) ? FusedCfg<WT>::G : FusedCfg<WT>::G / 2;
-    constexpr int U = FUSED_U, QM = FUSED_QM, NT = FUSED_NT;
+    // rows staged per lane and pass; the table-add QKV variant serves draft steps of at most two sequences and stages two
+    // rows only (its second set of row registers would otherwise spill)
+    constexpr int U = FUSED_U, QM = (EPI == FEPI_QKV_TAB) ? 2 : FUSED_QM, NT = FUSED_NT;
     static_assert(KBW == U && (G % 2) == 0, "one unit per tile slice; tiles are processed in pairs");
     constexpr int TILE = G * 64 * RPL;
     constexpr int SLOTS = TILE / NT;         // epilogue slots per thread (all of the same row and column-in-tile)
@@ -253,7 +264,9 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     float* inv_rms = ssq_w + NW * 16;        // [16]
     uint4* chunk = reinterpret_cast<uint4*>(inv_rms + 16);
 
-    const int epi = (EPI >= 0) ? EPI : ph.epi;       // compile-time epilogue when the phase has its own kernel
+    constexpr bool TAB = EPI == FEPI_QKV_TAB;        // the drafter's QKV with table rows added in the prologue: a kernel of its own, so
+                                                     // that the QKV kernel of the verify pass carries none of its registers
+    const int epi = (EPI >= 0) ? (TAB ? (int)FEPI_QKV : EPI) : ph.epi;       // compile-time epilogue when the phase has its own kernel
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wavefront index as a scalar: branches on it are uniform
     const int M = pp.M, K = ph.K, N = ph.N;
     const int kblks = K / KB, ntiles = N / 16;
@@ -315,20 +328,21 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     // raw activation loads of pass `ps`: float4 (row0 + q*RS, first k of the wavefront's slice + 4*col4) and the gain of
     // those 4 columns (unconditional loads from clamped addresses: a load under a divergent branch is followed by a
     // full wait, which would serialise the rows into one memory round trip each)
-    static_assert(QM * RS >= ROWS, "every row is staged by some lane");
+    static_assert(EPI == FEPI_QKV_TAB || QM * RS >= ROWS, "every row is staged by some lane");
     typedef typename Gain4<WT>::type gain4_t;
     // fusion FC with the embedding half taken from the table: the tokens of this lane's rows
     int tokr[QM];        // as loaded; forced into [0, V) where it is used, so that nothing waits for the load here
 #pragma unroll
     for (int q = 0; q < QM; ++q) {
         tokr[q] = 0;
-        if (EPI == FEPI_ADDVEC && ph.emb != nullptr && ph.tok != nullptr) {
+        if ((EPI == FEPI_ADDVEC && ph.emb != nullptr && ph.tok != nullptr) || (TAB && ph.tok != nullptr)) {
             const int r_ = min(row0 + q * RS, M - 1);
             tokr[q] = __hip_atomic_load(&ph.tok[(r_ / pp.m) * ph.tok_sseq + (r_ % pp.m) * ph.tok_srow], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     float4 araw[QM]; gain4_t graw = gain4_t();
     float4 araw2[SINGLE ? QM : 1]; gain4_t graw2 = gain4_t();      // rows of the second pass of a pair (one tile per workgroup)
+    float4 braw[TAB ? QM : 1];                                     // QKV with add_rows: the table rows added to the activation rows
 #define HIVIS_LOAD_RAW_TO(ps, ARAW, GRAW)                                                                          \
     {                                                                                                              \
         const int k_ = min(unit_kb0<NW, KBW>(kblks, ps, wave) * KB + 4 * col4, K - 4);                             \
@@ -338,6 +352,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             const int row_ = min(row0 + q * RS, M - 1);                                                            \
             if (from_emb_) ARAW[q] = load4_f32(reinterpret_cast<const WT*>(ph.emb) + (size_t)clamp_token(tokr[q], pp.V) * (K / 2) + (k_ - K / 2)); \
             else ARAW[q] = *reinterpret_cast<const float4*>(A + (size_t)row_ * lda + k_);                          \
+            if (TAB) braw[q] = *reinterpret_cast<const float4*>(ph.add_rows + (size_t)clamp_token(tokr[q], pp.V) * K + k_); \
         }                                                                                                          \
     }
 #define HIVIS_LOAD_RAW(ps) HIVIS_LOAD_RAW_TO(ps, araw, graw)
@@ -350,6 +365,13 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             const int row_ = row0 + q * RS;                                                                        \
             if (row_ < M && 4 * col4 < nkb_ * KB) {                                                                \
                 float x_[4] = {ARAW[q].x, ARAW[q].y, ARAW[q].z, ARAW[q].w};                                        \
+                if (TAB) {                                                                                         \
+                    x_[0] += braw[q].x; x_[1] += braw[q].y; x_[2] += braw[q].z; x_[3] += braw[q].w;                \
+                    if (blockIdx.x == 0 && tg == t_begin) {                                                        \
+                        float* wb_ = ph.wb + (size_t)row_ * K + unit_kb0<NW, KBW>(kblks, ps, wave) * KB + 4 * col4; \
+                        st_wt(wb_, x_[0]); st_wt(wb_ + 1, x_[1]); st_wt(wb_ + 2, x_[2]); st_wt(wb_ + 3, x_[3]);    \
+                    }                                                                                              \
+                }                                                                                                  \
                 if (do_ssq) ssq_acc[q] += x_[0] * x_[0] + x_[1] * x_[1] + x_[2] * x_[2] + x_[3] * x_[3];           \
                 if (gain) { _Pragma("unroll") for (int e = 0; e < 4; ++e) x_[e] *= Gain4<WT>::get(GRAW, e); }      \
                 stage_store(WT(), slice, RU, row_, 4 * col4, x_);                                                  \
@@ -372,7 +394,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
 #define HIVIS_STAGE(ps, nx, do_ssq) HIVIS_STAGE_FROM(ps, araw, graw, do_ssq, if ((nx) >= 0) HIVIS_LOAD_RAW(nx))
     // Tokens = greedy tokens of the LM-head phase before this one (fusion FC with ph.tok == null): every wavefront
     // reduces that phase's candidates itself (lowest index wins ties); workgroup 0 also stores them.
-    const bool cand_tokens = EPI == FEPI_ADDVEC && (ph.emb != nullptr || ph.add_rows != nullptr) && ph.tok == nullptr;
+    const bool cand_tokens = ((EPI == FEPI_ADDVEC && (ph.emb != nullptr || ph.add_rows != nullptr)) || TAB) && ph.tok == nullptr;
     // the token of THIS thread's epilogue row (all of a thread's epilogue slots serve one row), for the table form
     const int row_e = min(RPL * (((int)threadIdx.x / RPL & 63) >> 4) + (int)threadIdx.x % RPL, M - 1);
     int tok_e = 0;
@@ -555,8 +577,12 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
             case FEPI_ADD_TO: st_wt(&ph.Y[(size_t)row * ph.ldy + col], epi_a[sl] + v); break;
             case FEPI_ADDVEC: st_wt(&ph.Y[(size_t)row * ph.ldy + col], v + to_f32(((const WT*)ph.vec)[(size_t)ph.vec_idx * N + col]) + epi_a[sl]); break;
             case FEPI_LOGITS:
-                st_wt(&ph.Y[(size_t)row * ph.ldy + col], v);
-                if (v > best_v || (v == best_v && col < best_i)) { best_v = v; best_i = col; }
+                if (col < pp.V) {
+                    st_wt(&ph.Y[(size_t)row * ph.ldy + col], v);
+                    if (v > best_v || (v == best_v && col < best_i)) { best_v = v; best_i = col; }
+                } else {
+                    st_wt(&ph.Y2[(size_t)row * ph.ldy2 + (col - pp.V)], v + to_f32(((const WT*)ph.vec)[(size_t)ph.vec_idx * (N - pp.V) + (col - pp.V)]));
+                }
                 break;
             case FEPI_SILU:
                 if (cl < 8) {

@@ -608,7 +608,7 @@ void build_phases(hivis_ctx* c, int kind, int K, Pool& pool, std::vector<Phase>&
             const bool in_fc = fold && kind == PROG_DRAFT && i < K;
             // ... and with the extended LM head there is no FC phase: this LM-head launch also computes f' w1 + rho for the
             // next step (d extra columns), and the next step's QKV phase reduces the token and adds the table row of it
-            const bool ext = in_fc && c->lm_ext && B <= 2;       // (the QKV variant that adds the table rows stages two rows)
+            const bool ext = in_fc && c->lm_ext && B <= 4;       // (the QKV variants that add the table rows stage two or four rows)
             float* u_part = ext ? pool.take((size_t)B * d) : nullptr;
             if (ext) { lm.N = V + d; lm.Y2 = u_part; lm.ldy2 = d; lm.vec = c->rho; lm.vec_idx = std::min(i, g.n_resid - 1); }
             const bool in_lm = !in_fc && lm_elect && kind == PROG_DRAFT;
@@ -750,7 +750,11 @@ int launch_phases(hivis_ctx* c, const Phase* phases, int n, int kind, int K, con
             case FEPI_STORE: HIVIS_LAUNCH(PH_GEMM, FEPI_STORE); break;
             case FEPI_ADD_TO: HIVIS_LAUNCH(PH_GEMM, FEPI_ADD_TO); break;
             case FEPI_ADDVEC: HIVIS_LAUNCH(PH_GEMM, FEPI_ADDVEC); break;
-            case FEPI_QKV: if (ph.add_rows) HIVIS_LAUNCH(PH_GEMM, FEPI_QKV_TAB); else HIVIS_LAUNCH(PH_GEMM, FEPI_QKV); break;
+            case FEPI_QKV:
+                if (ph.add_rows && pp.M <= 2) HIVIS_LAUNCH(PH_GEMM, FEPI_QKV_TAB);
+                else if (ph.add_rows) HIVIS_LAUNCH(PH_GEMM, FEPI_QKV_TAB4);
+                else HIVIS_LAUNCH(PH_GEMM, FEPI_QKV);
+                break;
             case FEPI_SILU: HIVIS_LAUNCH(PH_GEMM, FEPI_SILU); break;
             default: HIVIS_LAUNCH(PH_GEMM, FEPI_LOGITS); break;
             }
@@ -897,7 +901,7 @@ int fused_setup(hivis_ctx* c) {
     {
         const void* ks[] = {(const void*)phase_kernel<WT, PH_GEMM, FEPI_STORE, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADD_TO, false>,
                             (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADDVEC, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_QKV, false>,
-                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_QKV_TAB, false>,
+                            (const void*)phase_kernel<WT, PH_GEMM, FEPI_QKV_TAB, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_QKV_TAB4, false>,
                             (const void*)phase_kernel<WT, PH_GEMM, FEPI_SILU, false>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_LOGITS, false>,
                             (const void*)phase_kernel<WT, PH_GEMM, FEPI_STORE, true>, (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADD_TO, true>,
                             (const void*)phase_kernel<WT, PH_GEMM, FEPI_ADDVEC, true>,

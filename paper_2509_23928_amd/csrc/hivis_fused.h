@@ -26,7 +26,8 @@ enum { PH_GEMM = 0, PH_ATTN = 1, PH_ATTN_MERGE = 2, PH_PREP = 3, PH_NORM_ROWS = 
 enum { PRO_PLAIN = 0, PRO_RMS = 1 };
 constexpr int FUSED_RMAX = 8;      // (head,row) pairs per attention work item in the persistent kernel
 enum { FEPI_STORE = 0, FEPI_ADD_TO = 1, FEPI_ADDVEC = 2, FEPI_QKV = 3, FEPI_SILU = 4, FEPI_LOGITS = 5,
-       FEPI_QKV_TAB = 6 };   // kernel variant only (never a Phase.epi): QKV whose rows are A + add_rows[token], see Phase.wb
+       FEPI_QKV_TAB = 6,     // kernel variants only (never a Phase.epi): QKV whose rows are A + add_rows[token], see Phase.wb;
+       FEPI_QKV_TAB4 = 7 };  // two staged rows (at most two sequences) / four staged rows (three or four sequences)
 
 struct Phase {
     int type, pro, epi;
@@ -247,9 +248,9 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     // tiles per group: the full group size where a workgroup owns many tiles (LM head, gate|up; also the generic
     // interpreter), half of it for the kernels whose workgroups own at most a few tiles (fewer accumulators)
     constexpr int G = (!SINGLE && (EPI < 0 || EPI == FEPI_LOGITS || EPI == FEPI_SILU)) ? FusedCfg<WT>::G : FusedCfg<WT>::G / 2;
-    // rows staged per lane and pass; the table-add QKV variant serves draft steps of at most two sequences and stages two
-    // rows only (its second set of row registers would otherwise spill)
-    constexpr int U = FUSED_U, QM = (EPI == FEPI_QKV_TAB) ? 2 : FUSED_QM, NT = FUSED_NT;
+    // rows staged per lane and pass; the table-add QKV variants serve draft steps of at most two / four sequences and stage
+    // that many rows only (with eight, their second set of row registers spills)
+    constexpr int U = FUSED_U, QM = (EPI == FEPI_QKV_TAB) ? 2 : (EPI == FEPI_QKV_TAB4) ? 4 : FUSED_QM, NT = FUSED_NT;
     static_assert(KBW == U && (G % 2) == 0, "one unit per tile slice; tiles are processed in pairs");
     constexpr int TILE = G * 64 * RPL;
     constexpr int SLOTS = TILE / NT;         // epilogue slots per thread (all of the same row and column-in-tile)
@@ -264,7 +265,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     float* inv_rms = ssq_w + NW * 16;        // [16]
     uint4* chunk = reinterpret_cast<uint4*>(inv_rms + 16);
 
-    constexpr bool TAB = EPI == FEPI_QKV_TAB;        // the drafter's QKV with table rows added in the prologue: a kernel of its own, so
+    constexpr bool TAB = EPI == FEPI_QKV_TAB || EPI == FEPI_QKV_TAB4;        // the drafter's QKV with table rows added in the prologue: a kernel of its own, so
                                                      // that the QKV kernel of the verify pass carries none of its registers
     const int epi = (EPI >= 0) ? (TAB ? (int)FEPI_QKV : EPI) : ph.epi;       // compile-time epilogue when the phase has its own kernel
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wavefront index as a scalar: branches on it are uniform
@@ -328,7 +329,7 @@ __device__ __forceinline__ void gemm_phase(const Phase& ph, const PassParams& pp
     // raw activation loads of pass `ps`: float4 (row0 + q*RS, first k of the wavefront's slice + 4*col4) and the gain of
     // those 4 columns (unconditional loads from clamped addresses: a load under a divergent branch is followed by a
     // full wait, which would serialise the rows into one memory round trip each)
-    static_assert(EPI == FEPI_QKV_TAB || QM * RS >= ROWS, "every row is staged by some lane");
+    static_assert(EPI == FEPI_QKV_TAB || EPI == FEPI_QKV_TAB4 || QM * RS >= ROWS, "every row is staged by some lane");
     typedef typename Gain4<WT>::type gain4_t;
     // fusion FC with the embedding half taken from the table: the tokens of this lane's rows
     int tokr[QM];        // as loaded; forced into [0, V) where it is used, so that nothing waits for the load here

@@ -1156,9 +1156,18 @@ __global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ l
     const int row = blockIdx.x;
     const float* l = logits + (size_t)row * V;
     float best = -INFINITY; int besti = 0x7FFFFFFF;
-    for (int c = threadIdx.x; c < V; c += 256) {
-        const float x = l[c];
-        if (x > best || (x == best && c < besti)) { best = x; besti = c; }
+    // eight independent loads per trip (a one-load-per-trip loop pays a memory round trip per trip: 39 us for the 61
+    // rows of a tree verify pass); a thread still sees its columns in ascending order, so ties keep the lowest index
+    constexpr int U = 8;
+    for (int c0 = threadIdx.x; c0 < V; c0 += 256 * U) {
+        float x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = l[min(c0 + 256 * u, V - 1)];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + 256 * u;
+            if (c < V && (x[u] > best || (x[u] == best && c < besti))) { best = x[u]; besti = c; }
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {

@@ -421,7 +421,7 @@ int layer_forward(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* h, co
     const int nqkv = qd + 2 * kd;
     hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, h, d, pending, d, (const WT*)L.norm1, c->a, d, d, g.rms_eps);
     if (int rc = gemm<WT>(c, c->a, d, M, d, L.wqkv, nqkv, c->qkv, nqkv, EPI_STORE)) return rc;
-    hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta, (const float*)L.bqkv);
+    hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta, (const float*)L.bqkv, (const float*)c->rope_tab, g.max_vis + g.max_text);
     if (c->fused && std::is_same<KT, f16_t>::value) { if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd, tr.mask)) return rc; }
     else if (int rc = attention<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, max_keys, c->att, qd, tr.mask)) return rc;
     if (int rc = gemm<WT>(c, c->att, qd, M, qd, L.wo, d, c->proj, d, EPI_STORE)) return rc;
@@ -936,7 +936,8 @@ int fused_setup(hivis_ctx* c) {
 int tall_gemm(hivis_ctx* c, const float* A, int lda, int M, int K, const uint4* Wp, int N, float* Y, int ldy) {
     const int kblks = K / 32, row_tiles = (M + 7) / 8, ntiles = N / 16;
     const size_t nfrag = (size_t)row_tiles * kblks * 64;
-    hipLaunchKernelGGL(pack_afrag_kernel, dim3((unsigned)std::min<size_t>((nfrag + 255) / 256, 65535)), dim3(256), 0, c->stream, A, lda, M, kblks, c->pf_frag);
+    // A == nullptr: the producing row kernel has already written the fragments to c->pf_frag
+    if (A) hipLaunchKernelGGL(pack_afrag_kernel, dim3((unsigned)std::min<size_t>((nfrag + 255) / 256, 65535)), dim3(256), 0, c->stream, A, lda, M, kblks, c->pf_frag);
     // LDS-tiled kernel: 64 real rows x 256 columns per workgroup when that still gives >= 2 workgroups per CU, else x 128
     const int macro_rows = (row_tiles + 7) / 8;
     // grid: (column blocks rounded up to a multiple of the 8 XCDs) x row blocks, 1-D (see the kernel's mapping)
@@ -1021,12 +1022,12 @@ int layer_forward_wide(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* 
     hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, h, d, pending, d, M, (const WT*)L.norm1, c->pf_frag, d, g.rms_eps);
     if (int rc = wide_gemm(c, nullptr, 0, M, d, L.wqkv, nqkv, c->qkv, nqkv, &pq)) return rc;
     hipLaunchKernelGGL((wide_rope_append_kernel<KT>), dim3(M, 8), dim3(256), 0, c->stream, pq, c->qkv, nqkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m,
-                       (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta, (const float*)L.bqkv);
+                       (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta, (const float*)L.bqkv, (const float*)c->rope_tab, g.max_vis + g.max_text);
     if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd, tr.mask)) return rc;
     if (int rc = wide_gemm(c, c->att, qd, M, qd, L.wo, d, c->proj, d, &po)) return rc;
     hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, h, d, po, d, M, (const WT*)L.norm2, c->pf_frag, d, g.rms_eps);
     if (int rc = wide_gemm(c, nullptr, 0, M, d, L.wgu, 2 * F, c->gu, 2 * F, &pg)) return rc;
-    hipLaunchKernelGGL(wide_silu_frag_kernel, dim3(Mp, 8), dim3(256), 0, c->stream, pg, M, F, c->pf_frag);
+    hipLaunchKernelGGL(wide_silu_frag_kernel, dim3(Mp / 8, std::min(64, (F / 8 + 31) / 32)), dim3(256), 0, c->stream, pg, M, F, c->pf_frag);
     if (int rc = wide_gemm(c, nullptr, 0, M, F, L.wd, d, c->proj, d, out_pending)) return rc;
     HIP_TRY(c, hipGetLastError());
     return HIVIS_OK;
@@ -1037,22 +1038,32 @@ int prefill_target_tall(hivis_ctx* c, int b, int v, int l) {
     typedef typename KVType<WT>::type KT;
     const hivis_config& g = c->cfg;
     const int M = v + l, d = g.d, qd = g.n_q_heads * g.head_dim, kd = g.n_kv_heads * g.head_dim, F = g.ffn, nqkv = qd + 2 * kd;
+    const int Mp = ((M + 7) / 8) * 8;
     hipLaunchKernelGGL((prefill_rows_kernel<WT>), dim3(M), dim3(256), 0, c->stream, (const WT*)c->vis + (size_t)b * g.max_vis * d, v,
                        (const WT*)c->embed, (const int32_t*)(c->text + (size_t)b * c->text_stride), 0, c->pf_x, d);
     const float* pending = nullptr;
     for (int l_ = 0; l_ < g.n_layers; ++l_) {
         const LayerDev& L = c->layers[l_];
         const KVDev& kv = c->tkv[l_];
-        hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, pending, d, (const WT*)L.norm1, c->pf_a, d, d, g.rms_eps);
-        if (int rc = tall_gemm(c, c->pf_a, d, M, d, L.wqkv, nqkv, c->pf_qkv, nqkv)) return rc;
-        hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->pf_qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, (const int*)c->zeros, 0, b, M, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, (const int*)nullptr, (const float*)L.bqkv);
+        // residual add + RMSNorm write the GEMM's A fragments directly (rows padded to whole tiles), SiLU * up likewise
+        const bool direct = d <= 8192 && d % 8 == 0 && F % 32 == 0;
+        const Parts pend{pending, 1, 0};
+        if (direct) hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, c->pf_x, d, pend, d, M, (const WT*)L.norm1, c->pf_frag, d, g.rms_eps);
+        else hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, pending, d, (const WT*)L.norm1, c->pf_a, d, d, g.rms_eps);
+        if (int rc = tall_gemm(c, direct ? nullptr : c->pf_a, d, M, d, L.wqkv, nqkv, c->pf_qkv, nqkv)) return rc;
+        hipLaunchKernelGGL((rope_append_kernel<KT>), dim3(M, row_chunks(M)), dim3(256), 0, c->stream, c->pf_qkv, g.n_q_heads, g.n_kv_heads, g.head_dim, (const int*)c->zeros, 0, b, M, (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, (const int*)nullptr, (const float*)L.bqkv, (const float*)c->rope_tab, g.max_vis + g.max_text);
         if (c->fused) { if (int rc = attention_rows_mfma<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, c->pf_att, qd)) return rc; }
         else if (int rc = attention<WT>(c, c->pf_qkv, nqkv, kv, c->zeros, 0, b, 1, M, M, c->pf_att, qd)) return rc;
         if (int rc = tall_gemm(c, c->pf_att, qd, M, qd, L.wo, d, c->pf_proj, d)) return rc;
-        hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, (const float*)c->pf_proj, d, (const WT*)L.norm2, c->pf_a, d, d, g.rms_eps);
-        if (int rc = tall_gemm(c, c->pf_a, d, M, d, L.wgu, 2 * F, c->pf_gu, 2 * F)) return rc;
-        hipLaunchKernelGGL(silu_mul_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, (const float*)c->pf_gu, c->pf_act, F);
-        if (int rc = tall_gemm(c, c->pf_act, F, M, F, L.wd, d, c->pf_proj, d)) return rc;
+        const Parts proj{c->pf_proj, 1, 0};
+        if (direct) hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, c->pf_x, d, proj, d, M, (const WT*)L.norm2, c->pf_frag, d, g.rms_eps);
+        else hipLaunchKernelGGL((add_rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, c->stream, c->pf_x, d, (const float*)c->pf_proj, d, (const WT*)L.norm2, c->pf_a, d, d, g.rms_eps);
+        if (int rc = tall_gemm(c, direct ? nullptr : c->pf_a, d, M, d, L.wgu, 2 * F, c->pf_gu, 2 * F)) return rc;
+        if (direct) {
+            const Parts gu{c->pf_gu, 1, 0};
+            hipLaunchKernelGGL(wide_silu_frag_kernel, dim3(Mp / 8, std::min(64, (F / 8 + 31) / 32)), dim3(256), 0, c->stream, gu, M, F, c->pf_frag);
+        } else hipLaunchKernelGGL(silu_mul_kernel, dim3(M, row_chunks(M)), dim3(256), 0, c->stream, (const float*)c->pf_gu, c->pf_act, F);
+        if (int rc = tall_gemm(c, direct ? nullptr : c->pf_act, F, M, F, L.wd, d, c->pf_proj, d)) return rc;
         pending = c->pf_proj;
     }
     // features of the text rows: final norm of (x + last MLP delta)

@@ -177,13 +177,13 @@ __device__ __forceinline__ void stage_store(bf16_t, uint4* chunk, int RU, int ro
                                             const float (&x)[4]) {
     const int kb = kl >> 5, g = (kl & 31) >> 3, e0 = kl & 7;
     const int slot = (kb * 4 + g) * RU + tile_row_of<bf16_t>(row);
-    bf16_t hi[4], lo[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { hi[e] = f32_to_bf16(x[e]); lo[e] = f32_to_bf16(x[e] - bf16_to_f32(hi[e])); }
+    uint32_t h01, l01, h23, l23;
+    f32_to_bf16x2_hilo(x[0], x[1], h01, l01);
+    f32_to_bf16x2_hilo(x[2], x[3], h23, l23);
     uint2* ph = reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(chunk + slot) + e0);
     uint2* pl = reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(chunk + slot + 2) + e0);
-    *ph = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-    *pl = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+    *ph = make_uint2(h01, h23);
+    *pl = make_uint2(l01, l23);
 }
 __device__ __forceinline__ void stage_store(float, uint4* chunk, int RU, int row, int kl, const float (&x)[4]) {
     const int kb = kl >> 4, g = (kl & 15) >> 2;

@@ -19,10 +19,20 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round to nearest even, finite inputs
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// round to nearest even: the conversion instruction of gfx950 (v_cvt_pk_bf16_f32), bit for bit what the integer
+// recipe u += 0x7FFF + ((u >> 16) & 1) gives for finite inputs, at a fifth of the instructions
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two values -> two bf16 in one 32-bit word (a in the low half)
+__device__ __forceinline__ uint32_t f32_to_bf16x2(float a, float b) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+// hi and lo parts of two values: hi = bf16(x), lo = bf16(x - hi)
+__device__ __forceinline__ void f32_to_bf16x2_hilo(float a, float b, uint32_t& hi, uint32_t& lo) {
+    hi = f32_to_bf16x2(a, b);
+    lo = f32_to_bf16x2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
 }
 typedef _Float16 f16_t;                                   // IEEE half: KV-cache storage of bf16 models
 __device__ __forceinline__ float to_f32(float x) { return x; }
@@ -96,6 +106,18 @@ __device__ __forceinline__ void kv_put(f16_t* row, int HD, int c, float x) {
     const f16_t hi = (f16_t)fminf(fmaxf(x, -65504.f), 65504.f);
     row[c] = hi;
     row[HD + c] = (f16_t)(x - (float)hi);
+}
+// two adjacent values c, c + 1 (c even): the hi halves and the lo halves each go out as one 32-bit store
+__device__ __forceinline__ void kv_put_pair(float* row, int HD, int c, float a, float b) { row[c] = a; row[c + 1] = b; }
+__device__ __forceinline__ void kv_put_pair(f16_t* row, int HD, int c, float a, float b) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 hi, lo;
+    hi[0] = (f16_t)fminf(fmaxf(a, -65504.f), 65504.f);
+    hi[1] = (f16_t)fminf(fmaxf(b, -65504.f), 65504.f);
+    lo[0] = (f16_t)(a - (float)hi[0]);
+    lo[1] = (f16_t)(b - (float)hi[1]);
+    *reinterpret_cast<h2*>(row + c) = hi;
+    *reinterpret_cast<h2*>(row + HD + c) = lo;
 }
 __device__ __forceinline__ float kv_get(const float* row, int HD, int c) { return row[c]; }
 __device__ __forceinline__ float kv_get(const f16_t* row, int HD, int c) { return (float)row[c] + (float)row[HD + c]; }
@@ -816,7 +838,10 @@ __global__ void silu_mul_kernel(const float* __restrict__ gu, float* __restrict_
 template <typename ST>
 __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int HD, const int* __restrict__ base,
                                    int offset, int seq0, int m, ST* __restrict__ kc, ST* __restrict__ vc, int maxL,
-                                   float theta, const int* __restrict__ pos_delta = nullptr, const float* __restrict__ bias = nullptr) {
+                                   float theta, const int* __restrict__ pos_delta = nullptr, const float* __restrict__ bias = nullptr,
+                                   const float* __restrict__ rope_tab = nullptr, int npos = 0) {
+    // rope_tab (optional): the context's table [npos][HD/2] of (cos, sin), see rope_table_kernel; without it the angle's
+    // sine and cosine are evaluated here (in double: ~100 us per layer for a 3008-row prefill)
     const int row = blockIdx.x;
     const int seq = seq0 + row / m;
     const int slot = base[seq] + offset + row % m;
@@ -826,9 +851,14 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int
     const int npair = (Hq + Hkv) * half;
     for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < npair; idx += gridDim.y * blockDim.x) {
         const int head = idx / half, i = idx % half;
-        const double inv_freq = exp2(-2.0 * (double)i / (double)HD * log2((double)theta));
         double s, c;
-        sincos((double)pos * inv_freq, &s, &c);
+        if (rope_tab) {
+            const float2 t = *reinterpret_cast<const float2*>(rope_tab + ((size_t)min(pos, npos - 1) * half + i) * 2);
+            c = (double)t.x; s = (double)t.y;
+        } else {
+            const double inv_freq = exp2(-2.0 * (double)i / (double)HD * log2((double)theta));
+            sincos((double)pos * inv_freq, &s, &c);
+        }
         float* x = r + (size_t)head * HD;          // the pair (i, i + hd/2) sits in columns 2i, 2i+1 (PACK_QKV order)
         const float b1 = bias ? bias[(size_t)head * HD + 2 * i] : 0.f, b2 = bias ? bias[(size_t)head * HD + 2 * i + 1] : 0.f;
         const float x1 = x[2 * i] + b1, x2 = x[2 * i + 1] + b2;
@@ -838,13 +868,14 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int Hq, int Hkv, int
             x[2 * i] = y1; x[2 * i + 1] = y2;
         } else {
             ST* dst = kc + (((size_t)seq * Hkv + (head - Hq)) * maxL + slot) * HD * KVWidth<ST>::W;
-            kv_put(dst, HD, 2 * i, y1); kv_put(dst, HD, 2 * i + 1, y2);
+            kv_put_pair(dst, HD, 2 * i, y1, y2);
         }
     }
     const float* v = r + (size_t)(Hq + Hkv) * HD;
-    for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < Hkv * HD; idx += gridDim.y * blockDim.x) {
-        const int head = idx / HD, c = idx % HD;
-        kv_put(vc + (((size_t)seq * Hkv + head) * maxL + slot) * HD * KVWidth<ST>::W, HD, c, v[idx] + (bias ? bias[(size_t)(Hq + Hkv) * HD + idx] : 0.f));
+    for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < Hkv * HD / 2; idx += gridDim.y * blockDim.x) {
+        const int head = (2 * idx) / HD, c = (2 * idx) % HD;
+        const float b0 = bias ? bias[(size_t)(Hq + Hkv) * HD + 2 * idx] : 0.f, b1 = bias ? bias[(size_t)(Hq + Hkv) * HD + 2 * idx + 1] : 0.f;
+        kv_put_pair(vc + (((size_t)seq * Hkv + head) * maxL + slot) * HD * KVWidth<ST>::W, HD, c, v[2 * idx] + b0, v[2 * idx + 1] + b1);
     }
 }
 

@@ -342,7 +342,10 @@ AttnShape fused_attn_shape(hivis_ctx* c, int nseq, int m, int offset, int maxL, 
 // keys, no key split), launched once over all items.  Rows of sequence seq0 + s sit at positions base[seq0 + s] + offset + i.
 template <typename WT>
 int attention_rows_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, const int* base, int offset, int seq0, int nseq, int m,
-                        float* out, int ldo, const unsigned long long* tmask = nullptr) {
+                        float* out, int ldo, const unsigned long long* tmask = nullptr, uint4* frag_out = nullptr, bool* wrote_frag = nullptr) {
+    // frag_out / wrote_frag (optional): where the kernel chosen can, the rows go out as A fragments of the next GEMM
+    // (K = ldo) instead of fp32 rows, and *wrote_frag says so
+    if (wrote_frag) *wrote_frag = false;
     const hivis_config& g = c->cfg;
     typedef typename KVType<WT>::type KT;
     if constexpr (std::is_same<KT, f16_t>::value) {
@@ -370,14 +373,16 @@ int attention_rows_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, 
             sh.seq0 = seq0; sh.offset = offset; sh.maxL = kv.maxL; sh.ldq = ldq; sh.nwaves = FUSED_NW; sh.nsplit = 1; sh.tmask = tmask;
             const int items = nseq * g.n_kv_heads * sh.n_hblk * sh.n_rblk;
             const size_t lds = fused_attn_mfma_lds_floats(g.head_dim, FUSED_NW, ATTN_ROWS_RM) * sizeof(float);
+            uint4* frag = (frag_out && wrote_frag && ldo % 32 == 0) ? frag_out : nullptr;
+            if (frag) *wrote_frag = true;
             if (g.head_dim == 128) {
                 static bool attr128 = false;
                 if (!attr128) { HIP_TRY(c, hipFuncSetAttribute((const void*)attn_rows_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); attr128 = true; }
-                hipLaunchKernelGGL((attn_rows_kernel<128>), dim3(items), dim3(FUSED_NT), lds, c->stream, q, (const f16_t*)kv.k, (const f16_t*)kv.v, base, sh, out, ldo);
+                hipLaunchKernelGGL((attn_rows_kernel<128>), dim3(items), dim3(FUSED_NT), lds, c->stream, q, (const f16_t*)kv.k, (const f16_t*)kv.v, base, sh, out, ldo, frag);
             } else {
                 static bool attr64 = false;
                 if (!attr64) { HIP_TRY(c, hipFuncSetAttribute((const void*)attn_rows_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); attr64 = true; }
-                hipLaunchKernelGGL((attn_rows_kernel<64>), dim3(items), dim3(FUSED_NT), lds, c->stream, q, (const f16_t*)kv.k, (const f16_t*)kv.v, base, sh, out, ldo);
+                hipLaunchKernelGGL((attn_rows_kernel<64>), dim3(items), dim3(FUSED_NT), lds, c->stream, q, (const f16_t*)kv.k, (const f16_t*)kv.v, base, sh, out, ldo, frag);
             }
             HIP_TRY(c, hipGetLastError());
             return HIVIS_OK;
@@ -1023,8 +1028,11 @@ int layer_forward_wide(hivis_ctx* c, const LayerDev& L, const KVDev& kv, float* 
     if (int rc = wide_gemm(c, nullptr, 0, M, d, L.wqkv, nqkv, c->qkv, nqkv, &pq)) return rc;
     hipLaunchKernelGGL((wide_rope_append_kernel<KT>), dim3(M, 8), dim3(256), 0, c->stream, pq, c->qkv, nqkv, g.n_q_heads, g.n_kv_heads, g.head_dim, base, offset, seq0, m,
                        (KT*)kv.k, (KT*)kv.v, kv.maxL, g.rope_theta, tr.pos_delta, (const float*)L.bqkv, (const float*)c->rope_tab, g.max_vis + g.max_text);
-    if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd, tr.mask)) return rc;
-    if (int rc = wide_gemm(c, c->att, qd, M, qd, L.wo, d, c->proj, d, &po)) return rc;
+    // (the attention writes the O projection's fragments itself where its kernel can; rows beyond M of the last row tile
+    // then keep whatever the buffer held: an MFMA output row depends on its own A row only, and those rows are never stored)
+    bool att_frag = false;
+    if (int rc = attention_rows_mfma<WT>(c, c->qkv, nqkv, kv, base, offset, seq0, nseq, m, c->att, qd, tr.mask, c->pf_frag, &att_frag)) return rc;
+    if (int rc = wide_gemm(c, att_frag ? nullptr : c->att, qd, M, qd, L.wo, d, c->proj, d, &po)) return rc;
     hipLaunchKernelGGL((wide_add_norm_frag_kernel<WT>), dim3(Mp), dim3(WNORM_NT), 0, c->stream, h, d, po, d, M, (const WT*)L.norm2, c->pf_frag, d, g.rms_eps);
     if (int rc = wide_gemm(c, nullptr, 0, M, d, L.wgu, 2 * F, c->gu, 2 * F, &pg)) return rc;
     hipLaunchKernelGGL(wide_silu_frag_kernel, dim3(Mp / 8, std::min(64, (F / 8 + 31) / 32)), dim3(256), 0, c->stream, pg, M, F, c->pf_frag);

@@ -741,10 +741,40 @@ __device__ __forceinline__ void attn_merge_splits(const float* __restrict__ pbas
 template <int HD, int RM>
 __device__ __forceinline__ void attn_wg_finish(const float* __restrict__ mrg, int* __restrict__ flag, const AttnShape& sh, int item_id, int split,
                                                int R, int ni, int head0, int i0, int sl, float* __restrict__ ws, int* __restrict__ cnt,
-                                               float* __restrict__ att_out, int ldo, unsigned long long* marks) {
+                                               float* __restrict__ att_out, int ldo, unsigned long long* marks, uint4* __restrict__ frag_out = nullptr) {
     constexpr int NW = FUSED_NW;
     lds_barrier();
     HIVIS_AMARK(4)
+    if (sh.nsplit == 1 && frag_out != nullptr) {
+        // the attention rows go straight out as A fragments of the O projection (K = ldo, bf16 hi/lo split, layout of
+        // pack_afrag_kernel): 8 consecutive dims of one row per thread and trip
+        for (int idx = threadIdx.x; idx < R * (HD / 8); idx += FUSED_NT) {
+            const int r = idx / (HD / 8), c0 = (idx % (HD / 8)) * 8;
+            float mx = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) mx = fmaxf(mx, mrg[(w * RM + r) * (HD + 2) + HD]);
+            float num[8], den = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) num[e] = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float mw = mrg[(w * RM + r) * (HD + 2) + HD];
+                if (mw != -INFINITY) {
+                    const float ew = __expf(mw - mx);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) num[e] += mrg[(w * RM + r) * (HD + 2) + c0 + e] * ew;
+                    den += mrg[(w * RM + r) * (HD + 2) + HD + 1] * ew;
+                }
+            }
+            float y[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = num[e] / den;
+            const int hh = head0 + r / ni, i = i0 + r % ni;
+            store_afrag8(frag_out, ldo / 32, sl * sh.m + i, hh * HD + c0, y, false);
+        }
+        lds_barrier();
+        return;
+    }
     if (sh.nsplit == 1) {
         // the whole key range was handled here: merge the NW partials and write the attention rows directly
         for (int idx = threadIdx.x; idx < R * HD; idx += FUSED_NT) {
@@ -844,7 +874,8 @@ template <int HD, int RM>
 __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const f16_t* __restrict__ kc, const f16_t* __restrict__ vc,
                                              const int* __restrict__ base, const AttnShape& sh, int item_id, int split,
                                              float* __restrict__ lds, float* __restrict__ ws, int* __restrict__ cnt,
-                                             float* __restrict__ att_out, int ldo, unsigned long long* marks = nullptr) {
+                                             float* __restrict__ att_out, int ldo, unsigned long long* marks = nullptr,
+                                             uint4* __restrict__ frag_out = nullptr) {
     HIVIS_AMARK(0)
     static_assert(RM <= 16 && HD % 32 == 0, "rows are the 16-wide MFMA dimension");
     constexpr int NW = FUSED_NW;
@@ -1022,7 +1053,7 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
         }
         if (g == 0) { mr[HD] = mrun; mr[HD + 1] = lsum; }
     }
-    attn_wg_finish<HD, RM>(mrg, flag, sh, item_id, split, R, ni, kvh * group + h0, i0, sl, ws, cnt, att_out, ldo, marks);
+    attn_wg_finish<HD, RM>(mrg, flag, sh, item_id, split, R, ni, kvh * group + h0, i0, sl, ws, cnt, att_out, ldo, marks, frag_out);
 }
 
 // The MFMA attention as a kernel of its own, with all 16 MFMA columns holding real (head,row) pairs: passes with many
@@ -1030,9 +1061,11 @@ __device__ __forceinline__ void attn_wg_mfma(const float* __restrict__ q, const 
 constexpr int ATTN_ROWS_RM = 16;
 template <int HD>
 __global__ __launch_bounds__(FUSED_NT) void attn_rows_kernel(const float* __restrict__ q, const f16_t* __restrict__ kc, const f16_t* __restrict__ vc,
-                                                             const int* __restrict__ base, AttnShape sh, float* __restrict__ out, int ldo) {
+                                                             const int* __restrict__ base, AttnShape sh, float* __restrict__ out, int ldo,
+                                                             uint4* __restrict__ frag_out) {
+    // frag_out (optional): the rows are written as A fragments of the next GEMM (K = ldo) instead of fp32 rows to `out`
     extern __shared__ __align__(16) float attn_rows_lds[];
-    attn_wg_mfma<HD, ATTN_ROWS_RM>(q, kc, vc, base, sh, blockIdx.x, 0, attn_rows_lds, nullptr, nullptr, out, ldo);
+    attn_wg_mfma<HD, ATTN_ROWS_RM>(q, kc, vc, base, sh, blockIdx.x, 0, attn_rows_lds, nullptr, nullptr, out, ldo, nullptr, frag_out);
 }
 
 // Attention of long row ranges (prefill): the published flash-attention work split.  A workgroup owns 128 consecutive

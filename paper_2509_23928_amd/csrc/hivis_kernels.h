@@ -435,6 +435,20 @@ __global__ void pack_afrag_kernel(const float* __restrict__ A, int lda, int M, i
     }
 }
 
+// 8 consecutive values x[0..8) of row `row` at k0 (a multiple of 8) -> the two fragment chunks (high and low parts)
+__device__ __forceinline__ void store_afrag8(uint4* __restrict__ frag, int kblks, int row, int k0, const float (&x)[8], bool zero) {
+    const int tt = row >> 3, rr = row & 7, i_hi = 4 * (rr >> 1) + (rr & 1);
+    const size_t base = ((size_t)tt * kblks + (k0 >> 5)) * 64 + ((k0 >> 3) & 3) * 16;
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f32_to_bf16x2_hilo(x[2 * e], x[2 * e + 1], hi[e], lo[e]);
+        if (zero) { hi[e] = 0u; lo[e] = 0u; }
+    }
+    frag[base + i_hi] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    frag[base + i_hi + 2] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+}
+
 // Tall GEMM of the prefill: a workgroup of 2 x 2 wavefronts computes 8 row tiles x 2*CTW column tiles (64 real rows x
 // 32*CTW columns); each wavefront owns 4 x CTW MFMA tiles.  Per K block the workgroup copies the 8 A blocks and 2*CTW B blocks
 // (1 KiB each, already in fragment order) from global memory to LDS once, and the wavefronts read their fragments with

@@ -319,20 +319,6 @@ __device__ __forceinline__ float4 parts_load4(const Parts& ps, size_t idx) {
     return a;
 }
 
-// 8 consecutive values x[0..8) of row `row` at k0 (a multiple of 8) -> the two fragment chunks (high and low parts)
-__device__ __forceinline__ void store_afrag8(uint4* __restrict__ frag, int kblks, int row, int k0, const float (&x)[8], bool zero) {
-    const int tt = row >> 3, rr = row & 7, i_hi = 4 * (rr >> 1) + (rr & 1);
-    const size_t base = ((size_t)tt * kblks + (k0 >> 5)) * 64 + ((k0 >> 3) & 3) * 16;
-    uint32_t hi[4], lo[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        f32_to_bf16x2_hilo(x[2 * e], x[2 * e + 1], hi[e], lo[e]);
-        if (zero) { hi[e] = 0u; lo[e] = 0u; }
-    }
-    frag[base + i_hi] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-    frag[base + i_hi + 2] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-}
-
 // h[row] += delta (sum of partials, optional); fragments of h[row] * gain / sqrt(mean(h^2) + eps).  One workgroup per row
 // of the padded row range (rows >= M write zero fragments); d <= 8192, d % 8 == 0.
 constexpr int WNORM_NT = 512;

@@ -319,32 +319,39 @@ __device__ __forceinline__ float4 parts_load4(const Parts& ps, size_t idx) {
     return a;
 }
 
-// h[row] += delta (sum of partials, optional); fragments of h[row] * gain / sqrt(mean(h^2) + eps).  One workgroup per row
-// of the padded row range (rows >= M write zero fragments); d <= 8192, d % 8 == 0.
-constexpr int WNORM_NT = 512;
+// h[row] += delta (sum of partials, optional); fragments of h[row] * gain / sqrt(mean(h^2) + eps).  One workgroup of 1024
+// threads per row of the padded row range (rows >= M write zero fragments); d <= 8192, d % 8 == 0.  A thread owns 4
+// consecutive columns and requests all slices of them at once (up to 16 loads in flight: with 8 columns per thread and
+// 8 slices per trip the kernel paid four memory round trips per row); two neighbouring lanes then hold the 8 values of
+// one fragment chunk, exchange them, and the even lane writes the chunk's high parts, the odd lane its low parts.
+constexpr int WNORM_NT = 1024;
 template <typename WT>
 __global__ __launch_bounds__(WNORM_NT) void wide_add_norm_frag_kernel(float* __restrict__ h, int ldh, Parts delta, int ldd, int M,
                                                                   const WT* __restrict__ gain, uint4* __restrict__ frag, int d, float eps) {
     __shared__ float part[WNORM_NT / 64];
-    constexpr int MAXG = 2;                         // groups of 8 values per thread
-    const int row = blockIdx.x, ng = d / 8, kblks = d / 32;
+    constexpr int MAXG = 2;                         // groups of 4 values per thread
+    const int row = blockIdx.x, ng = d / 4, kblks = d / 32;
     const bool live = row < M;
     const int rr = min(row, M - 1);
-    float x[MAXG][8];
+    float4 x[MAXG];
     float ss = 0.f;
 #pragma unroll
     for (int k = 0; k < MAXG; ++k) {
         const int gi = (int)threadIdx.x + WNORM_NT * k;
+        x[k] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (gi < ng) {
-            float4 a = *reinterpret_cast<const float4*>(h + (size_t)rr * ldh + 8 * gi), b = *reinterpret_cast<const float4*>(h + (size_t)rr * ldh + 8 * gi + 4);
+            float4 a = *reinterpret_cast<const float4*>(h + (size_t)rr * ldh + 4 * gi);
             if (delta.p) {
-                const float4 da = parts_load4(delta, (size_t)rr * ldd + 8 * gi), db = parts_load4(delta, (size_t)rr * ldd + 8 * gi + 4);
-                a.x += da.x; a.y += da.y; a.z += da.z; a.w += da.w; b.x += db.x; b.y += db.y; b.z += db.z; b.w += db.w;
-                if (live) { *reinterpret_cast<float4*>(h + (size_t)rr * ldh + 8 * gi) = a; *reinterpret_cast<float4*>(h + (size_t)rr * ldh + 8 * gi + 4) = b; }
+                const size_t idx = (size_t)rr * ldd + 4 * gi;
+                float4 da = *reinterpret_cast<const float4*>(delta.p + idx);
+                if (delta.n <= 4) parts_add<3>(da, delta, idx, 1);
+                else if (delta.n <= 8) parts_add<7>(da, delta, idx, 1);
+                else parts_add<15>(da, delta, idx, 1);        // slices 1..15 in one trip (at most 16 slices)
+                a.x += da.x; a.y += da.y; a.z += da.z; a.w += da.w;
+                if (live) *reinterpret_cast<float4*>(h + (size_t)rr * ldh + 4 * gi) = a;
             }
-            x[k][0] = a.x; x[k][1] = a.y; x[k][2] = a.z; x[k][3] = a.w; x[k][4] = b.x; x[k][5] = b.y; x[k][6] = b.z; x[k][7] = b.w;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) ss += x[k][e] * x[k][e];
+            x[k] = a;
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
         }
     }
     ss = wave_sum(ss);
@@ -354,14 +361,30 @@ __global__ __launch_bounds__(WNORM_NT) void wide_add_norm_frag_kernel(float* __r
 #pragma unroll
     for (int w = 0; w < WNORM_NT / 64; ++w) tot += part[w];
     const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    const int odd = threadIdx.x & 1;
 #pragma unroll
     for (int k = 0; k < MAXG; ++k) {
         const int gi = (int)threadIdx.x + WNORM_NT * k;
+        // (ng is even, so a lane and its neighbour are in range together; out-of-range lanes still take part in the exchange)
+        float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
         if (gi < ng) {
-            float y[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) y[e] = x[k][e] * to_f32(gain[8 * gi + e]) * inv;
-            store_afrag8(frag, kblks, row, 8 * gi, y, !live);
+            const WT* gp = gain + 4 * gi;
+            y = make_float4(x[k].x * to_f32(gp[0]) * inv, x[k].y * to_f32(gp[1]) * inv, x[k].z * to_f32(gp[2]) * inv, x[k].w * to_f32(gp[3]) * inv);
+        }
+        const float4 o = make_float4(__shfl_xor(y.x, 1, 64), __shfl_xor(y.y, 1, 64), __shfl_xor(y.z, 1, 64), __shfl_xor(y.w, 1, 64));
+        if (gi < ng) {
+            const float4 lo4 = odd ? o : y, hi4 = odd ? y : o;        // values 0..3 and 4..7 of the chunk
+            uint32_t wh[4], wl[4];
+            f32_to_bf16x2_hilo(lo4.x, lo4.y, wh[0], wl[0]);
+            f32_to_bf16x2_hilo(lo4.z, lo4.w, wh[1], wl[1]);
+            f32_to_bf16x2_hilo(hi4.x, hi4.y, wh[2], wl[2]);
+            f32_to_bf16x2_hilo(hi4.z, hi4.w, wh[3], wl[3]);
+            const int k0 = 8 * (gi >> 1);
+            const int tt = row >> 3, r8 = row & 7, i_hi = 4 * (r8 >> 1) + (r8 & 1);
+            const size_t base = ((size_t)tt * kblks + (k0 >> 5)) * 64 + ((k0 >> 3) & 3) * 16;
+            uint4 w4 = odd ? make_uint4(wl[0], wl[1], wl[2], wl[3]) : make_uint4(wh[0], wh[1], wh[2], wh[3]);
+            if (!live) w4 = make_uint4(0u, 0u, 0u, 0u);
+            frag[base + i_hi + (odd ? 2 : 0)] = w4;
         }
     }
 }

@@ -406,6 +406,9 @@ int attention_rows_mfma(hivis_ctx* c, const float* q, int ldq, const KVDev& kv, 
         while (nsplit > 1 && (size_t)items * nsplit * FUSED_RMAX * (g.head_dim + 2) > c->attn_ws_floats) --nsplit;
         if (nsplit > 1) { ph.att.nsplit = nsplit; ph.ws = c->attn_ws; ph.cnt = c->rows_cnt; }
     }
+    if constexpr (std::is_same<typename KVType<WT>::type, f16_t>::value) {
+        if (ph.att.nsplit == 1 && frag_out && wrote_frag && ldo % 32 == 0) { ph.frag = frag_out; *wrote_frag = true; }
+    }
     const int grid = ((ph.att.flags & 2) ? 8 * ((items + 7) / 8) : items) * ph.att.nsplit;
     PassParams pp{};
     pp.M = nseq * m; pp.nseq = nseq; pp.m = m; pp.d = g.d; pp.Hq = g.n_q_heads; pp.Hkv = g.n_kv_heads; pp.hd = g.head_dim; pp.F = g.ffn; pp.V = g.vocab;

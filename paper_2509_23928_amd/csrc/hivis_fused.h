@@ -68,6 +68,7 @@ struct Phase {
     float* pm; int* pi;                            // LOGITS writes, ARGMAX reads: greedy candidates [row][workgroup]
     const float* u; int u_sseq, u_idx;             // SAMPLE: uniform number of row (seq, i) = u[seq*u_sseq + u_idx]; logits rows in A (stride lda)
     const uint4* next_W; int next_K, next_N;       // GEMM: weights of the next GEMM phase of the program (prefetch), or null
+    uint4* frag;                                   // ATTN with one key split, optional: the rows go out as A fragments of the next GEMM (K = ldy) instead of to Y
 };
 
 struct PassParams {
@@ -1409,8 +1410,8 @@ __device__ __forceinline__ void run_phase(const Phase& ph, const PassParams& pp,
             if (xcd_map) { const int j = w >> 3; item = (w & 7) + 8 * (j / nsp); split = j % nsp; if (item >= ph.att_items) continue; }
             else { item = w / nsp; split = w % nsp; }
             if constexpr (std::is_same<KT, f16_t>::value) {
-                if (pp.hd == 128) attn_wg_mfma<128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2);
-                else attn_wg_mfma<64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2);
+                if (pp.hd == 128) attn_wg_mfma<128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2, ph.frag);
+                else attn_wg_mfma<64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2, ph.frag);
             } else {
                 if (pp.hd == 128) attn_wg_partial<KT, 128, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2);
                 else attn_wg_partial<KT, 64, FUSED_RMAX>(ph.A, (const KT*)ph.kc, (const KT*)ph.vc, ph.base, ph.att, item, split, lds, ph.ws, ph.cnt, ph.Y, ph.ldy, pp.prof2);

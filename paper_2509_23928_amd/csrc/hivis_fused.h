@@ -1066,7 +1066,13 @@ __global__ __launch_bounds__(FUSED_NT) void attn_rows_kernel(const float* __rest
                                                              uint4* __restrict__ frag_out) {
     // frag_out (optional): the rows are written as A fragments of the next GEMM (K = ldo) instead of fp32 rows to `out`
     extern __shared__ __align__(16) float attn_rows_lds[];
-    attn_wg_mfma<HD, ATTN_ROWS_RM>(q, kc, vc, base, sh, blockIdx.x, 0, attn_rows_lds, nullptr, nullptr, out, ldo, nullptr, frag_out);
+    // Work items are numbered row block fastest, and workgroup b runs on XCD b % 8: the row blocks of one head would land
+    // on different XCDs and each fetch the head's cached K and V rows from memory (61-row pass: 86 MB per layer for 23 MB
+    // of cache rows).  Where the heads divide by 8, XCD x takes the heads x, x + 8, ... with all their row blocks.
+    int item = blockIdx.x;
+    const int nr = sh.n_rblk, ngrp = (int)gridDim.x / nr;
+    if (nr > 1 && (ngrp & 7) == 0 && ngrp * nr == (int)gridDim.x) { const int x = item & 7, slot = item >> 3; item = (x + 8 * (slot / nr)) * nr + slot % nr; }
+    attn_wg_mfma<HD, ATTN_ROWS_RM>(q, kc, vc, base, sh, item, 0, attn_rows_lds, nullptr, nullptr, out, ldo, nullptr, frag_out);
 }
 
 // Attention of long row ranges (prefill): the published flash-attention work split.  A workgroup owns 128 consecutive
